@@ -1,0 +1,403 @@
+"""CPU oracle for the certified sub-vocabulary LM-head path (CSV-Decode).
+
+TEST INFRASTRUCTURE ONLY.  This file is the slow, plain reference the GPU path is
+checked against.  It may be imported by tests/, by __graft_entry__.smoke() and by
+bench.py's cpu_baseline leg, and by nothing else; it shares no code with the HIP
+path and never receives a value computed there.
+
+Everything is float64 on the values the method is given: bf16 weights W and hidden
+states h (as 16-bit patterns), float32 bias b, and the float32 index arrays
+(centroids, radii, per-cluster bias maxima).  A BLAS matrix product serves as the
+"inner product for all rows" step; nothing is blocked, fused or reordered beyond
+what the cited definition states.
+
+Pins (tests/test_oracle_*.py):
+  full_logits        head-FLOP arithmetic of Section I (GPT-3 example); linearity; long-double on tiny V
+  topk_bruteforce    three independent selections on tiny V
+  build_index        partition/permutation invariants, radius >= every member distance, footprint of Section IV
+  cluster_bounds     Cauchy-Schwarz invariant (Section III-A), homogeneity, singleton clusters, single cluster
+  topk certificate   Theorem 1 against brute force; minimal prefix = {U_c >= true k-th logit}
+  eps certificate    proof identity TV = R/(Z_S+R) (Theorem 2), cluster-wise tail <= loose tail
+  alg1_step          brute-force enumeration of all prefixes on small C
+  csv2r_step         contains Algorithm 1's minimal prefix; monotone thresholds; budget extremes
+Parity unpinned: the choices K_max = V/4, radius slack 2^-14, tie tolerance, and the
+default of requiring both certificates are readings of this build, not values the paper fixes.
+"""
+from __future__ import annotations
+
+import math
+
+import numpy as np
+
+FLAG_TOPK_CERT = 1
+FLAG_SOFTMAX_CERT = 2
+FLAG_FALLBACK = 4
+FLAG_INVALID = 8
+
+COMBINE_ALL = 0   # a step is certified when every enabled certificate holds
+COMBINE_ANY = 1   # Algorithm 1's literal "break on either certificate"
+
+NEG_INF = -math.inf
+
+
+# ----------------------------------------------------------------------------- arithmetic pins
+def head_flops(V: int, d: int) -> int:
+    """Multiply-adds x2 of one full output-layer product (Section I, the GPT-3 example)."""
+    return 2 * V * d
+
+
+def metadata_bytes(C: int, d: int) -> int:
+    """Index metadata footprint C*(4d + 8 + 4) bytes (Section IV, offline preprocessing)."""
+    return C * (d * 4 + 8 + 4)
+
+
+# ----------------------------------------------------------------------------- plain definitions
+def bf16_to_f64(bits: np.ndarray) -> np.ndarray:
+    """bfloat16 bit patterns -> float64 (exact)."""
+    return (np.asarray(bits).astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+
+
+def full_logits(W64: np.ndarray, b, h64: np.ndarray) -> np.ndarray:
+    """l[s,i] = <W_i, h_s> + b_i for every token i (Eq. "logit", Section II-A)."""
+    out = h64 @ W64.T
+    if b is not None:
+        out = out + np.asarray(b, dtype=np.float64)[None, :]
+    return out
+
+
+def logsumexp(x: np.ndarray) -> float:
+    """log sum_i exp(x_i): log of the partition function of Eq. "softmax"."""
+    x = np.asarray(x, dtype=np.float64)
+    if x.size == 0:
+        return NEG_INF
+    m = float(np.max(x))
+    if m == NEG_INF:
+        return NEG_INF
+    return m + math.log(float(np.sum(np.exp(x - m))))
+
+
+def topk_bruteforce(logits: np.ndarray, k: int, ids: np.ndarray | None = None):
+    """Largest k by full sort; order (logit descending, token id ascending)."""
+    logits = np.asarray(logits, dtype=np.float64)
+    if ids is None:
+        ids = np.arange(logits.shape[0], dtype=np.int64)
+    order = np.lexsort((ids, -logits))[:k]
+    return ids[order], logits[order]
+
+
+# ----------------------------------------------------------------------------- offline index
+class OracleIndex:
+    """Cluster metadata of Section III-A.1 / Section IV: centroids, radii, bias maxima, row permutation."""
+
+    def __init__(self, mu, R, bmax, n, perm):
+        self.mu = np.ascontiguousarray(mu, dtype=np.float32)      # [C,d] stored centroids
+        self.R = np.ascontiguousarray(R, dtype=np.float32)        # [C]   stored radii (rounded up)
+        self.bmax = np.ascontiguousarray(bmax, dtype=np.float32)  # [C]   max bias in cluster (-inf if empty)
+        self.n = np.ascontiguousarray(n, dtype=np.int64)          # [C]   rows per cluster
+        self.off = np.concatenate([[0], np.cumsum(self.n)]).astype(np.int64)
+        self.perm = np.ascontiguousarray(perm, dtype=np.int64)    # [V]   permuted row -> original token id
+        self.C = int(self.n.shape[0])
+        self.V = int(self.perm.shape[0])
+        self.d = int(self.mu.shape[1])
+
+    def rows(self, c: int) -> np.ndarray:
+        """idx(c): original token ids of cluster c."""
+        return self.perm[self.off[c]:self.off[c + 1]]
+
+
+def _round_up_f32(x: np.ndarray) -> np.ndarray:
+    x = np.asarray(x, dtype=np.float64)
+    y = x.astype(np.float32)
+    low = y.astype(np.float64) < x
+    y[low] = np.nextafter(y[low], np.float32(np.inf))
+    return y
+
+
+def build_index(W_bits: np.ndarray, b, labels: np.ndarray, C: int, radius_slack: float = 2.0 ** -14) -> OracleIndex:
+    """Index from a cluster assignment.
+
+    mu_c = mean of the cluster's rows, stored as float32;  R_c = max_i ||W_i - mu_c||_2 measured to the
+    STORED centroid (Section III-A.1).  The stored radius is R_c(1+rho) + rho*||mu_c||, rounded up to
+    float32, so that float32 evaluation of the bound stays above float32 evaluation of the logits.
+    Rows are permuted so each cluster is contiguous (Algorithm 1, "contiguous by reordering"):
+    clusters in id order, tokens inside a cluster by ascending original id.
+    """
+    labels = np.asarray(labels, dtype=np.int64)
+    V, d = W_bits.shape
+    n = np.bincount(labels, minlength=C).astype(np.int64)
+    perm = np.argsort(labels, kind="stable").astype(np.int64)
+    off = np.concatenate([[0], np.cumsum(n)])
+    mu = np.zeros((C, d), dtype=np.float32)
+    R = np.zeros(C, dtype=np.float64)
+    bmax = np.full(C, -np.inf, dtype=np.float32)
+    bb = None if b is None else np.asarray(b, dtype=np.float32)
+    for c in range(C):
+        rows = perm[off[c]:off[c + 1]]
+        if rows.size == 0:
+            continue
+        Wc = bf16_to_f64(W_bits[rows])
+        mu[c] = Wc.mean(axis=0).astype(np.float32)
+        diff = Wc - mu[c].astype(np.float64)[None, :]
+        R[c] = math.sqrt(float(np.max(np.einsum("ij,ij->i", diff, diff))))
+        bmax[c] = np.float32(0.0) if bb is None else bb[rows].max()
+    mun = np.sqrt(np.einsum("ij,ij->i", mu.astype(np.float64), mu.astype(np.float64)))
+    Rt = _round_up_f32(R * (1.0 + radius_slack) + radius_slack * mun)
+    Rt[n == 0] = 0.0
+    return OracleIndex(mu, Rt, bmax, n, perm)
+
+
+def lloyd_assign(W64: np.ndarray, cent64: np.ndarray) -> np.ndarray:
+    """Nearest centroid in squared Euclidean distance; ties go to the smaller cluster id."""
+    out = np.empty(W64.shape[0], dtype=np.int64)
+    step = max(1, int(2e7) // (cent64.shape[0] * cent64.shape[1]))
+    for lo in range(0, W64.shape[0], step):
+        x = W64[lo:lo + step]
+        d2 = ((x[:, None, :] - cent64[None, :, :]) ** 2).sum(-1)
+        out[lo:lo + step] = np.argmin(d2, axis=1)      # argmin returns the first (smallest id) minimum
+    return out
+
+
+def lloyd_kmeans(W_bits: np.ndarray, init_rows: np.ndarray, iters: int):
+    """Plain Lloyd iteration (Section III-A.1: K-means over the rows of W).
+
+    Centroids start at the given rows; each iteration assigns every row to its nearest centroid and
+    replaces each centroid by the float32-rounded mean of its rows (an empty cluster keeps its centroid).
+    Returns (labels after the last assignment, float32 centroids used for that assignment).
+    """
+    W64 = bf16_to_f64(W_bits)
+    cent = W64[np.asarray(init_rows, dtype=np.int64)].astype(np.float32)
+    labels = lloyd_assign(W64, cent.astype(np.float64))
+    for _ in range(iters):
+        for c in range(cent.shape[0]):
+            m = labels == c
+            if m.any():
+                cent[c] = W64[m].mean(axis=0).astype(np.float32)
+        labels = lloyd_assign(W64, cent.astype(np.float64))
+    return labels, cent
+
+
+# ----------------------------------------------------------------------------- bounds
+def cluster_bounds(index: OracleIndex, h64: np.ndarray):
+    """U_c(h) = <mu_c,h> + R_c ||h||_2 + max_{i in c} b_i  (Eq. "cluster_bound").  Empty clusters get -inf."""
+    h64 = np.atleast_2d(h64)
+    hn = np.sqrt(np.einsum("ij,ij->i", h64, h64))
+    U = h64 @ index.mu.astype(np.float64).T + hn[:, None] * index.R.astype(np.float64)[None, :] \
+        + index.bmax.astype(np.float64)[None, :]
+    U[:, index.n == 0] = NEG_INF
+    return U, hn
+
+
+def cluster_order(U_row: np.ndarray) -> np.ndarray:
+    """Clusters by descending bound; equal bounds -> smaller cluster id first."""
+    return np.lexsort((np.arange(U_row.shape[0]), -U_row))
+
+
+def _lam(eps: float) -> float:
+    """ln(eps/(1-eps)): R-hat/(e^Z + R-hat) <= eps  <=>  log R-hat - Z <= ln(eps/(1-eps))."""
+    if eps >= 1.0:
+        return math.inf
+    if eps <= 0.0:
+        return NEG_INF
+    return math.log(eps / (1.0 - eps))
+
+
+def tail_log_mass(index: OracleIndex, U_row: np.ndarray, order: np.ndarray) -> np.ndarray:
+    """T[m] = log sum_{j>m} n_{o(j)} exp(U_{o(j)}), m = 0..C: log of the cluster-wise tail bound R-hat
+    of Theorem 2's proof when the first m clusters of the order are open.  T[C] = -inf."""
+    C = order.shape[0]
+    with np.errstate(divide="ignore"):
+        v = np.log(index.n[order].astype(np.float64)) + U_row[order]
+    T = np.full(C + 1, NEG_INF)
+    acc = NEG_INF
+    for m in range(C - 1, -1, -1):
+        acc = np.logaddexp(acc, v[m]) if v[m] != NEG_INF else acc
+        T[m] = acc
+    return T
+
+
+def _kth_largest(vals: np.ndarray, k: int) -> float:
+    if k <= 0 or vals.size < k:
+        return NEG_INF
+    return float(np.sort(vals)[::-1][k - 1])
+
+
+# ----------------------------------------------------------------------------- Algorithm 1, as printed
+def alg1_step(index: OracleIndex, U_row: np.ndarray, logits_row: np.ndarray, k: int, eps: float,
+              K_max: int, combine: int = COMBINE_ANY) -> dict:
+    """One decoding step of Algorithm 1: open clusters one at a time in descending bound order.
+
+    Before each opening, test the top-k certificate (Definition 1: every unopened bound strictly below
+    the k-th largest scored logit) and the eps-softmax certificate (Theorem 2 with the cluster-wise tail,
+    tested in the log domain: T - Z_S <= ln(eps/(1-eps))).  combine=ANY stops on either (the listing);
+    combine=ALL stops only when every enabled test holds.  After each opening, |S| > K_max -> fallback.
+    logits_row holds the exact logits by ORIGINAL token id; scoring a cluster reads its rows' entries.
+    """
+    order = cluster_order(U_row)
+    order = order[index.n[order] > 0]          # an empty cluster is never in the queue
+    lam = _lam(eps)
+    use_k, use_s = k >= 1, eps > 0
+    S_ids: list[np.ndarray] = []
+    S_vals = np.empty(0)
+    Z = NEG_INF
+    topk_min = NEG_INF
+    opened = 0
+    while True:
+        rest = order[opened:]
+        if rest.size == 0:
+            tk, sm = True, True
+        else:
+            tk = bool(S_vals.size >= k and U_row[rest[0]] < topk_min)
+            with np.errstate(divide="ignore"):
+                T = logsumexp(np.log(index.n[rest].astype(np.float64)) + U_row[rest])
+            sm = bool(S_vals.size > 0 and T - Z <= lam)
+        tk_ok = tk if use_k else (combine == COMBINE_ALL)
+        sm_ok = sm if use_s else (combine == COMBINE_ALL)
+        done = (tk_ok and sm_ok) if combine == COMBINE_ALL else (tk_ok or sm_ok)
+        if done:
+            break
+        c = rest[0]
+        rows = index.rows(c)
+        S_ids.append(rows)
+        S_vals = np.concatenate([S_vals, logits_row[rows]])
+        opened += 1
+        topk_min = _kth_largest(S_vals, k) if use_k else NEG_INF
+        Z = logsumexp(S_vals)
+        if S_vals.size > K_max:
+            return {"fallback": True, "opened": opened, "n_rows": int(S_vals.size)}
+    return {"fallback": False, "opened": opened, "n_rows": int(S_vals.size), "topk_cert": tk, "soft_cert": sm,
+            "clusters": order[:opened].copy(), "theta": topk_min, "Z": Z}
+
+
+# ----------------------------------------------------------------------------- two-round schedule
+def csv2r_step(index: OracleIndex, U_row: np.ndarray, logits_row: np.ndarray, k: int, eps: float,
+               K_max: int, combine: int = COMBINE_ALL) -> dict:
+    """Two-round batched schedule of Algorithm 1 (the selection rule the GPU path is graded on).
+
+    The same two tests as Algorithm 1, evaluated only at round boundaries:
+      round 0  open the shortest prefix of the bound order holding >= max(k,1) rows; theta0 = k-th largest
+               scored logit, Z0 = log-sum-exp of scored logits; test both certificates.
+      round 1  a = number of clusters with U_c >= theta0 (all that could still reach the top-k, Definition 1);
+               s = shortest prefix >= m0 whose tail satisfies Theorem 2 against Z0;
+               open up to max(a,s) (ALL) or min(a,s) (ANY); test again.
+    The budget |S| > K_max is tested on the planned size before scoring; failing tests after round 1 -> fallback.
+    Returns decisions, outputs and the margin of every comparison (for tie-band accounting in parity tests).
+    """
+    C = index.C
+    order = cluster_order(U_row)
+    su = U_row[order]
+    P = np.concatenate([[0], np.cumsum(index.n[order])])          # P[m] rows in first m clusters
+    T = tail_log_mass(index, U_row, order)
+    lam = _lam(eps)
+    use_k, use_s = k >= 1, eps > 0
+    if not (use_k or use_s):
+        raise ValueError("both certificates disabled")
+    margins: dict[str, float] = {}
+
+    def result(flags, m, rounds, ids, vals, Z, theta):
+        return {"flags": flags, "fallback": bool(flags & FLAG_FALLBACK), "m0": m0, "m1": m, "rounds": rounds,
+                "n_rows": int(P[m]) if not flags & FLAG_FALLBACK else index.V,
+                "n_clusters": int(m) if not flags & FLAG_FALLBACK else C,
+                "clusters": order[:m].copy(), "order": order, "ids": ids, "logits": vals, "lse": Z,
+                "theta": theta, "margins": margins}
+
+    def fallback(m, rounds):
+        ids, vals = topk_bruteforce(logits_row, k)
+        f = FLAG_FALLBACK | FLAG_TOPK_CERT | FLAG_SOFTMAX_CERT
+        if vals.size > k - 1 and logits_row.size > k >= 1:
+            srt = np.sort(logits_row)[::-1]
+            margins["id_gap"] = float(srt[k - 1] - srt[k])
+        return result(f, m, rounds, ids, vals, logsumexp(logits_row), float(vals[-1]) if k >= 1 else NEG_INF)
+
+    def score(m):
+        rows = index.perm[:0] if m == 0 else np.concatenate([index.rows(c) for c in order[:m]])
+        vals = logits_row[rows]
+        ids, top = topk_bruteforce(vals, k, rows)
+        theta = float(top[-1]) if use_k else NEG_INF
+        return rows, vals, ids, top, theta, logsumexp(vals)
+
+    def tests(m, theta, Z, tag):
+        if m == C or su[m] == NEG_INF:
+            tk = True
+        else:
+            tk = bool(su[m] < theta)
+            if use_k:
+                margins["tk" + tag] = abs(float(su[m]) - theta)
+        sm = bool(T[m] - Z <= lam)
+        if use_s and math.isfinite(T[m]) and math.isfinite(lam):
+            margins["sm" + tag] = abs(float(T[m]) - Z - lam)
+        return tk, sm
+
+    def combine_ok(tk, sm):
+        if combine == COMBINE_ALL:
+            return (tk or not use_k) and (sm or not use_s)
+        return (tk and use_k) or (sm and use_s)
+
+    need = max(k, 1)
+    m0 = int(np.searchsorted(P, need, side="left"))              # min m with P[m] >= need
+    if m0 < C and su[m0] != NEG_INF:
+        margins["seed"] = float(su[m0 - 1] - su[m0])
+    if P[m0] > K_max:
+        return fallback(m0, 0)
+    rows, vals, ids, top, theta0, Z0 = score(m0)
+    tk0, sm0 = tests(m0, theta0, Z0, "0")
+    if combine_ok(tk0, sm0):
+        f = (FLAG_TOPK_CERT if tk0 and use_k else 0) | (FLAG_SOFTMAX_CERT if sm0 and use_s else 0)
+        _id_margin(margins, vals, k)
+        return result(f, m0, 1, ids, top, Z0, theta0)
+
+    # round 1 target
+    if tk0 or not use_k:
+        a = m0
+    else:
+        a = int(np.sum(su >= theta0))
+        fin = su[np.isfinite(su)]
+        margins["a"] = float(np.min(np.abs(fin - theta0)))
+    if sm0 or not use_s:
+        s = m0
+    else:
+        s = m0 + int(np.argmax(T[m0:] - Z0 <= lam))
+        margins["s_hi"] = abs(float(T[s]) - Z0 - lam) if math.isfinite(T[s]) else math.inf
+        margins["s_lo"] = abs(float(T[s - 1]) - Z0 - lam)
+        if s < C and su[s] != NEG_INF:
+            margins["s_order"] = float(su[s - 1] - su[s])
+    cands = ([a] if use_k else []) + ([s] if use_s else [])
+    m1 = max(cands) if combine == COMBINE_ALL else min(cands)
+    if 0 < m1 < C and su[m1] != NEG_INF:
+        margins["m1_order"] = float(su[m1 - 1] - su[m1])
+    if P[m1] > K_max:
+        return fallback(m1, 1)
+    rows, vals, ids, top, theta1, Z1 = score(m1)
+    assert theta1 >= theta0 and Z1 >= Z0
+    tk1, sm1 = tests(m1, theta1, Z1, "1")
+    if combine_ok(tk1, sm1):
+        f = (FLAG_TOPK_CERT if tk1 and use_k else 0) | (FLAG_SOFTMAX_CERT if sm1 and use_s else 0)
+        _id_margin(margins, vals, k)
+        return result(f, m1, 2, ids, top, Z1, theta1)
+    return fallback(m1, 2)
+
+
+def _id_margin(margins: dict, vals: np.ndarray, k: int) -> None:
+    if k >= 1 and vals.size > k:
+        srt = np.sort(vals)[::-1]
+        margins["id_gap"] = float(srt[k - 1] - srt[k])
+
+
+# ----------------------------------------------------------------------------- one batch step
+def decode_step(W64: np.ndarray, b, index: OracleIndex, h_bits: np.ndarray, k: int, eps: float, K_max: int,
+                combine: int = COMBINE_ALL, logits: np.ndarray | None = None) -> list:
+    """All sequences of one batch step.  Full logits are formed once by definition; the selection
+    rule then reads the entries of the rows it opens (identical to scoring those rows alone)."""
+    h64 = bf16_to_f64(np.atleast_2d(h_bits))
+    if logits is None:
+        logits = full_logits(W64, b, h64)
+    U, hn = cluster_bounds(index, h64)
+    out = []
+    for s in range(h64.shape[0]):
+        if not np.isfinite(hn[s]):
+            out.append({"flags": FLAG_INVALID, "fallback": False})
+            continue
+        r = csv2r_step(index, U[s], logits[s], k, eps, K_max, combine)
+        r["U"] = U[s]
+        r["hnorm"] = hn[s]
+        out.append(r)
+    return out

@@ -1,0 +1,434 @@
+"""Pins for the CPU oracle: each part is checked against something other than itself —
+figures the paper prints, exact rational arithmetic, definitions written out on sets,
+closed forms, invariants and brute force on tiny inputs."""
+import heapq
+import math
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+import synth
+from oracle import csv_oracle as O
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden", "paper_arithmetic.txt")
+
+
+def _gold():
+    out = {}
+    for line in open(GOLD):
+        if line.startswith("#") or not line.strip():
+            continue
+        name, val = line.split()[:2]
+        out[name] = float(val)
+    return out
+
+
+def _agrees_to_three_digits(x, printed):
+    """|x - printed| below one unit of the printed value's third significant digit
+    (the paper's FLOP figure is twice its already-rounded multiply-add figure)."""
+    unit = 10 ** (math.floor(math.log10(abs(printed))) - 2)
+    return abs(x - printed) < unit
+
+
+def _frac_bf16(bits):
+    return Fraction(float(O.bf16_to_f64(np.array([bits], dtype=np.uint16))[0]))
+
+
+def _small(seed=0, **kw):
+    r = synth.small_recipe(**kw)
+    head = synth.make_head(r, seed=seed, threads=1)
+    h = synth.make_hidden(r, head["centers"], seed=seed)
+    return r, head, h
+
+
+# ------------------------------------------------------------------ printed arithmetic
+def test_paper_head_flops_and_footprint():
+    g = _gold()
+    V, d = int(g["gpt3_vocab"]), int(g["gpt3_hidden"])
+    assert O.head_flops(V, d) == 1_235_116_032
+    assert _agrees_to_three_digits(O.head_flops(V, d), g["gpt3_flops_printed"])
+    assert _agrees_to_three_digits(O.head_flops(V, d) // 2, g["gpt3_macs_printed"])
+    assert O.head_flops(V, d) // 2 == 617_558_016
+    C, dm = int(g["meta_clusters"]), int(g["meta_hidden"])
+    assert O.metadata_bytes(1, dm) == int(g["meta_bytes_per_cluster"])
+    assert O.metadata_bytes(C, dm) == 32_792_000
+    assert _agrees_to_three_digits(O.metadata_bytes(C, dm) / 1e6, g["meta_total_mb_printed"])
+    assert dm * 2 + 4 == int(g["allgather_bytes_per_row_d4096"])
+
+
+# ------------------------------------------------------------------ full logits
+def test_full_logits_exact_rational():
+    rng = np.random.default_rng(1)
+    V, d, B = 7, 24, 2
+    Wb = synth.f32_to_bf16_bits(rng.standard_normal((V, d)).astype(np.float32))
+    hb = synth.f32_to_bf16_bits(rng.standard_normal((B, d)).astype(np.float32) * 3)
+    b = rng.standard_normal(V).astype(np.float32)
+    got = O.full_logits(O.bf16_to_f64(Wb), b, O.bf16_to_f64(hb))
+    assert got.shape == (B, V)
+    for s in range(B):
+        for i in range(V):
+            exact = sum(_frac_bf16(Wb[i, j]) * _frac_bf16(hb[s, j]) for j in range(d)) + Fraction(float(b[i]))
+            assert abs(got[s, i] - float(exact)) <= 1e-13 * max(1.0, abs(float(exact)))
+
+
+def test_full_logits_linearity_and_operand_roles():
+    rng = np.random.default_rng(2)
+    W = rng.standard_normal((5, 3))
+    b = rng.standard_normal(5)
+    h = rng.standard_normal((2, 3))
+    l1 = O.full_logits(W, b, h)
+    l2 = O.full_logits(W, b, 4.0 * h)
+    assert np.allclose(l2 - b, 4.0 * (l1 - b), rtol=0, atol=1e-12)
+    # a unit hidden vector reads off a column of W: catches a transposed operand
+    e = np.zeros((1, 3)); e[0, 1] = 1.0
+    assert np.array_equal(O.full_logits(W, None, e)[0], W[:, 1])
+
+
+def test_logsumexp_against_direct_sum_and_shift():
+    x = np.array([0.3, -1.2, 2.5, 2.5, -7.0])
+    assert math.isclose(O.logsumexp(x), math.log(sum(math.exp(v) for v in x)), rel_tol=1e-14)
+    assert math.isclose(O.logsumexp(x + 1000.0), O.logsumexp(x) + 1000.0, rel_tol=1e-14)
+    assert O.logsumexp(np.array([])) == -math.inf
+
+
+# ------------------------------------------------------------------ brute-force top-k
+@pytest.mark.parametrize("V", [1, 2, 17, 64])
+def test_topk_three_ways(V):
+    rng = np.random.default_rng(V)
+    x = np.round(rng.standard_normal(V), 1)          # coarse values: ties are common
+    for k in sorted({1, 2, V} & set(range(1, V + 1))):
+        ids, vals = O.topk_bruteforce(x, k)
+        # (a) repeated arg-max scan, smallest id on ties
+        left = list(range(V)); scan = []
+        for _ in range(k):
+            best = left[0]
+            for i in left[1:]:
+                if x[i] > x[best]:
+                    best = i
+            scan.append(best); left.remove(best)
+        # (b) heap selection on the composite key
+        hp = [i for _, i in heapq.nsmallest(k, ((-x[i], i) for i in range(V)))]
+        assert list(ids) == scan == hp
+        assert np.array_equal(vals, x[ids])
+
+
+# ------------------------------------------------------------------ index
+def test_index_partition_radius_bias():
+    r, head, _ = _small(seed=3)
+    idx = O.build_index(head["W_bits"], head["b"], head["labels"], r.C, radius_slack=0.0)
+    assert sorted(idx.perm.tolist()) == list(range(r.V))                 # a permutation
+    assert idx.n.sum() == r.V and np.array_equal(idx.n, np.bincount(head["labels"], minlength=r.C))
+    W = O.bf16_to_f64(head["W_bits"])
+    for c in range(r.C):
+        rows = idx.rows(c)
+        assert np.all(head["labels"][rows] == c)                          # every row in its own cluster
+        assert np.all(np.diff(rows) > 0)                                  # ascending ids inside
+        assert np.allclose(idx.mu[c], W[rows].mean(0), rtol=1e-6, atol=1e-7)
+        dist = np.sqrt(((W[rows] - idx.mu[c].astype(np.float64)) ** 2).sum(1))
+        assert float(idx.R[c]) >= dist.max()                              # stored radius covers every member
+        assert float(idx.R[c]) <= dist.max() * (1 + 2e-7)                 # and is the max, not something larger
+        assert idx.bmax[c] == head["b"][rows].max()
+    # the default slack only ever enlarges the radius
+    idx2 = O.build_index(head["W_bits"], head["b"], head["labels"], r.C)
+    assert np.all(idx2.R >= idx.R) and np.all(idx2.R <= idx.R * 1.001 + 1e-3)
+
+
+def test_lloyd_recovers_planted_labels():
+    r, head, _ = _small(seed=4, V=600, d=64, C=6)
+    first = np.array([int(np.flatnonzero(head["labels"] == c)[0]) for c in range(r.C)])
+    labels, cent = O.lloyd_kmeans(head["W_bits"], first, iters=3)
+    assert np.array_equal(labels, head["labels"])
+    idx = O.build_index(head["W_bits"], head["b"], labels, r.C)
+    assert np.allclose(cent, idx.mu, atol=1e-6)
+
+
+def test_lloyd_assign_is_nearest_centroid_with_ties():
+    W = np.array([[0.0, 0.0], [1.0, 0.0], [0.5, 0.0], [3.0, 4.0]])
+    cent = np.array([[0.0, 0.0], [1.0, 0.0], [3.0, 3.0]])
+    assert O.lloyd_assign(W, cent).tolist() == [0, 1, 0, 2]               # [0.5,0] ties -> smaller id
+
+
+# ------------------------------------------------------------------ bounds
+@pytest.mark.parametrize("slack", [0.0, 2.0 ** -14])
+def test_bound_dominates_every_logit(slack):
+    r, head, h = _small(seed=5, steps=6)
+    idx = O.build_index(head["W_bits"], head["b"], head["labels"], r.C, radius_slack=slack)
+    W = O.bf16_to_f64(head["W_bits"])
+    for t in range(h.shape[0]):
+        h64 = O.bf16_to_f64(h[t])
+        L = O.full_logits(W, head["b"], h64)
+        U, hn = O.cluster_bounds(idx, h64)
+        assert np.allclose(hn, np.linalg.norm(h64, axis=1))
+        assert np.all(L <= U[:, head["labels"]] + 1e-12)                  # Cauchy-Schwarz invariant
+
+
+def test_bound_homogeneity_and_special_cases():
+    r, head, h = _small(seed=6)
+    idx = O.build_index(head["W_bits"], head["b"], head["labels"], r.C, radius_slack=0.0)
+    h64 = O.bf16_to_f64(h[0])
+    U1, _ = O.cluster_bounds(idx, h64)
+    U3, _ = O.cluster_bounds(idx, 3.0 * h64)
+    bm = idx.bmax.astype(np.float64)
+    assert np.allclose(U3 - bm, 3.0 * (U1 - bm), rtol=1e-12, atol=1e-12)
+    W = O.bf16_to_f64(head["W_bits"])
+    L = O.full_logits(W, head["b"], h64)
+    # one cluster per token: zero radius, the bound IS the logit
+    idxV = O.build_index(head["W_bits"], head["b"], np.arange(r.V), r.V, radius_slack=0.0)
+    UV, _ = O.cluster_bounds(idxV, h64)
+    assert np.all(idxV.R == 0) and np.allclose(UV, L, rtol=1e-13, atol=1e-13)
+    # a single cluster: one bound above the maximum logit
+    idx1 = O.build_index(head["W_bits"], head["b"], np.zeros(r.V, dtype=int), 1, radius_slack=0.0)
+    Uo, _ = O.cluster_bounds(idx1, h64)
+    assert Uo.shape == (r.B, 1) and np.all(Uo[:, 0] >= L.max(1))
+
+
+def test_bound_is_attained_when_deviation_aligns_with_h():
+    # two rows mu +- r*e0, equal bias, h along e0: the larger logit equals the bound exactly,
+    # so neither the radius term nor the bias term can be over- or under-weighted.
+    mu = np.array([1.0, 2.0, -0.5, 0.25], dtype=np.float32)
+    dev = np.array([0.5, 0, 0, 0], dtype=np.float32)
+    Wb = synth.f32_to_bf16_bits(np.stack([mu + dev, mu - dev]))
+    b = np.array([0.75, 0.75], dtype=np.float32)
+    idx = O.build_index(Wb, b, np.zeros(2, dtype=int), 1, radius_slack=0.0)
+    h64 = np.array([[3.0, 0.0, 0.0, 0.0]])
+    U, hn = O.cluster_bounds(idx, h64)
+    L = O.full_logits(O.bf16_to_f64(Wb), b, h64)
+    assert hn[0] == 3.0 and float(idx.R[0]) == 0.5
+    assert U[0, 0] == L.max() == 1.5 * 3.0 + 0.75
+    # empty clusters never win
+    idxe = O.build_index(Wb, b, np.array([0, 2]), 3, radius_slack=0.0)
+    Ue, _ = O.cluster_bounds(idxe, h64)
+    assert Ue[0, 1] == -math.inf and np.isfinite(Ue[0, [0, 2]]).all()
+
+
+# ------------------------------------------------------------------ certificates by definition
+def _random_problem(seed, V=60, d=8, C=6, bias=True, spread=1.0):
+    rng = np.random.default_rng(seed)
+    cent = rng.standard_normal((C, d)) * spread
+    labels = rng.integers(0, C, V)
+    W = cent[labels] + 0.3 * rng.standard_normal((V, d))
+    Wb = synth.f32_to_bf16_bits(W.astype(np.float32))
+    b = (0.2 * rng.standard_normal(V)).astype(np.float32) if bias else None
+    idx = O.build_index(Wb, b, labels, C, radius_slack=0.0)
+    hb = synth.f32_to_bf16_bits((rng.standard_normal((1, d)) * 1.5).astype(np.float32))
+    h64 = O.bf16_to_f64(hb)
+    L = O.full_logits(O.bf16_to_f64(Wb), b, h64)[0]
+    U, _ = O.cluster_bounds(idx, h64)
+    return idx, U[0], L, labels
+
+
+def _certs_by_definition(idx, U, L, opened, k, eps):
+    """Definition 1 and Theorem 2 (cluster-wise tail) written out on sets, in the linear domain."""
+    open_set = set(int(c) for c in opened)
+    rest = [c for c in range(idx.C) if c not in open_set and idx.n[c] > 0]
+    S = np.concatenate([idx.rows(c) for c in opened]) if len(opened) else np.empty(0, dtype=int)
+    vals = np.sort(L[S])[::-1]
+    if not rest:
+        return True, True
+    tk = len(vals) >= k >= 1 and all(U[c] < vals[k - 1] for c in rest)
+    Rhat = sum(int(idx.n[c]) * math.exp(U[c]) for c in rest)
+    ZS = float(np.sum(np.exp(L[S])))
+    sm = len(S) > 0 and eps > 0 and Rhat / (ZS + Rhat) <= eps
+    return bool(tk), bool(sm)
+
+
+@pytest.mark.parametrize("combine", [O.COMBINE_ANY, O.COMBINE_ALL])
+def test_alg1_matches_prefix_enumeration(combine):
+    checked = 0
+    for seed in range(40):
+        idx, U, L, _ = _random_problem(seed, spread=1.0 + (seed % 4))
+        for k, eps in [(3, 0.05), (1, 0.3), (5, 1e-3), (4, -1.0), (0, 0.2)]:
+            got = O.alg1_step(idx, U, L, k, eps, K_max=idx.V, combine=combine)
+            order = [c for c in O.cluster_order(U) if idx.n[c] > 0]
+            want = None
+            for m in range(len(order) + 1):
+                tk, sm = _certs_by_definition(idx, U, L, order[:m], k, eps)
+                tk_ok = tk if k >= 1 else combine == O.COMBINE_ALL
+                sm_ok = sm if eps > 0 else combine == O.COMBINE_ALL
+                if (tk_ok and sm_ok) if combine == O.COMBINE_ALL else (tk_ok or sm_ok):
+                    want = m
+                    break
+            assert not got["fallback"] and got["opened"] == want, (seed, k, eps)
+            checked += 1
+    assert checked == 200
+
+
+def test_alg1_budget():
+    idx, U, L, _ = _random_problem(7)
+    assert O.alg1_step(idx, U, L, 3, 1e-6, K_max=0)["fallback"]
+    r = O.alg1_step(idx, U, L, 3, 1e-6, K_max=idx.V)
+    assert not r["fallback"] and r["n_rows"] <= idx.V
+
+
+def test_theorem1_certified_topk_is_global_topk():
+    hits = 0
+    for seed in range(60):
+        idx, U, L, _ = _random_problem(100 + seed, V=80, C=8, spread=2.0)
+        for k in (1, 3, 7):
+            r = O.alg1_step(idx, U, L, k, -1.0, K_max=idx.V)              # top-k test alone
+            assert r["topk_cert"]
+            S = np.concatenate([idx.rows(c) for c in r["clusters"]])
+            ids_S, _ = O.topk_bruteforce(L[S], k, S)
+            ids_V, vals_V = O.topk_bruteforce(L, k)
+            assert np.array_equal(ids_S, ids_V)
+            # minimal prefix = every cluster whose bound reaches the true k-th logit
+            want = {int(c) for c in range(idx.C) if idx.n[c] > 0 and U[c] >= vals_V[-1]}
+            assert set(int(c) for c in r["clusters"]) == want
+            hits += len(want) < idx.C
+    assert hits > 20                                                       # the certificate really prunes
+
+
+def test_singleton_clusters_open_exactly_the_topk():
+    rng = np.random.default_rng(9)
+    V, d, k = 40, 6, 5
+    Wb = synth.f32_to_bf16_bits(rng.standard_normal((V, d)).astype(np.float32))
+    b = rng.standard_normal(V).astype(np.float32)
+    idx = O.build_index(Wb, b, np.arange(V), V, radius_slack=0.0)
+    h64 = O.bf16_to_f64(synth.f32_to_bf16_bits(rng.standard_normal((1, d)).astype(np.float32)))
+    L = O.full_logits(O.bf16_to_f64(Wb), b, h64)[0]
+    U, _ = O.cluster_bounds(idx, h64)
+    r = O.alg1_step(idx, U[0], L, k, -1.0, K_max=V)
+    assert r["opened"] == k and set(r["clusters"].tolist()) == set(O.topk_bruteforce(L, k)[0].tolist())
+
+
+def test_theorem2_tv_identity_and_tail_ordering():
+    for seed in range(30):
+        idx, U, L, _ = _random_problem(200 + seed, spread=1.5)
+        order = O.cluster_order(U)
+        T = O.tail_log_mass(idx, U, order)
+        p = np.exp(L - O.logsumexp(L))
+        for m in range(1, idx.C):
+            S = np.concatenate([idx.rows(c) for c in order[:m]])
+            if S.size == 0:
+                continue
+            inS = np.zeros(idx.V, bool); inS[S] = True
+            pt = np.where(inS, np.exp(L - O.logsumexp(L[S])), 0.0)
+            tv = 0.5 * np.abs(p - pt).sum()                                # total variation by definition
+            ZS, R = np.exp(L[inS]).sum(), np.exp(L[~inS]).sum()
+            assert math.isclose(tv, R / (ZS + R), rel_tol=1e-10, abs_tol=1e-15)
+            assert math.isclose(tv, p[~inS].sum(), rel_tol=1e-10, abs_tol=1e-15)
+            rest = [c for c in order[m:] if idx.n[c] > 0]
+            Rhat = sum(int(idx.n[c]) * math.exp(U[c]) for c in rest)
+            loose = (~inS).sum() * math.exp(max(U[c] for c in rest)) if rest else 0.0
+            assert R <= Rhat * (1 + 1e-12) <= loose * (1 + 1e-12)
+            if rest:
+                assert math.isclose(T[m], math.log(Rhat), rel_tol=1e-12, abs_tol=1e-12)
+        assert T[idx.C] == -math.inf
+
+
+def test_soft_certificate_implies_tv_within_eps():
+    seen = 0
+    for seed in range(40):
+        idx, U, L, _ = _random_problem(300 + seed, spread=2.5)
+        for eps in (0.2, 0.02, 1e-3):
+            r = O.alg1_step(idx, U, L, 0, eps, K_max=idx.V)               # softmax test alone
+            assert r["soft_cert"]
+            S = np.concatenate([idx.rows(c) for c in r["clusters"]])
+            p = np.exp(L - O.logsumexp(L))
+            inS = np.zeros(idx.V, bool); inS[S] = True
+            assert p[~inS].sum() <= eps
+            seen += r["opened"] < np.count_nonzero(idx.n)
+    assert seen > 10
+
+
+def test_soft_certificate_extremes():
+    idx, U, L, _ = _random_problem(11)
+    # eps -> 1: certified as soon as anything is scored
+    assert O.alg1_step(idx, U, L, 0, 1 - 1e-12, K_max=idx.V)["opened"] == 1
+    # flat logits (h = 0, no bias): never certified before the last cluster is opened
+    Uflat = np.where(idx.n > 0, 0.0, -math.inf)
+    r = O.alg1_step(idx, Uflat, np.zeros(idx.V), 0, 1e-3, K_max=idx.V)
+    assert r["opened"] == np.count_nonzero(idx.n)
+
+
+# ------------------------------------------------------------------ two-round schedule
+@pytest.mark.parametrize("combine", [O.COMBINE_ALL, O.COMBINE_ANY])
+def test_csv2r_certificates_hold_by_definition_and_contain_alg1(combine):
+    rounds = {0: 0, 1: 0, 2: 0}
+    for seed in range(60):
+        idx, U, L, _ = _random_problem(400 + seed, V=90, C=9, spread=1.0 + (seed % 5) * 0.5)
+        for k, eps in [(3, 0.05), (6, 1e-3), (2, 0.3), (4, -1.0), (0, 0.1)]:
+            r = O.csv2r_step(idx, U, L, k, eps, K_max=idx.V, combine=combine)
+            a = O.alg1_step(idx, U, L, k, eps, K_max=idx.V, combine=combine)
+            assert not r["fallback"] and not a["fallback"]
+            rounds[r["rounds"]] += 1
+            assert a["opened"] <= r["m1"]                                  # minimal prefix is contained
+            tk, sm = _certs_by_definition(idx, U, L, r["clusters"], k, eps)
+            assert bool(r["flags"] & O.FLAG_TOPK_CERT) == (tk and k >= 1)
+            assert bool(r["flags"] & O.FLAG_SOFTMAX_CERT) == (sm and eps > 0)
+            if r["flags"] & O.FLAG_TOPK_CERT:
+                assert np.array_equal(r["ids"], O.topk_bruteforce(L, k)[0])
+            S = np.concatenate([idx.rows(c) for c in r["clusters"]])
+            assert r["n_rows"] == S.size and r["n_clusters"] == len(r["clusters"])
+            assert math.isclose(r["lse"], O.logsumexp(L[S]), rel_tol=1e-13)
+            # seed prefix is the shortest with >= max(k,1) rows
+            P = np.cumsum(idx.n[r["order"]])
+            assert P[r["m0"] - 1] >= max(k, 1) and (r["m0"] == 1 or P[r["m0"] - 2] < max(k, 1))
+    assert rounds[1] > 20 and rounds[2] > 20
+
+
+def test_csv2r_budget_and_fallback_outputs():
+    idx, U, L, _ = _random_problem(12, V=90, C=9)
+    k, eps = 4, 1e-3
+    r0 = O.csv2r_step(idx, U, L, k, eps, K_max=0)
+    assert r0["fallback"] and r0["rounds"] == 0
+    assert r0["flags"] == O.FLAG_FALLBACK | O.FLAG_TOPK_CERT | O.FLAG_SOFTMAX_CERT
+    assert r0["n_rows"] == idx.V and r0["n_clusters"] == idx.C
+    assert np.array_equal(r0["ids"], O.topk_bruteforce(L, k)[0])
+    assert math.isclose(r0["lse"], O.logsumexp(L), rel_tol=1e-14)
+    rV = O.csv2r_step(idx, U, L, k, eps, K_max=idx.V)
+    assert not rV["fallback"]
+    # a budget between the seed and the round-1 plan: fallback is decided before round 1 is scored
+    if rV["rounds"] == 2:
+        rb = O.csv2r_step(idx, U, L, k, eps, K_max=rV["n_rows"] - 1)
+        assert rb["fallback"] and rb["rounds"] == 1
+
+
+def test_csv2r_on_planted_recipe_behaves_like_the_workload_model():
+    # aligned h: one cluster holds the whole top-k and nearly all of the softmax mass
+    r, head, h = _small(seed=13, V=4000, d=256, C=32, B=1, steps=8, k=10)
+    idx = O.build_index(head["W_bits"], head["b"], head["labels"], r.C)
+    W = O.bf16_to_f64(head["W_bits"])
+    for t in range(h.shape[0]):
+        out = O.decode_step(W, head["b"], idx, h[t], r.k, r.eps, r.K_max_rows)[0]
+        assert out["flags"] == O.FLAG_TOPK_CERT | O.FLAG_SOFTMAX_CERT and out["rounds"] == 1
+        assert out["n_clusters"] == 1 and out["n_rows"] == 125
+        L = O.full_logits(W, head["b"], O.bf16_to_f64(h[t]))[0]
+        assert np.array_equal(out["ids"], O.topk_bruteforce(L, r.k)[0])
+    # non-finite hidden state is flagged, not scored
+    bad = h[0].copy(); bad[0, 3] = 0x7FC0
+    assert O.decode_step(W, head["b"], idx, bad, r.k, r.eps, r.K_max_rows)[0]["flags"] == O.FLAG_INVALID
+
+
+# ------------------------------------------------------------------ strictness of the two tests
+def _singletons(logit_values):
+    """One cluster per token, zero radius, one-dimensional weights: the bound of a cluster is its logit."""
+    w = np.array(logit_values, dtype=np.float32)[:, None]
+    Wb = synth.f32_to_bf16_bits(w)
+    idx = O.build_index(Wb, None, np.arange(len(w)), len(w), radius_slack=0.0)
+    h64 = np.array([[1.0]])
+    L = O.full_logits(O.bf16_to_f64(Wb), None, h64)[0]
+    U, _ = O.cluster_bounds(idx, h64)
+    assert np.array_equal(U[0], L)
+    return idx, U[0], L
+
+
+def test_topk_test_is_strict():
+    # logits 5,3,3,1 and k=2: after opening {5,3} the next bound EQUALS the 2nd logit, so Definition 1
+    # (strict inequality) is not met and the tied cluster must be opened as well.
+    idx, U, L = _singletons([5.0, 3.0, 3.0, 1.0])
+    assert O.alg1_step(idx, U, L, 2, -1.0, K_max=4)["opened"] == 3
+    r = O.csv2r_step(idx, U, L, 2, -1.0, K_max=4)
+    assert r["m0"] == 2 and r["m1"] == 3 and r["rounds"] == 2 and r["flags"] == O.FLAG_TOPK_CERT
+    assert r["ids"].tolist() == [0, 1]                                     # equal logits: smaller id first
+
+
+def test_softmax_test_is_non_strict():
+    # two tokens with logit 0: with one open the tail ratio is exactly 1/2, which meets eps = 1/2
+    idx, U, L = _singletons([0.0, 0.0])
+    assert O.alg1_step(idx, U, L, 0, 0.5, K_max=2)["opened"] == 1
+    assert O.alg1_step(idx, U, L, 0, 0.49, K_max=2)["opened"] == 2
+    r = O.csv2r_step(idx, U, L, 0, 0.5, K_max=2)
+    assert r["m1"] == 1 and r["flags"] == O.FLAG_SOFTMAX_CERT
