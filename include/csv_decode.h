@@ -1,0 +1,167 @@
+/*
+ * csv_decode.h — C ABI of the certified sub-vocabulary LM-head path (CSV-Decode) for AMD MI355X (gfx950).
+ *
+ * One decode step, per sequence: score a centroid-plus-radius upper bound for every vocabulary cluster,
+ * open the clusters that could still reach the top-k or carry more than eps of the softmax mass, score
+ * only those clusters' rows of W, certify (exact top-k, eps-softmax), and fall back to all V rows when
+ * certification fails within the row budget.
+ *
+ * Conventions
+ *   - Pointers named d_* are DEVICE pointers owned by the caller; h_* are HOST pointers owned by the
+ *     caller.  The library never frees caller memory and keeps no reference to h_* after a call returns.
+ *   - W and h are bfloat16 bit patterns (uint16_t); everything else is float32 / int32.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  csv_decode_step,
+ *     csv_bounds and csv_full_logits only enqueue work: outputs are valid once the caller has
+ *     synchronised the stream.  They allocate nothing and never synchronise.
+ *   - Every function returns CSV_OK (0) or a negative error code; csv_last_error() returns a
+ *     thread-local message for the last failure.  No C++ exception crosses the boundary.
+ *   - A csv_workspace serves one call at a time; calls sharing a workspace must be stream-ordered.
+ */
+#ifndef CSV_DECODE_H
+#define CSV_DECODE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define CSV_OK       0
+#define CSV_EINVAL  (-1)   /* bad argument value */
+#define CSV_ENOMEM  (-2)   /* device or host allocation failed */
+#define CSV_EHIP    (-3)   /* a HIP runtime call failed */
+#define CSV_ESHAPE  (-4)   /* shape outside what the kernels support, or workspace too small */
+
+/* csv_step_out.d_flags bits */
+#define CSV_FLAG_TOPK_CERT     1u   /* Definition 1 holds: returned top-k equals the full-vocabulary top-k */
+#define CSV_FLAG_SOFTMAX_CERT  2u   /* Theorem 2 holds: total variation of the sub-vocabulary softmax <= eps */
+#define CSV_FLAG_FALLBACK      4u   /* all V rows were scored for this sequence */
+#define CSV_FLAG_INVALID_INPUT 8u   /* ||h||^2 is not finite; other outputs of the sequence are cleared */
+
+#define CSV_COMBINE_ALL 0   /* certified when every enabled certificate holds */
+#define CSV_COMBINE_ANY 1   /* certified when any enabled certificate holds (Algorithm 1 stops on either) */
+
+#define CSV_MAX_K        1024   /* largest k */
+#define CSV_MAX_CLUSTERS 8192   /* largest C */
+#define CSV_MAX_BATCH    256    /* largest B */
+
+typedef struct csv_index csv_index;          /* opaque: permuted W', b', centroids, radii, bias maxima, sizes */
+typedef struct csv_workspace csv_workspace;  /* opaque: per-step device scratch */
+
+typedef struct {
+    int iters;                   /* Lloyd iterations to run (0 = keep the starting assignment) */
+    const int32_t* h_init_labels;/* HOST int32[V] starting cluster of each token, or NULL */
+    const int32_t* h_init_rows;  /* HOST int32[C] tokens whose rows are the starting centroids; used when
+                                    h_init_labels is NULL */
+    float radius_slack;          /* rho >= 0: stored radius = roundup_f32(R_c(1+rho) + rho*||mu_c||) */
+} csv_build_opts;
+
+/*
+ * Offline preprocessing (Section III-A.1, Section IV "Offline Preprocessing").
+ * Clusters the rows of W into C clusters by Lloyd's k-means (nearest centroid in squared Euclidean distance,
+ * ties to the smaller cluster id; an empty cluster keeps its centroid), then forms for every cluster the
+ * centroid mu_c = mean of its rows (stored float32), the radius R_c = max_i ||W_i - mu_c||_2 measured to the
+ * stored centroid, the bias maximum max_i b_i, and the row permutation that makes every cluster a contiguous
+ * range of rows (clusters in id order, tokens inside a cluster by ascending id).  The index keeps its own
+ * permuted copy of W and b: the caller may free d_W / d_b afterwards.
+ *   d_W  DEVICE bf16[V*d] row-major, original token order.   d_b  DEVICE float32[V] or NULL (no bias).
+ *   Requires d % 8 == 0, 1 <= C <= min(V, CSV_MAX_CLUSTERS).
+ * Synchronises the stream before returning.  On error *out is NULL.
+ */
+int csv_build_index(const uint16_t* d_W, const float* d_b, int V, int d, int C,
+                    const csv_build_opts* opts, void* stream, csv_index** out);
+
+/*
+ * Import an index whose metadata was computed elsewhere (tests, reload of saved metadata; Section IV keeps
+ * the metadata in a file).  h_mu float32[C*d], h_R float32[C], h_bmax float32[C], h_n int32[C] rows per
+ * cluster (sum V), h_perm int32[V]: permuted row -> original token id, clusters contiguous in id order.
+ * Gathers the permuted copy of W and b on the device.  Synchronises the stream before returning.
+ */
+int csv_index_from_arrays(const uint16_t* d_W, const float* d_b, int V, int d, int C,
+                          const float* h_mu, const float* h_R, const float* h_bmax,
+                          const int32_t* h_n, const int32_t* h_perm, void* stream, csv_index** out);
+
+/* Copy the metadata back to HOST buffers of the sizes above (any pointer may be NULL to skip it). Synchronous. */
+int csv_index_export(const csv_index* idx, float* h_mu, float* h_R, float* h_bmax, int32_t* h_n, int32_t* h_perm);
+int csv_index_dims(const csv_index* idx, int* V, int* d, int* C);
+void csv_index_free(csv_index* idx);
+
+/*
+ * Scratch for steps of up to B_max sequences in which at most K_cap_rows rows per sequence are scored on
+ * the sub-vocabulary path (the budget K_max of Algorithm 1 may not exceed it).  Allocates device memory:
+ * about B_max*(8*K_cap_rows + 4*V + 24*C) bytes.
+ */
+int csv_workspace_create(const csv_index* idx, int B_max, int K_cap_rows, csv_workspace** out);
+void csv_workspace_free(csv_workspace* ws);
+
+typedef struct {
+    int   k;           /* top-k size, 0..CSV_MAX_K; 0 disables the top-k certificate */
+    float eps;         /* softmax tolerance; <= 0 disables the softmax certificate, >= 1 always holds */
+    int   K_max_rows;  /* budget K_max of Algorithm 1: a sequence whose planned |S| exceeds it falls back */
+    int   combine;     /* CSV_COMBINE_ALL or CSV_COMBINE_ANY */
+} csv_step_params;
+
+typedef struct {
+    int32_t*  d_ids;          /* [B*k]  original token ids, by logit descending, equal logits by id ascending */
+    float*    d_logits;       /* [B*k]  their logits */
+    float*    d_lse;          /* [B]    log-sum-exp over the scored rows (over all V after fallback) */
+    uint32_t* d_flags;        /* [B]    CSV_FLAG_* */
+    int32_t*  d_n_rows;       /* [B]    rows scored, |S| (V after fallback) */
+    int32_t*  d_n_clusters;   /* [B]    clusters opened (C after fallback) */
+    int32_t*  d_rounds;       /* [B] or NULL: scoring rounds used on the sub-vocabulary path (0, 1 or 2) */
+    int32_t*  d_sel_clusters; /* [B*C] or NULL: opened cluster ids in bound order (first n_clusters entries) */
+    unsigned long long* d_fallback_count; /* or NULL: incremented once per sequence that falls back */
+} csv_step_out;
+
+/*
+ * One certified decode step for B sequences (Algorithm 1, evaluated as a two-round schedule; Definitions 1-2,
+ * Theorems 1-2, Eq. "cluster_bound").  Per sequence, with clusters in descending bound order (equal bounds:
+ * smaller id first), P(m) rows in the first m clusters and T(m) the log of the cluster-wise tail bound
+ * sum_{j>m} n_j exp(U_j):
+ *   round 0: open m0 = min{m : P(m) >= max(k,1)}; theta0 = k-th largest scored logit, Z0 = log-sum-exp;
+ *            top-k test: no unopened cluster, or next bound < theta0 (strict); softmax test:
+ *            T(m0) - Z0 <= ln(eps/(1-eps)).  Certified -> done.
+ *   round 1: a = #{c : U_c >= theta0}; s = min{m >= m0 : T(m) - Z0 <= ln(eps/(1-eps))};
+ *            m1 = max(a,s) under ALL, min(a,s) under ANY (a disabled test drops out); open up to m1, test again.
+ *   The budget is tested on the planned size before scoring: P(m) > K_max_rows -> fallback; tests failing after
+ *   round 1 -> fallback.  Fallback scores all V rows (flags FALLBACK|TOPK_CERT|SOFTMAX_CERT).
+ *   d_h  DEVICE bf16[B*d].  1 <= B <= workspace B_max.  Returns CSV_EINVAL when both certificates are disabled,
+ *   k > V, or K_max_rows exceeds the workspace capacity.
+ */
+int csv_decode_step(csv_workspace* ws, const csv_index* idx, const uint16_t* d_h, int B,
+                    const csv_step_params* params, const csv_step_out* out, void* stream);
+
+/*
+ * Cluster upper bounds only (Eq. "cluster_bound"): d_U[b*C+c] = <mu_c,h_b> + R_c*||h_b||_2 + max_{i in c} b_i
+ * (-inf for an empty cluster), d_hnorm[b] = ||h_b||_2.  d_U DEVICE float32[B*C], d_hnorm DEVICE float32[B] or NULL.
+ */
+int csv_bounds(csv_workspace* ws, const csv_index* idx, const uint16_t* d_h, int B,
+               float* d_U, float* d_hnorm, void* stream);
+
+/*
+ * Full-vocabulary logits (Eq. "logit"): d_logits[b*V + i] = <W_i,h_b> + b_i for every ORIGINAL token id i.
+ * d_logits DEVICE float32[B*V].
+ */
+int csv_full_logits(csv_workspace* ws, const csv_index* idx, const uint16_t* d_h, int B,
+                    float* d_logits, void* stream);
+
+/*
+ * Measurement support (not part of the method): time the stages of csv_decode_step with HIP events recorded on
+ * the step's own stream.  csv_profile_begin allocates events for max_steps steps and switches recording on;
+ * each following csv_decode_step on this workspace records CSV_PROFILE_STAGES+1 events (steps beyond max_steps
+ * are not recorded).  csv_profile_end synchronises, writes the summed milliseconds of every stage to
+ * h_stage_ms[CSV_PROFILE_STAGES] and the number of recorded steps to *h_steps, frees the events and switches
+ * recording off.  Stage order: bounds, select, gathered GEMV (round 0), certification (round 0), gathered GEMV
+ * (round 1), certification (round 1), full-vocabulary product, fallback top-k stage 1, fallback top-k stage 2.
+ * A stage's time runs from the end of the previous stage to its own end, so it includes its launch gap.
+ */
+#define CSV_PROFILE_STAGES 9
+int csv_profile_begin(csv_workspace* ws, int max_steps);
+int csv_profile_end(csv_workspace* ws, float* h_stage_ms, int* h_steps);
+
+const char* csv_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CSV_DECODE_H */

@@ -280,7 +280,8 @@ def csv2r_step(index: OracleIndex, U_row: np.ndarray, logits_row: np.ndarray, k:
                s = shortest prefix >= m0 whose tail satisfies Theorem 2 against Z0;
                open up to max(a,s) (ALL) or min(a,s) (ANY); test again.
     The budget |S| > K_max is tested on the planned size before scoring; failing tests after round 1 -> fallback.
-    Returns decisions, outputs and the margin of every comparison (for tie-band accounting in parity tests).
+    Returns decisions, outputs and, for every comparison that decided something, the pair
+    (|x - y|, max(1,|x|,|y|)) under "margins" (tie-band accounting in parity tests).
     """
     C = index.C
     order = cluster_order(U_row)
@@ -291,7 +292,14 @@ def csv2r_step(index: OracleIndex, U_row: np.ndarray, logits_row: np.ndarray, k:
     use_k, use_s = k >= 1, eps > 0
     if not (use_k or use_s):
         raise ValueError("both certificates disabled")
-    margins: dict[str, float] = {}
+    margins: dict[str, tuple] = {}
+
+    def gap(x, y):
+        x, y = float(x), float(y)
+        return (abs(x - y), max(1.0, abs(x), abs(y)))
+
+    def gap_soft(t, z):            # T - Z against lam: the rounding scale is that of T and Z themselves
+        return (abs(float(t) - z - lam), max(1.0, abs(float(t)), abs(z), abs(lam)))
 
     def result(flags, m, rounds, ids, vals, Z, theta):
         return {"flags": flags, "fallback": bool(flags & FLAG_FALLBACK), "m0": m0, "m1": m, "rounds": rounds,
@@ -305,7 +313,7 @@ def csv2r_step(index: OracleIndex, U_row: np.ndarray, logits_row: np.ndarray, k:
         f = FLAG_FALLBACK | FLAG_TOPK_CERT | FLAG_SOFTMAX_CERT
         if vals.size > k - 1 and logits_row.size > k >= 1:
             srt = np.sort(logits_row)[::-1]
-            margins["id_gap"] = float(srt[k - 1] - srt[k])
+            margins["id_gap"] = gap(srt[k - 1], srt[k])
         return result(f, m, rounds, ids, vals, logsumexp(logits_row), float(vals[-1]) if k >= 1 else NEG_INF)
 
     def score(m):
@@ -321,10 +329,10 @@ def csv2r_step(index: OracleIndex, U_row: np.ndarray, logits_row: np.ndarray, k:
         else:
             tk = bool(su[m] < theta)
             if use_k:
-                margins["tk" + tag] = abs(float(su[m]) - theta)
+                margins["tk" + tag] = gap(su[m], theta)
         sm = bool(T[m] - Z <= lam)
         if use_s and math.isfinite(T[m]) and math.isfinite(lam):
-            margins["sm" + tag] = abs(float(T[m]) - Z - lam)
+            margins["sm" + tag] = gap_soft(T[m], Z)
         return tk, sm
 
     def combine_ok(tk, sm):
@@ -335,7 +343,7 @@ def csv2r_step(index: OracleIndex, U_row: np.ndarray, logits_row: np.ndarray, k:
     need = max(k, 1)
     m0 = int(np.searchsorted(P, need, side="left"))              # min m with P[m] >= need
     if m0 < C and su[m0] != NEG_INF:
-        margins["seed"] = float(su[m0 - 1] - su[m0])
+        margins["seed"] = gap(su[m0 - 1], su[m0])
     if P[m0] > K_max:
         return fallback(m0, 0)
     rows, vals, ids, top, theta0, Z0 = score(m0)
@@ -351,19 +359,21 @@ def csv2r_step(index: OracleIndex, U_row: np.ndarray, logits_row: np.ndarray, k:
     else:
         a = int(np.sum(su >= theta0))
         fin = su[np.isfinite(su)]
-        margins["a"] = float(np.min(np.abs(fin - theta0)))
+        near = fin[np.argmin(np.abs(fin - theta0))]
+        margins["a"] = gap(near, theta0)
     if sm0 or not use_s:
         s = m0
     else:
         s = m0 + int(np.argmax(T[m0:] - Z0 <= lam))
-        margins["s_hi"] = abs(float(T[s]) - Z0 - lam) if math.isfinite(T[s]) else math.inf
-        margins["s_lo"] = abs(float(T[s - 1]) - Z0 - lam)
+        if math.isfinite(T[s]):
+            margins["s_hi"] = gap_soft(T[s], Z0)
+        margins["s_lo"] = gap_soft(T[s - 1], Z0)
         if s < C and su[s] != NEG_INF:
-            margins["s_order"] = float(su[s - 1] - su[s])
+            margins["s_order"] = gap(su[s - 1], su[s])
     cands = ([a] if use_k else []) + ([s] if use_s else [])
     m1 = max(cands) if combine == COMBINE_ALL else min(cands)
     if 0 < m1 < C and su[m1] != NEG_INF:
-        margins["m1_order"] = float(su[m1 - 1] - su[m1])
+        margins["m1_order"] = gap(su[m1 - 1], su[m1])
     if P[m1] > K_max:
         return fallback(m1, 1)
     rows, vals, ids, top, theta1, Z1 = score(m1)
@@ -379,7 +389,8 @@ def csv2r_step(index: OracleIndex, U_row: np.ndarray, logits_row: np.ndarray, k:
 def _id_margin(margins: dict, vals: np.ndarray, k: int) -> None:
     if k >= 1 and vals.size > k:
         srt = np.sort(vals)[::-1]
-        margins["id_gap"] = float(srt[k - 1] - srt[k])
+        x, y = float(srt[k - 1]), float(srt[k])
+        margins["id_gap"] = (x - y, max(1.0, abs(x), abs(y)))
 
 
 # ----------------------------------------------------------------------------- one batch step

@@ -1,0 +1,273 @@
+"""Python binding of the CSV-Decode C ABI (include/csv_decode.h) for MI355X.
+
+Argument marshalling only: every step of the path runs in the HIP kernels of libcsvdecode.so.
+PyTorch supplies device memory and the stream.  There is no CPU fallback: importing this package
+without the built library raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libcsvdecode.so")
+
+FLAG_TOPK_CERT, FLAG_SOFTMAX_CERT, FLAG_FALLBACK, FLAG_INVALID_INPUT = 1, 2, 4, 8
+COMBINE_ALL, COMBINE_ANY = 0, 1
+MAX_K, MAX_CLUSTERS, MAX_BATCH = 1024, 8192, 256
+
+EXPORTS = [
+    "csv_build_index", "csv_index_from_arrays", "csv_index_export", "csv_index_dims", "csv_index_free",
+    "csv_workspace_create", "csv_workspace_free", "csv_decode_step", "csv_bounds", "csv_full_logits",
+    "csv_profile_begin", "csv_profile_end", "csv_last_error",
+]
+PROFILE_STAGES = ["bounds", "select", "gemv_round0", "cert_round0", "gemv_round1", "cert_round1",
+                  "full_product", "fallback_topk_1", "fallback_topk_2"]
+
+
+class BuildOpts(C.Structure):
+    _fields_ = [("iters", C.c_int), ("h_init_labels", C.c_void_p), ("h_init_rows", C.c_void_p),
+                ("radius_slack", C.c_float)]
+
+
+class StepParams(C.Structure):
+    _fields_ = [("k", C.c_int), ("eps", C.c_float), ("K_max_rows", C.c_int), ("combine", C.c_int)]
+
+
+class StepOut(C.Structure):
+    _fields_ = [("d_ids", C.c_void_p), ("d_logits", C.c_void_p), ("d_lse", C.c_void_p), ("d_flags", C.c_void_p),
+                ("d_n_rows", C.c_void_p), ("d_n_clusters", C.c_void_p), ("d_rounds", C.c_void_p),
+                ("d_sel_clusters", C.c_void_p), ("d_fallback_count", C.c_void_p)]
+
+
+def _load() -> C.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: run `python -m paper_2511_21702_amd.build` "
+                          "(or __graft_entry__.build()) first; there is no fallback path")
+    lib = C.CDLL(LIB_PATH)
+    vp, ci = C.c_void_p, C.c_int
+    lib.csv_last_error.restype = C.c_char_p
+    lib.csv_build_index.argtypes = [vp, vp, ci, ci, ci, C.POINTER(BuildOpts), vp, C.POINTER(vp)]
+    lib.csv_index_from_arrays.argtypes = [vp, vp, ci, ci, ci, vp, vp, vp, vp, vp, vp, C.POINTER(vp)]
+    lib.csv_index_export.argtypes = [vp, vp, vp, vp, vp, vp]
+    lib.csv_index_dims.argtypes = [vp, C.POINTER(ci), C.POINTER(ci), C.POINTER(ci)]
+    lib.csv_index_free.argtypes = [vp]
+    lib.csv_index_free.restype = None
+    lib.csv_workspace_create.argtypes = [vp, ci, ci, C.POINTER(vp)]
+    lib.csv_workspace_free.argtypes = [vp]
+    lib.csv_workspace_free.restype = None
+    lib.csv_decode_step.argtypes = [vp, vp, vp, ci, C.POINTER(StepParams), C.POINTER(StepOut), vp]
+    lib.csv_bounds.argtypes = [vp, vp, vp, ci, vp, vp, vp]
+    lib.csv_full_logits.argtypes = [vp, vp, vp, ci, vp, vp]
+    lib.csv_profile_begin.argtypes = [vp, ci]
+    lib.csv_profile_end.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(ci)]
+    return lib
+
+
+lib = _load()
+
+
+class CsvError(RuntimeError):
+    def __init__(self, code: int):
+        self.code = code
+        super().__init__(f"csv error {code}: {lib.csv_last_error().decode()}")
+
+
+def _check(rc: int) -> None:
+    if rc != 0:
+        raise CsvError(rc)
+
+
+def _stream(stream=None) -> int:
+    s = torch.cuda.current_stream() if stream is None else stream
+    return s.cuda_stream
+
+
+def _dev2(t: torch.Tensor, what: str) -> torch.Tensor:
+    if not t.is_cuda or t.element_size() != 2 or not t.is_contiguous():
+        raise ValueError(f"{what} must be a contiguous 16-bit (bf16 pattern) CUDA tensor")
+    return t
+
+
+class CsvIndex:
+    """Owner of a csv_index handle."""
+
+    def __init__(self, handle: int):
+        self._h = C.c_void_p(handle)
+        V, d, Cc = C.c_int(), C.c_int(), C.c_int()
+        _check(lib.csv_index_dims(self._h, C.byref(V), C.byref(d), C.byref(Cc)))
+        self.V, self.d, self.C = V.value, d.value, Cc.value
+
+    def export(self) -> dict:
+        import numpy as np
+        mu = np.empty((self.C, self.d), np.float32)
+        R = np.empty(self.C, np.float32)
+        bmax = np.empty(self.C, np.float32)
+        n = np.empty(self.C, np.int32)
+        perm = np.empty(self.V, np.int32)
+        _check(lib.csv_index_export(self._h, mu.ctypes.data, R.ctypes.data, bmax.ctypes.data, n.ctypes.data,
+                                    perm.ctypes.data))
+        return {"mu": mu, "R": R, "bmax": bmax, "n": n, "perm": perm}
+
+    def free(self) -> None:
+        if self._h:
+            lib.csv_index_free(self._h)
+            self._h = C.c_void_p(0)
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+def csv_build_index(W: torch.Tensor, b, C_clusters: int, init_labels=None, init_rows=None, iters: int = 0,
+                    radius_slack: float = 2.0 ** -14, stream=None) -> CsvIndex:
+    """W: [V,d] 16-bit CUDA tensor (bf16 patterns, original token order); b: float32 CUDA [V] or None.
+    init_labels / init_rows: host int32 numpy arrays (see csv_build_opts)."""
+    import numpy as np
+    _dev2(W, "W")
+    V, d = W.shape
+    keep = []
+    opts = BuildOpts(iters=iters, h_init_labels=None, h_init_rows=None, radius_slack=radius_slack)
+    if init_labels is not None:
+        a = np.ascontiguousarray(init_labels, dtype=np.int32)
+        assert a.shape == (V,)
+        keep.append(a)
+        opts.h_init_labels = a.ctypes.data
+    if init_rows is not None:
+        a = np.ascontiguousarray(init_rows, dtype=np.int32)
+        assert a.shape == (C_clusters,)
+        keep.append(a)
+        opts.h_init_rows = a.ctypes.data
+    out = C.c_void_p()
+    bptr = None if b is None else b.data_ptr()
+    if b is not None:
+        assert b.is_cuda and b.dtype == torch.float32 and b.is_contiguous() and b.numel() == V
+    _check(lib.csv_build_index(W.data_ptr(), bptr, V, d, C_clusters, C.byref(opts), _stream(stream), C.byref(out)))
+    return CsvIndex(out.value)
+
+
+def csv_index_from_arrays(W: torch.Tensor, b, mu, R, bmax, n, perm, stream=None) -> CsvIndex:
+    """Import metadata computed elsewhere (host numpy arrays)."""
+    import numpy as np
+    _dev2(W, "W")
+    V, d = W.shape
+    mu = np.ascontiguousarray(mu, dtype=np.float32)
+    R = np.ascontiguousarray(R, dtype=np.float32)
+    bmax = np.ascontiguousarray(bmax, dtype=np.float32)
+    n = np.ascontiguousarray(n, dtype=np.int32)
+    perm = np.ascontiguousarray(perm, dtype=np.int32)
+    Cc = mu.shape[0]
+    assert mu.shape == (Cc, d) and R.shape == (Cc,) and bmax.shape == (Cc,) and n.shape == (Cc,) and perm.shape == (V,)
+    out = C.c_void_p()
+    bptr = None if b is None else b.data_ptr()
+    _check(lib.csv_index_from_arrays(W.data_ptr(), bptr, V, d, Cc, mu.ctypes.data, R.ctypes.data, bmax.ctypes.data,
+                                     n.ctypes.data, perm.ctypes.data, _stream(stream), C.byref(out)))
+    return CsvIndex(out.value)
+
+
+class CsvWorkspace:
+    def __init__(self, index: CsvIndex, B_max: int, K_cap_rows: int):
+        out = C.c_void_p()
+        _check(lib.csv_workspace_create(index._h, B_max, K_cap_rows, C.byref(out)))
+        self._h = out
+        self.index = index
+        self.B_max, self.K_cap = B_max, K_cap_rows
+
+    def profile_begin(self, max_steps: int) -> None:
+        _check(lib.csv_profile_begin(self._h, max_steps))
+
+    def profile_end(self) -> tuple[dict, int]:
+        """(summed milliseconds per stage, recorded steps)."""
+        ms = (C.c_float * len(PROFILE_STAGES))()
+        n = C.c_int()
+        _check(lib.csv_profile_end(self._h, ms, C.byref(n)))
+        return dict(zip(PROFILE_STAGES, list(ms))), n.value
+
+    def free(self) -> None:
+        if self._h:
+            lib.csv_workspace_free(self._h)
+            self._h = C.c_void_p(0)
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+@dataclass
+class StepBuffers:
+    """Device output buffers of csv_decode_step plus the ctypes structs that point at them."""
+    ids: torch.Tensor
+    logits: torch.Tensor
+    lse: torch.Tensor
+    flags: torch.Tensor
+    n_rows: torch.Tensor
+    n_clusters: torch.Tensor
+    rounds: torch.Tensor
+    sel_clusters: torch.Tensor | None
+    fallback_count: torch.Tensor
+    params: StepParams
+    out: StepOut
+
+
+def make_step_buffers(index: CsvIndex, B: int, k: int, eps: float, K_max_rows: int, combine: int = COMBINE_ALL,
+                      want_sel: bool = False, device="cuda") -> StepBuffers:
+    kk = max(k, 1)
+    ids = torch.full((B, kk), -2, dtype=torch.int32, device=device)
+    logits = torch.zeros((B, kk), dtype=torch.float32, device=device)
+    lse = torch.zeros(B, dtype=torch.float32, device=device)
+    flags = torch.zeros(B, dtype=torch.int32, device=device)
+    n_rows = torch.zeros(B, dtype=torch.int32, device=device)
+    n_clusters = torch.zeros(B, dtype=torch.int32, device=device)
+    rounds = torch.zeros(B, dtype=torch.int32, device=device)
+    sel = torch.full((B, index.C), -1, dtype=torch.int32, device=device) if want_sel else None
+    fbc = torch.zeros(1, dtype=torch.int64, device=device)
+    params = StepParams(k=k, eps=eps, K_max_rows=K_max_rows, combine=combine)
+    out = StepOut(ids.data_ptr(), logits.data_ptr(), lse.data_ptr(), flags.data_ptr(), n_rows.data_ptr(),
+                  n_clusters.data_ptr(), rounds.data_ptr(), sel.data_ptr() if want_sel else None, fbc.data_ptr())
+    return StepBuffers(ids, logits, lse, flags, n_rows, n_clusters, rounds, sel, fbc, params, out)
+
+
+def csv_decode_step(ws: CsvWorkspace, index: CsvIndex, h: torch.Tensor, buf: StepBuffers, stream=None) -> StepBuffers:
+    """Enqueue one certified decode step for h [B,d] (bf16 patterns).  Results land in `buf` after a stream sync."""
+    _dev2(h, "h")
+    B = h.shape[0]
+    _check(lib.csv_decode_step(ws._h, index._h, h.data_ptr(), B, C.byref(buf.params), C.byref(buf.out), _stream(stream)))
+    return buf
+
+
+def csv_decode_step_raw(ws: CsvWorkspace, index: CsvIndex, h_ptr: int, B: int, buf: StepBuffers, stream_ptr: int) -> None:
+    """Same call with a raw device pointer and stream handle (tight loops: no tensor checks)."""
+    rc = lib.csv_decode_step(ws._h, index._h, h_ptr, B, C.byref(buf.params), C.byref(buf.out), stream_ptr)
+    if rc:
+        raise CsvError(rc)
+
+
+def csv_bounds(ws: CsvWorkspace, index: CsvIndex, h: torch.Tensor, stream=None):
+    _dev2(h, "h")
+    B = h.shape[0]
+    U = torch.empty((B, index.C), dtype=torch.float32, device=h.device)
+    hn = torch.empty(B, dtype=torch.float32, device=h.device)
+    _check(lib.csv_bounds(ws._h, index._h, h.data_ptr(), B, U.data_ptr(), hn.data_ptr(), _stream(stream)))
+    return U, hn
+
+
+def csv_full_logits(ws: CsvWorkspace, index: CsvIndex, h: torch.Tensor, out: torch.Tensor | None = None, stream=None):
+    _dev2(h, "h")
+    B = h.shape[0]
+    if out is None:
+        out = torch.empty((B, index.V), dtype=torch.float32, device=h.device)
+    _check(lib.csv_full_logits(ws._h, index._h, h.data_ptr(), B, out.data_ptr(), _stream(stream)))
+    return out
+
+
+def bits_to_device(bits) -> torch.Tensor:
+    """numpy uint16 bf16 patterns -> CUDA int16 tensor with the same bits."""
+    import numpy as np
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda()

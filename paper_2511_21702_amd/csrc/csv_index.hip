@@ -1,0 +1,384 @@
+// Offline preprocessing: Lloyd's k-means over the rows of W, cluster metadata (centroid, radius, bias maximum)
+// and the row permutation that makes every cluster contiguous (Section III-A.1; Section IV "Offline Preprocessing").
+// Off the per-step hot path: clarity over speed, float64 accumulation for the metadata.
+#include "csv_common.h"
+
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include <vector>
+
+// ------------------------------------------------------------------------------------------------ kernels
+// W'[r] = W[perm[r]], b'[r] = b[perm[r]] (0 without bias).  One block per permuted row.
+__global__ __launch_bounds__(256) void gather_rows_kernel(const uint16_t* __restrict__ W, const float* __restrict__ b,
+                                                          const int32_t* __restrict__ perm, int V, int d,
+                                                          uint16_t* __restrict__ Wp, float* __restrict__ bp) {
+    const int r = blockIdx.x;
+    if (r >= V) return;
+    const int src = perm[r];
+    const uint4* s = reinterpret_cast<const uint4*>(W + (size_t)src * d);
+    uint4* t = reinterpret_cast<uint4*>(Wp + (size_t)r * d);
+    for (int i = threadIdx.x; i < (d >> 3); i += 256) t[i] = s[i];
+    if (threadIdx.x == 0) bp[r] = b ? b[src] : 0.f;
+}
+
+// mu_c = mean of the cluster's rows, accumulated in float64 row by row, stored as float32.
+// An empty cluster keeps its centroid (Lloyd) or is zeroed (final metadata).
+__global__ __launch_bounds__(256) void centroid_kernel(const uint16_t* __restrict__ Wp, const int32_t* __restrict__ off, int d,
+                                                       int zero_empty, float* __restrict__ mu) {
+    const int c = blockIdx.x;
+    const int col = blockIdx.y * 256 + threadIdx.x;
+    if (col >= d) return;
+    const int r0 = off[c], r1 = off[c + 1];
+    if (r1 == r0) {
+        if (zero_empty) mu[(size_t)c * d + col] = 0.f;
+        return;
+    }
+    double sum = 0.0;
+    for (int r = r0; r < r1; ++r) sum += (double)__uint_as_float((uint32_t)Wp[(size_t)r * d + col] << 16);
+    mu[(size_t)c * d + col] = (float)(sum / (double)(r1 - r0));
+}
+
+__device__ __forceinline__ double wave_sum_d(double v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, CSV_WAVE);
+    return v;
+}
+
+// R_c = max_i ||W_i - mu_c||_2 to the stored float32 centroid, in float64; stored radius
+// roundup_f32(R_c (1+rho) + rho ||mu_c||); bias maximum; ln n_c.  One block per cluster.
+__global__ __launch_bounds__(256) void radius_kernel(const uint16_t* __restrict__ Wp, const float* __restrict__ bp,
+                                                     const int32_t* __restrict__ off, const float* __restrict__ mu, int d,
+                                                     double rho, float* __restrict__ R, float* __restrict__ bmax,
+                                                     float* __restrict__ lnn) {
+    __shared__ double wmax[4];
+    __shared__ float wb[4];
+    __shared__ double mun2;
+    const int c = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int r0 = off[c], r1 = off[c + 1];
+    const float* m = mu + (size_t)c * d;
+    double best = 0.0;
+    for (int r = r0 + wave; r < r1; r += 4) {
+        const uint16_t* w = Wp + (size_t)r * d;
+        double acc = 0.0;
+        for (int j = lane; j < d; j += 64) {
+            const double diff = (double)__uint_as_float((uint32_t)w[j] << 16) - (double)m[j];
+            acc += diff * diff;
+        }
+        acc = wave_sum_d(acc);
+        best = fmax(best, acc);
+    }
+    float bm = -INFINITY;
+    for (int r = r0 + tid; r < r1; r += 256) bm = fmaxf(bm, bp[r]);
+    bm = wave_max(bm);
+    if (wave == 0) {
+        double acc = 0.0;
+        for (int j = lane; j < d; j += 64) acc += (double)m[j] * (double)m[j];
+        acc = wave_sum_d(acc);
+        if (lane == 0) mun2 = acc;
+    }
+    if (lane == 0) {
+        wmax[wave] = best;
+        wb[wave] = bm;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        const int n = r1 - r0;
+        if (n == 0) {
+            R[c] = 0.f;
+            bmax[c] = -INFINITY;
+            lnn[c] = -INFINITY;
+        } else {
+            const double d2 = fmax(fmax(wmax[0], wmax[1]), fmax(wmax[2], wmax[3]));
+            const double x = sqrt(d2) * (1.0 + rho) + rho * sqrt(mun2);
+            float y = (float)x;
+            if ((double)y < x) y = nextafterf(y, INFINITY);
+            R[c] = y;
+            bmax[c] = fmaxf(fmaxf(wb[0], wb[1]), fmaxf(wb[2], wb[3]));
+            lnn[c] = (float)log((double)n);
+        }
+    }
+}
+
+// Lloyd assignment: labels[i] = argmin_c sum_j (W_ij - mu_cj)^2, ties to the smaller cluster id.
+// A block owns 64 rows and walks all clusters 64 at a time; each thread holds a 4x4 patch of distances.
+#define AS_TM 64
+#define AS_TN 64
+#define AS_TK 32
+__global__ __launch_bounds__(256) void assign_kernel(const uint16_t* __restrict__ W, const float* __restrict__ mu, int V, int d,
+                                                     int C, int32_t* __restrict__ labels) {
+    __shared__ float Ws[AS_TK][AS_TM + 4];
+    __shared__ float Ms[AS_TK][AS_TN + 4];
+    __shared__ float bd[AS_TM][17];
+    __shared__ int bi[AS_TM][17];
+    const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+    const int row0 = blockIdx.x * AS_TM;
+    float best[4];
+    int besti[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        best[i] = INFINITY;
+        besti[i] = 0x7fffffff;
+    }
+    const int lr = tid >> 2, lc = (tid & 3) * 8;
+    for (int c0 = 0; c0 < C; c0 += AS_TN) {
+        float acc[4][4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc[i][j] = 0.f;
+        for (int k0 = 0; k0 < d; k0 += AS_TK) {
+            __syncthreads();
+            {
+                const int gr = row0 + lr, col = k0 + lc;
+                uint4 v = make_uint4(0, 0, 0, 0);
+                if (gr < V && col < d) v = *reinterpret_cast<const uint4*>(W + (size_t)gr * d + col);
+                Ws[lc + 0][lr] = bf16_lo(v.x); Ws[lc + 1][lr] = bf16_hi(v.x);
+                Ws[lc + 2][lr] = bf16_lo(v.y); Ws[lc + 3][lr] = bf16_hi(v.y);
+                Ws[lc + 4][lr] = bf16_lo(v.z); Ws[lc + 5][lr] = bf16_hi(v.z);
+                Ws[lc + 6][lr] = bf16_lo(v.w); Ws[lc + 7][lr] = bf16_hi(v.w);
+                const int gc = c0 + lr;
+                float4 m0 = make_float4(0, 0, 0, 0), m1 = m0;
+                if (gc < C && col < d) {
+                    const float4* p = reinterpret_cast<const float4*>(mu + (size_t)gc * d + col);
+                    m0 = p[0];
+                    m1 = p[1];
+                }
+                Ms[lc + 0][lr] = m0.x; Ms[lc + 1][lr] = m0.y; Ms[lc + 2][lr] = m0.z; Ms[lc + 3][lr] = m0.w;
+                Ms[lc + 4][lr] = m1.x; Ms[lc + 5][lr] = m1.y; Ms[lc + 6][lr] = m1.z; Ms[lc + 7][lr] = m1.w;
+            }
+            __syncthreads();
+#pragma unroll 8
+            for (int kk = 0; kk < AS_TK; ++kk) {
+                float w[4], m[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) w[i] = Ws[kk][ty * 4 + i];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) m[j] = Ms[kk][tx * 4 + j];
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const float df = w[i] - m[j];
+                        acc[i][j] = fmaf(df, df, acc[i][j]);
+                    }
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int gc = c0 + tx * 4 + j;
+            if (gc < C) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (acc[i][j] < best[i]) {
+                        best[i] = acc[i][j];
+                        besti[i] = gc;
+                    }
+            }
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        bd[ty * 4 + i][tx] = best[i];
+        bi[ty * 4 + i][tx] = besti[i];
+    }
+    __syncthreads();
+    if (tid < AS_TM && row0 + tid < V) {
+        float b = bd[tid][0];
+        int id = bi[tid][0];
+        for (int t = 1; t < 16; ++t) {
+            const float x = bd[tid][t];
+            const int xi = bi[tid][t];
+            if (x < b || (x == b && xi < id)) {
+                b = x;
+                id = xi;
+            }
+        }
+        labels[row0 + tid] = id;
+    }
+}
+
+// mu[c] = row init_rows[c] of W widened to float32 (starting centroids).
+__global__ __launch_bounds__(256) void init_centroid_kernel(const uint16_t* __restrict__ W, const int32_t* __restrict__ rows,
+                                                            int d, float* __restrict__ mu) {
+    const int c = blockIdx.x;
+    const uint16_t* w = W + (size_t)rows[c] * d;
+    for (int j = threadIdx.x; j < d; j += 256) mu[(size_t)c * d + j] = __uint_as_float((uint32_t)w[j] << 16);
+}
+
+// ------------------------------------------------------------------------------------------------ host side
+static int check_shape(int V, int d, int C) {
+    if (V < 1 || d < 8 || (d & 7) != 0) { csv_set_error("need V >= 1 and d a positive multiple of 8 (V=%d, d=%d)", V, d); return CSV_ESHAPE; }
+    if (C < 1 || C > V || C > CSV_MAX_CLUSTERS) { csv_set_error("C=%d outside 1..min(V,%d)", C, CSV_MAX_CLUSTERS); return CSV_ESHAPE; }
+    return CSV_OK;
+}
+
+int csv_index_alloc(int V, int d, int C, csv_index** out) {
+    csv_index* x = (csv_index*)calloc(1, sizeof(csv_index));
+    if (!x) { csv_set_error("host allocation failed"); return CSV_ENOMEM; }
+    x->V = V; x->d = d; x->C = C;
+    hipError_t e = hipGetDevice(&x->device);
+    auto A = [&](void** p, size_t bytes) { if (e == hipSuccess) e = hipMalloc(p, bytes); };
+    A((void**)&x->Wp, (size_t)V * d * 2); A((void**)&x->bp, (size_t)V * 4); A((void**)&x->perm, (size_t)V * 4);
+    A((void**)&x->mu, (size_t)C * d * 4); A((void**)&x->R, (size_t)C * 4); A((void**)&x->bmax, (size_t)C * 4);
+    A((void**)&x->n, (size_t)C * 4); A((void**)&x->off, (size_t)(C + 1) * 4); A((void**)&x->lnn, (size_t)C * 4);
+    if (e != hipSuccess) {
+        csv_set_error("index allocation failed: %s", hipGetErrorString(e));
+        csv_index_free(x);
+        return e == hipErrorOutOfMemory ? CSV_ENOMEM : CSV_EHIP;
+    }
+    *out = x;
+    return CSV_OK;
+}
+
+extern "C" void csv_index_free(csv_index* x) {
+    if (!x) return;
+    void* ptrs[] = {x->Wp, x->bp, x->perm, x->mu, x->R, x->bmax, x->n, x->off, x->lnn};
+    for (void* p : ptrs)
+        if (p) (void)hipFree(p);
+    free(x);
+}
+
+extern "C" int csv_index_dims(const csv_index* x, int* V, int* d, int* C) {
+    if (!x) { csv_set_error("null index"); return CSV_EINVAL; }
+    if (V) *V = x->V;
+    if (d) *d = x->d;
+    if (C) *C = x->C;
+    return CSV_OK;
+}
+
+// labels -> sizes, offsets and the permutation (clusters in id order, tokens by ascending id inside a cluster)
+static int layout_from_labels(const int32_t* labels, int V, int C, std::vector<int32_t>& n, std::vector<int32_t>& off,
+                              std::vector<int32_t>& perm) {
+    n.assign(C, 0);
+    for (int i = 0; i < V; ++i) {
+        if (labels[i] < 0 || labels[i] >= C) { csv_set_error("label %d of token %d outside 0..C-1", labels[i], i); return CSV_EINVAL; }
+        n[labels[i]]++;
+    }
+    off.assign(C + 1, 0);
+    for (int c = 0; c < C; ++c) off[c + 1] = off[c] + n[c];
+    perm.resize(V);
+    std::vector<int32_t> cur(off.begin(), off.end() - 1);
+    for (int i = 0; i < V; ++i) perm[cur[labels[i]]++] = i;
+    return CSV_OK;
+}
+
+static int upload_layout(csv_index* x, const std::vector<int32_t>& n, const std::vector<int32_t>& off,
+                         const std::vector<int32_t>& perm, hipStream_t st) {
+    CSV_HIP(hipMemcpyAsync(x->n, n.data(), (size_t)x->C * 4, hipMemcpyHostToDevice, st));
+    CSV_HIP(hipMemcpyAsync(x->off, off.data(), (size_t)(x->C + 1) * 4, hipMemcpyHostToDevice, st));
+    CSV_HIP(hipMemcpyAsync(x->perm, perm.data(), (size_t)x->V * 4, hipMemcpyHostToDevice, st));
+    CSV_HIP(hipStreamSynchronize(st));   // the host vectors may go away after this
+    return CSV_OK;
+}
+
+static int gather(csv_index* x, const uint16_t* d_W, const float* d_b, hipStream_t st) {
+    gather_rows_kernel<<<x->V, 256, 0, st>>>(d_W, d_b, x->perm, x->V, x->d, x->Wp, x->bp);
+    CSV_LAUNCH_CHECK("gather_rows_kernel");
+    return CSV_OK;
+}
+
+extern "C" int csv_build_index(const uint16_t* d_W, const float* d_b, int V, int d, int C, const csv_build_opts* o,
+                               void* stream, csv_index** out) {
+    if (out) *out = nullptr;
+    if (!d_W || !o || !out) { csv_set_error("null W, opts or out"); return CSV_EINVAL; }
+    int rc = check_shape(V, d, C);
+    if (rc) return rc;
+    if (o->iters < 0 || !(o->radius_slack >= 0.f)) { csv_set_error("iters and radius_slack must be >= 0"); return CSV_EINVAL; }
+    if (!o->h_init_labels && !o->h_init_rows) { csv_set_error("need h_init_labels or h_init_rows"); return CSV_EINVAL; }
+    hipStream_t st = (hipStream_t)stream;
+    csv_index* x = nullptr;
+    rc = csv_index_alloc(V, d, C, &x);
+    if (rc) return rc;
+    int32_t* d_labels = nullptr;
+    std::vector<int32_t> labels(V), n, off, perm;
+    auto fail = [&](int code) {
+        if (d_labels) (void)hipFree(d_labels);
+        csv_index_free(x);
+        return code;
+    };
+    if (hipMalloc((void**)&d_labels, (size_t)V * 4) != hipSuccess) { csv_set_error("label buffer allocation failed"); return fail(CSV_ENOMEM); }
+    const dim3 cgrid(C, (d + 255) / 256);
+    auto assign = [&]() -> int {
+        assign_kernel<<<(V + AS_TM - 1) / AS_TM, 256, 0, st>>>(d_W, x->mu, V, d, C, d_labels);
+        CSV_LAUNCH_CHECK("assign_kernel");
+        CSV_HIP(hipMemcpyAsync(labels.data(), d_labels, (size_t)V * 4, hipMemcpyDeviceToHost, st));
+        CSV_HIP(hipStreamSynchronize(st));
+        return CSV_OK;
+    };
+    if (o->h_init_labels) {
+        memcpy(labels.data(), o->h_init_labels, (size_t)V * 4);
+    } else {
+        for (int c = 0; c < C; ++c)
+            if (o->h_init_rows[c] < 0 || o->h_init_rows[c] >= V) { csv_set_error("init row %d outside 0..V-1", o->h_init_rows[c]); return fail(CSV_EINVAL); }
+        // x->n doubles as the staging buffer for the starting rows
+        if (hipMemcpyAsync(x->n, o->h_init_rows, (size_t)C * 4, hipMemcpyHostToDevice, st) != hipSuccess) { csv_set_error("copy of init rows failed"); return fail(CSV_EHIP); }
+        init_centroid_kernel<<<C, 256, 0, st>>>(d_W, x->n, d, x->mu);
+        if ((rc = assign())) return fail(rc);
+    }
+    for (int it = 0;; ++it) {
+        if ((rc = layout_from_labels(labels.data(), V, C, n, off, perm))) return fail(rc);
+        if ((rc = upload_layout(x, n, off, perm, st))) return fail(rc);
+        if ((rc = gather(x, d_W, d_b, st))) return fail(rc);
+        const bool last = it == o->iters;
+        centroid_kernel<<<cgrid, 256, 0, st>>>(x->Wp, x->off, d, last ? 1 : 0, x->mu);
+        if (hipGetLastError() != hipSuccess) { csv_set_error("launch of centroid_kernel failed"); return fail(CSV_EHIP); }
+        if (last) break;
+        if ((rc = assign())) return fail(rc);
+    }
+    radius_kernel<<<C, 256, 0, st>>>(x->Wp, x->bp, x->off, x->mu, d, (double)o->radius_slack, x->R, x->bmax, x->lnn);
+    if (hipGetLastError() != hipSuccess) { csv_set_error("launch of radius_kernel failed"); return fail(CSV_EHIP); }
+    if (hipStreamSynchronize(st) != hipSuccess) { csv_set_error("index build failed on the device: %s", hipGetErrorString(hipGetLastError())); return fail(CSV_EHIP); }
+    (void)hipFree(d_labels);
+    *out = x;
+    return CSV_OK;
+}
+
+extern "C" int csv_index_from_arrays(const uint16_t* d_W, const float* d_b, int V, int d, int C, const float* h_mu,
+                                     const float* h_R, const float* h_bmax, const int32_t* h_n, const int32_t* h_perm,
+                                     void* stream, csv_index** out) {
+    if (out) *out = nullptr;
+    if (!d_W || !h_mu || !h_R || !h_bmax || !h_n || !h_perm || !out) { csv_set_error("null argument"); return CSV_EINVAL; }
+    int rc = check_shape(V, d, C);
+    if (rc) return rc;
+    std::vector<int32_t> n(h_n, h_n + C), off(C + 1, 0), perm(h_perm, h_perm + V);
+    std::vector<float> lnn(C);
+    for (int c = 0; c < C; ++c) {
+        if (n[c] < 0) { csv_set_error("negative cluster size"); return CSV_EINVAL; }
+        off[c + 1] = off[c] + n[c];
+        lnn[c] = n[c] > 0 ? (float)log((double)n[c]) : -INFINITY;
+    }
+    if (off[C] != V) { csv_set_error("cluster sizes sum to %d, not V=%d", off[C], V); return CSV_EINVAL; }
+    std::vector<char> seen(V, 0);
+    for (int i = 0; i < V; ++i) {
+        if (perm[i] < 0 || perm[i] >= V || seen[perm[i]]) { csv_set_error("h_perm is not a permutation of 0..V-1"); return CSV_EINVAL; }
+        seen[perm[i]] = 1;
+    }
+    hipStream_t st = (hipStream_t)stream;
+    csv_index* x = nullptr;
+    rc = csv_index_alloc(V, d, C, &x);
+    if (rc) return rc;
+    auto fail = [&](int code) { csv_index_free(x); return code; };
+    hipError_t e = hipMemcpyAsync(x->mu, h_mu, (size_t)C * d * 4, hipMemcpyHostToDevice, st);
+    if (e == hipSuccess) e = hipMemcpyAsync(x->R, h_R, (size_t)C * 4, hipMemcpyHostToDevice, st);
+    if (e == hipSuccess) e = hipMemcpyAsync(x->bmax, h_bmax, (size_t)C * 4, hipMemcpyHostToDevice, st);
+    if (e == hipSuccess) e = hipMemcpyAsync(x->lnn, lnn.data(), (size_t)C * 4, hipMemcpyHostToDevice, st);
+    if (e != hipSuccess) { csv_set_error("metadata upload failed: %s", hipGetErrorString(e)); return fail(CSV_EHIP); }
+    if ((rc = upload_layout(x, n, off, perm, st))) return fail(rc);
+    if ((rc = gather(x, d_W, d_b, st))) return fail(rc);
+    if (hipStreamSynchronize(st) != hipSuccess) { csv_set_error("index import failed on the device"); return fail(CSV_EHIP); }
+    *out = x;
+    return CSV_OK;
+}
+
+extern "C" int csv_index_export(const csv_index* x, float* h_mu, float* h_R, float* h_bmax, int32_t* h_n, int32_t* h_perm) {
+    if (!x) { csv_set_error("null index"); return CSV_EINVAL; }
+    if (h_mu) CSV_HIP(hipMemcpy(h_mu, x->mu, (size_t)x->C * x->d * 4, hipMemcpyDeviceToHost));
+    if (h_R) CSV_HIP(hipMemcpy(h_R, x->R, (size_t)x->C * 4, hipMemcpyDeviceToHost));
+    if (h_bmax) CSV_HIP(hipMemcpy(h_bmax, x->bmax, (size_t)x->C * 4, hipMemcpyDeviceToHost));
+    if (h_n) CSV_HIP(hipMemcpy(h_n, x->n, (size_t)x->C * 4, hipMemcpyDeviceToHost));
+    if (h_perm) CSV_HIP(hipMemcpy(h_perm, x->perm, (size_t)x->V * 4, hipMemcpyDeviceToHost));
+    return CSV_OK;
+}

@@ -1,0 +1,1039 @@
+// Per-step kernels of the certified sub-vocabulary LM-head path and the entry points that enqueue them.
+//
+//   bound_kernel        U[b,c] = <mu_c,h_b> + R_c ||h_b|| + bmax_c              (Eq. "cluster_bound")
+//   select0_kernel      order clusters by bound, prefix rows P, log tail mass T, seed prefix m0   (Algorithm 1: queue)
+//   gemv_gather_kernel  logits of the opened rows of W' (contiguous per cluster)                   (Algorithm 1: sparse GEMV)
+//   cert_kernel         k-th largest / top-k, log-sum-exp, both certificates, round-1 plan          (Definitions 1-2, Theorems 1-2)
+//   full_gemv_kernel    all V logits for the sequences that fall back                               (Eq. "logit")
+//   fb_topk_kernel / fb_final_kernel   top-k and log-sum-exp over V for those sequences
+//
+// Everything is enqueued on the caller's stream; decisions (round 1, fallback) are taken on the device.
+#include "csv_common.h"
+
+#include <math.h>
+#include <stdarg.h>
+#include <string.h>
+
+// ------------------------------------------------------------------------------------------------ errors
+static thread_local char g_err[512] = "";
+void csv_set_error(const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+extern "C" const char* csv_last_error(void) { return g_err; }
+
+// ------------------------------------------------------------------------------------------------ arguments
+struct StepArgs {
+    int V, d, C;
+    const uint16_t* Wp;
+    const float* bp;
+    const int32_t* perm;
+    const float* mu;
+    const float* R;
+    const float* bmax;
+    const int32_t* n;
+    const int32_t* off;
+    const float* lnn;
+    int B, K_cap, Npad, n_chunks;
+    float* U;
+    float* hnorm;
+    int32_t* order;
+    float* su;
+    float* T;
+    int32_t* P;
+    SeqState* st;
+    int32_t* rstart;
+    int32_t* rcount;
+    float* slog;
+    int32_t* rowmap;
+    int32_t* counters;
+    int32_t* fb_list;
+    float* fb_logits;
+    float* cand_val;
+    int32_t* cand_id;
+    float* cand_max;
+    float* cand_sum;
+    const uint16_t* h;
+    int k, K_max, combine, use_k, use_s;
+    float lam;   // ln(eps/(1-eps)); +inf when eps >= 1
+    csv_step_out out;
+};
+
+#define GEMV_ROWS_PER_WAVE 2
+#define GEMV_TILE (4 * GEMV_ROWS_PER_WAVE)   // rows per work item of the gathered GEMV (4 waves per block)
+#define FB_CHUNK 8192                        // rows per block of the fallback top-k first stage
+#define FULL_G 4                             // sequences per pass of the vector full-vocabulary product
+
+// ================================================================================================ bounds
+// One wave per cluster, BT sequences per block.  h is staged in LDS as bf16; centroids stream as float4.
+// Blocks are dealt round-robin to the 8 XCDs, so group g = (block % 8) * groups_per_xcd + block / 8 keeps
+// every XCD on the same centroid slice step after step (the slice stays resident in that XCD's L2).
+template <int BT>
+__global__ __launch_bounds__(256) void bound_kernel(StepArgs a, float* __restrict__ U_out, float* __restrict__ hn_out,
+                                                    int reset_counters, int groups, int groups_per_xcd) {
+    extern __shared__ uint4 hs4[];
+    __shared__ float hn[BT];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int b0 = blockIdx.y * BT;
+    const int nb = min(BT, a.B - b0);
+    const int nch = a.d >> 3;
+    const uint4* hsrc = reinterpret_cast<const uint4*>(a.h) + (size_t)b0 * nch;
+    for (int i = tid; i < BT * nch; i += 256) hs4[i] = (i < nb * nch) ? hsrc[i] : make_uint4(0, 0, 0, 0);
+    if (reset_counters && blockIdx.x == 0 && blockIdx.y == 0 && tid < 16) a.counters[tid] = 0;
+    __syncthreads();
+    for (int s = wave; s < BT; s += 4) {
+        float acc = 0.f;
+        for (int i = lane; i < nch; i += 64) {
+            uint4 v = hs4[s * nch + i];
+            acc = dot8_bf16(v, v, acc);
+        }
+        acc = wave_sum(acc);
+        if (lane == 0) hn[s] = sqrtf(acc);
+    }
+    __syncthreads();
+    if (blockIdx.x == 0 && tid < nb && hn_out) hn_out[b0 + tid] = hn[tid];
+
+    const int g = (blockIdx.x & 7) * groups_per_xcd + (blockIdx.x >> 3);
+    if (g >= groups || (blockIdx.x >> 3) >= groups_per_xcd) return;
+    const int c = g * 4 + wave;
+    if (c >= a.C) return;
+    const float4* mrow = reinterpret_cast<const float4*>(a.mu + (size_t)c * a.d);
+    const uint2* hs2 = reinterpret_cast<const uint2*>(hs4);
+    const int nq = a.d >> 2;
+    float acc[BT];
+#pragma unroll
+    for (int s = 0; s < BT; ++s) acc[s] = 0.f;
+#pragma unroll 4
+    for (int i = lane; i < nq; i += 64) {
+        const float4 m = mrow[i];
+#pragma unroll
+        for (int s = 0; s < BT; ++s) {
+            const uint2 hv = hs2[s * nq + i];
+            acc[s] = fmaf(m.x, bf16_lo(hv.x), acc[s]);
+            acc[s] = fmaf(m.y, bf16_hi(hv.x), acc[s]);
+            acc[s] = fmaf(m.z, bf16_lo(hv.y), acc[s]);
+            acc[s] = fmaf(m.w, bf16_hi(hv.y), acc[s]);
+        }
+    }
+#pragma unroll
+    for (int s = 0; s < BT; ++s) acc[s] = wave_sum(acc[s]);
+    if (lane == 0) {
+        const float Rc = a.R[c], bm = a.bmax[c];
+        const bool empty = a.n[c] == 0;
+#pragma unroll
+        for (int s = 0; s < BT; ++s)
+            if (s < nb) U_out[(size_t)(b0 + s) * a.C + c] = empty ? -INFINITY : (acc[s] + Rc * hn[s] + bm);
+    }
+}
+
+// ================================================================================================ block scans
+// Exclusive prefix sum over one int per thread (blockDim <= 1024).  wtot: 17 ints of LDS.
+__device__ __forceinline__ int block_excl_scan_i(int v, int* wtot, int* total) {
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+    int x = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        int y = __shfl_up(x, o, CSV_WAVE);
+        if (lane >= o) x += y;
+    }
+    __syncthreads();
+    if (lane == 63) wtot[w] = x;
+    __syncthreads();
+    int base = 0, tot = 0;
+    for (int i = 0; i < nw; ++i) {
+        if (i < w) base += wtot[i];
+        tot += wtot[i];
+    }
+    if (total) *total = tot;
+    return base + x - v;
+}
+
+// Combination of everything owned by the threads AFTER this one (exclusive suffix), for log-sum-exp partials.
+__device__ __forceinline__ LseAcc block_excl_suffix_lse(LseAcc v, LseAcc* wtot) {
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+    LseAcc x = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        LseAcc y;
+        y.m = __shfl_down(x.m, o, CSV_WAVE);
+        y.s = __shfl_down(x.s, o, CSV_WAVE);
+        if (lane + o < 64) x = lse_combine(x, y);
+    }
+    // x = combination of lanes lane..63 of this wave
+    LseAcc after;
+    after.m = __shfl_down(x.m, 1, CSV_WAVE);
+    after.s = __shfl_down(x.s, 1, CSV_WAVE);
+    if (lane == 63) {
+        after.m = -INFINITY;
+        after.s = 0.f;
+    }
+    __syncthreads();
+    if (lane == 0) wtot[w] = x;
+    __syncthreads();
+    LseAcc tail;
+    tail.m = -INFINITY;
+    tail.s = 0.f;
+    for (int i = nw - 1; i > w; --i) tail = lse_combine(wtot[i], tail);
+    return lse_combine(after, tail);
+}
+
+// ================================================================================================ helpers shared by select/cert
+__device__ __forceinline__ void write_invalid(const StepArgs& a, int b) {
+    for (int t = threadIdx.x; t < a.k; t += blockDim.x) {
+        a.out.d_ids[(size_t)b * a.k + t] = -1;
+        a.out.d_logits[(size_t)b * a.k + t] = NAN;
+    }
+    if (threadIdx.x == 0) {
+        a.out.d_lse[b] = NAN;
+        a.out.d_flags[b] = CSV_FLAG_INVALID_INPUT;
+        a.out.d_n_rows[b] = 0;
+        a.out.d_n_clusters[b] = 0;
+        if (a.out.d_rounds) a.out.d_rounds[b] = 0;
+    }
+}
+
+// Called by one thread: hand sequence b to the full-vocabulary path.
+__device__ __forceinline__ void push_fallback(const StepArgs& a, int b, int rounds) {
+    const int slot = atomicAdd(&a.counters[0], 1);
+    a.fb_list[slot] = b;
+    a.st[b].status = ST_FALLBACK;
+    a.st[b].fb_slot = slot;
+    a.rcount[b] = 0;
+    if (a.out.d_rounds) a.out.d_rounds[b] = rounds;
+}
+
+// Record the permuted row of every position opened by clusters [j0,j1) of sequence b's order (one wave per cluster).
+__device__ __forceinline__ void write_rowmap(const StepArgs& a, int b, int j0, int j1) {
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, nw = blockDim.x >> 6;
+    for (int j = j0 + w; j < j1; j += nw) {
+        const int c = a.order[(size_t)b * a.C + j];
+        const int p0 = a.P[(size_t)b * (a.C + 1) + j];
+        const int r0 = a.off[c], nc = a.n[c];
+        int32_t* dst = a.rowmap + (size_t)b * a.K_cap + p0;
+        for (int r = lane; r < nc; r += 64) dst[r] = r0 + r;
+    }
+}
+
+// ================================================================================================ select (round 0)
+// One block per sequence.  Sorts (bound, cluster) pairs with a bitonic network on 64-bit keys
+// (monotone image of the bound in the high word, ~cluster id in the low word: descending key order is
+// descending bound, equal bounds by ascending id), then scans row counts and log tail masses.
+__global__ __launch_bounds__(1024) void select0_kernel(StepArgs a) {
+    extern __shared__ unsigned long long keys[];
+    __shared__ int wtot_i[17];
+    __shared__ LseAcc wtot_l[17];
+    __shared__ int s_m0, s_rows0;
+    const int b = blockIdx.x, tid = threadIdx.x, nt = blockDim.x;
+    const int C = a.C, N = a.Npad;
+    const float hn = a.hnorm[b];
+    if (!isfinite(hn)) {
+        write_invalid(a, b);
+        if (tid == 0) {
+            a.st[b].status = ST_INVALID;
+            a.rcount[b] = 0;
+        }
+        return;
+    }
+    for (int i = tid; i < N; i += nt) {
+        unsigned long long kx = 0ull;
+        if (i < C) kx = ((unsigned long long)fkey(a.U[(size_t)b * C + i]) << 32) | (unsigned long long)(0xFFFFFFFFu - (uint32_t)i);
+        keys[i] = kx;
+    }
+    __syncthreads();
+    for (int k2 = 2; k2 <= N; k2 <<= 1) {
+        for (int j = k2 >> 1; j > 0; j >>= 1) {
+            for (int i = tid; i < N; i += nt) {
+                const int ixj = i ^ j;
+                if (ixj > i) {
+                    const unsigned long long x = keys[i], y = keys[ixj];
+                    const bool first_larger = (i & k2) == 0;
+                    if (first_larger ? (x < y) : (x > y)) {
+                        keys[i] = y;
+                        keys[ixj] = x;
+                    }
+                }
+            }
+            __syncthreads();
+        }
+    }
+    // each thread owns E consecutive sorted positions
+    const int E = N >= nt ? N / nt : 1;
+    const int j0 = tid * E;
+    int nloc[8];
+    LseAcc vloc[8];
+    int nsum = 0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        nloc[e] = 0;
+        vloc[e].m = -INFINITY;
+        vloc[e].s = 0.f;
+        const int j = j0 + e;
+        if (e < E && j < C) {
+            const unsigned long long kx = keys[j];
+            const int c = (int)(0xFFFFFFFFu - (uint32_t)kx);
+            const float u = fkey_inv((uint32_t)(kx >> 32));
+            a.order[(size_t)b * C + j] = c;
+            a.su[(size_t)b * C + j] = u;
+            nloc[e] = a.n[c];
+            const float v = a.lnn[c] + u;
+            if (nloc[e] > 0 && v > -INFINITY) {
+                vloc[e].m = v;
+                vloc[e].s = 1.f;
+            }
+        }
+        nsum += nloc[e];
+    }
+    const int base = block_excl_scan_i(nsum, wtot_i, nullptr);
+    // suffix log-sum-exp inside the thread, then across threads
+    LseAcc suf[8];
+    LseAcc run;
+    run.m = -INFINITY;
+    run.s = 0.f;
+#pragma unroll
+    for (int e = 7; e >= 0; --e) {
+        run = lse_combine(vloc[e], run);
+        suf[e] = run;
+    }
+    const LseAcc after = block_excl_suffix_lse(run, wtot_l);
+    const int need = max(a.k, 1);
+    int32_t* Pb = a.P + (size_t)b * (C + 1);
+    float* Tb = a.T + (size_t)b * (C + 1);
+    if (tid == 0) {
+        Pb[0] = 0;
+        Tb[C] = -INFINITY;
+    }
+    int pin = base;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const int j = j0 + e;
+        if (e < E && j < C) {
+            const int pex = pin;
+            pin += nloc[e];
+            Pb[j + 1] = pin;
+            Tb[j] = lse_value(lse_combine(suf[e], after));
+            if (pex < need && pin >= need) {
+                s_m0 = j + 1;
+                s_rows0 = pin;
+            }
+        }
+    }
+    __threadfence_block();
+    __syncthreads();
+    const int m0 = s_m0;
+    const int rows0 = s_rows0;
+    if (rows0 > a.K_max) {
+        if (tid == 0) {
+            a.st[b].m0 = m0;
+            a.st[b].m1 = m0;
+            push_fallback(a, b, 0);
+        }
+        return;
+    }
+    write_rowmap(a, b, 0, m0);
+    if (tid == 0) {
+        a.st[b].status = ST_ACTIVE;
+        a.st[b].m0 = m0;
+        a.st[b].m1 = m0;
+        a.rstart[b] = 0;
+        a.rcount[b] = rows0;
+    }
+}
+
+// ================================================================================================ gathered GEMV
+// Work item = GEMV_TILE consecutive opened positions of one sequence.  A block stages the sequence's h in LDS
+// (bf16) and each wave streams two rows of W' at a time with 128-bit loads, float32 accumulation, wave reduction.
+__global__ __launch_bounds__(256) void gemv_gather_kernel(StepArgs a) {
+    extern __shared__ uint4 hs4[];
+    __shared__ int pre[CSV_MAX_BATCH + 1];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    // tiles per sequence, then an inclusive prefix over sequences (B <= 256 = blockDim)
+    {
+        const int mine = tid < a.B ? (a.rcount[tid] + GEMV_TILE - 1) / GEMV_TILE : 0;
+        int x = mine;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int y = __shfl_up(x, o, CSV_WAVE);
+            if (lane >= o) x += y;
+        }
+        __shared__ int wsum[4];
+        if (lane == 63) wsum[wave] = x;
+        __syncthreads();
+        int base = 0;
+        for (int i = 0; i < wave; ++i) base += wsum[i];
+        if (tid == 0) pre[0] = 0;
+        pre[tid + 1] = base + x;
+    }
+    __syncthreads();
+    const int total = pre[a.B];
+    const int nch = a.d >> 3;
+    int cur_b = -1;
+    for (int g = blockIdx.x; g < total; g += gridDim.x) {
+        int lo = 0, hi = a.B;   // largest b with pre[b] <= g
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (pre[mid] <= g) lo = mid; else hi = mid;
+        }
+        const int b = lo;
+        if (b != cur_b) {
+            __syncthreads();
+            const uint4* hsrc = reinterpret_cast<const uint4*>(a.h) + (size_t)b * nch;
+            for (int i = tid; i < nch; i += 256) hs4[i] = hsrc[i];
+            __syncthreads();
+            cur_b = b;
+        }
+        const int t = g - pre[b];
+        const int pbeg = a.rstart[b] + t * GEMV_TILE;
+        const int pend = min(a.rstart[b] + a.rcount[b], pbeg + GEMV_TILE);
+        const int p = pbeg + wave * GEMV_ROWS_PER_WAVE;
+        if (p >= pend) continue;
+        const int32_t* rm = a.rowmap + (size_t)b * a.K_cap;
+        const int r0 = rm[p];
+        const bool two = p + 1 < pend;
+        const int r1 = two ? rm[p + 1] : r0;
+        const uint4* w0 = reinterpret_cast<const uint4*>(a.Wp + (size_t)r0 * a.d);
+        const uint4* w1 = reinterpret_cast<const uint4*>(a.Wp + (size_t)r1 * a.d);
+        float acc0 = 0.f, acc1 = 0.f;
+        int i = lane;
+        for (; i + 192 < nch; i += 256) {
+            const uint4 a0 = w0[i], a1 = w0[i + 64], a2 = w0[i + 128], a3 = w0[i + 192];
+            const uint4 c0 = w1[i], c1 = w1[i + 64], c2 = w1[i + 128], c3 = w1[i + 192];
+            const uint4 h0 = hs4[i], h1 = hs4[i + 64], h2 = hs4[i + 128], h3 = hs4[i + 192];
+            acc0 = dot8_bf16(a0, h0, acc0);
+            acc1 = dot8_bf16(c0, h0, acc1);
+            acc0 = dot8_bf16(a1, h1, acc0);
+            acc1 = dot8_bf16(c1, h1, acc1);
+            acc0 = dot8_bf16(a2, h2, acc0);
+            acc1 = dot8_bf16(c2, h2, acc1);
+            acc0 = dot8_bf16(a3, h3, acc0);
+            acc1 = dot8_bf16(c3, h3, acc1);
+        }
+        for (; i < nch; i += 64) {
+            const uint4 hv = hs4[i];
+            acc0 = dot8_bf16(w0[i], hv, acc0);
+            acc1 = dot8_bf16(w1[i], hv, acc1);
+        }
+        acc0 = wave_sum(acc0);
+        acc1 = wave_sum(acc1);
+        if (lane == 0) {
+            float* dst = a.slog + (size_t)b * a.K_cap;
+            dst[p] = acc0 + a.bp[r0];
+            if (two) dst[p + 1] = acc1 + a.bp[r1];
+        }
+    }
+}
+
+// ================================================================================================ block top-k
+struct TopkShared {
+    unsigned hist[256];
+    unsigned suf[257];
+    float red[16];
+    int redi[16];
+    unsigned sel, rem, eq, cnt;
+    float wval[CSV_MAX_K];
+    int wid[CSV_MAX_K];
+    float oval[CSV_MAX_K];
+    int oid[CSV_MAX_K];
+};
+
+// Key of a logit for selection: -0 and +0 compare equal.
+__device__ __forceinline__ uint32_t lkey(float v) { return fkey(v + 0.0f); }
+
+// kk-th largest key among the elements for which key(i, kx) returns true (1 <= kk <= their number).
+// On return: kth = that key, need_eq = how many elements equal to it belong to the largest kk, n_eq = how many equal it.
+template <class KeyFn>
+__device__ __forceinline__ void radix_select(int n, unsigned kk, KeyFn key, TopkShared& s, unsigned& kth,
+                                             unsigned& need_eq, unsigned& n_eq) {
+    const int tid = threadIdx.x, nt = blockDim.x;
+    unsigned prefix = 0, mask = 0, rem = kk, eq = 0;
+    for (int shift = 24; shift >= 0; shift -= 8) {
+        for (int t = tid; t < 256; t += nt) s.hist[t] = 0;
+        __syncthreads();
+        for (int i = tid; i < n; i += nt) {
+            unsigned kx;
+            if (key(i, kx) && (kx & mask) == prefix) atomicAdd(&s.hist[(kx >> shift) & 255u], 1u);
+        }
+        __syncthreads();
+        if (tid < 256) s.suf[tid] = s.hist[tid];
+        if (tid == 0) s.suf[256] = 0;
+        __syncthreads();
+        for (int o = 1; o < 256; o <<= 1) {
+            unsigned v = 0;
+            if (tid < 256) {
+                v = s.suf[tid];
+                if (tid + o < 256) v += s.suf[tid + o];
+            }
+            __syncthreads();
+            if (tid < 256) s.suf[tid] = v;
+            __syncthreads();
+        }
+        if (tid < 256) {
+            const unsigned ge = s.suf[tid], gt = s.suf[tid + 1];
+            if (ge >= rem && gt < rem) {
+                s.sel = (unsigned)tid;
+                s.rem = rem - gt;
+                s.eq = ge - gt;
+            }
+        }
+        __syncthreads();
+        prefix |= s.sel << shift;
+        mask |= 0xffu << shift;
+        rem = s.rem;
+        eq = s.eq;
+        __syncthreads();
+    }
+    kth = prefix;
+    need_eq = rem;
+    n_eq = eq;
+}
+
+// Largest min(k,n) of n values in order (value descending, id ascending).  Result in s.oval / s.oid.
+// Needs blockDim.x >= 256.  val(i) and id_of(i) may read global memory; id_of is only evaluated for elements
+// that reach the selection boundary.
+template <class ValFn, class IdFn>
+__device__ __forceinline__ int block_topk(int n, int k, ValFn val, IdFn id_of, TopkShared& s) {
+    const int tid = threadIdx.x, nt = blockDim.x;
+    const int kk = min(k, n);
+    if (kk <= 0) return 0;
+    if (kk < n) {
+        unsigned kth, need, neq;
+        radix_select(n, (unsigned)kk, [&](int i, unsigned& kx) { kx = lkey(val(i)); return true; }, s, kth, need, neq);
+        unsigned idkey = 0;   // boundary elements win when ~id >= idkey
+        if (need < neq) {
+            unsigned u1, u2;
+            radix_select(n, need,
+                         [&](int i, unsigned& kx) {
+                             if (lkey(val(i)) != kth) return false;
+                             kx = ~(unsigned)id_of(i);
+                             return true;
+                         },
+                         s, idkey, u1, u2);
+        }
+        if (tid == 0) s.cnt = 0;
+        __syncthreads();
+        for (int i = tid; i < n; i += nt) {
+            const float v = val(i);
+            const unsigned kx = lkey(v);
+            if (kx >= kth) {
+                const int id = id_of(i);
+                if (kx > kth || (~(unsigned)id) >= idkey) {
+                    const unsigned slot = atomicAdd(&s.cnt, 1u);
+                    if (slot < CSV_MAX_K) {
+                        s.wval[slot] = v;
+                        s.wid[slot] = id;
+                    }
+                }
+            }
+        }
+        __syncthreads();
+    } else {
+        for (int i = tid; i < n; i += nt) {
+            s.wval[i] = val(i);
+            s.wid[i] = id_of(i);
+        }
+        __syncthreads();
+    }
+    for (int t = tid; t < kk; t += nt) {
+        const float v = s.wval[t];
+        const int id = s.wid[t];
+        int rank = 0;
+        for (int j = 0; j < kk; ++j) {
+            const float vj = s.wval[j];
+            rank += (vj > v) || (vj == v && s.wid[j] < id);
+        }
+        s.oval[rank] = v;
+        s.oid[rank] = id;
+    }
+    __syncthreads();
+    return kk;
+}
+
+// max and sum exp(x - max) of n values, fixed reduction order
+template <class ValFn>
+__device__ __forceinline__ LseAcc block_lse(int n, ValFn val, TopkShared& s) {
+    float mx = -INFINITY;
+    for (int i = threadIdx.x; i < n; i += blockDim.x) mx = fmaxf(mx, val(i));
+    mx = block_max(mx, s.red);
+    float sm = 0.f;
+    if (mx > -INFINITY)
+        for (int i = threadIdx.x; i < n; i += blockDim.x) sm += expf(val(i) - mx);
+    sm = block_sum(sm, s.red);
+    LseAcc r;
+    r.m = mx;
+    r.s = sm;
+    return r;
+}
+
+// ================================================================================================ certification
+// One block per sequence.  round 0: certify or plan round 1 (or fall back on budget); round 1: certify or fall back.
+__global__ __launch_bounds__(1024) void cert_kernel(StepArgs a, int round) {
+    __shared__ TopkShared s;
+    const int b = blockIdx.x, tid = threadIdx.x, nt = blockDim.x;
+    if (a.st[b].status != ST_ACTIVE) return;
+    const int C = a.C;
+    const int m = round == 0 ? a.st[b].m0 : a.st[b].m1;
+    const int32_t* Pb = a.P + (size_t)b * (C + 1);
+    const float* Tb = a.T + (size_t)b * (C + 1);
+    const float* sub = a.su + (size_t)b * C;
+    const int n = Pb[m];
+    const float* vals = a.slog + (size_t)b * a.K_cap;
+    const int32_t* rm = a.rowmap + (size_t)b * a.K_cap;
+    auto val = [&](int i) { return vals[i]; };
+    auto idf = [&](int i) { return a.perm[rm[i]]; };
+
+    const LseAcc l = block_lse(n, val, s);
+    const float Z = lse_value(l);
+    float theta = -INFINITY;
+    if (a.use_k) {
+        block_topk(n, a.k, val, idf, s);
+        theta = s.oval[a.k - 1];
+    }
+    const float nxt = m < C ? sub[m] : -INFINITY;
+    const bool tk = (m == C) || (nxt == -INFINITY) || (nxt < theta);
+    const bool sm = (Tb[m] - Z <= a.lam) || (Tb[m] == -INFINITY);
+    bool ok;
+    if (a.combine == CSV_COMBINE_ALL)
+        ok = (tk || !a.use_k) && (sm || !a.use_s);
+    else
+        ok = (tk && a.use_k) || (sm && a.use_s);
+
+    if (ok) {
+        for (int t = tid; t < a.k; t += nt) {
+            a.out.d_ids[(size_t)b * a.k + t] = s.oid[t];
+            a.out.d_logits[(size_t)b * a.k + t] = s.oval[t];
+        }
+        if (a.out.d_sel_clusters)
+            for (int j = tid; j < m; j += nt) a.out.d_sel_clusters[(size_t)b * C + j] = a.order[(size_t)b * C + j];
+        if (tid == 0) {
+            a.out.d_lse[b] = Z;
+            a.out.d_flags[b] = ((tk && a.use_k) ? CSV_FLAG_TOPK_CERT : 0u) | ((sm && a.use_s) ? CSV_FLAG_SOFTMAX_CERT : 0u);
+            a.out.d_n_rows[b] = n;
+            a.out.d_n_clusters[b] = m;
+            if (a.out.d_rounds) a.out.d_rounds[b] = round + 1;
+            a.st[b].status = ST_DONE;
+            a.rcount[b] = 0;
+        }
+        return;
+    }
+    if (round == 1) {
+        if (tid == 0) push_fallback(a, b, 2);
+        return;
+    }
+    // plan round 1
+    int av = m, sv = m;
+    if (a.use_k && !tk) {
+        int cnt = 0;
+        for (int j = tid; j < C; j += nt) cnt += (sub[j] >= theta) ? 1 : 0;
+        av = block_sum_i(cnt, s.redi);
+    }
+    if (a.use_s && !sm) {
+        int best = C;
+        for (int j = m + tid; j <= C; j += nt)
+            if (Tb[j] - Z <= a.lam || Tb[j] == -INFINITY) best = min(best, j);
+        sv = block_min_i(best, s.redi);
+    }
+    int m1;
+    if (a.use_k && a.use_s)
+        m1 = a.combine == CSV_COMBINE_ALL ? max(av, sv) : min(av, sv);
+    else
+        m1 = a.use_k ? av : sv;
+    const int rows1 = Pb[m1];
+    if (rows1 > a.K_max) {
+        if (tid == 0) {
+            a.st[b].m1 = m1;
+            push_fallback(a, b, 1);
+        }
+        return;
+    }
+    write_rowmap(a, b, m, m1);
+    if (tid == 0) {
+        a.st[b].m1 = m1;
+        a.st[b].theta0 = theta;
+        a.st[b].Z0 = Z;
+        a.rstart[b] = n;
+        a.rcount[b] = rows1 - n;
+    }
+}
+
+// ================================================================================================ full-vocabulary product
+struct FullArgs {
+    int V, d;
+    const uint16_t* Wp;
+    const float* bp;
+    const int32_t* perm;
+    const uint16_t* h;
+    const int32_t* list;    // sequences to score
+    const int32_t* n_ptr;   // device count of entries in list, or NULL
+    int n_fixed;            // count when n_ptr is NULL
+    float* out;             // [slot*out_stride + row]
+    long long out_stride;
+    int scatter;            // 1: write at the original token id instead of the permuted row
+};
+
+// Vector path: FULL_G sequences per pass over W', h of the pass in LDS, two rows per wave at a time.
+__global__ __launch_bounds__(256) void full_gemv_kernel(FullArgs f) {
+    extern __shared__ uint4 hs4[];
+    const int n = f.n_ptr ? *f.n_ptr : f.n_fixed;
+    if (n <= 0) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int nch = f.d >> 3;
+    const int ntiles = (f.V + 7) / 8;
+    for (int g0 = 0; g0 < n; g0 += FULL_G) {
+        const int ng = min(FULL_G, n - g0);
+        __syncthreads();
+        for (int i = tid; i < FULL_G * nch; i += 256) {
+            const int s = i / nch, j = i - s * nch;
+            hs4[i] = s < ng ? (reinterpret_cast<const uint4*>(f.h) + (size_t)f.list[g0 + s] * nch)[j] : make_uint4(0, 0, 0, 0);
+        }
+        __syncthreads();
+        for (int tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+            const int r0 = tile * 8 + wave * 2;
+            if (r0 >= f.V) continue;
+            const bool two = r0 + 1 < f.V;
+            const int r1 = two ? r0 + 1 : r0;
+            const uint4* w0 = reinterpret_cast<const uint4*>(f.Wp + (size_t)r0 * f.d);
+            const uint4* w1 = reinterpret_cast<const uint4*>(f.Wp + (size_t)r1 * f.d);
+            float acc0[FULL_G], acc1[FULL_G];
+#pragma unroll
+            for (int s = 0; s < FULL_G; ++s) acc0[s] = acc1[s] = 0.f;
+            int i = lane;
+            for (; i + 64 < nch; i += 128) {
+                const uint4 a0 = w0[i], a1 = w0[i + 64];
+                const uint4 c0 = w1[i], c1 = w1[i + 64];
+#pragma unroll
+                for (int s = 0; s < FULL_G; ++s) {
+                    if (s < ng) {
+                        const uint4 h0 = hs4[s * nch + i], h1 = hs4[s * nch + i + 64];
+                        acc0[s] = dot8_bf16(a0, h0, acc0[s]);
+                        acc1[s] = dot8_bf16(c0, h0, acc1[s]);
+                        acc0[s] = dot8_bf16(a1, h1, acc0[s]);
+                        acc1[s] = dot8_bf16(c1, h1, acc1[s]);
+                    }
+                }
+            }
+            for (; i < nch; i += 64) {
+                const uint4 a0 = w0[i], c0 = w1[i];
+#pragma unroll
+                for (int s = 0; s < FULL_G; ++s) {
+                    if (s < ng) {
+                        const uint4 h0 = hs4[s * nch + i];
+                        acc0[s] = dot8_bf16(a0, h0, acc0[s]);
+                        acc1[s] = dot8_bf16(c0, h0, acc1[s]);
+                    }
+                }
+            }
+#pragma unroll
+            for (int s = 0; s < FULL_G; ++s) {
+                if (s < ng) {
+                    const float v0 = wave_sum(acc0[s]), v1 = wave_sum(acc1[s]);
+                    if (lane == 0) {
+                        float* dst = f.out + (size_t)(g0 + s) * f.out_stride;
+                        dst[f.scatter ? f.perm[r0] : r0] = v0 + f.bp[r0];
+                        if (two) dst[f.scatter ? f.perm[r1] : r1] = v1 + f.bp[r1];
+                    }
+                }
+            }
+        }
+    }
+}
+
+// First stage of top-k / log-sum-exp over V: one block per (chunk of rows, fallback slot).
+__global__ __launch_bounds__(1024) void fb_topk_kernel(StepArgs a) {
+    __shared__ TopkShared s;
+    const int slot = blockIdx.y, chunk = blockIdx.x, tid = threadIdx.x, nt = blockDim.x;
+    if (slot >= a.counters[0]) return;
+    const int c0 = chunk * FB_CHUNK;
+    const int n = min(FB_CHUNK, a.V - c0);
+    const float* vals = a.fb_logits + (size_t)slot * a.V + c0;
+    auto val = [&](int i) { return vals[i]; };
+    auto idf = [&](int i) { return a.perm[c0 + i]; };
+    const LseAcc l = block_lse(n, val, s);
+    const size_t pc = (size_t)slot * a.n_chunks + chunk;
+    if (tid == 0) {
+        a.cand_max[pc] = l.m;
+        a.cand_sum[pc] = l.s;
+    }
+    if (a.k > 0) {
+        const int kk = block_topk(n, a.k, val, idf, s);
+        for (int t = tid; t < a.k; t += nt) {
+            a.cand_val[pc * a.k + t] = t < kk ? s.oval[t] : -INFINITY;
+            a.cand_id[pc * a.k + t] = t < kk ? s.oid[t] : 0x7fffffff;
+        }
+    }
+}
+
+// Second stage: merge the chunk candidates of one fallback sequence and write its outputs.
+__global__ __launch_bounds__(1024) void fb_final_kernel(StepArgs a) {
+    __shared__ TopkShared s;
+    const int slot = blockIdx.x, tid = threadIdx.x, nt = blockDim.x;
+    if (slot >= a.counters[0]) return;
+    const int b = a.fb_list[slot];
+    const float* cm = a.cand_max + (size_t)slot * a.n_chunks;
+    const float* cs = a.cand_sum + (size_t)slot * a.n_chunks;
+    float mx = -INFINITY;
+    for (int i = tid; i < a.n_chunks; i += nt) mx = fmaxf(mx, cm[i]);
+    mx = block_max(mx, s.red);
+    float sm = 0.f;
+    for (int i = tid; i < a.n_chunks; i += nt) sm += cs[i] * expf(cm[i] - mx);
+    sm = block_sum(sm, s.red);
+    if (a.k > 0) {
+        const float* cv = a.cand_val + (size_t)slot * a.n_chunks * a.k;
+        const int32_t* ci = a.cand_id + (size_t)slot * a.n_chunks * a.k;
+        block_topk(a.n_chunks * a.k, a.k, [&](int i) { return cv[i]; }, [&](int i) { return ci[i]; }, s);
+        for (int t = tid; t < a.k; t += nt) {
+            a.out.d_ids[(size_t)b * a.k + t] = s.oid[t];
+            a.out.d_logits[(size_t)b * a.k + t] = s.oval[t];
+        }
+    }
+    if (tid == 0) {
+        a.out.d_lse[b] = mx + logf(sm);
+        a.out.d_flags[b] = CSV_FLAG_FALLBACK | CSV_FLAG_TOPK_CERT | CSV_FLAG_SOFTMAX_CERT;
+        a.out.d_n_rows[b] = a.V;
+        a.out.d_n_clusters[b] = a.C;
+        if (a.out.d_fallback_count) atomicAdd(a.out.d_fallback_count, 1ull);
+    }
+}
+
+// ================================================================================================ host side
+static void profile_release(csv_workspace* ws);
+
+static int next_pow2(int x) {
+    int p = 1;
+    while (p < x) p <<= 1;
+    return p;
+}
+
+static void fill_args(StepArgs& a, const csv_workspace* ws, const csv_index* idx) {
+    memset(&a, 0, sizeof(a));
+    a.V = idx->V; a.d = idx->d; a.C = idx->C;
+    a.Wp = idx->Wp; a.bp = idx->bp; a.perm = idx->perm; a.mu = idx->mu; a.R = idx->R; a.bmax = idx->bmax;
+    a.n = idx->n; a.off = idx->off; a.lnn = idx->lnn;
+    a.K_cap = ws->K_cap; a.Npad = ws->Npad; a.n_chunks = ws->n_chunks;
+    a.U = ws->U; a.hnorm = ws->hnorm; a.order = ws->order; a.su = ws->su; a.T = ws->T; a.P = ws->P; a.st = ws->st;
+    a.rstart = ws->rstart; a.rcount = ws->rcount; a.slog = ws->slog; a.rowmap = ws->rowmap; a.counters = ws->counters;
+    a.fb_list = ws->fb_list; a.fb_logits = ws->fb_logits; a.cand_val = ws->cand_val; a.cand_id = ws->cand_id;
+    a.cand_max = ws->cand_max; a.cand_sum = ws->cand_sum;
+}
+
+static int check_pair(const csv_workspace* ws, const csv_index* idx, const void* d_h, int B) {
+    if (!ws || !idx || !d_h) { csv_set_error("null workspace, index or h"); return CSV_EINVAL; }
+    if (ws->V != idx->V || ws->d != idx->d || ws->C != idx->C) { csv_set_error("workspace was created for another index shape"); return CSV_ESHAPE; }
+    if (B < 1 || B > ws->B_max) { csv_set_error("B=%d outside 1..%d", B, ws->B_max); return CSV_ESHAPE; }
+    return CSV_OK;
+}
+
+static int launch_bounds_kernel(const StepArgs& a, float* U, float* hn, int reset, hipStream_t st) {
+    int bt = 1;
+    while (bt < a.B && bt < 8) bt <<= 1;
+    while (bt > 1 && (size_t)bt * a.d * 2 > 65536) bt >>= 1;
+    const int groups = (a.C + 3) / 4;
+    const int gpx = (groups + 7) / 8;
+    dim3 grid(gpx * 8, (a.B + bt - 1) / bt);
+    const size_t lds = (size_t)bt * a.d * 2;
+    switch (bt) {
+        case 1: bound_kernel<1><<<grid, 256, lds, st>>>(a, U, hn, reset, groups, gpx); break;
+        case 2: bound_kernel<2><<<grid, 256, lds, st>>>(a, U, hn, reset, groups, gpx); break;
+        case 4: bound_kernel<4><<<grid, 256, lds, st>>>(a, U, hn, reset, groups, gpx); break;
+        default: bound_kernel<8><<<grid, 256, lds, st>>>(a, U, hn, reset, groups, gpx); break;
+    }
+    CSV_LAUNCH_CHECK("bound_kernel");
+    return CSV_OK;
+}
+
+static int gemv_grid(const csv_workspace* ws, int B) {
+    long long tiles = ((long long)ws->K_cap + GEMV_TILE - 1) / GEMV_TILE * B;
+    return (int)(tiles < 2048 ? (tiles < 1 ? 1 : tiles) : 2048);
+}
+
+static int launch_full(const csv_index* idx, const uint16_t* d_h, const int32_t* list, const int32_t* n_ptr, int n_fixed,
+                       float* out, long long stride, int scatter, hipStream_t st) {
+    FullArgs f;
+    f.V = idx->V; f.d = idx->d; f.Wp = idx->Wp; f.bp = idx->bp; f.perm = idx->perm; f.h = d_h;
+    f.list = list; f.n_ptr = n_ptr; f.n_fixed = n_fixed; f.out = out; f.out_stride = stride; f.scatter = scatter;
+    const int ntiles = (idx->V + 7) / 8;
+    const int grid = ntiles < 2048 ? ntiles : 2048;
+    full_gemv_kernel<<<grid, 256, (size_t)FULL_G * idx->d * 2, st>>>(f);
+    CSV_LAUNCH_CHECK("full_gemv_kernel");
+    return CSV_OK;
+}
+
+extern "C" int csv_workspace_create(const csv_index* idx, int B_max, int K_cap_rows, csv_workspace** out) {
+    if (out) *out = nullptr;
+    if (!idx || !out) { csv_set_error("null index or out"); return CSV_EINVAL; }
+    if (B_max < 1 || B_max > CSV_MAX_BATCH) { csv_set_error("B_max=%d outside 1..%d", B_max, CSV_MAX_BATCH); return CSV_ESHAPE; }
+    if (K_cap_rows < 0 || K_cap_rows > idx->V) { csv_set_error("K_cap_rows=%d outside 0..V", K_cap_rows); return CSV_EINVAL; }
+    if ((size_t)FULL_G * idx->d * 2 > 65536) { csv_set_error("d=%d too large for the LDS staging of h", idx->d); return CSV_ESHAPE; }
+    csv_workspace* ws = (csv_workspace*)calloc(1, sizeof(csv_workspace));
+    if (!ws) { csv_set_error("host allocation failed"); return CSV_ENOMEM; }
+    ws->B_max = B_max; ws->K_cap = K_cap_rows > 0 ? K_cap_rows : 1; ws->V = idx->V; ws->d = idx->d; ws->C = idx->C;
+    ws->Npad = next_pow2(idx->C);
+    ws->n_chunks = (idx->V + FB_CHUNK - 1) / FB_CHUNK;
+    ws->device = idx->device;
+    const size_t B = B_max, C = idx->C, V = idx->V, K = ws->K_cap, NC = ws->n_chunks;
+    hipError_t e = hipSuccess;
+    auto A = [&](void** p, size_t bytes) { if (e == hipSuccess) e = hipMalloc(p, bytes ? bytes : 16); };
+    A((void**)&ws->U, B * C * 4); A((void**)&ws->hnorm, B * 4); A((void**)&ws->order, B * C * 4); A((void**)&ws->su, B * C * 4);
+    A((void**)&ws->T, B * (C + 1) * 4); A((void**)&ws->P, B * (C + 1) * 4); A((void**)&ws->st, B * sizeof(SeqState));
+    A((void**)&ws->rstart, B * 4); A((void**)&ws->rcount, B * 4); A((void**)&ws->slog, B * K * 4); A((void**)&ws->rowmap, B * K * 4);
+    A((void**)&ws->counters, 16 * 4); A((void**)&ws->fb_list, B * 4); A((void**)&ws->all_list, B * 4);
+    A((void**)&ws->fb_logits, B * V * 4); A((void**)&ws->cand_val, B * NC * CSV_MAX_K * 4); A((void**)&ws->cand_id, B * NC * CSV_MAX_K * 4);
+    A((void**)&ws->cand_max, B * NC * 4); A((void**)&ws->cand_sum, B * NC * 4);
+    if (e == hipSuccess) e = hipMemset(ws->counters, 0, 16 * 4);
+    if (e == hipSuccess) e = hipMemset(ws->rcount, 0, B * 4);
+    if (e == hipSuccess) e = hipMemset(ws->st, 0, B * sizeof(SeqState));
+    if (e == hipSuccess) {
+        int32_t* tmp = (int32_t*)malloc(B * 4);
+        for (size_t i = 0; i < B; ++i) tmp[i] = (int32_t)i;
+        e = hipMemcpy(ws->all_list, tmp, B * 4, hipMemcpyHostToDevice);
+        free(tmp);
+    }
+    if (e != hipSuccess) {
+        csv_set_error("workspace allocation failed: %s", hipGetErrorString(e));
+        csv_workspace_free(ws);
+        return e == hipErrorOutOfMemory ? CSV_ENOMEM : CSV_EHIP;
+    }
+    *out = ws;
+    return CSV_OK;
+}
+
+extern "C" void csv_workspace_free(csv_workspace* ws) {
+    if (!ws) return;
+    void* ptrs[] = {ws->U, ws->hnorm, ws->order, ws->su, ws->T, ws->P, ws->st, ws->rstart, ws->rcount, ws->slog, ws->rowmap,
+                    ws->counters, ws->fb_list, ws->all_list, ws->fb_logits, ws->cand_val, ws->cand_id, ws->cand_max, ws->cand_sum};
+    for (void* p : ptrs)
+        if (p) (void)hipFree(p);
+    profile_release(ws);
+    free(ws);
+}
+
+extern "C" int csv_bounds(csv_workspace* ws, const csv_index* idx, const uint16_t* d_h, int B, float* d_U, float* d_hnorm,
+                          void* stream) {
+    int rc = check_pair(ws, idx, d_h, B);
+    if (rc) return rc;
+    if (!d_U) { csv_set_error("null d_U"); return CSV_EINVAL; }
+    StepArgs a;
+    fill_args(a, ws, idx);
+    a.B = B; a.h = d_h;
+    return launch_bounds_kernel(a, d_U, d_hnorm, 0, (hipStream_t)stream);
+}
+
+extern "C" int csv_full_logits(csv_workspace* ws, const csv_index* idx, const uint16_t* d_h, int B, float* d_logits,
+                               void* stream) {
+    int rc = check_pair(ws, idx, d_h, B);
+    if (rc) return rc;
+    if (!d_logits) { csv_set_error("null d_logits"); return CSV_EINVAL; }
+    return launch_full(idx, d_h, ws->all_list, nullptr, B, d_logits, idx->V, 1, (hipStream_t)stream);
+}
+
+extern "C" int csv_decode_step(csv_workspace* ws, const csv_index* idx, const uint16_t* d_h, int B,
+                               const csv_step_params* p, const csv_step_out* o, void* stream) {
+    int rc = check_pair(ws, idx, d_h, B);
+    if (rc) return rc;
+    if (!p || !o) { csv_set_error("null params or out"); return CSV_EINVAL; }
+    const bool use_k = p->k >= 1, use_s = p->eps > 0.f;
+    if (!use_k && !use_s) { csv_set_error("both certificates disabled (k=%d, eps=%g)", p->k, (double)p->eps); return CSV_EINVAL; }
+    if (p->k < 0 || p->k > CSV_MAX_K || p->k > idx->V) { csv_set_error("k=%d outside 0..min(V,%d)", p->k, CSV_MAX_K); return CSV_EINVAL; }
+    if (p->K_max_rows < 0 || p->K_max_rows > ws->K_cap) { csv_set_error("K_max_rows=%d exceeds workspace capacity %d", p->K_max_rows, ws->K_cap); return CSV_EINVAL; }
+    if (p->combine != CSV_COMBINE_ALL && p->combine != CSV_COMBINE_ANY) { csv_set_error("bad combine=%d", p->combine); return CSV_EINVAL; }
+    if (!o->d_lse || !o->d_flags || !o->d_n_rows || !o->d_n_clusters || (use_k && (!o->d_ids || !o->d_logits))) {
+        csv_set_error("null output buffer");
+        return CSV_EINVAL;
+    }
+    hipStream_t st = (hipStream_t)stream;
+    StepArgs a;
+    fill_args(a, ws, idx);
+    a.B = B; a.h = d_h; a.k = p->k; a.K_max = p->K_max_rows; a.combine = p->combine; a.use_k = use_k; a.use_s = use_s;
+    if (!use_s) a.lam = -INFINITY;
+    else if (p->eps >= 1.f) a.lam = INFINITY;
+    else a.lam = (float)log((double)p->eps / (1.0 - (double)p->eps));
+    a.out = *o;
+
+    hipEvent_t* ev = nullptr;
+    if (ws->prof_on && ws->prof_n < ws->prof_cap) ev = ws->prof_ev + (size_t)ws->prof_n++ * (CSV_PROFILE_STAGES + 1);
+#define CSV_MARK(i) do { if (ev) CSV_HIP(hipEventRecord(ev[i], st)); } while (0)
+    CSV_MARK(0);
+    rc = launch_bounds_kernel(a, ws->U, ws->hnorm, 1, st);
+    if (rc) return rc;
+    CSV_MARK(1);
+    select0_kernel<<<B, 1024, (size_t)ws->Npad * 8, st>>>(a);
+    CSV_LAUNCH_CHECK("select0_kernel");
+    CSV_MARK(2);
+    const int gg = gemv_grid(ws, B);
+    const size_t hl = (size_t)idx->d * 2;
+    gemv_gather_kernel<<<gg, 256, hl, st>>>(a);
+    CSV_LAUNCH_CHECK("gemv_gather_kernel");
+    CSV_MARK(3);
+    cert_kernel<<<B, 1024, 0, st>>>(a, 0);
+    CSV_LAUNCH_CHECK("cert_kernel");
+    CSV_MARK(4);
+    gemv_gather_kernel<<<gg, 256, hl, st>>>(a);
+    CSV_LAUNCH_CHECK("gemv_gather_kernel");
+    CSV_MARK(5);
+    cert_kernel<<<B, 1024, 0, st>>>(a, 1);
+    CSV_LAUNCH_CHECK("cert_kernel");
+    CSV_MARK(6);
+    rc = launch_full(idx, d_h, ws->fb_list, ws->counters, 0, ws->fb_logits, idx->V, 0, st);
+    if (rc) return rc;
+    CSV_MARK(7);
+    fb_topk_kernel<<<dim3(ws->n_chunks, B), 1024, 0, st>>>(a);
+    CSV_LAUNCH_CHECK("fb_topk_kernel");
+    CSV_MARK(8);
+    fb_final_kernel<<<B, 1024, 0, st>>>(a);
+    CSV_LAUNCH_CHECK("fb_final_kernel");
+    CSV_MARK(9);
+#undef CSV_MARK
+    return CSV_OK;
+}
+
+// ------------------------------------------------------------------------------------------------ stage timing
+static void profile_release(csv_workspace* ws) {
+    if (ws->prof_ev) {
+        for (size_t i = 0; i < (size_t)ws->prof_cap * (CSV_PROFILE_STAGES + 1); ++i)
+            if (ws->prof_ev[i]) (void)hipEventDestroy(ws->prof_ev[i]);
+        free(ws->prof_ev);
+    }
+    ws->prof_ev = nullptr;
+    ws->prof_cap = ws->prof_n = ws->prof_on = 0;
+}
+
+extern "C" int csv_profile_begin(csv_workspace* ws, int max_steps) {
+    if (!ws || max_steps < 1 || max_steps > (1 << 16)) { csv_set_error("bad workspace or max_steps"); return CSV_EINVAL; }
+    profile_release(ws);
+    const size_t n = (size_t)max_steps * (CSV_PROFILE_STAGES + 1);
+    ws->prof_ev = (hipEvent_t*)calloc(n, sizeof(hipEvent_t));
+    if (!ws->prof_ev) { csv_set_error("host allocation failed"); return CSV_ENOMEM; }
+    ws->prof_cap = max_steps;
+    for (size_t i = 0; i < n; ++i) {
+        hipError_t e = hipEventCreate(&ws->prof_ev[i]);
+        if (e != hipSuccess) {
+            csv_set_error("hipEventCreate failed: %s", hipGetErrorString(e));
+            profile_release(ws);
+            return CSV_EHIP;
+        }
+    }
+    ws->prof_on = 1;
+    return CSV_OK;
+}
+
+extern "C" int csv_profile_end(csv_workspace* ws, float* h_stage_ms, int* h_steps) {
+    if (!ws || !h_stage_ms || !h_steps) { csv_set_error("null argument"); return CSV_EINVAL; }
+    for (int i = 0; i < CSV_PROFILE_STAGES; ++i) h_stage_ms[i] = 0.f;
+    *h_steps = ws->prof_n;
+    int rc = CSV_OK;
+    for (int s = 0; s < ws->prof_n && rc == CSV_OK; ++s) {
+        hipEvent_t* ev = ws->prof_ev + (size_t)s * (CSV_PROFILE_STAGES + 1);
+        hipError_t e = hipEventSynchronize(ev[CSV_PROFILE_STAGES]);
+        for (int i = 0; i < CSV_PROFILE_STAGES && e == hipSuccess; ++i) {
+            float ms = 0.f;
+            e = hipEventElapsedTime(&ms, ev[i], ev[i + 1]);
+            h_stage_ms[i] += ms;
+        }
+        if (e != hipSuccess) {
+            csv_set_error("event timing failed: %s", hipGetErrorString(e));
+            rc = CSV_EHIP;
+        }
+    }
+    profile_release(ws);
+    return rc;
+}

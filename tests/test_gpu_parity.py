@@ -1,0 +1,240 @@
+"""GPU parity: every entry point of the C ABI against the CPU oracle on the same seeded inputs.
+
+Bars: decisions (flags, rounds, opened cluster set, rows) and ordered top-k ids identical outside the tie band
+(see _parity.py); logits and log-sum-exp within 1e-3 relative (asserted at the tighter 2e-5 the float32
+accumulation achieves); bounds within 1e-5 relative.
+"""
+import math
+
+import numpy as np
+import pytest
+
+import synth
+from oracle import csv_oracle as O
+
+from . import _parity as PAR
+from ._harness import Case, log
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+def _finish(t: PAR.Tally, tag: str, max_band_frac=0.2):
+    log(f"[{tag}] {t.summary()}")
+    assert not t.mismatch, "\n".join(t.mismatch[:10])
+    assert t.inband <= max_band_frac * t.n + 2, f"too many in-band cases: {t.summary()}"
+
+
+# ------------------------------------------------------------------ per-kernel parity
+@pytest.mark.parametrize("V,d,C,B", [(2000, 256, 16, 1), (3001, 520, 37, 3), (4096, 1024, 64, 8), (1500, 4096, 5, 11)])
+def test_full_logits_and_bounds(V, d, C, B):
+    r = synth.small_recipe(f"s{V}", V=V, d=d, C=C, B=B, steps=2)
+    log(f"full_logits/bounds V={V} d={d} C={C} B={B}")
+    case = Case(r, seed=7)
+    csv = case.csv
+    h = case.hidden()
+    dh = csv.bits_to_device(h)
+    for s in range(h.shape[0]):
+        Lg = csv.csv_full_logits(case.ws, case.gidx, dh[s]).cpu().numpy()
+        Ug, hg = csv.csv_bounds(case.ws, case.gidx, dh[s])
+        Ug, hg = Ug.cpu().numpy(), hg.cpu().numpy()
+        h64 = O.bf16_to_f64(h[s])
+        L = O.full_logits(case.W64, case.b, h64)
+        U, hn = O.cluster_bounds(case.oidx, h64)
+        err = np.abs(Lg - L) / np.maximum(1.0, np.abs(L))
+        log(f"  step {s}: max logit rel err {err.max():.2e}, max bound err {np.abs(Ug - U).max():.2e}")
+        assert err.max() < PAR.LOGIT_TIGHT < PAR.LOGIT_RTOL
+        assert np.allclose(hg, hn, rtol=1e-6)
+        assert np.all(np.abs(Ug - U) <= 1e-5 * np.maximum(1.0, np.abs(U)))
+    case.close()
+
+
+def test_bounds_empty_cluster_and_zero_h():
+    r = synth.small_recipe("empty", V=1000, d=128, C=8, B=2, steps=1)
+    head = synth.make_head(r, seed=3, threads=1)
+    labels = head["labels"].copy()
+    labels[labels == 5] = 2                      # cluster 5 becomes empty
+    case = Case(r, seed=3, labels=labels)
+    csv = case.csv
+    h = case.hidden()
+    h[0, 1] = 0                                  # second sequence: h = 0  ->  U_c = bmax_c
+    Ug, hg = csv.csv_bounds(case.ws, case.gidx, csv.bits_to_device(h[0]))
+    Ug, hg = Ug.cpu().numpy(), hg.cpu().numpy()
+    assert np.isneginf(Ug[:, 5]).all() and np.isfinite(np.delete(Ug, 5, axis=1)).all()
+    assert hg[1] == 0 and np.array_equal(np.delete(Ug[1], 5), np.delete(case.oidx.bmax, 5))
+    t = case.run_steps(h, 5, 1e-3, r.K_max_rows, O.COMBINE_ALL, "empty-cluster")
+    _finish(t, "empty-cluster")
+    case.close()
+
+
+# ------------------------------------------------------------------ whole step, small shapes, all modes
+MODES = [
+    ("all", dict(k=5, eps=1e-3, combine=O.COMBINE_ALL)),
+    ("any", dict(k=5, eps=1e-3, combine=O.COMBINE_ANY)),
+    ("topk-only", dict(k=7, eps=-1.0, combine=O.COMBINE_ALL)),
+    ("softmax-only", dict(k=0, eps=1e-2, combine=O.COMBINE_ALL)),
+    ("eps>=1", dict(k=3, eps=1.0, combine=O.COMBINE_ALL)),
+    ("k>cluster", dict(k=200, eps=1e-3, combine=O.COMBINE_ALL)),
+]
+
+
+@pytest.mark.parametrize("name,mode", MODES)
+def test_step_modes_small(name, mode):
+    r = synth.small_recipe("modes", V=4000, d=256, C=32, B=5, steps=6, iso_frac=0.3, h_mode="mix")
+    case = Case(r, seed=11)
+    h = case.hidden()
+    t = case.run_steps(h, mode["k"], mode["eps"], r.K_max_rows, mode["combine"], name)
+    _finish(t, name)
+    case.close()
+
+
+def test_step_budget_extremes_and_counter():
+    r = synth.small_recipe("budget", V=4000, d=256, C=32, B=4, steps=3)
+    case = Case(r, seed=12, K_cap=4000)
+    csv = case.csv
+    h = case.hidden()
+    t = case.run_steps(h, 5, 1e-3, 0, O.COMBINE_ALL, "K_max=0")          # every sequence falls back before scoring
+    _finish(t, "K_max=0")
+    assert t.fallbacks == t.n
+    t = case.run_steps(h, 5, 1e-3, 4000, O.COMBINE_ALL, "K_max=V")       # never a budget fallback
+    _finish(t, "K_max=V")
+    assert t.fallbacks == 0
+    t = case.run_steps(h, 5, 1e-9, 130, O.COMBINE_ALL, "K_max=130")      # seed fits, round-1 plan does not
+    _finish(t, "K_max=130")
+    assert t.fallbacks == t.n
+    buf = csv.make_step_buffers(case.gidx, 4, 5, 1e-3, 0)
+    dh = csv.bits_to_device(h)
+    for s in range(3):
+        csv.csv_decode_step(case.ws, case.gidx, dh[s], buf)
+    torch.cuda.synchronize()
+    assert int(buf.fallback_count.item()) == 12
+    case.close()
+
+
+def test_step_zipf_sizes_no_bias_ragged_batch():
+    r = synth.small_recipe("zipf", V=6000, d=520, C=48, B=7, steps=4, sizes="zipf", h_mode="mix", k=20, eps=1e-4)
+    case = Case(r, seed=13, bias=False)
+    h = case.hidden()
+    t = case.run_steps(h, r.k, r.eps, r.K_max_rows, O.COMBINE_ALL, "zipf")
+    _finish(t, "zipf")
+    case.close()
+
+
+def test_step_single_cluster_and_singletons():
+    r = synth.small_recipe("C1", V=700, d=64, C=1, B=2, steps=2)
+    case = Case(r, seed=14, K_cap=700)
+    t = case.run_steps(case.hidden(), 5, 1e-3, 700, O.COMBINE_ALL, "C=1")
+    _finish(t, "C=1")
+    case.close()
+    r = synth.small_recipe("CV", V=512, d=64, C=8, B=2, steps=2)
+    case = Case(r, seed=15, labels=np.arange(512), K_cap=512, radius_slack=0.0)
+    t = case.run_steps(case.hidden(), 5, 1e-3, 512, O.COMBINE_ALL, "C=V", )
+    _finish(t, "C=V", max_band_frac=1.0)
+    case.close()
+
+
+def test_step_invalid_hidden_state_is_flagged():
+    r = synth.small_recipe("inv", V=2000, d=256, C=16, B=3, steps=1)
+    case = Case(r, seed=16)
+    h = case.hidden()
+    h[0, 1, 5] = 0x7FC0                                                    # NaN in the second sequence
+    t = case.run_steps(h, 5, 1e-3, r.K_max_rows, O.COMBINE_ALL, "invalid")
+    _finish(t, "invalid")
+    case.close()
+
+
+def test_argument_errors():
+    r = synth.small_recipe("err", V=1000, d=64, C=8, B=2, steps=1)
+    case = Case(r, seed=17)
+    csv = case.csv
+    dh = csv.bits_to_device(case.hidden()[0])
+    with pytest.raises(csv.CsvError):
+        csv.csv_decode_step(case.ws, case.gidx, dh, csv.make_step_buffers(case.gidx, 2, 0, -1.0, 10))      # both tests off
+    with pytest.raises(csv.CsvError):
+        csv.csv_decode_step(case.ws, case.gidx, dh, csv.make_step_buffers(case.gidx, 2, 5, 1e-3, r.V))     # budget > capacity
+    with pytest.raises(csv.CsvError):
+        csv.csv_decode_step(case.ws, case.gidx, dh, csv.make_step_buffers(case.gidx, 2, 2000, 1e-3, 10))   # k > V
+    with pytest.raises(csv.CsvError):
+        csv.CsvWorkspace(case.gidx, 1000, 10)                                                              # B_max too large
+    case.close()
+
+
+# ------------------------------------------------------------------ index built on the GPU
+def test_build_index_from_labels_matches_oracle():
+    r = synth.small_recipe("idx", V=5000, d=264, C=40, B=2, steps=2, sizes="zipf")
+    case = Case(r, seed=18)
+    csv = case.csv
+    g = csv.csv_build_index(case.dW, case.db, r.C, init_labels=case.labels.astype(np.int32), iters=0)
+    e = g.export()
+    o = case.oidx
+    assert np.array_equal(e["n"], o.n) and np.array_equal(e["perm"], o.perm)
+    assert np.array_equal(e["bmax"], o.bmax)
+    ulp_mu = np.abs(e["mu"].view(np.int32).astype(np.int64) - o.mu.view(np.int32).astype(np.int64))
+    ulp_R = np.abs(e["R"].view(np.int32).astype(np.int64) - o.R.view(np.int32).astype(np.int64))
+    log(f"  centroid ulp diff max {ulp_mu.max()}, exact {np.mean(ulp_mu == 0):.6f}; radius ulp diff max {ulp_R.max()}")
+    assert ulp_mu.max() <= 1 and np.mean(ulp_mu == 0) > 0.9999
+    assert ulp_R.max() <= 2
+    # the GPU-built index drives the step to the same results
+    ws = csv.CsvWorkspace(g, r.B, r.K_max_rows)
+    h = case.hidden()
+    dh = csv.bits_to_device(h)
+    buf = csv.make_step_buffers(g, r.B, 5, 1e-3, r.K_max_rows, want_sel=True)
+    t = PAR.Tally()
+    for s in range(h.shape[0]):
+        csv.csv_decode_step(ws, g, dh[s], buf)
+        torch.cuda.synchronize()
+        L = O.full_logits(case.W64, case.b, O.bf16_to_f64(h[s]))
+        orc = O.decode_step(case.W64, case.b, o, h[s], 5, 1e-3, r.K_max_rows, O.COMBINE_ALL, logits=L)
+        PAR.compare_step(f"gpu-index step={s}", t, orc, PAR.gpu_step_to_numpy(buf), L, o, 5, 1e-3, r.K_max_rows, O.COMBINE_ALL)
+    _finish(t, "gpu-built index")
+    ws.free(); g.free(); case.close()
+
+
+def test_build_index_kmeans_matches_oracle_lloyd():
+    r = synth.small_recipe("km", V=3000, d=128, C=12, B=1, steps=1)
+    case = Case(r, seed=19)
+    csv = case.csv
+    first = np.array([int(np.flatnonzero(case.labels == c)[0]) for c in range(r.C)], dtype=np.int32)
+    first[3] = first[2] + 0                      # two starting centroids coincide: cluster 3 starts empty (tie -> smaller id)
+    labels, cent = O.lloyd_kmeans(case.head["W_bits"], first, iters=2)
+    want = O.build_index(case.head["W_bits"], case.b, labels, r.C)
+    g = csv.csv_build_index(case.dW, case.db, r.C, init_rows=first, iters=2)
+    e = g.export()
+    assert np.array_equal(e["n"], want.n) and np.array_equal(e["perm"], want.perm)
+    assert np.allclose(e["mu"], want.mu, rtol=0, atol=1e-7) and np.allclose(e["R"], want.R, rtol=1e-6)
+    g.free(); case.close()
+
+
+# ------------------------------------------------------------------ the five configurations
+def _run_config(name, step_ids, max_band_frac):
+    r = synth.CONFIGS[name]
+    case = Case(r)
+    h = case.hidden()
+    t = case.run_steps(h, r.k, r.eps, r.K_max_rows, O.COMBINE_ALL, name, step_ids=step_ids)
+    _finish(t, f"{name} ({len(step_ids)} of {r.steps} steps, B={r.B})", max_band_frac)
+    case.close()
+    return t
+
+
+def test_config_c1_all_steps():
+    t = _run_config("c1", range(64), 0.05)
+    assert t.fallbacks == 0 and t.rows == 125 * 64
+
+
+def test_config_c2_sampled_steps():
+    t = _run_config("c2", range(0, 512, 16), 0.05)
+    assert t.fallbacks == 0
+
+
+def test_config_c3_sampled_steps():
+    _run_config("c3", range(0, 256, 32), 0.3)
+
+
+def test_config_c4_sampled_steps():
+    _run_config("c4", range(0, 128, 64), 0.5)
+
+
+def test_config_c5_sampled_steps():
+    t = _run_config("c5", range(0, 128, 64), 0.1)
+    assert 0.1 < t.fallbacks / t.n < 0.45
