@@ -100,7 +100,7 @@ def test_step_budget_extremes_and_counter():
     t = case.run_steps(h, 5, 1e-3, 4000, O.COMBINE_ALL, "K_max=V")       # never a budget fallback
     _finish(t, "K_max=V")
     assert t.fallbacks == 0
-    t = case.run_steps(h, 5, 1e-9, 130, O.COMBINE_ALL, "K_max=130")      # seed fits, round-1 plan does not
+    t = case.run_steps(h, 5, 1e-15, 130, O.COMBINE_ALL, "K_max=130")      # seed fits, round-1 plan does not
     _finish(t, "K_max=130")
     assert t.fallbacks == t.n
     buf = csv.make_step_buffers(case.gidx, 4, 5, 1e-3, 0)
