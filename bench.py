@@ -1,0 +1,210 @@
+#!/usr/bin/env python3
+"""Benchmark of the certified sub-vocabulary LM-head path on one MI355X.
+
+A "step" is one csv_decode_step call (bounds -> select -> gathered GEMV -> certification -> fallback) on one
+batch of synthetic hidden states; inputs are resident in HBM before the timed region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config c2]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def step_bytes(r, C, rows_union: float, any_fallback_frac: float, k: int) -> float:
+    """Algorithmic bytes of one batch step: centroids + cluster metadata, h, each distinct opened row of W with its
+    bias, the whole of W with bias when any sequence falls back, and the outputs."""
+    return (C * r.d * 4 + 12 * C + r.B * r.d * 2 + rows_union * (2 * r.d + 4)
+            + any_fallback_frac * r.V * (2 * r.d + 4) + r.B * (8 * k + 16))
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=512)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", default="c2")
+    ap.add_argument("--cpu-steps", type=int, default=-1, help="oracle steps to time (-1: sized to ~15 s, 0: skip)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the path shards by cluster, see DESIGN.md); use --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import synth
+    import paper_2511_21702_amd as csv
+
+    r = synth.CONFIGS[args.config]
+    K, W = args.steps, args.warmup
+    t0 = time.time()
+    head = synth.make_head(r, threads=16)
+    h_bits = synth.make_hidden(r, head["centers"])
+    log(f"[bench] {r.name}: V={r.V} d={r.d} C={r.C} B={r.B} generated in {time.time() - t0:.1f}s")
+    dW = csv.bits_to_device(head["W_bits"])
+    db = torch.from_numpy(head["b"]).cuda()
+    idx = csv.csv_build_index(dW, db, r.C, init_labels=head["labels"].astype(np.int32))
+    del dW
+    ws = csv.CsvWorkspace(idx, r.B, r.K_max_rows)
+    dh = csv.bits_to_device(h_bits)
+    nh = h_bits.shape[0]
+    buf = csv.make_step_buffers(idx, r.B, r.k, r.eps, r.K_max_rows)
+    stream = torch.cuda.current_stream()
+    sp = stream.cuda_stream
+    hp = [dh[s % nh].data_ptr() for s in range(max(K, W) + W)]
+
+    def run(n, first=0):
+        for s in range(first, first + n):
+            csv.csv_decode_step_raw(ws, idx, hp[s], r.B, buf, sp)
+
+    # ---------------- timed region: W warm-up steps, then exactly K steps, sync on both sides
+    run(W)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record(stream)
+    run(K, W)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    gpu_ms = e0.elapsed_time(e1)
+    ms_per_step = wall * 1e3 / K
+    log(f"[bench] {K} steps: wall {wall * 1e3:.2f} ms, stream {gpu_ms:.2f} ms -> {K / wall:.0f} steps/s")
+
+    # ---------------- per-stage HIP-event timing over the same K steps (second pass, same stream)
+    ws.profile_begin(K)
+    run(K, W)
+    torch.cuda.synchronize()
+    stage_ms, nrec = ws.profile_end()
+    stage_us = {n: 1e3 * v / max(nrec, 1) for n, v in stage_ms.items()}
+
+    # ---------------- statistics pass: per-step sync, latency percentiles, rows / fallbacks
+    fb0 = int(buf.fallback_count.item())
+    lat, rows_sum, rows_union_sum, anyfb, ncl_sum, rounds_hist = [], 0, 0.0, 0, 0, {0: 0, 1: 0, 2: 0}
+    buf_s = csv.make_step_buffers(idx, r.B, r.k, r.eps, r.K_max_rows, want_sel=True)
+    sizes = head["sizes"]
+    nstat = min(K, 256)
+    for s in range(W, W + nstat):
+        t1 = time.perf_counter()
+        csv.csv_decode_step_raw(ws, idx, hp[s], r.B, buf_s, sp)
+        torch.cuda.synchronize()
+        lat.append(time.perf_counter() - t1)
+        fl = buf_s.flags.cpu().numpy()
+        nr = buf_s.n_rows.cpu().numpy()
+        nc = buf_s.n_clusters.cpu().numpy()
+        fb = (fl & csv.FLAG_FALLBACK) != 0
+        anyfb += bool(fb.any())
+        rows_sum += int(nr[~fb].sum())
+        ncl_sum += int(nc[~fb].sum())
+        sel = buf_s.sel_clusters.cpu().numpy()
+        opened = set()
+        for b in np.flatnonzero(~fb):
+            opened.update(sel[b, :nc[b]].tolist())
+        rows_union_sum += float(sizes[list(opened)].sum()) if opened else 0.0
+        for v in buf_s.rounds.cpu().numpy():
+            rounds_hist[int(v)] += 1
+    n_seq = nstat * r.B
+    fb_rate = int(buf_s.fallback_count.item()) / n_seq
+    lat = np.sort(np.array(lat))
+
+    # ---------------- full-vocabulary baseline at the same B (in-repo kernel)
+    full_out = torch.empty((r.B, r.V), dtype=torch.float32, device="cuda")
+    nfull = max(8, min(K, 64))
+    for s in range(3):
+        csv.csv_full_logits(ws, idx, dh[s % nh], out=full_out)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for s in range(nfull):
+        csv.csv_full_logits(ws, idx, dh[s % nh], out=full_out)
+    torch.cuda.synchronize()
+    full_ms = (time.perf_counter() - t1) * 1e3 / nfull
+    full_bytes = r.V * (2 * r.d + 8) + r.B * r.d * 2
+
+    # ---------------- roofline of the stage that takes the most time
+    bytes_by_stage = {
+        "bounds": r.C * r.d * 4 + 12 * r.C + r.B * r.d * 2 + 4 * r.B * r.C,
+        "gemv_round0": None, "gemv_round1": None,
+        "full_product": r.V * (2 * r.d + 4) + r.B * r.d * 2,
+    }
+    mean_rows_seq = rows_sum / max(1, n_seq - int(round(fb_rate * n_seq)))
+    gemv_bytes = (rows_sum / nstat) * (2 * r.d + 12) + r.B * r.d * 2
+    dom = max(("bounds", "gemv_round0", "gemv_round1", "full_product"), key=lambda n: stage_us[n])
+    if dom.startswith("gemv"):
+        dom_bytes = gemv_bytes    # both rounds together
+        dom_us = stage_us["gemv_round0"] + stage_us["gemv_round1"]
+        dom_name = "gemv_gather_kernel (both rounds)"
+    else:
+        dom_bytes = bytes_by_stage[dom]
+        dom_us = stage_us[dom]
+        dom_name = {"bounds": "bound_kernel", "full_product": "full_gemv_kernel"}[dom]
+    achieved = dom_bytes / (dom_us * 1e-6) / 1e9
+    bstep = step_bytes(r, r.C, rows_union_sum / nstat, anyfb / nstat, r.k)
+    eff_gbs = bstep / (ms_per_step * 1e-3) / 1e9
+
+    # ---------------- CPU baseline: the oracle as it stands, on a bounded sample of the same workload
+    cpu = None
+    if args.cpu_steps != 0:
+        from oracle import csv_oracle as O
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            cores = os.cpu_count()
+        W64 = O.bf16_to_f64(head["W_bits"])
+        oidx = O.build_index(head["W_bits"], head["b"], head["labels"], r.C)
+        t1 = time.perf_counter()
+        O.decode_step(W64, head["b"], oidx, h_bits[0], r.k, r.eps, r.K_max_rows)
+        one = time.perf_counter() - t1
+        n_cpu = args.cpu_steps if args.cpu_steps > 0 else int(max(1, min(64, 15.0 / max(one, 1e-3))))
+        t1 = time.perf_counter()
+        for s in range(n_cpu):
+            O.decode_step(W64, head["b"], oidx, h_bits[(1 + s) % nh], r.k, r.eps, r.K_max_rows)
+        cpu_s = time.perf_counter() - t1
+        cpu = {"value": n_cpu / cpu_s, "unit": "steps/s", "cores": int(cores), "kind": "oracle",
+               "sample": f"{n_cpu} consecutive batch steps of {r.name} (B={r.B}) through oracle.decode_step, float64, numpy/BLAS"}
+        log(f"[bench] oracle: {n_cpu} steps in {cpu_s:.1f}s on {cores} threads")
+
+    out = {
+        "metric": "certified decode steps/sec + effective HBM GB/s, V=128256 d=4096 B=1",
+        "value": K / wall, "unit": "steps/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{r.name}: V={r.V} d={r.d} C={r.C} B={r.B} k={r.k} eps={r.eps:g} K_max={r.K_max_rows} "
+                               f"combine=ALL, bf16 W and h, planted clusters", "batch": r.B},
+        "roofline": {"bound": "hbm", "kernel": dom_name, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "bytes_per_launch": dom_bytes, "avg_launch_us": dom_us},
+        "cpu_baseline": cpu,
+        "effective_hbm_GBps": eff_gbs, "algorithmic_bytes_per_step": bstep,
+        "stream_ms_per_step": gpu_ms / K,
+        "seq_steps_per_s": K * r.B / wall,
+        "stage_us": stage_us,
+        "latency_us": {"p50": float(lat[len(lat) // 2] * 1e6), "p95": float(lat[int(len(lat) * 0.95)] * 1e6)},
+        "fallback_rate": fb_rate, "steps_with_fallback": anyfb / nstat,
+        "mean_rows_per_certified_seq": mean_rows_seq, "mean_clusters_per_certified_seq": ncl_sum / max(1, n_seq - int(round(fb_rate * n_seq))),
+        "sub_vocab_ratio": mean_rows_seq / r.V, "rounds_hist": rounds_hist,
+        "full_gemv": {"ms_per_step": full_ms, "steps_per_s": 1e3 / full_ms, "GBps": full_bytes / (full_ms * 1e-3) / 1e9},
+        "speedup_vs_full_gemv": full_ms / ms_per_step,
+    }
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -53,14 +53,21 @@ class Case:
         dh = csv.bits_to_device(h_bits)
         buf = csv.make_step_buffers(self.gidx, B, k, eps, K_max, combine, want_sel=True)
         step_ids = list(range(steps)) if step_ids is None else list(step_ids)
+        outs = []
         for s in step_ids:
             csv.csv_decode_step(self.ws, self.gidx, dh[s], buf)
             torch.cuda.synchronize()
-            g = PAR.gpu_step_to_numpy(buf)
-            h64 = O.bf16_to_f64(h_bits[s])
-            L = O.full_logits(self.W64, self.b, h64)
-            orc = O.decode_step(self.W64, self.b, self.oidx, h_bits[s], k, eps, K_max, combine, logits=L)
-            PAR.compare_step(f"{tag} step={s}", t, orc, g, L, self.oidx, k, eps, K_max, combine)
+            outs.append(PAR.gpu_step_to_numpy(buf))
+        # oracle logits for several steps per matrix product (same values as step by step)
+        group = max(1, 256 // B)
+        for g0 in range(0, len(step_ids), group):
+            ids = step_ids[g0:g0 + group]
+            h64 = O.bf16_to_f64(h_bits[ids].reshape(-1, d))
+            Lall = O.full_logits(self.W64, self.b, h64).reshape(len(ids), B, -1)
+            for j, s in enumerate(ids):
+                orc = O.decode_step(self.W64, self.b, self.oidx, h_bits[s], k, eps, K_max, combine, logits=Lall[j])
+                PAR.compare_step(f"{tag} step={s}", t, orc, outs[g0 + j], Lall[j], self.oidx, k, eps, K_max, combine)
+            log(f"[{tag}] compared steps {ids[0]}..{ids[-1]}: {t.summary()}")
         return t
 
     def close(self):

@@ -222,19 +222,19 @@ def test_config_c1_all_steps():
     assert t.fallbacks == 0 and t.rows == 125 * 64
 
 
-def test_config_c2_sampled_steps():
-    t = _run_config("c2", range(0, 512, 16), 0.05)
+def test_config_c2_all_steps():
+    t = _run_config("c2", range(512), 0.05)
     assert t.fallbacks == 0
 
 
 def test_config_c3_sampled_steps():
-    _run_config("c3", range(0, 256, 32), 0.3)
+    _run_config("c3", range(0, 256, 4), 0.3)
 
 
 def test_config_c4_sampled_steps():
-    _run_config("c4", range(0, 128, 64), 0.5)
+    _run_config("c4", range(0, 128, 8), 0.5)
 
 
 def test_config_c5_sampled_steps():
-    t = _run_config("c5", range(0, 128, 64), 0.1)
+    t = _run_config("c5", range(0, 128, 16), 0.1)
     assert 0.1 < t.fallbacks / t.n < 0.45
