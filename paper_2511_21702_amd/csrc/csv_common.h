@@ -24,31 +24,41 @@ struct csv_index {
 };
 
 enum { ST_ACTIVE = 0, ST_DONE = 1, ST_FALLBACK = 2, ST_INVALID = 3 };
+enum { CNT_FALLBACK = 0, CNT_TILES0 = 1, CNT_TILES1 = 2 };
 
+// A cluster's position in the bound order is carried by one 64-bit key: monotone image of U_c in the high word,
+// ~c in the low word.  Larger key = larger bound, equal bounds = smaller cluster id first.  Empty clusters have key 0.
+// The open set of a sequence is always {c : key_c >= kappa}.
 struct SeqState {
     int status;
-    int m0, m1;       // clusters open after round 0 / planned for round 1
-    int fb_slot;      // row of the fallback logits buffer
-    float theta0, Z0; // k-th largest logit and log-sum-exp after round 0
-    int pad[2];
+    int n_open;               // clusters open
+    int n_rows;               // rows scored or planned so far (= positions used in slog / sid)
+    int rounds;               // scoring rounds completed
+    unsigned long long kappa; // threshold key of the open set
+    float nxtU;               // largest bound among unopened clusters (-inf if none)
+    float T;                  // log tail mass  log sum_{unopened} n_c exp(U_c)
+    int fb_slot;              // row of the fallback logits buffer
+    int pad[3];
+};
+
+// Work item of the gathered GEMV: nrows (<= 8) consecutive rows of W' from row0, results to positions pos.. of sequence b.
+struct Tile {
+    int b, row0, nrows, pos;
 };
 
 struct csv_workspace {
     int B_max, K_cap, V, d, C, Npad;   // Npad: C rounded up to a power of two (sort width)
     int n_chunks;                      // fallback top-k chunks per sequence
+    int tile_cap;                      // entries of each tile list
     int device;
     float* U;          // [B*C]      cluster bounds
     float* hnorm;      // [B]
-    int32_t* order;    // [B*C]      cluster ids by descending bound
-    float* su;         // [B*C]      bounds in that order
-    float* T;          // [B*(C+1)]  log tail mass with the first m clusters open
-    int32_t* P;        // [B*(C+1)]  rows in the first m clusters
     SeqState* st;      // [B]
-    int32_t* rstart;   // [B]        first position of slog/rowmap to score this round
-    int32_t* rcount;   // [B]        positions to score this round (0: nothing to do)
-    float* slog;       // [B*K_cap]  logits of opened rows, in opening order
-    int32_t* rowmap;   // [B*K_cap]  permuted row index of each opened position
-    int32_t* counters; // [16]       [0] = number of fallback sequences this step
+    int32_t* sel;      // [B*C]      opened cluster ids
+    float* slog;       // [B*K_cap]  logits of opened rows
+    int32_t* sid;      // [B*K_cap]  their original token ids
+    Tile* tiles[2];    // work lists of round 0 / round 1
+    int32_t* counters; // [16]       CNT_*
     int32_t* fb_list;  // [B]        sequences that fall back this step
     int32_t* all_list; // [B]        0..B-1 (csv_full_logits runs the fallback product over everyone)
     float* fb_logits;  // [B*V]      full logits of fallback sequences (permuted row order)
@@ -166,6 +176,26 @@ __device__ __forceinline__ int block_min_i(int v, int* red) {
     return r;
 }
 
+__device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const unsigned long long y = __shfl_xor(v, o, CSV_WAVE);
+        v = y > v ? y : v;
+    }
+    return v;
+}
+// red: >= 16 64-bit words of LDS
+__device__ __forceinline__ unsigned long long block_max_u64(unsigned long long v, unsigned long long* red) {
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+    v = wave_max_u64(v);
+    __syncthreads();
+    if (lane == 0) red[w] = v;
+    __syncthreads();
+    unsigned long long r = red[0];
+    for (int i = 1; i < nw; ++i) r = red[i] > r ? red[i] : r;
+    return r;
+}
+
 // Monotone map float -> uint32: a > b  <=>  fkey(a) > fkey(b)  (for non-NaN values; -0 < +0)
 __device__ __forceinline__ uint32_t fkey(float f) {
     uint32_t u = __float_as_uint(f);
@@ -186,6 +216,37 @@ __device__ __forceinline__ LseAcc lse_combine(LseAcc a, LseAcc b) {
     LseAcc r;
     r.m = fmaxf(a.m, b.m);
     r.s = a.s * expf(a.m - r.m) + b.s * expf(b.m - r.m);
+    return r;
+}
+// fold one more value into a running partial
+__device__ __forceinline__ LseAcc lse_push(LseAcc a, float x) {
+    if (x == -INFINITY) return a;
+    if (a.s == 0.f) {
+        a.m = x;
+        a.s = 1.f;
+    } else if (x > a.m) {
+        a.s = a.s * expf(a.m - x) + 1.f;
+        a.m = x;
+    } else {
+        a.s += expf(x - a.m);
+    }
+    return a;
+}
+// Block-wide combination in a fixed order; every thread gets the result.  red: >= 16 LseAcc of LDS.
+__device__ __forceinline__ LseAcc block_lse_combine(LseAcc v, LseAcc* red) {
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        LseAcc y;
+        y.m = __shfl_down(v.m, o, CSV_WAVE);
+        y.s = __shfl_down(v.s, o, CSV_WAVE);
+        if (lane + o < 64) v = lse_combine(v, y);
+    }
+    __syncthreads();
+    if (lane == 0) red[w] = v;
+    __syncthreads();
+    LseAcc r = red[0];
+    for (int i = 1; i < nw; ++i) r = lse_combine(r, red[i]);
     return r;
 }
 __device__ __forceinline__ float lse_value(LseAcc a) { return a.s == 0.f ? -INFINITY : a.m + logf(a.s); }

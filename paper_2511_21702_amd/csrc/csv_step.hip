@@ -1,13 +1,16 @@
 // Per-step kernels of the certified sub-vocabulary LM-head path and the entry points that enqueue them.
 //
-//   bound_kernel        U[b,c] = <mu_c,h_b> + R_c ||h_b|| + bmax_c              (Eq. "cluster_bound")
-//   select0_kernel      order clusters by bound, prefix rows P, log tail mass T, seed prefix m0   (Algorithm 1: queue)
-//   gemv_gather_kernel  logits of the opened rows of W' (contiguous per cluster)                   (Algorithm 1: sparse GEMV)
-//   cert_kernel         k-th largest / top-k, log-sum-exp, both certificates, round-1 plan          (Definitions 1-2, Theorems 1-2)
-//   full_gemv_kernel    all V logits for the sequences that fall back                               (Eq. "logit")
+//   bound_kernel       U[b,c] = <mu_c,h_b> + R_c ||h_b|| + bmax_c                               (Eq. "cluster_bound")
+//   seed_kernel        shortest prefix of the bound order holding >= max(k,1) rows, next bound, log tail mass;
+//                      compaction of the opened clusters into row tiles                         (Algorithm 1: queue, PopMax)
+//   gemv_tiles_kernel  logits of the opened rows of W' (contiguous per cluster)                 (Algorithm 1: sparse GEMV)
+//   cert_kernel        top-k, log-sum-exp, both certificates; round-1 plan and compaction       (Definitions 1-2, Theorems 1-2)
+//   full_gemv_kernel   all V logits for the sequences that fall back                            (Eq. "logit")
 //   fb_topk_kernel / fb_final_kernel   top-k and log-sum-exp over V for those sequences
 //
 // Everything is enqueued on the caller's stream; decisions (round 1, fallback) are taken on the device.
+// The open set of a sequence is {c : key_c >= kappa} for a 64-bit key that encodes (bound, cluster id), so the
+// common path needs reductions only; the bound order is sorted only when the softmax test asks for a longer prefix.
 #include "csv_common.h"
 
 #include <math.h>
@@ -39,15 +42,11 @@ struct StepArgs {
     int B, K_cap, Npad, n_chunks;
     float* U;
     float* hnorm;
-    int32_t* order;
-    float* su;
-    float* T;
-    int32_t* P;
     SeqState* st;
-    int32_t* rstart;
-    int32_t* rcount;
+    int32_t* sel;
     float* slog;
-    int32_t* rowmap;
+    int32_t* sid;
+    Tile* tiles[2];
     int32_t* counters;
     int32_t* fb_list;
     float* fb_logits;
@@ -61,15 +60,26 @@ struct StepArgs {
     csv_step_out out;
 };
 
-#define GEMV_ROWS_PER_WAVE 2
-#define GEMV_TILE (4 * GEMV_ROWS_PER_WAVE)   // rows per work item of the gathered GEMV (4 waves per block)
-#define FB_CHUNK 8192                        // rows per block of the fallback top-k first stage
-#define FULL_G 4                             // sequences per pass of the vector full-vocabulary product
+#define TILE_ROWS 8        // rows per work item of the gathered GEMV (4 waves x 2 rows)
+#define SEQ_THREADS 512    // block size of the per-sequence kernels (seed, cert, fallback top-k)
+#define STAGE_CAP 4096     // scored logits kept in LDS by cert_kernel when a sequence has at most this many
+#define FB_CHUNK 8192      // rows per block of the fallback top-k first stage
+#define FULL_G 4           // sequences per pass of the vector full-vocabulary product
+#define BIGQ 32            // clusters whose tiles are written cooperatively per emit call
+
+typedef unsigned long long u64;
+
+// Key of a value for ordering: -0 and +0 compare equal.
+__device__ __forceinline__ uint32_t lkey(float v) { return fkey(v + 0.0f); }
+__device__ __forceinline__ u64 ckey(float U, int c) { return ((u64)lkey(U) << 32) | (u64)(0xFFFFFFFFu - (uint32_t)c); }
+__device__ __forceinline__ float ckey_bound(u64 k) { return fkey_inv((uint32_t)(k >> 32)); }
 
 // ================================================================================================ bounds
-// One wave per cluster, BT sequences per block.  h is staged in LDS as bf16; centroids stream as float4.
+// One wave per cluster, BT sequences per block.  The first 16 KB of the wave's centroid row is requested before
+// h is staged (the two do not depend on each other); h sits in LDS as bf16.
 // Blocks are dealt round-robin to the 8 XCDs, so group g = (block % 8) * groups_per_xcd + block / 8 keeps
 // every XCD on the same centroid slice step after step (the slice stays resident in that XCD's L2).
+#define BOUND_PF 16
 template <int BT>
 __global__ __launch_bounds__(256) void bound_kernel(StepArgs a, float* __restrict__ U_out, float* __restrict__ hn_out,
                                                     int reset_counters, int groups, int groups_per_xcd) {
@@ -78,7 +88,24 @@ __global__ __launch_bounds__(256) void bound_kernel(StepArgs a, float* __restric
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int b0 = blockIdx.y * BT;
     const int nb = min(BT, a.B - b0);
-    const int nch = a.d >> 3;
+    const int nch = a.d >> 3, nq = a.d >> 2;
+    const int g = (blockIdx.x & 7) * groups_per_xcd + (blockIdx.x >> 3);
+    const int c = g * 4 + wave;
+    const bool valid = g < groups && c < a.C;
+    const float4* mrow = reinterpret_cast<const float4*>(a.mu + (size_t)(valid ? c : 0) * a.d);
+    float4 pf[BOUND_PF];
+#pragma unroll
+    for (int j = 0; j < BOUND_PF; ++j) {
+        const int i = lane + 64 * j;
+        pf[j] = (valid && i < nq) ? mrow[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    float Rc = 0.f, bm = 0.f;
+    int ncl = 0;
+    if (valid && lane == 0) {
+        Rc = a.R[c];
+        bm = a.bmax[c];
+        ncl = a.n[c];
+    }
     const uint4* hsrc = reinterpret_cast<const uint4*>(a.h) + (size_t)b0 * nch;
     for (int i = tid; i < BT * nch; i += 256) hs4[i] = (i < nb * nch) ? hsrc[i] : make_uint4(0, 0, 0, 0);
     if (reset_counters && blockIdx.x == 0 && blockIdx.y == 0 && tid < 16) a.counters[tid] = 0;
@@ -94,19 +121,29 @@ __global__ __launch_bounds__(256) void bound_kernel(StepArgs a, float* __restric
     }
     __syncthreads();
     if (blockIdx.x == 0 && tid < nb && hn_out) hn_out[b0 + tid] = hn[tid];
+    if (!valid) return;
 
-    const int g = (blockIdx.x & 7) * groups_per_xcd + (blockIdx.x >> 3);
-    if (g >= groups || (blockIdx.x >> 3) >= groups_per_xcd) return;
-    const int c = g * 4 + wave;
-    if (c >= a.C) return;
-    const float4* mrow = reinterpret_cast<const float4*>(a.mu + (size_t)c * a.d);
     const uint2* hs2 = reinterpret_cast<const uint2*>(hs4);
-    const int nq = a.d >> 2;
     float acc[BT];
 #pragma unroll
     for (int s = 0; s < BT; ++s) acc[s] = 0.f;
+#pragma unroll
+    for (int j = 0; j < BOUND_PF; ++j) {
+        const int i = lane + 64 * j;
+        if (i < nq) {
+            const float4 m = pf[j];
+#pragma unroll
+            for (int s = 0; s < BT; ++s) {
+                const uint2 hv = hs2[s * nq + i];
+                acc[s] = fmaf(m.x, bf16_lo(hv.x), acc[s]);
+                acc[s] = fmaf(m.y, bf16_hi(hv.x), acc[s]);
+                acc[s] = fmaf(m.z, bf16_lo(hv.y), acc[s]);
+                acc[s] = fmaf(m.w, bf16_hi(hv.y), acc[s]);
+            }
+        }
+    }
 #pragma unroll 4
-    for (int i = lane; i < nq; i += 64) {
+    for (int i = lane + 64 * BOUND_PF; i < nq; i += 64) {
         const float4 m = mrow[i];
 #pragma unroll
         for (int s = 0; s < BT; ++s) {
@@ -120,8 +157,7 @@ __global__ __launch_bounds__(256) void bound_kernel(StepArgs a, float* __restric
 #pragma unroll
     for (int s = 0; s < BT; ++s) acc[s] = wave_sum(acc[s]);
     if (lane == 0) {
-        const float Rc = a.R[c], bm = a.bmax[c];
-        const bool empty = a.n[c] == 0;
+        const bool empty = ncl == 0;
 #pragma unroll
         for (int s = 0; s < BT; ++s)
             if (s < nb) U_out[(size_t)(b0 + s) * a.C + c] = empty ? -INFINITY : (acc[s] + Rc * hn[s] + bm);
@@ -129,7 +165,7 @@ __global__ __launch_bounds__(256) void bound_kernel(StepArgs a, float* __restric
 }
 
 // ================================================================================================ block scans
-// Exclusive prefix sum over one int per thread (blockDim <= 1024).  wtot: 17 ints of LDS.
+// Exclusive prefix sum over one int per thread (blockDim <= 1024).  wtot: 16 ints of LDS.
 __device__ __forceinline__ int block_excl_scan_i(int v, int* wtot, int* total) {
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
     int x = v;
@@ -161,7 +197,6 @@ __device__ __forceinline__ LseAcc block_excl_suffix_lse(LseAcc v, LseAcc* wtot) 
         y.s = __shfl_down(x.s, o, CSV_WAVE);
         if (lane + o < 64) x = lse_combine(x, y);
     }
-    // x = combination of lanes lane..63 of this wave
     LseAcc after;
     after.m = __shfl_down(x.m, 1, CSV_WAVE);
     after.s = __shfl_down(x.s, 1, CSV_WAVE);
@@ -179,7 +214,24 @@ __device__ __forceinline__ LseAcc block_excl_suffix_lse(LseAcc v, LseAcc* wtot) 
     return lse_combine(after, tail);
 }
 
-// ================================================================================================ helpers shared by select/cert
+// ================================================================================================ shared LDS of the per-sequence kernels
+struct BigItem {
+    int row0, n, pos, tbase;
+};
+struct SeqShared {
+    unsigned hist[256];
+    float redf[16];
+    int redi[16];
+    u64 redu[16];
+    LseAcc redl[16];
+    unsigned sel, rem, eq, cnt;
+    int tbase, nbig;
+    BigItem big[BIGQ];
+    float wval[CSV_MAX_K];
+    int wid[CSV_MAX_K];
+};
+
+// ================================================================================================ helpers shared by seed/cert
 __device__ __forceinline__ void write_invalid(const StepArgs& a, int b) {
     for (int t = threadIdx.x; t < a.k; t += blockDim.x) {
         a.out.d_ids[(size_t)b * a.k + t] = -1;
@@ -191,207 +243,190 @@ __device__ __forceinline__ void write_invalid(const StepArgs& a, int b) {
         a.out.d_n_rows[b] = 0;
         a.out.d_n_clusters[b] = 0;
         if (a.out.d_rounds) a.out.d_rounds[b] = 0;
+        a.st[b].status = ST_INVALID;
     }
 }
 
 // Called by one thread: hand sequence b to the full-vocabulary path.
 __device__ __forceinline__ void push_fallback(const StepArgs& a, int b, int rounds) {
-    const int slot = atomicAdd(&a.counters[0], 1);
+    const int slot = atomicAdd(&a.counters[CNT_FALLBACK], 1);
     a.fb_list[slot] = b;
     a.st[b].status = ST_FALLBACK;
     a.st[b].fb_slot = slot;
-    a.rcount[b] = 0;
     if (a.out.d_rounds) a.out.d_rounds[b] = rounds;
 }
 
-// Record the permuted row of every position opened by clusters [j0,j1) of sequence b's order (one wave per cluster).
-__device__ __forceinline__ void write_rowmap(const StepArgs& a, int b, int j0, int j1) {
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, nw = blockDim.x >> 6;
-    for (int j = j0 + w; j < j1; j += nw) {
-        const int c = a.order[(size_t)b * a.C + j];
-        const int p0 = a.P[(size_t)b * (a.C + 1) + j];
-        const int r0 = a.off[c], nc = a.n[c];
-        int32_t* dst = a.rowmap + (size_t)b * a.K_cap + p0;
-        for (int r = lane; r < nc; r += 64) dst[r] = r0 + r;
+// Opens every cluster c with flag(c): its rows get consecutive positions from pos_base on (cluster id order), its
+// row tiles are appended to the round's work list, its id is appended to the sequence's list of opened clusters.
+// nl: rows per cluster (LDS).  All threads of the block call; flag must be the same function of c in both passes.
+template <class FlagFn>
+__device__ __forceinline__ void emit_clusters(const StepArgs& a, int b, int round, int pos_base, int sel_base, FlagFn flag,
+                                              const int* nl, SeqShared& s) {
+    const int tid = threadIdx.x, nt = blockDim.x, C = a.C;
+    const int E = (C + nt - 1) / nt;
+    const int c0 = min(C, tid * E), c1 = min(C, c0 + E);
+    int cnt = 0, rows = 0, tiles = 0;
+    for (int c = c0; c < c1; ++c)
+        if (flag(c)) {
+            const int n = nl[c];
+            cnt += 1;
+            rows += n;
+            tiles += (n + TILE_ROWS - 1) / TILE_ROWS;
+        }
+    int tot_tiles;
+    const int bc = block_excl_scan_i(cnt, s.redi, nullptr);
+    const int br = block_excl_scan_i(rows, s.redi, nullptr);
+    const int bt = block_excl_scan_i(tiles, s.redi, &tot_tiles);
+    if (tid == 0) {
+        s.tbase = tot_tiles > 0 ? atomicAdd(&a.counters[CNT_TILES0 + round], tot_tiles) : 0;
+        s.nbig = 0;
+    }
+    __syncthreads();
+    Tile* tl = a.tiles[round];
+    int tb = s.tbase + bt, pos = pos_base + br, si = sel_base + bc;
+    for (int c = c0; c < c1; ++c)
+        if (flag(c)) {
+            const int n = nl[c], r0 = a.off[c], ntc = (n + TILE_ROWS - 1) / TILE_ROWS;
+            a.sel[(size_t)b * C + si++] = c;
+            int slot = BIGQ;
+            if (ntc > 16) slot = atomicAdd(&s.nbig, 1);
+            if (slot < BIGQ) {
+                BigItem it;
+                it.row0 = r0; it.n = n; it.pos = pos; it.tbase = tb;
+                s.big[slot] = it;
+            } else {
+                for (int t = 0; t < ntc; ++t) {
+                    Tile x;
+                    x.b = b; x.row0 = r0 + t * TILE_ROWS; x.nrows = min(TILE_ROWS, n - t * TILE_ROWS); x.pos = pos + t * TILE_ROWS;
+                    tl[tb + t] = x;
+                }
+            }
+            tb += ntc;
+            pos += n;
+        }
+    __syncthreads();
+    const int nbig = min(s.nbig, BIGQ);
+    for (int q = 0; q < nbig; ++q) {
+        const BigItem it = s.big[q];
+        const int ntc = (it.n + TILE_ROWS - 1) / TILE_ROWS;
+        for (int t = tid; t < ntc; t += nt) {
+            Tile x;
+            x.b = b; x.row0 = it.row0 + t * TILE_ROWS; x.nrows = min(TILE_ROWS, it.n - t * TILE_ROWS); x.pos = it.pos + t * TILE_ROWS;
+            tl[it.tbase + t] = x;
+        }
+    }
+    __syncthreads();
+}
+
+// Largest bound and log tail mass over the unopened clusters {c : 0 < key_c < kappa}.
+__device__ __forceinline__ void tail_stats(const StepArgs& a, const u64* keys, u64 kappa, SeqShared& s, float& nxtU, float& T) {
+    u64 best = 0;
+    LseAcc acc;
+    acc.m = -INFINITY;
+    acc.s = 0.f;
+    for (int c = threadIdx.x; c < a.C; c += blockDim.x) {
+        const u64 kx = keys[c];
+        if (kx != 0 && kx < kappa) {
+            best = kx > best ? kx : best;
+            acc = lse_push(acc, a.lnn[c] + ckey_bound(kx));
+        }
+    }
+    best = block_max_u64(best, s.redu);
+    acc = block_lse_combine(acc, s.redl);
+    nxtU = best ? ckey_bound(best) : -INFINITY;
+    T = lse_value(acc);
+}
+
+// keys[c] and rows-per-cluster of sequence b into LDS
+__device__ __forceinline__ void load_keys(const StepArgs& a, int b, u64* keys, int* nl) {
+    for (int c = threadIdx.x; c < a.C; c += blockDim.x) {
+        const float u = a.U[(size_t)b * a.C + c];
+        const int n = a.n[c];
+        nl[c] = n;
+        keys[c] = n > 0 ? ckey(u, c) : 0ull;
     }
 }
 
-// ================================================================================================ select (round 0)
-// One block per sequence.  Sorts (bound, cluster) pairs with a bitonic network on 64-bit keys
-// (monotone image of the bound in the high word, ~cluster id in the low word: descending key order is
-// descending bound, equal bounds by ascending id), then scans row counts and log tail masses.
-__global__ __launch_bounds__(1024) void select0_kernel(StepArgs a) {
-    extern __shared__ unsigned long long keys[];
-    __shared__ int wtot_i[17];
-    __shared__ LseAcc wtot_l[17];
-    __shared__ int s_m0, s_rows0;
-    const int b = blockIdx.x, tid = threadIdx.x, nt = blockDim.x;
-    const int C = a.C, N = a.Npad;
+// ================================================================================================ seed (round 0)
+// One block per sequence.  The seed prefix is found by repeated block-wide arg-max over the keys (it is a
+// handful of clusters), not by sorting.
+__global__ __launch_bounds__(SEQ_THREADS) void seed_kernel(StepArgs a) {
+    extern __shared__ u64 arena[];
+    __shared__ SeqShared s;
+    const int b = blockIdx.x, tid = threadIdx.x, nt = blockDim.x, C = a.C;
+    u64* keys = arena;
+    int* nl = reinterpret_cast<int*>(keys + C);
     const float hn = a.hnorm[b];
+    load_keys(a, b, keys, nl);
     if (!isfinite(hn)) {
         write_invalid(a, b);
-        if (tid == 0) {
-            a.st[b].status = ST_INVALID;
-            a.rcount[b] = 0;
-        }
         return;
     }
-    for (int i = tid; i < N; i += nt) {
-        unsigned long long kx = 0ull;
-        if (i < C) kx = ((unsigned long long)fkey(a.U[(size_t)b * C + i]) << 32) | (unsigned long long)(0xFFFFFFFFu - (uint32_t)i);
-        keys[i] = kx;
-    }
     __syncthreads();
-    for (int k2 = 2; k2 <= N; k2 <<= 1) {
-        for (int j = k2 >> 1; j > 0; j >>= 1) {
-            for (int i = tid; i < N; i += nt) {
-                const int ixj = i ^ j;
-                if (ixj > i) {
-                    const unsigned long long x = keys[i], y = keys[ixj];
-                    const bool first_larger = (i & k2) == 0;
-                    if (first_larger ? (x < y) : (x > y)) {
-                        keys[i] = y;
-                        keys[ixj] = x;
-                    }
-                }
-            }
-            __syncthreads();
-        }
-    }
-    // each thread owns E consecutive sorted positions
-    const int E = N >= nt ? N / nt : 1;
-    const int j0 = tid * E;
-    int nloc[8];
-    LseAcc vloc[8];
-    int nsum = 0;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        nloc[e] = 0;
-        vloc[e].m = -INFINITY;
-        vloc[e].s = 0.f;
-        const int j = j0 + e;
-        if (e < E && j < C) {
-            const unsigned long long kx = keys[j];
-            const int c = (int)(0xFFFFFFFFu - (uint32_t)kx);
-            const float u = fkey_inv((uint32_t)(kx >> 32));
-            a.order[(size_t)b * C + j] = c;
-            a.su[(size_t)b * C + j] = u;
-            nloc[e] = a.n[c];
-            const float v = a.lnn[c] + u;
-            if (nloc[e] > 0 && v > -INFINITY) {
-                vloc[e].m = v;
-                vloc[e].s = 1.f;
-            }
-        }
-        nsum += nloc[e];
-    }
-    const int base = block_excl_scan_i(nsum, wtot_i, nullptr);
-    // suffix log-sum-exp inside the thread, then across threads
-    LseAcc suf[8];
-    LseAcc run;
-    run.m = -INFINITY;
-    run.s = 0.f;
-#pragma unroll
-    for (int e = 7; e >= 0; --e) {
-        run = lse_combine(vloc[e], run);
-        suf[e] = run;
-    }
-    const LseAcc after = block_excl_suffix_lse(run, wtot_l);
     const int need = max(a.k, 1);
-    int32_t* Pb = a.P + (size_t)b * (C + 1);
-    float* Tb = a.T + (size_t)b * (C + 1);
-    if (tid == 0) {
-        Pb[0] = 0;
-        Tb[C] = -INFINITY;
-    }
-    int pin = base;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        const int j = j0 + e;
-        if (e < E && j < C) {
-            const int pex = pin;
-            pin += nloc[e];
-            Pb[j + 1] = pin;
-            Tb[j] = lse_value(lse_combine(suf[e], after));
-            if (pex < need && pin >= need) {
-                s_m0 = j + 1;
-                s_rows0 = pin;
-            }
+    int rows = 0, m0 = 0;
+    u64 kappa = ~0ull;
+    while (rows < need) {
+        u64 best = 0;
+        for (int c = tid; c < C; c += nt) {
+            const u64 kx = keys[c];
+            if (kx < kappa && kx > best) best = kx;
         }
+        best = block_max_u64(best, s.redu);
+        if (best == 0) break;   // no cluster left (cannot happen while k <= V)
+        rows += nl[(int)(0xFFFFFFFFu - (uint32_t)best)];
+        m0 += 1;
+        kappa = best;
     }
-    __threadfence_block();
-    __syncthreads();
-    const int m0 = s_m0;
-    const int rows0 = s_rows0;
-    if (rows0 > a.K_max) {
+    float nxtU, T0;
+    tail_stats(a, keys, kappa, s, nxtU, T0);
+    if (rows > a.K_max) {
         if (tid == 0) {
-            a.st[b].m0 = m0;
-            a.st[b].m1 = m0;
+            a.st[b].n_open = m0;
+            a.st[b].n_rows = rows;
             push_fallback(a, b, 0);
         }
         return;
     }
-    write_rowmap(a, b, 0, m0);
+    emit_clusters(a, b, 0, 0, 0, [&](int c) { return keys[c] >= kappa; }, nl, s);
     if (tid == 0) {
-        a.st[b].status = ST_ACTIVE;
-        a.st[b].m0 = m0;
-        a.st[b].m1 = m0;
-        a.rstart[b] = 0;
-        a.rcount[b] = rows0;
+        SeqState st;
+        st.status = ST_ACTIVE; st.n_open = m0; st.n_rows = rows; st.rounds = 0; st.kappa = kappa; st.nxtU = nxtU; st.T = T0;
+        st.fb_slot = -1; st.pad[0] = st.pad[1] = st.pad[2] = 0;
+        a.st[b] = st;
     }
 }
 
 // ================================================================================================ gathered GEMV
-// Work item = GEMV_TILE consecutive opened positions of one sequence.  A block stages the sequence's h in LDS
-// (bf16) and each wave streams two rows of W' at a time with 128-bit loads, float32 accumulation, wave reduction.
-__global__ __launch_bounds__(256) void gemv_gather_kernel(StepArgs a) {
+// Work item = up to TILE_ROWS consecutive rows of W' for one sequence.  A block stages the sequence's h in LDS
+// (bf16) and each wave streams two rows at a time with 128-bit loads, float32 accumulation, wave reduction.
+__global__ __launch_bounds__(256) void gemv_tiles_kernel(StepArgs a, int round) {
     extern __shared__ uint4 hs4[];
-    __shared__ int pre[CSV_MAX_BATCH + 1];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    // tiles per sequence, then an inclusive prefix over sequences (B <= 256 = blockDim)
-    {
-        const int mine = tid < a.B ? (a.rcount[tid] + GEMV_TILE - 1) / GEMV_TILE : 0;
-        int x = mine;
-#pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-            const int y = __shfl_up(x, o, CSV_WAVE);
-            if (lane >= o) x += y;
-        }
-        __shared__ int wsum[4];
-        if (lane == 63) wsum[wave] = x;
-        __syncthreads();
-        int base = 0;
-        for (int i = 0; i < wave; ++i) base += wsum[i];
-        if (tid == 0) pre[0] = 0;
-        pre[tid + 1] = base + x;
-    }
-    __syncthreads();
-    const int total = pre[a.B];
+    const Tile* tl = a.tiles[round];
+    Tile t = tl[blockIdx.x];                       // speculative: the list always has >= gridDim.x entries allocated
+    const int total = a.counters[CNT_TILES0 + round];
     const int nch = a.d >> 3;
     int cur_b = -1;
     for (int g = blockIdx.x; g < total; g += gridDim.x) {
-        int lo = 0, hi = a.B;   // largest b with pre[b] <= g
-        while (hi - lo > 1) {
-            const int mid = (lo + hi) >> 1;
-            if (pre[mid] <= g) lo = mid; else hi = mid;
-        }
-        const int b = lo;
-        if (b != cur_b) {
+        if (g != (int)blockIdx.x) t = tl[g];
+        if (t.b != cur_b) {
             __syncthreads();
-            const uint4* hsrc = reinterpret_cast<const uint4*>(a.h) + (size_t)b * nch;
+            const uint4* hsrc = reinterpret_cast<const uint4*>(a.h) + (size_t)t.b * nch;
             for (int i = tid; i < nch; i += 256) hs4[i] = hsrc[i];
             __syncthreads();
-            cur_b = b;
+            cur_b = t.b;
         }
-        const int t = g - pre[b];
-        const int pbeg = a.rstart[b] + t * GEMV_TILE;
-        const int pend = min(a.rstart[b] + a.rcount[b], pbeg + GEMV_TILE);
-        const int p = pbeg + wave * GEMV_ROWS_PER_WAVE;
-        if (p >= pend) continue;
-        const int32_t* rm = a.rowmap + (size_t)b * a.K_cap;
-        const int r0 = rm[p];
-        const bool two = p + 1 < pend;
-        const int r1 = two ? rm[p + 1] : r0;
+        const int i0 = wave * 2;
+        if (i0 >= t.nrows) continue;
+        const bool two = i0 + 1 < t.nrows;
+        const int r0 = t.row0 + i0, r1 = two ? r0 + 1 : r0;
+        float b0 = 0.f, b1 = 0.f;
+        int id0 = 0, id1 = 0;
+        if (lane == 0) {
+            b0 = a.bp[r0]; id0 = a.perm[r0];
+            b1 = a.bp[r1]; id1 = a.perm[r1];
+        }
         const uint4* w0 = reinterpret_cast<const uint4*>(a.Wp + (size_t)r0 * a.d);
         const uint4* w1 = reinterpret_cast<const uint4*>(a.Wp + (size_t)r1 * a.d);
         float acc0 = 0.f, acc1 = 0.f;
@@ -417,35 +452,25 @@ __global__ __launch_bounds__(256) void gemv_gather_kernel(StepArgs a) {
         acc0 = wave_sum(acc0);
         acc1 = wave_sum(acc1);
         if (lane == 0) {
-            float* dst = a.slog + (size_t)b * a.K_cap;
-            dst[p] = acc0 + a.bp[r0];
-            if (two) dst[p + 1] = acc1 + a.bp[r1];
+            const size_t o = (size_t)t.b * a.K_cap + t.pos + i0;
+            a.slog[o] = acc0 + b0;
+            a.sid[o] = id0;
+            if (two) {
+                a.slog[o + 1] = acc1 + b1;
+                a.sid[o + 1] = id1;
+            }
         }
     }
 }
 
 // ================================================================================================ block top-k
-struct TopkShared {
-    unsigned hist[256];
-    unsigned suf[257];
-    float red[16];
-    int redi[16];
-    unsigned sel, rem, eq, cnt;
-    float wval[CSV_MAX_K];
-    int wid[CSV_MAX_K];
-    float oval[CSV_MAX_K];
-    int oid[CSV_MAX_K];
-};
-
-// Key of a logit for selection: -0 and +0 compare equal.
-__device__ __forceinline__ uint32_t lkey(float v) { return fkey(v + 0.0f); }
-
 // kk-th largest key among the elements for which key(i, kx) returns true (1 <= kk <= their number).
 // On return: kth = that key, need_eq = how many elements equal to it belong to the largest kk, n_eq = how many equal it.
+// Needs blockDim.x >= 256.
 template <class KeyFn>
-__device__ __forceinline__ void radix_select(int n, unsigned kk, KeyFn key, TopkShared& s, unsigned& kth,
+__device__ __forceinline__ void radix_select(int n, unsigned kk, KeyFn key, SeqShared& s, unsigned& kth,
                                              unsigned& need_eq, unsigned& n_eq) {
-    const int tid = threadIdx.x, nt = blockDim.x;
+    const int tid = threadIdx.x, nt = blockDim.x, lane = tid & 63;
     unsigned prefix = 0, mask = 0, rem = kk, eq = 0;
     for (int shift = 24; shift >= 0; shift -= 8) {
         for (int t = tid; t < 256; t += nt) s.hist[t] = 0;
@@ -455,25 +480,27 @@ __device__ __forceinline__ void radix_select(int n, unsigned kk, KeyFn key, Topk
             if (key(i, kx) && (kx & mask) == prefix) atomicAdd(&s.hist[(kx >> shift) & 255u], 1u);
         }
         __syncthreads();
-        if (tid < 256) s.suf[tid] = s.hist[tid];
-        if (tid == 0) s.suf[256] = 0;
-        __syncthreads();
-        for (int o = 1; o < 256; o <<= 1) {
-            unsigned v = 0;
-            if (tid < 256) {
-                v = s.suf[tid];
-                if (tid + o < 256) v += s.suf[tid + o];
+        if (tid < 64) {
+            // lane l owns bins 4l..4l+3; suffix sums by a descending scan inside the first wave
+            const unsigned h0 = s.hist[4 * lane], h1 = s.hist[4 * lane + 1], h2 = s.hist[4 * lane + 2], h3 = s.hist[4 * lane + 3];
+            const unsigned mine = h0 + h1 + h2 + h3;
+            unsigned x = mine;
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const unsigned y = __shfl_down(x, o, CSV_WAVE);
+                if (lane + o < 64) x += y;
             }
-            __syncthreads();
-            if (tid < 256) s.suf[tid] = v;
-            __syncthreads();
-        }
-        if (tid < 256) {
-            const unsigned ge = s.suf[tid], gt = s.suf[tid + 1];
-            if (ge >= rem && gt < rem) {
-                s.sel = (unsigned)tid;
+            const unsigned gt3 = x - mine;          // elements in bins above 4l+3
+            const unsigned gt2 = gt3 + h3, gt1 = gt2 + h2, gt0 = gt1 + h1, ge0 = gt0 + h0;
+            if (ge0 >= rem && gt3 < rem) {           // the kk-th falls into one of my bins
+                unsigned selb, gt, cntb;
+                if (gt2 >= rem) { selb = 3; gt = gt3; cntb = h3; }
+                else if (gt1 >= rem) { selb = 2; gt = gt2; cntb = h2; }
+                else if (gt0 >= rem) { selb = 1; gt = gt1; cntb = h1; }
+                else { selb = 0; gt = gt0; cntb = h0; }
+                s.sel = 4u * lane + selb;
                 s.rem = rem - gt;
-                s.eq = ge - gt;
+                s.eq = cntb;
             }
         }
         __syncthreads();
@@ -481,21 +508,41 @@ __device__ __forceinline__ void radix_select(int n, unsigned kk, KeyFn key, Topk
         mask |= 0xffu << shift;
         rem = s.rem;
         eq = s.eq;
-        __syncthreads();
     }
     kth = prefix;
     need_eq = rem;
     n_eq = eq;
 }
 
-// Largest min(k,n) of n values in order (value descending, id ascending).  Result in s.oval / s.oid.
-// Needs blockDim.x >= 256.  val(i) and id_of(i) may read global memory; id_of is only evaluated for elements
-// that reach the selection boundary.
+// Largest min(k,n) of n values in order (value descending, id ascending).  Result in s.wval / s.wid.
+// val(i) and id_of(i) may read LDS or global memory.  Returns min(k,n).
 template <class ValFn, class IdFn>
-__device__ __forceinline__ int block_topk(int n, int k, ValFn val, IdFn id_of, TopkShared& s) {
+__device__ __forceinline__ int block_topk(int n, int k, ValFn val, IdFn id_of, SeqShared& s) {
     const int tid = threadIdx.x, nt = blockDim.x;
     const int kk = min(k, n);
     if (kk <= 0) return 0;
+    if (n <= nt) {
+        // one element per thread: rank by counting
+        float v = 0.f;
+        int id = 0;
+        __syncthreads();
+        if (tid < n) {
+            v = val(tid);
+            id = id_of(tid);
+        }
+        int rank = 0;
+        for (int j = 0; j < n; ++j) {
+            const float vj = val(j);
+            if (vj > v || (vj == v && id_of(j) < id)) rank += 1;
+        }
+        __syncthreads();
+        if (tid < n && rank < kk) {
+            s.wval[rank] = v;
+            s.wid[rank] = id;
+        }
+        __syncthreads();
+        return kk;
+    }
     if (kk < n) {
         unsigned kth, need, neq;
         radix_select(n, (unsigned)kk, [&](int i, unsigned& kx) { kx = lkey(val(i)); return true; }, s, kth, need, neq);
@@ -534,64 +581,143 @@ __device__ __forceinline__ int block_topk(int n, int k, ValFn val, IdFn id_of, T
         }
         __syncthreads();
     }
-    for (int t = tid; t < kk; t += nt) {
-        const float v = s.wval[t];
-        const int id = s.wid[t];
-        int rank = 0;
-        for (int j = 0; j < kk; ++j) {
-            const float vj = s.wval[j];
-            rank += (vj > v) || (vj == v && s.wid[j] < id);
+    // order the winners in place: ranks first, then a permuted write (CSV_MAX_K <= 4 * 256 threads)
+    float mv[4];
+    int mi[4], mr[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const int t = tid + e * nt;
+        mr[e] = -1;
+        if (t < kk) {
+            const float v = s.wval[t];
+            const int id = s.wid[t];
+            int rank = 0;
+            for (int j = 0; j < kk; ++j) {
+                const float vj = s.wval[j];
+                rank += (vj > v) || (vj == v && s.wid[j] < id);
+            }
+            mv[e] = v; mi[e] = id; mr[e] = rank;
         }
-        s.oval[rank] = v;
-        s.oid[rank] = id;
     }
+    __syncthreads();
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+        if (mr[e] >= 0) {
+            s.wval[mr[e]] = mv[e];
+            s.wid[mr[e]] = mi[e];
+        }
     __syncthreads();
     return kk;
 }
 
 // max and sum exp(x - max) of n values, fixed reduction order
 template <class ValFn>
-__device__ __forceinline__ LseAcc block_lse(int n, ValFn val, TopkShared& s) {
+__device__ __forceinline__ LseAcc block_lse(int n, ValFn val, SeqShared& s) {
     float mx = -INFINITY;
     for (int i = threadIdx.x; i < n; i += blockDim.x) mx = fmaxf(mx, val(i));
-    mx = block_max(mx, s.red);
+    mx = block_max(mx, s.redf);
     float sm = 0.f;
     if (mx > -INFINITY)
         for (int i = threadIdx.x; i < n; i += blockDim.x) sm += expf(val(i) - mx);
-    sm = block_sum(sm, s.red);
+    sm = block_sum(sm, s.redf);
     LseAcc r;
     r.m = mx;
     r.s = sm;
     return r;
 }
 
-// ================================================================================================ certification
-// One block per sequence.  round 0: certify or plan round 1 (or fall back on budget); round 1: certify or fall back.
-__global__ __launch_bounds__(1024) void cert_kernel(StepArgs a, int round) {
-    __shared__ TopkShared s;
-    const int b = blockIdx.x, tid = threadIdx.x, nt = blockDim.x;
-    if (a.st[b].status != ST_ACTIVE) return;
-    const int C = a.C;
-    const int m = round == 0 ? a.st[b].m0 : a.st[b].m1;
-    const int32_t* Pb = a.P + (size_t)b * (C + 1);
-    const float* Tb = a.T + (size_t)b * (C + 1);
-    const float* sub = a.su + (size_t)b * C;
-    const int n = Pb[m];
-    const float* vals = a.slog + (size_t)b * a.K_cap;
-    const int32_t* rm = a.rowmap + (size_t)b * a.K_cap;
-    auto val = [&](int i) { return vals[i]; };
-    auto idf = [&](int i) { return a.perm[rm[i]]; };
-
-    const LseAcc l = block_lse(n, val, s);
-    const float Z = lse_value(l);
-    float theta = -INFINITY;
-    if (a.use_k) {
-        block_topk(n, a.k, val, idf, s);
-        theta = s.oval[a.k - 1];
+// ================================================================================================ sorted prefix search
+// s = min{m >= m0 : log tail mass with the first m clusters of the bound order open  -  Z0 <= lam}; returns the key
+// of the s-th cluster of the order (the threshold of that prefix).  Sorts the keys in LDS with a bitonic network;
+// only needed when the softmax test fails after round 0.  skeys: Npad entries; destroys their by-cluster order.
+__device__ __forceinline__ u64 softmax_prefix_key(const StepArgs& a, u64* skeys, int m0, float Z0, SeqShared& s) {
+    const int tid = threadIdx.x, nt = blockDim.x, N = a.Npad;
+    for (int i = a.C + tid; i < N; i += nt) skeys[i] = 0ull;
+    __syncthreads();
+    for (int k2 = 2; k2 <= N; k2 <<= 1) {
+        for (int j = k2 >> 1; j > 0; j >>= 1) {
+            for (int i = tid; i < N; i += nt) {
+                const int ixj = i ^ j;
+                if (ixj > i) {
+                    const u64 x = skeys[i], y = skeys[ixj];
+                    const bool first_larger = (i & k2) == 0;
+                    if (first_larger ? (x < y) : (x > y)) {
+                        skeys[i] = y;
+                        skeys[ixj] = x;
+                    }
+                }
+            }
+            __syncthreads();
+        }
     }
-    const float nxt = m < C ? sub[m] : -INFINITY;
-    const bool tk = (m == C) || (nxt == -INFINITY) || (nxt < theta);
-    const bool sm = (Tb[m] - Z <= a.lam) || (Tb[m] == -INFINITY);
+    // each thread owns E consecutive sorted positions
+    const int E = N >= nt ? N / nt : 1;
+    const int j0 = tid * E, j1 = min(N, j0 + E);
+    LseAcc run;
+    run.m = -INFINITY;
+    run.s = 0.f;
+    int nonempty = 0;
+    for (int j = j1 - 1; j >= j0 && j < N; --j) {
+        const u64 kx = skeys[j];
+        if (kx) {
+            run = lse_combine(lse_push(LseAcc{-INFINITY, 0.f}, a.lnn[(int)(0xFFFFFFFFu - (uint32_t)kx)] + ckey_bound(kx)), run);
+            nonempty += 1;
+        }
+    }
+    const LseAcc after = block_excl_suffix_lse(tid * E < N ? run : LseAcc{-INFINITY, 0.f}, s.redl);
+    const int ceff = block_sum_i(tid * E < N ? nonempty : 0, s.redi);
+    int best = ceff;
+    run = after;
+    for (int j = j1 - 1; j >= j0 && j < N; --j) {
+        const u64 kx = skeys[j];
+        if (kx) {
+            run = lse_combine(lse_push(LseAcc{-INFINITY, 0.f}, a.lnn[(int)(0xFFFFFFFFu - (uint32_t)kx)] + ckey_bound(kx)), run);
+            const float Tj = lse_value(run);     // tail with the first j clusters open
+            if (j >= m0 && (Tj - Z0 <= a.lam)) best = min(best, j);
+        }
+    }
+    best = block_min_i(best, s.redi);
+    return skeys[max(best, 1) - 1];
+}
+
+// ================================================================================================ certification
+// One block per sequence.  round 0: certify, or plan round 1 (or fall back on budget); round 1: certify or fall back.
+__global__ __launch_bounds__(SEQ_THREADS) void cert_kernel(StepArgs a, int round) {
+    extern __shared__ u64 arena[];
+    __shared__ SeqShared s;
+    const int b = blockIdx.x, tid = threadIdx.x, nt = blockDim.x, C = a.C;
+    const SeqState st = a.st[b];
+    if (st.status != ST_ACTIVE || st.rounds != round) return;
+    const int n = st.n_rows;
+    const float* gv = a.slog + (size_t)b * a.K_cap;
+    const int32_t* gi = a.sid + (size_t)b * a.K_cap;
+    float* sv = reinterpret_cast<float*>(arena);
+    int* si = reinterpret_cast<int*>(arena) + STAGE_CAP;
+    const bool staged = n <= STAGE_CAP;
+    if (staged) {
+        for (int i = tid; i < n; i += nt) {
+            sv[i] = gv[i];
+            si[i] = gi[i];
+        }
+        __syncthreads();
+    }
+    LseAcc l;
+    float theta = -INFINITY;
+    if (staged) {
+        auto val = [&](int i) { return sv[i]; };
+        auto idf = [&](int i) { return si[i]; };
+        l = block_lse(n, val, s);
+        if (a.use_k) block_topk(n, a.k, val, idf, s);
+    } else {
+        auto val = [&](int i) { return gv[i]; };
+        auto idf = [&](int i) { return gi[i]; };
+        l = block_lse(n, val, s);
+        if (a.use_k) block_topk(n, a.k, val, idf, s);
+    }
+    const float Z = lse_value(l);
+    if (a.use_k) theta = s.wval[a.k - 1];
+    const bool tk = (st.nxtU == -INFINITY) || (st.nxtU < theta);
+    const bool sm = (st.T - Z <= a.lam) || (st.T == -INFINITY);
     bool ok;
     if (a.combine == CSV_COMBINE_ALL)
         ok = (tk || !a.use_k) && (sm || !a.use_s);
@@ -600,19 +726,18 @@ __global__ __launch_bounds__(1024) void cert_kernel(StepArgs a, int round) {
 
     if (ok) {
         for (int t = tid; t < a.k; t += nt) {
-            a.out.d_ids[(size_t)b * a.k + t] = s.oid[t];
-            a.out.d_logits[(size_t)b * a.k + t] = s.oval[t];
+            a.out.d_ids[(size_t)b * a.k + t] = s.wid[t];
+            a.out.d_logits[(size_t)b * a.k + t] = s.wval[t];
         }
         if (a.out.d_sel_clusters)
-            for (int j = tid; j < m; j += nt) a.out.d_sel_clusters[(size_t)b * C + j] = a.order[(size_t)b * C + j];
+            for (int j = tid; j < st.n_open; j += nt) a.out.d_sel_clusters[(size_t)b * C + j] = a.sel[(size_t)b * C + j];
         if (tid == 0) {
             a.out.d_lse[b] = Z;
             a.out.d_flags[b] = ((tk && a.use_k) ? CSV_FLAG_TOPK_CERT : 0u) | ((sm && a.use_s) ? CSV_FLAG_SOFTMAX_CERT : 0u);
             a.out.d_n_rows[b] = n;
-            a.out.d_n_clusters[b] = m;
+            a.out.d_n_clusters[b] = st.n_open;
             if (a.out.d_rounds) a.out.d_rounds[b] = round + 1;
             a.st[b].status = ST_DONE;
-            a.rcount[b] = 0;
         }
         return;
     }
@@ -620,39 +745,50 @@ __global__ __launch_bounds__(1024) void cert_kernel(StepArgs a, int round) {
         if (tid == 0) push_fallback(a, b, 2);
         return;
     }
-    // plan round 1
-    int av = m, sv = m;
-    if (a.use_k && !tk) {
-        int cnt = 0;
-        for (int j = tid; j < C; j += nt) cnt += (sub[j] >= theta) ? 1 : 0;
-        av = block_sum_i(cnt, s.redi);
-    }
+    // ---- plan round 1: the open set grows from {key >= kappa0} to {key >= kappa1}
+    __syncthreads();                                   // the staged logits are dead; the arena is reused
+    u64* keys = arena;
+    int* nl = reinterpret_cast<int*>(keys + a.Npad);
+    const u64 kappa0 = st.kappa;
+    u64 kappa_a = kappa0, kappa_s = kappa0;
+    if (a.use_k && !tk) kappa_a = (u64)lkey(theta) << 32;                 // every cluster with U_c >= theta0
     if (a.use_s && !sm) {
-        int best = C;
-        for (int j = m + tid; j <= C; j += nt)
-            if (Tb[j] - Z <= a.lam || Tb[j] == -INFINITY) best = min(best, j);
-        sv = block_min_i(best, s.redi);
+        load_keys(a, b, keys, nl);
+        __syncthreads();
+        kappa_s = softmax_prefix_key(a, keys, st.n_open, Z, s);
+        __syncthreads();
     }
-    int m1;
+    u64 kappa1;
     if (a.use_k && a.use_s)
-        m1 = a.combine == CSV_COMBINE_ALL ? max(av, sv) : min(av, sv);
+        kappa1 = a.combine == CSV_COMBINE_ALL ? (kappa_a < kappa_s ? kappa_a : kappa_s) : (kappa_a > kappa_s ? kappa_a : kappa_s);
     else
-        m1 = a.use_k ? av : sv;
-    const int rows1 = Pb[m1];
-    if (rows1 > a.K_max) {
+        kappa1 = a.use_k ? kappa_a : kappa_s;
+    load_keys(a, b, keys, nl);
+    __syncthreads();
+    auto isnew = [&](int c) { const u64 kx = keys[c]; return kx >= kappa1 && kx < kappa0 && kx != 0; };
+    int cnt = 0, rows = 0;
+    for (int c = tid; c < C; c += nt)
+        if (isnew(c)) {
+            cnt += 1;
+            rows += nl[c];
+        }
+    cnt = block_sum_i(cnt, s.redi);
+    rows = block_sum_i(rows, s.redi);
+    if (n + rows > a.K_max) {
         if (tid == 0) {
-            a.st[b].m1 = m1;
+            a.st[b].n_open = st.n_open + cnt;
+            a.st[b].n_rows = n + rows;
             push_fallback(a, b, 1);
         }
         return;
     }
-    write_rowmap(a, b, m, m1);
+    float nxtU, T1;
+    tail_stats(a, keys, kappa1, s, nxtU, T1);
+    emit_clusters(a, b, 1, n, st.n_open, isnew, nl, s);
     if (tid == 0) {
-        a.st[b].m1 = m1;
-        a.st[b].theta0 = theta;
-        a.st[b].Z0 = Z;
-        a.rstart[b] = n;
-        a.rcount[b] = rows1 - n;
+        SeqState o = st;
+        o.n_open = st.n_open + cnt; o.n_rows = n + rows; o.rounds = 1; o.kappa = kappa1; o.nxtU = nxtU; o.T = T1;
+        a.st[b] = o;
     }
 }
 
@@ -739,10 +875,10 @@ __global__ __launch_bounds__(256) void full_gemv_kernel(FullArgs f) {
 }
 
 // First stage of top-k / log-sum-exp over V: one block per (chunk of rows, fallback slot).
-__global__ __launch_bounds__(1024) void fb_topk_kernel(StepArgs a) {
-    __shared__ TopkShared s;
+__global__ __launch_bounds__(SEQ_THREADS) void fb_topk_kernel(StepArgs a) {
+    __shared__ SeqShared s;
     const int slot = blockIdx.y, chunk = blockIdx.x, tid = threadIdx.x, nt = blockDim.x;
-    if (slot >= a.counters[0]) return;
+    if (slot >= a.counters[CNT_FALLBACK]) return;
     const int c0 = chunk * FB_CHUNK;
     const int n = min(FB_CHUNK, a.V - c0);
     const float* vals = a.fb_logits + (size_t)slot * a.V + c0;
@@ -757,33 +893,33 @@ __global__ __launch_bounds__(1024) void fb_topk_kernel(StepArgs a) {
     if (a.k > 0) {
         const int kk = block_topk(n, a.k, val, idf, s);
         for (int t = tid; t < a.k; t += nt) {
-            a.cand_val[pc * a.k + t] = t < kk ? s.oval[t] : -INFINITY;
-            a.cand_id[pc * a.k + t] = t < kk ? s.oid[t] : 0x7fffffff;
+            a.cand_val[pc * a.k + t] = t < kk ? s.wval[t] : -INFINITY;
+            a.cand_id[pc * a.k + t] = t < kk ? s.wid[t] : 0x7fffffff;
         }
     }
 }
 
 // Second stage: merge the chunk candidates of one fallback sequence and write its outputs.
-__global__ __launch_bounds__(1024) void fb_final_kernel(StepArgs a) {
-    __shared__ TopkShared s;
+__global__ __launch_bounds__(SEQ_THREADS) void fb_final_kernel(StepArgs a) {
+    __shared__ SeqShared s;
     const int slot = blockIdx.x, tid = threadIdx.x, nt = blockDim.x;
-    if (slot >= a.counters[0]) return;
+    if (slot >= a.counters[CNT_FALLBACK]) return;
     const int b = a.fb_list[slot];
     const float* cm = a.cand_max + (size_t)slot * a.n_chunks;
     const float* cs = a.cand_sum + (size_t)slot * a.n_chunks;
     float mx = -INFINITY;
     for (int i = tid; i < a.n_chunks; i += nt) mx = fmaxf(mx, cm[i]);
-    mx = block_max(mx, s.red);
+    mx = block_max(mx, s.redf);
     float sm = 0.f;
     for (int i = tid; i < a.n_chunks; i += nt) sm += cs[i] * expf(cm[i] - mx);
-    sm = block_sum(sm, s.red);
+    sm = block_sum(sm, s.redf);
     if (a.k > 0) {
         const float* cv = a.cand_val + (size_t)slot * a.n_chunks * a.k;
         const int32_t* ci = a.cand_id + (size_t)slot * a.n_chunks * a.k;
         block_topk(a.n_chunks * a.k, a.k, [&](int i) { return cv[i]; }, [&](int i) { return ci[i]; }, s);
         for (int t = tid; t < a.k; t += nt) {
-            a.out.d_ids[(size_t)b * a.k + t] = s.oid[t];
-            a.out.d_logits[(size_t)b * a.k + t] = s.oval[t];
+            a.out.d_ids[(size_t)b * a.k + t] = s.wid[t];
+            a.out.d_logits[(size_t)b * a.k + t] = s.wval[t];
         }
     }
     if (tid == 0) {
@@ -810,8 +946,8 @@ static void fill_args(StepArgs& a, const csv_workspace* ws, const csv_index* idx
     a.Wp = idx->Wp; a.bp = idx->bp; a.perm = idx->perm; a.mu = idx->mu; a.R = idx->R; a.bmax = idx->bmax;
     a.n = idx->n; a.off = idx->off; a.lnn = idx->lnn;
     a.K_cap = ws->K_cap; a.Npad = ws->Npad; a.n_chunks = ws->n_chunks;
-    a.U = ws->U; a.hnorm = ws->hnorm; a.order = ws->order; a.su = ws->su; a.T = ws->T; a.P = ws->P; a.st = ws->st;
-    a.rstart = ws->rstart; a.rcount = ws->rcount; a.slog = ws->slog; a.rowmap = ws->rowmap; a.counters = ws->counters;
+    a.U = ws->U; a.hnorm = ws->hnorm; a.st = ws->st; a.sel = ws->sel; a.slog = ws->slog; a.sid = ws->sid;
+    a.tiles[0] = ws->tiles[0]; a.tiles[1] = ws->tiles[1]; a.counters = ws->counters;
     a.fb_list = ws->fb_list; a.fb_logits = ws->fb_logits; a.cand_val = ws->cand_val; a.cand_id = ws->cand_id;
     a.cand_max = ws->cand_max; a.cand_sum = ws->cand_sum;
 }
@@ -841,9 +977,11 @@ static int launch_bounds_kernel(const StepArgs& a, float* U, float* hn, int rese
     return CSV_OK;
 }
 
-static int gemv_grid(const csv_workspace* ws, int B) {
-    long long tiles = ((long long)ws->K_cap + GEMV_TILE - 1) / GEMV_TILE * B;
-    return (int)(tiles < 2048 ? (tiles < 1 ? 1 : tiles) : 2048);
+// dynamic LDS of the per-sequence kernels
+static size_t seed_lds(const csv_workspace* ws) { return (size_t)ws->C * 12; }
+static size_t cert_lds(const csv_workspace* ws) {
+    const size_t plan = (size_t)ws->Npad * 8 + (size_t)ws->C * 4, stage = (size_t)STAGE_CAP * 8;
+    return plan > stage ? plan : stage;
 }
 
 static int launch_full(const csv_index* idx, const uint16_t* d_h, const int32_t* list, const int32_t* n_ptr, int n_fixed,
@@ -871,23 +1009,32 @@ extern "C" int csv_workspace_create(const csv_index* idx, int B_max, int K_cap_r
     ws->n_chunks = (idx->V + FB_CHUNK - 1) / FB_CHUNK;
     ws->device = idx->device;
     const size_t B = B_max, C = idx->C, V = idx->V, K = ws->K_cap, NC = ws->n_chunks;
+    size_t tcap = B * (K / TILE_ROWS + C + 1);
+    if (tcap < 4096) tcap = 4096;
+    ws->tile_cap = (int)tcap;
     hipError_t e = hipSuccess;
     auto A = [&](void** p, size_t bytes) { if (e == hipSuccess) e = hipMalloc(p, bytes ? bytes : 16); };
-    A((void**)&ws->U, B * C * 4); A((void**)&ws->hnorm, B * 4); A((void**)&ws->order, B * C * 4); A((void**)&ws->su, B * C * 4);
-    A((void**)&ws->T, B * (C + 1) * 4); A((void**)&ws->P, B * (C + 1) * 4); A((void**)&ws->st, B * sizeof(SeqState));
-    A((void**)&ws->rstart, B * 4); A((void**)&ws->rcount, B * 4); A((void**)&ws->slog, B * K * 4); A((void**)&ws->rowmap, B * K * 4);
+    A((void**)&ws->U, B * C * 4); A((void**)&ws->hnorm, B * 4); A((void**)&ws->st, B * sizeof(SeqState));
+    A((void**)&ws->sel, B * C * 4); A((void**)&ws->slog, B * K * 4); A((void**)&ws->sid, B * K * 4);
+    A((void**)&ws->tiles[0], tcap * sizeof(Tile)); A((void**)&ws->tiles[1], tcap * sizeof(Tile));
     A((void**)&ws->counters, 16 * 4); A((void**)&ws->fb_list, B * 4); A((void**)&ws->all_list, B * 4);
     A((void**)&ws->fb_logits, B * V * 4); A((void**)&ws->cand_val, B * NC * CSV_MAX_K * 4); A((void**)&ws->cand_id, B * NC * CSV_MAX_K * 4);
     A((void**)&ws->cand_max, B * NC * 4); A((void**)&ws->cand_sum, B * NC * 4);
     if (e == hipSuccess) e = hipMemset(ws->counters, 0, 16 * 4);
-    if (e == hipSuccess) e = hipMemset(ws->rcount, 0, B * 4);
     if (e == hipSuccess) e = hipMemset(ws->st, 0, B * sizeof(SeqState));
+    if (e == hipSuccess) e = hipMemset(ws->tiles[0], 0, tcap * sizeof(Tile));
+    if (e == hipSuccess) e = hipMemset(ws->tiles[1], 0, tcap * sizeof(Tile));
     if (e == hipSuccess) {
         int32_t* tmp = (int32_t*)malloc(B * 4);
         for (size_t i = 0; i < B; ++i) tmp[i] = (int32_t)i;
         e = hipMemcpy(ws->all_list, tmp, B * 4, hipMemcpyHostToDevice);
         free(tmp);
     }
+    // the per-sequence kernels may need more dynamic LDS than the default limit when C is large
+    if (e == hipSuccess && seed_lds(ws) + sizeof(SeqShared) > 65536)
+        e = hipFuncSetAttribute((const void*)seed_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)seed_lds(ws));
+    if (e == hipSuccess && cert_lds(ws) + sizeof(SeqShared) > 65536)
+        e = hipFuncSetAttribute((const void*)cert_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)cert_lds(ws));
     if (e != hipSuccess) {
         csv_set_error("workspace allocation failed: %s", hipGetErrorString(e));
         csv_workspace_free(ws);
@@ -899,7 +1046,7 @@ extern "C" int csv_workspace_create(const csv_index* idx, int B_max, int K_cap_r
 
 extern "C" void csv_workspace_free(csv_workspace* ws) {
     if (!ws) return;
-    void* ptrs[] = {ws->U, ws->hnorm, ws->order, ws->su, ws->T, ws->P, ws->st, ws->rstart, ws->rcount, ws->slog, ws->rowmap,
+    void* ptrs[] = {ws->U, ws->hnorm, ws->st, ws->sel, ws->slog, ws->sid, ws->tiles[0], ws->tiles[1],
                     ws->counters, ws->fb_list, ws->all_list, ws->fb_logits, ws->cand_val, ws->cand_id, ws->cand_max, ws->cand_sum};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
@@ -956,30 +1103,31 @@ extern "C" int csv_decode_step(csv_workspace* ws, const csv_index* idx, const ui
     rc = launch_bounds_kernel(a, ws->U, ws->hnorm, 1, st);
     if (rc) return rc;
     CSV_MARK(1);
-    select0_kernel<<<B, 1024, (size_t)ws->Npad * 8, st>>>(a);
-    CSV_LAUNCH_CHECK("select0_kernel");
+    seed_kernel<<<B, SEQ_THREADS, seed_lds(ws), st>>>(a);
+    CSV_LAUNCH_CHECK("seed_kernel");
     CSV_MARK(2);
-    const int gg = gemv_grid(ws, B);
+    long long want = ((long long)ws->K_cap / TILE_ROWS + 1) * B;
+    const int gg = (int)(want < 2048 ? want : 2048);
     const size_t hl = (size_t)idx->d * 2;
-    gemv_gather_kernel<<<gg, 256, hl, st>>>(a);
-    CSV_LAUNCH_CHECK("gemv_gather_kernel");
+    gemv_tiles_kernel<<<gg, 256, hl, st>>>(a, 0);
+    CSV_LAUNCH_CHECK("gemv_tiles_kernel");
     CSV_MARK(3);
-    cert_kernel<<<B, 1024, 0, st>>>(a, 0);
+    cert_kernel<<<B, SEQ_THREADS, cert_lds(ws), st>>>(a, 0);
     CSV_LAUNCH_CHECK("cert_kernel");
     CSV_MARK(4);
-    gemv_gather_kernel<<<gg, 256, hl, st>>>(a);
-    CSV_LAUNCH_CHECK("gemv_gather_kernel");
+    gemv_tiles_kernel<<<gg, 256, hl, st>>>(a, 1);
+    CSV_LAUNCH_CHECK("gemv_tiles_kernel");
     CSV_MARK(5);
-    cert_kernel<<<B, 1024, 0, st>>>(a, 1);
+    cert_kernel<<<B, SEQ_THREADS, cert_lds(ws), st>>>(a, 1);
     CSV_LAUNCH_CHECK("cert_kernel");
     CSV_MARK(6);
-    rc = launch_full(idx, d_h, ws->fb_list, ws->counters, 0, ws->fb_logits, idx->V, 0, st);
+    rc = launch_full(idx, d_h, ws->fb_list, ws->counters + CNT_FALLBACK, 0, ws->fb_logits, idx->V, 0, st);
     if (rc) return rc;
     CSV_MARK(7);
-    fb_topk_kernel<<<dim3(ws->n_chunks, B), 1024, 0, st>>>(a);
+    fb_topk_kernel<<<dim3(ws->n_chunks, B), SEQ_THREADS, 0, st>>>(a);
     CSV_LAUNCH_CHECK("fb_topk_kernel");
     CSV_MARK(8);
-    fb_final_kernel<<<B, 1024, 0, st>>>(a);
+    fb_final_kernel<<<B, SEQ_THREADS, 0, st>>>(a);
     CSV_LAUNCH_CHECK("fb_final_kernel");
     CSV_MARK(9);
 #undef CSV_MARK
