@@ -136,23 +136,19 @@ def main() -> int:
     full_ms = (time.perf_counter() - t1) * 1e3 / nfull
     full_bytes = r.V * (2 * r.d + 8) + r.B * r.d * 2
 
-    # ---------------- roofline of the stage that takes the most time
-    bytes_by_stage = {
-        "bounds": r.C * r.d * 4 + 12 * r.C + r.B * r.d * 2 + 4 * r.B * r.C,
-        "gemv_round0": None, "gemv_round1": None,
-        "full_product": r.V * (2 * r.d + 4) + r.B * r.d * 2,
-    }
+    # ---------------- roofline of the dominant kernel
+    # Algorithmic bytes per launch: bound_kernel reads the centroids and cluster metadata once and h, writes U;
+    # the gathered GEMV reads each opened row with its bias and id and h per tile; the tail's full product reads W' once.
     mean_rows_seq = rows_sum / max(1, n_seq - int(round(fb_rate * n_seq)))
-    gemv_bytes = (rows_sum / nstat) * (2 * r.d + 12) + r.B * r.d * 2
-    dom = max(("bounds", "gemv_round0", "gemv_round1", "full_product"), key=lambda n: stage_us[n])
-    if dom.startswith("gemv"):
-        dom_bytes = gemv_bytes    # both rounds together
-        dom_us = stage_us["gemv_round0"] + stage_us["gemv_round1"]
-        dom_name = "gemv_gather_kernel (both rounds)"
+    bound_bytes = r.C * r.d * 4 + 12 * r.C + r.B * r.d * 2 + 4 * r.B * r.C
+    gemv_bytes = (rows_sum / nstat) * (2 * r.d + 16) + r.B * r.d * 2
+    full_bytes_launch = r.V * (2 * r.d + 8) + r.B * r.d * 2
+    if anyfb / nstat > 0.5:
+        dom_name, dom_bytes, dom_us = "tail_kernel (full-vocabulary product for fallback sequences)", full_bytes_launch, stage_us["tail"]
+    elif rounds_hist[2] == 0 and stage_us["gemv_round0"] > stage_us["bounds"]:
+        dom_name, dom_bytes, dom_us = "gemv_tiles_kernel", gemv_bytes, stage_us["gemv_round0"]
     else:
-        dom_bytes = bytes_by_stage[dom]
-        dom_us = stage_us[dom]
-        dom_name = {"bounds": "bound_kernel", "full_product": "full_gemv_kernel"}[dom]
+        dom_name, dom_bytes, dom_us = "bound_kernel", bound_bytes, stage_us["bounds"]
     achieved = dom_bytes / (dom_us * 1e-6) / 1e9
     bstep = step_bytes(r, r.C, rows_union_sum / nstat, anyfb / nstat, r.k)
     eff_gbs = bstep / (ms_per_step * 1e-3) / 1e9

@@ -36,7 +36,8 @@ extern "C" {
 #define CSV_FLAG_TOPK_CERT     1u   /* Definition 1 holds: returned top-k equals the full-vocabulary top-k */
 #define CSV_FLAG_SOFTMAX_CERT  2u   /* Theorem 2 holds: total variation of the sub-vocabulary softmax <= eps */
 #define CSV_FLAG_FALLBACK      4u   /* all V rows were scored for this sequence */
-#define CSV_FLAG_INVALID_INPUT 8u   /* ||h||^2 is not finite; other outputs of the sequence are cleared */
+#define CSV_FLAG_INVALID_INPUT 8u   /* ||h||^2 is not finite (other outputs of the sequence are cleared), or the
+                                       step could not finish the sequence (a bounded device-side wait ran out) */
 
 #define CSV_COMBINE_ALL 0   /* certified when every enabled certificate holds */
 #define CSV_COMBINE_ANY 1   /* certified when any enabled certificate holds (Algorithm 1 stops on either) */
@@ -109,7 +110,8 @@ typedef struct {
     int32_t*  d_n_rows;       /* [B]    rows scored, |S| (V after fallback) */
     int32_t*  d_n_clusters;   /* [B]    clusters opened (C after fallback) */
     int32_t*  d_rounds;       /* [B] or NULL: scoring rounds used on the sub-vocabulary path (0, 1 or 2) */
-    int32_t*  d_sel_clusters; /* [B*C] or NULL: opened cluster ids in bound order (first n_clusters entries) */
+    int32_t*  d_sel_clusters; /* [B*C] or NULL: opened cluster ids (first n_clusters entries): round-0 clusters,
+                                 then round-1 clusters, each group by ascending id; untouched on fallback */
     unsigned long long* d_fallback_count; /* or NULL: incremented once per sequence that falls back */
 } csv_step_out;
 
@@ -151,11 +153,11 @@ int csv_full_logits(csv_workspace* ws, const csv_index* idx, const uint16_t* d_h
  * each following csv_decode_step on this workspace records CSV_PROFILE_STAGES+1 events (steps beyond max_steps
  * are not recorded).  csv_profile_end synchronises, writes the summed milliseconds of every stage to
  * h_stage_ms[CSV_PROFILE_STAGES] and the number of recorded steps to *h_steps, frees the events and switches
- * recording off.  Stage order: bounds, select, gathered GEMV (round 0), certification (round 0), gathered GEMV
- * (round 1), certification (round 1), full-vocabulary product, fallback top-k stage 1, fallback top-k stage 2.
+ * recording off.  Stage order: bounds, seed selection, gathered GEMV (round 0), certification (round 0), and the
+ * tail (round-1 GEMV and certification, full-vocabulary product and top-k for fallback sequences; one kernel).
  * A stage's time runs from the end of the previous stage to its own end, so it includes its launch gap.
  */
-#define CSV_PROFILE_STAGES 9
+#define CSV_PROFILE_STAGES 5
 int csv_profile_begin(csv_workspace* ws, int max_steps);
 int csv_profile_end(csv_workspace* ws, float* h_stage_ms, int* h_steps);
 

@@ -24,7 +24,10 @@ struct csv_index {
 };
 
 enum { ST_ACTIVE = 0, ST_DONE = 1, ST_FALLBACK = 2, ST_INVALID = 3 };
-enum { CNT_FALLBACK = 0, CNT_TILES0 = 1, CNT_TILES1 = 2 };
+// counters[]: [CNT_FALLBACK] sequences that fall back this step; [CNT_TILES + round*CSV_MAX_BATCH + b] row tiles
+// of sequence b in the round's work list.  All are zeroed by the bound kernel at the start of a step.
+// [CNT_BARRIER + i] arrivals at the i-th grid barrier of the tail kernel; [CNT_ABORT] set when a bounded wait ran out.
+enum { CNT_FALLBACK = 0, CNT_BARRIER = 1, CNT_ABORT = 5, CNT_TILES = 16, CNT_TOTAL = 16 + 2 * CSV_MAX_BATCH };
 
 // A cluster's position in the bound order is carried by one 64-bit key: monotone image of U_c in the high word,
 // ~c in the low word.  Larger key = larger bound, equal bounds = smaller cluster id first.  Empty clusters have key 0.
@@ -49,7 +52,9 @@ struct Tile {
 struct csv_workspace {
     int B_max, K_cap, V, d, C, Npad;   // Npad: C rounded up to a power of two (sort width)
     int n_chunks;                      // fallback top-k chunks per sequence
-    int tile_cap;                      // entries of each tile list
+    int tile_stride;                   // entries of each sequence's region of a tile list
+    int tail_grid;                     // blocks of the tail kernel (all resident together)
+    size_t tail_lds;                   // its dynamic LDS
     int device;
     float* U;          // [B*C]      cluster bounds
     float* hnorm;      // [B]
@@ -58,7 +63,7 @@ struct csv_workspace {
     float* slog;       // [B*K_cap]  logits of opened rows
     int32_t* sid;      // [B*K_cap]  their original token ids
     Tile* tiles[2];    // work lists of round 0 / round 1
-    int32_t* counters; // [16]       CNT_*
+    int32_t* counters; // [CNT_TOTAL]
     int32_t* fb_list;  // [B]        sequences that fall back this step
     int32_t* all_list; // [B]        0..B-1 (csv_full_logits runs the fallback product over everyone)
     float* fb_logits;  // [B*V]      full logits of fallback sequences (permuted row order)
@@ -113,26 +118,37 @@ __device__ __forceinline__ float dot8_bf16(const uint4& w, const uint4& h, float
     return acc;
 }
 
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, CSV_WAVE);
-    return v;
+// Wave-wide reductions with DPP lane exchanges (no LDS traffic): pairs, quads, half rows and rows of 16 lanes by
+// quad_perm / row_half_mirror / row_mirror, then row_bcast15 and row_bcast31 carry the row totals to lane 63, whose
+// value is broadcast.  Must be called with all 64 lanes active.  The combination order is fixed, so results are
+// reproducible run to run.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ int dpp_move(int old, int src) {
+    return __builtin_amdgcn_update_dpp(old, src, CTRL, ROW_MASK, 0xf, false);
 }
-__device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, CSV_WAVE));
-    return v;
-}
-__device__ __forceinline__ int wave_sum_i(int v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, CSV_WAVE);
-    return v;
-}
-__device__ __forceinline__ int wave_min_i(int v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = min(v, __shfl_xor(v, o, CSV_WAVE));
-    return v;
-}
+#define CSV_DPP_REDUCE(T, TOI, FROMI, OP, IDENT)                                              \
+    {                                                                                         \
+        v = OP(v, FROMI(dpp_move<0xB1, 0xf>(TOI(v), TOI(v))));  /* quad_perm [1,0,3,2] */     \
+        v = OP(v, FROMI(dpp_move<0x4E, 0xf>(TOI(v), TOI(v))));  /* quad_perm [2,3,0,1] */     \
+        v = OP(v, FROMI(dpp_move<0x141, 0xf>(TOI(v), TOI(v)))); /* row_half_mirror */         \
+        v = OP(v, FROMI(dpp_move<0x140, 0xf>(TOI(v), TOI(v)))); /* row_mirror */              \
+        v = OP(v, FROMI(dpp_move<0x142, 0xa>(TOI((T)(IDENT)), TOI(v)))); /* row_bcast15 */    \
+        v = OP(v, FROMI(dpp_move<0x143, 0xc>(TOI((T)(IDENT)), TOI(v)))); /* row_bcast31 */    \
+        return FROMI(__builtin_amdgcn_readlane(TOI(v), 63));                                  \
+    }
+__device__ __forceinline__ float csv_addf(float a, float b) { return a + b; }
+__device__ __forceinline__ int csv_addi(int a, int b) { return a + b; }
+__device__ __forceinline__ int csv_mini(int a, int b) { return a < b ? a : b; }
+__device__ __forceinline__ unsigned csv_maxu(unsigned a, unsigned b) { return a > b ? a : b; }
+__device__ __forceinline__ int csv_id_i(int x) { return x; }
+__device__ __forceinline__ int csv_u2i(unsigned x) { return (int)x; }
+__device__ __forceinline__ unsigned csv_i2u(int x) { return (unsigned)x; }
+
+__device__ __forceinline__ float wave_sum(float v) CSV_DPP_REDUCE(float, __float_as_int, __int_as_float, csv_addf, 0.f)
+__device__ __forceinline__ float wave_max(float v) CSV_DPP_REDUCE(float, __float_as_int, __int_as_float, fmaxf, -INFINITY)
+__device__ __forceinline__ int wave_sum_i(int v) CSV_DPP_REDUCE(int, csv_id_i, csv_id_i, csv_addi, 0)
+__device__ __forceinline__ int wave_min_i(int v) CSV_DPP_REDUCE(int, csv_id_i, csv_id_i, csv_mini, 0x7fffffff)
+__device__ __forceinline__ unsigned wave_max_u(unsigned v) CSV_DPP_REDUCE(unsigned, csv_u2i, csv_i2u, csv_maxu, 0u)
 
 // Block-wide reductions in a fixed order (deterministic).  red: >= 16 words of LDS.  All threads get the result.
 __device__ __forceinline__ float block_sum(float v, float* red) {
@@ -177,12 +193,10 @@ __device__ __forceinline__ int block_min_i(int v, int* red) {
 }
 
 __device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-        const unsigned long long y = __shfl_xor(v, o, CSV_WAVE);
-        v = y > v ? y : v;
-    }
-    return v;
+    const unsigned hi = (unsigned)(v >> 32), lo = (unsigned)v;
+    const unsigned mhi = wave_max_u(hi);
+    const unsigned mlo = wave_max_u(hi == mhi ? lo : 0u);
+    return ((unsigned long long)mhi << 32) | mlo;
 }
 // red: >= 16 64-bit words of LDS
 __device__ __forceinline__ unsigned long long block_max_u64(unsigned long long v, unsigned long long* red) {

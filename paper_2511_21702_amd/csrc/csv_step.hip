@@ -39,7 +39,7 @@ struct StepArgs {
     const int32_t* n;
     const int32_t* off;
     const float* lnn;
-    int B, K_cap, Npad, n_chunks;
+    int B, K_cap, Npad, n_chunks, tile_stride;
     float* U;
     float* hnorm;
     SeqState* st;
@@ -58,7 +58,16 @@ struct StepArgs {
     int k, K_max, combine, use_k, use_s;
     float lam;   // ln(eps/(1-eps)); +inf when eps >= 1
     csv_step_out out;
+#ifdef CSV_DEBUG_TIMING
+    unsigned long long* dbg;   // [B*64] wall-clock marks of the per-sequence kernels (debug builds only)
+#endif
 };
+
+#ifdef CSV_DEBUG_TIMING
+#define DBG_T(slot) do { if (threadIdx.x == 0 && a.dbg) { a.dbg[blockIdx.x * 64 + (slot)] = wall_clock64(); a.dbg[blockIdx.x * 64 + 32 + (slot)] = clock64(); } } while (0)
+#else
+#define DBG_T(slot) do { } while (0)
+#endif
 
 #define TILE_ROWS 8        // rows per work item of the gathered GEMV (4 waves x 2 rows)
 #define SEQ_THREADS 512    // block size of the per-sequence kernels (seed, cert, fallback top-k)
@@ -108,7 +117,8 @@ __global__ __launch_bounds__(256) void bound_kernel(StepArgs a, float* __restric
     }
     const uint4* hsrc = reinterpret_cast<const uint4*>(a.h) + (size_t)b0 * nch;
     for (int i = tid; i < BT * nch; i += 256) hs4[i] = (i < nb * nch) ? hsrc[i] : make_uint4(0, 0, 0, 0);
-    if (reset_counters && blockIdx.x == 0 && blockIdx.y == 0 && tid < 16) a.counters[tid] = 0;
+    if (reset_counters && blockIdx.x == 0 && blockIdx.y == 0)
+        for (int i = tid; i < CNT_TOTAL; i += 256) a.counters[i] = 0;
     __syncthreads();
     for (int s = wave; s < BT; s += 4) {
         float acc = 0.f;
@@ -222,6 +232,8 @@ struct SeqShared {
     unsigned hist[256];
     float redf[16];
     int redi[16];
+    int scan3[48];
+    int rank[SEQ_THREADS];
     u64 redu[16];
     LseAcc redl[16];
     unsigned sel, rem, eq, cnt;
@@ -256,37 +268,98 @@ __device__ __forceinline__ void push_fallback(const StepArgs& a, int b, int roun
     if (a.out.d_rounds) a.out.d_rounds[b] = rounds;
 }
 
+// Per-sequence cluster data in LDS: keys[Npad], first permuted row of each cluster offl[C+1], and
+// vl[c] = ln n_c + U_c (the cluster's term of the log tail mass; -inf for an empty cluster).
+struct ClusterLds {
+    u64* keys;
+    int* offl;
+    float* vl;
+};
+__device__ __forceinline__ ClusterLds carve_clusters(u64* arena, int Npad, int C) {
+    ClusterLds L;
+    L.keys = arena;
+    L.offl = reinterpret_cast<int*>(arena + Npad);
+    L.vl = reinterpret_cast<float*>(L.offl + C + 1);
+    return L;
+}
+__device__ __forceinline__ void load_clusters(const StepArgs& a, int b, const ClusterLds& L) {
+    for (int c = threadIdx.x; c <= a.C; c += blockDim.x) L.offl[c] = a.off[c];
+    for (int c = threadIdx.x; c < a.C; c += blockDim.x) {
+        const float u = a.U[(size_t)b * a.C + c];
+        const int n = a.n[c];
+        const float ln = a.lnn[c];
+        L.keys[c] = n > 0 ? ckey(u, c) : 0ull;
+        L.vl[c] = n > 0 ? ln + u : -INFINITY;
+    }
+}
+
+// Exclusive prefix sums of three ints per thread in one pass.  wtot: 48 ints of LDS.
+__device__ __forceinline__ void block_excl_scan3(int& v0, int& v1, int& v2, int* wtot, int& t0, int& t1, int& t2) {
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+    int x0 = v0, x1 = v1, x2 = v2;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int y0 = __shfl_up(x0, o, CSV_WAVE), y1 = __shfl_up(x1, o, CSV_WAVE), y2 = __shfl_up(x2, o, CSV_WAVE);
+        if (lane >= o) {
+            x0 += y0;
+            x1 += y1;
+            x2 += y2;
+        }
+    }
+    __syncthreads();
+    if (lane == 63) {
+        wtot[w] = x0;
+        wtot[16 + w] = x1;
+        wtot[32 + w] = x2;
+    }
+    __syncthreads();
+    int b0 = 0, b1 = 0, b2 = 0;
+    t0 = t1 = t2 = 0;
+    for (int i = 0; i < nw; ++i) {
+        const int a0 = wtot[i], a1 = wtot[16 + i], a2 = wtot[32 + i];
+        if (i < w) {
+            b0 += a0;
+            b1 += a1;
+            b2 += a2;
+        }
+        t0 += a0;
+        t1 += a1;
+        t2 += a2;
+    }
+    v0 = b0 + x0 - v0;
+    v1 = b1 + x1 - v1;
+    v2 = b2 + x2 - v2;
+}
+
 // Opens every cluster c with flag(c): its rows get consecutive positions from pos_base on (cluster id order), its
-// row tiles are appended to the round's work list, its id is appended to the sequence's list of opened clusters.
-// nl: rows per cluster (LDS).  All threads of the block call; flag must be the same function of c in both passes.
+// row tiles go to the sequence's region of the round's work list, its id is appended to the sequence's list of
+// opened clusters.  All threads of the block call; flag must be the same function of c in both passes.
 template <class FlagFn>
 __device__ __forceinline__ void emit_clusters(const StepArgs& a, int b, int round, int pos_base, int sel_base, FlagFn flag,
-                                              const int* nl, SeqShared& s) {
+                                              const ClusterLds& L, SeqShared& s) {
     const int tid = threadIdx.x, nt = blockDim.x, C = a.C;
     const int E = (C + nt - 1) / nt;
     const int c0 = min(C, tid * E), c1 = min(C, c0 + E);
     int cnt = 0, rows = 0, tiles = 0;
     for (int c = c0; c < c1; ++c)
         if (flag(c)) {
-            const int n = nl[c];
+            const int n = L.offl[c + 1] - L.offl[c];
             cnt += 1;
             rows += n;
             tiles += (n + TILE_ROWS - 1) / TILE_ROWS;
         }
-    int tot_tiles;
-    const int bc = block_excl_scan_i(cnt, s.redi, nullptr);
-    const int br = block_excl_scan_i(rows, s.redi, nullptr);
-    const int bt = block_excl_scan_i(tiles, s.redi, &tot_tiles);
+    int tot_cnt, tot_rows, tot_tiles;
+    block_excl_scan3(cnt, rows, tiles, s.scan3, tot_cnt, tot_rows, tot_tiles);
     if (tid == 0) {
-        s.tbase = tot_tiles > 0 ? atomicAdd(&a.counters[CNT_TILES0 + round], tot_tiles) : 0;
+        a.counters[CNT_TILES + round * CSV_MAX_BATCH + b] = tot_tiles;
         s.nbig = 0;
     }
     __syncthreads();
-    Tile* tl = a.tiles[round];
-    int tb = s.tbase + bt, pos = pos_base + br, si = sel_base + bc;
+    Tile* tl = a.tiles[round] + (size_t)b * a.tile_stride;
+    int tb = tiles, pos = pos_base + rows, si = sel_base + cnt;
     for (int c = c0; c < c1; ++c)
         if (flag(c)) {
-            const int n = nl[c], r0 = a.off[c], ntc = (n + TILE_ROWS - 1) / TILE_ROWS;
+            const int r0 = L.offl[c], n = L.offl[c + 1] - r0, ntc = (n + TILE_ROWS - 1) / TILE_ROWS;
             a.sel[(size_t)b * C + si++] = c;
             int slot = BIGQ;
             if (ntc > 16) slot = atomicAdd(&s.nbig, 1);
@@ -318,33 +391,41 @@ __device__ __forceinline__ void emit_clusters(const StepArgs& a, int b, int roun
     __syncthreads();
 }
 
-// Largest bound and log tail mass over the unopened clusters {c : 0 < key_c < kappa}.
-__device__ __forceinline__ void tail_stats(const StepArgs& a, const u64* keys, u64 kappa, SeqShared& s, float& nxtU, float& T) {
+// Largest bound and log tail mass over the unopened clusters {c : 0 < key_c < kappa}: a max pass, then a sum pass.
+__device__ __forceinline__ void tail_stats(const StepArgs& a, const ClusterLds& L, u64 kappa, SeqShared& s, float& nxtU, float& T) {
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
     u64 best = 0;
-    LseAcc acc;
-    acc.m = -INFINITY;
-    acc.s = 0.f;
+    float vmax = -INFINITY;
     for (int c = threadIdx.x; c < a.C; c += blockDim.x) {
-        const u64 kx = keys[c];
+        const u64 kx = L.keys[c];
         if (kx != 0 && kx < kappa) {
             best = kx > best ? kx : best;
-            acc = lse_push(acc, a.lnn[c] + ckey_bound(kx));
+            vmax = fmaxf(vmax, L.vl[c]);
         }
     }
-    best = block_max_u64(best, s.redu);
-    acc = block_lse_combine(acc, s.redl);
-    nxtU = best ? ckey_bound(best) : -INFINITY;
-    T = lse_value(acc);
-}
-
-// keys[c] and rows-per-cluster of sequence b into LDS
-__device__ __forceinline__ void load_keys(const StepArgs& a, int b, u64* keys, int* nl) {
-    for (int c = threadIdx.x; c < a.C; c += blockDim.x) {
-        const float u = a.U[(size_t)b * a.C + c];
-        const int n = a.n[c];
-        nl[c] = n;
-        keys[c] = n > 0 ? ckey(u, c) : 0ull;
+    best = wave_max_u64(best);
+    vmax = wave_max(vmax);
+    __syncthreads();
+    if (lane == 0) {
+        s.redu[w] = best;
+        s.redf[w] = vmax;
     }
+    __syncthreads();
+    best = s.redu[0];
+    vmax = s.redf[0];
+    for (int i = 1; i < nw; ++i) {
+        best = s.redu[i] > best ? s.redu[i] : best;
+        vmax = fmaxf(vmax, s.redf[i]);
+    }
+    float sum = 0.f;
+    if (vmax > -INFINITY)
+        for (int c = threadIdx.x; c < a.C; c += blockDim.x) {
+            const u64 kx = L.keys[c];
+            if (kx != 0 && kx < kappa) sum += expf(L.vl[c] - vmax);
+        }
+    sum = block_sum(sum, s.redf);
+    nxtU = best ? ckey_bound(best) : -INFINITY;
+    T = vmax > -INFINITY ? vmax + logf(sum) : -INFINITY;
 }
 
 // ================================================================================================ seed (round 0)
@@ -354,32 +435,37 @@ __global__ __launch_bounds__(SEQ_THREADS) void seed_kernel(StepArgs a) {
     extern __shared__ u64 arena[];
     __shared__ SeqShared s;
     const int b = blockIdx.x, tid = threadIdx.x, nt = blockDim.x, C = a.C;
-    u64* keys = arena;
-    int* nl = reinterpret_cast<int*>(keys + C);
+    const ClusterLds L = carve_clusters(arena, a.Npad, C);
+    DBG_T(0);
     const float hn = a.hnorm[b];
-    load_keys(a, b, keys, nl);
+    if (tid == 0) a.out.d_flags[b] = CSV_FLAG_INVALID_INPUT;   // pending: overwritten by whichever path finishes the sequence
+    load_clusters(a, b, L);
     if (!isfinite(hn)) {
         write_invalid(a, b);
         return;
     }
     __syncthreads();
+    DBG_T(1);
     const int need = max(a.k, 1);
     int rows = 0, m0 = 0;
     u64 kappa = ~0ull;
     while (rows < need) {
         u64 best = 0;
         for (int c = tid; c < C; c += nt) {
-            const u64 kx = keys[c];
+            const u64 kx = L.keys[c];
             if (kx < kappa && kx > best) best = kx;
         }
         best = block_max_u64(best, s.redu);
         if (best == 0) break;   // no cluster left (cannot happen while k <= V)
-        rows += nl[(int)(0xFFFFFFFFu - (uint32_t)best)];
+        const int cw = (int)(0xFFFFFFFFu - (uint32_t)best);
+        rows += L.offl[cw + 1] - L.offl[cw];
         m0 += 1;
         kappa = best;
     }
+    DBG_T(2);
     float nxtU, T0;
-    tail_stats(a, keys, kappa, s, nxtU, T0);
+    tail_stats(a, L, kappa, s, nxtU, T0);
+    DBG_T(3);
     if (rows > a.K_max) {
         if (tid == 0) {
             a.st[b].n_open = m0;
@@ -388,7 +474,8 @@ __global__ __launch_bounds__(SEQ_THREADS) void seed_kernel(StepArgs a) {
         }
         return;
     }
-    emit_clusters(a, b, 0, 0, 0, [&](int c) { return keys[c] >= kappa; }, nl, s);
+    emit_clusters(a, b, 0, 0, 0, [&](int c) { return L.keys[c] >= kappa; }, L, s);
+    DBG_T(4);
     if (tid == 0) {
         SeqState st;
         st.status = ST_ACTIVE; st.n_open = m0; st.n_rows = rows; st.rounds = 0; st.kappa = kappa; st.nxtU = nxtU; st.T = T0;
@@ -398,69 +485,134 @@ __global__ __launch_bounds__(SEQ_THREADS) void seed_kernel(StepArgs a) {
 }
 
 // ================================================================================================ gathered GEMV
-// Work item = up to TILE_ROWS consecutive rows of W' for one sequence.  A block stages the sequence's h in LDS
-// (bf16) and each wave streams two rows at a time with 128-bit loads, float32 accumulation, wave reduction.
-__global__ __launch_bounds__(256) void gemv_tiles_kernel(StepArgs a, int round) {
-    extern __shared__ uint4 hs4[];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const Tile* tl = a.tiles[round];
-    Tile t = tl[blockIdx.x];                       // speculative: the list always has >= gridDim.x entries allocated
-    const int total = a.counters[CNT_TILES0 + round];
+// Work item = up to TILE_ROWS consecutive rows of W' for one sequence.  Each wave takes two rows and requests
+// their first 8 KB before the sequence's h is staged in LDS (bf16); 128-bit loads, float32 accumulation,
+// wave reduction.  Tiles of sequence b sit in its own region of the list; a prefix over the per-sequence
+// counts maps a global tile number to (sequence, tile).
+#define GEMV_PF 8
+struct GemvShared {
+    int pre[CSV_MAX_BATCH + 1];
+    int wsum[16];
+};
+// RPW rows per wave; a block of TILE_ROWS / RPW waves covers one tile at a time.  block / nblocks: this block's
+// position in the set of blocks that share the work.
+template <int RPW>
+__device__ __forceinline__ void gemv_tiles_device(const StepArgs& a, int round, uint4* hs4, GemvShared& gs, int block, int nblocks) {
+    const int tid = threadIdx.x, nt = blockDim.x, lane = tid & 63, wave = tid >> 6;
+    if (block == 0 && round == 0) DBG_T(16);
+    {
+        const int mine = tid < a.B ? a.counters[CNT_TILES + round * CSV_MAX_BATCH + tid] : 0;
+        int x = mine;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int y = __shfl_up(x, o, CSV_WAVE);
+            if (lane >= o) x += y;
+        }
+        __syncthreads();
+        if (lane == 63) gs.wsum[wave] = x;
+        __syncthreads();
+        int base = 0;
+        for (int i = 0; i < wave; ++i) base += gs.wsum[i];
+        if (tid == 0) gs.pre[0] = 0;
+        if (tid < CSV_MAX_BATCH) gs.pre[tid + 1] = base + x;
+        __syncthreads();
+    }
+    if (block == 0 && round == 0) DBG_T(17);
+    const int total = gs.pre[a.B];
     const int nch = a.d >> 3;
+    const Tile* tl = a.tiles[round];
     int cur_b = -1;
-    for (int g = blockIdx.x; g < total; g += gridDim.x) {
-        if (g != (int)blockIdx.x) t = tl[g];
+    for (int g = block; g < total; g += nblocks) {
+        int lo = 0, hi = a.B;   // largest b with pre[b] <= g
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (gs.pre[mid] <= g) lo = mid; else hi = mid;
+        }
+        const Tile t = tl[(size_t)lo * a.tile_stride + (g - gs.pre[lo])];
+        const int i0 = wave * RPW;
+        const bool active = i0 < t.nrows;
+        int r[RPW];
+        const uint4* w[RPW];
+        uint4 pf[RPW][GEMV_PF];
+        float bias[RPW];
+        int ids[RPW];
+#pragma unroll
+        for (int q = 0; q < RPW; ++q) {
+            r[q] = t.row0 + ((i0 + q < t.nrows) ? i0 + q : 0);
+            w[q] = reinterpret_cast<const uint4*>(a.Wp + (size_t)r[q] * a.d);
+#pragma unroll
+            for (int j = 0; j < GEMV_PF; ++j) {
+                const int i = lane + 64 * j;
+                pf[q][j] = (active && i < nch) ? w[q][i] : make_uint4(0, 0, 0, 0);
+            }
+            bias[q] = 0.f;
+            ids[q] = 0;
+            if (active && lane == 0) {
+                bias[q] = a.bp[r[q]];
+                ids[q] = a.perm[r[q]];
+            }
+        }
         if (t.b != cur_b) {
             __syncthreads();
             const uint4* hsrc = reinterpret_cast<const uint4*>(a.h) + (size_t)t.b * nch;
-            for (int i = tid; i < nch; i += 256) hs4[i] = hsrc[i];
+            for (int i = tid; i < nch; i += nt) hs4[i] = hsrc[i];
             __syncthreads();
             cur_b = t.b;
         }
-        const int i0 = wave * 2;
-        if (i0 >= t.nrows) continue;
-        const bool two = i0 + 1 < t.nrows;
-        const int r0 = t.row0 + i0, r1 = two ? r0 + 1 : r0;
-        float b0 = 0.f, b1 = 0.f;
-        int id0 = 0, id1 = 0;
-        if (lane == 0) {
-            b0 = a.bp[r0]; id0 = a.perm[r0];
-            b1 = a.bp[r1]; id1 = a.perm[r1];
+        if (block == 0 && round == 0) DBG_T(18);
+        if (!active) continue;
+        float acc[RPW];
+#pragma unroll
+        for (int q = 0; q < RPW; ++q) acc[q] = 0.f;
+#pragma unroll
+        for (int j = 0; j < GEMV_PF; ++j) {
+            const int i = lane + 64 * j;
+            if (i < nch) {
+                const uint4 hv = hs4[i];
+#pragma unroll
+                for (int q = 0; q < RPW; ++q) acc[q] = dot8_bf16(pf[q][j], hv, acc[q]);
+            }
         }
-        const uint4* w0 = reinterpret_cast<const uint4*>(a.Wp + (size_t)r0 * a.d);
-        const uint4* w1 = reinterpret_cast<const uint4*>(a.Wp + (size_t)r1 * a.d);
-        float acc0 = 0.f, acc1 = 0.f;
-        int i = lane;
+        int i = lane + 64 * GEMV_PF;
         for (; i + 192 < nch; i += 256) {
-            const uint4 a0 = w0[i], a1 = w0[i + 64], a2 = w0[i + 128], a3 = w0[i + 192];
-            const uint4 c0 = w1[i], c1 = w1[i + 64], c2 = w1[i + 128], c3 = w1[i + 192];
             const uint4 h0 = hs4[i], h1 = hs4[i + 64], h2 = hs4[i + 128], h3 = hs4[i + 192];
-            acc0 = dot8_bf16(a0, h0, acc0);
-            acc1 = dot8_bf16(c0, h0, acc1);
-            acc0 = dot8_bf16(a1, h1, acc0);
-            acc1 = dot8_bf16(c1, h1, acc1);
-            acc0 = dot8_bf16(a2, h2, acc0);
-            acc1 = dot8_bf16(c2, h2, acc1);
-            acc0 = dot8_bf16(a3, h3, acc0);
-            acc1 = dot8_bf16(c3, h3, acc1);
+            uint4 x[RPW][4];
+#pragma unroll
+            for (int q = 0; q < RPW; ++q) {
+                x[q][0] = w[q][i]; x[q][1] = w[q][i + 64]; x[q][2] = w[q][i + 128]; x[q][3] = w[q][i + 192];
+            }
+#pragma unroll
+            for (int q = 0; q < RPW; ++q) {
+                acc[q] = dot8_bf16(x[q][0], h0, acc[q]);
+                acc[q] = dot8_bf16(x[q][1], h1, acc[q]);
+                acc[q] = dot8_bf16(x[q][2], h2, acc[q]);
+                acc[q] = dot8_bf16(x[q][3], h3, acc[q]);
+            }
         }
         for (; i < nch; i += 64) {
             const uint4 hv = hs4[i];
-            acc0 = dot8_bf16(w0[i], hv, acc0);
-            acc1 = dot8_bf16(w1[i], hv, acc1);
+#pragma unroll
+            for (int q = 0; q < RPW; ++q) acc[q] = dot8_bf16(w[q][i], hv, acc[q]);
         }
-        acc0 = wave_sum(acc0);
-        acc1 = wave_sum(acc1);
+#pragma unroll
+        for (int q = 0; q < RPW; ++q) acc[q] = wave_sum(acc[q]);
+        if (block == 0 && round == 0) DBG_T(19);
         if (lane == 0) {
             const size_t o = (size_t)t.b * a.K_cap + t.pos + i0;
-            a.slog[o] = acc0 + b0;
-            a.sid[o] = id0;
-            if (two) {
-                a.slog[o + 1] = acc1 + b1;
-                a.sid[o + 1] = id1;
-            }
+#pragma unroll
+            for (int q = 0; q < RPW; ++q)
+                if (i0 + q < t.nrows) {
+                    a.slog[o + q] = acc[q] + bias[q];
+                    a.sid[o + q] = ids[q];
+                }
         }
     }
+}
+
+__global__ __launch_bounds__(256) void gemv_tiles_kernel(StepArgs a, int round) {
+    extern __shared__ uint4 hs4[];
+    __shared__ GemvShared gs;
+    gemv_tiles_device<2>(a, round, hs4, gs, blockIdx.x, gridDim.x);
 }
 
 // ================================================================================================ block top-k
@@ -522,23 +674,49 @@ __device__ __forceinline__ int block_topk(int n, int k, ValFn val, IdFn id_of, S
     const int kk = min(k, n);
     if (kk <= 0) return 0;
     if (n <= nt) {
-        // one element per thread: rank by counting
-        float v = 0.f;
-        int id = 0;
+        // rank of every element = number of larger values.  The n x n comparisons are spread over all threads:
+        // thread (e, slice) compares element e with one slice of the others and adds its count (larger values in
+        // the low half, equal values in the high half) to rank[e].  Ids are looked at only by elements that have
+        // an equal somewhere else.  blockDim.x must be a power of two.
+        int lg = 0;
+        while ((1 << lg) < n) ++lg;
+        const int npad = 1 << lg, slices = nt >> lg;
+        const int e = tid & (npad - 1), sl = tid >> lg;
+        __syncthreads();
+        if (tid < npad) s.rank[tid] = 0;
+        __syncthreads();
+        const int len = ((n + slices - 1) / slices + 3) & ~3;
+        const int j0 = sl * len, j1 = min(n, j0 + len);
+        if (e < n && j0 < j1) {
+            const float v = val(e);
+            int gt = 0, eq = 0;
+            int j = j0;
+#pragma unroll 2
+            for (; j + 4 <= j1; j += 4) {
+                const float q0 = val(j), q1 = val(j + 1), q2 = val(j + 2), q3 = val(j + 3);
+                gt += (q0 > v) + (q1 > v) + (q2 > v) + (q3 > v);
+                eq += (q0 == v) + (q1 == v) + (q2 == v) + (q3 == v);
+            }
+            for (; j < j1; ++j) {
+                const float vj = val(j);
+                gt += vj > v;
+                eq += vj == v;
+            }
+            atomicAdd(&s.rank[e], gt | (eq << 16));
+        }
         __syncthreads();
         if (tid < n) {
-            v = val(tid);
-            id = id_of(tid);
-        }
-        int rank = 0;
-        for (int j = 0; j < n; ++j) {
-            const float vj = val(j);
-            if (vj > v || (vj == v && id_of(j) < id)) rank += 1;
-        }
-        __syncthreads();
-        if (tid < n && rank < kk) {
-            s.wval[rank] = v;
-            s.wid[rank] = id;
+            const float v = val(tid);
+            const int id = id_of(tid);
+            const int packed = s.rank[tid];
+            int rank = packed & 0xffff;
+            if ((packed >> 16) > 1)
+                for (int i = 0; i < n; ++i)
+                    if (val(i) == v && id_of(i) < id) rank += 1;
+            if (rank < kk) {
+                s.wval[rank] = v;
+                s.wid[rank] = id;
+            }
         }
         __syncthreads();
         return kk;
@@ -629,9 +807,10 @@ __device__ __forceinline__ LseAcc block_lse(int n, ValFn val, SeqShared& s) {
 // ================================================================================================ sorted prefix search
 // s = min{m >= m0 : log tail mass with the first m clusters of the bound order open  -  Z0 <= lam}; returns the key
 // of the s-th cluster of the order (the threshold of that prefix).  Sorts the keys in LDS with a bitonic network;
-// only needed when the softmax test fails after round 0.  skeys: Npad entries; destroys their by-cluster order.
-__device__ __forceinline__ u64 softmax_prefix_key(const StepArgs& a, u64* skeys, int m0, float Z0, SeqShared& s) {
+// only needed when the softmax test fails after round 0.  Destroys the by-cluster order of L.keys (L.vl stays valid).
+__device__ __forceinline__ u64 softmax_prefix_key(const StepArgs& a, const ClusterLds& L, int m0, float Z0, SeqShared& s) {
     const int tid = threadIdx.x, nt = blockDim.x, N = a.Npad;
+    u64* skeys = L.keys;
     for (int i = a.C + tid; i < N; i += nt) skeys[i] = 0ull;
     __syncthreads();
     for (int k2 = 2; k2 <= N; k2 <<= 1) {
@@ -660,7 +839,7 @@ __device__ __forceinline__ u64 softmax_prefix_key(const StepArgs& a, u64* skeys,
     for (int j = j1 - 1; j >= j0 && j < N; --j) {
         const u64 kx = skeys[j];
         if (kx) {
-            run = lse_combine(lse_push(LseAcc{-INFINITY, 0.f}, a.lnn[(int)(0xFFFFFFFFu - (uint32_t)kx)] + ckey_bound(kx)), run);
+            run = lse_combine(lse_push(LseAcc{-INFINITY, 0.f}, L.vl[(int)(0xFFFFFFFFu - (uint32_t)kx)]), run);
             nonempty += 1;
         }
     }
@@ -671,7 +850,7 @@ __device__ __forceinline__ u64 softmax_prefix_key(const StepArgs& a, u64* skeys,
     for (int j = j1 - 1; j >= j0 && j < N; --j) {
         const u64 kx = skeys[j];
         if (kx) {
-            run = lse_combine(lse_push(LseAcc{-INFINITY, 0.f}, a.lnn[(int)(0xFFFFFFFFu - (uint32_t)kx)] + ckey_bound(kx)), run);
+            run = lse_combine(lse_push(LseAcc{-INFINITY, 0.f}, L.vl[(int)(0xFFFFFFFFu - (uint32_t)kx)]), run);
             const float Tj = lse_value(run);     // tail with the first j clusters open
             if (j >= m0 && (Tj - Z0 <= a.lam)) best = min(best, j);
         }
@@ -682,31 +861,34 @@ __device__ __forceinline__ u64 softmax_prefix_key(const StepArgs& a, u64* skeys,
 
 // ================================================================================================ certification
 // One block per sequence.  round 0: certify, or plan round 1 (or fall back on budget); round 1: certify or fall back.
-__global__ __launch_bounds__(SEQ_THREADS) void cert_kernel(StepArgs a, int round) {
+__device__ __forceinline__ void cert_device(const StepArgs& a, int b, int round, SeqShared& s) {
     extern __shared__ u64 arena[];
-    __shared__ SeqShared s;
-    const int b = blockIdx.x, tid = threadIdx.x, nt = blockDim.x, C = a.C;
+    const int tid = threadIdx.x, nt = blockDim.x, C = a.C;
+    if (round == 0) DBG_T(8);
     const SeqState st = a.st[b];
     if (st.status != ST_ACTIVE || st.rounds != round) return;
     const int n = st.n_rows;
     const float* gv = a.slog + (size_t)b * a.K_cap;
     const int32_t* gi = a.sid + (size_t)b * a.K_cap;
-    float* sv = reinterpret_cast<float*>(arena);
-    int* si = reinterpret_cast<int*>(arena) + STAGE_CAP;
     const bool staged = n <= STAGE_CAP;
     if (staged) {
+        float* sv = reinterpret_cast<float*>(arena);
+        int* si = reinterpret_cast<int*>(arena) + STAGE_CAP;
         for (int i = tid; i < n; i += nt) {
             sv[i] = gv[i];
             si[i] = gi[i];
         }
         __syncthreads();
     }
+    if (round == 0) DBG_T(9);
     LseAcc l;
     float theta = -INFINITY;
     if (staged) {
-        auto val = [&](int i) { return sv[i]; };
-        auto idf = [&](int i) { return si[i]; };
+        // the accessors name the LDS array itself so that the reads compile to LDS instructions
+        auto val = [](int i) { return reinterpret_cast<const float*>(arena)[i]; };
+        auto idf = [](int i) { return reinterpret_cast<const int*>(arena)[STAGE_CAP + i]; };
         l = block_lse(n, val, s);
+        if (round == 0) DBG_T(10);
         if (a.use_k) block_topk(n, a.k, val, idf, s);
     } else {
         auto val = [&](int i) { return gv[i]; };
@@ -714,6 +896,7 @@ __global__ __launch_bounds__(SEQ_THREADS) void cert_kernel(StepArgs a, int round
         l = block_lse(n, val, s);
         if (a.use_k) block_topk(n, a.k, val, idf, s);
     }
+    if (round == 0) DBG_T(11);
     const float Z = lse_value(l);
     if (a.use_k) theta = s.wval[a.k - 1];
     const bool tk = (st.nxtU == -INFINITY) || (st.nxtU < theta);
@@ -739,6 +922,7 @@ __global__ __launch_bounds__(SEQ_THREADS) void cert_kernel(StepArgs a, int round
             if (a.out.d_rounds) a.out.d_rounds[b] = round + 1;
             a.st[b].status = ST_DONE;
         }
+        if (round == 0) DBG_T(12);
         return;
     }
     if (round == 1) {
@@ -747,15 +931,14 @@ __global__ __launch_bounds__(SEQ_THREADS) void cert_kernel(StepArgs a, int round
     }
     // ---- plan round 1: the open set grows from {key >= kappa0} to {key >= kappa1}
     __syncthreads();                                   // the staged logits are dead; the arena is reused
-    u64* keys = arena;
-    int* nl = reinterpret_cast<int*>(keys + a.Npad);
+    const ClusterLds L = carve_clusters(arena, a.Npad, C);
     const u64 kappa0 = st.kappa;
     u64 kappa_a = kappa0, kappa_s = kappa0;
     if (a.use_k && !tk) kappa_a = (u64)lkey(theta) << 32;                 // every cluster with U_c >= theta0
     if (a.use_s && !sm) {
-        load_keys(a, b, keys, nl);
+        load_clusters(a, b, L);
         __syncthreads();
-        kappa_s = softmax_prefix_key(a, keys, st.n_open, Z, s);
+        kappa_s = softmax_prefix_key(a, L, st.n_open, Z, s);
         __syncthreads();
     }
     u64 kappa1;
@@ -763,14 +946,14 @@ __global__ __launch_bounds__(SEQ_THREADS) void cert_kernel(StepArgs a, int round
         kappa1 = a.combine == CSV_COMBINE_ALL ? (kappa_a < kappa_s ? kappa_a : kappa_s) : (kappa_a > kappa_s ? kappa_a : kappa_s);
     else
         kappa1 = a.use_k ? kappa_a : kappa_s;
-    load_keys(a, b, keys, nl);
+    load_clusters(a, b, L);
     __syncthreads();
-    auto isnew = [&](int c) { const u64 kx = keys[c]; return kx >= kappa1 && kx < kappa0 && kx != 0; };
+    auto isnew = [&](int c) { const u64 kx = L.keys[c]; return kx >= kappa1 && kx < kappa0 && kx != 0; };
     int cnt = 0, rows = 0;
     for (int c = tid; c < C; c += nt)
         if (isnew(c)) {
             cnt += 1;
-            rows += nl[c];
+            rows += L.offl[c + 1] - L.offl[c];
         }
     cnt = block_sum_i(cnt, s.redi);
     rows = block_sum_i(rows, s.redi);
@@ -783,13 +966,18 @@ __global__ __launch_bounds__(SEQ_THREADS) void cert_kernel(StepArgs a, int round
         return;
     }
     float nxtU, T1;
-    tail_stats(a, keys, kappa1, s, nxtU, T1);
-    emit_clusters(a, b, 1, n, st.n_open, isnew, nl, s);
+    tail_stats(a, L, kappa1, s, nxtU, T1);
+    emit_clusters(a, b, 1, n, st.n_open, isnew, L, s);
     if (tid == 0) {
         SeqState o = st;
         o.n_open = st.n_open + cnt; o.n_rows = n + rows; o.rounds = 1; o.kappa = kappa1; o.nxtU = nxtU; o.T = T1;
         a.st[b] = o;
     }
+}
+
+__global__ __launch_bounds__(SEQ_THREADS) void cert_kernel(StepArgs a, int round) {
+    __shared__ SeqShared s;
+    cert_device(a, blockIdx.x, round, s);
 }
 
 // ================================================================================================ full-vocabulary product
@@ -808,23 +996,21 @@ struct FullArgs {
 };
 
 // Vector path: FULL_G sequences per pass over W', h of the pass in LDS, two rows per wave at a time.
-__global__ __launch_bounds__(256) void full_gemv_kernel(FullArgs f) {
-    extern __shared__ uint4 hs4[];
-    const int n = f.n_ptr ? *f.n_ptr : f.n_fixed;
-    if (n <= 0) return;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+__device__ __forceinline__ void full_gemv_device(const FullArgs& f, int n, uint4* hs4, int block, int nblocks) {
+    const int tid = threadIdx.x, nt = blockDim.x, lane = tid & 63, wave = tid >> 6;
     const int nch = f.d >> 3;
-    const int ntiles = (f.V + 7) / 8;
+    const int rpt = (nt >> 6) * 2;                 // rows per tile: two per wave
+    const int ntiles = (f.V + rpt - 1) / rpt;
     for (int g0 = 0; g0 < n; g0 += FULL_G) {
         const int ng = min(FULL_G, n - g0);
         __syncthreads();
-        for (int i = tid; i < FULL_G * nch; i += 256) {
+        for (int i = tid; i < FULL_G * nch; i += nt) {
             const int s = i / nch, j = i - s * nch;
             hs4[i] = s < ng ? (reinterpret_cast<const uint4*>(f.h) + (size_t)f.list[g0 + s] * nch)[j] : make_uint4(0, 0, 0, 0);
         }
         __syncthreads();
-        for (int tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
-            const int r0 = tile * 8 + wave * 2;
+        for (int tile = block; tile < ntiles; tile += nblocks) {
+            const int r0 = tile * rpt + wave * 2;
             if (r0 >= f.V) continue;
             const bool two = r0 + 1 < f.V;
             const int r1 = two ? r0 + 1 : r0;
@@ -874,15 +1060,24 @@ __global__ __launch_bounds__(256) void full_gemv_kernel(FullArgs f) {
     }
 }
 
-// First stage of top-k / log-sum-exp over V: one block per (chunk of rows, fallback slot).
-__global__ __launch_bounds__(SEQ_THREADS) void fb_topk_kernel(StepArgs a) {
-    __shared__ SeqShared s;
-    const int slot = blockIdx.y, chunk = blockIdx.x, tid = threadIdx.x, nt = blockDim.x;
-    if (slot >= a.counters[CNT_FALLBACK]) return;
+__global__ __launch_bounds__(256) void full_gemv_kernel(FullArgs f) {
+    extern __shared__ uint4 hs4[];
+    const int n = f.n_ptr ? *f.n_ptr : f.n_fixed;
+    if (n <= 0) return;
+    full_gemv_device(f, n, hs4, blockIdx.x, gridDim.x);
+}
+
+// First stage of top-k / log-sum-exp over V: one block per (chunk of rows, fallback slot).  The chunk's logits
+// are staged in LDS; token ids come from the permutation only for elements at the selection boundary.
+__device__ __forceinline__ void fb_topk_device(const StepArgs& a, int slot, int chunk, SeqShared& s) {
+    extern __shared__ u64 arena[];
+    const int tid = threadIdx.x, nt = blockDim.x;
     const int c0 = chunk * FB_CHUNK;
     const int n = min(FB_CHUNK, a.V - c0);
     const float* vals = a.fb_logits + (size_t)slot * a.V + c0;
-    auto val = [&](int i) { return vals[i]; };
+    for (int i = tid; i < n; i += nt) reinterpret_cast<float*>(arena)[i] = vals[i];
+    __syncthreads();
+    auto val = [](int i) { return reinterpret_cast<const float*>(arena)[i]; };
     auto idf = [&](int i) { return a.perm[c0 + i]; };
     const LseAcc l = block_lse(n, val, s);
     const size_t pc = (size_t)slot * a.n_chunks + chunk;
@@ -900,10 +1095,9 @@ __global__ __launch_bounds__(SEQ_THREADS) void fb_topk_kernel(StepArgs a) {
 }
 
 // Second stage: merge the chunk candidates of one fallback sequence and write its outputs.
-__global__ __launch_bounds__(SEQ_THREADS) void fb_final_kernel(StepArgs a) {
-    __shared__ SeqShared s;
-    const int slot = blockIdx.x, tid = threadIdx.x, nt = blockDim.x;
-    if (slot >= a.counters[CNT_FALLBACK]) return;
+__device__ __forceinline__ void fb_final_device(const StepArgs& a, int slot, SeqShared& s) {
+    extern __shared__ u64 arena[];
+    const int tid = threadIdx.x, nt = blockDim.x;
     const int b = a.fb_list[slot];
     const float* cm = a.cand_max + (size_t)slot * a.n_chunks;
     const float* cs = a.cand_sum + (size_t)slot * a.n_chunks;
@@ -916,7 +1110,18 @@ __global__ __launch_bounds__(SEQ_THREADS) void fb_final_kernel(StepArgs a) {
     if (a.k > 0) {
         const float* cv = a.cand_val + (size_t)slot * a.n_chunks * a.k;
         const int32_t* ci = a.cand_id + (size_t)slot * a.n_chunks * a.k;
-        block_topk(a.n_chunks * a.k, a.k, [&](int i) { return cv[i]; }, [&](int i) { return ci[i]; }, s);
+        const int n = a.n_chunks * a.k;
+        if (n <= STAGE_CAP) {
+            for (int i = tid; i < n; i += nt) {
+                reinterpret_cast<float*>(arena)[i] = cv[i];
+                reinterpret_cast<int*>(arena)[STAGE_CAP + i] = ci[i];
+            }
+            __syncthreads();
+            block_topk(n, a.k, [](int i) { return reinterpret_cast<const float*>(arena)[i]; },
+                       [](int i) { return reinterpret_cast<const int*>(arena)[STAGE_CAP + i]; }, s);
+        } else {
+            block_topk(n, a.k, [&](int i) { return cv[i]; }, [&](int i) { return ci[i]; }, s);
+        }
         for (int t = tid; t < a.k; t += nt) {
             a.out.d_ids[(size_t)b * a.k + t] = s.wid[t];
             a.out.d_logits[(size_t)b * a.k + t] = s.wval[t];
@@ -931,7 +1136,85 @@ __global__ __launch_bounds__(SEQ_THREADS) void fb_final_kernel(StepArgs a) {
     }
 }
 
+// ================================================================================================ tail of a step
+// Everything that is rarely needed runs in ONE kernel, so that a step whose sequences were all certified in round 0
+// pays for one (immediately returning) launch instead of five: round-1 gathered GEMV, round-1 certification, the
+// full-vocabulary product for fallback sequences, and the two stages of their top-k / log-sum-exp.  The phases
+// depend on each other grid-wide, so the blocks meet at barriers built on device-scope atomics.  The grid is sized
+// by the host so that all blocks are resident together; every wait is bounded: a block that waits too long raises
+// the abort flag and every block leaves (the step's unfinished sequences keep the INVALID flag seed_kernel gave them).
+#define TAIL_THREADS 512
+#define TAIL_SPIN_LIMIT (1 << 22)
+
+// Returns false when the step was aborted.  Each barrier of a step uses its own counter.
+__device__ __forceinline__ bool grid_barrier(int* counters, int which, int nblocks, int* s_flag) {
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        __threadfence();
+        atomicAdd(&counters[CNT_BARRIER + which], 1);
+        int ok = 1, spins = 0;
+        while (__hip_atomic_load(&counters[CNT_BARRIER + which], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) < nblocks) {
+            if (__hip_atomic_load(&counters[CNT_ABORT], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) { ok = 0; break; }
+            if (++spins > TAIL_SPIN_LIMIT) {
+                atomicExch(&counters[CNT_ABORT], 1);
+                ok = 0;
+                break;
+            }
+            __builtin_amdgcn_s_sleep(8);
+        }
+        __threadfence();
+        *s_flag = ok;
+    }
+    __syncthreads();
+    return *s_flag != 0;
+}
+
+__global__ __launch_bounds__(TAIL_THREADS) void tail_kernel(StepArgs a, FullArgs f) {
+    extern __shared__ u64 arena[];
+    __shared__ SeqShared s;
+    __shared__ GemvShared gs;
+    __shared__ int s_flag;
+    const int tid = threadIdx.x;
+    const int nblocks = gridDim.x, block = blockIdx.x;
+    // is any sequence waiting for round 1 or for the full product?  Every block reads the same, settled values.
+    int mine = 0;
+    if (tid < a.B) mine = a.counters[CNT_TILES + CSV_MAX_BATCH + tid];
+    const int n_fb0 = a.counters[CNT_FALLBACK];
+    const int tiles1 = block_sum_i(mine, s.redi);
+    if (tiles1 == 0 && n_fb0 == 0) return;
+
+    if (tiles1 > 0) {
+        gemv_tiles_device<1>(a, 1, reinterpret_cast<uint4*>(arena), gs, block, nblocks);
+        if (!grid_barrier(a.counters, 0, nblocks, &s_flag)) return;
+        for (int b = block; b < a.B; b += nblocks) {
+            cert_device(a, b, 1, s);
+            __syncthreads();
+        }
+        if (!grid_barrier(a.counters, 1, nblocks, &s_flag)) return;
+    }
+    const int n_fb = __hip_atomic_load(&a.counters[CNT_FALLBACK], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
+    if (n_fb == 0) return;
+    full_gemv_device(f, n_fb, reinterpret_cast<uint4*>(arena), block, nblocks);
+    if (!grid_barrier(a.counters, 2, nblocks, &s_flag)) return;
+    for (int item = block; item < n_fb * a.n_chunks; item += nblocks) {
+        fb_topk_device(a, item / a.n_chunks, item % a.n_chunks, s);
+        __syncthreads();
+    }
+    if (!grid_barrier(a.counters, 3, nblocks, &s_flag)) return;
+    for (int slot = block; slot < n_fb; slot += nblocks) {
+        fb_final_device(a, slot, s);
+        __syncthreads();
+    }
+}
+
 // ================================================================================================ host side
+#ifdef CSV_DEBUG_TIMING
+static unsigned long long* g_dbg = nullptr;
+extern "C" int csv_debug_read(unsigned long long* h_out, int n) {
+    if (!g_dbg) return -1;
+    return hipMemcpy(h_out, g_dbg, (size_t)n * 8, hipMemcpyDeviceToHost) == hipSuccess ? 0 : -3;
+}
+#endif
 static void profile_release(csv_workspace* ws);
 
 static int next_pow2(int x) {
@@ -945,7 +1228,7 @@ static void fill_args(StepArgs& a, const csv_workspace* ws, const csv_index* idx
     a.V = idx->V; a.d = idx->d; a.C = idx->C;
     a.Wp = idx->Wp; a.bp = idx->bp; a.perm = idx->perm; a.mu = idx->mu; a.R = idx->R; a.bmax = idx->bmax;
     a.n = idx->n; a.off = idx->off; a.lnn = idx->lnn;
-    a.K_cap = ws->K_cap; a.Npad = ws->Npad; a.n_chunks = ws->n_chunks;
+    a.K_cap = ws->K_cap; a.Npad = ws->Npad; a.n_chunks = ws->n_chunks; a.tile_stride = ws->tile_stride;
     a.U = ws->U; a.hnorm = ws->hnorm; a.st = ws->st; a.sel = ws->sel; a.slog = ws->slog; a.sid = ws->sid;
     a.tiles[0] = ws->tiles[0]; a.tiles[1] = ws->tiles[1]; a.counters = ws->counters;
     a.fb_list = ws->fb_list; a.fb_logits = ws->fb_logits; a.cand_val = ws->cand_val; a.cand_id = ws->cand_id;
@@ -978,9 +1261,9 @@ static int launch_bounds_kernel(const StepArgs& a, float* U, float* hn, int rese
 }
 
 // dynamic LDS of the per-sequence kernels
-static size_t seed_lds(const csv_workspace* ws) { return (size_t)ws->C * 12; }
+static size_t seed_lds(const csv_workspace* ws) { return (size_t)ws->Npad * 8 + (size_t)ws->C * 8 + 8; }
 static size_t cert_lds(const csv_workspace* ws) {
-    const size_t plan = (size_t)ws->Npad * 8 + (size_t)ws->C * 4, stage = (size_t)STAGE_CAP * 8;
+    const size_t plan = seed_lds(ws), stage = (size_t)STAGE_CAP * 8;
     return plan > stage ? plan : stage;
 }
 
@@ -1009,18 +1292,17 @@ extern "C" int csv_workspace_create(const csv_index* idx, int B_max, int K_cap_r
     ws->n_chunks = (idx->V + FB_CHUNK - 1) / FB_CHUNK;
     ws->device = idx->device;
     const size_t B = B_max, C = idx->C, V = idx->V, K = ws->K_cap, NC = ws->n_chunks;
-    size_t tcap = B * (K / TILE_ROWS + C + 1);
-    if (tcap < 4096) tcap = 4096;
-    ws->tile_cap = (int)tcap;
+    ws->tile_stride = (int)(K / TILE_ROWS + C + 1);
+    const size_t tcap = B * (size_t)ws->tile_stride;
     hipError_t e = hipSuccess;
     auto A = [&](void** p, size_t bytes) { if (e == hipSuccess) e = hipMalloc(p, bytes ? bytes : 16); };
     A((void**)&ws->U, B * C * 4); A((void**)&ws->hnorm, B * 4); A((void**)&ws->st, B * sizeof(SeqState));
     A((void**)&ws->sel, B * C * 4); A((void**)&ws->slog, B * K * 4); A((void**)&ws->sid, B * K * 4);
     A((void**)&ws->tiles[0], tcap * sizeof(Tile)); A((void**)&ws->tiles[1], tcap * sizeof(Tile));
-    A((void**)&ws->counters, 16 * 4); A((void**)&ws->fb_list, B * 4); A((void**)&ws->all_list, B * 4);
+    A((void**)&ws->counters, CNT_TOTAL * 4); A((void**)&ws->fb_list, B * 4); A((void**)&ws->all_list, B * 4);
     A((void**)&ws->fb_logits, B * V * 4); A((void**)&ws->cand_val, B * NC * CSV_MAX_K * 4); A((void**)&ws->cand_id, B * NC * CSV_MAX_K * 4);
     A((void**)&ws->cand_max, B * NC * 4); A((void**)&ws->cand_sum, B * NC * 4);
-    if (e == hipSuccess) e = hipMemset(ws->counters, 0, 16 * 4);
+    if (e == hipSuccess) e = hipMemset(ws->counters, 0, CNT_TOTAL * 4);
     if (e == hipSuccess) e = hipMemset(ws->st, 0, B * sizeof(SeqState));
     if (e == hipSuccess) e = hipMemset(ws->tiles[0], 0, tcap * sizeof(Tile));
     if (e == hipSuccess) e = hipMemset(ws->tiles[1], 0, tcap * sizeof(Tile));
@@ -1035,6 +1317,25 @@ extern "C" int csv_workspace_create(const csv_index* idx, int B_max, int K_cap_r
         e = hipFuncSetAttribute((const void*)seed_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)seed_lds(ws));
     if (e == hipSuccess && cert_lds(ws) + sizeof(SeqShared) > 65536)
         e = hipFuncSetAttribute((const void*)cert_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)cert_lds(ws));
+    if (e == hipSuccess) {
+        size_t l = cert_lds(ws);
+        const size_t cand[] = {(size_t)FULL_G * idx->d * 2, (size_t)FB_CHUNK * 4, (size_t)STAGE_CAP * 8};
+        for (size_t c : cand) l = c > l ? c : l;
+        ws->tail_lds = l;
+        if (l + sizeof(SeqShared) + sizeof(GemvShared) + 64 > 65536)
+            e = hipFuncSetAttribute((const void*)tail_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)l);
+        int per_cu = 0, dev = 0, cus = 0;
+        if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, tail_kernel, TAIL_THREADS, l);
+        if (e == hipSuccess) e = hipGetDevice(&dev);
+        if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e == hipSuccess && (per_cu < 1 || cus < 1)) {
+            csv_set_error("tail kernel does not fit a compute unit (dynamic LDS %zu bytes)", l);
+            csv_workspace_free(ws);
+            return CSV_ESHAPE;
+        }
+        // all blocks of the tail kernel must be resident together: never more than the device holds at once
+        ws->tail_grid = (per_cu > 2 ? 2 : per_cu) * cus;
+    }
     if (e != hipSuccess) {
         csv_set_error("workspace allocation failed: %s", hipGetErrorString(e));
         csv_workspace_free(ws);
@@ -1095,6 +1396,10 @@ extern "C" int csv_decode_step(csv_workspace* ws, const csv_index* idx, const ui
     else if (p->eps >= 1.f) a.lam = INFINITY;
     else a.lam = (float)log((double)p->eps / (1.0 - (double)p->eps));
     a.out = *o;
+#ifdef CSV_DEBUG_TIMING
+    if (!g_dbg) CSV_HIP(hipMalloc((void**)&g_dbg, CSV_MAX_BATCH * 64 * 8));
+    a.dbg = g_dbg;
+#endif
 
     hipEvent_t* ev = nullptr;
     if (ws->prof_on && ws->prof_n < ws->prof_cap) ev = ws->prof_ev + (size_t)ws->prof_n++ * (CSV_PROFILE_STAGES + 1);
@@ -1115,21 +1420,14 @@ extern "C" int csv_decode_step(csv_workspace* ws, const csv_index* idx, const ui
     cert_kernel<<<B, SEQ_THREADS, cert_lds(ws), st>>>(a, 0);
     CSV_LAUNCH_CHECK("cert_kernel");
     CSV_MARK(4);
-    gemv_tiles_kernel<<<gg, 256, hl, st>>>(a, 1);
-    CSV_LAUNCH_CHECK("gemv_tiles_kernel");
+    {
+        FullArgs f;
+        f.V = idx->V; f.d = idx->d; f.Wp = idx->Wp; f.bp = idx->bp; f.perm = idx->perm; f.h = d_h;
+        f.list = ws->fb_list; f.n_ptr = nullptr; f.n_fixed = 0; f.out = ws->fb_logits; f.out_stride = idx->V; f.scatter = 0;
+        tail_kernel<<<ws->tail_grid, TAIL_THREADS, ws->tail_lds, st>>>(a, f);
+        CSV_LAUNCH_CHECK("tail_kernel");
+    }
     CSV_MARK(5);
-    cert_kernel<<<B, SEQ_THREADS, cert_lds(ws), st>>>(a, 1);
-    CSV_LAUNCH_CHECK("cert_kernel");
-    CSV_MARK(6);
-    rc = launch_full(idx, d_h, ws->fb_list, ws->counters + CNT_FALLBACK, 0, ws->fb_logits, idx->V, 0, st);
-    if (rc) return rc;
-    CSV_MARK(7);
-    fb_topk_kernel<<<dim3(ws->n_chunks, B), SEQ_THREADS, 0, st>>>(a);
-    CSV_LAUNCH_CHECK("fb_topk_kernel");
-    CSV_MARK(8);
-    fb_final_kernel<<<B, SEQ_THREADS, 0, st>>>(a);
-    CSV_LAUNCH_CHECK("fb_final_kernel");
-    CSV_MARK(9);
 #undef CSV_MARK
     return CSV_OK;
 }
