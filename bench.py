@@ -143,12 +143,31 @@ def main() -> int:
     bound_bytes = r.C * r.d * 4 + 12 * r.C + r.B * r.d * 2 + 4 * r.B * r.C
     gemv_bytes = (rows_sum / nstat) * (2 * r.d + 16) + r.B * r.d * 2
     full_bytes_launch = r.V * (2 * r.d + 8) + r.B * r.d * 2
+    # The dominant kernel is the one that moves most of the step's bytes: the bound kernel (all centroids) on the
+    # sub-vocabulary path, the full-vocabulary product when most steps contain a fallback.  Its average launch
+    # duration is measured with HIP events around back-to-back launches of that kernel alone on the same stream
+    # (events between the kernels of a step would add their own few microseconds to every stage).
+    nrep = 200
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     if anyfb / nstat > 0.5:
-        dom_name, dom_bytes, dom_us = "tail_kernel (full-vocabulary product for fallback sequences)", full_bytes_launch, stage_us["tail"]
-    elif rounds_hist[2] == 0 and stage_us["gemv_round0"] > stage_us["bounds"]:
-        dom_name, dom_bytes, dom_us = "gemv_tiles_kernel", gemv_bytes, stage_us["gemv_round0"]
+        dom_name, dom_bytes = "full_gemv_kernel (full-vocabulary product, all B sequences)", full_bytes_launch
+        nrep = 20
+        ev0.record(stream)
+        for s in range(nrep):
+            csv.csv_full_logits(ws, idx, dh[s % nh], out=full_out)
+        ev1.record(stream)
     else:
-        dom_name, dom_bytes, dom_us = "bound_kernel", bound_bytes, stage_us["bounds"]
+        dom_name, dom_bytes = "bound_kernel", bound_bytes
+        U_out = torch.empty((r.B, r.C), dtype=torch.float32, device="cuda")
+        hn_out = torch.empty(r.B, dtype=torch.float32, device="cuda")
+        for s in range(10):
+            csv.lib.csv_bounds(ws._h, idx._h, hp[s], r.B, U_out.data_ptr(), hn_out.data_ptr(), sp)
+        ev0.record(stream)
+        for s in range(nrep):
+            csv.lib.csv_bounds(ws._h, idx._h, hp[s % len(hp)], r.B, U_out.data_ptr(), hn_out.data_ptr(), sp)
+        ev1.record(stream)
+    torch.cuda.synchronize()
+    dom_us = ev0.elapsed_time(ev1) * 1e3 / nrep
     achieved = dom_bytes / (dom_us * 1e-6) / 1e9
     bstep = step_bytes(r, r.C, rows_union_sum / nstat, anyfb / nstat, r.k)
     eff_gbs = bstep / (ms_per_step * 1e-3) / 1e9
