@@ -40,6 +40,8 @@ struct StepArgs {
     const int32_t* off;
     const float* lnn;
     int B, K_cap, Npad, n_chunks, tile_stride;
+    int sp_chunks;     // most STAGE_CAP-sized chunks a sequence's scored rows can span
+    int cand_chunks;   // chunk stride of the candidate buffers
     float* U;
     float* hnorm;
     SeqState* st;
@@ -170,6 +172,109 @@ __global__ __launch_bounds__(256) void bound_kernel(StepArgs a, float* __restric
         const bool empty = ncl == 0;
 #pragma unroll
         for (int s = 0; s < BT; ++s)
+            if (s < nb) U_out[(size_t)(b0 + s) * a.C + c] = empty ? -INFINITY : (acc[s] + Rc * hn[s] + bm);
+    }
+}
+
+// Bounds for larger batches: every sequence of the pass meets each centroid row exactly once.  K is walked in
+// chunks whose h slices (all NB sequences, bf16) fit in LDS; a lane keeps NB accumulators.  The kernel turns
+// ALU-bound near NB = 32 (about 8 vector instructions per sequence and 16 centroid bytes), which is still several
+// times faster than re-reading the centroids once per group of 8 sequences.
+#define BATCH_MAXQ 6
+template <int NB>
+__global__ __launch_bounds__(256) void bound_batched_kernel(StepArgs a, float* __restrict__ U_out, float* __restrict__ hn_out,
+                                                            int reset_counters, int kc) {
+    extern __shared__ uint4 hs4[];            // [NB][kc] bf16
+    __shared__ float hn[NB];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int b0 = blockIdx.y * NB;
+    const int nb = min(NB, a.B - b0);
+    const int c = blockIdx.x * 4 + wave;
+    const bool valid = c < a.C;
+    const float4* mrow = reinterpret_cast<const float4*>(a.mu + (size_t)(valid ? c : 0) * a.d);
+    const int nch = a.d >> 3;                 // 16-byte chunks per h row
+    const int kq = kc >> 2, kch = kc >> 3;    // float4 / uint4 per chunk row
+    if (reset_counters && blockIdx.x == 0 && blockIdx.y == 0)
+        for (int i = tid; i < CNT_TOTAL; i += 256) a.counters[i] = 0;
+    float acc[NB];
+    float nrm[(NB + 3) / 4];
+#pragma unroll
+    for (int s = 0; s < NB; ++s) acc[s] = 0.f;
+#pragma unroll
+    for (int j = 0; j < (NB + 3) / 4; ++j) nrm[j] = 0.f;
+    const uint2* hs2 = reinterpret_cast<const uint2*>(hs4);
+    // the lane's centroid values of a chunk are requested one chunk ahead (BATCH_MAXQ float4 cover kc <= 1536)
+    float4 cur[BATCH_MAXQ], nxt[BATCH_MAXQ];
+    auto fetch = [&](float4* dst, int k0) {
+        const int nq = min(kc, a.d - k0) >> 2;
+        const float4* mp = mrow + (k0 >> 2);
+#pragma unroll
+        for (int j = 0; j < BATCH_MAXQ; ++j) {
+            const int i = lane + 64 * j;
+            dst[j] = (valid && k0 < a.d && i < nq) ? mp[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+    };
+    fetch(cur, 0);
+    for (int k0 = 0; k0 < a.d; k0 += kc) {
+        const int kn = min(kc, a.d - k0);     // multiple of 8
+        __syncthreads();
+        for (int i = tid; i < NB * kch; i += 256) {
+            const int s = i / kch, j = i - s * kch;
+            hs4[i] = (s < nb && j * 8 < kn) ? (reinterpret_cast<const uint4*>(a.h) + (size_t)(b0 + s) * nch)[(k0 >> 3) + j]
+                                           : make_uint4(0, 0, 0, 0);
+        }
+        fetch(nxt, k0 + kc);
+        __syncthreads();
+        // squared norms: wave w owns sequences w, w+4, ...
+#pragma unroll
+        for (int j = 0; j < (NB + 3) / 4; ++j) {
+            const int sq = wave + 4 * j;
+            if (sq < NB) {
+                float p = 0.f;
+                for (int i = lane; i < kch; i += 64) {
+                    const uint4 v = hs4[sq * kch + i];
+                    p = dot8_bf16(v, v, p);
+                }
+                nrm[j] += p;
+            }
+        }
+        if (valid) {
+            const int nq = kn >> 2;
+#pragma unroll
+            for (int j = 0; j < BATCH_MAXQ; ++j) {
+                const int i = lane + 64 * j;
+                if (i < nq) {
+                    const float4 m = cur[j];
+#pragma unroll
+                    for (int s = 0; s < NB; ++s) {
+                        const uint2 hv = hs2[s * kq + i];
+                        acc[s] = fmaf(m.x, bf16_lo(hv.x), acc[s]);
+                        acc[s] = fmaf(m.y, bf16_hi(hv.x), acc[s]);
+                        acc[s] = fmaf(m.z, bf16_lo(hv.y), acc[s]);
+                        acc[s] = fmaf(m.w, bf16_hi(hv.y), acc[s]);
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < BATCH_MAXQ; ++j) cur[j] = nxt[j];
+    }
+#pragma unroll
+    for (int j = 0; j < (NB + 3) / 4; ++j) {
+        const int sq = wave + 4 * j;
+        const float t = wave_sum(nrm[j]);
+        if (sq < NB && lane == 0) hn[sq] = sqrtf(t);
+    }
+    __syncthreads();
+    if (blockIdx.x == 0 && tid < nb && hn_out) hn_out[b0 + tid] = hn[tid];
+    if (!valid) return;
+#pragma unroll
+    for (int s = 0; s < NB; ++s) acc[s] = wave_sum(acc[s]);
+    if (lane == 0) {
+        const float Rc = a.R[c], bm = a.bmax[c];
+        const bool empty = a.n[c] == 0;
+#pragma unroll
+        for (int s = 0; s < NB; ++s)
             if (s < nb) U_out[(size_t)(b0 + s) * a.C + c] = empty ? -INFINITY : (acc[s] + Rc * hn[s] + bm);
     }
 }
@@ -615,6 +720,21 @@ __global__ __launch_bounds__(256) void gemv_tiles_kernel(StepArgs a, int round) 
     gemv_tiles_device<2>(a, round, hs4, gs, blockIdx.x, gridDim.x);
 }
 
+// Copy n 32-bit words from global memory to LDS with eight loads in flight per thread.
+template <class T>
+__device__ __forceinline__ void stage_to_lds(T* dst, const T* __restrict__ src, int n) {
+    const int tid = threadIdx.x, nt = blockDim.x;
+    int i = tid;
+    for (; i + 7 * nt < n; i += 8 * nt) {
+        T r[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) r[q] = src[i + q * nt];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) dst[i + q * nt] = r[q];
+    }
+    for (; i < n; i += nt) dst[i] = src[i];
+}
+
 // ================================================================================================ block top-k
 // kk-th largest key among the elements for which key(i, kx) returns true (1 <= kk <= their number).
 // On return: kth = that key, need_eq = how many elements equal to it belong to the largest kk, n_eq = how many equal it.
@@ -622,14 +742,57 @@ __global__ __launch_bounds__(256) void gemv_tiles_kernel(StepArgs a, int round) 
 template <class KeyFn>
 __device__ __forceinline__ void radix_select(int n, unsigned kk, KeyFn key, SeqShared& s, unsigned& kth,
                                              unsigned& need_eq, unsigned& n_eq) {
-    const int tid = threadIdx.x, nt = blockDim.x, lane = tid & 63;
+    const int tid = threadIdx.x, nt = blockDim.x, lane = tid & 63, w = tid >> 6, nw = (nt + 63) >> 6;
+    // Bytes that all keys share from the top need no pass (logits of one cluster differ only in their low bits,
+    // and a histogram pass over a shared byte would send every element to the same bin).
+    unsigned kmin = 0xffffffffu, kmax = 0u;
+    for (int i = tid; i < n; i += nt) {
+        unsigned kx;
+        if (key(i, kx)) {
+            kmin = kx < kmin ? kx : kmin;
+            kmax = kx > kmax ? kx : kmax;
+        }
+    }
+    kmax = wave_max_u(kmax);
+    kmin = ~wave_max_u(~kmin);
+    __syncthreads();
+    if (lane == 0) {
+        s.hist[w] = kmax;
+        s.hist[16 + w] = kmin;
+    }
+    __syncthreads();
+    for (int i = 0; i < nw; ++i) {
+        kmax = s.hist[i] > kmax ? s.hist[i] : kmax;
+        kmin = s.hist[16 + i] < kmin ? s.hist[16 + i] : kmin;
+    }
+    __syncthreads();
+    const unsigned diff = kmin ^ kmax;
+    int first_shift = 24;
     unsigned prefix = 0, mask = 0, rem = kk, eq = 0;
-    for (int shift = 24; shift >= 0; shift -= 8) {
+    while (first_shift > 0 && ((diff >> first_shift) & 0xffu) == 0) {
+        prefix |= kmax & (0xffu << first_shift);
+        mask |= 0xffu << first_shift;
+        first_shift -= 8;
+    }
+    for (int shift = first_shift; shift >= 0; shift -= 8) {
         for (int t = tid; t < 256; t += nt) s.hist[t] = 0;
         __syncthreads();
-        for (int i = tid; i < n; i += nt) {
-            unsigned kx;
-            if (key(i, kx) && (kx & mask) == prefix) atomicAdd(&s.hist[(kx >> shift) & 255u], 1u);
+        for (int i0 = 0; i0 < n; i0 += nt) {
+            const int i = i0 + tid;
+            unsigned kx = 0;
+            const bool in = i < n && key(i, kx) && (kx & mask) == prefix;
+            const unsigned dg = (kx >> shift) & 255u;
+            // one atomic per wave when every participating lane has the same digit
+            const unsigned long long act = __ballot(in);
+            if (act) {
+                const unsigned d0 = __shfl(dg, __ffsll((long long)act) - 1, CSV_WAVE);
+                const unsigned long long same = __ballot(in && dg == d0);
+                if (same == act) {
+                    if (lane == __ffsll((long long)act) - 1) atomicAdd(&s.hist[d0], (unsigned)__popcll(act));
+                } else if (in) {
+                    atomicAdd(&s.hist[dg], 1u);
+                }
+            }
         }
         __syncthreads();
         if (tid < 64) {
@@ -861,43 +1024,76 @@ __device__ __forceinline__ u64 softmax_prefix_key(const StepArgs& a, const Clust
 
 // ================================================================================================ certification
 // One block per sequence.  round 0: certify, or plan round 1 (or fall back on budget); round 1: certify or fall back.
-__device__ __forceinline__ void cert_device(const StepArgs& a, int b, int round, SeqShared& s) {
+// Sequences with more than STAGE_CAP scored rows are handled by several blocks: each takes one chunk of STAGE_CAP
+// logits, publishes the chunk's top-k candidates and log-sum-exp partial, and the block that arrives last (a
+// device-scope counter; nobody waits) merges them and goes on to the tests.
+__device__ __forceinline__ void cert_device(const StepArgs& a, int b, int chunk, int round, SeqShared& s) {
     extern __shared__ u64 arena[];
     const int tid = threadIdx.x, nt = blockDim.x, C = a.C;
-    if (round == 0) DBG_T(8);
+    if (round == 0 || blockIdx.x == 0) DBG_T(8);
     const SeqState st = a.st[b];
     if (st.status != ST_ACTIVE || st.rounds != round) return;
     const int n = st.n_rows;
-    const float* gv = a.slog + (size_t)b * a.K_cap;
-    const int32_t* gi = a.sid + (size_t)b * a.K_cap;
-    const bool staged = n <= STAGE_CAP;
-    if (staged) {
-        float* sv = reinterpret_cast<float*>(arena);
-        int* si = reinterpret_cast<int*>(arena) + STAGE_CAP;
-        for (int i = tid; i < n; i += nt) {
-            sv[i] = gv[i];
-            si[i] = gi[i];
-        }
+    const int nchunks = (n + STAGE_CAP - 1) / STAGE_CAP;
+    if (chunk >= nchunks) return;
+    const int c0 = chunk * STAGE_CAP, len = min(STAGE_CAP, n - c0);
+    {
+        const float* gv = a.slog + (size_t)b * a.K_cap + c0;
+        const int32_t* gi = a.sid + (size_t)b * a.K_cap + c0;
+        stage_to_lds(reinterpret_cast<float*>(arena), gv, len);
+        stage_to_lds(reinterpret_cast<int*>(arena) + STAGE_CAP, gi, len);
         __syncthreads();
     }
-    if (round == 0) DBG_T(9);
-    LseAcc l;
-    float theta = -INFINITY;
-    if (staged) {
-        // the accessors name the LDS array itself so that the reads compile to LDS instructions
-        auto val = [](int i) { return reinterpret_cast<const float*>(arena)[i]; };
-        auto idf = [](int i) { return reinterpret_cast<const int*>(arena)[STAGE_CAP + i]; };
-        l = block_lse(n, val, s);
-        if (round == 0) DBG_T(10);
-        if (a.use_k) block_topk(n, a.k, val, idf, s);
-    } else {
-        auto val = [&](int i) { return gv[i]; };
-        auto idf = [&](int i) { return gi[i]; };
-        l = block_lse(n, val, s);
-        if (a.use_k) block_topk(n, a.k, val, idf, s);
+    if (round == 0 || blockIdx.x == 0) DBG_T(9);
+    // the accessors name the LDS array itself so that the reads compile to LDS instructions
+    auto val = [](int i) { return reinterpret_cast<const float*>(arena)[i]; };
+    auto idf = [](int i) { return reinterpret_cast<const int*>(arena)[STAGE_CAP + i]; };
+    LseAcc l = block_lse(len, val, s);
+    if (round == 0 || blockIdx.x == 0) DBG_T(10);
+    if (a.use_k) block_topk(len, a.k, val, idf, s);
+    if (round == 0 || blockIdx.x == 0) DBG_T(13);
+    if (nchunks > 1) {
+        const size_t pb = (size_t)b * a.cand_chunks, pc = pb + chunk;
+        const int kk = min(a.k, len);
+        for (int t = tid; t < a.k; t += nt) {
+            a.cand_val[pc * a.k + t] = t < kk ? s.wval[t] : -INFINITY;
+            a.cand_id[pc * a.k + t] = t < kk ? s.wid[t] : 0x7fffffff;
+        }
+        if (tid == 0) {
+            a.cand_max[pc] = l.m;
+            a.cand_sum[pc] = l.s;
+        }
+        __threadfence();
+        __syncthreads();
+        if (tid == 0) s.sel = atomicAdd(&a.counters[CNT_CHUNKS + round * CSV_MAX_BATCH + b], 1) == nchunks - 1;
+        __syncthreads();
+        if (!s.sel) return;
+        __threadfence();
+        float mx = -INFINITY;
+        for (int i = tid; i < nchunks; i += nt) mx = fmaxf(mx, a.cand_max[pb + i]);
+        mx = block_max(mx, s.redf);
+        float sm = 0.f;
+        for (int i = tid; i < nchunks; i += nt) sm += a.cand_sum[pb + i] * expf(a.cand_max[pb + i] - mx);
+        l.m = mx;
+        l.s = block_sum(sm, s.redf);
+        if (a.use_k) {
+            const float* cv = a.cand_val + pb * a.k;
+            const int32_t* ci = a.cand_id + pb * a.k;
+            const int nc = nchunks * a.k;
+            if (nc <= STAGE_CAP) {
+                __syncthreads();
+                stage_to_lds(reinterpret_cast<float*>(arena), cv, nc);
+                stage_to_lds(reinterpret_cast<int*>(arena) + STAGE_CAP, ci, nc);
+                __syncthreads();
+                block_topk(nc, a.k, val, idf, s);
+            } else {
+                block_topk(nc, a.k, [&](int i) { return cv[i]; }, [&](int i) { return ci[i]; }, s);
+            }
+        }
     }
-    if (round == 0) DBG_T(11);
+    if (round == 0 || blockIdx.x == 0) DBG_T(11);
     const float Z = lse_value(l);
+    float theta = -INFINITY;
     if (a.use_k) theta = s.wval[a.k - 1];
     const bool tk = (st.nxtU == -INFINITY) || (st.nxtU < theta);
     const bool sm = (st.T - Z <= a.lam) || (st.T == -INFINITY);
@@ -977,7 +1173,7 @@ __device__ __forceinline__ void cert_device(const StepArgs& a, int b, int round,
 
 __global__ __launch_bounds__(SEQ_THREADS) void cert_kernel(StepArgs a, int round) {
     __shared__ SeqShared s;
-    cert_device(a, blockIdx.x, round, s);
+    cert_device(a, blockIdx.x, blockIdx.y, round, s);
 }
 
 // ================================================================================================ full-vocabulary product
@@ -1067,6 +1263,99 @@ __global__ __launch_bounds__(256) void full_gemv_kernel(FullArgs f) {
     full_gemv_device(f, n, hs4, blockIdx.x, gridDim.x);
 }
 
+// MFMA path of the full-vocabulary product, used when more than FULL_G sequences share the pass over W' (then it
+// is a real dense contraction: [V x d] . [d x n]).  v_mfma_f32_16x16x32_bf16: a wave owns 16*MT rows of W' and
+// 16*NT sequences; K is walked in blocks of 128 (four MFMAs).  Lane (li = lane%16, g = lane/16) feeds row/sequence
+// li and, for the jj-th MFMA of a block, the eight k values at  block + 32 jj + 8 g: one load instruction reads
+// 64 contiguous bytes from each of 16 rows.  Both operands go straight from global memory to registers (h rows are L2-resident);
+// the kernel is HBM-bound, so the loads of one wave are hidden by the other waves of the SIMD rather than by
+// double buffering (which would cost the registers that keep four waves per SIMD resident).  Accumulator register r of lane (li, g) is  out[row 4g + r][sequence li].
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4_t;
+
+template <int MT, int NT>
+__device__ __forceinline__ void full_mfma_device(const FullArgs& f, int n, int seq0, int block, int nblocks) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nw = blockDim.x >> 6;
+    const int li = lane & 15, g = lane >> 4;
+    const int rpw = 16 * MT;
+    const int ntiles = (f.V + rpw - 1) / rpw;
+    const int nq = f.d >> 3;                         // 16-byte chunks per row
+    const int nsb = (f.d + 127) >> 7;
+    const uint4 zero = make_uint4(0, 0, 0, 0);
+    const uint4* hp[NT];
+    bool hv[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        const int sq = seq0 + t * 16 + li;
+        hv[t] = sq < n;
+        hp[t] = reinterpret_cast<const uint4*>(f.h) + (size_t)f.list[hv[t] ? sq : seq0] * nq;
+    }
+    for (int tile = block * nw + wave; tile < ntiles; tile += nblocks * nw) {
+        const int r0 = tile * rpw;
+        const uint4* ap[MT];
+#pragma unroll
+        for (int m = 0; m < MT; ++m) {
+            const int row = min(r0 + m * 16 + li, f.V - 1);
+            ap[m] = reinterpret_cast<const uint4*>(f.Wp + (size_t)row * f.d);
+        }
+        floatx4_t acc[MT][NT];
+#pragma unroll
+        for (int m = 0; m < MT; ++m)
+#pragma unroll
+            for (int t = 0; t < NT; ++t) acc[m][t] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+        for (int sb = 0; sb < nsb; ++sb) {
+            uint4 A[MT][4], Bv[NT][4];
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) {
+                const int q = sb * 16 + jj * 4 + g;     // chunk index of k = 128 sb + 32 jj + 8 g
+                const bool ok = q < nq;
+#pragma unroll
+                for (int m = 0; m < MT; ++m) A[m][jj] = ok ? ap[m][q] : zero;
+#pragma unroll
+                for (int t = 0; t < NT; ++t) Bv[t][jj] = (ok && hv[t]) ? hp[t][q] : zero;
+            }
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj)
+#pragma unroll
+                for (int m = 0; m < MT; ++m)
+#pragma unroll
+                    for (int t = 0; t < NT; ++t)
+                        acc[m][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, A[m][jj]),
+                                                                            __builtin_bit_cast(bf16x8_t, Bv[t][jj]), acc[m][t], 0, 0, 0);
+        }
+#pragma unroll
+        for (int m = 0; m < MT; ++m)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int row = r0 + m * 16 + 4 * g + r;
+                if (row < f.V) {
+                    const float bias = f.bp[row];
+                    const size_t col = f.scatter ? (size_t)f.perm[row] : (size_t)row;
+#pragma unroll
+                    for (int t = 0; t < NT; ++t) {
+                        const int sq = seq0 + t * 16 + li;
+                        if (sq < n) f.out[(size_t)sq * f.out_stride + col] = acc[m][t][r] + bias;
+                    }
+                }
+            }
+    }
+}
+
+// All n sequences through the MFMA path: 32 per pass over W' (16 when that covers them).
+__device__ __forceinline__ void full_mfma_all(const FullArgs& f, int n, int block, int nblocks) {
+    if (n <= 16) {
+        full_mfma_device<2, 1>(f, n, 0, block, nblocks);
+    } else {
+        for (int s0 = 0; s0 < n; s0 += 32) full_mfma_device<2, 2>(f, n, s0, block, nblocks);
+    }
+}
+
+__global__ __launch_bounds__(256) void full_mfma_kernel(FullArgs f) {
+    const int n = f.n_ptr ? *f.n_ptr : f.n_fixed;
+    if (n <= 0) return;
+    full_mfma_all(f, n, blockIdx.x, gridDim.x);
+}
+
 // First stage of top-k / log-sum-exp over V: one block per (chunk of rows, fallback slot).  The chunk's logits
 // are staged in LDS; token ids come from the permutation only for elements at the selection boundary.
 __device__ __forceinline__ void fb_topk_device(const StepArgs& a, int slot, int chunk, SeqShared& s) {
@@ -1075,7 +1364,7 @@ __device__ __forceinline__ void fb_topk_device(const StepArgs& a, int slot, int 
     const int c0 = chunk * FB_CHUNK;
     const int n = min(FB_CHUNK, a.V - c0);
     const float* vals = a.fb_logits + (size_t)slot * a.V + c0;
-    for (int i = tid; i < n; i += nt) reinterpret_cast<float*>(arena)[i] = vals[i];
+    stage_to_lds(reinterpret_cast<float*>(arena), vals, n);
     __syncthreads();
     auto val = [](int i) { return reinterpret_cast<const float*>(arena)[i]; };
     auto idf = [&](int i) { return a.perm[c0 + i]; };
@@ -1112,10 +1401,8 @@ __device__ __forceinline__ void fb_final_device(const StepArgs& a, int slot, Seq
         const int32_t* ci = a.cand_id + (size_t)slot * a.n_chunks * a.k;
         const int n = a.n_chunks * a.k;
         if (n <= STAGE_CAP) {
-            for (int i = tid; i < n; i += nt) {
-                reinterpret_cast<float*>(arena)[i] = cv[i];
-                reinterpret_cast<int*>(arena)[STAGE_CAP + i] = ci[i];
-            }
+            stage_to_lds(reinterpret_cast<float*>(arena), cv, n);
+            stage_to_lds(reinterpret_cast<int*>(arena) + STAGE_CAP, ci, n);
             __syncthreads();
             block_topk(n, a.k, [](int i) { return reinterpret_cast<const float*>(arena)[i]; },
                        [](int i) { return reinterpret_cast<const int*>(arena)[STAGE_CAP + i]; }, s);
@@ -1160,7 +1447,7 @@ __device__ __forceinline__ bool grid_barrier(int* counters, int which, int nbloc
                 ok = 0;
                 break;
             }
-            __builtin_amdgcn_s_sleep(8);
+            __builtin_amdgcn_s_sleep(32);
         }
         __threadfence();
         *s_flag = ok;
@@ -1182,29 +1469,42 @@ __global__ __launch_bounds__(TAIL_THREADS) void tail_kernel(StepArgs a, FullArgs
     const int n_fb0 = a.counters[CNT_FALLBACK];
     const int tiles1 = block_sum_i(mine, s.redi);
     if (tiles1 == 0 && n_fb0 == 0) return;
+    if (block == 0) DBG_T(20);
 
     if (tiles1 > 0) {
         gemv_tiles_device<1>(a, 1, reinterpret_cast<uint4*>(arena), gs, block, nblocks);
+        if (block == 0) DBG_T(21);
         if (!grid_barrier(a.counters, 0, nblocks, &s_flag)) return;
-        for (int b = block; b < a.B; b += nblocks) {
-            cert_device(a, b, 1, s);
+        if (block == 0) DBG_T(22);
+        for (int item = block; item < a.B * a.sp_chunks; item += nblocks) {
+            cert_device(a, item / a.sp_chunks, item % a.sp_chunks, 1, s);
             __syncthreads();
         }
+        if (block == 0) DBG_T(23);
         if (!grid_barrier(a.counters, 1, nblocks, &s_flag)) return;
+        if (block == 0) DBG_T(24);
     }
     const int n_fb = __hip_atomic_load(&a.counters[CNT_FALLBACK], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
     if (n_fb == 0) return;
-    full_gemv_device(f, n_fb, reinterpret_cast<uint4*>(arena), block, nblocks);
+    if (n_fb > FULL_G)
+        full_mfma_all(f, n_fb, block, nblocks);
+    else
+        full_gemv_device(f, n_fb, reinterpret_cast<uint4*>(arena), block, nblocks);
+    if (block == 0) DBG_T(25);
     if (!grid_barrier(a.counters, 2, nblocks, &s_flag)) return;
+    if (block == 0) DBG_T(26);
     for (int item = block; item < n_fb * a.n_chunks; item += nblocks) {
         fb_topk_device(a, item / a.n_chunks, item % a.n_chunks, s);
         __syncthreads();
     }
+    if (block == 0) DBG_T(27);
     if (!grid_barrier(a.counters, 3, nblocks, &s_flag)) return;
+    if (block == 0) DBG_T(28);
     for (int slot = block; slot < n_fb; slot += nblocks) {
         fb_final_device(a, slot, s);
         __syncthreads();
     }
+    if (block == 0) DBG_T(29);
 }
 
 // ================================================================================================ host side
@@ -1228,7 +1528,7 @@ static void fill_args(StepArgs& a, const csv_workspace* ws, const csv_index* idx
     a.V = idx->V; a.d = idx->d; a.C = idx->C;
     a.Wp = idx->Wp; a.bp = idx->bp; a.perm = idx->perm; a.mu = idx->mu; a.R = idx->R; a.bmax = idx->bmax;
     a.n = idx->n; a.off = idx->off; a.lnn = idx->lnn;
-    a.K_cap = ws->K_cap; a.Npad = ws->Npad; a.n_chunks = ws->n_chunks; a.tile_stride = ws->tile_stride;
+    a.K_cap = ws->K_cap; a.Npad = ws->Npad; a.n_chunks = ws->n_chunks; a.tile_stride = ws->tile_stride; a.sp_chunks = ws->sp_chunks; a.cand_chunks = ws->cand_chunks;
     a.U = ws->U; a.hnorm = ws->hnorm; a.st = ws->st; a.sel = ws->sel; a.slog = ws->slog; a.sid = ws->sid;
     a.tiles[0] = ws->tiles[0]; a.tiles[1] = ws->tiles[1]; a.counters = ws->counters;
     a.fb_list = ws->fb_list; a.fb_logits = ws->fb_logits; a.cand_val = ws->cand_val; a.cand_id = ws->cand_id;
@@ -1243,6 +1543,19 @@ static int check_pair(const csv_workspace* ws, const csv_index* idx, const void*
 }
 
 static int launch_bounds_kernel(const StepArgs& a, float* U, float* hn, int reset, hipStream_t st) {
+    if (a.B > 8) {
+        const int nbp = a.B <= 16 ? 16 : 32;                        // sequences per pass over the centroids
+        int kc = (49152 / (2 * nbp)) & ~255;                        // h slices of a chunk fit in 48 KB of LDS
+        if (kc > a.d) kc = (a.d + 7) & ~7;
+        dim3 grid((a.C + 3) / 4, (a.B + nbp - 1) / nbp);
+        const size_t lds = (size_t)nbp * kc * 2;
+        switch (nbp) {
+            case 16: bound_batched_kernel<16><<<grid, 256, lds, st>>>(a, U, hn, reset, kc); break;
+            default: bound_batched_kernel<32><<<grid, 256, lds, st>>>(a, U, hn, reset, kc); break;
+        }
+        CSV_LAUNCH_CHECK("bound_batched_kernel");
+        return CSV_OK;
+    }
     int bt = 1;
     while (bt < a.B && bt < 8) bt <<= 1;
     while (bt > 1 && (size_t)bt * a.d * 2 > 65536) bt >>= 1;
@@ -1272,6 +1585,13 @@ static int launch_full(const csv_index* idx, const uint16_t* d_h, const int32_t*
     FullArgs f;
     f.V = idx->V; f.d = idx->d; f.Wp = idx->Wp; f.bp = idx->bp; f.perm = idx->perm; f.h = d_h;
     f.list = list; f.n_ptr = n_ptr; f.n_fixed = n_fixed; f.out = out; f.out_stride = stride; f.scatter = scatter;
+    if (!n_ptr && n_fixed > FULL_G) {
+        const int wtiles = (idx->V + 31) / 32;          // 32 rows per wave, 4 waves per block
+        const int grid = (wtiles + 3) / 4 < 2048 ? (wtiles + 3) / 4 : 2048;
+        full_mfma_kernel<<<grid, 256, 0, st>>>(f);
+        CSV_LAUNCH_CHECK("full_mfma_kernel");
+        return CSV_OK;
+    }
     const int ntiles = (idx->V + 7) / 8;
     const int grid = ntiles < 2048 ? ntiles : 2048;
     full_gemv_kernel<<<grid, 256, (size_t)FULL_G * idx->d * 2, st>>>(f);
@@ -1291,7 +1611,9 @@ extern "C" int csv_workspace_create(const csv_index* idx, int B_max, int K_cap_r
     ws->Npad = next_pow2(idx->C);
     ws->n_chunks = (idx->V + FB_CHUNK - 1) / FB_CHUNK;
     ws->device = idx->device;
-    const size_t B = B_max, C = idx->C, V = idx->V, K = ws->K_cap, NC = ws->n_chunks;
+    ws->sp_chunks = (ws->K_cap + STAGE_CAP - 1) / STAGE_CAP;
+    ws->cand_chunks = ws->n_chunks > ws->sp_chunks ? ws->n_chunks : ws->sp_chunks;
+    const size_t B = B_max, C = idx->C, V = idx->V, K = ws->K_cap, NC = ws->cand_chunks;
     ws->tile_stride = (int)(K / TILE_ROWS + C + 1);
     const size_t tcap = B * (size_t)ws->tile_stride;
     hipError_t e = hipSuccess;
@@ -1417,7 +1739,7 @@ extern "C" int csv_decode_step(csv_workspace* ws, const csv_index* idx, const ui
     gemv_tiles_kernel<<<gg, 256, hl, st>>>(a, 0);
     CSV_LAUNCH_CHECK("gemv_tiles_kernel");
     CSV_MARK(3);
-    cert_kernel<<<B, SEQ_THREADS, cert_lds(ws), st>>>(a, 0);
+    cert_kernel<<<dim3(B, ws->sp_chunks), SEQ_THREADS, cert_lds(ws), st>>>(a, 0);
     CSV_LAUNCH_CHECK("cert_kernel");
     CSV_MARK(4);
     {
