@@ -39,6 +39,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", default="c2")
     ap.add_argument("--cpu-steps", type=int, default=-1, help="oracle steps to time (-1: sized to ~15 s, 0: skip)")
+    ap.add_argument("--traffic-probe", action="store_true",
+                    help="for `rocprofv3 --pmc FETCH_SIZE|WRITE_SIZE`: launch a device-to-device copy of known size, "
+                         "the bound kernel and a few whole steps, then exit (no timing, no JSON)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the path shards by cluster, see DESIGN.md); use --gpus 1",
@@ -72,6 +75,24 @@ def main() -> int:
     def run(n, first=0):
         for s in range(first, first + n):
             csv.csv_decode_step_raw(ws, idx, hp[s], r.B, buf, sp)
+
+    if args.traffic_probe:
+        # calibration: a plain copy of 256 MiB reads 256 MiB and writes 256 MiB
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").random_(0, 255)
+        dst = torch.empty_like(src)
+        U_out = torch.empty((r.B, r.C), dtype=torch.float32, device="cuda")
+        hn_out = torch.empty(r.B, dtype=torch.float32, device="cuda")
+        full_out = torch.empty((r.B, r.V), dtype=torch.float32, device="cuda")
+        for s in range(8):
+            dst.copy_(src)
+        for s in range(32):
+            csv.lib.csv_bounds(ws._h, idx._h, hp[s], r.B, U_out.data_ptr(), hn_out.data_ptr(), sp)
+        run(32)
+        for s in range(4):
+            csv.csv_full_logits(ws, idx, dh[s % nh], out=full_out)
+        torch.cuda.synchronize()
+        log("[bench] traffic probe done: 8 copies of 256 MiB, 32 bound launches, 32 steps, 4 full products")
+        return 0
 
     # ---------------- timed region: W warm-up steps, then exactly K steps, sync on both sides
     run(W)
@@ -169,6 +190,14 @@ def main() -> int:
     torch.cuda.synchronize()
     dom_us = ev0.elapsed_time(ev1) * 1e3 / nrep
     achieved = dom_bytes / (dom_us * 1e-6) / 1e9
+    # measured HBM bytes per launch of that kernel: taken from the committed rocprofv3 --pmc summary of this workload
+    traffic = None
+    tfile = os.path.join(ROOT, "profiles", f"decode_step_{r.name}_hbm_traffic.txt")
+    if os.path.exists(tfile):
+        for line in open(tfile):
+            f = line.split()
+            if len(f) == 3 and f[0] == "traffic_bytes_per_launch" and dom_name.startswith(f[1]):
+                traffic = int(f[2])
     bstep = step_bytes(r, r.C, rows_union_sum / nstat, anyfb / nstat, r.k)
     eff_gbs = bstep / (ms_per_step * 1e-3) / 1e9
 
@@ -203,7 +232,7 @@ def main() -> int:
         "config": {"workload": f"{r.name}: V={r.V} d={r.d} C={r.C} B={r.B} k={r.k} eps={r.eps:g} K_max={r.K_max_rows} "
                                f"combine=ALL, bf16 W and h, planted clusters", "batch": r.B},
         "roofline": {"bound": "hbm", "kernel": dom_name, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "bytes_per_launch": dom_bytes, "avg_launch_us": dom_us},
         "cpu_baseline": cpu,
         "effective_hbm_GBps": eff_gbs, "algorithmic_bytes_per_step": bstep,
