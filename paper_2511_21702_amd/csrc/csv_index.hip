@@ -328,6 +328,11 @@ extern "C" int csv_build_index(const uint16_t* d_W, const float* d_b, int V, int
         if (last) break;
         if ((rc = assign())) return fail(rc);
     }
+    {
+        int nmax = 1;
+        for (int c = 0; c < C; ++c) nmax = n[c] > nmax ? n[c] : nmax;
+        x->ln_nmax = (float)log((double)nmax);
+    }
     radius_kernel<<<C, 256, 0, st>>>(x->Wp, x->bp, x->off, x->mu, d, (double)o->radius_slack, x->R, x->bmax, x->lnn);
     if (hipGetLastError() != hipSuccess) { csv_set_error("launch of radius_kernel failed"); return fail(CSV_EHIP); }
     if (hipStreamSynchronize(st) != hipSuccess) { csv_set_error("index build failed on the device: %s", hipGetErrorString(hipGetLastError())); return fail(CSV_EHIP); }
@@ -361,6 +366,11 @@ extern "C" int csv_index_from_arrays(const uint16_t* d_W, const float* d_b, int 
     rc = csv_index_alloc(V, d, C, &x);
     if (rc) return rc;
     auto fail = [&](int code) { csv_index_free(x); return code; };
+    {
+        int nmax = 1;
+        for (int c = 0; c < C; ++c) nmax = n[c] > nmax ? n[c] : nmax;
+        x->ln_nmax = (float)log((double)nmax);
+    }
     hipError_t e = hipMemcpyAsync(x->mu, h_mu, (size_t)C * d * 4, hipMemcpyHostToDevice, st);
     if (e == hipSuccess) e = hipMemcpyAsync(x->R, h_R, (size_t)C * 4, hipMemcpyHostToDevice, st);
     if (e == hipSuccess) e = hipMemcpyAsync(x->bmax, h_bmax, (size_t)C * 4, hipMemcpyHostToDevice, st);

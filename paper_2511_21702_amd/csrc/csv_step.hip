@@ -15,6 +15,7 @@
 
 #include <math.h>
 #include <stdarg.h>
+#include <stdlib.h>
 #include <string.h>
 
 // ------------------------------------------------------------------------------------------------ errors
@@ -39,6 +40,7 @@ struct StepArgs {
     const int32_t* n;
     const int32_t* off;
     const float* lnn;
+    float ln_nmax;
     int B, K_cap, Npad, n_chunks, tile_stride;
     int sp_chunks;     // most STAGE_CAP-sized chunks a sequence's scored rows can span
     int cand_chunks;   // chunk stride of the candidate buffers
@@ -388,13 +390,28 @@ __device__ __forceinline__ ClusterLds carve_clusters(u64* arena, int Npad, int C
     return L;
 }
 __device__ __forceinline__ void load_clusters(const StepArgs& a, int b, const ClusterLds& L) {
-    for (int c = threadIdx.x; c <= a.C; c += blockDim.x) L.offl[c] = a.off[c];
-    for (int c = threadIdx.x; c < a.C; c += blockDim.x) {
-        const float u = a.U[(size_t)b * a.C + c];
-        const int n = a.n[c];
-        const float ln = a.lnn[c];
-        L.keys[c] = n > 0 ? ckey(u, c) : 0ull;
-        L.vl[c] = n > 0 ? ln + u : -INFINITY;
+    const int tid = threadIdx.x, nt = blockDim.x;
+    for (int c = tid; c <= a.C; c += nt) L.offl[c] = a.off[c];
+    // four clusters per thread and trip, all twelve loads issued before the first use
+    for (int c0 = 0; c0 < a.C; c0 += 4 * nt) {
+        float u[4], ln[4];
+        int n[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int c = c0 + q * nt + tid;
+            const bool in = c < a.C;
+            u[q] = in ? a.U[(size_t)b * a.C + c] : 0.f;
+            n[q] = in ? a.n[c] : 0;
+            ln[q] = in ? a.lnn[c] : 0.f;
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int c = c0 + q * nt + tid;
+            if (c < a.C) {
+                L.keys[c] = n[q] > 0 ? ckey(u[q], c) : 0ull;
+                L.vl[c] = n[q] > 0 ? ln[q] + u[q] : -INFINITY;
+            }
+        }
     }
 }
 
@@ -536,7 +553,7 @@ __device__ __forceinline__ void tail_stats(const StepArgs& a, const ClusterLds& 
 // ================================================================================================ seed (round 0)
 // One block per sequence.  The seed prefix is found by repeated block-wide arg-max over the keys (it is a
 // handful of clusters), not by sorting.
-__global__ __launch_bounds__(SEQ_THREADS) void seed_kernel(StepArgs a) {
+__global__ __launch_bounds__(1024) void seed_kernel(StepArgs a) {
     extern __shared__ u64 arena[];
     __shared__ SeqShared s;
     const int b = blockIdx.x, tid = threadIdx.x, nt = blockDim.x, C = a.C;
@@ -551,26 +568,42 @@ __global__ __launch_bounds__(SEQ_THREADS) void seed_kernel(StepArgs a) {
     }
     __syncthreads();
     DBG_T(1);
+    // Open clusters one at a time by block-wide arg-max until max(k,1) rows are open; the tiles of each winner are
+    // written at once (positions in bound order), so no compaction pass is needed here.
     const int need = max(a.k, 1);
-    int rows = 0, m0 = 0;
-    u64 kappa = ~0ull;
-    while (rows < need) {
+    int rows = 0, m0 = 0, ntile = 0;
+    u64 kappa = ~0ull, nxt = 0;
+    Tile* tl = a.tiles[0] + (size_t)b * a.tile_stride;
+    bool over = false;
+    while (true) {
         u64 best = 0;
         for (int c = tid; c < C; c += nt) {
             const u64 kx = L.keys[c];
             if (kx < kappa && kx > best) best = kx;
         }
         best = block_max_u64(best, s.redu);
-        if (best == 0) break;   // no cluster left (cannot happen while k <= V)
+        if (rows >= need || best == 0) {   // best is now the largest unopened key (0: none left)
+            nxt = best;
+            break;
+        }
         const int cw = (int)(0xFFFFFFFFu - (uint32_t)best);
-        rows += L.offl[cw + 1] - L.offl[cw];
+        const int r0 = L.offl[cw], n = L.offl[cw + 1] - r0;
+        over = over || rows + n > a.K_max;
+        if (!over) {
+            const int ntc = (n + TILE_ROWS - 1) / TILE_ROWS;
+            for (int t = tid; t < ntc; t += nt) {
+                Tile x;
+                x.b = b; x.row0 = r0 + t * TILE_ROWS; x.nrows = min(TILE_ROWS, n - t * TILE_ROWS); x.pos = rows + t * TILE_ROWS;
+                tl[ntile + t] = x;
+            }
+            if (tid == 0) a.sel[(size_t)b * C + m0] = cw;
+            ntile += ntc;
+        }
+        rows += n;
         m0 += 1;
         kappa = best;
     }
     DBG_T(2);
-    float nxtU, T0;
-    tail_stats(a, L, kappa, s, nxtU, T0);
-    DBG_T(3);
     if (rows > a.K_max) {
         if (tid == 0) {
             a.st[b].n_open = m0;
@@ -579,9 +612,23 @@ __global__ __launch_bounds__(SEQ_THREADS) void seed_kernel(StepArgs a) {
         }
         return;
     }
-    emit_clusters(a, b, 0, 0, 0, [&](int c) { return L.keys[c] >= kappa; }, L, s);
+    // log tail mass of the unopened clusters, shifted by an upper bound of its largest term
+    const float nxtU = nxt ? ckey_bound(nxt) : -INFINITY;
+    float T0 = -INFINITY;
+    if (nxt) {
+        const float shift = a.ln_nmax + nxtU;
+        float sum = 0.f;
+        for (int c = tid; c < C; c += nt) {
+            const u64 kx = L.keys[c];
+            if (kx != 0 && kx < kappa) sum += expf(L.vl[c] - shift);
+        }
+        sum = block_sum(sum, s.redf);
+        T0 = shift + logf(sum);
+    }
+    DBG_T(3);
     DBG_T(4);
     if (tid == 0) {
+        a.counters[CNT_TILES + b] = ntile;
         SeqState st;
         st.status = ST_ACTIVE; st.n_open = m0; st.n_rows = rows; st.rounds = 0; st.kappa = kappa; st.nxtU = nxtU; st.T = T0;
         st.fb_slot = -1; st.pad[0] = st.pad[1] = st.pad[2] = 0;
@@ -1527,7 +1574,7 @@ static void fill_args(StepArgs& a, const csv_workspace* ws, const csv_index* idx
     memset(&a, 0, sizeof(a));
     a.V = idx->V; a.d = idx->d; a.C = idx->C;
     a.Wp = idx->Wp; a.bp = idx->bp; a.perm = idx->perm; a.mu = idx->mu; a.R = idx->R; a.bmax = idx->bmax;
-    a.n = idx->n; a.off = idx->off; a.lnn = idx->lnn;
+    a.n = idx->n; a.off = idx->off; a.lnn = idx->lnn; a.ln_nmax = idx->ln_nmax;
     a.K_cap = ws->K_cap; a.Npad = ws->Npad; a.n_chunks = ws->n_chunks; a.tile_stride = ws->tile_stride; a.sp_chunks = ws->sp_chunks; a.cand_chunks = ws->cand_chunks;
     a.U = ws->U; a.hnorm = ws->hnorm; a.st = ws->st; a.sel = ws->sel; a.slog = ws->slog; a.sid = ws->sid;
     a.tiles[0] = ws->tiles[0]; a.tiles[1] = ws->tiles[1]; a.counters = ws->counters;
@@ -1574,6 +1621,7 @@ static int launch_bounds_kernel(const StepArgs& a, float* U, float* hn, int rese
 }
 
 // dynamic LDS of the per-sequence kernels
+static int seed_threads(const csv_workspace*) { return SEQ_THREADS; }
 static size_t seed_lds(const csv_workspace* ws) { return (size_t)ws->Npad * 8 + (size_t)ws->C * 8 + 8; }
 static size_t cert_lds(const csv_workspace* ws) {
     const size_t plan = seed_lds(ws), stage = (size_t)STAGE_CAP * 8;
@@ -1730,7 +1778,7 @@ extern "C" int csv_decode_step(csv_workspace* ws, const csv_index* idx, const ui
     rc = launch_bounds_kernel(a, ws->U, ws->hnorm, 1, st);
     if (rc) return rc;
     CSV_MARK(1);
-    seed_kernel<<<B, SEQ_THREADS, seed_lds(ws), st>>>(a);
+    seed_kernel<<<B, seed_threads(ws), seed_lds(ws), st>>>(a);
     CSV_LAUNCH_CHECK("seed_kernel");
     CSV_MARK(2);
     long long want = ((long long)ws->K_cap / TILE_ROWS + 1) * B;
