@@ -61,6 +61,7 @@ struct csv_workspace {
     size_t tail_lds;                   // its dynamic LDS
     int device;
     float* U;          // [B*C]      cluster bounds
+    float* bound_partial; // K-slice partial sums of the batched (MFMA) bound product
     float* hnorm;      // [B]
     SeqState* st;      // [B]
     int32_t* sel;      // [B*C]      opened cluster ids

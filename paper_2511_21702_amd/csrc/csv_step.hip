@@ -46,6 +46,7 @@ struct StepArgs {
     int cand_chunks;   // chunk stride of the candidate buffers
     float* U;
     float* hnorm;
+    float* bound_partial;   // [BOUND_KS_MAX * B * C] K-slice partial sums of the batched bound product
     SeqState* st;
     int32_t* sel;
     float* slog;
@@ -178,107 +179,126 @@ __global__ __launch_bounds__(256) void bound_kernel(StepArgs a, float* __restric
     }
 }
 
-// Bounds for larger batches: every sequence of the pass meets each centroid row exactly once.  K is walked in
-// chunks whose h slices (all NB sequences, bf16) fit in LDS; a lane keeps NB accumulators.  The kernel turns
-// ALU-bound near NB = 32 (about 8 vector instructions per sequence and 16 centroid bytes), which is still several
-// times faster than re-reading the centroids once per group of 8 sequences.
-#define BATCH_MAXQ 6
-template <int NB>
-__global__ __launch_bounds__(256) void bound_batched_kernel(StepArgs a, float* __restrict__ U_out, float* __restrict__ hn_out,
-                                                            int reset_counters, int kc) {
-    extern __shared__ uint4 hs4[];            // [NB][kc] bf16
-    __shared__ float hn[NB];
+// Bounds for larger batches (B > 8): [C x d] fp32 centroids times [d x B] bf16 hidden states is a dense contraction,
+// done with v_mfma_f32_16x16x32_bf16.  A float32 centroid value is split exactly into three bf16 pieces
+// (x = hi + mid + lo, 8 mantissa bits each), so three MFMAs per k-block give the float32-exact products with float32
+// accumulation; the split costs a handful of vector instructions per value, independent of B.
+// A wave owns 16 clusters and one slice of K; lane (li, g) feeds cluster/sequence li with the eight k values
+// 32 kb + 8 g.  Partial sums of the K slices go to P[slice][sequence][cluster]; bound_finish_kernel adds them in a
+// fixed order together with R_c ||h|| + bmax_c, so the result does not depend on scheduling.
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4_t;
+
+__device__ __forceinline__ void split3_bf16(const float4& x0, const float4& x1, uint4& hi, uint4& mid, uint4& lo) {
+    const float v[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
+    uint32_t h[8], m[8], l[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        h[i] = __float_as_uint(v[i]) & 0xffff0000u;
+        const float r1 = v[i] - __uint_as_float(h[i]);
+        m[i] = __float_as_uint(r1) & 0xffff0000u;
+        const float r2 = r1 - __uint_as_float(m[i]);
+        l[i] = __float_as_uint(r2) & 0xffff0000u;
+    }
+    hi = make_uint4((h[0] >> 16) | h[1], (h[2] >> 16) | h[3], (h[4] >> 16) | h[5], (h[6] >> 16) | h[7]);
+    mid = make_uint4((m[0] >> 16) | m[1], (m[2] >> 16) | m[3], (m[4] >> 16) | m[5], (m[6] >> 16) | m[7]);
+    lo = make_uint4((l[0] >> 16) | l[1], (l[2] >> 16) | l[3], (l[4] >> 16) | l[5], (l[6] >> 16) | l[7]);
+}
+
+#define BOUND_KS_PER_BLOCK 8
+#define BOUND_KS_MAX 32
+#define BOUND_KB_UNROLL 4      // k-blocks (of 32) whose loads are issued together
+template <int NT>
+__global__ __launch_bounds__(512) void bound_mfma_kernel(StepArgs a, float* __restrict__ P, int seq0, int KS, int kb_per_slice,
+                                                         int reset_counters) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int b0 = blockIdx.y * NB;
-    const int nb = min(NB, a.B - b0);
-    const int c = blockIdx.x * 4 + wave;
-    const bool valid = c < a.C;
-    const float4* mrow = reinterpret_cast<const float4*>(a.mu + (size_t)(valid ? c : 0) * a.d);
-    const int nch = a.d >> 3;                 // 16-byte chunks per h row
-    const int kq = kc >> 2, kch = kc >> 3;    // float4 / uint4 per chunk row
+    const int li = lane & 15, g = lane >> 4;
     if (reset_counters && blockIdx.x == 0 && blockIdx.y == 0)
-        for (int i = tid; i < CNT_TOTAL; i += 256) a.counters[i] = 0;
-    float acc[NB];
-    float nrm[(NB + 3) / 4];
+        for (int i = tid; i < CNT_TOTAL; i += 512) a.counters[i] = 0;
+    const int ks = blockIdx.y * BOUND_KS_PER_BLOCK + wave;
+    if (ks >= KS) return;
+    const int c0 = blockIdx.x * 16;
+    const float4* ap = reinterpret_cast<const float4*>(a.mu + (size_t)min(c0 + li, a.C - 1) * a.d);
+    const uint4* hp[NT];
+    bool hv[NT];
 #pragma unroll
-    for (int s = 0; s < NB; ++s) acc[s] = 0.f;
+    for (int t = 0; t < NT; ++t) {
+        const int sq = seq0 + t * 16 + li;
+        hv[t] = sq < a.B;
+        hp[t] = reinterpret_cast<const uint4*>(a.h) + (size_t)(hv[t] ? sq : 0) * (a.d >> 3);
+    }
+    floatx4_t acc[NT];
 #pragma unroll
-    for (int j = 0; j < (NB + 3) / 4; ++j) nrm[j] = 0.f;
-    const uint2* hs2 = reinterpret_cast<const uint2*>(hs4);
-    // the lane's centroid values of a chunk are requested one chunk ahead (BATCH_MAXQ float4 cover kc <= 1536)
-    float4 cur[BATCH_MAXQ], nxt[BATCH_MAXQ];
-    auto fetch = [&](float4* dst, int k0) {
-        const int nq = min(kc, a.d - k0) >> 2;
-        const float4* mp = mrow + (k0 >> 2);
+    for (int t = 0; t < NT; ++t) acc[t] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+    const int nkb = (a.d + 31) >> 5;
+    const int kb0 = ks * kb_per_slice, kb1 = min(nkb, kb0 + kb_per_slice);
+    const uint4 zero = make_uint4(0, 0, 0, 0);
+    const float4 fzero = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int kb = kb0; kb < kb1; kb += BOUND_KB_UNROLL) {
+        float4 x[BOUND_KB_UNROLL][2];
+        uint4 hb[BOUND_KB_UNROLL][NT];
 #pragma unroll
-        for (int j = 0; j < BATCH_MAXQ; ++j) {
-            const int i = lane + 64 * j;
-            dst[j] = (valid && k0 < a.d && i < nq) ? mp[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int u = 0; u < BOUND_KB_UNROLL; ++u) {
+            const int k = (kb + u) * 32 + g * 8;
+            const bool ok = kb + u < kb1 && k < a.d;       // d is a multiple of 8: the eight values are all in or all out
+            x[u][0] = ok ? ap[k >> 2] : fzero;
+            x[u][1] = ok ? ap[(k >> 2) + 1] : fzero;
+#pragma unroll
+            for (int t = 0; t < NT; ++t) hb[u][t] = (ok && hv[t]) ? hp[t][k >> 3] : zero;
         }
-    };
-    fetch(cur, 0);
-    for (int k0 = 0; k0 < a.d; k0 += kc) {
-        const int kn = min(kc, a.d - k0);     // multiple of 8
-        __syncthreads();
-        for (int i = tid; i < NB * kch; i += 256) {
-            const int s = i / kch, j = i - s * kch;
-            hs4[i] = (s < nb && j * 8 < kn) ? (reinterpret_cast<const uint4*>(a.h) + (size_t)(b0 + s) * nch)[(k0 >> 3) + j]
-                                           : make_uint4(0, 0, 0, 0);
-        }
-        fetch(nxt, k0 + kc);
-        __syncthreads();
-        // squared norms: wave w owns sequences w, w+4, ...
 #pragma unroll
-        for (int j = 0; j < (NB + 3) / 4; ++j) {
-            const int sq = wave + 4 * j;
-            if (sq < NB) {
-                float p = 0.f;
-                for (int i = lane; i < kch; i += 64) {
-                    const uint4 v = hs4[sq * kch + i];
-                    p = dot8_bf16(v, v, p);
-                }
-                nrm[j] += p;
+        for (int u = 0; u < BOUND_KB_UNROLL; ++u) {
+            uint4 hi, mid, lo;
+            split3_bf16(x[u][0], x[u][1], hi, mid, lo);
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                const bf16x8_t bv = __builtin_bit_cast(bf16x8_t, hb[u][t]);
+                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, hi), bv, acc[t], 0, 0, 0);
+                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, mid), bv, acc[t], 0, 0, 0);
+                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, lo), bv, acc[t], 0, 0, 0);
             }
         }
-        if (valid) {
-            const int nq = kn >> 2;
+    }
+    // accumulator register r of lane (li, g) is  [cluster 4g + r][sequence li]
 #pragma unroll
-            for (int j = 0; j < BATCH_MAXQ; ++j) {
-                const int i = lane + 64 * j;
-                if (i < nq) {
-                    const float4 m = cur[j];
+    for (int t = 0; t < NT; ++t) {
+        const int sq = seq0 + t * 16 + li;
+        if (sq < a.B) {
 #pragma unroll
-                    for (int s = 0; s < NB; ++s) {
-                        const uint2 hv = hs2[s * kq + i];
-                        acc[s] = fmaf(m.x, bf16_lo(hv.x), acc[s]);
-                        acc[s] = fmaf(m.y, bf16_hi(hv.x), acc[s]);
-                        acc[s] = fmaf(m.z, bf16_lo(hv.y), acc[s]);
-                        acc[s] = fmaf(m.w, bf16_hi(hv.y), acc[s]);
-                    }
-                }
+            for (int r = 0; r < 4; ++r) {
+                const int c = c0 + 4 * g + r;
+                if (c < a.C) P[((size_t)ks * a.B + sq) * a.C + c] = acc[t][r];
             }
         }
-#pragma unroll
-        for (int j = 0; j < BATCH_MAXQ; ++j) cur[j] = nxt[j];
     }
+}
+
+// Block (x, b): ||h_b|| (every block of the sequence recomputes it: d values), then for 256 clusters
+// U[b,c] = sum of the K-slice partials (ascending slice) + R_c ||h_b|| + bmax_c.
+__global__ __launch_bounds__(256) void bound_finish_kernel(StepArgs a, const float* __restrict__ P, int KS,
+                                                           float* __restrict__ U_out, float* __restrict__ hn_out) {
+    __shared__ float red[16];
+    const int b = blockIdx.y, tid = threadIdx.x;
+    const int c = blockIdx.x * 256 + tid;
+    const bool in = c < a.C;
+    float part[BOUND_KS_MAX];
 #pragma unroll
-    for (int j = 0; j < (NB + 3) / 4; ++j) {
-        const int sq = wave + 4 * j;
-        const float t = wave_sum(nrm[j]);
-        if (sq < NB && lane == 0) hn[sq] = sqrtf(t);
+    for (int ks = 0; ks < BOUND_KS_MAX; ++ks) part[ks] = (in && ks < KS) ? P[((size_t)ks * a.B + b) * a.C + c] : 0.f;
+    const float Rc = in ? a.R[c] : 0.f, bm = in ? a.bmax[c] : 0.f;
+    const int nc = in ? a.n[c] : 0;
+    const uint4* hsrc = reinterpret_cast<const uint4*>(a.h) + (size_t)b * (a.d >> 3);
+    float ss = 0.f;
+    for (int i = tid; i < (a.d >> 3); i += 256) {
+        const uint4 v = hsrc[i];
+        ss = dot8_bf16(v, v, ss);
     }
-    __syncthreads();
-    if (blockIdx.x == 0 && tid < nb && hn_out) hn_out[b0 + tid] = hn[tid];
-    if (!valid) return;
+    const float hn = sqrtf(block_sum(ss, red));
+    if (blockIdx.x == 0 && tid == 0 && hn_out) hn_out[b] = hn;
+    if (!in) return;
+    float u = 0.f;
 #pragma unroll
-    for (int s = 0; s < NB; ++s) acc[s] = wave_sum(acc[s]);
-    if (lane == 0) {
-        const float Rc = a.R[c], bm = a.bmax[c];
-        const bool empty = a.n[c] == 0;
-#pragma unroll
-        for (int s = 0; s < NB; ++s)
-            if (s < nb) U_out[(size_t)(b0 + s) * a.C + c] = empty ? -INFINITY : (acc[s] + Rc * hn[s] + bm);
-    }
+    for (int ks = 0; ks < BOUND_KS_MAX; ++ks) u += part[ks];
+    U_out[(size_t)b * a.C + c] = nc == 0 ? -INFINITY : (u + Rc * hn + bm);
 }
 
 // ================================================================================================ block scans
@@ -1317,9 +1337,6 @@ __global__ __launch_bounds__(256) void full_gemv_kernel(FullArgs f) {
 // 64 contiguous bytes from each of 16 rows.  Both operands go straight from global memory to registers (h rows are L2-resident);
 // the kernel is HBM-bound, so the loads of one wave are hidden by the other waves of the SIMD rather than by
 // double buffering (which would cost the registers that keep four waves per SIMD resident).  Accumulator register r of lane (li, g) is  out[row 4g + r][sequence li].
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
-typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4_t;
-
 template <int MT, int NT>
 __device__ __forceinline__ void full_mfma_device(const FullArgs& f, int n, int seq0, int block, int nblocks) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nw = blockDim.x >> 6;
@@ -1576,7 +1593,7 @@ static void fill_args(StepArgs& a, const csv_workspace* ws, const csv_index* idx
     a.Wp = idx->Wp; a.bp = idx->bp; a.perm = idx->perm; a.mu = idx->mu; a.R = idx->R; a.bmax = idx->bmax;
     a.n = idx->n; a.off = idx->off; a.lnn = idx->lnn; a.ln_nmax = idx->ln_nmax;
     a.K_cap = ws->K_cap; a.Npad = ws->Npad; a.n_chunks = ws->n_chunks; a.tile_stride = ws->tile_stride; a.sp_chunks = ws->sp_chunks; a.cand_chunks = ws->cand_chunks;
-    a.U = ws->U; a.hnorm = ws->hnorm; a.st = ws->st; a.sel = ws->sel; a.slog = ws->slog; a.sid = ws->sid;
+    a.U = ws->U; a.hnorm = ws->hnorm; a.bound_partial = ws->bound_partial; a.st = ws->st; a.sel = ws->sel; a.slog = ws->slog; a.sid = ws->sid;
     a.tiles[0] = ws->tiles[0]; a.tiles[1] = ws->tiles[1]; a.counters = ws->counters;
     a.fb_list = ws->fb_list; a.fb_logits = ws->fb_logits; a.cand_val = ws->cand_val; a.cand_id = ws->cand_id;
     a.cand_max = ws->cand_max; a.cand_sum = ws->cand_sum;
@@ -1591,16 +1608,25 @@ static int check_pair(const csv_workspace* ws, const csv_index* idx, const void*
 
 static int launch_bounds_kernel(const StepArgs& a, float* U, float* hn, int reset, hipStream_t st) {
     if (a.B > 8) {
-        const int nbp = a.B <= 16 ? 16 : 32;                        // sequences per pass over the centroids
-        int kc = (49152 / (2 * nbp)) & ~255;                        // h slices of a chunk fit in 48 KB of LDS
-        if (kc > a.d) kc = (a.d + 7) & ~7;
-        dim3 grid((a.C + 3) / 4, (a.B + nbp - 1) / nbp);
-        const size_t lds = (size_t)nbp * kc * 2;
-        switch (nbp) {
-            case 16: bound_batched_kernel<16><<<grid, 256, lds, st>>>(a, U, hn, reset, kc); break;
-            default: bound_batched_kernel<32><<<grid, 256, lds, st>>>(a, U, hn, reset, kc); break;
+        // enough K slices that (cluster tiles x slices) fills the device; at most BOUND_KS_MAX (size of the partial buffer)
+        const int tiles = (a.C + 15) / 16, nkb = (a.d + 31) / 32;
+        int KS = (2048 + tiles - 1) / tiles;
+        KS = ((KS + BOUND_KS_PER_BLOCK - 1) / BOUND_KS_PER_BLOCK) * BOUND_KS_PER_BLOCK;
+        if (KS > BOUND_KS_MAX) KS = BOUND_KS_MAX;
+        int kbs = (nkb + KS - 1) / KS;
+        kbs = (kbs + BOUND_KB_UNROLL - 1) / BOUND_KB_UNROLL * BOUND_KB_UNROLL;   // whole trips of the k loop
+        KS = (nkb + kbs - 1) / kbs;
+        dim3 grid(tiles, (KS + BOUND_KS_PER_BLOCK - 1) / BOUND_KS_PER_BLOCK);
+        for (int s0 = 0; s0 < a.B; s0 += 64) {
+            const int nseq = a.B - s0 < 64 ? a.B - s0 : 64;
+            const int r = reset && s0 == 0;
+            if (nseq <= 16) bound_mfma_kernel<1><<<grid, 512, 0, st>>>(a, a.bound_partial, s0, KS, kbs, r);
+            else if (nseq <= 32) bound_mfma_kernel<2><<<grid, 512, 0, st>>>(a, a.bound_partial, s0, KS, kbs, r);
+            else bound_mfma_kernel<4><<<grid, 512, 0, st>>>(a, a.bound_partial, s0, KS, kbs, r);
+            CSV_LAUNCH_CHECK("bound_mfma_kernel");
         }
-        CSV_LAUNCH_CHECK("bound_batched_kernel");
+        bound_finish_kernel<<<dim3((a.C + 255) / 256, a.B), 256, 0, st>>>(a, a.bound_partial, KS, U, hn);
+        CSV_LAUNCH_CHECK("bound_finish_kernel");
         return CSV_OK;
     }
     int bt = 1;
@@ -1666,7 +1692,7 @@ extern "C" int csv_workspace_create(const csv_index* idx, int B_max, int K_cap_r
     const size_t tcap = B * (size_t)ws->tile_stride;
     hipError_t e = hipSuccess;
     auto A = [&](void** p, size_t bytes) { if (e == hipSuccess) e = hipMalloc(p, bytes ? bytes : 16); };
-    A((void**)&ws->U, B * C * 4); A((void**)&ws->hnorm, B * 4); A((void**)&ws->st, B * sizeof(SeqState));
+    A((void**)&ws->U, B * C * 4); A((void**)&ws->bound_partial, B_max > 8 ? B * C * 4 * BOUND_KS_MAX : 16); A((void**)&ws->hnorm, B * 4); A((void**)&ws->st, B * sizeof(SeqState));
     A((void**)&ws->sel, B * C * 4); A((void**)&ws->slog, B * K * 4); A((void**)&ws->sid, B * K * 4);
     A((void**)&ws->tiles[0], tcap * sizeof(Tile)); A((void**)&ws->tiles[1], tcap * sizeof(Tile));
     A((void**)&ws->counters, CNT_TOTAL * 4); A((void**)&ws->fb_list, B * 4); A((void**)&ws->all_list, B * 4);
@@ -1717,7 +1743,7 @@ extern "C" int csv_workspace_create(const csv_index* idx, int B_max, int K_cap_r
 
 extern "C" void csv_workspace_free(csv_workspace* ws) {
     if (!ws) return;
-    void* ptrs[] = {ws->U, ws->hnorm, ws->st, ws->sel, ws->slog, ws->sid, ws->tiles[0], ws->tiles[1],
+    void* ptrs[] = {ws->U, ws->bound_partial, ws->hnorm, ws->st, ws->sel, ws->slog, ws->sid, ws->tiles[0], ws->tiles[1],
                     ws->counters, ws->fb_list, ws->all_list, ws->fb_logits, ws->cand_val, ws->cand_id, ws->cand_max, ws->cand_sum};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
