@@ -1729,8 +1729,10 @@ extern "C" int csv_workspace_create(const csv_index* idx, int B_max, int K_cap_r
             csv_workspace_free(ws);
             return CSV_ESHAPE;
         }
-        // all blocks of the tail kernel must be resident together: never more than the device holds at once
-        ws->tail_grid = (per_cu > 2 ? 2 : per_cu) * cus;
+        // All blocks of the tail kernel must be resident together, which the occupancy check above guarantees
+        // for one block per compute unit.  A second block per unit measured slower at every batch size: the
+        // grid barriers cost more with twice the arrivals, and the row loops already keep enough loads in flight.
+        ws->tail_grid = cus;
     }
     if (e != hipSuccess) {
         csv_set_error("workspace allocation failed: %s", hipGetErrorString(e));
