@@ -153,11 +153,12 @@ int csv_full_logits(csv_workspace* ws, const csv_index* idx, const uint16_t* d_h
  * each following csv_decode_step on this workspace records CSV_PROFILE_STAGES+1 events (steps beyond max_steps
  * are not recorded).  csv_profile_end synchronises, writes the summed milliseconds of every stage to
  * h_stage_ms[CSV_PROFILE_STAGES] and the number of recorded steps to *h_steps, frees the events and switches
- * recording off.  Stage order: bounds, seed selection, gathered GEMV (round 0), certification (round 0), and the
- * tail (round-1 GEMV and certification, full-vocabulary product and top-k for fallback sequences; one kernel).
+ * recording off.  Stage order: bounds; round 0 (seed selection, gathered GEMV over the seed prefix and its
+ * certification; one kernel); the tail (round-1 GEMV and certification, full-vocabulary product and top-k for
+ * fallback sequences; one kernel).
  * A stage's time runs from the end of the previous stage to its own end, so it includes its launch gap.
  */
-#define CSV_PROFILE_STAGES 5
+#define CSV_PROFILE_STAGES 3
 int csv_profile_begin(csv_workspace* ws, int max_steps);
 int csv_profile_end(csv_workspace* ws, float* h_stage_ms, int* h_steps);
 

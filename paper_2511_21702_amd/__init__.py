@@ -24,7 +24,7 @@ EXPORTS = [
     "csv_workspace_create", "csv_workspace_free", "csv_decode_step", "csv_bounds", "csv_full_logits",
     "csv_profile_begin", "csv_profile_end", "csv_last_error",
 ]
-PROFILE_STAGES = ["bounds", "seed", "gemv_round0", "cert_round0", "tail"]
+PROFILE_STAGES = ["bounds", "round0", "tail"]
 
 
 class BuildOpts(C.Structure):

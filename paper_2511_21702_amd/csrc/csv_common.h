@@ -27,10 +27,11 @@ struct csv_index {
 enum { ST_ACTIVE = 0, ST_DONE = 1, ST_FALLBACK = 2, ST_INVALID = 3 };
 // counters[]: [CNT_FALLBACK] sequences that fall back this step; [CNT_TILES + round*CSV_MAX_BATCH + b] row tiles
 // of sequence b in the round's work list; [CNT_CHUNKS + round*CSV_MAX_BATCH + b] chunk blocks of the round's
-// certification that have published their partial results.  All are zeroed by the bound kernel at the start of a step.
+// certification that have published their partial results; [CNT_ARRIVE + b] blocks of the round-0 kernel that have
+// finished their share of sequence b's seed rows.  All are zeroed by the bound kernel at the start of a step.
 // [CNT_BARRIER + i] arrivals at the i-th grid barrier of the tail kernel; [CNT_ABORT] set when a bounded wait ran out.
-enum { CNT_FALLBACK = 0, CNT_BARRIER = 1, CNT_ABORT = 5, CNT_TILES = 16, CNT_CHUNKS = 16 + 2 * CSV_MAX_BATCH,
-       CNT_TOTAL = 16 + 4 * CSV_MAX_BATCH };
+enum { CNT_FALLBACK = 0, CNT_BARRIER = 1, CNT_ABORT = 7, CNT_TILES = 16, CNT_CHUNKS = 16 + 2 * CSV_MAX_BATCH,
+       CNT_ARRIVE = 16 + 4 * CSV_MAX_BATCH, CNT_TOTAL = 16 + 5 * CSV_MAX_BATCH };
 
 // A cluster's position in the bound order is carried by one 64-bit key: monotone image of U_c in the high word,
 // ~c in the low word.  Larger key = larger bound, equal bounds = smaller cluster id first.  Empty clusters have key 0.

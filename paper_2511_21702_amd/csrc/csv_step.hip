@@ -44,6 +44,7 @@ struct StepArgs {
     int B, K_cap, Npad, n_chunks, tile_stride;
     int sp_chunks;     // most STAGE_CAP-sized chunks a sequence's scored rows can span
     int cand_chunks;   // chunk stride of the candidate buffers
+    int r0_h_off;      // offset of h in the round-0 kernel's LDS arena, in 128-bit units (behind the cluster data)
     float* U;
     float* hnorm;
     float* bound_partial;   // [BOUND_KS_MAX * B * C] K-slice partial sums of the batched bound product
@@ -411,25 +412,28 @@ __device__ __forceinline__ ClusterLds carve_clusters(u64* arena, int Npad, int C
 }
 __device__ __forceinline__ void load_clusters(const StepArgs& a, int b, const ClusterLds& L) {
     const int tid = threadIdx.x, nt = blockDim.x;
-    for (int c = tid; c <= a.C; c += nt) L.offl[c] = a.off[c];
-    // four clusters per thread and trip, all twelve loads issued before the first use
+    // four clusters per thread and trip, all sixteen loads issued before the first use (n_c = off[c+1] - off[c])
     for (int c0 = 0; c0 < a.C; c0 += 4 * nt) {
         float u[4], ln[4];
-        int n[4];
+        int o0[4], o1[4];
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             const int c = c0 + q * nt + tid;
             const bool in = c < a.C;
             u[q] = in ? a.U[(size_t)b * a.C + c] : 0.f;
-            n[q] = in ? a.n[c] : 0;
             ln[q] = in ? a.lnn[c] : 0.f;
+            o0[q] = in ? a.off[c] : 0;
+            o1[q] = in ? a.off[c + 1] : 0;
         }
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             const int c = c0 + q * nt + tid;
             if (c < a.C) {
-                L.keys[c] = n[q] > 0 ? ckey(u[q], c) : 0ull;
-                L.vl[c] = n[q] > 0 ? ln[q] + u[q] : -INFINITY;
+                const bool some = o1[q] > o0[q];
+                L.offl[c] = o0[q];
+                if (c == a.C - 1) L.offl[a.C] = o1[q];
+                L.keys[c] = some ? ckey(u[q], c) : 0ull;
+                L.vl[c] = some ? ln[q] + u[q] : -INFINITY;
             }
         }
     }
@@ -570,92 +574,6 @@ __device__ __forceinline__ void tail_stats(const StepArgs& a, const ClusterLds& 
     T = vmax > -INFINITY ? vmax + logf(sum) : -INFINITY;
 }
 
-// ================================================================================================ seed (round 0)
-// One block per sequence.  The seed prefix is found by repeated block-wide arg-max over the keys (it is a
-// handful of clusters), not by sorting.
-__global__ __launch_bounds__(1024) void seed_kernel(StepArgs a) {
-    extern __shared__ u64 arena[];
-    __shared__ SeqShared s;
-    const int b = blockIdx.x, tid = threadIdx.x, nt = blockDim.x, C = a.C;
-    const ClusterLds L = carve_clusters(arena, a.Npad, C);
-    DBG_T(0);
-    const float hn = a.hnorm[b];
-    if (tid == 0) a.out.d_flags[b] = CSV_FLAG_INVALID_INPUT;   // pending: overwritten by whichever path finishes the sequence
-    load_clusters(a, b, L);
-    if (!isfinite(hn)) {
-        write_invalid(a, b);
-        return;
-    }
-    __syncthreads();
-    DBG_T(1);
-    // Open clusters one at a time by block-wide arg-max until max(k,1) rows are open; the tiles of each winner are
-    // written at once (positions in bound order), so no compaction pass is needed here.
-    const int need = max(a.k, 1);
-    int rows = 0, m0 = 0, ntile = 0;
-    u64 kappa = ~0ull, nxt = 0;
-    Tile* tl = a.tiles[0] + (size_t)b * a.tile_stride;
-    bool over = false;
-    while (true) {
-        u64 best = 0;
-        for (int c = tid; c < C; c += nt) {
-            const u64 kx = L.keys[c];
-            if (kx < kappa && kx > best) best = kx;
-        }
-        best = block_max_u64(best, s.redu);
-        if (rows >= need || best == 0) {   // best is now the largest unopened key (0: none left)
-            nxt = best;
-            break;
-        }
-        const int cw = (int)(0xFFFFFFFFu - (uint32_t)best);
-        const int r0 = L.offl[cw], n = L.offl[cw + 1] - r0;
-        over = over || rows + n > a.K_max;
-        if (!over) {
-            const int ntc = (n + TILE_ROWS - 1) / TILE_ROWS;
-            for (int t = tid; t < ntc; t += nt) {
-                Tile x;
-                x.b = b; x.row0 = r0 + t * TILE_ROWS; x.nrows = min(TILE_ROWS, n - t * TILE_ROWS); x.pos = rows + t * TILE_ROWS;
-                tl[ntile + t] = x;
-            }
-            if (tid == 0) a.sel[(size_t)b * C + m0] = cw;
-            ntile += ntc;
-        }
-        rows += n;
-        m0 += 1;
-        kappa = best;
-    }
-    DBG_T(2);
-    if (rows > a.K_max) {
-        if (tid == 0) {
-            a.st[b].n_open = m0;
-            a.st[b].n_rows = rows;
-            push_fallback(a, b, 0);
-        }
-        return;
-    }
-    // log tail mass of the unopened clusters, shifted by an upper bound of its largest term
-    const float nxtU = nxt ? ckey_bound(nxt) : -INFINITY;
-    float T0 = -INFINITY;
-    if (nxt) {
-        const float shift = a.ln_nmax + nxtU;
-        float sum = 0.f;
-        for (int c = tid; c < C; c += nt) {
-            const u64 kx = L.keys[c];
-            if (kx != 0 && kx < kappa) sum += expf(L.vl[c] - shift);
-        }
-        sum = block_sum(sum, s.redf);
-        T0 = shift + logf(sum);
-    }
-    DBG_T(3);
-    DBG_T(4);
-    if (tid == 0) {
-        a.counters[CNT_TILES + b] = ntile;
-        SeqState st;
-        st.status = ST_ACTIVE; st.n_open = m0; st.n_rows = rows; st.rounds = 0; st.kappa = kappa; st.nxtU = nxtU; st.T = T0;
-        st.fb_slot = -1; st.pad[0] = st.pad[1] = st.pad[2] = 0;
-        a.st[b] = st;
-    }
-}
-
 // ================================================================================================ gathered GEMV
 // Work item = up to TILE_ROWS consecutive rows of W' for one sequence.  Each wave takes two rows and requests
 // their first 8 KB before the sequence's h is staged in LDS (bf16); 128-bit loads, float32 accumulation,
@@ -671,7 +589,6 @@ struct GemvShared {
 template <int RPW>
 __device__ __forceinline__ void gemv_tiles_device(const StepArgs& a, int round, uint4* hs4, GemvShared& gs, int block, int nblocks) {
     const int tid = threadIdx.x, nt = blockDim.x, lane = tid & 63, wave = tid >> 6;
-    if (block == 0 && round == 0) DBG_T(16);
     {
         const int mine = tid < a.B ? a.counters[CNT_TILES + round * CSV_MAX_BATCH + tid] : 0;
         int x = mine;
@@ -689,7 +606,6 @@ __device__ __forceinline__ void gemv_tiles_device(const StepArgs& a, int round, 
         if (tid < CSV_MAX_BATCH) gs.pre[tid + 1] = base + x;
         __syncthreads();
     }
-    if (block == 0 && round == 0) DBG_T(17);
     const int total = gs.pre[a.B];
     const int nch = a.d >> 3;
     const Tile* tl = a.tiles[round];
@@ -731,7 +647,6 @@ __device__ __forceinline__ void gemv_tiles_device(const StepArgs& a, int round, 
             __syncthreads();
             cur_b = t.b;
         }
-        if (block == 0 && round == 0) DBG_T(18);
         if (!active) continue;
         float acc[RPW];
 #pragma unroll
@@ -768,7 +683,6 @@ __device__ __forceinline__ void gemv_tiles_device(const StepArgs& a, int round, 
         }
 #pragma unroll
         for (int q = 0; q < RPW; ++q) acc[q] = wave_sum(acc[q]);
-        if (block == 0 && round == 0) DBG_T(19);
         if (lane == 0) {
             const size_t o = (size_t)t.b * a.K_cap + t.pos + i0;
 #pragma unroll
@@ -779,12 +693,6 @@ __device__ __forceinline__ void gemv_tiles_device(const StepArgs& a, int round, 
                 }
         }
     }
-}
-
-__global__ __launch_bounds__(256) void gemv_tiles_kernel(StepArgs a, int round) {
-    extern __shared__ uint4 hs4[];
-    __shared__ GemvShared gs;
-    gemv_tiles_device<2>(a, round, hs4, gs, blockIdx.x, gridDim.x);
 }
 
 // Copy n 32-bit words from global memory to LDS with eight loads in flight per thread.
@@ -1094,11 +1002,9 @@ __device__ __forceinline__ u64 softmax_prefix_key(const StepArgs& a, const Clust
 // Sequences with more than STAGE_CAP scored rows are handled by several blocks: each takes one chunk of STAGE_CAP
 // logits, publishes the chunk's top-k candidates and log-sum-exp partial, and the block that arrives last (a
 // device-scope counter; nobody waits) merges them and goes on to the tests.
-__device__ __forceinline__ void cert_device(const StepArgs& a, int b, int chunk, int round, SeqShared& s) {
+__device__ __forceinline__ void cert_body(const StepArgs& a, int b, int chunk, int round, const SeqState& st, SeqShared& s) {
     extern __shared__ u64 arena[];
     const int tid = threadIdx.x, nt = blockDim.x, C = a.C;
-    if (round == 0 || blockIdx.x == 0) DBG_T(8);
-    const SeqState st = a.st[b];
     if (st.status != ST_ACTIVE || st.rounds != round) return;
     const int n = st.n_rows;
     const int nchunks = (n + STAGE_CAP - 1) / STAGE_CAP;
@@ -1111,14 +1017,24 @@ __device__ __forceinline__ void cert_device(const StepArgs& a, int b, int chunk,
         stage_to_lds(reinterpret_cast<int*>(arena) + STAGE_CAP, gi, len);
         __syncthreads();
     }
-    if (round == 0 || blockIdx.x == 0) DBG_T(9);
+    if (round == 0) DBG_T(9);
     // the accessors name the LDS array itself so that the reads compile to LDS instructions
     auto val = [](int i) { return reinterpret_cast<const float*>(arena)[i]; };
     auto idf = [](int i) { return reinterpret_cast<const int*>(arena)[STAGE_CAP + i]; };
-    LseAcc l = block_lse(len, val, s);
-    if (round == 0 || blockIdx.x == 0) DBG_T(10);
-    if (a.use_k) block_topk(len, a.k, val, idf, s);
-    if (round == 0 || blockIdx.x == 0) DBG_T(13);
+    // with a top-k the largest logit is already known when the sum is taken: one block reduction instead of two
+    LseAcc l;
+    if (a.use_k) {
+        block_topk(len, a.k, val, idf, s);
+        if (round == 0) DBG_T(10);
+        l.m = s.wval[0];
+        float sm = 0.f;
+        if (l.m > -INFINITY)
+            for (int i = tid; i < len; i += nt) sm += expf(val(i) - l.m);
+        l.s = block_sum(sm, s.redf);
+    } else {
+        l = block_lse(len, val, s);
+    }
+    if (round == 0) DBG_T(11);
     if (nchunks > 1) {
         const size_t pb = (size_t)b * a.cand_chunks, pc = pb + chunk;
         const int kk = min(a.k, len);
@@ -1158,7 +1074,6 @@ __device__ __forceinline__ void cert_device(const StepArgs& a, int b, int chunk,
             }
         }
     }
-    if (round == 0 || blockIdx.x == 0) DBG_T(11);
     const float Z = lse_value(l);
     float theta = -INFINITY;
     if (a.use_k) theta = s.wval[a.k - 1];
@@ -1185,7 +1100,6 @@ __device__ __forceinline__ void cert_device(const StepArgs& a, int b, int chunk,
             if (a.out.d_rounds) a.out.d_rounds[b] = round + 1;
             a.st[b].status = ST_DONE;
         }
-        if (round == 0) DBG_T(12);
         return;
     }
     if (round == 1) {
@@ -1238,9 +1152,208 @@ __device__ __forceinline__ void cert_device(const StepArgs& a, int b, int chunk,
     }
 }
 
-__global__ __launch_bounds__(SEQ_THREADS) void cert_kernel(StepArgs a, int round) {
+__device__ __forceinline__ void cert_device(const StepArgs& a, int b, int chunk, int round, SeqShared& s) {
+    const SeqState st = a.st[b];
+    cert_body(a, b, chunk, round, st, s);
+}
+
+// ================================================================================================ round 0
+// Grid (NB, B): the NB blocks of a sequence each derive the same seed prefix from the sequence's bounds (the
+// prefix is a handful of clusters found by repeated block-wide arg-max over the keys, no sort), so no block
+// waits for another to plan the work; they share the prefix rows wave by wave, and the block that arrives last at
+// the sequence's counter (nobody waits) certifies, or plans round 1, or hands the sequence to the full product.
+// A prefix with more rows than the NB blocks should score themselves (one giant cluster) goes to the round-0
+// work list instead and is scored and certified by the tail kernel with the whole device.
+#define ROUND0_ROWS_PER_WAVE 8     // with at most 32 blocks of 8 waves a sequence: no more than 2048 <= STAGE_CAP rows
+#define ROUND0_HREG 4     // 128-bit pieces of h a thread carries in registers across the seed (d <= 4 * 8 * SEQ_THREADS)
+// log tail mass of the clusters below the threshold key kappa, shifted by an upper bound of its largest term
+// (nxt: the largest unopened key, 0 if none; nxtU: its bound)
+__device__ __forceinline__ float seed_tail_mass(const StepArgs& a, const ClusterLds& L, u64 kappa, u64 nxt, float nxtU, SeqShared& s) {
+    if (!nxt) return -INFINITY;
+    const float shift = a.ln_nmax + nxtU;
+    float sum = 0.f;
+    for (int c = threadIdx.x; c < a.C; c += blockDim.x) {
+        const u64 kx = L.keys[c];
+        if (kx != 0 && kx < kappa) sum += expf(L.vl[c] - shift);
+    }
+    sum = block_sum(sum, s.redf);
+    return shift + logf(sum);
+}
+__device__ __forceinline__ SeqState seed_state(int m0, int rows, u64 kappa, float nxtU, float T0) {
+    SeqState st;
+    st.status = ST_ACTIVE; st.n_open = m0; st.n_rows = rows; st.rounds = 0; st.kappa = kappa; st.nxtU = nxtU; st.T = T0;
+    st.fb_slot = -1; st.pad[0] = st.pad[1] = st.pad[2] = 0;
+    return st;
+}
+
+__global__ __launch_bounds__(SEQ_THREADS) void round0_kernel(StepArgs a) {
+    extern __shared__ u64 arena[];
     __shared__ SeqShared s;
-    cert_device(a, blockIdx.x, blockIdx.y, round, s);
+    const int b = blockIdx.y, j = blockIdx.x, NB = gridDim.x;
+    const int tid = threadIdx.x, nt = SEQ_THREADS, lane = tid & 63, wave = tid >> 6, C = a.C;
+    const int nch = a.d >> 3;
+    const ClusterLds L = carve_clusters(arena, a.Npad, C);
+    DBG_T(0);
+    // h is requested now and parked in registers: it moves to LDS once the cluster data there is dead
+    uint4 hreg[ROUND0_HREG];
+    {
+        const uint4* hsrc = reinterpret_cast<const uint4*>(a.h) + (size_t)b * nch;
+#pragma unroll
+        for (int q = 0; q < ROUND0_HREG; ++q) {
+            const int i = tid + q * nt;
+            hreg[q] = i < nch ? hsrc[i] : make_uint4(0, 0, 0, 0);
+        }
+    }
+    const float hn = a.hnorm[b];
+    if (j == 0 && tid == 0) a.out.d_flags[b] = CSV_FLAG_INVALID_INPUT;   // pending: overwritten by whichever path finishes the sequence
+    load_clusters(a, b, L);
+    if (!isfinite(hn)) {
+        if (j == 0) write_invalid(a, b);
+        return;
+    }
+    __syncthreads();
+    DBG_T(1);
+    // Open clusters one at a time by block-wide arg-max until max(k,1) rows are open.  Every opened cluster has
+    // at least one row, so at most max(k,1) <= CSV_MAX_K clusters open: their ids and positions fit the k-sized
+    // arrays.  Nothing is written to global memory inside the loop (a store would be waited for at the next barrier).
+    int* scl = s.wid;
+    int* spos = reinterpret_cast<int*>(s.wval);
+    const int need = max(a.k, 1);
+    int rows = 0, m0 = 0;
+    u64 kappa = ~0ull, nxt = 0;
+    while (true) {
+        u64 best = 0;
+        for (int c = tid; c < C; c += nt) {
+            const u64 kx = L.keys[c];
+            if (kx < kappa && kx > best) best = kx;
+        }
+        best = block_max_u64(best, s.redu);
+        if (rows >= need || best == 0) {   // best is now the largest unopened key (0: none left)
+            nxt = best;
+            break;
+        }
+        const int cw = (int)(0xFFFFFFFFu - (uint32_t)best);
+        if (tid == 0) {
+            scl[m0] = cw;
+            spos[m0] = rows;
+        }
+        rows += L.offl[cw + 1] - L.offl[cw];
+        m0 += 1;
+        kappa = best;
+    }
+    DBG_T(2);
+    if (rows > a.K_max) {
+        if (j == 0 && tid == 0) {
+            a.st[b].n_open = m0;
+            a.st[b].n_rows = rows;
+            push_fallback(a, b, 0);
+        }
+        return;
+    }
+    __syncthreads();   // scl / spos complete
+    if (j == 0)
+        for (int i = tid; i < m0; i += nt) a.sel[(size_t)b * C + i] = scl[i];
+    const int GW = NB * (nt >> 6);
+    if (rows > GW * ROUND0_ROWS_PER_WAVE || nch > ROUND0_HREG * nt) {
+        // too much for these blocks: the first block queues the prefix for the tail kernel
+        if (j != 0) return;
+        const float nxtU = nxt ? ckey_bound(nxt) : -INFINITY;
+        const float T0 = seed_tail_mass(a, L, kappa, nxt, nxtU, s);
+        Tile* tl = a.tiles[0] + (size_t)b * a.tile_stride;
+        int ntile = 0;
+        for (int i = 0; i < m0; ++i) {
+            const int r0 = L.offl[scl[i]], p0 = spos[i], n = (i + 1 < m0 ? spos[i + 1] : rows) - p0;
+            const int ntc = (n + TILE_ROWS - 1) / TILE_ROWS;
+            for (int t = tid; t < ntc; t += nt) {
+                Tile x;
+                x.b = b; x.row0 = r0 + t * TILE_ROWS; x.nrows = min(TILE_ROWS, n - t * TILE_ROWS); x.pos = p0 + t * TILE_ROWS;
+                tl[ntile + t] = x;
+            }
+            ntile += ntc;
+        }
+        if (tid == 0) {
+            a.counters[CNT_TILES + b] = ntile;
+            a.st[b] = seed_state(m0, rows, kappa, nxtU, T0);
+        }
+        return;
+    }
+
+    // h goes to its own LDS region behind the cluster data; the wave's first row is requested before the tail
+    // mass is summed, so that sum runs while the loads are in flight
+    uint4* hs4 = reinterpret_cast<uint4*>(arena) + a.r0_h_off;
+#pragma unroll
+    for (int q = 0; q < ROUND0_HREG; ++q) {
+        const int i = tid + q * nt;
+        if (i < nch) hs4[i] = hreg[q];
+    }
+    uint4 pf[GEMV_PF];
+    const uint4* w = nullptr;
+    float bias = 0.f;
+    int id = 0;
+    auto request = [&](int p) {
+        int lo = 0, hi = m0;   // largest i with spos[i] <= p
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (spos[mid] <= p) lo = mid; else hi = mid;
+        }
+        const int r = L.offl[scl[lo]] + (p - spos[lo]);
+        w = reinterpret_cast<const uint4*>(a.Wp + (size_t)r * a.d);
+#pragma unroll
+        for (int q = 0; q < GEMV_PF; ++q) {
+            const int i = lane + 64 * q;
+            pf[q] = i < nch ? w[i] : make_uint4(0, 0, 0, 0);
+        }
+        if (lane == 0) {
+            bias = a.bp[r];
+            id = a.perm[r];
+        }
+    };
+    int p = wave * NB + j;   // neighbouring rows go to different compute units
+    if (p < rows) request(p);
+    const float nxtU = nxt ? ckey_bound(nxt) : -INFINITY;
+    const float T0 = seed_tail_mass(a, L, kappa, nxt, nxtU, s);
+    const SeqState st = seed_state(m0, rows, kappa, nxtU, T0);
+    __syncthreads();
+    DBG_T(4);
+    while (p < rows) {
+        float acc = 0.f;
+#pragma unroll
+        for (int q = 0; q < GEMV_PF; ++q) {
+            const int i = lane + 64 * q;
+            if (i < nch) acc = dot8_bf16(pf[q], hs4[i], acc);
+        }
+        int i = lane + 64 * GEMV_PF;
+        for (; i + 192 < nch; i += 256) {
+            const uint4 x0 = w[i], x1 = w[i + 64], x2 = w[i + 128], x3 = w[i + 192];
+            acc = dot8_bf16(x0, hs4[i], acc);
+            acc = dot8_bf16(x1, hs4[i + 64], acc);
+            acc = dot8_bf16(x2, hs4[i + 128], acc);
+            acc = dot8_bf16(x3, hs4[i + 192], acc);
+        }
+        for (; i < nch; i += 64) acc = dot8_bf16(w[i], hs4[i], acc);
+        acc = wave_sum(acc);
+        if (lane == 0) {
+            a.slog[(size_t)b * a.K_cap + p] = acc + bias;
+            a.sid[(size_t)b * a.K_cap + p] = id;
+        }
+        p += GW;
+        if (p < rows) request(p);
+    }
+    DBG_T(5);
+    // The block that arrives last at the sequence's counter goes on.  Thread 0 releases after the barrier has
+    // collected the block's stores, and acquires again if it is the last; the barrier hands that on to the block.
+    __syncthreads();
+    if (tid == 0) {
+        __threadfence();
+        const bool last = atomicAdd(&a.counters[CNT_ARRIVE + b], 1) == NB - 1;
+        if (last) __threadfence();
+        s.sel = last;
+    }
+    __syncthreads();
+    DBG_T(6);
+    if (!s.sel) return;
+    if (tid == 0) a.st[b] = st;
+    cert_body(a, b, 0, 0, st, s);
 }
 
 // ================================================================================================ full-vocabulary product
@@ -1527,14 +1640,31 @@ __global__ __launch_bounds__(TAIL_THREADS) void tail_kernel(StepArgs a, FullArgs
     __shared__ int s_flag;
     const int tid = threadIdx.x;
     const int nblocks = gridDim.x, block = blockIdx.x;
-    // is any sequence waiting for round 1 or for the full product?  Every block reads the same, settled values.
-    int mine = 0;
-    if (tid < a.B) mine = a.counters[CNT_TILES + CSV_MAX_BATCH + tid];
+    // is any sequence waiting for round 0 (a seed prefix too large for the round-0 kernel), for round 1 or for the
+    // full product?  Every block reads the same, settled values.
+    int mine0 = 0, mine1 = 0;
+    if (tid < a.B) {
+        mine0 = a.counters[CNT_TILES + tid];
+        mine1 = a.counters[CNT_TILES + CSV_MAX_BATCH + tid];
+    }
     const int n_fb0 = a.counters[CNT_FALLBACK];
-    const int tiles1 = block_sum_i(mine, s.redi);
-    if (tiles1 == 0 && n_fb0 == 0) return;
+    const int tiles0 = block_sum_i(mine0, s.redi);
+    int tiles1 = block_sum_i(mine1, s.redi);
+    if (tiles0 == 0 && tiles1 == 0 && n_fb0 == 0) return;
     if (block == 0) DBG_T(20);
 
+    if (tiles0 > 0) {
+        gemv_tiles_device<1>(a, 0, reinterpret_cast<uint4*>(arena), gs, block, nblocks);
+        if (!grid_barrier(a.counters, 4, nblocks, &s_flag)) return;
+        for (int item = block; item < a.B * a.sp_chunks; item += nblocks) {
+            cert_device(a, item / a.sp_chunks, item % a.sp_chunks, 0, s);
+            __syncthreads();
+        }
+        if (!grid_barrier(a.counters, 5, nblocks, &s_flag)) return;
+        // the round-0 certification may have planned round 1 for these sequences
+        mine1 = tid < a.B ? __hip_atomic_load(&a.counters[CNT_TILES + CSV_MAX_BATCH + tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0;
+        tiles1 = block_sum_i(mine1, s.redi);
+    }
     if (tiles1 > 0) {
         gemv_tiles_device<1>(a, 1, reinterpret_cast<uint4*>(arena), gs, block, nblocks);
         if (block == 0) DBG_T(21);
@@ -1587,6 +1717,18 @@ static int next_pow2(int x) {
     return p;
 }
 
+// dynamic LDS of the per-sequence kernels
+static size_t seed_lds(const csv_workspace* ws) { return (size_t)ws->Npad * 8 + (size_t)ws->C * 8 + 8; }
+static size_t cert_lds(const csv_workspace* ws) {
+    const size_t plan = seed_lds(ws), stage = (size_t)STAGE_CAP * 8;
+    return plan > stage ? plan : stage;
+}
+static size_t round0_h_off(const csv_workspace* ws) { return (seed_lds(ws) + 15) / 16 * 16; }
+static size_t round0_lds(const csv_workspace* ws) {
+    const size_t c = cert_lds(ws), h = round0_h_off(ws) + (size_t)ws->d * 2;
+    return c > h ? c : h;
+}
+
 static void fill_args(StepArgs& a, const csv_workspace* ws, const csv_index* idx) {
     memset(&a, 0, sizeof(a));
     a.V = idx->V; a.d = idx->d; a.C = idx->C;
@@ -1595,6 +1737,7 @@ static void fill_args(StepArgs& a, const csv_workspace* ws, const csv_index* idx
     a.K_cap = ws->K_cap; a.Npad = ws->Npad; a.n_chunks = ws->n_chunks; a.tile_stride = ws->tile_stride; a.sp_chunks = ws->sp_chunks; a.cand_chunks = ws->cand_chunks;
     a.U = ws->U; a.hnorm = ws->hnorm; a.bound_partial = ws->bound_partial; a.st = ws->st; a.sel = ws->sel; a.slog = ws->slog; a.sid = ws->sid;
     a.tiles[0] = ws->tiles[0]; a.tiles[1] = ws->tiles[1]; a.counters = ws->counters;
+    a.r0_h_off = (int)(round0_h_off(ws) / 16);
     a.fb_list = ws->fb_list; a.fb_logits = ws->fb_logits; a.cand_val = ws->cand_val; a.cand_id = ws->cand_id;
     a.cand_max = ws->cand_max; a.cand_sum = ws->cand_sum;
 }
@@ -1644,14 +1787,6 @@ static int launch_bounds_kernel(const StepArgs& a, float* U, float* hn, int rese
     }
     CSV_LAUNCH_CHECK("bound_kernel");
     return CSV_OK;
-}
-
-// dynamic LDS of the per-sequence kernels
-static int seed_threads(const csv_workspace*) { return SEQ_THREADS; }
-static size_t seed_lds(const csv_workspace* ws) { return (size_t)ws->Npad * 8 + (size_t)ws->C * 8 + 8; }
-static size_t cert_lds(const csv_workspace* ws) {
-    const size_t plan = seed_lds(ws), stage = (size_t)STAGE_CAP * 8;
-    return plan > stage ? plan : stage;
 }
 
 static int launch_full(const csv_index* idx, const uint16_t* d_h, const int32_t* list, const int32_t* n_ptr, int n_fixed,
@@ -1709,10 +1844,8 @@ extern "C" int csv_workspace_create(const csv_index* idx, int B_max, int K_cap_r
         free(tmp);
     }
     // the per-sequence kernels may need more dynamic LDS than the default limit when C is large
-    if (e == hipSuccess && seed_lds(ws) + sizeof(SeqShared) > 65536)
-        e = hipFuncSetAttribute((const void*)seed_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)seed_lds(ws));
-    if (e == hipSuccess && cert_lds(ws) + sizeof(SeqShared) > 65536)
-        e = hipFuncSetAttribute((const void*)cert_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)cert_lds(ws));
+    if (e == hipSuccess && round0_lds(ws) + sizeof(SeqShared) > 65536)
+        e = hipFuncSetAttribute((const void*)round0_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)round0_lds(ws));
     if (e == hipSuccess) {
         size_t l = cert_lds(ws);
         const size_t cand[] = {(size_t)FULL_G * idx->d * 2, (size_t)FB_CHUNK * 4, (size_t)STAGE_CAP * 8};
@@ -1806,18 +1939,14 @@ extern "C" int csv_decode_step(csv_workspace* ws, const csv_index* idx, const ui
     rc = launch_bounds_kernel(a, ws->U, ws->hnorm, 1, st);
     if (rc) return rc;
     CSV_MARK(1);
-    seed_kernel<<<B, seed_threads(ws), seed_lds(ws), st>>>(a);
-    CSV_LAUNCH_CHECK("seed_kernel");
+    {
+        // blocks per sequence: enough waves that a typical seed prefix (one or two clusters) is one row per wave
+        int nb = 512 / B;
+        nb = nb < 2 ? 2 : (nb > 32 ? 32 : nb);
+        round0_kernel<<<dim3(nb, B), SEQ_THREADS, round0_lds(ws), st>>>(a);
+        CSV_LAUNCH_CHECK("round0_kernel");
+    }
     CSV_MARK(2);
-    long long want = ((long long)ws->K_cap / TILE_ROWS + 1) * B;
-    const int gg = (int)(want < 2048 ? want : 2048);
-    const size_t hl = (size_t)idx->d * 2;
-    gemv_tiles_kernel<<<gg, 256, hl, st>>>(a, 0);
-    CSV_LAUNCH_CHECK("gemv_tiles_kernel");
-    CSV_MARK(3);
-    cert_kernel<<<dim3(B, ws->sp_chunks), SEQ_THREADS, cert_lds(ws), st>>>(a, 0);
-    CSV_LAUNCH_CHECK("cert_kernel");
-    CSV_MARK(4);
     {
         FullArgs f;
         f.V = idx->V; f.d = idx->d; f.Wp = idx->Wp; f.bp = idx->bp; f.perm = idx->perm; f.h = d_h;
@@ -1825,7 +1954,7 @@ extern "C" int csv_decode_step(csv_workspace* ws, const csv_index* idx, const ui
         tail_kernel<<<ws->tail_grid, TAIL_THREADS, ws->tail_lds, st>>>(a, f);
         CSV_LAUNCH_CHECK("tail_kernel");
     }
-    CSV_MARK(5);
+    CSV_MARK(3);
 #undef CSV_MARK
     return CSV_OK;
 }
