@@ -90,43 +90,64 @@ __device__ __forceinline__ u64 ckey(float U, int c) { return ((u64)lkey(U) << 32
 __device__ __forceinline__ float ckey_bound(u64 k) { return fkey_inv((uint32_t)(k >> 32)); }
 
 // ================================================================================================ bounds
-// One wave per cluster, BT sequences per block.  The first 16 KB of the wave's centroid row is requested before
-// h is staged (the two do not depend on each other); h sits in LDS as bf16.
+// Block = 8 waves = 8/WPC clusters x WPC column slices (WPC = 1, 2 or 4, chosen so that a wave's slice of the
+// centroid row is at most 8 KB = one batch of eight 128-bit loads per lane), BT sequences per block.
+// Order of requests matters: a wave's loads return in order, so h (needed first, to fill LDS and for ||h||) is
+// requested before the centroid slice, and the slice is in flight while h is staged and the norms are taken.
 // Blocks are dealt round-robin to the 8 XCDs, so group g = (block % 8) * groups_per_xcd + block / 8 keeps
-// every XCD on the same centroid slice step after step (the slice stays resident in that XCD's L2).
-#define BOUND_PF 16
+// every XCD on the same centroid slice step after step.
+#define BOUND_PF 8
+#define BOUND_THREADS 512
+#define BOUND_HREG 8       // 128-bit pieces of h per thread: 8 x 512 x 16 B covers the 64 KB that BT sequences may take in LDS
 template <int BT>
-__global__ __launch_bounds__(256) void bound_kernel(StepArgs a, float* __restrict__ U_out, float* __restrict__ hn_out,
-                                                    int reset_counters, int groups, int groups_per_xcd) {
+__global__ __launch_bounds__(BOUND_THREADS) void bound_kernel(StepArgs a, float* __restrict__ U_out, float* __restrict__ hn_out,
+                                                              int reset_counters, int groups, int groups_per_xcd, int wpc) {
     extern __shared__ uint4 hs4[];
     __shared__ float hn[BT];
+    __shared__ float part[BOUND_THREADS / 64][BT];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int b0 = blockIdx.y * BT;
     const int nb = min(BT, a.B - b0);
     const int nch = a.d >> 3, nq = a.d >> 2;
+    const int cpb = (BOUND_THREADS / 64) / wpc, cl = wave / wpc, slice = wave - cl * wpc;
     const int g = (blockIdx.x & 7) * groups_per_xcd + (blockIdx.x >> 3);
-    const int c = g * 4 + wave;
+    const int c = g * cpb + cl;
     const bool valid = g < groups && c < a.C;
+    // h of the block's sequences: registers first
+    uint4 hreg[BOUND_HREG];
+    {
+        const uint4* hsrc = reinterpret_cast<const uint4*>(a.h) + (size_t)b0 * nch;
+#pragma unroll
+        for (int q = 0; q < BOUND_HREG; ++q) {
+            const int i = tid + q * BOUND_THREADS;
+            hreg[q] = i < nb * nch ? hsrc[i] : make_uint4(0, 0, 0, 0);
+        }
+    }
+    // this wave's slice of the centroid row
+    const int seg = (nq + wpc - 1) / wpc, lo = slice * seg, hi = min(nq, lo + seg);
     const float4* mrow = reinterpret_cast<const float4*>(a.mu + (size_t)(valid ? c : 0) * a.d);
     float4 pf[BOUND_PF];
 #pragma unroll
     for (int j = 0; j < BOUND_PF; ++j) {
-        const int i = lane + 64 * j;
-        pf[j] = (valid && i < nq) ? mrow[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+        const int i = lo + lane + 64 * j;
+        pf[j] = (valid && i < hi) ? mrow[i] : make_float4(0.f, 0.f, 0.f, 0.f);
     }
     float Rc = 0.f, bm = 0.f;
     int ncl = 0;
-    if (valid && lane == 0) {
+    if (valid && slice == 0 && lane == 0) {
         Rc = a.R[c];
         bm = a.bmax[c];
         ncl = a.n[c];
     }
-    const uint4* hsrc = reinterpret_cast<const uint4*>(a.h) + (size_t)b0 * nch;
-    for (int i = tid; i < BT * nch; i += 256) hs4[i] = (i < nb * nch) ? hsrc[i] : make_uint4(0, 0, 0, 0);
+#pragma unroll
+    for (int q = 0; q < BOUND_HREG; ++q) {
+        const int i = tid + q * BOUND_THREADS;
+        if (i < BT * nch) hs4[i] = hreg[q];
+    }
     if (reset_counters && blockIdx.x == 0 && blockIdx.y == 0)
-        for (int i = tid; i < CNT_TOTAL; i += 256) a.counters[i] = 0;
+        for (int i = tid; i < CNT_TOTAL; i += BOUND_THREADS) a.counters[i] = 0;
     __syncthreads();
-    for (int s = wave; s < BT; s += 4) {
+    for (int s = wave; s < BT; s += BOUND_THREADS / 64) {
         float acc = 0.f;
         for (int i = lane; i < nch; i += 64) {
             uint4 v = hs4[s * nch + i];
@@ -137,7 +158,6 @@ __global__ __launch_bounds__(256) void bound_kernel(StepArgs a, float* __restric
     }
     __syncthreads();
     if (blockIdx.x == 0 && tid < nb && hn_out) hn_out[b0 + tid] = hn[tid];
-    if (!valid) return;
 
     const uint2* hs2 = reinterpret_cast<const uint2*>(hs4);
     float acc[BT];
@@ -145,8 +165,8 @@ __global__ __launch_bounds__(256) void bound_kernel(StepArgs a, float* __restric
     for (int s = 0; s < BT; ++s) acc[s] = 0.f;
 #pragma unroll
     for (int j = 0; j < BOUND_PF; ++j) {
-        const int i = lane + 64 * j;
-        if (i < nq) {
+        const int i = lo + lane + 64 * j;
+        if (i < hi) {
             const float4 m = pf[j];
 #pragma unroll
             for (int s = 0; s < BT; ++s) {
@@ -158,21 +178,38 @@ __global__ __launch_bounds__(256) void bound_kernel(StepArgs a, float* __restric
             }
         }
     }
+    if (valid) {
 #pragma unroll 4
-    for (int i = lane + 64 * BOUND_PF; i < nq; i += 64) {
-        const float4 m = mrow[i];
+        for (int i = lo + lane + 64 * BOUND_PF; i < hi; i += 64) {
+            const float4 m = mrow[i];
 #pragma unroll
-        for (int s = 0; s < BT; ++s) {
-            const uint2 hv = hs2[s * nq + i];
-            acc[s] = fmaf(m.x, bf16_lo(hv.x), acc[s]);
-            acc[s] = fmaf(m.y, bf16_hi(hv.x), acc[s]);
-            acc[s] = fmaf(m.z, bf16_lo(hv.y), acc[s]);
-            acc[s] = fmaf(m.w, bf16_hi(hv.y), acc[s]);
+            for (int s = 0; s < BT; ++s) {
+                const uint2 hv = hs2[s * nq + i];
+                acc[s] = fmaf(m.x, bf16_lo(hv.x), acc[s]);
+                acc[s] = fmaf(m.y, bf16_hi(hv.x), acc[s]);
+                acc[s] = fmaf(m.z, bf16_lo(hv.y), acc[s]);
+                acc[s] = fmaf(m.w, bf16_hi(hv.y), acc[s]);
+            }
         }
     }
 #pragma unroll
     for (int s = 0; s < BT; ++s) acc[s] = wave_sum(acc[s]);
-    if (lane == 0) {
+    if (wpc > 1) {   // column slices of a cluster are added in slice order
+        if (lane == 0) {
+#pragma unroll
+            for (int s = 0; s < BT; ++s) part[wave][s] = acc[s];
+        }
+        __syncthreads();
+        if (slice == 0) {
+#pragma unroll
+            for (int s = 0; s < BT; ++s) {
+                float t = part[wave][s];
+                for (int q = 1; q < wpc; ++q) t += part[wave + q][s];
+                acc[s] = t;
+            }
+        }
+    }
+    if (valid && slice == 0 && lane == 0) {
         const bool empty = ncl == 0;
 #pragma unroll
         for (int s = 0; s < BT; ++s)
@@ -1775,15 +1812,19 @@ static int launch_bounds_kernel(const StepArgs& a, float* U, float* hn, int rese
     int bt = 1;
     while (bt < a.B && bt < 8) bt <<= 1;
     while (bt > 1 && (size_t)bt * a.d * 2 > 65536) bt >>= 1;
-    const int groups = (a.C + 3) / 4;
+    const int nq = a.d >> 2;
+    int wpc = 1;
+    while (wpc < 4 && (nq + wpc - 1) / wpc > 64 * BOUND_PF) wpc <<= 1;
+    const int cpb = (BOUND_THREADS / 64) / wpc;
+    const int groups = (a.C + cpb - 1) / cpb;
     const int gpx = (groups + 7) / 8;
     dim3 grid(gpx * 8, (a.B + bt - 1) / bt);
     const size_t lds = (size_t)bt * a.d * 2;
     switch (bt) {
-        case 1: bound_kernel<1><<<grid, 256, lds, st>>>(a, U, hn, reset, groups, gpx); break;
-        case 2: bound_kernel<2><<<grid, 256, lds, st>>>(a, U, hn, reset, groups, gpx); break;
-        case 4: bound_kernel<4><<<grid, 256, lds, st>>>(a, U, hn, reset, groups, gpx); break;
-        default: bound_kernel<8><<<grid, 256, lds, st>>>(a, U, hn, reset, groups, gpx); break;
+        case 1: bound_kernel<1><<<grid, BOUND_THREADS, lds, st>>>(a, U, hn, reset, groups, gpx, wpc); break;
+        case 2: bound_kernel<2><<<grid, BOUND_THREADS, lds, st>>>(a, U, hn, reset, groups, gpx, wpc); break;
+        case 4: bound_kernel<4><<<grid, BOUND_THREADS, lds, st>>>(a, U, hn, reset, groups, gpx, wpc); break;
+        default: bound_kernel<8><<<grid, BOUND_THREADS, lds, st>>>(a, U, hn, reset, groups, gpx, wpc); break;
     }
     CSV_LAUNCH_CHECK("bound_kernel");
     return CSV_OK;
