@@ -217,6 +217,81 @@ __global__ __launch_bounds__(BOUND_THREADS) void bound_kernel(StepArgs a, float*
     }
 }
 
+// One sequence (B = 1): no LDS staging at all.  h is 2d bytes that every wave of the device reads, so it comes from
+// L2 / L1 with the same addresses in every block; each wave takes its slice of h straight from global memory next to
+// its centroid slice, and ||h||^2 is the sum of the slices' partial sums of squares (slice order: the same value
+// in every block).
+__global__ __launch_bounds__(BOUND_THREADS) void bound1_kernel(StepArgs a, float* __restrict__ U_out, float* __restrict__ hn_out,
+                                                               int reset_counters, int groups, int groups_per_xcd, int wpc) {
+    __shared__ float part[BOUND_THREADS / 64], parth[BOUND_THREADS / 64];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int nq = a.d >> 2;
+    const int cpb = (BOUND_THREADS / 64) / wpc, cl = wave / wpc, slice = wave - cl * wpc;
+    const int g = (blockIdx.x & 7) * groups_per_xcd + (blockIdx.x >> 3);
+    const int c = g * cpb + cl;
+    const bool valid = g < groups && c < a.C;
+    const int seg = (nq + wpc - 1) / wpc, lo = slice * seg, hi = min(nq, lo + seg);
+    const float4* mrow = reinterpret_cast<const float4*>(a.mu + (size_t)(valid ? c : 0) * a.d);
+    const uint2* h2 = reinterpret_cast<const uint2*>(a.h);
+    float4 pf[BOUND_PF];
+    uint2 ph[BOUND_PF];
+#pragma unroll
+    for (int j = 0; j < BOUND_PF; ++j) {
+        const int i = lo + lane + 64 * j;
+        pf[j] = (valid && i < hi) ? mrow[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+#pragma unroll
+    for (int j = 0; j < BOUND_PF; ++j) {
+        const int i = lo + lane + 64 * j;
+        ph[j] = i < hi ? h2[i] : make_uint2(0, 0);
+    }
+    float Rc = 0.f, bm = 0.f;
+    int ncl = 0;
+    if (valid && slice == 0 && lane == 0) {
+        Rc = a.R[c];
+        bm = a.bmax[c];
+        ncl = a.n[c];
+    }
+    if (reset_counters && blockIdx.x == 0)
+        for (int i = tid; i < CNT_TOTAL; i += BOUND_THREADS) a.counters[i] = 0;
+    float acc = 0.f, hh = 0.f;
+    auto step = [&](const float4& m, const uint2& hv) {
+        const float h0 = bf16_lo(hv.x), h1 = bf16_hi(hv.x), h2v = bf16_lo(hv.y), h3 = bf16_hi(hv.y);
+        acc = fmaf(m.x, h0, acc);
+        acc = fmaf(m.y, h1, acc);
+        acc = fmaf(m.z, h2v, acc);
+        acc = fmaf(m.w, h3, acc);
+        hh = fmaf(h0, h0, hh);
+        hh = fmaf(h1, h1, hh);
+        hh = fmaf(h2v, h2v, hh);
+        hh = fmaf(h3, h3, hh);
+    };
+#pragma unroll
+    for (int j = 0; j < BOUND_PF; ++j) step(pf[j], ph[j]);
+#pragma unroll 4
+    for (int i = lo + lane + 64 * BOUND_PF; i < hi; i += 64) {
+        const float4 m = valid ? mrow[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+        step(m, h2[i]);
+    }
+    acc = wave_sum(acc);
+    hh = wave_sum(hh);
+    if (lane == 0) {
+        part[wave] = acc;
+        parth[wave] = hh;
+    }
+    __syncthreads();
+    if (slice == 0 && lane == 0) {
+        float t = part[wave], th = parth[wave];
+        for (int q = 1; q < wpc; ++q) {
+            t += part[wave + q];
+            th += parth[wave + q];
+        }
+        const float hn = sqrtf(th);
+        if (blockIdx.x == 0 && wave == 0 && hn_out) hn_out[0] = hn;
+        if (valid) U_out[c] = ncl == 0 ? -INFINITY : (t + Rc * hn + bm);
+    }
+}
+
 // Bounds for larger batches (B > 8): [C x d] fp32 centroids times [d x B] bf16 hidden states is a dense contraction,
 // done with v_mfma_f32_16x16x32_bf16.  A float32 centroid value is split exactly into three bf16 pieces
 // (x = hi + mid + lo, 8 mantissa bits each), so three MFMAs per k-block give the float32-exact products with float32
@@ -1821,7 +1896,10 @@ static int launch_bounds_kernel(const StepArgs& a, float* U, float* hn, int rese
     dim3 grid(gpx * 8, (a.B + bt - 1) / bt);
     const size_t lds = (size_t)bt * a.d * 2;
     switch (bt) {
-        case 1: bound_kernel<1><<<grid, BOUND_THREADS, lds, st>>>(a, U, hn, reset, groups, gpx, wpc); break;
+        case 1:
+            if (a.B == 1) bound1_kernel<<<grid, BOUND_THREADS, 0, st>>>(a, U, hn, reset, groups, gpx, wpc);
+            else bound_kernel<1><<<grid, BOUND_THREADS, lds, st>>>(a, U, hn, reset, groups, gpx, wpc);
+            break;
         case 2: bound_kernel<2><<<grid, BOUND_THREADS, lds, st>>>(a, U, hn, reset, groups, gpx, wpc); break;
         case 4: bound_kernel<4><<<grid, BOUND_THREADS, lds, st>>>(a, U, hn, reset, groups, gpx, wpc); break;
         default: bound_kernel<8><<<grid, BOUND_THREADS, lds, st>>>(a, U, hn, reset, groups, gpx, wpc); break;
