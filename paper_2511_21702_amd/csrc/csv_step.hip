@@ -44,6 +44,7 @@ struct StepArgs {
     int B, K_cap, Npad, n_chunks, tile_stride;
     int sp_chunks;     // most STAGE_CAP-sized chunks a sequence's scored rows can span
     int cand_chunks;   // chunk stride of the candidate buffers
+    int tail_lds;      // dynamic LDS bytes of the tail kernel
     int r0_h_off;      // offset of h in the round-0 kernel's LDS arena, in 128-bit units (behind the cluster data)
     float* U;
     float* hnorm;
@@ -1556,93 +1557,110 @@ __global__ __launch_bounds__(256) void full_gemv_kernel(FullArgs f) {
 }
 
 // MFMA path of the full-vocabulary product, used when more than FULL_G sequences share the pass over W' (then it
-// is a real dense contraction: [V x d] . [d x n]).  v_mfma_f32_16x16x32_bf16: a wave owns 16*MT rows of W' and
-// 16*NT sequences; K is walked in blocks of 128 (four MFMAs).  Lane (li = lane%16, g = lane/16) feeds row/sequence
-// li and, for the jj-th MFMA of a block, the eight k values at  block + 32 jj + 8 g: one load instruction reads
-// 64 contiguous bytes from each of 16 rows.  Both operands go straight from global memory to registers (h rows are L2-resident);
-// the kernel is HBM-bound, so the loads of one wave are hidden by the other waves of the SIMD rather than by
-// double buffering (which would cost the registers that keep four waves per SIMD resident).  Accumulator register r of lane (li, g) is  out[row 4g + r][sequence li].
-template <int MT, int NT>
-__device__ __forceinline__ void full_mfma_device(const FullArgs& f, int n, int seq0, int block, int nblocks) {
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nw = blockDim.x >> 6;
+// is a real dense contraction: [V x d] . [d x n]).  v_mfma_f32_16x16x32_bf16: a wave owns 16 rows of W' and 16*NT
+// sequences.  Lane (li = lane%16, g = lane/16) feeds row/sequence li and, for the jj-th MFMA of a 128-wide K block,
+// the eight k values at  block + 32 jj + 8 g.
+// The h operand is shared by every wave of the block, so it is staged once per K chunk in LDS, already in fragment
+// order (the 64 lanes of a fragment read 1 KB contiguously: no bank conflicts), instead of being fetched from L2 by
+// every wave for every row tile; a chunk is as many K blocks as fit (16*NT sequences x chunk x 2 bytes).  With
+// several chunks a wave revisits its own row tiles and adds to the logits it wrote in the previous chunk.
+// The W' operand goes straight from global memory to registers, MFMA_SBG K blocks (MFMA_SBG x 256 contiguous bytes
+// of each of the 16 rows) per batch of loads: long runs per row keep the DRAM pages open, which short 64-byte
+// pieces of many rows do not.
+// h is fed as the first operand and W' as the second, so accumulator register r of lane (li, g) is
+// out[sequence 4g + r][row li]: stores are 64-byte runs per sequence instead of 4-byte pieces 4V bytes apart.
+#ifndef MFMA_SBG
+#define MFMA_SBG 2
+#endif
+template <int NT>
+__device__ __forceinline__ void full_mfma_device(const FullArgs& f, int n, int seq0, uint4* lds, int lds_bytes, int block, int nblocks) {
+    const int tid = threadIdx.x, nt = blockDim.x, lane = tid & 63, wave = tid >> 6, nw = nt >> 6;
     const int li = lane & 15, g = lane >> 4;
-    const int rpw = 16 * MT;
-    const int ntiles = (f.V + rpw - 1) / rpw;
+    const int ntiles = (f.V + 15) >> 4;
     const int nq = f.d >> 3;                         // 16-byte chunks per row
-    const int nsb = (f.d + 127) >> 7;
+    const int nsb = (f.d + 127) >> 7;                // K blocks of 128
+    int sb_chunk = lds_bytes / (NT * 16 * 256);      // K blocks whose h fragments fit: NT*16 sequences x 128 x 2 bytes each
+    if (sb_chunk > nsb) sb_chunk = nsb;
     const uint4 zero = make_uint4(0, 0, 0, 0);
-    const uint4* hp[NT];
-    bool hv[NT];
-#pragma unroll
-    for (int t = 0; t < NT; ++t) {
-        const int sq = seq0 + t * 16 + li;
-        hv[t] = sq < n;
-        hp[t] = reinterpret_cast<const uint4*>(f.h) + (size_t)f.list[hv[t] ? sq : seq0] * nq;
-    }
-    for (int tile = block * nw + wave; tile < ntiles; tile += nblocks * nw) {
-        const int r0 = tile * rpw;
-        const uint4* ap[MT];
-#pragma unroll
-        for (int m = 0; m < MT; ++m) {
-            const int row = min(r0 + m * 16 + li, f.V - 1);
-            ap[m] = reinterpret_cast<const uint4*>(f.Wp + (size_t)row * f.d);
+    for (int sb0 = 0; sb0 < nsb; sb0 += sb_chunk) {
+        const int sbn = min(sb_chunk, nsb - sb0);
+        __syncthreads();
+        // stage h: piece (t, seq, q) -> fragment slot ((q/4)*NT + t)*64 + (q%4)*16 + seq, q counted from the chunk start
+        const int qn = sbn * 16;
+        for (int p = tid; p < NT * 16 * qn; p += nt) {
+            const int sl = p / qn, q = p - sl * qn;           // sl = t*16 + seq
+            const int sq = seq0 + sl, qa = sb0 * 16 + q;
+            uint4 v = zero;
+            if (sq < n && qa < nq) v = (reinterpret_cast<const uint4*>(f.h) + (size_t)f.list[sq] * nq)[qa];
+            lds[(((q >> 2) * NT + (sl >> 4)) << 6) + ((q & 3) << 4) + (sl & 15)] = v;
         }
-        floatx4_t acc[MT][NT];
+        __syncthreads();
+        for (int tile = block * nw + wave; tile < ntiles; tile += nblocks * nw) {
+            const int r0 = tile << 4;
+            const uint4* ap = reinterpret_cast<const uint4*>(f.Wp + (size_t)min(r0 + li, f.V - 1) * f.d);
+            floatx4_t acc[NT];
 #pragma unroll
-        for (int m = 0; m < MT; ++m)
+            for (int t = 0; t < NT; ++t) acc[t] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+            for (int s0 = 0; s0 < sbn; s0 += MFMA_SBG) {
+                uint4 A[MFMA_SBG][4];
 #pragma unroll
-            for (int t = 0; t < NT; ++t) acc[m][t] = floatx4_t{0.f, 0.f, 0.f, 0.f};
-        for (int sb = 0; sb < nsb; ++sb) {
-            uint4 A[MT][4], Bv[NT][4];
+                for (int u = 0; u < MFMA_SBG; ++u)
 #pragma unroll
-            for (int jj = 0; jj < 4; ++jj) {
-                const int q = sb * 16 + jj * 4 + g;     // chunk index of k = 128 sb + 32 jj + 8 g
-                const bool ok = q < nq;
-#pragma unroll
-                for (int m = 0; m < MT; ++m) A[m][jj] = ok ? ap[m][q] : zero;
-#pragma unroll
-                for (int t = 0; t < NT; ++t) Bv[t][jj] = (ok && hv[t]) ? hp[t][q] : zero;
-            }
-#pragma unroll
-            for (int jj = 0; jj < 4; ++jj)
-#pragma unroll
-                for (int m = 0; m < MT; ++m)
-#pragma unroll
-                    for (int t = 0; t < NT; ++t)
-                        acc[m][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, A[m][jj]),
-                                                                            __builtin_bit_cast(bf16x8_t, Bv[t][jj]), acc[m][t], 0, 0, 0);
-        }
-#pragma unroll
-        for (int m = 0; m < MT; ++m)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int row = r0 + m * 16 + 4 * g + r;
-                if (row < f.V) {
-                    const float bias = f.bp[row];
-                    const size_t col = f.scatter ? (size_t)f.perm[row] : (size_t)row;
-#pragma unroll
-                    for (int t = 0; t < NT; ++t) {
-                        const int sq = seq0 + t * 16 + li;
-                        if (sq < n) f.out[(size_t)sq * f.out_stride + col] = acc[m][t][r] + bias;
+                    for (int jj = 0; jj < 4; ++jj) {
+                        const int q = (sb0 + s0 + u) * 16 + jj * 4 + g;     // chunk index of k = 128 sb + 32 jj + 8 g
+                        const uint4 v = ap[min(q, nq - 1)];
+                        A[u][jj] = (s0 + u < sbn && q < nq) ? v : zero;
                     }
+#pragma unroll
+                for (int u = 0; u < MFMA_SBG; ++u) {
+                    const int sk = min(s0 + u, sbn - 1);    // past the chunk the A fragments are zero
+#pragma unroll
+                    for (int jj = 0; jj < 4; ++jj)
+#pragma unroll
+                        for (int t = 0; t < NT; ++t) {
+                            const uint4 Bv = lds[(((sk * 4 + jj) * NT + t) << 6) + lane];
+                            acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, Bv),
+                                                                             __builtin_bit_cast(bf16x8_t, A[u][jj]), acc[t], 0, 0, 0);
+                        }
                 }
             }
+            // h is the first MFMA operand: register r of lane (li, g) is out[sequence 4g + r][row li], so the 16 lanes
+            // of a group store 64 contiguous bytes of one sequence's logits
+            const int row = r0 + li;
+            if (row < f.V) {
+                const float bias = sb0 == 0 ? f.bp[row] : 0.f;
+                const size_t col = f.scatter ? (size_t)f.perm[row] : (size_t)row;
+#pragma unroll
+                for (int t = 0; t < NT; ++t)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const int sq = seq0 + t * 16 + 4 * g + r;
+                        if (sq < n) {
+                            float* o = f.out + (size_t)sq * f.out_stride + col;
+                            *o = (sb0 == 0 ? 0.f : *o) + acc[t][r] + bias;
+                        }
+                    }
+            }
+        }
     }
 }
 
 // All n sequences through the MFMA path: 32 per pass over W' (16 when that covers them).
-__device__ __forceinline__ void full_mfma_all(const FullArgs& f, int n, int block, int nblocks) {
+__device__ __forceinline__ void full_mfma_all(const FullArgs& f, int n, uint4* lds, int lds_bytes, int block, int nblocks) {
     if (n <= 16) {
-        full_mfma_device<2, 1>(f, n, 0, block, nblocks);
+        full_mfma_device<1>(f, n, 0, lds, lds_bytes, block, nblocks);
     } else {
-        for (int s0 = 0; s0 < n; s0 += 32) full_mfma_device<2, 2>(f, n, s0, block, nblocks);
+        for (int s0 = 0; s0 < n; s0 += 32) full_mfma_device<2>(f, n, s0, lds, lds_bytes, block, nblocks);
     }
 }
 
-__global__ __launch_bounds__(256) void full_mfma_kernel(FullArgs f) {
+#define MFMA_THREADS 512
+#define MFMA_LDS (128 * 1024)
+__global__ __launch_bounds__(MFMA_THREADS, 2) void full_mfma_kernel(FullArgs f) {
+    extern __shared__ uint4 mfma_lds[];
     const int n = f.n_ptr ? *f.n_ptr : f.n_fixed;
     if (n <= 0) return;
-    full_mfma_all(f, n, blockIdx.x, gridDim.x);
+    full_mfma_all(f, n, mfma_lds, MFMA_LDS, blockIdx.x, gridDim.x);
 }
 
 // First stage of top-k / log-sum-exp over V: one block per (chunk of rows, fallback slot).  The chunk's logits
@@ -1745,7 +1763,7 @@ __device__ __forceinline__ bool grid_barrier(int* counters, int which, int nbloc
     return *s_flag != 0;
 }
 
-__global__ __launch_bounds__(TAIL_THREADS) void tail_kernel(StepArgs a, FullArgs f) {
+__global__ __launch_bounds__(TAIL_THREADS, 2) void tail_kernel(StepArgs a, FullArgs f) {
     extern __shared__ u64 arena[];
     __shared__ SeqShared s;
     __shared__ GemvShared gs;
@@ -1793,7 +1811,7 @@ __global__ __launch_bounds__(TAIL_THREADS) void tail_kernel(StepArgs a, FullArgs
     const int n_fb = __hip_atomic_load(&a.counters[CNT_FALLBACK], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
     if (n_fb == 0) return;
     if (n_fb > FULL_G)
-        full_mfma_all(f, n_fb, block, nblocks);
+        full_mfma_all(f, n_fb, reinterpret_cast<uint4*>(arena), a.tail_lds, block, nblocks);
     else
         full_gemv_device(f, n_fb, reinterpret_cast<uint4*>(arena), block, nblocks);
     if (block == 0) DBG_T(25);
@@ -1850,6 +1868,7 @@ static void fill_args(StepArgs& a, const csv_workspace* ws, const csv_index* idx
     a.U = ws->U; a.hnorm = ws->hnorm; a.bound_partial = ws->bound_partial; a.st = ws->st; a.sel = ws->sel; a.slog = ws->slog; a.sid = ws->sid;
     a.tiles[0] = ws->tiles[0]; a.tiles[1] = ws->tiles[1]; a.counters = ws->counters;
     a.r0_h_off = (int)(round0_h_off(ws) / 16);
+    a.tail_lds = (int)ws->tail_lds;
     a.fb_list = ws->fb_list; a.fb_logits = ws->fb_logits; a.cand_val = ws->cand_val; a.cand_id = ws->cand_id;
     a.cand_max = ws->cand_max; a.cand_sum = ws->cand_sum;
 }
@@ -1908,16 +1927,34 @@ static int launch_bounds_kernel(const StepArgs& a, float* U, float* hn, int rese
     return CSV_OK;
 }
 
+// out[s][perm[r]] = tmp[s][r]: coalesced reads, scattered 4-byte writes, kept out of the streaming product kernel
+__global__ __launch_bounds__(256) void unpermute_kernel(const float* __restrict__ tmp, const int32_t* __restrict__ perm, int V,
+                                                        float* __restrict__ out) {
+    const int r = blockIdx.x * 256 + threadIdx.x, s = blockIdx.y;
+    if (r < V) out[(size_t)s * V + perm[r]] = tmp[(size_t)s * V + r];
+}
+
+// tmp: [n_fixed x V] scratch for the MFMA path when the result is wanted in token-id order (may be NULL otherwise)
 static int launch_full(const csv_index* idx, const uint16_t* d_h, const int32_t* list, const int32_t* n_ptr, int n_fixed,
-                       float* out, long long stride, int scatter, hipStream_t st) {
+                       float* out, long long stride, int scatter, float* tmp, hipStream_t st) {
     FullArgs f;
     f.V = idx->V; f.d = idx->d; f.Wp = idx->Wp; f.bp = idx->bp; f.perm = idx->perm; f.h = d_h;
     f.list = list; f.n_ptr = n_ptr; f.n_fixed = n_fixed; f.out = out; f.out_stride = stride; f.scatter = scatter;
     if (!n_ptr && n_fixed > FULL_G) {
-        const int wtiles = (idx->V + 31) / 32;          // 32 rows per wave, 4 waves per block
-        const int grid = (wtiles + 3) / 4 < 2048 ? (wtiles + 3) / 4 : 2048;
-        full_mfma_kernel<<<grid, 256, 0, st>>>(f);
+        int dev = 0, cus = 0;
+        CSV_HIP(hipGetDevice(&dev));
+        CSV_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+        const bool two_step = scatter && tmp && stride == idx->V;
+        if (two_step) {
+            f.out = tmp;
+            f.scatter = 0;
+        }
+        full_mfma_kernel<<<cus, MFMA_THREADS, MFMA_LDS, st>>>(f);
         CSV_LAUNCH_CHECK("full_mfma_kernel");
+        if (two_step) {
+            unpermute_kernel<<<dim3((idx->V + 255) / 256, n_fixed), 256, 0, st>>>(tmp, idx->perm, idx->V, out);
+            CSV_LAUNCH_CHECK("unpermute_kernel");
+        }
         return CSV_OK;
     }
     const int ntiles = (idx->V + 7) / 8;
@@ -1963,11 +2000,15 @@ extern "C" int csv_workspace_create(const csv_index* idx, int B_max, int K_cap_r
         free(tmp);
     }
     // the per-sequence kernels may need more dynamic LDS than the default limit when C is large
+    if (e == hipSuccess)
+        e = hipFuncSetAttribute((const void*)full_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, MFMA_LDS);
     if (e == hipSuccess && round0_lds(ws) + sizeof(SeqShared) > 65536)
         e = hipFuncSetAttribute((const void*)round0_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)round0_lds(ws));
     if (e == hipSuccess) {
         size_t l = cert_lds(ws);
-        const size_t cand[] = {(size_t)FULL_G * idx->d * 2, (size_t)FB_CHUNK * 4, (size_t)STAGE_CAP * 8};
+        // more than FULL_G fallback sequences go through the MFMA product, whose h fragments want a large LDS chunk
+        const size_t cand[] = {(size_t)FULL_G * idx->d * 2, (size_t)FB_CHUNK * 4, (size_t)STAGE_CAP * 8,
+                               B_max > FULL_G ? (size_t)MFMA_LDS : 0};
         for (size_t c : cand) l = c > l ? c : l;
         ws->tail_lds = l;
         if (l + sizeof(SeqShared) + sizeof(GemvShared) + 64 > 65536)
@@ -2021,7 +2062,7 @@ extern "C" int csv_full_logits(csv_workspace* ws, const csv_index* idx, const ui
     int rc = check_pair(ws, idx, d_h, B);
     if (rc) return rc;
     if (!d_logits) { csv_set_error("null d_logits"); return CSV_EINVAL; }
-    return launch_full(idx, d_h, ws->all_list, nullptr, B, d_logits, idx->V, 1, (hipStream_t)stream);
+    return launch_full(idx, d_h, ws->all_list, nullptr, B, d_logits, idx->V, 1, ws->fb_logits, (hipStream_t)stream);
 }
 
 extern "C" int csv_decode_step(csv_workspace* ws, const csv_index* idx, const uint16_t* d_h, int B,
