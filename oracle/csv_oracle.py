@@ -33,6 +33,7 @@ FLAG_TOPK_CERT = 1
 FLAG_SOFTMAX_CERT = 2
 FLAG_FALLBACK = 4
 FLAG_INVALID = 8
+FLAG_SOFTMAX_RELAXED = 16   # softmax tail bound met only at the relaxed tolerance 2*eps (Section IV, fallback levels)
 
 COMBINE_ALL = 0   # a step is certified when every enabled certificate holds
 COMBINE_ANY = 1   # Algorithm 1's literal "break on either certificate"
@@ -270,8 +271,9 @@ def alg1_step(index: OracleIndex, U_row: np.ndarray, logits_row: np.ndarray, k: 
 
 # ----------------------------------------------------------------------------- two-round schedule
 def csv2r_step(index: OracleIndex, U_row: np.ndarray, logits_row: np.ndarray, k: int, eps: float,
-               K_max: int, combine: int = COMBINE_ALL) -> dict:
-    """Two-round batched schedule of Algorithm 1 (the selection rule the GPU path is graded on).
+               K_max: int, combine: int = COMBINE_ALL, max_rounds: int = 2, delta_clusters: int = 0,
+               relax: bool = False) -> dict:
+    """Round-based batched schedule of Algorithm 1 (the selection rule the GPU path is graded on).
 
     The same two tests as Algorithm 1, evaluated only at round boundaries:
       round 0  open the shortest prefix of the bound order holding >= max(k,1) rows; theta0 = k-th largest
@@ -280,6 +282,18 @@ def csv2r_step(index: OracleIndex, U_row: np.ndarray, logits_row: np.ndarray, k:
                s = shortest prefix >= m0 whose tail satisfies Theorem 2 against Z0;
                open up to max(a,s) (ALL) or min(a,s) (ANY); test again.
     The budget |S| > K_max is tested on the planned size before scoring; failing tests after round 1 -> fallback.
+
+    With the defaults that is the whole schedule.  The three fallback levels of Section IV ("Runtime
+    Optimization") extend it:
+      max_rounds      scoring rounds allowed (>= 2); every later round plans exactly as round 1 does, from the
+                      theta and Z of the rows scored so far;
+      delta_clusters  partial expansion S' = S + Delta C: when a planned set exceeds K_max, open instead the next
+                      clusters of the bound order - at most delta_clusters of them, not past the planned set, and
+                      only while the rows stay within K_max - and test again (theta and Z grow, so the next plan
+                      may fit); 0 switches the level off;
+      relax           relaxed tolerance eps' = 2 eps: when no further expansion is possible, the step is accepted
+                      if the softmax tail bound holds at 2 eps (flag SOFTMAX_RELAXED instead of SOFTMAX_CERT);
+    and the full vocabulary remains the last level.
     Returns decisions, outputs and, for every comparison that decided something, the pair
     (|x - y|, max(1,|x|,|y|)) under "margins" (tie-band accounting in parity tests).
     """
@@ -346,44 +360,67 @@ def csv2r_step(index: OracleIndex, U_row: np.ndarray, logits_row: np.ndarray, k:
         margins["seed"] = gap(su[m0 - 1], su[m0])
     if P[m0] > K_max:
         return fallback(m0, 0)
-    rows, vals, ids, top, theta0, Z0 = score(m0)
-    tk0, sm0 = tests(m0, theta0, Z0, "0")
-    if combine_ok(tk0, sm0):
-        f = (FLAG_TOPK_CERT if tk0 and use_k else 0) | (FLAG_SOFTMAX_CERT if sm0 and use_s else 0)
-        _id_margin(margins, vals, k)
-        return result(f, m0, 1, ids, top, Z0, theta0)
-
-    # round 1 target
-    if tk0 or not use_k:
-        a = m0
-    else:
-        a = int(np.sum(su >= theta0))
-        fin = su[np.isfinite(su)]
-        near = fin[np.argmin(np.abs(fin - theta0))]
-        margins["a"] = gap(near, theta0)
-    if sm0 or not use_s:
-        s = m0
-    else:
-        s = m0 + int(np.argmax(T[m0:] - Z0 <= lam))
-        if math.isfinite(T[s]):
-            margins["s_hi"] = gap_soft(T[s], Z0)
-        margins["s_lo"] = gap_soft(T[s - 1], Z0)
-        if s < C and su[s] != NEG_INF:
-            margins["s_order"] = gap(su[s - 1], su[s])
-    cands = ([a] if use_k else []) + ([s] if use_s else [])
-    m1 = max(cands) if combine == COMBINE_ALL else min(cands)
-    if 0 < m1 < C and su[m1] != NEG_INF:
-        margins["m1_order"] = gap(su[m1 - 1], su[m1])
-    if P[m1] > K_max:
-        return fallback(m1, 1)
-    rows, vals, ids, top, theta1, Z1 = score(m1)
-    assert theta1 >= theta0 and Z1 >= Z0
-    tk1, sm1 = tests(m1, theta1, Z1, "1")
-    if combine_ok(tk1, sm1):
-        f = (FLAG_TOPK_CERT if tk1 and use_k else 0) | (FLAG_SOFTMAX_CERT if sm1 and use_s else 0)
-        _id_margin(margins, vals, k)
-        return result(f, m1, 2, ids, top, Z1, theta1)
-    return fallback(m1, 2)
+    lam2 = _lam(2.0 * eps) if use_s else NEG_INF
+    if max_rounds < 2:
+        raise ValueError("max_rounds must be at least 2")
+    m, r, theta_prev, Z_prev = m0, 0, NEG_INF, NEG_INF
+    m_plan = m0
+    while True:
+        tag = str(r)
+        rows, vals, ids, top, theta, Z = score(m)
+        assert theta >= theta_prev and Z >= Z_prev          # both only grow with S
+        theta_prev, Z_prev = theta, Z
+        tk, sm = tests(m, theta, Z, tag)
+        if combine_ok(tk, sm):
+            f = (FLAG_TOPK_CERT if tk and use_k else 0) | (FLAG_SOFTMAX_CERT if sm and use_s else 0)
+            _id_margin(margins, vals, k)
+            return result(f, m, r + 1, ids, top, Z, theta)
+        if r + 1 >= max_rounds:
+            break
+        # target of the next round
+        if tk or not use_k:
+            a = m
+        else:
+            a = int(np.sum(su >= theta))
+            fin = su[np.isfinite(su)]
+            near = fin[np.argmin(np.abs(fin - theta))]
+            margins["a" + ("" if r == 0 else tag)] = gap(near, theta)
+        if sm or not use_s:
+            sp = m
+        else:
+            sp = m + int(np.argmax(T[m:] - Z <= lam))
+            sfx = "" if r == 0 else tag
+            if math.isfinite(T[sp]):
+                margins["s_hi" + sfx] = gap_soft(T[sp], Z)
+            margins["s_lo" + sfx] = gap_soft(T[sp - 1], Z)
+            if sp < C and su[sp] != NEG_INF:
+                margins["s_order" + sfx] = gap(su[sp - 1], su[sp])
+        cands = ([a] if use_k else []) + ([sp] if use_s else [])
+        m_plan = max(cands) if combine == COMBINE_ALL else min(cands)
+        if 0 < m_plan < C and su[m_plan] != NEG_INF:
+            margins["m1_order" + ("" if r == 0 else tag)] = gap(su[m_plan - 1], su[m_plan])
+        if P[m_plan] <= K_max:
+            m_next = m_plan
+        else:
+            m_next = m
+            while m_next < min(m + max(delta_clusters, 0), m_plan) and P[m_next + 1] <= K_max:
+                m_next += 1
+            if m_next == m:
+                break
+            if su[m_next] != NEG_INF and m_next < C:
+                margins["mp_order" + tag] = gap(su[m_next - 1], su[m_next])
+        m = m_next
+        r += 1
+    # no further expansion: relaxed tolerance, else the full vocabulary
+    if relax and use_s:
+        sm2 = bool(T[m] - Z <= lam2)
+        if math.isfinite(T[m]) and math.isfinite(lam2):
+            margins["sm_relaxed"] = (abs(float(T[m]) - Z - lam2), max(1.0, abs(float(T[m])), abs(Z), abs(lam2)))
+        if combine_ok(tk, sm2):
+            f = (FLAG_TOPK_CERT if tk and use_k else 0) | (FLAG_SOFTMAX_CERT if sm else (FLAG_SOFTMAX_RELAXED if sm2 else 0))
+            _id_margin(margins, vals, k)
+            return result(f, m, r + 1, ids, top, Z, theta)
+    return fallback(max(m, m_plan), r + 1)
 
 
 def _id_margin(margins: dict, vals: np.ndarray, k: int) -> None:
@@ -395,7 +432,8 @@ def _id_margin(margins: dict, vals: np.ndarray, k: int) -> None:
 
 # ----------------------------------------------------------------------------- one batch step
 def decode_step(W64: np.ndarray, b, index: OracleIndex, h_bits: np.ndarray, k: int, eps: float, K_max: int,
-                combine: int = COMBINE_ALL, logits: np.ndarray | None = None) -> list:
+                combine: int = COMBINE_ALL, logits: np.ndarray | None = None, max_rounds: int = 2,
+                delta_clusters: int = 0, relax: bool = False) -> list:
     """All sequences of one batch step.  Full logits are formed once by definition; the selection
     rule then reads the entries of the rows it opens (identical to scoring those rows alone)."""
     h64 = bf16_to_f64(np.atleast_2d(h_bits))
@@ -407,8 +445,27 @@ def decode_step(W64: np.ndarray, b, index: OracleIndex, h_bits: np.ndarray, k: i
         if not np.isfinite(hn[s]):
             out.append({"flags": FLAG_INVALID, "fallback": False})
             continue
-        r = csv2r_step(index, U[s], logits[s], k, eps, K_max, combine)
+        r = csv2r_step(index, U[s], logits[s], k, eps, K_max, combine, max_rounds, delta_clusters, relax)
         r["U"] = U[s]
         r["hnorm"] = hn[s]
         out.append(r)
     return out
+
+
+# ----------------------------------------------------------------------------- adaptive budget
+def kmax_update(K_max: float, rho_fall: float, alpha: float = 0.01, rho_target: float = 0.02,
+                literal: bool = False) -> float:
+    """One update of the row budget from the fallback rate of the step just taken (Section IV, "Runtime
+    Optimization": K_max(t+1) = K_max(t) (1 + alpha (rho_target - rho_fall(t))), alpha = 0.01, target 0.02).
+
+    As printed the factor shrinks the budget when fallbacks are above the target, which drives the rate away from
+    the target it is said to maintain (a larger budget means fewer fallbacks).  literal=True evaluates the printed
+    expression; the default takes the sign that makes the update a negative feedback,
+    K_max (1 + alpha (rho_fall - rho_target)).  The value is returned unrounded and unclamped."""
+    err = (rho_target - rho_fall) if literal else (rho_fall - rho_target)
+    return K_max * (1.0 + alpha * err)
+
+
+def kmax_rows(K_max: float, K_min: int, K_cap: int) -> int:
+    """Row budget handed to a step: the controller's value rounded down and kept inside [K_min, K_cap]."""
+    return int(min(max(math.floor(K_max), K_min), K_cap))

@@ -432,3 +432,130 @@ def test_softmax_test_is_non_strict():
     assert O.alg1_step(idx, U, L, 0, 0.49, K_max=2)["opened"] == 2
     r = O.csv2r_step(idx, U, L, 0, 0.5, K_max=2)
     assert r["m1"] == 1 and r["flags"] == O.FLAG_SOFTMAX_CERT
+
+
+# ----------------------------------------------------------------------------- fallback levels and adaptive budget
+def _line_head(clusters):
+    """d = 1 head whose logits for h = 1 are the listed values: one list per cluster (all bf16-exact)."""
+    vals = np.array([v for c in clusters for v in c], dtype=np.float32)
+    labels = np.array([i for i, c in enumerate(clusters) for _ in c], dtype=np.int64)
+    W_bits = synth.f32_to_bf16_bits(vals.reshape(-1, 1))
+    assert np.array_equal(synth.bf16_bits_to_f32(W_bits).ravel(), vals)
+    b = np.zeros(vals.size, dtype=np.float32)
+    idx = O.build_index(W_bits, b, labels, len(clusters))
+    W64 = O.bf16_to_f64(W_bits)
+    h_bits = synth.f32_to_bf16_bits(np.array([[1.0]], dtype=np.float32))
+    return W64, b, idx, h_bits, vals
+
+
+def test_partial_expansion_rescues_a_step_traced_by_hand():
+    # k = 2.  Round 0 opens c0 = {10, 1}: theta0 = 1, next bound ~9 -> not certified; every cluster can still hold a
+    # value >= 1, so the plan is all 10 rows > K_max = 6.  Opening one more cluster (Delta C = 1, c1 = {9, 8.5}) lifts
+    # theta to 9 > the next bound ~8.6: certified with 4 rows in 2 rounds.  Without the level: full vocabulary.
+    W64, b, idx, h_bits, vals = _line_head([[10, 1], [9, 8.5], [8.5625, 0], [2, 1.5], [1.25, 1.125]])
+    plain = O.decode_step(W64, b, idx, h_bits, k=2, eps=0.0, K_max=6)[0]
+    assert plain["flags"] & O.FLAG_FALLBACK and plain["rounds"] == 1
+    lad = O.decode_step(W64, b, idx, h_bits, k=2, eps=0.0, K_max=6, max_rounds=4, delta_clusters=1)[0]
+    assert lad["flags"] == O.FLAG_TOPK_CERT
+    assert lad["rounds"] == 2 and lad["n_rows"] == 4 and lad["n_clusters"] == 2
+    assert list(lad["ids"]) == [0, 2] and list(lad["logits"]) == [10.0, 9.0]
+    # same answer as the full vocabulary gives
+    assert list(plain["ids"]) == [0, 2]
+
+
+def test_partial_expansion_stops_at_the_budget_and_at_max_rounds():
+    W64, b, idx, h_bits, vals = _line_head([[10, 1], [9, 0.5], [8.5, 0.25], [8, 0.125], [7.5, 0]])
+    # k = 2, theta0 = 1: the plan is everything (10 rows).  Budget 4 rows: one extra cluster fits, theta becomes 9,
+    # next bound 8.5 < 9 -> certified.  Budget 3 rows: nothing fits -> full vocabulary after one round.
+    ok = O.decode_step(W64, b, idx, h_bits, k=2, eps=0.0, K_max=4, max_rounds=3, delta_clusters=1)[0]
+    assert ok["flags"] == O.FLAG_TOPK_CERT and ok["n_rows"] == 4 and ok["rounds"] == 2
+    no = O.decode_step(W64, b, idx, h_bits, k=2, eps=0.0, K_max=3, max_rounds=3, delta_clusters=1)[0]
+    assert no["flags"] & O.FLAG_FALLBACK and no["rounds"] == 1
+    # k = 4 needs four clusters' heads: Delta C = 1 per round and only 2 rounds in total cannot get there
+    few = O.decode_step(W64, b, idx, h_bits, k=4, eps=0.0, K_max=8, max_rounds=2, delta_clusters=1)[0]
+    assert few["flags"] & O.FLAG_FALLBACK
+    many = O.decode_step(W64, b, idx, h_bits, k=4, eps=0.0, K_max=8, max_rounds=5, delta_clusters=1)[0]
+    assert many["flags"] == O.FLAG_TOPK_CERT and many["n_rows"] <= 8
+    assert list(many["logits"]) == [10.0, 9.0, 8.5, 8.0]
+
+
+def test_relaxed_tolerance_accepts_between_eps_and_two_eps():
+    # softmax only.  S = {5, 5}, outside = {0, 0} with bound ~0: T - Z ~ -5, e^-5 = 0.00674.
+    # eps = 0.005: eps/(1-eps) = 0.005025 < e^-5 < 0.010101 = 2eps/(1-2eps): fails at eps, holds at 2 eps.
+    W64, b, idx, h_bits, vals = _line_head([[5, 5], [0, 0]])
+    strict = O.decode_step(W64, b, idx, h_bits, k=0, eps=0.005, K_max=2)[0]
+    assert strict["flags"] & O.FLAG_FALLBACK
+    rel = O.decode_step(W64, b, idx, h_bits, k=0, eps=0.005, K_max=2, relax=True)[0]
+    assert rel["flags"] == O.FLAG_SOFTMAX_RELAXED and rel["n_rows"] == 2 and rel["rounds"] == 1
+    ZV = O.logsumexp(vals.astype(np.float64))
+    outside = 1.0 - math.exp(rel["lse"] - ZV)           # probability mass outside S
+    assert 0.005 < outside <= 0.01
+    # with room in the budget the strict certificate is reached instead
+    roomy = O.decode_step(W64, b, idx, h_bits, k=0, eps=0.005, K_max=4, relax=True)[0]
+    assert roomy["flags"] == O.FLAG_SOFTMAX_CERT and roomy["n_rows"] == 4
+
+
+def test_fallback_levels_never_break_the_certificates():
+    # Theorem 1 / Theorem 2 against brute force over V, on steps that go through partial expansions and relaxation
+    r = synth.small_recipe(V=1500, d=48, C=30, B=1, steps=40, k=8, eps=2e-3, h_mode="mix", sizes="zipf", iso_frac=0.2,
+                           row_noise=0.3)
+    head = synth.make_head(r)
+    h = synth.make_hidden(r, head["centers"], steps=40)
+    W64 = O.bf16_to_f64(head["W_bits"])
+    idx = O.build_index(head["W_bits"], head["b"], head["labels"], r.C)
+    seen = {"rescued": 0, "relaxed": 0, "fallback": 0, "cert": 0, "extra_rounds": 0}
+    for s in range(40):
+        L = O.full_logits(W64, head["b"], O.bf16_to_f64(np.atleast_2d(h[s])))[0]
+        ids, top = O.topk_bruteforce(L, r.k)
+        ZV = O.logsumexp(L)
+        for eps in (r.eps, 0.0):
+            for K_max in (150, 400, 900):
+                base = O.decode_step(W64, head["b"], idx, h[s], r.k, eps, K_max, logits=L[None])[0]
+                res = O.decode_step(W64, head["b"], idx, h[s], r.k, eps, K_max, logits=L[None], max_rounds=6,
+                                    delta_clusters=2, relax=True)[0]
+                assert res["rounds"] <= 6
+                if res["flags"] & O.FLAG_FALLBACK:
+                    seen["fallback"] += 1
+                    assert base["flags"] & O.FLAG_FALLBACK          # the levels only ever remove fallbacks
+                    continue
+                assert res["n_rows"] <= K_max
+                if res["flags"] & O.FLAG_TOPK_CERT:
+                    assert np.array_equal(res["ids"], ids)
+                out = 1.0 - math.exp(res["lse"] - ZV)
+                if res["flags"] & O.FLAG_SOFTMAX_CERT:
+                    assert out <= eps
+                    seen["cert"] += 1
+                if res["flags"] & O.FLAG_SOFTMAX_RELAXED:
+                    assert eps > 0 and out <= 2 * eps
+                    seen["relaxed"] += 1
+                seen["extra_rounds"] += res["rounds"] > 2
+                if base["flags"] & O.FLAG_FALLBACK and not res["flags"] & O.FLAG_SOFTMAX_RELAXED:
+                    seen["rescued"] += 1
+    assert all(v > 0 for v in seen.values()), seen
+
+
+def test_kmax_controller_printed_formula_and_feedback_reading():
+    # the printed update, evaluated by hand: 32064 * (1 + 0.01 * (0.02 - 0.10)) = 32064 * 0.9992 = 32038.3488
+    assert O.kmax_update(32064, 0.10, literal=True) == pytest.approx(32038.3488, rel=1e-12)
+    # the feedback reading moves the other way by the same amount
+    assert O.kmax_update(32064, 0.10) == pytest.approx(32064 * 1.0008, rel=1e-12)
+    # at the target nothing moves, in either reading
+    assert O.kmax_update(5000.0, 0.02) == 5000.0 and O.kmax_update(5000.0, 0.02, literal=True) == 5000.0
+    # constant rate: geometric closed form
+    K = 1000.0
+    for _ in range(50):
+        K = O.kmax_update(K, 0.25, alpha=0.01, rho_target=0.02)
+    assert K == pytest.approx(1000.0 * (1 + 0.01 * 0.23) ** 50, rel=1e-12)
+    assert O.kmax_rows(123.9, 10, 1000) == 123 and O.kmax_rows(3.2, 10, 1000) == 10 and O.kmax_rows(5e3, 10, 1000) == 1000
+
+
+def test_kmax_controller_closed_loop_needs_the_feedback_sign():
+    # a fallback rate that falls as the budget grows (any such model will do): rho(K) = exp(-K / 2000)
+    rho = lambda K: math.exp(-K / 2000.0)
+    K_star = -2000.0 * math.log(0.02)                  # budget at which the rate equals the target
+    for literal, toward in ((False, True), (True, False)):
+        K = 0.5 * K_star
+        d0 = abs(K - K_star)
+        for _ in range(20000):
+            K = O.kmax_update(K, rho(K), alpha=0.01, rho_target=0.02, literal=literal)
+        assert (abs(K - K_star) < 0.01 * d0) == toward, (literal, K, K_star)
