@@ -36,6 +36,8 @@ extern "C" {
 #define CSV_FLAG_TOPK_CERT     1u   /* Definition 1 holds: returned top-k equals the full-vocabulary top-k */
 #define CSV_FLAG_SOFTMAX_CERT  2u   /* Theorem 2 holds: total variation of the sub-vocabulary softmax <= eps */
 #define CSV_FLAG_FALLBACK      4u   /* all V rows were scored for this sequence */
+#define CSV_FLAG_SOFTMAX_RELAXED 16u /* the softmax tail bound holds only at the relaxed tolerance 2*eps (Section IV,
+                                       fallback levels); never set together with SOFTMAX_CERT */
 #define CSV_FLAG_INVALID_INPUT 8u   /* ||h||^2 is not finite (other outputs of the sequence are cleared), or the
                                        step could not finish the sequence (a bounded device-side wait ran out) */
 
@@ -44,6 +46,7 @@ extern "C" {
 
 #define CSV_MAX_K        1024   /* largest k */
 #define CSV_MAX_CLUSTERS 8192   /* largest C */
+#define CSV_MAX_ROUNDS 8         /* most scoring rounds of a sequence on the sub-vocabulary path */
 #define CSV_MAX_BATCH    256    /* largest B */
 
 typedef struct csv_index csv_index;          /* opaque: permuted W', b', centroids, radii, bias maxima, sizes */
@@ -100,6 +103,14 @@ typedef struct {
     float eps;         /* softmax tolerance; <= 0 disables the softmax certificate, >= 1 always holds */
     int   K_max_rows;  /* budget K_max of Algorithm 1: a sequence whose planned |S| exceeds it falls back */
     int   combine;     /* CSV_COMBINE_ALL or CSV_COMBINE_ANY */
+    /* Fallback levels (Section IV, "Runtime Optimization"); all zero = the two-round schedule with the full
+       vocabulary as the only fallback. */
+    int   max_rounds;      /* scoring rounds allowed, 2..CSV_MAX_ROUNDS (0 is read as 2): later rounds plan as round 1 does */
+    int   delta_clusters;  /* partial expansion S' = S + Delta C: when a planned set exceeds K_max_rows, open the next
+                              clusters of the bound order instead (at most this many, not past the planned set, rows
+                              within the budget) and test again; 0 = off */
+    int   relax;           /* nonzero: when no further expansion is possible, accept a step whose softmax tail bound
+                              holds at 2*eps (flag SOFTMAX_RELAXED) before falling back to the full vocabulary */
 } csv_step_params;
 
 typedef struct {
@@ -109,9 +120,10 @@ typedef struct {
     uint32_t* d_flags;        /* [B]    CSV_FLAG_* */
     int32_t*  d_n_rows;       /* [B]    rows scored, |S| (V after fallback) */
     int32_t*  d_n_clusters;   /* [B]    clusters opened (C after fallback) */
-    int32_t*  d_rounds;       /* [B] or NULL: scoring rounds used on the sub-vocabulary path (0, 1 or 2) */
+    int32_t*  d_rounds;       /* [B] or NULL: scoring rounds used on the sub-vocabulary path (0..max_rounds) */
     int32_t*  d_sel_clusters; /* [B*C] or NULL: opened cluster ids (first n_clusters entries): round-0 clusters,
-                                 then round-1 clusters, each group by ascending id; untouched on fallback */
+                                 then the clusters of each later round, each group by ascending id; untouched on
+                                 fallback */
     unsigned long long* d_fallback_count; /* or NULL: incremented once per sequence that falls back */
 } csv_step_out;
 
@@ -127,6 +139,9 @@ typedef struct {
  *            m1 = max(a,s) under ALL, min(a,s) under ANY (a disabled test drops out); open up to m1, test again.
  *   The budget is tested on the planned size before scoring: P(m) > K_max_rows -> fallback; tests failing after
  *   round 1 -> fallback.  Fallback scores all V rows (flags FALLBACK|TOPK_CERT|SOFTMAX_CERT).
+ *   With max_rounds > 2, delta_clusters > 0 or relax set, the fallback levels of Section IV apply before the full
+ *   vocabulary: every later round plans from the theta and Z of all rows scored so far; a plan over the budget is
+ *   replaced by a partial expansion; when neither fits, the relaxed tolerance is tried (see csv_step_params).
  *   d_h  DEVICE bf16[B*d].  1 <= B <= workspace B_max.  Returns CSV_EINVAL when both certificates are disabled,
  *   k > V, or K_max_rows exceeds the workspace capacity.
  */
@@ -161,6 +176,25 @@ int csv_full_logits(csv_workspace* ws, const csv_index* idx, const uint16_t* d_h
 #define CSV_PROFILE_STAGES 3
 int csv_profile_begin(csv_workspace* ws, int max_steps);
 int csv_profile_end(csv_workspace* ws, float* h_stage_ms, int* h_steps);
+
+/*
+ * Adaptive row budget (Section IV, "Runtime Optimization": K_max(t+1) = K_max(t) * (1 + alpha * (rho_target -
+ * rho_fall(t))), alpha = 0.01, rho_target = 0.02).  Host-side state, no device work.  rho_fall(t) is the fraction of
+ * the step's sequences that fell back.  As printed the update lowers the budget when fallbacks exceed the target,
+ * which moves the rate away from the target it is meant to hold; literal = 0 uses the sign that gives a negative
+ * feedback, K_max * (1 + alpha * (rho_fall - rho_target)), literal = 1 the printed expression.
+ * csv_kmax_init: K0 rows to start from; the value handed to a step is floor(K_max) kept inside [K_min, K_cap].
+ * csv_kmax_update: feed one step's fallback count (0 <= n_fallback <= n_sequences, n_sequences >= 1); returns the
+ * budget in rows for the next step, or a negative CSV_E* code.
+ */
+typedef struct {
+    double K_max;          /* unrounded controller state */
+    double alpha, rho_target;
+    int    K_min, K_cap;
+    int    literal;
+} csv_kmax_ctl;
+int csv_kmax_init(csv_kmax_ctl* c, int K0, int K_min, int K_cap, double alpha, double rho_target, int literal);
+int csv_kmax_update(csv_kmax_ctl* c, int n_fallback, int n_sequences);
 
 const char* csv_last_error(void);
 

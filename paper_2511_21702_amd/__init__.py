@@ -15,14 +15,14 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libcsvdecode.so")
 
-FLAG_TOPK_CERT, FLAG_SOFTMAX_CERT, FLAG_FALLBACK, FLAG_INVALID_INPUT = 1, 2, 4, 8
+FLAG_TOPK_CERT, FLAG_SOFTMAX_CERT, FLAG_FALLBACK, FLAG_INVALID_INPUT, FLAG_SOFTMAX_RELAXED = 1, 2, 4, 8, 16
 COMBINE_ALL, COMBINE_ANY = 0, 1
 MAX_K, MAX_CLUSTERS, MAX_BATCH = 1024, 8192, 256
 
 EXPORTS = [
     "csv_build_index", "csv_index_from_arrays", "csv_index_export", "csv_index_dims", "csv_index_free",
     "csv_workspace_create", "csv_workspace_free", "csv_decode_step", "csv_bounds", "csv_full_logits",
-    "csv_profile_begin", "csv_profile_end", "csv_last_error",
+    "csv_profile_begin", "csv_profile_end", "csv_last_error", "csv_kmax_init", "csv_kmax_update",
 ]
 PROFILE_STAGES = ["bounds", "round0", "tail"]
 
@@ -33,7 +33,13 @@ class BuildOpts(C.Structure):
 
 
 class StepParams(C.Structure):
-    _fields_ = [("k", C.c_int), ("eps", C.c_float), ("K_max_rows", C.c_int), ("combine", C.c_int)]
+    _fields_ = [("k", C.c_int), ("eps", C.c_float), ("K_max_rows", C.c_int), ("combine", C.c_int),
+                ("max_rounds", C.c_int), ("delta_clusters", C.c_int), ("relax", C.c_int)]
+
+
+class KmaxCtl(C.Structure):
+    _fields_ = [("K_max", C.c_double), ("alpha", C.c_double), ("rho_target", C.c_double), ("K_min", C.c_int),
+                ("K_cap", C.c_int), ("literal", C.c_int)]
 
 
 class StepOut(C.Structure):
@@ -63,6 +69,8 @@ def _load() -> C.CDLL:
     lib.csv_full_logits.argtypes = [vp, vp, vp, ci, vp, vp]
     lib.csv_profile_begin.argtypes = [vp, ci]
     lib.csv_profile_end.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(ci)]
+    lib.csv_kmax_init.argtypes = [C.POINTER(KmaxCtl), ci, ci, ci, C.c_double, C.c_double, ci]
+    lib.csv_kmax_update.argtypes = [C.POINTER(KmaxCtl), ci, ci]
     return lib
 
 
@@ -216,7 +224,8 @@ class StepBuffers:
 
 
 def make_step_buffers(index: CsvIndex, B: int, k: int, eps: float, K_max_rows: int, combine: int = COMBINE_ALL,
-                      want_sel: bool = False, device="cuda") -> StepBuffers:
+                      want_sel: bool = False, device="cuda", max_rounds: int = 0, delta_clusters: int = 0,
+                      relax: bool = False) -> StepBuffers:
     kk = max(k, 1)
     ids = torch.full((B, kk), -2, dtype=torch.int32, device=device)
     logits = torch.zeros((B, kk), dtype=torch.float32, device=device)
@@ -227,7 +236,8 @@ def make_step_buffers(index: CsvIndex, B: int, k: int, eps: float, K_max_rows: i
     rounds = torch.zeros(B, dtype=torch.int32, device=device)
     sel = torch.full((B, index.C), -1, dtype=torch.int32, device=device) if want_sel else None
     fbc = torch.zeros(1, dtype=torch.int64, device=device)
-    params = StepParams(k=k, eps=eps, K_max_rows=K_max_rows, combine=combine)
+    params = StepParams(k=k, eps=eps, K_max_rows=K_max_rows, combine=combine, max_rounds=max_rounds,
+                        delta_clusters=delta_clusters, relax=int(bool(relax)))
     out = StepOut(ids.data_ptr(), logits.data_ptr(), lse.data_ptr(), flags.data_ptr(), n_rows.data_ptr(),
                   n_clusters.data_ptr(), rounds.data_ptr(), sel.data_ptr() if want_sel else None, fbc.data_ptr())
     return StepBuffers(ids, logits, lse, flags, n_rows, n_clusters, rounds, sel, fbc, params, out)
@@ -270,3 +280,21 @@ def bits_to_device(bits) -> torch.Tensor:
     """numpy uint16 bf16 patterns -> CUDA int16 tensor with the same bits."""
     import numpy as np
     return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda()
+
+
+class KmaxController:
+    """Host-side adaptive row budget (csv_kmax_init / csv_kmax_update)."""
+
+    def __init__(self, K0: int, K_min: int, K_cap: int, alpha: float = 0.01, rho_target: float = 0.02, literal: bool = False):
+        self.ctl = KmaxCtl()
+        _check(lib.csv_kmax_init(C.byref(self.ctl), K0, K_min, K_cap, alpha, rho_target, int(literal)))
+
+    def update(self, n_fallback: int, n_sequences: int) -> int:
+        rc = lib.csv_kmax_update(C.byref(self.ctl), n_fallback, n_sequences)
+        if rc < 0:
+            raise CsvError(rc)
+        return rc
+
+    @property
+    def value(self) -> float:
+        return self.ctl.K_max

@@ -63,7 +63,9 @@ struct StepArgs {
     float* cand_sum;
     const uint16_t* h;
     int k, K_max, combine, use_k, use_s;
+    int max_rounds, delta_clusters, relax;   // fallback levels
     float lam;   // ln(eps/(1-eps)); +inf when eps >= 1
+    float lam2;  // the same for the relaxed tolerance 2 eps
     csv_step_out out;
 #ifdef CSV_DEBUG_TIMING
     unsigned long long* dbg;   // [B*64] wall-clock marks of the per-sequence kernels (debug builds only)
@@ -591,7 +593,7 @@ __device__ __forceinline__ void block_excl_scan3(int& v0, int& v1, int& v2, int*
 }
 
 // Opens every cluster c with flag(c): its rows get consecutive positions from pos_base on (cluster id order), its
-// row tiles go to the sequence's region of the round's work list, its id is appended to the sequence's list of
+// row tiles go to the sequence's region of the round's work list (two lists, used by even and odd rounds), its id is appended to the sequence's list of
 // opened clusters.  All threads of the block call; flag must be the same function of c in both passes.
 template <class FlagFn>
 __device__ __forceinline__ void emit_clusters(const StepArgs& a, int b, int round, int pos_base, int sel_base, FlagFn flag,
@@ -614,7 +616,7 @@ __device__ __forceinline__ void emit_clusters(const StepArgs& a, int b, int roun
         s.nbig = 0;
     }
     __syncthreads();
-    Tile* tl = a.tiles[round] + (size_t)b * a.tile_stride;
+    Tile* tl = a.tiles[round & 1] + (size_t)b * a.tile_stride;
     int tb = tiles, pos = pos_base + rows, si = sel_base + cnt;
     for (int c = c0; c < c1; ++c)
         if (flag(c)) {
@@ -721,7 +723,7 @@ __device__ __forceinline__ void gemv_tiles_device(const StepArgs& a, int round, 
     }
     const int total = gs.pre[a.B];
     const int nch = a.d >> 3;
-    const Tile* tl = a.tiles[round];
+    const Tile* tl = a.tiles[round & 1];
     int cur_b = -1;
     for (int g = block; g < total; g += nblocks) {
         int lo = 0, hi = a.B;   // largest b with pre[b] <= g
@@ -1198,7 +1200,7 @@ __device__ __forceinline__ void cert_body(const StepArgs& a, int b, int chunk, i
     else
         ok = (tk && a.use_k) || (sm && a.use_s);
 
-    if (ok) {
+    auto finish = [&](unsigned flags) {
         for (int t = tid; t < a.k; t += nt) {
             a.out.d_ids[(size_t)b * a.k + t] = s.wid[t];
             a.out.d_logits[(size_t)b * a.k + t] = s.wval[t];
@@ -1207,62 +1209,102 @@ __device__ __forceinline__ void cert_body(const StepArgs& a, int b, int chunk, i
             for (int j = tid; j < st.n_open; j += nt) a.out.d_sel_clusters[(size_t)b * C + j] = a.sel[(size_t)b * C + j];
         if (tid == 0) {
             a.out.d_lse[b] = Z;
-            a.out.d_flags[b] = ((tk && a.use_k) ? CSV_FLAG_TOPK_CERT : 0u) | ((sm && a.use_s) ? CSV_FLAG_SOFTMAX_CERT : 0u);
+            a.out.d_flags[b] = flags;
             a.out.d_n_rows[b] = n;
             a.out.d_n_clusters[b] = st.n_open;
             if (a.out.d_rounds) a.out.d_rounds[b] = round + 1;
             a.st[b].status = ST_DONE;
         }
+    };
+    if (ok) {
+        finish(((tk && a.use_k) ? CSV_FLAG_TOPK_CERT : 0u) | ((sm && a.use_s) ? CSV_FLAG_SOFTMAX_CERT : 0u));
         return;
     }
-    if (round == 1) {
-        if (tid == 0) push_fallback(a, b, 2);
-        return;
-    }
-    // ---- plan round 1: the open set grows from {key >= kappa0} to {key >= kappa1}
-    __syncthreads();                                   // the staged logits are dead; the arena is reused
-    const ClusterLds L = carve_clusters(arena, a.Npad, C);
-    const u64 kappa0 = st.kappa;
-    u64 kappa_a = kappa0, kappa_s = kappa0;
-    if (a.use_k && !tk) kappa_a = (u64)lkey(theta) << 32;                 // every cluster with U_c >= theta0
-    if (a.use_s && !sm) {
+    if (round + 1 < a.max_rounds) {
+        // ---- plan the next round: the open set grows from {key >= kappa0} to {key >= kappa1}
+        __syncthreads();                                   // the staged logits are dead; the arena is reused
+        const ClusterLds L = carve_clusters(arena, a.Npad, C);
+        const u64 kappa0 = st.kappa;
+        u64 kappa_a = kappa0, kappa_s = kappa0;
+        if (a.use_k && !tk) kappa_a = (u64)lkey(theta) << 32;                 // every cluster with U_c >= theta
+        if (a.use_s && !sm) {
+            load_clusters(a, b, L);
+            __syncthreads();
+            kappa_s = softmax_prefix_key(a, L, st.n_open, Z, s);
+            __syncthreads();
+        }
+        u64 kappa1;
+        if (a.use_k && a.use_s)
+            kappa1 = a.combine == CSV_COMBINE_ALL ? (kappa_a < kappa_s ? kappa_a : kappa_s) : (kappa_a > kappa_s ? kappa_a : kappa_s);
+        else
+            kappa1 = a.use_k ? kappa_a : kappa_s;
         load_clusters(a, b, L);
         __syncthreads();
-        kappa_s = softmax_prefix_key(a, L, st.n_open, Z, s);
-        __syncthreads();
-    }
-    u64 kappa1;
-    if (a.use_k && a.use_s)
-        kappa1 = a.combine == CSV_COMBINE_ALL ? (kappa_a < kappa_s ? kappa_a : kappa_s) : (kappa_a > kappa_s ? kappa_a : kappa_s);
-    else
-        kappa1 = a.use_k ? kappa_a : kappa_s;
-    load_clusters(a, b, L);
-    __syncthreads();
-    auto isnew = [&](int c) { const u64 kx = L.keys[c]; return kx >= kappa1 && kx < kappa0 && kx != 0; };
-    int cnt = 0, rows = 0;
-    for (int c = tid; c < C; c += nt)
-        if (isnew(c)) {
-            cnt += 1;
-            rows += L.offl[c + 1] - L.offl[c];
+        int cnt = 0, rows = 0;
+        for (int c = tid; c < C; c += nt) {
+            const u64 kx = L.keys[c];
+            if (kx >= kappa1 && kx < kappa0 && kx != 0) {
+                cnt += 1;
+                rows += L.offl[c + 1] - L.offl[c];
+            }
         }
-    cnt = block_sum_i(cnt, s.redi);
-    rows = block_sum_i(rows, s.redi);
-    if (n + rows > a.K_max) {
-        if (tid == 0) {
-            a.st[b].n_open = st.n_open + cnt;
-            a.st[b].n_rows = n + rows;
-            push_fallback(a, b, 1);
+        cnt = block_sum_i(cnt, s.redi);
+        rows = block_sum_i(rows, s.redi);
+        bool expand = n + rows <= a.K_max;
+        if (!expand) {
+            if (tid == 0) {          // sizes of the plan that did not fit (reported if the sequence falls back)
+                a.st[b].n_open = st.n_open + cnt;
+                a.st[b].n_rows = n + rows;
+            }
+            // partial expansion: the next clusters of the bound order, at most delta_clusters of them, not past
+            // the planned set, while the rows stay within the budget
+            u64 kp = kappa0;
+            int add = 0, radd = 0;
+            for (int i = 0; i < a.delta_clusters; ++i) {
+                u64 best = 0;
+                for (int c = tid; c < C; c += nt) {
+                    const u64 kx = L.keys[c];
+                    if (kx < kp && kx > best) best = kx;
+                }
+                best = block_max_u64(best, s.redu);
+                if (best == 0 || best < kappa1) break;
+                const int cw = (int)(0xFFFFFFFFu - (uint32_t)best);
+                const int nr = L.offl[cw + 1] - L.offl[cw];
+                if (n + radd + nr > a.K_max) break;
+                kp = best;
+                add += 1;
+                radd += nr;
+            }
+            if (add > 0) {
+                kappa1 = kp;
+                cnt = add;
+                rows = radd;
+                expand = true;
+            }
         }
-        return;
+        if (expand) {
+            auto isnew = [&](int c) { const u64 kx = L.keys[c]; return kx >= kappa1 && kx < kappa0 && kx != 0; };
+            float nxtU, T1;
+            tail_stats(a, L, kappa1, s, nxtU, T1);
+            emit_clusters(a, b, round + 1, n, st.n_open, isnew, L, s);
+            if (tid == 0) {
+                SeqState o = st;
+                o.n_open = st.n_open + cnt; o.n_rows = n + rows; o.rounds = round + 1; o.kappa = kappa1; o.nxtU = nxtU; o.T = T1;
+                a.st[b] = o;
+            }
+            return;
+        }
     }
-    float nxtU, T1;
-    tail_stats(a, L, kappa1, s, nxtU, T1);
-    emit_clusters(a, b, 1, n, st.n_open, isnew, L, s);
-    if (tid == 0) {
-        SeqState o = st;
-        o.n_open = st.n_open + cnt; o.n_rows = n + rows; o.rounds = 1; o.kappa = kappa1; o.nxtU = nxtU; o.T = T1;
-        a.st[b] = o;
+    // ---- no further expansion: the relaxed tolerance, then the full vocabulary
+    if (a.relax && a.use_s) {
+        const bool sm2 = (st.T - Z <= a.lam2) || (st.T == -INFINITY);
+        const bool ok2 = a.combine == CSV_COMBINE_ALL ? ((tk || !a.use_k) && sm2) : ((tk && a.use_k) || sm2);
+        if (ok2) {
+            finish(((tk && a.use_k) ? CSV_FLAG_TOPK_CERT : 0u) | (sm ? CSV_FLAG_SOFTMAX_CERT : (sm2 ? CSV_FLAG_SOFTMAX_RELAXED : 0u)));
+            return;
+        }
     }
+    if (tid == 0) push_fallback(a, b, round + 1);
 }
 
 __device__ __forceinline__ void cert_device(const StepArgs& a, int b, int chunk, int round, SeqShared& s) {
@@ -1779,34 +1821,31 @@ __global__ __launch_bounds__(TAIL_THREADS, 2) void tail_kernel(StepArgs a, FullA
     }
     const int n_fb0 = a.counters[CNT_FALLBACK];
     const int tiles0 = block_sum_i(mine0, s.redi);
-    int tiles1 = block_sum_i(mine1, s.redi);
-    if (tiles0 == 0 && tiles1 == 0 && n_fb0 == 0) return;
+    int tiles = block_sum_i(mine1, s.redi);
+    if (tiles0 == 0 && tiles == 0 && n_fb0 == 0) return;
     if (block == 0) DBG_T(20);
 
-    if (tiles0 > 0) {
-        gemv_tiles_device<1>(a, 0, reinterpret_cast<uint4*>(arena), gs, block, nblocks);
-        if (!grid_barrier(a.counters, 4, nblocks, &s_flag)) return;
+    // Rounds: the GEMV over the round's work list, then the certification, which may plan the next round.
+    // Round 0 is here only for seed prefixes that the round-0 kernel handed over.
+    for (int r = tiles0 > 0 ? 0 : 1; r < a.max_rounds; ++r) {
+        if (r > 0) {
+            if (r > 1 || tiles0 > 0) {   // planned by a certification earlier in this kernel: read past the barrier
+                const int mine = tid < a.B ? __hip_atomic_load(&a.counters[CNT_TILES + r * CSV_MAX_BATCH + tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0;
+                tiles = block_sum_i(mine, s.redi);
+            }
+            if (tiles == 0) break;
+        }
+        gemv_tiles_device<1>(a, r, reinterpret_cast<uint4*>(arena), gs, block, nblocks);
+        if (block == 0 && r == 1) DBG_T(21);
+        if (!grid_barrier(a.counters, 2 * r, nblocks, &s_flag)) return;
+        if (block == 0 && r == 1) DBG_T(22);
         for (int item = block; item < a.B * a.sp_chunks; item += nblocks) {
-            cert_device(a, item / a.sp_chunks, item % a.sp_chunks, 0, s);
+            cert_device(a, item / a.sp_chunks, item % a.sp_chunks, r, s);
             __syncthreads();
         }
-        if (!grid_barrier(a.counters, 5, nblocks, &s_flag)) return;
-        // the round-0 certification may have planned round 1 for these sequences
-        mine1 = tid < a.B ? __hip_atomic_load(&a.counters[CNT_TILES + CSV_MAX_BATCH + tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0;
-        tiles1 = block_sum_i(mine1, s.redi);
-    }
-    if (tiles1 > 0) {
-        gemv_tiles_device<1>(a, 1, reinterpret_cast<uint4*>(arena), gs, block, nblocks);
-        if (block == 0) DBG_T(21);
-        if (!grid_barrier(a.counters, 0, nblocks, &s_flag)) return;
-        if (block == 0) DBG_T(22);
-        for (int item = block; item < a.B * a.sp_chunks; item += nblocks) {
-            cert_device(a, item / a.sp_chunks, item % a.sp_chunks, 1, s);
-            __syncthreads();
-        }
-        if (block == 0) DBG_T(23);
-        if (!grid_barrier(a.counters, 1, nblocks, &s_flag)) return;
-        if (block == 0) DBG_T(24);
+        if (block == 0 && r == 1) DBG_T(23);
+        if (!grid_barrier(a.counters, 2 * r + 1, nblocks, &s_flag)) return;
+        if (block == 0 && r == 1) DBG_T(24);
     }
     const int n_fb = __hip_atomic_load(&a.counters[CNT_FALLBACK], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
     if (n_fb == 0) return;
@@ -1815,14 +1854,14 @@ __global__ __launch_bounds__(TAIL_THREADS, 2) void tail_kernel(StepArgs a, FullA
     else
         full_gemv_device(f, n_fb, reinterpret_cast<uint4*>(arena), block, nblocks);
     if (block == 0) DBG_T(25);
-    if (!grid_barrier(a.counters, 2, nblocks, &s_flag)) return;
+    if (!grid_barrier(a.counters, 2 * CSV_MAX_ROUNDS, nblocks, &s_flag)) return;
     if (block == 0) DBG_T(26);
     for (int item = block; item < n_fb * a.n_chunks; item += nblocks) {
         fb_topk_device(a, item / a.n_chunks, item % a.n_chunks, s);
         __syncthreads();
     }
     if (block == 0) DBG_T(27);
-    if (!grid_barrier(a.counters, 3, nblocks, &s_flag)) return;
+    if (!grid_barrier(a.counters, 2 * CSV_MAX_ROUNDS + 1, nblocks, &s_flag)) return;
     if (block == 0) DBG_T(28);
     for (int slot = block; slot < n_fb; slot += nblocks) {
         fb_final_device(a, slot, s);
@@ -2075,6 +2114,9 @@ extern "C" int csv_decode_step(csv_workspace* ws, const csv_index* idx, const ui
     if (p->k < 0 || p->k > CSV_MAX_K || p->k > idx->V) { csv_set_error("k=%d outside 0..min(V,%d)", p->k, CSV_MAX_K); return CSV_EINVAL; }
     if (p->K_max_rows < 0 || p->K_max_rows > ws->K_cap) { csv_set_error("K_max_rows=%d exceeds workspace capacity %d", p->K_max_rows, ws->K_cap); return CSV_EINVAL; }
     if (p->combine != CSV_COMBINE_ALL && p->combine != CSV_COMBINE_ANY) { csv_set_error("bad combine=%d", p->combine); return CSV_EINVAL; }
+    const int max_rounds = p->max_rounds == 0 ? 2 : p->max_rounds;
+    if (max_rounds < 2 || max_rounds > CSV_MAX_ROUNDS) { csv_set_error("max_rounds=%d outside 2..%d", p->max_rounds, CSV_MAX_ROUNDS); return CSV_EINVAL; }
+    if (p->delta_clusters < 0) { csv_set_error("delta_clusters=%d is negative", p->delta_clusters); return CSV_EINVAL; }
     if (!o->d_lse || !o->d_flags || !o->d_n_rows || !o->d_n_clusters || (use_k && (!o->d_ids || !o->d_logits))) {
         csv_set_error("null output buffer");
         return CSV_EINVAL;
@@ -2086,6 +2128,10 @@ extern "C" int csv_decode_step(csv_workspace* ws, const csv_index* idx, const ui
     if (!use_s) a.lam = -INFINITY;
     else if (p->eps >= 1.f) a.lam = INFINITY;
     else a.lam = (float)log((double)p->eps / (1.0 - (double)p->eps));
+    a.max_rounds = max_rounds; a.delta_clusters = p->delta_clusters; a.relax = p->relax != 0;
+    if (!use_s) a.lam2 = -INFINITY;
+    else if (2.0 * (double)p->eps >= 1.0) a.lam2 = INFINITY;
+    else a.lam2 = (float)log(2.0 * (double)p->eps / (1.0 - 2.0 * (double)p->eps));
     a.out = *o;
 #ifdef CSV_DEBUG_TIMING
     if (!g_dbg) CSV_HIP(hipMalloc((void**)&g_dbg, CSV_MAX_BATCH * 64 * 8));
@@ -2169,4 +2215,26 @@ extern "C" int csv_profile_end(csv_workspace* ws, float* h_stage_ms, int* h_step
     }
     profile_release(ws);
     return rc;
+}
+
+// ------------------------------------------------------------------------------------------------ adaptive budget
+extern "C" int csv_kmax_init(csv_kmax_ctl* c, int K0, int K_min, int K_cap, double alpha, double rho_target, int literal) {
+    if (!c) { csv_set_error("null controller"); return CSV_EINVAL; }
+    if (K_min < 0 || K_cap < K_min || K0 < K_min || K0 > K_cap) { csv_set_error("need 0 <= K_min <= K0 <= K_cap (got %d, %d, %d)", K_min, K0, K_cap); return CSV_EINVAL; }
+    if (!(alpha >= 0.0) || !(rho_target >= 0.0 && rho_target <= 1.0)) { csv_set_error("bad alpha=%g or rho_target=%g", alpha, rho_target); return CSV_EINVAL; }
+    c->K_max = (double)K0; c->alpha = alpha; c->rho_target = rho_target; c->K_min = K_min; c->K_cap = K_cap; c->literal = literal != 0;
+    return CSV_OK;
+}
+
+extern "C" int csv_kmax_update(csv_kmax_ctl* c, int n_fallback, int n_sequences) {
+    if (!c) { csv_set_error("null controller"); return CSV_EINVAL; }
+    if (n_sequences < 1 || n_fallback < 0 || n_fallback > n_sequences) { csv_set_error("bad counts %d of %d", n_fallback, n_sequences); return CSV_EINVAL; }
+    const double rho = (double)n_fallback / (double)n_sequences;
+    const double err = c->literal ? (c->rho_target - rho) : (rho - c->rho_target);
+    double K = c->K_max * (1.0 + c->alpha * err);
+    // the state itself stays inside the range, so a long run at one end does not have to be unwound
+    if (K < (double)c->K_min) K = (double)c->K_min;
+    if (K > (double)c->K_cap) K = (double)c->K_cap;
+    c->K_max = K;
+    return (int)floor(K);
 }

@@ -19,13 +19,15 @@ def log(msg: str) -> None:
 
 class Case:
     def __init__(self, recipe: synth.Recipe, seed: int = synth.SEED, bias: bool = True, radius_slack: float = 2.0 ** -14,
-                 labels=None, B_max=None, K_cap=None, want_W64: bool = True):
+                 labels=None, B_max=None, K_cap=None, want_W64: bool = True, W_bits=None):
         import torch
         import paper_2511_21702_amd as csv
         self.csv, self.torch = csv, torch
         self.r = recipe
         t0 = time.time()
         self.head = synth.make_head(recipe, seed=seed, threads=16)
+        if W_bits is not None:                      # a hand-made matrix in place of the generated one
+            self.head = dict(self.head, W_bits=np.ascontiguousarray(W_bits))
         self.b = self.head["b"] if bias else None
         self.labels = self.head["labels"] if labels is None else labels
         self.C = recipe.C if labels is None else int(np.max(labels)) + 1
@@ -45,13 +47,14 @@ class Case:
         return synth.make_hidden(self.r, self.head["centers"], steps=steps, seed=seed)
 
     def run_steps(self, h_bits: np.ndarray, k: int, eps: float, K_max: int, combine: int, tag: str, tally=None,
-                  step_ids=None) -> PAR.Tally:
+                  step_ids=None, max_rounds: int = 2, delta_clusters: int = 0, relax: bool = False) -> PAR.Tally:
         """h_bits [steps,B,d].  Runs every step on the GPU; compares the steps in step_ids (default all) with the oracle."""
         csv, torch = self.csv, self.torch
         steps, B, d = h_bits.shape
         t = tally or PAR.Tally()
         dh = csv.bits_to_device(h_bits)
-        buf = csv.make_step_buffers(self.gidx, B, k, eps, K_max, combine, want_sel=True)
+        buf = csv.make_step_buffers(self.gidx, B, k, eps, K_max, combine, want_sel=True, max_rounds=max_rounds,
+                                    delta_clusters=delta_clusters, relax=relax)
         step_ids = list(range(steps)) if step_ids is None else list(step_ids)
         outs = []
         for s in step_ids:
@@ -65,7 +68,8 @@ class Case:
             h64 = O.bf16_to_f64(h_bits[ids].reshape(-1, d))
             Lall = O.full_logits(self.W64, self.b, h64).reshape(len(ids), B, -1)
             for j, s in enumerate(ids):
-                orc = O.decode_step(self.W64, self.b, self.oidx, h_bits[s], k, eps, K_max, combine, logits=Lall[j])
+                orc = O.decode_step(self.W64, self.b, self.oidx, h_bits[s], k, eps, K_max, combine, logits=Lall[j],
+                                    max_rounds=max_rounds, delta_clusters=delta_clusters, relax=relax)
                 PAR.compare_step(f"{tag} step={s}", t, orc, outs[g0 + j], Lall[j], self.oidx, k, eps, K_max, combine)
             log(f"[{tag}] compared steps {ids[0]}..{ids[-1]}: {t.summary()}")
         return t

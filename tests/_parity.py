@@ -30,10 +30,12 @@ class Tally:
         self.fallbacks = 0
         self.rows = 0
         self.n = 0
+        self.relaxed = 0          # sequences accepted at the relaxed tolerance
+        self.late_rounds = 0      # sequences that went through more than two scoring rounds
 
     def summary(self) -> str:
         return (f"exact={self.exact} in-band={self.inband} id-ties={self.id_ties} mismatch={len(self.mismatch)} "
-                f"fallback={self.fallbacks}/{self.n} mean_rows={self.rows / max(self.n, 1):.1f} "
+                f"fallback={self.fallbacks}/{self.n} relaxed={self.relaxed} late={self.late_rounds} mean_rows={self.rows / max(self.n, 1):.1f} "
                 f"max_logit_err={self.max_logit_err:.2e} max_lse_err={self.max_lse_err:.2e}")
 
 
@@ -83,6 +85,8 @@ def compare_step(tag: str, t: Tally, orc: list, gpu: dict, L: np.ndarray, index:
         t.fallbacks += g_fb
         g_rows, g_ncl, g_rounds = int(gpu["n_rows"][b]), int(gpu["n_clusters"][b]), int(gpu["rounds"][b])
         t.rows += g_rows
+        t.relaxed += bool(gf & O.FLAG_SOFTMAX_RELAXED)
+        t.late_rounds += g_rounds > 2
         same_dec = (gf == r["flags"] and g_rows == r["n_rows"] and g_ncl == r["n_clusters"] and g_rounds == r["rounds"])
         if g_fb:
             S_rows = None
@@ -134,6 +138,12 @@ def compare_step(tag: str, t: Tally, orc: list, gpu: dict, L: np.ndarray, index:
             p_out = float(np.exp(Lrow[~inS] - O.logsumexp(Lrow)).sum())
             if p_out > eps * (1 + 1e-6):
                 t.mismatch.append(f"{tg}: softmax certificate set but outside mass {p_out:.3e} > eps")
+                continue
+        if (gf & O.FLAG_SOFTMAX_RELAXED) and eps < 0.5:
+            inS = np.zeros(index.V, bool); inS[S_rows] = True
+            p_out = float(np.exp(Lrow[~inS] - O.logsumexp(Lrow)).sum())
+            if g_fb or (gf & O.FLAG_SOFTMAX_CERT) or p_out > 2 * eps * (1 + 1e-6):
+                t.mismatch.append(f"{tg}: relaxed flag set but flags={gf}, outside mass {p_out:.3e} vs 2 eps")
                 continue
         if same_dec:
             if ids_same:

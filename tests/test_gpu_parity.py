@@ -113,6 +113,86 @@ def test_step_budget_extremes_and_counter():
     case.close()
 
 
+# ------------------------------------------------------------------ fallback levels (Section IV)
+LADDERS = [
+    ("rounds6-delta2-relax", dict(max_rounds=6, delta_clusters=2, relax=True)),
+    ("rounds4-delta1", dict(max_rounds=4, delta_clusters=1, relax=False)),
+    ("relax-only", dict(max_rounds=2, delta_clusters=0, relax=True)),
+    ("rounds8-delta64", dict(max_rounds=8, delta_clusters=64, relax=False)),
+]
+
+
+@pytest.mark.parametrize("name,lad", LADDERS)
+def test_step_fallback_levels(name, lad):
+    # overlapping clusters (row noise half the centre scale) and budgets tight enough that plans overflow: the levels
+    # run through several partial expansions; most such steps still end in the full vocabulary, a few are rescued
+    seen = relaxed = late = fb = fb_plain = 0
+    for mode in ("single", "mix"):
+        r = synth.small_recipe("ladder-" + mode, V=6000, d=136, C=60, B=3, steps=10, k=8, eps=2e-3, h_mode=mode,
+                               sizes="zipf", row_noise=2.0)
+        case = Case(r, seed=21, K_cap=6000)
+        h = case.hidden()
+        for K_max in (600, 1500, 3000):
+            for k, eps, comb in ((r.k, r.eps, O.COMBINE_ALL), (r.k, r.eps, O.COMBINE_ANY), (0, r.eps, O.COMBINE_ALL)):
+                t = case.run_steps(h, k, eps, K_max, comb, f"{name} {mode} K={K_max} k={k} c={comb}", **lad)
+                _finish(t, f"{name} K={K_max}")
+                seen, relaxed, late, fb = seen + t.n, relaxed + t.relaxed, late + t.late_rounds, fb + t.fallbacks
+                t0 = case.run_steps(h, k, eps, K_max, comb, f"plain {mode} K={K_max} k={k} c={comb}")
+                _finish(t0, f"plain K={K_max}")
+                fb_plain += t0.fallbacks
+        case.close()
+    log(f"[{name}] sequences {seen}: relaxed {relaxed}, more than two rounds {late}, fallbacks {fb} (plain schedule: {fb_plain})")
+    assert seen == 2 * 3 * 3 * 30 and fb <= fb_plain and fb_plain > 0
+    if lad["relax"] and lad["delta_clusters"] > 0:
+        assert relaxed > 0 and fb < fb_plain
+    if lad["max_rounds"] > 2 and lad["delta_clusters"] <= 2:    # a large Delta C fills the budget in one expansion
+        assert late > 0
+
+
+def test_step_fallback_levels_hand_traced_case():
+    # the d = 1 example of the oracle pins, padded to d = 8: k = 2, budget 6 rows, Delta C = 1 rescues the step
+    clusters = [[10, 1], [9, 8.5], [8.5625, 0], [2, 1.5], [1.25, 1.125]]
+    vals = np.array([v for c in clusters for v in c], dtype=np.float32)
+    labels = np.array([i for i, c in enumerate(clusters) for _ in c], dtype=np.int64)
+    W = np.zeros((vals.size, 8), dtype=np.float32)
+    W[:, 0] = vals
+    hvec = np.zeros((1, 1, 8), dtype=np.float32)
+    hvec[0, 0, 0] = 1.0
+    r = synth.small_recipe("traced", V=vals.size, d=8, C=len(clusters), B=1, steps=1)
+    case = Case(r, seed=1, bias=False, labels=labels, K_cap=vals.size, W_bits=synth.f32_to_bf16_bits(W))
+    h = synth.f32_to_bf16_bits(hvec)
+    t = case.run_steps(h, 2, -1.0, 6, O.COMBINE_ALL, "traced plain")
+    _finish(t, "traced plain")
+    assert t.fallbacks == 1
+    csv = case.csv
+    buf = csv.make_step_buffers(case.gidx, 1, 2, -1.0, 6, max_rounds=4, delta_clusters=1)
+    csv.csv_decode_step(case.ws, case.gidx, csv.bits_to_device(h[0]), buf)
+    torch.cuda.synchronize()
+    assert int(buf.flags[0]) == csv.FLAG_TOPK_CERT and int(buf.rounds[0]) == 2 and int(buf.n_rows[0]) == 4
+    assert buf.ids[0].tolist() == [0, 2] and buf.logits[0].tolist() == [10.0, 9.0]
+    t = case.run_steps(h, 2, -1.0, 6, O.COMBINE_ALL, "traced ladder", max_rounds=4, delta_clusters=1)
+    _finish(t, "traced ladder")
+    assert t.fallbacks == 0
+    case.close()
+
+    # relaxed tolerance, traced by hand in the oracle pins: S = {5, 5}, outside {0, 0}, eps = 0.005, budget 2 rows
+    vals = np.array([5, 5, 0, 0], dtype=np.float32)
+    W = np.zeros((4, 8), dtype=np.float32)
+    W[:, 0] = vals
+    r = synth.small_recipe("traced-relax", V=4, d=8, C=2, B=1, steps=1)
+    case = Case(r, seed=1, bias=False, labels=np.array([0, 0, 1, 1]), K_cap=4, W_bits=synth.f32_to_bf16_bits(W))
+    t = case.run_steps(h, 0, 0.005, 2, O.COMBINE_ALL, "traced strict")
+    _finish(t, "traced strict")
+    assert t.fallbacks == 1
+    t = case.run_steps(h, 0, 0.005, 2, O.COMBINE_ALL, "traced relaxed", relax=True)
+    _finish(t, "traced relaxed")
+    assert t.fallbacks == 0 and t.relaxed == 1
+    t = case.run_steps(h, 0, 0.005, 4, O.COMBINE_ALL, "traced roomy", relax=True)
+    _finish(t, "traced roomy")
+    assert t.fallbacks == 0 and t.relaxed == 0
+    case.close()
+
+
 def test_step_zipf_sizes_no_bias_ragged_batch():
     r = synth.small_recipe("zipf", V=6000, d=520, C=48, B=7, steps=4, sizes="zipf", h_mode="mix", k=20, eps=1e-4)
     case = Case(r, seed=13, bias=False)
@@ -156,6 +236,9 @@ def test_argument_errors():
         csv.csv_decode_step(case.ws, case.gidx, dh, csv.make_step_buffers(case.gidx, 2, 5, 1e-3, r.V))     # budget > capacity
     with pytest.raises(csv.CsvError):
         csv.csv_decode_step(case.ws, case.gidx, dh, csv.make_step_buffers(case.gidx, 2, 2000, 1e-3, 10))   # k > V
+    for bad in (dict(max_rounds=1), dict(max_rounds=9), dict(delta_clusters=-1)):                          # fallback levels
+        with pytest.raises(csv.CsvError):
+            csv.csv_decode_step(case.ws, case.gidx, dh, csv.make_step_buffers(case.gidx, 2, 5, 1e-3, 10, **bad))
     with pytest.raises(csv.CsvError):
         csv.CsvWorkspace(case.gidx, 1000, 10)                                                              # B_max too large
     case.close()

@@ -42,3 +42,34 @@ def test_host_side_argument_checks_need_no_gpu():
     assert lib.csv_decode_step(None, None, None, 1, None, None, None) == -1
     assert b"null" in lib.csv_last_error()
     assert lib.csv_index_dims(None, None, None, None) == -1
+
+
+def test_kmax_controller_matches_the_oracle_update():
+    """Host logic only: the C controller against oracle.kmax_update over a seeded run of fallback counts."""
+    import numpy as np
+    _lib()
+    import paper_2511_21702_amd as csv
+    from oracle import csv_oracle as O
+    rng = np.random.default_rng(5)
+    for literal in (False, True):
+        ctl = csv.KmaxController(K0=32064, K_min=1000, K_cap=128256, alpha=0.01, rho_target=0.02, literal=literal)
+        K = 32064.0
+        for _ in range(500):
+            B = int(rng.integers(1, 65))
+            nfb = int(rng.binomial(B, 0.1))
+            got = ctl.update(nfb, B)
+            K = min(max(O.kmax_update(K, nfb / B, 0.01, 0.02, literal=literal), 1000.0), 128256.0)
+            assert got == O.kmax_rows(K, 1000, 128256)
+            assert abs(ctl.value - K) <= 1e-9 * K
+    # range clamps and argument errors
+    ctl = csv.KmaxController(K0=1000, K_min=1000, K_cap=1010, alpha=0.5, rho_target=0.02)
+    for _ in range(10):
+        v = ctl.update(4, 4)
+    assert v == 1010
+    lib = csv.lib
+    assert lib.csv_kmax_update(None, 0, 1) == -1
+    import ctypes as C
+    c = csv.KmaxCtl()
+    assert lib.csv_kmax_init(C.byref(c), 5, 10, 20, 0.01, 0.02, 0) == -1      # K0 below K_min
+    assert lib.csv_kmax_init(C.byref(c), 15, 10, 20, 0.01, 0.02, 0) == 0
+    assert lib.csv_kmax_update(C.byref(c), 3, 2) == -1                         # more fallbacks than sequences
