@@ -38,6 +38,9 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=512)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", default="c2")
+    ap.add_argument("--max-rounds", type=int, default=0, help="fallback levels: scoring rounds allowed (0 = the two-round schedule)")
+    ap.add_argument("--delta-clusters", type=int, default=0, help="fallback levels: clusters per partial expansion (0 = off)")
+    ap.add_argument("--relax", action="store_true", help="fallback levels: accept the softmax bound at 2 eps before falling back")
     ap.add_argument("--cpu-steps", type=int, default=-1, help="oracle steps to time (-1: sized to ~15 s, 0: skip)")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="for `rocprofv3 --pmc FETCH_SIZE|WRITE_SIZE`: launch a device-to-device copy of known size, "
@@ -67,7 +70,8 @@ def main() -> int:
     ws = csv.CsvWorkspace(idx, r.B, r.K_max_rows)
     dh = csv.bits_to_device(h_bits)
     nh = h_bits.shape[0]
-    buf = csv.make_step_buffers(idx, r.B, r.k, r.eps, r.K_max_rows)
+    lad = dict(max_rounds=args.max_rounds, delta_clusters=args.delta_clusters, relax=args.relax)
+    buf = csv.make_step_buffers(idx, r.B, r.k, r.eps, r.K_max_rows, **lad)
     stream = torch.cuda.current_stream()
     sp = stream.cuda_stream
     hp = [dh[s % nh].data_ptr() for s in range(max(K, W) + W)]
@@ -117,8 +121,9 @@ def main() -> int:
 
     # ---------------- statistics pass: per-step sync, latency percentiles, rows / fallbacks
     fb0 = int(buf.fallback_count.item())
-    lat, rows_sum, rows_union_sum, anyfb, ncl_sum, rounds_hist = [], 0, 0.0, 0, 0, {0: 0, 1: 0, 2: 0}
-    buf_s = csv.make_step_buffers(idx, r.B, r.k, r.eps, r.K_max_rows, want_sel=True)
+    lat, rows_sum, rows_union_sum, anyfb, ncl_sum, rounds_hist = [], 0, 0.0, 0, 0, {i: 0 for i in range(9)}
+    n_relaxed = 0
+    buf_s = csv.make_step_buffers(idx, r.B, r.k, r.eps, r.K_max_rows, want_sel=True, **lad)
     sizes = head["sizes"]
     nstat = min(K, 256)
     for s in range(W, W + nstat):
@@ -130,6 +135,7 @@ def main() -> int:
         nr = buf_s.n_rows.cpu().numpy()
         nc = buf_s.n_clusters.cpu().numpy()
         fb = (fl & csv.FLAG_FALLBACK) != 0
+        n_relaxed += int(((fl & csv.FLAG_SOFTMAX_RELAXED) != 0).sum())
         anyfb += bool(fb.any())
         rows_sum += int(nr[~fb].sum())
         ncl_sum += int(nc[~fb].sum())
@@ -232,12 +238,13 @@ def main() -> int:
         W64 = O.bf16_to_f64(head["W_bits"])
         oidx = O.build_index(head["W_bits"], head["b"], head["labels"], r.C)
         t1 = time.perf_counter()
-        O.decode_step(W64, head["b"], oidx, h_bits[0], r.k, r.eps, r.K_max_rows)
+        olad = dict(max_rounds=max(args.max_rounds, 2), delta_clusters=args.delta_clusters, relax=args.relax)
+        O.decode_step(W64, head["b"], oidx, h_bits[0], r.k, r.eps, r.K_max_rows, **olad)
         one = time.perf_counter() - t1
         n_cpu = args.cpu_steps if args.cpu_steps > 0 else int(max(1, min(64, 15.0 / max(one, 1e-3))))
         t1 = time.perf_counter()
         for s in range(n_cpu):
-            O.decode_step(W64, head["b"], oidx, h_bits[(1 + s) % nh], r.k, r.eps, r.K_max_rows)
+            O.decode_step(W64, head["b"], oidx, h_bits[(1 + s) % nh], r.k, r.eps, r.K_max_rows, **olad)
         cpu_s = time.perf_counter() - t1
         cpu = {"value": n_cpu / cpu_s, "unit": "steps/s", "cores": int(cores), "kind": "oracle",
                "sample": f"{n_cpu} consecutive batch steps of {r.name} (B={r.B}) through oracle.decode_step, float64, numpy/BLAS"}
@@ -249,7 +256,9 @@ def main() -> int:
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{r.name}: V={r.V} d={r.d} C={r.C} B={r.B} k={r.k} eps={r.eps:g} K_max={r.K_max_rows} "
-                               f"combine=ALL, bf16 W and h, planted clusters", "batch": r.B},
+                               f"combine=ALL, bf16 W and h, planted clusters"
+                               + (f", fallback levels max_rounds={args.max_rounds} delta_clusters={args.delta_clusters} relax={int(args.relax)}"
+                                  if (args.max_rounds or args.delta_clusters or args.relax) else ""), "batch": r.B},
         "roofline": {"bound": "hbm", "kernel": dom_name, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "bytes_per_launch": dom_bytes, "avg_launch_us": dom_us},
@@ -261,7 +270,8 @@ def main() -> int:
         "latency_us": {"p50": float(lat[len(lat) // 2] * 1e6), "p95": float(lat[int(len(lat) * 0.95)] * 1e6)},
         "fallback_rate": fb_rate, "steps_with_fallback": anyfb / nstat,
         "mean_rows_per_certified_seq": mean_rows_seq, "mean_clusters_per_certified_seq": ncl_sum / max(1, n_seq - int(round(fb_rate * n_seq))),
-        "sub_vocab_ratio": mean_rows_seq / r.V, "rounds_hist": rounds_hist,
+        "sub_vocab_ratio": mean_rows_seq / r.V, "rounds_hist": {k: v for k, v in rounds_hist.items() if v or k <= 2},
+        "relaxed_rate": n_relaxed / n_seq,
         "full_gemv": {"ms_per_step": full_ms, "steps_per_s": 1e3 / full_ms, "GBps": full_bytes / (full_ms * 1e-3) / 1e9},
         "speedup_vs_full_gemv": full_ms / ms_per_step,
     }
