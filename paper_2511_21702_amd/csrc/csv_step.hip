@@ -690,18 +690,19 @@ __device__ __forceinline__ void tail_stats(const StepArgs& a, const ClusterLds& 
 }
 
 // ================================================================================================ gathered GEMV
-// Work item = up to TILE_ROWS consecutive rows of W' for one sequence.  Each wave takes two rows and requests
-// their first 8 KB before the sequence's h is staged in LDS (bf16); 128-bit loads, float32 accumulation,
-// wave reduction.  Tiles of sequence b sit in its own region of the list; a prefix over the per-sequence
-// counts maps a global tile number to (sequence, tile).
-#define GEMV_PF 8
+// Work item = up to TILE_ROWS consecutive rows of W' for one sequence; one row per wave (8 waves).  Tiles of
+// sequence b sit in its own region of the round's list; a prefix over the per-sequence counts maps a global tile
+// number to (sequence, tile).  A block takes a contiguous run of tiles and has two of them in flight: both tiles' rows are requested in full (up to
+// 16 KB per row) before anything is reduced, and the descriptors of the next pair are requested behind them, so an
+// iteration costs one memory round trip for 16 rows.  h of the two tiles' sequences sits in two LDS slots (bf16)
+// that are refilled only when the sequence changes.  128-bit loads, float32 accumulation, DPP wave reduction.
+#define GEMV_PF 8          // 128-bit pieces of a row requested at once by the round-0 kernel
+#define TILE_PF 16         // the same for the tile loop: a whole row up to d = 8192
 struct GemvShared {
     int pre[CSV_MAX_BATCH + 1];
     int wsum[16];
 };
-// RPW rows per wave; a block of TILE_ROWS / RPW waves covers one tile at a time.  block / nblocks: this block's
-// position in the set of blocks that share the work.
-template <int RPW>
+// block / nblocks: this block's position in the set of blocks that share the work.  hs4: 2 * d * 2 bytes of LDS.
 __device__ __forceinline__ void gemv_tiles_device(const StepArgs& a, int round, uint4* hs4, GemvShared& gs, int block, int nblocks) {
     const int tid = threadIdx.x, nt = blockDim.x, lane = tid & 63, wave = tid >> 6;
     {
@@ -724,88 +725,81 @@ __device__ __forceinline__ void gemv_tiles_device(const StepArgs& a, int round, 
     const int total = gs.pre[a.B];
     const int nch = a.d >> 3;
     const Tile* tl = a.tiles[round & 1];
-    int cur_b = -1;
-    for (int g = block; g < total; g += nblocks) {
-        int lo = 0, hi = a.B;   // largest b with pre[b] <= g
-        while (hi - lo > 1) {
-            const int mid = (lo + hi) >> 1;
-            if (gs.pre[mid] <= g) lo = mid; else hi = mid;
+    auto fetch = [&](int g) {        // descriptor of global tile g; an empty tile past the end
+        Tile t;
+        t.b = 0; t.row0 = 0; t.nrows = 0; t.pos = 0;
+        if (g < total) {
+            int lo = 0, hi = a.B;   // largest b with pre[b] <= g
+            while (hi - lo > 1) {
+                const int mid = (lo + hi) >> 1;
+                if (gs.pre[mid] <= g) lo = mid; else hi = mid;
+            }
+            t = tl[(size_t)lo * a.tile_stride + (g - gs.pre[lo])];
         }
-        const Tile t = tl[(size_t)lo * a.tile_stride + (g - gs.pre[lo])];
-        const int i0 = wave * RPW;
-        const bool active = i0 < t.nrows;
-        int r[RPW];
-        const uint4* w[RPW];
-        uint4 pf[RPW][GEMV_PF];
-        float bias[RPW];
-        int ids[RPW];
+        return t;
+    };
+    // a block takes a contiguous run of the list: mostly one sequence (h is staged once or twice per block, not
+    // once per tile) and neighbouring rows
+    const int per = (total + nblocks - 1) / nblocks;
+    const int g0 = block * per, g1 = min(total, g0 + per);
+    int cached[2] = {-1, -1};
+    Tile tA = fetch(g0 < g1 ? g0 : total), tB = fetch(g0 + 1 < g1 ? g0 + 1 : total);
+    for (int g = g0; g < g1; g += 2) {
+        const Tile t[2] = {tA, tB};
+        uint4 pf[2][TILE_PF];
+        const uint4* w[2];
+        float bias[2];
+        int ids[2];
+        bool act[2];
 #pragma unroll
-        for (int q = 0; q < RPW; ++q) {
-            r[q] = t.row0 + ((i0 + q < t.nrows) ? i0 + q : 0);
-            w[q] = reinterpret_cast<const uint4*>(a.Wp + (size_t)r[q] * a.d);
+        for (int q = 0; q < 2; ++q) {
+            act[q] = wave < t[q].nrows;
+            const int r = t[q].row0 + (act[q] ? wave : 0);
+            w[q] = reinterpret_cast<const uint4*>(a.Wp + (size_t)r * a.d);
 #pragma unroll
-            for (int j = 0; j < GEMV_PF; ++j) {
+            for (int j = 0; j < TILE_PF; ++j) {
                 const int i = lane + 64 * j;
-                pf[q][j] = (active && i < nch) ? w[q][i] : make_uint4(0, 0, 0, 0);
+                pf[q][j] = (act[q] && i < nch) ? w[q][i] : make_uint4(0, 0, 0, 0);
             }
             bias[q] = 0.f;
             ids[q] = 0;
-            if (active && lane == 0) {
-                bias[q] = a.bp[r[q]];
-                ids[q] = a.perm[r[q]];
+            if (act[q] && lane == 0) {
+                bias[q] = a.bp[r];
+                ids[q] = a.perm[r];
             }
         }
-        if (t.b != cur_b) {
-            __syncthreads();
-            const uint4* hsrc = reinterpret_cast<const uint4*>(a.h) + (size_t)t.b * nch;
-            for (int i = tid; i < nch; i += nt) hs4[i] = hsrc[i];
-            __syncthreads();
-            cur_b = t.b;
-        }
-        if (!active) continue;
-        float acc[RPW];
+        // next pair's descriptors ride behind the row requests
+        tA = fetch(g + 2 < g1 ? g + 2 : total);
+        tB = fetch(g + 3 < g1 ? g + 3 : total);
+        // h of the two sequences: slot q holds the sequence of tile q
+        bool staged = false;
 #pragma unroll
-        for (int q = 0; q < RPW; ++q) acc[q] = 0.f;
-#pragma unroll
-        for (int j = 0; j < GEMV_PF; ++j) {
-            const int i = lane + 64 * j;
-            if (i < nch) {
-                const uint4 hv = hs4[i];
-#pragma unroll
-                for (int q = 0; q < RPW; ++q) acc[q] = dot8_bf16(pf[q][j], hv, acc[q]);
+        for (int q = 0; q < 2; ++q)
+            if (t[q].nrows > 0 && cached[q] != t[q].b) {
+                if (!staged) __syncthreads();          // everyone is done with the slots' previous contents
+                staged = true;
+                const uint4* hsrc = reinterpret_cast<const uint4*>(a.h) + (size_t)t[q].b * nch;
+                for (int i = tid; i < nch; i += nt) hs4[q * nch + i] = hsrc[i];
+                cached[q] = t[q].b;
             }
-        }
-        int i = lane + 64 * GEMV_PF;
-        for (; i + 192 < nch; i += 256) {
-            const uint4 h0 = hs4[i], h1 = hs4[i + 64], h2 = hs4[i + 128], h3 = hs4[i + 192];
-            uint4 x[RPW][4];
+        if (staged) __syncthreads();
 #pragma unroll
-            for (int q = 0; q < RPW; ++q) {
-                x[q][0] = w[q][i]; x[q][1] = w[q][i + 64]; x[q][2] = w[q][i + 128]; x[q][3] = w[q][i + 192];
+        for (int q = 0; q < 2; ++q) {
+            if (!act[q]) continue;
+            const uint4* hq = hs4 + q * nch;
+            float acc = 0.f;
+#pragma unroll
+            for (int j = 0; j < TILE_PF; ++j) {
+                const int i = lane + 64 * j;
+                if (i < nch) acc = dot8_bf16(pf[q][j], hq[i], acc);
             }
-#pragma unroll
-            for (int q = 0; q < RPW; ++q) {
-                acc[q] = dot8_bf16(x[q][0], h0, acc[q]);
-                acc[q] = dot8_bf16(x[q][1], h1, acc[q]);
-                acc[q] = dot8_bf16(x[q][2], h2, acc[q]);
-                acc[q] = dot8_bf16(x[q][3], h3, acc[q]);
+            for (int i = lane + 64 * TILE_PF; i < nch; i += 64) acc = dot8_bf16(w[q][i], hq[i], acc);
+            acc = wave_sum(acc);
+            if (lane == 0) {
+                const size_t o = (size_t)t[q].b * a.K_cap + t[q].pos + wave;
+                a.slog[o] = acc + bias[q];
+                a.sid[o] = ids[q];
             }
-        }
-        for (; i < nch; i += 64) {
-            const uint4 hv = hs4[i];
-#pragma unroll
-            for (int q = 0; q < RPW; ++q) acc[q] = dot8_bf16(w[q][i], hv, acc[q]);
-        }
-#pragma unroll
-        for (int q = 0; q < RPW; ++q) acc[q] = wave_sum(acc[q]);
-        if (lane == 0) {
-            const size_t o = (size_t)t.b * a.K_cap + t.pos + i0;
-#pragma unroll
-            for (int q = 0; q < RPW; ++q)
-                if (i0 + q < t.nrows) {
-                    a.slog[o + q] = acc[q] + bias[q];
-                    a.sid[o + q] = ids[q];
-                }
         }
     }
 }
@@ -1835,7 +1829,7 @@ __global__ __launch_bounds__(TAIL_THREADS, 2) void tail_kernel(StepArgs a, FullA
             }
             if (tiles == 0) break;
         }
-        gemv_tiles_device<1>(a, r, reinterpret_cast<uint4*>(arena), gs, block, nblocks);
+        gemv_tiles_device(a, r, reinterpret_cast<uint4*>(arena), gs, block, nblocks);
         if (block == 0 && r == 1) DBG_T(21);
         if (!grid_barrier(a.counters, 2 * r, nblocks, &s_flag)) return;
         if (block == 0 && r == 1) DBG_T(22);
@@ -2046,7 +2040,7 @@ extern "C" int csv_workspace_create(const csv_index* idx, int B_max, int K_cap_r
     if (e == hipSuccess) {
         size_t l = cert_lds(ws);
         // more than FULL_G fallback sequences go through the MFMA product, whose h fragments want a large LDS chunk
-        const size_t cand[] = {(size_t)FULL_G * idx->d * 2, (size_t)FB_CHUNK * 4, (size_t)STAGE_CAP * 8,
+        const size_t cand[] = {(size_t)FULL_G * idx->d * 2 /* also covers the two h slots of the tile loop */, (size_t)FB_CHUNK * 4, (size_t)STAGE_CAP * 8,
                                B_max > FULL_G ? (size_t)MFMA_LDS : 0};
         for (size_t c : cand) l = c > l ? c : l;
         ws->tail_lds = l;
