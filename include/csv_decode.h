@@ -163,6 +163,15 @@ int csv_full_logits(csv_workspace* ws, const csv_index* idx, const uint16_t* d_h
                     float* d_logits, void* stream);
 
 /*
+ * Failure handling of the device-side waits.  The kernel that runs round 1 and the fallback keeps all its blocks
+ * resident and separates its phases with grid barriers; a block polls a barrier at most `polls` times (default
+ * 2^22, about a second), then sets an abort flag that makes every block leave.  Sequences the step had not finished
+ * by then keep flag INVALID_INPUT; the next csv_decode_step starts from a clean state.  polls = 0 restores the
+ * default.  A tiny limit is how the error path is exercised in tests without any kernel failing to exit.
+ */
+int csv_workspace_set_spin_limit(csv_workspace* ws, int polls);
+
+/*
  * Measurement support (not part of the method): time the stages of csv_decode_step with HIP events recorded on
  * the step's own stream.  csv_profile_begin allocates events for max_steps steps and switches recording on;
  * each following csv_decode_step on this workspace records CSV_PROFILE_STAGES+1 events (steps beyond max_steps

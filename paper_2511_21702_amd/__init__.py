@@ -23,6 +23,7 @@ EXPORTS = [
     "csv_build_index", "csv_index_from_arrays", "csv_index_export", "csv_index_dims", "csv_index_free",
     "csv_workspace_create", "csv_workspace_free", "csv_decode_step", "csv_bounds", "csv_full_logits",
     "csv_profile_begin", "csv_profile_end", "csv_last_error", "csv_kmax_init", "csv_kmax_update",
+    "csv_workspace_set_spin_limit",
 ]
 PROFILE_STAGES = ["bounds", "round0", "tail"]
 
@@ -71,6 +72,7 @@ def _load() -> C.CDLL:
     lib.csv_profile_end.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(ci)]
     lib.csv_kmax_init.argtypes = [C.POINTER(KmaxCtl), ci, ci, ci, C.c_double, C.c_double, ci]
     lib.csv_kmax_update.argtypes = [C.POINTER(KmaxCtl), ci, ci]
+    lib.csv_workspace_set_spin_limit.argtypes = [vp, ci]
     return lib
 
 
@@ -184,6 +186,10 @@ class CsvWorkspace:
         self._h = out
         self.index = index
         self.B_max, self.K_cap = B_max, K_cap_rows
+
+    def set_spin_limit(self, polls: int) -> None:
+        """Polls a grid barrier of the tail kernel waits before giving the step up (0 = default)."""
+        _check(lib.csv_workspace_set_spin_limit(self._h, polls))
 
     def profile_begin(self, max_steps: int) -> None:
         _check(lib.csv_profile_begin(self._h, max_steps))

@@ -60,6 +60,7 @@ struct csv_workspace {
     int sp_chunks, cand_chunks;        // certification chunks per sequence; chunk stride of the candidate buffers
     int tile_stride;                   // entries of each sequence's region of a tile list
     int tail_grid;                     // blocks of the tail kernel (all resident together)
+    int spin_limit;                    // polls a grid barrier waits before the step is given up
     size_t tail_lds;                   // its dynamic LDS
     int device;
     float* U;          // [B*C]      cluster bounds

@@ -45,6 +45,7 @@ struct StepArgs {
     int sp_chunks;     // most STAGE_CAP-sized chunks a sequence's scored rows can span
     int cand_chunks;   // chunk stride of the candidate buffers
     int tail_lds;      // dynamic LDS bytes of the tail kernel
+    int spin_limit;    // polls a grid barrier of the tail kernel waits before it gives the step up
     int r0_h_off;      // offset of h in the round-0 kernel's LDS arena, in 128-bit units (behind the cluster data)
     float* U;
     float* hnorm;
@@ -1777,7 +1778,7 @@ __device__ __forceinline__ void fb_final_device(const StepArgs& a, int slot, Seq
 #define TAIL_SPIN_LIMIT (1 << 22)
 
 // Returns false when the step was aborted.  Each barrier of a step uses its own counter.
-__device__ __forceinline__ bool grid_barrier(int* counters, int which, int nblocks, int* s_flag) {
+__device__ __forceinline__ bool grid_barrier(int* counters, int which, int nblocks, int* s_flag, int spin_limit) {
     __syncthreads();
     if (threadIdx.x == 0) {
         __threadfence();
@@ -1785,7 +1786,7 @@ __device__ __forceinline__ bool grid_barrier(int* counters, int which, int nbloc
         int ok = 1, spins = 0;
         while (__hip_atomic_load(&counters[CNT_BARRIER + which], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) < nblocks) {
             if (__hip_atomic_load(&counters[CNT_ABORT], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) { ok = 0; break; }
-            if (++spins > TAIL_SPIN_LIMIT) {
+            if (++spins > spin_limit) {
                 atomicExch(&counters[CNT_ABORT], 1);
                 ok = 0;
                 break;
@@ -1831,14 +1832,14 @@ __global__ __launch_bounds__(TAIL_THREADS, 2) void tail_kernel(StepArgs a, FullA
         }
         gemv_tiles_device(a, r, reinterpret_cast<uint4*>(arena), gs, block, nblocks);
         if (block == 0 && r == 1) DBG_T(21);
-        if (!grid_barrier(a.counters, 2 * r, nblocks, &s_flag)) return;
+        if (!grid_barrier(a.counters, 2 * r, nblocks, &s_flag, a.spin_limit)) return;
         if (block == 0 && r == 1) DBG_T(22);
         for (int item = block; item < a.B * a.sp_chunks; item += nblocks) {
             cert_device(a, item / a.sp_chunks, item % a.sp_chunks, r, s);
             __syncthreads();
         }
         if (block == 0 && r == 1) DBG_T(23);
-        if (!grid_barrier(a.counters, 2 * r + 1, nblocks, &s_flag)) return;
+        if (!grid_barrier(a.counters, 2 * r + 1, nblocks, &s_flag, a.spin_limit)) return;
         if (block == 0 && r == 1) DBG_T(24);
     }
     const int n_fb = __hip_atomic_load(&a.counters[CNT_FALLBACK], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
@@ -1848,14 +1849,14 @@ __global__ __launch_bounds__(TAIL_THREADS, 2) void tail_kernel(StepArgs a, FullA
     else
         full_gemv_device(f, n_fb, reinterpret_cast<uint4*>(arena), block, nblocks);
     if (block == 0) DBG_T(25);
-    if (!grid_barrier(a.counters, 2 * CSV_MAX_ROUNDS, nblocks, &s_flag)) return;
+    if (!grid_barrier(a.counters, 2 * CSV_MAX_ROUNDS, nblocks, &s_flag, a.spin_limit)) return;
     if (block == 0) DBG_T(26);
     for (int item = block; item < n_fb * a.n_chunks; item += nblocks) {
         fb_topk_device(a, item / a.n_chunks, item % a.n_chunks, s);
         __syncthreads();
     }
     if (block == 0) DBG_T(27);
-    if (!grid_barrier(a.counters, 2 * CSV_MAX_ROUNDS + 1, nblocks, &s_flag)) return;
+    if (!grid_barrier(a.counters, 2 * CSV_MAX_ROUNDS + 1, nblocks, &s_flag, a.spin_limit)) return;
     if (block == 0) DBG_T(28);
     for (int slot = block; slot < n_fb; slot += nblocks) {
         fb_final_device(a, slot, s);
@@ -1902,6 +1903,7 @@ static void fill_args(StepArgs& a, const csv_workspace* ws, const csv_index* idx
     a.tiles[0] = ws->tiles[0]; a.tiles[1] = ws->tiles[1]; a.counters = ws->counters;
     a.r0_h_off = (int)(round0_h_off(ws) / 16);
     a.tail_lds = (int)ws->tail_lds;
+    a.spin_limit = ws->spin_limit;
     a.fb_list = ws->fb_list; a.fb_logits = ws->fb_logits; a.cand_val = ws->cand_val; a.cand_id = ws->cand_id;
     a.cand_max = ws->cand_max; a.cand_sum = ws->cand_sum;
 }
@@ -2059,6 +2061,7 @@ extern "C" int csv_workspace_create(const csv_index* idx, int B_max, int K_cap_r
         // for one block per compute unit.  A second block per unit measured slower at every batch size: the
         // grid barriers cost more with twice the arrivals, and the row loops already keep enough loads in flight.
         ws->tail_grid = cus;
+        ws->spin_limit = TAIL_SPIN_LIMIT;
     }
     if (e != hipSuccess) {
         csv_set_error("workspace allocation failed: %s", hipGetErrorString(e));
@@ -2156,6 +2159,13 @@ extern "C" int csv_decode_step(csv_workspace* ws, const csv_index* idx, const ui
     }
     CSV_MARK(3);
 #undef CSV_MARK
+    return CSV_OK;
+}
+
+extern "C" int csv_workspace_set_spin_limit(csv_workspace* ws, int polls) {
+    if (!ws) { csv_set_error("null workspace"); return CSV_EINVAL; }
+    if (polls < 0) { csv_set_error("polls=%d is negative", polls); return CSV_EINVAL; }
+    ws->spin_limit = polls == 0 ? TAIL_SPIN_LIMIT : polls;
     return CSV_OK;
 }
 

@@ -225,6 +225,44 @@ def test_step_invalid_hidden_state_is_flagged():
     case.close()
 
 
+def test_barrier_timeout_gives_the_step_up_cleanly():
+    # Error path of the device-side waits, forced from the host: with a poll limit of 1 the grid barriers of the
+    # tail kernel run out, every block leaves, unfinished sequences keep INVALID_INPUT; the next step is clean.
+    r = synth.small_recipe("abort", V=4000, d=256, C=32, B=5, steps=6, iso_frac=0.3, h_mode="mix")
+    case = Case(r, seed=11)
+    csv = case.csv
+    h = case.hidden()
+    dh = csv.bits_to_device(h)
+
+    def run_all():
+        res = []
+        buf = csv.make_step_buffers(case.gidx, r.B, 5, 1e-3, r.K_max_rows)
+        for s in range(h.shape[0]):
+            csv.csv_decode_step(case.ws, case.gidx, dh[s], buf)
+            torch.cuda.synchronize()
+            res.append((buf.flags.cpu().numpy().copy(), buf.ids.cpu().numpy().copy(), buf.rounds.cpu().numpy().copy()))
+        return res
+
+    ref = run_all()
+    assert any((rd > 1).any() or (fl & csv.FLAG_FALLBACK).any() for fl, _, rd in ref), "workload never reaches the tail kernel"
+    case.ws.set_spin_limit(1)
+    cut = run_all()
+    n_invalid = 0
+    for (fl0, id0, _), (fl1, id1, _) in zip(ref, cut):
+        for b in range(r.B):
+            if fl1[b] == csv.FLAG_INVALID_INPUT:
+                n_invalid += 1
+            else:
+                assert fl1[b] == fl0[b] and np.array_equal(id1[b], id0[b])
+    log(f"[abort] {n_invalid} of {len(ref) * r.B} sequences given up with a poll limit of 1")
+    assert n_invalid > 0
+    case.ws.set_spin_limit(0)
+    again = run_all()
+    for (fl0, id0, rd0), (fl2, id2, rd2) in zip(ref, again):
+        assert np.array_equal(fl0, fl2) and np.array_equal(id0, id2) and np.array_equal(rd0, rd2)
+    case.close()
+
+
 def test_argument_errors():
     r = synth.small_recipe("err", V=1000, d=64, C=8, B=2, steps=1)
     case = Case(r, seed=17)
