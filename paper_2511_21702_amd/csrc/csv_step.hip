@@ -1120,6 +1120,7 @@ __device__ __forceinline__ void cert_body(const StepArgs& a, int b, int chunk, i
     const int nchunks = (n + STAGE_CAP - 1) / STAGE_CAP;
     if (chunk >= nchunks) return;
     const int c0 = chunk * STAGE_CAP, len = min(STAGE_CAP, n - c0);
+    if (round >= 1) DBG_T(12);
     {
         const float* gv = a.slog + (size_t)b * a.K_cap + c0;
         const int32_t* gi = a.sid + (size_t)b * a.K_cap + c0;
@@ -1127,7 +1128,7 @@ __device__ __forceinline__ void cert_body(const StepArgs& a, int b, int chunk, i
         stage_to_lds(reinterpret_cast<int*>(arena) + STAGE_CAP, gi, len);
         __syncthreads();
     }
-    if (round == 0) DBG_T(9);
+    if (round == 0) DBG_T(9); else DBG_T(13);
     // the accessors name the LDS array itself so that the reads compile to LDS instructions
     auto val = [](int i) { return reinterpret_cast<const float*>(arena)[i]; };
     auto idf = [](int i) { return reinterpret_cast<const int*>(arena)[STAGE_CAP + i]; };
@@ -1135,7 +1136,7 @@ __device__ __forceinline__ void cert_body(const StepArgs& a, int b, int chunk, i
     LseAcc l;
     if (a.use_k) {
         block_topk(len, a.k, val, idf, s);
-        if (round == 0) DBG_T(10);
+        if (round == 0) DBG_T(10); else DBG_T(14);
         l.m = s.wval[0];
         float sm = 0.f;
         if (l.m > -INFINITY)
@@ -1144,7 +1145,7 @@ __device__ __forceinline__ void cert_body(const StepArgs& a, int b, int chunk, i
     } else {
         l = block_lse(len, val, s);
     }
-    if (round == 0) DBG_T(11);
+    if (round == 0) DBG_T(11); else DBG_T(15);
     if (nchunks > 1) {
         const size_t pb = (size_t)b * a.cand_chunks, pc = pb + chunk;
         const int kk = min(a.k, len);
@@ -1213,6 +1214,7 @@ __device__ __forceinline__ void cert_body(const StepArgs& a, int b, int chunk, i
     };
     if (ok) {
         finish(((tk && a.use_k) ? CSV_FLAG_TOPK_CERT : 0u) | ((sm && a.use_s) ? CSV_FLAG_SOFTMAX_CERT : 0u));
+        if (round >= 1) DBG_T(16);
         return;
     }
     if (round + 1 < a.max_rounds) {
@@ -1784,7 +1786,8 @@ __device__ __forceinline__ bool grid_barrier(int* counters, int which, int nbloc
         __threadfence();
         atomicAdd(&counters[CNT_BARRIER + which], 1);
         int ok = 1, spins = 0;
-        while (__hip_atomic_load(&counters[CNT_BARRIER + which], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) < nblocks) {
+        // relaxed polls (an acquire per poll would invalidate the XCD's L2 every time); the fence below acquires once
+        while (__hip_atomic_load(&counters[CNT_BARRIER + which], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < nblocks) {
             if (__hip_atomic_load(&counters[CNT_ABORT], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) { ok = 0; break; }
             if (++spins > spin_limit) {
                 atomicExch(&counters[CNT_ABORT], 1);
@@ -1818,7 +1821,7 @@ __global__ __launch_bounds__(TAIL_THREADS, 2) void tail_kernel(StepArgs a, FullA
     const int tiles0 = block_sum_i(mine0, s.redi);
     int tiles = block_sum_i(mine1, s.redi);
     if (tiles0 == 0 && tiles == 0 && n_fb0 == 0) return;
-    if (block == 0) DBG_T(20);
+    DBG_T(20);
 
     // Rounds: the GEMV over the round's work list, then the certification, which may plan the next round.
     // Round 0 is here only for seed prefixes that the round-0 kernel handed over.
@@ -1831,16 +1834,17 @@ __global__ __launch_bounds__(TAIL_THREADS, 2) void tail_kernel(StepArgs a, FullA
             if (tiles == 0) break;
         }
         gemv_tiles_device(a, r, reinterpret_cast<uint4*>(arena), gs, block, nblocks);
-        if (block == 0 && r == 1) DBG_T(21);
+        if (r == 1) DBG_T(21);
         if (!grid_barrier(a.counters, 2 * r, nblocks, &s_flag, a.spin_limit)) return;
-        if (block == 0 && r == 1) DBG_T(22);
+        if (r == 1) DBG_T(22);
+        // chunk-major items: the first chunks of all sequences (often the only ones with work) go to distinct blocks
         for (int item = block; item < a.B * a.sp_chunks; item += nblocks) {
-            cert_device(a, item / a.sp_chunks, item % a.sp_chunks, r, s);
+            cert_device(a, item % a.B, item / a.B, r, s);
             __syncthreads();
         }
-        if (block == 0 && r == 1) DBG_T(23);
+        if (r == 1) DBG_T(23);
         if (!grid_barrier(a.counters, 2 * r + 1, nblocks, &s_flag, a.spin_limit)) return;
-        if (block == 0 && r == 1) DBG_T(24);
+        if (r == 1) DBG_T(24);
     }
     const int n_fb = __hip_atomic_load(&a.counters[CNT_FALLBACK], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
     if (n_fb == 0) return;
