@@ -61,6 +61,7 @@ struct csv_workspace {
     int tile_stride;                   // entries of each sequence's region of a tile list
     int tail_grid;                     // blocks of the tail kernel (all resident together)
     int spin_limit;                    // polls a grid barrier waits before the step is given up
+    int round0_capacity;               // blocks of the round-0 kernel that are resident together
     size_t tail_lds;                   // its dynamic LDS
     int device;
     float* U;          // [B*C]      cluster bounds

@@ -1316,7 +1316,8 @@ __device__ __forceinline__ void cert_device(const StepArgs& a, int b, int chunk,
 // the sequence's counter (nobody waits) certifies, or plans round 1, or hands the sequence to the full product.
 // A prefix with more rows than the NB blocks should score themselves (one giant cluster) goes to the round-0
 // work list instead and is scored and certified by the tail kernel with the whole device.
-#define ROUND0_ROWS_PER_WAVE 8     // with at most 32 blocks of 8 waves a sequence: no more than 2048 <= STAGE_CAP rows
+#define ROUND0_ROWS_PER_WAVE 8     // with at most 32 blocks of 8 waves a sequence: no more than 2048 <= STAGE_CAP rows;
+                                   // with a single block: 64 rows, larger prefixes go to the tail kernel
 #define ROUND0_HREG 4     // 128-bit pieces of h a thread carries in registers across the seed (d <= 4 * 8 * SEQ_THREADS)
 // log tail mass of the clusters below the threshold key kappa, shifted by an upper bound of its largest term
 // (nxt: the largest unopened key, 0 if none; nxtU: its bound)
@@ -2066,6 +2067,14 @@ extern "C" int csv_workspace_create(const csv_index* idx, int B_max, int K_cap_r
         // grid barriers cost more with twice the arrivals, and the row loops already keep enough loads in flight.
         ws->tail_grid = cus;
         ws->spin_limit = TAIL_SPIN_LIMIT;
+        int r0_per_cu = 0;
+        if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&r0_per_cu, round0_kernel, SEQ_THREADS, round0_lds(ws));
+        if (e == hipSuccess && r0_per_cu < 1) {
+            csv_set_error("round-0 kernel does not fit a compute unit (dynamic LDS %zu bytes)", round0_lds(ws));
+            csv_workspace_free(ws);
+            return CSV_ESHAPE;
+        }
+        ws->round0_capacity = r0_per_cu * cus;
     }
     if (e != hipSuccess) {
         csv_set_error("workspace allocation failed: %s", hipGetErrorString(e));
@@ -2148,8 +2157,9 @@ extern "C" int csv_decode_step(csv_workspace* ws, const csv_index* idx, const ui
     CSV_MARK(1);
     {
         // blocks per sequence: enough waves that a typical seed prefix (one or two clusters) is one row per wave
-        int nb = 512 / B;
-        nb = nb < 2 ? 2 : (nb > 32 ? 32 : nb);
+        // as many as stay resident together (a second wave of blocks would double the kernel's time), at most 32
+        int nb = ws->round0_capacity / B;
+        nb = nb < 1 ? 1 : (nb > 32 ? 32 : nb);
         round0_kernel<<<dim3(nb, B), SEQ_THREADS, round0_lds(ws), st>>>(a);
         CSV_LAUNCH_CHECK("round0_kernel");
     }
