@@ -697,8 +697,7 @@ __device__ __forceinline__ void tail_stats(const StepArgs& a, const ClusterLds& 
 // 16 KB per row) before anything is reduced, and the descriptors of the next pair are requested behind them, so an
 // iteration costs one memory round trip for 16 rows.  h of the two tiles' sequences sits in two LDS slots (bf16)
 // that are refilled only when the sequence changes.  128-bit loads, float32 accumulation, DPP wave reduction.
-#define GEMV_PF 8          // 128-bit pieces of a row requested at once by the round-0 kernel
-#define TILE_PF 16         // the same for the tile loop: a whole row up to d = 8192
+#define TILE_PF 16         // 128-bit pieces of a row requested at once per lane: a whole row up to d = 8192
 struct GemvShared {
     int pre[CSV_MAX_BATCH + 1];
     int wsum[16];
@@ -1439,7 +1438,7 @@ __global__ __launch_bounds__(SEQ_THREADS) void round0_kernel(StepArgs a) {
         const int i = tid + q * nt;
         if (i < nch) hs4[i] = hreg[q];
     }
-    uint4 pf[GEMV_PF];
+    uint4 pf[TILE_PF];
     const uint4* w = nullptr;
     float bias = 0.f;
     int id = 0;
@@ -1452,7 +1451,7 @@ __global__ __launch_bounds__(SEQ_THREADS) void round0_kernel(StepArgs a) {
         const int r = L.offl[scl[lo]] + (p - spos[lo]);
         w = reinterpret_cast<const uint4*>(a.Wp + (size_t)r * a.d);
 #pragma unroll
-        for (int q = 0; q < GEMV_PF; ++q) {
+        for (int q = 0; q < TILE_PF; ++q) {
             const int i = lane + 64 * q;
             pf[q] = i < nch ? w[i] : make_uint4(0, 0, 0, 0);
         }
@@ -1471,11 +1470,11 @@ __global__ __launch_bounds__(SEQ_THREADS) void round0_kernel(StepArgs a) {
     while (p < rows) {
         float acc = 0.f;
 #pragma unroll
-        for (int q = 0; q < GEMV_PF; ++q) {
+        for (int q = 0; q < TILE_PF; ++q) {
             const int i = lane + 64 * q;
             if (i < nch) acc = dot8_bf16(pf[q], hs4[i], acc);
         }
-        int i = lane + 64 * GEMV_PF;
+        int i = lane + 64 * TILE_PF;
         for (; i + 192 < nch; i += 256) {
             const uint4 x0 = w[i], x1 = w[i + 64], x2 = w[i + 128], x3 = w[i + 192];
             acc = dot8_bf16(x0, hs4[i], acc);
