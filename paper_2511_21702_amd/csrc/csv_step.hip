@@ -93,6 +93,15 @@ __device__ __forceinline__ uint32_t lkey(float v) { return fkey(v + 0.0f); }
 __device__ __forceinline__ u64 ckey(float U, int c) { return ((u64)lkey(U) << 32) | (u64)(0xFFFFFFFFu - (uint32_t)c); }
 __device__ __forceinline__ float ckey_bound(u64 k) { return fkey_inv((uint32_t)(k >> 32)); }
 
+// Zero the step's counters: the fixed slots and, of every per-sequence row, the entries of the B sequences in use.
+__device__ __forceinline__ void reset_step_counters(int* counters, int B, int nthreads) {
+    constexpr int rows = (CNT_TOTAL - CNT_TILES) / CSV_MAX_BATCH;
+    for (int i = threadIdx.x; i < CNT_TILES + rows * B; i += nthreads) {
+        const int j = i - CNT_TILES;
+        counters[i < CNT_TILES ? i : CNT_TILES + (j / B) * CSV_MAX_BATCH + (j % B)] = 0;
+    }
+}
+
 // ================================================================================================ bounds
 // Block = 8 waves = 8/WPC clusters x WPC column slices (WPC = 1, 2 or 4, chosen so that a wave's slice of the
 // centroid row is at most 8 KB = one batch of eight 128-bit loads per lane), BT sequences per block.
@@ -149,7 +158,7 @@ __global__ __launch_bounds__(BOUND_THREADS) void bound_kernel(StepArgs a, float*
         if (i < BT * nch) hs4[i] = hreg[q];
     }
     if (reset_counters && blockIdx.x == 0 && blockIdx.y == 0)
-        for (int i = tid; i < CNT_TOTAL; i += BOUND_THREADS) a.counters[i] = 0;
+        reset_step_counters(a.counters, a.B, BOUND_THREADS);
     __syncthreads();
     for (int s = wave; s < BT; s += BOUND_THREADS / 64) {
         float acc = 0.f;
@@ -257,7 +266,7 @@ __global__ __launch_bounds__(BOUND_THREADS) void bound1_kernel(StepArgs a, float
         ncl = a.n[c];
     }
     if (reset_counters && blockIdx.x == 0)
-        for (int i = tid; i < CNT_TOTAL; i += BOUND_THREADS) a.counters[i] = 0;
+        reset_step_counters(a.counters, a.B, BOUND_THREADS);
     float acc = 0.f, hh = 0.f;
     auto step = [&](const float4& m, const uint2& hv) {
         const float h0 = bf16_lo(hv.x), h1 = bf16_hi(hv.x), h2v = bf16_lo(hv.y), h3 = bf16_hi(hv.y);
@@ -331,7 +340,7 @@ __global__ __launch_bounds__(512) void bound_mfma_kernel(StepArgs a, float* __re
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int li = lane & 15, g = lane >> 4;
     if (reset_counters && blockIdx.x == 0 && blockIdx.y == 0)
-        for (int i = tid; i < CNT_TOTAL; i += 512) a.counters[i] = 0;
+        reset_step_counters(a.counters, a.B, 512);
     const int ks = blockIdx.y * BOUND_KS_PER_BLOCK + wave;
     if (ks >= KS) return;
     const int c0 = blockIdx.x * 16;
