@@ -367,10 +367,16 @@ __global__ __launch_bounds__(512) void bound_mfma_kernel(StepArgs a, float* __re
         for (int u = 0; u < BOUND_KB_UNROLL; ++u) {
             const int k = (kb + u) * 32 + g * 8;
             const bool ok = kb + u < kb1 && k < a.d;       // d is a multiple of 8: the eight values are all in or all out
-            x[u][0] = ok ? ap[k >> 2] : fzero;
-            x[u][1] = ok ? ap[(k >> 2) + 1] : fzero;
+            // unconditional 128-bit loads at a clamped address, then a select: a predicated load would be split up
+            const int kc = ok ? k : 0;
+            const float4 v0 = ap[kc >> 2], v1 = ap[(kc >> 2) + 1];
+            x[u][0] = ok ? v0 : fzero;
+            x[u][1] = ok ? v1 : fzero;
 #pragma unroll
-            for (int t = 0; t < NT; ++t) hb[u][t] = (ok && hv[t]) ? hp[t][k >> 3] : zero;
+            for (int t = 0; t < NT; ++t) {
+                const uint4 hvv = hp[t][kc >> 3];
+                hb[u][t] = (ok && hv[t]) ? hvv : zero;
+            }
         }
 #pragma unroll
         for (int u = 0; u < BOUND_KB_UNROLL; ++u) {
@@ -379,23 +385,23 @@ __global__ __launch_bounds__(512) void bound_mfma_kernel(StepArgs a, float* __re
 #pragma unroll
             for (int t = 0; t < NT; ++t) {
                 const bf16x8_t bv = __builtin_bit_cast(bf16x8_t, hb[u][t]);
-                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, hi), bv, acc[t], 0, 0, 0);
-                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, mid), bv, acc[t], 0, 0, 0);
-                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, lo), bv, acc[t], 0, 0, 0);
+                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bv, __builtin_bit_cast(bf16x8_t, hi), acc[t], 0, 0, 0);
+                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bv, __builtin_bit_cast(bf16x8_t, mid), acc[t], 0, 0, 0);
+                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bv, __builtin_bit_cast(bf16x8_t, lo), acc[t], 0, 0, 0);
             }
         }
     }
-    // accumulator register r of lane (li, g) is  [cluster 4g + r][sequence li]
+    // h is the first operand: accumulator register r of lane (li, g) is  [sequence 4g + r][cluster li], so the 16
+    // lanes of a group store 64 contiguous bytes of one sequence's partial bounds
+    const int c = c0 + li;
+    if (c < a.C) {
 #pragma unroll
-    for (int t = 0; t < NT; ++t) {
-        const int sq = seq0 + t * 16 + li;
-        if (sq < a.B) {
+        for (int t = 0; t < NT; ++t)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                const int c = c0 + 4 * g + r;
-                if (c < a.C) P[((size_t)ks * a.B + sq) * a.C + c] = acc[t][r];
+                const int sq = seq0 + t * 16 + 4 * g + r;
+                if (sq < a.B) P[((size_t)ks * a.B + sq) * a.C + c] = acc[t][r];
             }
-        }
     }
 }
 
@@ -1932,7 +1938,10 @@ static int launch_bounds_kernel(const StepArgs& a, float* U, float* hn, int rese
     if (a.B > 8) {
         // enough K slices that (cluster tiles x slices) fills the device; at most BOUND_KS_MAX (size of the partial buffer)
         const int tiles = (a.C + 15) / 16, nkb = (a.d + 31) / 32;
-        int KS = (2048 + tiles - 1) / tiles;
+#ifndef BOUND_WAVE_TARGET
+#define BOUND_WAVE_TARGET 4096
+#endif
+        int KS = (BOUND_WAVE_TARGET + tiles - 1) / tiles;
         KS = ((KS + BOUND_KS_PER_BLOCK - 1) / BOUND_KS_PER_BLOCK) * BOUND_KS_PER_BLOCK;
         if (KS > BOUND_KS_MAX) KS = BOUND_KS_MAX;
         int kbs = (nkb + KS - 1) / KS;
