@@ -819,19 +819,40 @@ __device__ __forceinline__ void gemv_tiles_device(const StepArgs& a, int round, 
     }
 }
 
-// Copy n 32-bit words from global memory to LDS with eight loads in flight per thread.
+// Copy n 32-bit words from global memory to LDS.  Every trip issues eight loads per thread before the first
+// store, also in the ragged last trip (out-of-range lanes load nothing), so a copy of up to 8 x blockDim words is
+// one memory round trip.
 template <class T>
 __device__ __forceinline__ void stage_to_lds(T* dst, const T* __restrict__ src, int n) {
     const int tid = threadIdx.x, nt = blockDim.x;
-    int i = tid;
-    for (; i + 7 * nt < n; i += 8 * nt) {
+    for (int i = tid; i < n; i += 8 * nt) {
         T r[8];
 #pragma unroll
-        for (int q = 0; q < 8; ++q) r[q] = src[i + q * nt];
+        for (int q = 0; q < 8; ++q) r[q] = i + q * nt < n ? src[i + q * nt] : T(0);
 #pragma unroll
-        for (int q = 0; q < 8; ++q) dst[i + q * nt] = r[q];
+        for (int q = 0; q < 8; ++q)
+            if (i + q * nt < n) dst[i + q * nt] = r[q];
     }
-    for (; i < n; i += nt) dst[i] = src[i];
+}
+// Two arrays of the same length at once (logits and token ids): both arrays' loads are in flight together.
+__device__ __forceinline__ void stage2_to_lds(float* dv, const float* __restrict__ sv, int* di, const int* __restrict__ si, int n) {
+    const int tid = threadIdx.x, nt = blockDim.x;
+    for (int i = tid; i < n; i += 8 * nt) {
+        float rv[8];
+        int ri[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const bool in = i + q * nt < n;
+            rv[q] = in ? sv[i + q * nt] : 0.f;
+            ri[q] = in ? si[i + q * nt] : 0;
+        }
+#pragma unroll
+        for (int q = 0; q < 8; ++q)
+            if (i + q * nt < n) {
+                dv[i + q * nt] = rv[q];
+                di[i + q * nt] = ri[q];
+            }
+    }
 }
 
 // ================================================================================================ block top-k
@@ -922,6 +943,37 @@ __device__ __forceinline__ void radix_select(int n, unsigned kk, KeyFn key, SeqS
         mask |= 0xffu << shift;
         rem = s.rem;
         eq = s.eq;
+        if (shift > 0 && eq <= 256u) {
+            // few candidates left in the selected bin: list them and rank them directly instead of more passes
+            __syncthreads();
+            if (tid == 0) s.cnt = 0;
+            __syncthreads();
+            for (int i = tid; i < n; i += nt) {
+                unsigned kx = 0;
+                if (key(i, kx) && (kx & mask) == prefix) s.hist[atomicAdd(&s.cnt, 1u)] = kx;
+            }
+            __syncthreads();
+            if (tid < (int)eq) {
+                const unsigned v = s.hist[tid];
+                unsigned gt = 0, ge = 0;
+                for (unsigned j = 0; j < eq; ++j) {
+                    const unsigned x = s.hist[j];
+                    gt += x > v;
+                    ge += x >= v;
+                }
+                if (gt < rem && rem <= ge) {     // every thread holding this value writes the same three numbers
+                    s.sel = v;
+                    s.rem = rem - gt;
+                    s.eq = ge - gt;
+                }
+            }
+            __syncthreads();
+            kth = s.sel;
+            need_eq = s.rem;
+            n_eq = s.eq;
+            __syncthreads();
+            return;
+        }
     }
     kth = prefix;
     need_eq = rem;
@@ -1138,8 +1190,7 @@ __device__ __forceinline__ void cert_body(const StepArgs& a, int b, int chunk, i
     {
         const float* gv = a.slog + (size_t)b * a.K_cap + c0;
         const int32_t* gi = a.sid + (size_t)b * a.K_cap + c0;
-        stage_to_lds(reinterpret_cast<float*>(arena), gv, len);
-        stage_to_lds(reinterpret_cast<int*>(arena) + STAGE_CAP, gi, len);
+        stage2_to_lds(reinterpret_cast<float*>(arena), gv, reinterpret_cast<int*>(arena) + STAGE_CAP, gi, len);
         __syncthreads();
     }
     if (round == 0) DBG_T(9); else DBG_T(13);
@@ -1190,8 +1241,7 @@ __device__ __forceinline__ void cert_body(const StepArgs& a, int b, int chunk, i
             const int nc = nchunks * a.k;
             if (nc <= STAGE_CAP) {
                 __syncthreads();
-                stage_to_lds(reinterpret_cast<float*>(arena), cv, nc);
-                stage_to_lds(reinterpret_cast<int*>(arena) + STAGE_CAP, ci, nc);
+                stage2_to_lds(reinterpret_cast<float*>(arena), cv, reinterpret_cast<int*>(arena) + STAGE_CAP, ci, nc);
                 __syncthreads();
                 block_topk(nc, a.k, val, idf, s);
             } else {
@@ -1762,8 +1812,7 @@ __device__ __forceinline__ void fb_final_device(const StepArgs& a, int slot, Seq
         const int32_t* ci = a.cand_id + (size_t)slot * a.n_chunks * a.k;
         const int n = a.n_chunks * a.k;
         if (n <= STAGE_CAP) {
-            stage_to_lds(reinterpret_cast<float*>(arena), cv, n);
-            stage_to_lds(reinterpret_cast<int*>(arena) + STAGE_CAP, ci, n);
+            stage2_to_lds(reinterpret_cast<float*>(arena), cv, reinterpret_cast<int*>(arena) + STAGE_CAP, ci, n);
             __syncthreads();
             block_topk(n, a.k, [](int i) { return reinterpret_cast<const float*>(arena)[i]; },
                        [](int i) { return reinterpret_cast<const int*>(arena)[STAGE_CAP + i]; }, s);
