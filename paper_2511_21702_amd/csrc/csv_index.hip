@@ -47,40 +47,60 @@ __device__ __forceinline__ double wave_sum_d(double v) {
 }
 
 // R_c = max_i ||W_i - mu_c||_2 to the stored float32 centroid, in float64; stored radius
-// roundup_f32(R_c (1+rho) + rho ||mu_c||); bias maximum; ln n_c.  One block per cluster.
-__global__ __launch_bounds__(256) void radius_kernel(const uint16_t* __restrict__ Wp, const float* __restrict__ bp,
-                                                     const int32_t* __restrict__ off, const float* __restrict__ mu, int d,
-                                                     double rho, float* __restrict__ R, float* __restrict__ bmax,
-                                                     float* __restrict__ lnn) {
-    __shared__ double wmax[4];
+// roundup_f32(R_c (1+rho) + rho ||mu_c||); bias maximum; ln n_c.
+// Pass 1, one wave per permuted row (so a cluster of any size is spread over the whole device): squared distance in
+// float64, folded into d2max[c] with an integer atomic max (non-negative doubles order like their bit patterns).
+__global__ __launch_bounds__(256) void row_dist_kernel(const uint16_t* __restrict__ Wp, const int32_t* __restrict__ off,
+                                                       const float* __restrict__ mu, int V, int d, int C,
+                                                       unsigned long long* __restrict__ d2max) {
+    const int lane = threadIdx.x & 63;
+    const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (r >= V) return;
+    int lo = 0, hi = C;                       // cluster of the row: largest c with off[c] <= r
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (off[mid] <= r) lo = mid; else hi = mid;
+    }
+    const uint4* w = reinterpret_cast<const uint4*>(Wp + (size_t)r * d);
+    const float4* m = reinterpret_cast<const float4*>(mu + (size_t)lo * d);
+    double acc = 0.0;
+    for (int q = lane; q < (d >> 3); q += 64) {
+        const uint4 x = w[q];
+        const float4 m0 = m[2 * q], m1 = m[2 * q + 1];
+        const uint32_t xs[4] = {x.x, x.y, x.z, x.w};
+        const float ms[8] = {m0.x, m0.y, m0.z, m0.w, m1.x, m1.y, m1.z, m1.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const double d0 = (double)__uint_as_float(xs[e] << 16) - (double)ms[2 * e];
+            const double d1 = (double)__uint_as_float(xs[e] & 0xffff0000u) - (double)ms[2 * e + 1];
+            acc = fma(d0, d0, acc);
+            acc = fma(d1, d1, acc);
+        }
+    }
+    acc = wave_sum_d(acc);
+    if (lane == 0) atomicMax(&d2max[lo], (unsigned long long)__double_as_longlong(acc));
+}
+
+// Pass 2, one block per cluster: bias maximum, ||mu_c||, the stored radius and ln n_c.
+__global__ __launch_bounds__(256) void radius_finish_kernel(const float* __restrict__ bp, const int32_t* __restrict__ off,
+                                                            const float* __restrict__ mu, int d, double rho,
+                                                            const unsigned long long* __restrict__ d2max,
+                                                            float* __restrict__ R, float* __restrict__ bmax,
+                                                            float* __restrict__ lnn) {
     __shared__ float wb[4];
-    __shared__ double mun2;
+    __shared__ double wm[4];
     const int c = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int r0 = off[c], r1 = off[c + 1];
     const float* m = mu + (size_t)c * d;
-    double best = 0.0;
-    for (int r = r0 + wave; r < r1; r += 4) {
-        const uint16_t* w = Wp + (size_t)r * d;
-        double acc = 0.0;
-        for (int j = lane; j < d; j += 64) {
-            const double diff = (double)__uint_as_float((uint32_t)w[j] << 16) - (double)m[j];
-            acc += diff * diff;
-        }
-        acc = wave_sum_d(acc);
-        best = fmax(best, acc);
-    }
     float bm = -INFINITY;
     for (int r = r0 + tid; r < r1; r += 256) bm = fmaxf(bm, bp[r]);
     bm = wave_max(bm);
-    if (wave == 0) {
-        double acc = 0.0;
-        for (int j = lane; j < d; j += 64) acc += (double)m[j] * (double)m[j];
-        acc = wave_sum_d(acc);
-        if (lane == 0) mun2 = acc;
-    }
+    double acc = 0.0;
+    for (int j = tid; j < d; j += 256) acc += (double)m[j] * (double)m[j];
+    acc = wave_sum_d(acc);
     if (lane == 0) {
-        wmax[wave] = best;
         wb[wave] = bm;
+        wm[wave] = acc;
     }
     __syncthreads();
     if (tid == 0) {
@@ -90,7 +110,8 @@ __global__ __launch_bounds__(256) void radius_kernel(const uint16_t* __restrict_
             bmax[c] = -INFINITY;
             lnn[c] = -INFINITY;
         } else {
-            const double d2 = fmax(fmax(wmax[0], wmax[1]), fmax(wmax[2], wmax[3]));
+            const double mun2 = (wm[0] + wm[1]) + (wm[2] + wm[3]);
+            const double d2 = __longlong_as_double((long long)d2max[c]);
             const double x = sqrt(d2) * (1.0 + rho) + rho * sqrt(mun2);
             float y = (float)x;
             if ((double)y < x) y = nextafterf(y, INFINITY);
@@ -333,9 +354,21 @@ extern "C" int csv_build_index(const uint16_t* d_W, const float* d_b, int V, int
         for (int c = 0; c < C; ++c) nmax = n[c] > nmax ? n[c] : nmax;
         x->ln_nmax = (float)log((double)nmax);
     }
-    radius_kernel<<<C, 256, 0, st>>>(x->Wp, x->bp, x->off, x->mu, d, (double)o->radius_slack, x->R, x->bmax, x->lnn);
-    if (hipGetLastError() != hipSuccess) { csv_set_error("launch of radius_kernel failed"); return fail(CSV_EHIP); }
-    if (hipStreamSynchronize(st) != hipSuccess) { csv_set_error("index build failed on the device: %s", hipGetErrorString(hipGetLastError())); return fail(CSV_EHIP); }
+    unsigned long long* d_d2max = nullptr;
+    if (hipMalloc((void**)&d_d2max, (size_t)C * 8) != hipSuccess) { csv_set_error("out of device memory (radius scratch)"); return fail(CSV_ENOMEM); }
+    bool launched = hipMemsetAsync(d_d2max, 0, (size_t)C * 8, st) == hipSuccess;
+    if (launched) {
+        row_dist_kernel<<<(V + 3) / 4, 256, 0, st>>>(x->Wp, x->off, x->mu, V, d, C, d_d2max);
+        launched = hipGetLastError() == hipSuccess;
+    }
+    if (launched) {
+        radius_finish_kernel<<<C, 256, 0, st>>>(x->bp, x->off, x->mu, d, (double)o->radius_slack, d_d2max, x->R, x->bmax, x->lnn);
+        launched = hipGetLastError() == hipSuccess;
+    }
+    const bool synced = hipStreamSynchronize(st) == hipSuccess;
+    (void)hipFree(d_d2max);
+    if (!launched) { csv_set_error("launch of the radius kernels failed"); return fail(CSV_EHIP); }
+    if (!synced) { csv_set_error("index build failed on the device: %s", hipGetErrorString(hipGetLastError())); return fail(CSV_EHIP); }
     (void)hipFree(d_labels);
     *out = x;
     return CSV_OK;
