@@ -219,6 +219,69 @@ __device__ __forceinline__ unsigned long long block_max_u64(unsigned long long v
     return r;
 }
 
+// The two largest of a set of distinct 64-bit keys (0 = none), reduced in one pass: the seed selection needs the
+// best unopened cluster and the one after it, and one reduction of pairs is cheaper than two reductions in a row.
+struct Top2 {
+    unsigned long long a, b;   // a > b, or 0 when absent
+};
+__device__ __forceinline__ Top2 top2_merge(Top2 x, Top2 y) {
+    const bool xg = x.a > y.a;
+    Top2 r;
+    r.a = xg ? x.a : y.a;
+    const unsigned long long loser = xg ? y.a : x.a, second = xg ? x.b : y.b;   // the winner's own runner-up
+    r.b = loser > second ? loser : second;
+    return r;
+}
+__device__ __forceinline__ Top2 top2_push(Top2 t, unsigned long long k) {
+    if (k > t.a) {
+        t.b = t.a;
+        t.a = k;
+    } else if (k > t.b) {
+        t.b = k;
+    }
+    return t;
+}
+template <int CTRL, int ROW_MASK, bool KEEP>
+__device__ __forceinline__ Top2 top2_dpp_step(Top2 v) {
+    // KEEP: lanes the move does not reach combine with their own value; otherwise with the identity (0, 0)
+    const int a_lo = (int)(unsigned)v.a, a_hi = (int)(unsigned)(v.a >> 32), b_lo = (int)(unsigned)v.b, b_hi = (int)(unsigned)(v.b >> 32);
+    Top2 y;
+    y.a = ((unsigned long long)(unsigned)dpp_move<CTRL, ROW_MASK>(KEEP ? a_hi : 0, a_hi) << 32) | (unsigned)dpp_move<CTRL, ROW_MASK>(KEEP ? a_lo : 0, a_lo);
+    y.b = ((unsigned long long)(unsigned)dpp_move<CTRL, ROW_MASK>(KEEP ? b_hi : 0, b_hi) << 32) | (unsigned)dpp_move<CTRL, ROW_MASK>(KEEP ? b_lo : 0, b_lo);
+    return y;
+}
+__device__ __forceinline__ Top2 wave_top2(Top2 v) {
+    // a lane never meets its own value in the first four steps (the moves are permutations); keys are distinct, so
+    // merging a pair with a pair that shares an element cannot happen before the broadcast steps, where the partner is
+    // another row's total
+    v = top2_merge(v, top2_dpp_step<0xB1, 0xf, true>(v));    // quad_perm [1,0,3,2]
+    v = top2_merge(v, top2_dpp_step<0x4E, 0xf, true>(v));    // quad_perm [2,3,0,1]
+    v = top2_merge(v, top2_dpp_step<0x141, 0xf, true>(v));   // row_half_mirror
+    v = top2_merge(v, top2_dpp_step<0x140, 0xf, true>(v));   // row_mirror
+    v = top2_merge(v, top2_dpp_step<0x142, 0xa, false>(v));  // row_bcast15 into rows 1 and 3
+    v = top2_merge(v, top2_dpp_step<0x143, 0xc, false>(v));  // row_bcast31 into rows 2 and 3
+    Top2 r;
+    r.a = ((unsigned long long)(unsigned)__builtin_amdgcn_readlane((int)(unsigned)(v.a >> 32), 63) << 32) | (unsigned)__builtin_amdgcn_readlane((int)(unsigned)v.a, 63);
+    r.b = ((unsigned long long)(unsigned)__builtin_amdgcn_readlane((int)(unsigned)(v.b >> 32), 63) << 32) | (unsigned)__builtin_amdgcn_readlane((int)(unsigned)v.b, 63);
+    return r;
+}
+// red: >= 32 64-bit words of LDS
+__device__ __forceinline__ Top2 block_top2(Top2 v, unsigned long long* red) {
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+    v = wave_top2(v);
+    __syncthreads();
+    if (lane == 0) {
+        red[2 * w] = v.a;
+        red[2 * w + 1] = v.b;
+    }
+    __syncthreads();
+    Top2 r;
+    r.a = red[0];
+    r.b = red[1];
+    for (int i = 1; i < nw; ++i) r = top2_merge(r, Top2{red[2 * i], red[2 * i + 1]});
+    return r;
+}
+
 // Monotone map float -> uint32: a > b  <=>  fkey(a) > fkey(b)  (for non-NaN values; -0 < +0)
 __device__ __forceinline__ uint32_t fkey(float f) {
     uint32_t u = __float_as_uint(f);

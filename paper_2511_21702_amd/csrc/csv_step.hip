@@ -493,7 +493,7 @@ struct SeqShared {
     int redi[16];
     int scan3[48];
     int rank[SEQ_THREADS];
-    u64 redu[16];
+    u64 redu[32];
     LseAcc redl[16];
     unsigned sel, rem, eq, cnt;
     int tbase, nbig;
@@ -1439,24 +1439,30 @@ __global__ __launch_bounds__(SEQ_THREADS) void round0_kernel(StepArgs a) {
     int rows = 0, m0 = 0;
     u64 kappa = ~0ull, nxt = 0;
     while (true) {
-        u64 best = 0;
+        // the best unopened cluster and the one after it, in one reduction: when the best completes the prefix,
+        // the runner-up is already the next unopened bound
+        Top2 t2{0ull, 0ull};
         for (int c = tid; c < C; c += nt) {
             const u64 kx = L.keys[c];
-            if (kx < kappa && kx > best) best = kx;
+            if (kx < kappa) t2 = top2_push(t2, kx);
         }
-        best = block_max_u64(best, s.redu);
-        if (rows >= need || best == 0) {   // best is now the largest unopened key (0: none left)
-            nxt = best;
+        t2 = block_top2(t2, s.redu);
+        if (t2.a == 0) {                   // nothing left to open
+            nxt = 0;
             break;
         }
-        const int cw = (int)(0xFFFFFFFFu - (uint32_t)best);
+        const int cw = (int)(0xFFFFFFFFu - (uint32_t)t2.a);
         if (tid == 0) {
             scl[m0] = cw;
             spos[m0] = rows;
         }
         rows += L.offl[cw + 1] - L.offl[cw];
         m0 += 1;
-        kappa = best;
+        kappa = t2.a;
+        if (rows >= need) {
+            nxt = t2.b;
+            break;
+        }
     }
     DBG_T(2);
     if (rows > a.K_max) {
