@@ -215,6 +215,49 @@ def test_step_single_cluster_and_singletons():
     case.close()
 
 
+def test_step_maximum_sizes():
+    # the limits the header states: CSV_MAX_BATCH sequences, CSV_MAX_K results, CSV_MAX_CLUSTERS clusters
+    r = synth.small_recipe("B256", V=3000, d=64, C=24, B=256, steps=1, iso_frac=0.2)
+    case = Case(r, seed=31)
+    t = case.run_steps(case.hidden(), 5, 1e-3, r.K_max_rows, O.COMBINE_ALL, "B=256")
+    _finish(t, "B=256")
+    assert t.n == 256
+    case.close()
+    r = synth.small_recipe("k1024", V=6000, d=72, C=12, B=2, steps=2, h_mode="mix")
+    case = Case(r, seed=32, K_cap=6000)
+    t = case.run_steps(case.hidden(), 1024, 1e-3, 6000, O.COMBINE_ALL, "k=1024")
+    _finish(t, "k=1024")
+    case.close()
+    r = synth.small_recipe("C8192", V=20000, d=128, C=8192, B=3, steps=2, sizes="zipf", zipf_min=1, h_mode="mix")
+    case = Case(r, seed=33, K_cap=20000)
+    t = case.run_steps(case.hidden(), 20, 1e-3, 5000, O.COMBINE_ALL, "C=8192")
+    _finish(t, "C=8192")
+    t = case.run_steps(case.hidden(), 20, 1e-3, 5000, O.COMBINE_ALL, "C=8192 levels", max_rounds=5, delta_clusters=40, relax=True)
+    _finish(t, "C=8192 levels")
+    case.close()
+
+
+def test_workspace_for_the_largest_shape_fits():
+    # C = CSV_MAX_CLUSTERS with the widest rows the LDS staging allows (d = 8192): the per-sequence kernels need
+    # almost all of a compute unit's LDS; creating the workspace checks that they fit
+    import paper_2511_21702_amd as csv
+    V, d, C = 8192, 8192, 8192
+    W = torch.zeros((V, d), dtype=torch.int16, device="cuda")
+    mu = np.zeros((C, d), dtype=np.float32)
+    idx = csv.csv_index_from_arrays(W, None, mu, np.ones(C, np.float32), np.zeros(C, np.float32), np.ones(C, np.int32),
+                                    np.arange(V, dtype=np.int32))
+    ws = csv.CsvWorkspace(idx, 64, V)
+    h = torch.zeros((2, d), dtype=torch.int16, device="cuda")
+    h[:, 0] = 0x3F80                                   # 1.0 in bf16
+    buf = csv.make_step_buffers(idx, 2, 4, 1e-3, V)
+    csv.csv_decode_step(ws, idx, h, buf)
+    torch.cuda.synchronize()
+    # every logit is 0 and every bound is R ||h|| = 1 > 0: no certificate can hold before all rows are open
+    assert (buf.flags.cpu().numpy() & csv.FLAG_INVALID_INPUT == 0).all()
+    assert np.allclose(buf.lse.cpu().numpy(), math.log(V), rtol=1e-6)
+    ws.free(); idx.free()
+
+
 def test_step_invalid_hidden_state_is_flagged():
     r = synth.small_recipe("inv", V=2000, d=256, C=16, B=3, steps=1)
     case = Case(r, seed=16)
