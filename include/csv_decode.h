@@ -100,7 +100,9 @@ void csv_workspace_free(csv_workspace* ws);
 
 typedef struct {
     int   k;           /* top-k size, 0..CSV_MAX_K; 0 disables the top-k certificate */
-    float eps;         /* softmax tolerance; <= 0 disables the softmax certificate, >= 1 always holds */
+    float eps;         /* softmax tolerance; <= 0 disables the softmax certificate, >= 1 always holds.  The top-p
+                          (nucleus) certificate of Section III is this test in delta form: eps = delta / (1 + delta)
+                          certifies a coverage of 1 - eps by the scored rows */
     int   K_max_rows;  /* budget K_max of Algorithm 1: a sequence whose planned |S| exceeds it falls back */
     int   combine;     /* CSV_COMBINE_ALL or CSV_COMBINE_ANY */
     /* Fallback levels (Section IV, "Runtime Optimization"); all zero = the two-round schedule with the full

@@ -452,6 +452,27 @@ def decode_step(W64: np.ndarray, b, index: OracleIndex, h_bits: np.ndarray, k: i
     return out
 
 
+# ----------------------------------------------------------------------------- top-p (nucleus) form
+def nucleus_eps(delta: float) -> float:
+    """Top-p certification (Section III, "Advanced Theoretical Improvements"): when the unopened clusters satisfy
+    sum_c n_c e^{U_c} <= delta e^{Z_S}, the probability mass outside S is at most delta / (1 + delta).  That is the
+    softmax test of Theorem 2 read with eps = delta / (1 + delta), since ln(eps / (1 - eps)) = ln(delta): a step
+    run with this eps carries the top-p coverage certificate 1 - eps; the stopping rule delta <= eps / (1 - eps)
+    is the same statement solved for delta."""
+    return delta / (1.0 + delta)
+
+
+def nucleus_holds(index: OracleIndex, U_row: np.ndarray, opened: np.ndarray, Z_S: float, delta: float) -> bool:
+    """The delta-form written out: sum over unopened, non-empty clusters of n_c e^{U_c} <= delta e^{Z_S}."""
+    mask = np.ones(index.C, dtype=bool)
+    mask[np.asarray(opened, dtype=np.int64)] = False
+    mask &= index.n > 0
+    if not mask.any():
+        return True
+    terms = np.log(index.n[mask].astype(np.float64)) + U_row[mask].astype(np.float64)
+    return bool(logsumexp(terms) <= math.log(delta) + Z_S)
+
+
 # ----------------------------------------------------------------------------- adaptive budget
 def kmax_update(K_max: float, rho_fall: float, alpha: float = 0.01, rho_target: float = 0.02,
                 literal: bool = False) -> float:

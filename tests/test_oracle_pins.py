@@ -559,3 +559,28 @@ def test_kmax_controller_closed_loop_needs_the_feedback_sign():
         for _ in range(20000):
             K = O.kmax_update(K, rho(K), alpha=0.01, rho_target=0.02, literal=literal)
         assert (abs(K - K_star) < 0.01 * d0) == toward, (literal, K, K_star)
+
+
+def test_nucleus_certificate_is_the_softmax_test_in_delta_form():
+    # Section III, top-p certification: the delta-form on the final open set agrees with the step's softmax flag at
+    # eps = delta / (1 + delta), and a certified step leaves at most that mass outside S (brute force over V)
+    r = synth.small_recipe(V=1500, d=48, C=30, B=1, steps=30, k=0, eps=1e-3, h_mode="mix", row_noise=0.3)
+    head = synth.make_head(r)
+    h = synth.make_hidden(r, head["centers"], steps=30)
+    W64 = O.bf16_to_f64(head["W_bits"])
+    idx = O.build_index(head["W_bits"], head["b"], head["labels"], r.C)
+    assert O.nucleus_eps(0.25) == 0.2 and math.isclose(math.log(0.25), math.log(0.2 / 0.8), rel_tol=1e-15)
+    seen = 0
+    for delta in (1e-3, 1e-2, 0.2):
+        eps = O.nucleus_eps(delta)
+        for s in range(30):
+            L = O.full_logits(W64, head["b"], O.bf16_to_f64(np.atleast_2d(h[s])))
+            res = O.decode_step(W64, head["b"], idx, h[s], 0, eps, r.K_max_rows, logits=L)[0]
+            if res["flags"] & O.FLAG_FALLBACK:
+                continue
+            seen += 1
+            assert res["flags"] == O.FLAG_SOFTMAX_CERT
+            assert O.nucleus_holds(idx, res["U"], res["clusters"], res["lse"], delta)
+            outside = 1.0 - math.exp(res["lse"] - O.logsumexp(L[0]))
+            assert outside <= delta / (1.0 + delta)
+    assert seen > 40
