@@ -318,23 +318,6 @@ __device__ __forceinline__ LseAcc lse_push(LseAcc a, float x) {
     }
     return a;
 }
-// Block-wide combination in a fixed order; every thread gets the result.  red: >= 16 LseAcc of LDS.
-__device__ __forceinline__ LseAcc block_lse_combine(LseAcc v, LseAcc* red) {
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-        LseAcc y;
-        y.m = __shfl_down(v.m, o, CSV_WAVE);
-        y.s = __shfl_down(v.s, o, CSV_WAVE);
-        if (lane + o < 64) v = lse_combine(v, y);
-    }
-    __syncthreads();
-    if (lane == 0) red[w] = v;
-    __syncthreads();
-    LseAcc r = red[0];
-    for (int i = 1; i < nw; ++i) r = lse_combine(r, red[i]);
-    return r;
-}
 __device__ __forceinline__ float lse_value(LseAcc a) { return a.s == 0.f ? -INFINITY : a.m + logf(a.s); }
 
 // ---------------------------------------------------------------------------------------------- internal entry points

@@ -1,12 +1,14 @@
 // Per-step kernels of the certified sub-vocabulary LM-head path and the entry points that enqueue them.
 //
-//   bound_kernel       U[b,c] = <mu_c,h_b> + R_c ||h_b|| + bmax_c                               (Eq. "cluster_bound")
-//   seed_kernel        shortest prefix of the bound order holding >= max(k,1) rows, next bound, log tail mass;
-//                      compaction of the opened clusters into row tiles                         (Algorithm 1: queue, PopMax)
-//   gemv_tiles_kernel  logits of the opened rows of W' (contiguous per cluster)                 (Algorithm 1: sparse GEMV)
-//   cert_kernel        top-k, log-sum-exp, both certificates; round-1 plan and compaction       (Definitions 1-2, Theorems 1-2)
-//   full_gemv_kernel   all V logits for the sequences that fall back                            (Eq. "logit")
-//   fb_topk_kernel / fb_final_kernel   top-k and log-sum-exp over V for those sequences
+//   bound1_kernel / bound_kernel / bound_mfma_kernel + bound_finish_kernel
+//                      U[b,c] = <mu_c,h_b> + R_c ||h_b|| + bmax_c  for 1, 2..8 and more sequences   (Eq. "cluster_bound")
+//   round0_kernel      per sequence: shortest prefix of the bound order holding >= max(k,1) rows, next bound, log tail
+//                      mass (Algorithm 1: queue, PopMax); logits of the prefix rows of W' (Algorithm 1: sparse GEMV);
+//                      top-k, log-sum-exp and both certificates, or the plan of the next round
+//                                                                                      (Definitions 1-2, Theorems 1-2)
+//   tail_kernel        only when some sequence needs it: further rounds (tile GEMV + certification), then all V logits,
+//                      top-k and log-sum-exp for the sequences that fall back                          (Eq. "logit")
+//   full_gemv_kernel / full_mfma_kernel   all V logits as an entry point of their own
 //
 // Everything is enqueued on the caller's stream; decisions (round 1, fallback) are taken on the device.
 // The open set of a sequence is {c : key_c >= kappa} for a 64-bit key that encodes (bound, cluster id), so the
@@ -434,27 +436,6 @@ __global__ __launch_bounds__(256) void bound_finish_kernel(StepArgs a, const flo
 }
 
 // ================================================================================================ block scans
-// Exclusive prefix sum over one int per thread (blockDim <= 1024).  wtot: 16 ints of LDS.
-__device__ __forceinline__ int block_excl_scan_i(int v, int* wtot, int* total) {
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
-    int x = v;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        int y = __shfl_up(x, o, CSV_WAVE);
-        if (lane >= o) x += y;
-    }
-    __syncthreads();
-    if (lane == 63) wtot[w] = x;
-    __syncthreads();
-    int base = 0, tot = 0;
-    for (int i = 0; i < nw; ++i) {
-        if (i < w) base += wtot[i];
-        tot += wtot[i];
-    }
-    if (total) *total = tot;
-    return base + x - v;
-}
-
 // Combination of everything owned by the threads AFTER this one (exclusive suffix), for log-sum-exp partials.
 __device__ __forceinline__ LseAcc block_excl_suffix_lse(LseAcc v, LseAcc* wtot) {
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
