@@ -737,6 +737,9 @@ __device__ __forceinline__ void gemv_tiles_device(const StepArgs& a, int round, 
     // a block takes a contiguous run of the list: mostly one sequence (h is staged once or twice per block, not
     // once per tile) and neighbouring rows
     const int per = (total + nblocks - 1) / nblocks;
+#ifdef CSV_DEBUG_TIMING
+    if (threadIdx.x == 0 && a.dbg && round == 1) a.dbg[blockIdx.x * 64 + 30] = (unsigned long long)total;
+#endif
     const int g0 = block * per, g1 = min(total, g0 + per);
     int cached[2] = {-1, -1};
     Tile tA = fetch(g0 < g1 ? g0 : total), tB = fetch(g0 + 1 < g1 ? g0 + 1 : total);
