@@ -47,6 +47,11 @@ def head_flops(V: int, d: int) -> int:
     return 2 * V * d
 
 
+def metadata_bytes_bf16(C: int, d: int) -> int:
+    """Footprint with bfloat16 centroids and float32 radius / bias maximum / size: C (2d + 4 + 4 + 4)."""
+    return C * (2 * d + 12)
+
+
 def metadata_bytes(C: int, d: int) -> int:
     """Index metadata footprint C*(4d + 8 + 4) bytes (Section IV, offline preprocessing)."""
     return C * (d * 4 + 8 + 4)
@@ -106,6 +111,13 @@ class OracleIndex:
         return self.perm[self.off[c]:self.off[c + 1]]
 
 
+def _round_bf16(x: np.ndarray) -> np.ndarray:
+    """float32 -> nearest bfloat16 (ties to even), returned as float32 values."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    r = (u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))) & np.uint32(0xFFFF0000)
+    return r.view(np.float32)
+
+
 def _round_up_f32(x: np.ndarray) -> np.ndarray:
     x = np.asarray(x, dtype=np.float64)
     y = x.astype(np.float32)
@@ -114,7 +126,8 @@ def _round_up_f32(x: np.ndarray) -> np.ndarray:
     return y
 
 
-def build_index(W_bits: np.ndarray, b, labels: np.ndarray, C: int, radius_slack: float = 2.0 ** -14) -> OracleIndex:
+def build_index(W_bits: np.ndarray, b, labels: np.ndarray, C: int, radius_slack: float = 2.0 ** -14,
+                centroid_bf16: bool = False) -> OracleIndex:
     """Index from a cluster assignment.
 
     mu_c = mean of the cluster's rows, stored as float32;  R_c = max_i ||W_i - mu_c||_2 measured to the
@@ -122,6 +135,8 @@ def build_index(W_bits: np.ndarray, b, labels: np.ndarray, C: int, radius_slack:
     float32, so that float32 evaluation of the bound stays above float32 evaluation of the logits.
     Rows are permuted so each cluster is contiguous (Algorithm 1, "contiguous by reordering"):
     clusters in id order, tokens inside a cluster by ascending original id.
+    centroid_bf16: the stored centroid is the mean rounded to bfloat16 (nearest even); the radius is measured to
+    that stored value, so the bound of Eq. "cluster_bound" stays valid and the centroids take half the bytes.
     """
     labels = np.asarray(labels, dtype=np.int64)
     V, d = W_bits.shape
@@ -138,6 +153,8 @@ def build_index(W_bits: np.ndarray, b, labels: np.ndarray, C: int, radius_slack:
             continue
         Wc = bf16_to_f64(W_bits[rows])
         mu[c] = Wc.mean(axis=0).astype(np.float32)
+        if centroid_bf16:
+            mu[c] = _round_bf16(mu[c])
         diff = Wc - mu[c].astype(np.float64)[None, :]
         R[c] = math.sqrt(float(np.max(np.einsum("ij,ij->i", diff, diff))))
         bmax[c] = np.float32(0.0) if bb is None else bb[rows].max()

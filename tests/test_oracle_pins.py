@@ -584,3 +584,35 @@ def test_nucleus_certificate_is_the_softmax_test_in_delta_form():
             outside = 1.0 - math.exp(res["lse"] - O.logsumexp(L[0]))
             assert outside <= delta / (1.0 + delta)
     assert seen > 40
+
+
+def test_bf16_centroids_keep_the_bound_sound_and_cost_little():
+    # the radius is measured to the stored (rounded) centroid, so Eq. "cluster_bound" still dominates every logit
+    r = synth.small_recipe(V=3000, d=96, C=24, B=4, steps=6, h_mode="mix", iso_frac=0.3)
+    head = synth.make_head(r)
+    h = synth.make_hidden(r, head["centers"], steps=6)
+    W64 = O.bf16_to_f64(head["W_bits"])
+    i32 = O.build_index(head["W_bits"], head["b"], head["labels"], r.C)
+    i16 = O.build_index(head["W_bits"], head["b"], head["labels"], r.C, centroid_bf16=True)
+    # stored values are bfloat16-exact and within half a bf16 ulp (at most 2^-8 relative) of the float32 centroid
+    bits = i16.mu.view(np.uint32)
+    assert np.all(bits & 0xFFFF == 0)
+    assert np.all(np.abs(i16.mu - i32.mu) <= 2.0 ** -8 * np.abs(i32.mu) + 1e-45)
+    assert np.array_equal(i16.perm, i32.perm) and np.array_equal(i16.bmax, i32.bmax)
+    # triangle inequality: the radius moves by at most the distance between the two stored centroids
+    shift = np.sqrt(((i16.mu.astype(np.float64) - i32.mu.astype(np.float64)) ** 2).sum(axis=1))
+    assert np.all(np.abs(i16.R.astype(np.float64) - i32.R.astype(np.float64)) <= 1.001 * shift * (1 + 2.0 ** -14) + 1e-6)
+    for s in range(6):
+        h64 = O.bf16_to_f64(h[s])
+        L = O.full_logits(W64, head["b"], h64)
+        for idx in (i16, i32):
+            U, hn = O.cluster_bounds(idx, h64)
+            for c in range(r.C):
+                rows = idx.rows(c)
+                assert np.all(L[:, rows].max(axis=1) <= U[:, c])
+        # steps stay certified-correct with the looser bounds
+        for b_, res in enumerate(O.decode_step(W64, head["b"], i16, h[s], 5, 1e-3, r.K_max_rows, logits=L)):
+            if res["flags"] & O.FLAG_TOPK_CERT:
+                ids, _ = O.topk_bruteforce(L[b_], 5)
+                assert np.array_equal(res["ids"], ids)
+    assert O.metadata_bytes_bf16(1024, 4096) == 1024 * (8192 + 12)
