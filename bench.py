@@ -25,10 +25,10 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def step_bytes(r, C, rows_union: float, any_fallback_frac: float, k: int) -> float:
+def step_bytes(r, C, rows_union: float, any_fallback_frac: float, k: int, mu_bytes: int = 4) -> float:
     """Algorithmic bytes of one batch step: centroids + cluster metadata, h, each distinct opened row of W with its
     bias, the whole of W with bias when any sequence falls back, and the outputs."""
-    return (C * r.d * 4 + 12 * C + r.B * r.d * 2 + rows_union * (2 * r.d + 4)
+    return (C * r.d * mu_bytes + 12 * C + r.B * r.d * 2 + rows_union * (2 * r.d + 4)
             + any_fallback_frac * r.V * (2 * r.d + 4) + r.B * (8 * k + 16))
 
 
@@ -40,6 +40,7 @@ def main() -> int:
     ap.add_argument("--config", default="c2")
     ap.add_argument("--max-rounds", type=int, default=0, help="fallback levels: scoring rounds allowed (0 = the two-round schedule)")
     ap.add_argument("--delta-clusters", type=int, default=0, help="fallback levels: clusters per partial expansion (0 = off)")
+    ap.add_argument("--bf16-centroids", action="store_true", help="index option: centroids stored as bfloat16 (half the bound kernel's bytes)")
     ap.add_argument("--relax", action="store_true", help="fallback levels: accept the softmax bound at 2 eps before falling back")
     ap.add_argument("--cpu-steps", type=int, default=-1, help="oracle steps to time (-1: sized to ~15 s, 0: skip)")
     ap.add_argument("--traffic-probe", action="store_true",
@@ -65,7 +66,7 @@ def main() -> int:
     log(f"[bench] {r.name}: V={r.V} d={r.d} C={r.C} B={r.B} generated in {time.time() - t0:.1f}s")
     dW = csv.bits_to_device(head["W_bits"])
     db = torch.from_numpy(head["b"]).cuda()
-    idx = csv.csv_build_index(dW, db, r.C, init_labels=head["labels"].astype(np.int32))
+    idx = csv.csv_build_index(dW, db, r.C, init_labels=head["labels"].astype(np.int32), centroid_bf16=args.bf16_centroids)
     del dW
     ws = csv.CsvWorkspace(idx, r.B, r.K_max_rows)
     dh = csv.bits_to_device(h_bits)
@@ -167,7 +168,7 @@ def main() -> int:
     # Algorithmic bytes per launch: bound_kernel reads the centroids and cluster metadata once and h, writes U;
     # the gathered GEMV reads each opened row with its bias and id and h per tile; the tail's full product reads W' once.
     mean_rows_seq = rows_sum / max(1, n_seq - int(round(fb_rate * n_seq)))
-    bound_bytes = r.C * r.d * 4 + 12 * r.C + r.B * r.d * 2 + 4 * r.B * r.C
+    bound_bytes = r.C * r.d * (2 if args.bf16_centroids else 4) + 12 * r.C + r.B * r.d * 2 + 4 * r.B * r.C
     gemv_bytes = (rows_sum / nstat) * (2 * r.d + 16) + r.B * r.d * 2
     full_bytes_launch = r.V * (2 * r.d + 8) + r.B * r.d * 2
     # The dominant kernel is the one that moves most of the step's bytes: the bound kernel (all centroids) on the
@@ -223,7 +224,7 @@ def main() -> int:
             f = line.split()
             if len(f) == 3 and f[0] == "traffic_bytes_per_launch" and dom_name.startswith(f[1]):
                 traffic = int(f[2])
-    bstep = step_bytes(r, r.C, rows_union_sum / nstat, anyfb / nstat, r.k)
+    bstep = step_bytes(r, r.C, rows_union_sum / nstat, anyfb / nstat, r.k, 2 if args.bf16_centroids else 4)
     eff_gbs = bstep / (ms_per_step * 1e-3) / 1e9
 
     # ---------------- CPU baseline: the oracle as it stands, on a bounded sample of the same workload
@@ -236,7 +237,7 @@ def main() -> int:
         except Exception:
             cores = os.cpu_count()
         W64 = O.bf16_to_f64(head["W_bits"])
-        oidx = O.build_index(head["W_bits"], head["b"], head["labels"], r.C)
+        oidx = O.build_index(head["W_bits"], head["b"], head["labels"], r.C, centroid_bf16=args.bf16_centroids)
         t1 = time.perf_counter()
         olad = dict(max_rounds=max(args.max_rounds, 2), delta_clusters=args.delta_clusters, relax=args.relax)
         O.decode_step(W64, head["b"], oidx, h_bits[0], r.k, r.eps, r.K_max_rows, **olad)
@@ -257,6 +258,7 @@ def main() -> int:
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{r.name}: V={r.V} d={r.d} C={r.C} B={r.B} k={r.k} eps={r.eps:g} K_max={r.K_max_rows} "
                                f"combine=ALL, bf16 W and h, planted clusters"
+                               + (", bf16 centroids" if args.bf16_centroids else "")
                                + (f", fallback levels max_rounds={args.max_rounds} delta_clusters={args.delta_clusters} relax={int(args.relax)}"
                                   if (args.max_rounds or args.delta_clusters or args.relax) else ""), "batch": r.B},
         "roofline": {"bound": "hbm", "kernel": dom_name, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",

@@ -58,6 +58,8 @@ typedef struct {
     const int32_t* h_init_rows;  /* HOST int32[C] tokens whose rows are the starting centroids; used when
                                     h_init_labels is NULL */
     float radius_slack;          /* rho >= 0: stored radius = roundup_f32(R_c(1+rho) + rho*||mu_c||) */
+    int   centroid_bf16;         /* nonzero: store the centroids rounded to bfloat16 (nearest even) and measure the radii
+                                    to the rounded values: the bound stays valid, the bound kernels read half the bytes */
 } csv_build_opts;
 
 /*
@@ -84,6 +86,12 @@ int csv_build_index(const uint16_t* d_W, const float* d_b, int V, int d, int C,
 int csv_index_from_arrays(const uint16_t* d_W, const float* d_b, int V, int d, int C,
                           const float* h_mu, const float* h_R, const float* h_bmax,
                           const int32_t* h_n, const int32_t* h_perm, void* stream, csv_index** out);
+
+/*
+ * Switch an imported index to bfloat16 centroids: every value of h_mu must already be a bfloat16 (the radii must have
+ * been measured to those rounded centroids); otherwise CSV_EINVAL and the index is unchanged.  Allocates C*d*2 bytes.
+ */
+int csv_index_use_bf16_centroids(csv_index* idx, void* stream);
 
 /* Copy the metadata back to HOST buffers of the sizes above (any pointer may be NULL to skip it). Synchronous. */
 int csv_index_export(const csv_index* idx, float* h_mu, float* h_R, float* h_bmax, int32_t* h_n, int32_t* h_perm);

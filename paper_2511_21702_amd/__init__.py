@@ -23,14 +23,14 @@ EXPORTS = [
     "csv_build_index", "csv_index_from_arrays", "csv_index_export", "csv_index_dims", "csv_index_free",
     "csv_workspace_create", "csv_workspace_free", "csv_decode_step", "csv_bounds", "csv_full_logits",
     "csv_profile_begin", "csv_profile_end", "csv_last_error", "csv_kmax_init", "csv_kmax_update",
-    "csv_workspace_set_spin_limit",
+    "csv_workspace_set_spin_limit", "csv_index_use_bf16_centroids",
 ]
 PROFILE_STAGES = ["bounds", "round0", "tail"]
 
 
 class BuildOpts(C.Structure):
     _fields_ = [("iters", C.c_int), ("h_init_labels", C.c_void_p), ("h_init_rows", C.c_void_p),
-                ("radius_slack", C.c_float)]
+                ("radius_slack", C.c_float), ("centroid_bf16", C.c_int)]
 
 
 class StepParams(C.Structure):
@@ -73,6 +73,7 @@ def _load() -> C.CDLL:
     lib.csv_kmax_init.argtypes = [C.POINTER(KmaxCtl), ci, ci, ci, C.c_double, C.c_double, ci]
     lib.csv_kmax_update.argtypes = [C.POINTER(KmaxCtl), ci, ci]
     lib.csv_workspace_set_spin_limit.argtypes = [vp, ci]
+    lib.csv_index_use_bf16_centroids.argtypes = [vp, vp]
     return lib
 
 
@@ -134,14 +135,15 @@ class CsvIndex:
 
 
 def csv_build_index(W: torch.Tensor, b, C_clusters: int, init_labels=None, init_rows=None, iters: int = 0,
-                    radius_slack: float = 2.0 ** -14, stream=None) -> CsvIndex:
+                    radius_slack: float = 2.0 ** -14, stream=None, centroid_bf16: bool = False) -> CsvIndex:
     """W: [V,d] 16-bit CUDA tensor (bf16 patterns, original token order); b: float32 CUDA [V] or None.
     init_labels / init_rows: host int32 numpy arrays (see csv_build_opts)."""
     import numpy as np
     _dev2(W, "W")
     V, d = W.shape
     keep = []
-    opts = BuildOpts(iters=iters, h_init_labels=None, h_init_rows=None, radius_slack=radius_slack)
+    opts = BuildOpts(iters=iters, h_init_labels=None, h_init_rows=None, radius_slack=radius_slack,
+                     centroid_bf16=int(bool(centroid_bf16)))
     if init_labels is not None:
         a = np.ascontiguousarray(init_labels, dtype=np.int32)
         assert a.shape == (V,)
@@ -160,8 +162,9 @@ def csv_build_index(W: torch.Tensor, b, C_clusters: int, init_labels=None, init_
     return CsvIndex(out.value)
 
 
-def csv_index_from_arrays(W: torch.Tensor, b, mu, R, bmax, n, perm, stream=None) -> CsvIndex:
-    """Import metadata computed elsewhere (host numpy arrays)."""
+def csv_index_from_arrays(W: torch.Tensor, b, mu, R, bmax, n, perm, stream=None, centroid_bf16: bool = False) -> CsvIndex:
+    """Import metadata computed elsewhere (host numpy arrays).  centroid_bf16: mu holds bfloat16 values (and the
+    radii were measured to them); the index then keeps and reads the centroids as bfloat16."""
     import numpy as np
     _dev2(W, "W")
     V, d = W.shape
@@ -176,7 +179,10 @@ def csv_index_from_arrays(W: torch.Tensor, b, mu, R, bmax, n, perm, stream=None)
     bptr = None if b is None else b.data_ptr()
     _check(lib.csv_index_from_arrays(W.data_ptr(), bptr, V, d, Cc, mu.ctypes.data, R.ctypes.data, bmax.ctypes.data,
                                      n.ctypes.data, perm.ctypes.data, _stream(stream), C.byref(out)))
-    return CsvIndex(out.value)
+    idx = CsvIndex(out.value)
+    if centroid_bf16:
+        _check(lib.csv_index_use_bf16_centroids(idx._h, _stream(stream)))
+    return idx
 
 
 class CsvWorkspace:

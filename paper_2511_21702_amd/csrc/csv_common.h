@@ -16,6 +16,8 @@ struct csv_index {
     float* bp;       // [V]   permuted bias (zeros when the head has none)
     int32_t* perm;   // [V]   permuted row -> original token id
     float* mu;       // [C*d] centroids, float32
+    uint16_t* mu16;  // [C*d] the same centroids as bf16 when they are stored rounded (NULL otherwise); mu then holds
+                     //       the rounded values too
     float* R;        // [C]   stored radii
     float* bmax;     // [C]   per-cluster bias maximum (-inf for an empty cluster)
     int32_t* n;      // [C]   rows per cluster

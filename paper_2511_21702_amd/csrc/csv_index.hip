@@ -256,7 +256,7 @@ int csv_index_alloc(int V, int d, int C, csv_index** out) {
 
 extern "C" void csv_index_free(csv_index* x) {
     if (!x) return;
-    void* ptrs[] = {x->Wp, x->bp, x->perm, x->mu, x->R, x->bmax, x->n, x->off, x->lnn};
+    void* ptrs[] = {x->Wp, x->bp, x->perm, x->mu, x->mu16, x->R, x->bmax, x->n, x->off, x->lnn};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
     free(x);
@@ -268,6 +268,53 @@ extern "C" int csv_index_dims(const csv_index* x, int* V, int* d, int* C) {
     if (d) *d = x->d;
     if (C) *C = x->C;
     return CSV_OK;
+}
+
+// Centroids stored as bfloat16: mu is rounded in place (nearest even) and the 16-bit patterns go to mu16.
+// check != 0: nothing is rounded; *bad is set when a value is not already a bfloat16.
+__global__ __launch_bounds__(256) void centroid_bf16_kernel(float* __restrict__ mu, uint16_t* __restrict__ mu16, size_t n, int check,
+                                                            int* __restrict__ bad) {
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    const uint32_t u = __float_as_uint(mu[i]);
+    if (check) {
+        if (u & 0xffffu) *bad = 1;
+        mu16[i] = (uint16_t)(u >> 16);
+        return;
+    }
+    const uint32_t r = (u + 0x7fffu + ((u >> 16) & 1u)) & 0xffff0000u;
+    mu[i] = __uint_as_float(r);
+    mu16[i] = (uint16_t)(r >> 16);
+}
+
+static int store_centroids_bf16(csv_index* x, int check, hipStream_t st) {
+    const size_t n = (size_t)x->C * x->d;
+    if (!x->mu16 && hipMalloc((void**)&x->mu16, n * 2) != hipSuccess) { csv_set_error("out of device memory (bf16 centroids)"); return CSV_ENOMEM; }
+    int* d_bad = nullptr;
+    if (hipMalloc((void**)&d_bad, 4) != hipSuccess) { csv_set_error("out of device memory"); return CSV_ENOMEM; }
+    int h_bad = 0;
+    hipError_t e = hipMemsetAsync(d_bad, 0, 4, st);
+    if (e == hipSuccess) {
+        centroid_bf16_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(x->mu, x->mu16, n, check, d_bad);
+        e = hipGetLastError();
+    }
+    if (e == hipSuccess) e = hipMemcpyAsync(&h_bad, d_bad, 4, hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    (void)hipFree(d_bad);
+    if (e != hipSuccess) { csv_set_error("bf16 centroid conversion failed: %s", hipGetErrorString(e)); return CSV_EHIP; }
+    if (h_bad) {
+        (void)hipFree(x->mu16);
+        x->mu16 = nullptr;
+        csv_set_error("centroids are not bfloat16 values: the radii of this index were not measured to rounded centroids");
+        return CSV_EINVAL;
+    }
+    return CSV_OK;
+}
+
+extern "C" int csv_index_use_bf16_centroids(csv_index* x, void* stream) {
+    if (!x) { csv_set_error("null index"); return CSV_EINVAL; }
+    if (x->mu16) return CSV_OK;
+    return store_centroids_bf16(x, 1, (hipStream_t)stream);
 }
 
 // labels -> sizes, offsets and the permutation (clusters in id order, tokens by ascending id inside a cluster)
@@ -354,6 +401,7 @@ extern "C" int csv_build_index(const uint16_t* d_W, const float* d_b, int V, int
         for (int c = 0; c < C; ++c) nmax = n[c] > nmax ? n[c] : nmax;
         x->ln_nmax = (float)log((double)nmax);
     }
+    if (o->centroid_bf16 && (rc = store_centroids_bf16(x, 0, st))) return fail(rc);
     unsigned long long* d_d2max = nullptr;
     if (hipMalloc((void**)&d_d2max, (size_t)C * 8) != hipSuccess) { csv_set_error("out of device memory (radius scratch)"); return fail(CSV_ENOMEM); }
     bool launched = hipMemsetAsync(d_d2max, 0, (size_t)C * 8, st) == hipSuccess;

@@ -16,6 +16,7 @@
 #include "csv_common.h"
 
 #include <math.h>
+#include <type_traits>
 #include <stdarg.h>
 #include <stdlib.h>
 #include <string.h>
@@ -37,6 +38,7 @@ struct StepArgs {
     const float* bp;
     const int32_t* perm;
     const float* mu;
+    const uint16_t* mu16;   // bf16 copy of the centroids, or NULL
     const float* R;
     const float* bmax;
     const int32_t* n;
@@ -112,9 +114,32 @@ __device__ __forceinline__ void reset_step_counters(int* counters, int B, int nt
 // Blocks are dealt round-robin to the 8 XCDs, so group g = (block % 8) * groups_per_xcd + block / 8 keeps
 // every XCD on the same centroid slice step after step.
 #define BOUND_PF 8
+// A "unit" is one 128-bit load of a centroid row: four float32 values, or eight bfloat16 values when the index
+// stores its centroids rounded (MU16).  The matching piece of h is 8 resp. 16 bytes of bf16.
+template <bool MU16>
+__device__ __forceinline__ const uint4* mu_row(const StepArgs& a, int c) {
+    return MU16 ? reinterpret_cast<const uint4*>(a.mu16 + (size_t)c * a.d) : reinterpret_cast<const uint4*>(a.mu + (size_t)c * a.d);
+}
+template <bool MU16>
+__device__ __forceinline__ int mu_units(int d) { return MU16 ? d >> 3 : d >> 2; }
+// acc += <unit of mu, matching piece of h>;  hrow: the sequence's h as 32-bit words (two bf16 each)
+template <bool MU16, class HP>
+__device__ __forceinline__ float mu_fma(const uint4& m, HP hrow, int unit, float acc) {
+    if constexpr (MU16) {
+        const uint4 hv = reinterpret_cast<const uint4*>(hrow)[unit];
+        return dot8_bf16(m, hv, acc);
+    } else {
+        const uint2 hv = reinterpret_cast<const uint2*>(hrow)[unit];
+        acc = fmaf(__uint_as_float(m.x), bf16_lo(hv.x), acc);
+        acc = fmaf(__uint_as_float(m.y), bf16_hi(hv.x), acc);
+        acc = fmaf(__uint_as_float(m.z), bf16_lo(hv.y), acc);
+        acc = fmaf(__uint_as_float(m.w), bf16_hi(hv.y), acc);
+        return acc;
+    }
+}
 #define BOUND_THREADS 512
 #define BOUND_HREG 8       // 128-bit pieces of h per thread: 8 x 512 x 16 B covers the 64 KB that BT sequences may take in LDS
-template <int BT>
+template <int BT, bool MU16>
 __global__ __launch_bounds__(BOUND_THREADS) void bound_kernel(StepArgs a, float* __restrict__ U_out, float* __restrict__ hn_out,
                                                               int reset_counters, int groups, int groups_per_xcd, int wpc) {
     extern __shared__ uint4 hs4[];
@@ -123,7 +148,7 @@ __global__ __launch_bounds__(BOUND_THREADS) void bound_kernel(StepArgs a, float*
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int b0 = blockIdx.y * BT;
     const int nb = min(BT, a.B - b0);
-    const int nch = a.d >> 3, nq = a.d >> 2;
+    const int nch = a.d >> 3, nq = mu_units<MU16>(a.d);
     const int cpb = (BOUND_THREADS / 64) / wpc, cl = wave / wpc, slice = wave - cl * wpc;
     const int g = (blockIdx.x & 7) * groups_per_xcd + (blockIdx.x >> 3);
     const int c = g * cpb + cl;
@@ -140,12 +165,12 @@ __global__ __launch_bounds__(BOUND_THREADS) void bound_kernel(StepArgs a, float*
     }
     // this wave's slice of the centroid row
     const int seg = (nq + wpc - 1) / wpc, lo = slice * seg, hi = min(nq, lo + seg);
-    const float4* mrow = reinterpret_cast<const float4*>(a.mu + (size_t)(valid ? c : 0) * a.d);
-    float4 pf[BOUND_PF];
+    const uint4* mrow = mu_row<MU16>(a, valid ? c : 0);
+    uint4 pf[BOUND_PF];
 #pragma unroll
     for (int j = 0; j < BOUND_PF; ++j) {
         const int i = lo + lane + 64 * j;
-        pf[j] = (valid && i < hi) ? mrow[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+        pf[j] = (valid && i < hi) ? mrow[i] : make_uint4(0, 0, 0, 0);
     }
     float Rc = 0.f, bm = 0.f;
     int ncl = 0;
@@ -174,7 +199,6 @@ __global__ __launch_bounds__(BOUND_THREADS) void bound_kernel(StepArgs a, float*
     __syncthreads();
     if (blockIdx.x == 0 && tid < nb && hn_out) hn_out[b0 + tid] = hn[tid];
 
-    const uint2* hs2 = reinterpret_cast<const uint2*>(hs4);
     float acc[BT];
 #pragma unroll
     for (int s = 0; s < BT; ++s) acc[s] = 0.f;
@@ -182,29 +206,16 @@ __global__ __launch_bounds__(BOUND_THREADS) void bound_kernel(StepArgs a, float*
     for (int j = 0; j < BOUND_PF; ++j) {
         const int i = lo + lane + 64 * j;
         if (i < hi) {
-            const float4 m = pf[j];
 #pragma unroll
-            for (int s = 0; s < BT; ++s) {
-                const uint2 hv = hs2[s * nq + i];
-                acc[s] = fmaf(m.x, bf16_lo(hv.x), acc[s]);
-                acc[s] = fmaf(m.y, bf16_hi(hv.x), acc[s]);
-                acc[s] = fmaf(m.z, bf16_lo(hv.y), acc[s]);
-                acc[s] = fmaf(m.w, bf16_hi(hv.y), acc[s]);
-            }
+            for (int s = 0; s < BT; ++s) acc[s] = mu_fma<MU16>(pf[j], hs4 + s * nch, i, acc[s]);
         }
     }
     if (valid) {
 #pragma unroll 4
         for (int i = lo + lane + 64 * BOUND_PF; i < hi; i += 64) {
-            const float4 m = mrow[i];
+            const uint4 m = mrow[i];
 #pragma unroll
-            for (int s = 0; s < BT; ++s) {
-                const uint2 hv = hs2[s * nq + i];
-                acc[s] = fmaf(m.x, bf16_lo(hv.x), acc[s]);
-                acc[s] = fmaf(m.y, bf16_hi(hv.x), acc[s]);
-                acc[s] = fmaf(m.z, bf16_lo(hv.y), acc[s]);
-                acc[s] = fmaf(m.w, bf16_hi(hv.y), acc[s]);
-            }
+            for (int s = 0; s < BT; ++s) acc[s] = mu_fma<MU16>(m, hs4 + s * nch, i, acc[s]);
         }
     }
 #pragma unroll
@@ -236,29 +247,31 @@ __global__ __launch_bounds__(BOUND_THREADS) void bound_kernel(StepArgs a, float*
 // L2 / L1 with the same addresses in every block; each wave takes its slice of h straight from global memory next to
 // its centroid slice, and ||h||^2 is the sum of the slices' partial sums of squares (slice order: the same value
 // in every block).
+template <bool MU16>
 __global__ __launch_bounds__(BOUND_THREADS) void bound1_kernel(StepArgs a, float* __restrict__ U_out, float* __restrict__ hn_out,
                                                                int reset_counters, int groups, int groups_per_xcd, int wpc) {
     __shared__ float part[BOUND_THREADS / 64], parth[BOUND_THREADS / 64];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int nq = a.d >> 2;
+    const int nq = mu_units<MU16>(a.d);
     const int cpb = (BOUND_THREADS / 64) / wpc, cl = wave / wpc, slice = wave - cl * wpc;
     const int g = (blockIdx.x & 7) * groups_per_xcd + (blockIdx.x >> 3);
     const int c = g * cpb + cl;
     const bool valid = g < groups && c < a.C;
     const int seg = (nq + wpc - 1) / wpc, lo = slice * seg, hi = min(nq, lo + seg);
-    const float4* mrow = reinterpret_cast<const float4*>(a.mu + (size_t)(valid ? c : 0) * a.d);
-    const uint2* h2 = reinterpret_cast<const uint2*>(a.h);
-    float4 pf[BOUND_PF];
-    uint2 ph[BOUND_PF];
+    const uint4* mrow = mu_row<MU16>(a, valid ? c : 0);
+    typedef typename std::conditional<MU16, uint4, uint2>::type hpiece;   // the piece of h that goes with one unit
+    const hpiece* hp = reinterpret_cast<const hpiece*>(a.h);
+    uint4 pf[BOUND_PF];
+    hpiece ph[BOUND_PF];
 #pragma unroll
     for (int j = 0; j < BOUND_PF; ++j) {
         const int i = lo + lane + 64 * j;
-        pf[j] = (valid && i < hi) ? mrow[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+        pf[j] = (valid && i < hi) ? mrow[i] : make_uint4(0, 0, 0, 0);
     }
 #pragma unroll
     for (int j = 0; j < BOUND_PF; ++j) {
         const int i = lo + lane + 64 * j;
-        ph[j] = i < hi ? h2[i] : make_uint2(0, 0);
+        ph[j] = i < hi ? hp[i] : hpiece{};
     }
     float Rc = 0.f, bm = 0.f;
     int ncl = 0;
@@ -270,23 +283,21 @@ __global__ __launch_bounds__(BOUND_THREADS) void bound1_kernel(StepArgs a, float
     if (reset_counters && blockIdx.x == 0)
         reset_step_counters(a.counters, a.B, BOUND_THREADS);
     float acc = 0.f, hh = 0.f;
-    auto step = [&](const float4& m, const uint2& hv) {
-        const float h0 = bf16_lo(hv.x), h1 = bf16_hi(hv.x), h2v = bf16_lo(hv.y), h3 = bf16_hi(hv.y);
-        acc = fmaf(m.x, h0, acc);
-        acc = fmaf(m.y, h1, acc);
-        acc = fmaf(m.z, h2v, acc);
-        acc = fmaf(m.w, h3, acc);
-        hh = fmaf(h0, h0, hh);
-        hh = fmaf(h1, h1, hh);
-        hh = fmaf(h2v, h2v, hh);
-        hh = fmaf(h3, h3, hh);
+    auto step = [&](const uint4& m, const hpiece& hv) {
+        acc = mu_fma<MU16>(m, &hv, 0, acc);
+        const uint32_t* w = reinterpret_cast<const uint32_t*>(&hv);
+#pragma unroll
+        for (int e = 0; e < (int)(sizeof(hpiece) / 4); ++e) {
+            hh = fmaf(bf16_lo(w[e]), bf16_lo(w[e]), hh);
+            hh = fmaf(bf16_hi(w[e]), bf16_hi(w[e]), hh);
+        }
     };
 #pragma unroll
     for (int j = 0; j < BOUND_PF; ++j) step(pf[j], ph[j]);
 #pragma unroll 4
     for (int i = lo + lane + 64 * BOUND_PF; i < hi; i += 64) {
-        const float4 m = valid ? mrow[i] : make_float4(0.f, 0.f, 0.f, 0.f);
-        step(m, h2[i]);
+        const uint4 m = valid ? mrow[i] : make_uint4(0, 0, 0, 0);
+        step(m, hp[i]);
     }
     acc = wave_sum(acc);
     hh = wave_sum(hh);
@@ -336,7 +347,7 @@ __device__ __forceinline__ void split3_bf16(const float4& x0, const float4& x1, 
 #define BOUND_KS_PER_BLOCK 8
 #define BOUND_KS_MAX 32
 #define BOUND_KB_UNROLL 4      // k-blocks (of 32) whose loads are issued together
-template <int NT>
+template <int NT, bool MU16>
 __global__ __launch_bounds__(512) void bound_mfma_kernel(StepArgs a, float* __restrict__ P, int seq0, int KS, int kb_per_slice,
                                                          int reset_counters) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -347,6 +358,7 @@ __global__ __launch_bounds__(512) void bound_mfma_kernel(StepArgs a, float* __re
     if (ks >= KS) return;
     const int c0 = blockIdx.x * 16;
     const float4* ap = reinterpret_cast<const float4*>(a.mu + (size_t)min(c0 + li, a.C - 1) * a.d);
+    const uint4* ap16 = reinterpret_cast<const uint4*>(a.mu16 + (size_t)min(c0 + li, a.C - 1) * a.d);   // used when MU16
     const uint4* hp[NT];
     bool hv[NT];
 #pragma unroll
@@ -364,6 +376,7 @@ __global__ __launch_bounds__(512) void bound_mfma_kernel(StepArgs a, float* __re
     const float4 fzero = make_float4(0.f, 0.f, 0.f, 0.f);
     for (int kb = kb0; kb < kb1; kb += BOUND_KB_UNROLL) {
         float4 x[BOUND_KB_UNROLL][2];
+        uint4 x16[BOUND_KB_UNROLL];
         uint4 hb[BOUND_KB_UNROLL][NT];
 #pragma unroll
         for (int u = 0; u < BOUND_KB_UNROLL; ++u) {
@@ -371,9 +384,14 @@ __global__ __launch_bounds__(512) void bound_mfma_kernel(StepArgs a, float* __re
             const bool ok = kb + u < kb1 && k < a.d;       // d is a multiple of 8: the eight values are all in or all out
             // unconditional 128-bit loads at a clamped address, then a select: a predicated load would be split up
             const int kc = ok ? k : 0;
-            const float4 v0 = ap[kc >> 2], v1 = ap[(kc >> 2) + 1];
-            x[u][0] = ok ? v0 : fzero;
-            x[u][1] = ok ? v1 : fzero;
+            if constexpr (MU16) {
+                const uint4 v = ap16[kc >> 3];
+                x16[u] = ok ? v : zero;
+            } else {
+                const float4 v0 = ap[kc >> 2], v1 = ap[(kc >> 2) + 1];
+                x[u][0] = ok ? v0 : fzero;
+                x[u][1] = ok ? v1 : fzero;
+            }
 #pragma unroll
             for (int t = 0; t < NT; ++t) {
                 const uint4 hvv = hp[t][kc >> 3];
@@ -382,14 +400,21 @@ __global__ __launch_bounds__(512) void bound_mfma_kernel(StepArgs a, float* __re
         }
 #pragma unroll
         for (int u = 0; u < BOUND_KB_UNROLL; ++u) {
-            uint4 hi, mid, lo;
-            split3_bf16(x[u][0], x[u][1], hi, mid, lo);
+            if constexpr (MU16) {       // bf16 centroids feed the MFMA as they are
 #pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                const bf16x8_t bv = __builtin_bit_cast(bf16x8_t, hb[u][t]);
-                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bv, __builtin_bit_cast(bf16x8_t, hi), acc[t], 0, 0, 0);
-                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bv, __builtin_bit_cast(bf16x8_t, mid), acc[t], 0, 0, 0);
-                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bv, __builtin_bit_cast(bf16x8_t, lo), acc[t], 0, 0, 0);
+                for (int t = 0; t < NT; ++t)
+                    acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, hb[u][t]),
+                                                                     __builtin_bit_cast(bf16x8_t, x16[u]), acc[t], 0, 0, 0);
+            } else {
+                uint4 hi, mid, lo;
+                split3_bf16(x[u][0], x[u][1], hi, mid, lo);
+#pragma unroll
+                for (int t = 0; t < NT; ++t) {
+                    const bf16x8_t bv = __builtin_bit_cast(bf16x8_t, hb[u][t]);
+                    acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bv, __builtin_bit_cast(bf16x8_t, hi), acc[t], 0, 0, 0);
+                    acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bv, __builtin_bit_cast(bf16x8_t, mid), acc[t], 0, 0, 0);
+                    acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bv, __builtin_bit_cast(bf16x8_t, lo), acc[t], 0, 0, 0);
+                }
             }
         }
     }
@@ -1954,7 +1979,7 @@ static size_t round0_lds(const csv_workspace* ws) {
 static void fill_args(StepArgs& a, const csv_workspace* ws, const csv_index* idx) {
     memset(&a, 0, sizeof(a));
     a.V = idx->V; a.d = idx->d; a.C = idx->C;
-    a.Wp = idx->Wp; a.bp = idx->bp; a.perm = idx->perm; a.mu = idx->mu; a.R = idx->R; a.bmax = idx->bmax;
+    a.Wp = idx->Wp; a.bp = idx->bp; a.perm = idx->perm; a.mu = idx->mu; a.mu16 = idx->mu16; a.R = idx->R; a.bmax = idx->bmax;
     a.n = idx->n; a.off = idx->off; a.lnn = idx->lnn; a.ln_nmax = idx->ln_nmax;
     a.K_cap = ws->K_cap; a.Npad = ws->Npad; a.n_chunks = ws->n_chunks; a.tile_stride = ws->tile_stride; a.sp_chunks = ws->sp_chunks; a.cand_chunks = ws->cand_chunks;
     a.U = ws->U; a.hnorm = ws->hnorm; a.bound_partial = ws->bound_partial; a.st = ws->st; a.sel = ws->sel; a.slog = ws->slog; a.sid = ws->sid;
@@ -1990,9 +2015,15 @@ static int launch_bounds_kernel(const StepArgs& a, float* U, float* hn, int rese
         for (int s0 = 0; s0 < a.B; s0 += 64) {
             const int nseq = a.B - s0 < 64 ? a.B - s0 : 64;
             const int r = reset && s0 == 0;
-            if (nseq <= 16) bound_mfma_kernel<1><<<grid, 512, 0, st>>>(a, a.bound_partial, s0, KS, kbs, r);
-            else if (nseq <= 32) bound_mfma_kernel<2><<<grid, 512, 0, st>>>(a, a.bound_partial, s0, KS, kbs, r);
-            else bound_mfma_kernel<4><<<grid, 512, 0, st>>>(a, a.bound_partial, s0, KS, kbs, r);
+            if (a.mu16) {
+                if (nseq <= 16) bound_mfma_kernel<1, true><<<grid, 512, 0, st>>>(a, a.bound_partial, s0, KS, kbs, r);
+                else if (nseq <= 32) bound_mfma_kernel<2, true><<<grid, 512, 0, st>>>(a, a.bound_partial, s0, KS, kbs, r);
+                else bound_mfma_kernel<4, true><<<grid, 512, 0, st>>>(a, a.bound_partial, s0, KS, kbs, r);
+            } else {
+                if (nseq <= 16) bound_mfma_kernel<1, false><<<grid, 512, 0, st>>>(a, a.bound_partial, s0, KS, kbs, r);
+                else if (nseq <= 32) bound_mfma_kernel<2, false><<<grid, 512, 0, st>>>(a, a.bound_partial, s0, KS, kbs, r);
+                else bound_mfma_kernel<4, false><<<grid, 512, 0, st>>>(a, a.bound_partial, s0, KS, kbs, r);
+            }
             CSV_LAUNCH_CHECK("bound_mfma_kernel");
         }
         bound_finish_kernel<<<dim3((a.C + 255) / 256, a.B), 256, 0, st>>>(a, a.bound_partial, KS, U, hn);
@@ -2002,7 +2033,8 @@ static int launch_bounds_kernel(const StepArgs& a, float* U, float* hn, int rese
     int bt = 1;
     while (bt < a.B && bt < 8) bt <<= 1;
     while (bt > 1 && (size_t)bt * a.d * 2 > 65536) bt >>= 1;
-    const int nq = a.d >> 2;
+    const bool m16 = a.mu16 != nullptr;
+    const int nq = m16 ? a.d >> 3 : a.d >> 2;     // 128-bit units per centroid row
     int wpc = 1;
     while (wpc < 4 && (nq + wpc - 1) / wpc > 64 * BOUND_PF) wpc <<= 1;
     const int cpb = (BOUND_THREADS / 64) / wpc;
@@ -2010,15 +2042,25 @@ static int launch_bounds_kernel(const StepArgs& a, float* U, float* hn, int rese
     const int gpx = (groups + 7) / 8;
     dim3 grid(gpx * 8, (a.B + bt - 1) / bt);
     const size_t lds = (size_t)bt * a.d * 2;
+#define CSV_BOUND_LAUNCH(BT)                                                                                      \
+    do {                                                                                                          \
+        if (m16) bound_kernel<BT, true><<<grid, BOUND_THREADS, lds, st>>>(a, U, hn, reset, groups, gpx, wpc);     \
+        else bound_kernel<BT, false><<<grid, BOUND_THREADS, lds, st>>>(a, U, hn, reset, groups, gpx, wpc);        \
+    } while (0)
     switch (bt) {
         case 1:
-            if (a.B == 1) bound1_kernel<<<grid, BOUND_THREADS, 0, st>>>(a, U, hn, reset, groups, gpx, wpc);
-            else bound_kernel<1><<<grid, BOUND_THREADS, lds, st>>>(a, U, hn, reset, groups, gpx, wpc);
+            if (a.B == 1) {
+                if (m16) bound1_kernel<true><<<grid, BOUND_THREADS, 0, st>>>(a, U, hn, reset, groups, gpx, wpc);
+                else bound1_kernel<false><<<grid, BOUND_THREADS, 0, st>>>(a, U, hn, reset, groups, gpx, wpc);
+            } else {
+                CSV_BOUND_LAUNCH(1);
+            }
             break;
-        case 2: bound_kernel<2><<<grid, BOUND_THREADS, lds, st>>>(a, U, hn, reset, groups, gpx, wpc); break;
-        case 4: bound_kernel<4><<<grid, BOUND_THREADS, lds, st>>>(a, U, hn, reset, groups, gpx, wpc); break;
-        default: bound_kernel<8><<<grid, BOUND_THREADS, lds, st>>>(a, U, hn, reset, groups, gpx, wpc); break;
+        case 2: CSV_BOUND_LAUNCH(2); break;
+        case 4: CSV_BOUND_LAUNCH(4); break;
+        default: CSV_BOUND_LAUNCH(8); break;
     }
+#undef CSV_BOUND_LAUNCH
     CSV_LAUNCH_CHECK("bound_kernel");
     return CSV_OK;
 }

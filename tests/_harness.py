@@ -19,7 +19,7 @@ def log(msg: str) -> None:
 
 class Case:
     def __init__(self, recipe: synth.Recipe, seed: int = synth.SEED, bias: bool = True, radius_slack: float = 2.0 ** -14,
-                 labels=None, B_max=None, K_cap=None, want_W64: bool = True, W_bits=None):
+                 labels=None, B_max=None, K_cap=None, want_W64: bool = True, W_bits=None, centroid_bf16: bool = False):
         import torch
         import paper_2511_21702_amd as csv
         self.csv, self.torch = csv, torch
@@ -33,13 +33,15 @@ class Case:
         self.C = recipe.C if labels is None else int(np.max(labels)) + 1
         log(f"[{recipe.name}] head V={recipe.V} d={recipe.d} C={self.C} generated in {time.time() - t0:.1f}s")
         t0 = time.time()
-        self.oidx = O.build_index(self.head["W_bits"], self.b, self.labels, self.C, radius_slack=radius_slack)
+        self.oidx = O.build_index(self.head["W_bits"], self.b, self.labels, self.C, radius_slack=radius_slack,
+                                  centroid_bf16=centroid_bf16)
         log(f"[{recipe.name}] oracle index in {time.time() - t0:.1f}s")
         self.W64 = O.bf16_to_f64(self.head["W_bits"]) if want_W64 else None
         self.dW = csv.bits_to_device(self.head["W_bits"])
         self.db = None if self.b is None else torch.from_numpy(self.b).cuda()
         self.gidx = csv.csv_index_from_arrays(self.dW, self.db, self.oidx.mu, self.oidx.R, self.oidx.bmax,
-                                              self.oidx.n.astype(np.int32), self.oidx.perm.astype(np.int32))
+                                              self.oidx.n.astype(np.int32), self.oidx.perm.astype(np.int32),
+                                              centroid_bf16=centroid_bf16)
         self.ws = csv.CsvWorkspace(self.gidx, B_max or recipe.B, K_cap if K_cap is not None else recipe.K_max_rows)
         torch.cuda.synchronize()
 

@@ -258,6 +258,49 @@ def test_workspace_for_the_largest_shape_fits():
     ws.free(); idx.free()
 
 
+@pytest.mark.parametrize("B,d", [(1, 520), (1, 8192), (3, 264), (8, 1032), (20, 520), (40, 264)])
+def test_bf16_centroids_bounds_and_steps(B, d):
+    # centroids stored as bfloat16 (radius measured to the rounded value): every bound kernel variant and the step
+    r = synth.small_recipe(f"mu16-{B}-{d}", V=3001, d=d, C=37, B=B, steps=3, h_mode="mix", iso_frac=0.2)
+    case = Case(r, seed=41, centroid_bf16=True)
+    csv = case.csv
+    h = case.hidden()
+    dh = csv.bits_to_device(h)
+    for s in range(h.shape[0]):
+        Ug, hg = csv.csv_bounds(case.ws, case.gidx, dh[s])
+        Ug, hg = Ug.cpu().numpy(), hg.cpu().numpy()
+        U, hn = O.cluster_bounds(case.oidx, O.bf16_to_f64(h[s]))
+        assert np.allclose(hg, hn, rtol=1e-6)
+        assert np.all(np.abs(Ug - U) <= 1e-5 * np.maximum(1.0, np.abs(U)))
+    t = case.run_steps(h, 5, 1e-3, r.K_max_rows, O.COMBINE_ALL, f"mu16 B={B}")
+    _finish(t, f"mu16 B={B}")
+    case.close()
+
+
+def test_bf16_centroids_built_on_the_gpu_and_refused_when_not_rounded():
+    r = synth.small_recipe("mu16-build", V=5000, d=264, C=40, B=2, steps=2, sizes="zipf")
+    case = Case(r, seed=42, centroid_bf16=True)
+    csv = case.csv
+    g = csv.csv_build_index(case.dW, case.db, r.C, init_labels=case.labels.astype(np.int32), iters=0, centroid_bf16=True)
+    e = g.export()
+    o = case.oidx
+    assert np.all(e["mu"].view(np.uint32) & 0xFFFF == 0)
+    same = e["mu"] == o.mu                       # a float32 mean one ulp off can round to the neighbouring bfloat16
+    log(f"  bf16 centroids identical: {same.mean():.6f}")
+    assert same.mean() > 0.999
+    assert np.all(np.abs(e["mu"] - o.mu) <= 2.0 ** -7 * np.abs(o.mu) + 1e-30)
+    if same.all():
+        ulp_R = np.abs(e["R"].view(np.int32).astype(np.int64) - o.R.view(np.int32).astype(np.int64))
+        assert ulp_R.max() <= 2
+    g.free()
+    plain = Case(r, seed=42)                      # float32 centroids: not bfloat16 values
+    with pytest.raises(csv.CsvError):
+        csv.csv_index_from_arrays(plain.dW, plain.db, plain.oidx.mu, plain.oidx.R, plain.oidx.bmax,
+                                  plain.oidx.n.astype(np.int32), plain.oidx.perm.astype(np.int32), centroid_bf16=True)
+    plain.close()
+    case.close()
+
+
 def test_step_invalid_hidden_state_is_flagged():
     r = synth.small_recipe("inv", V=2000, d=256, C=16, B=3, steps=1)
     case = Case(r, seed=16)
