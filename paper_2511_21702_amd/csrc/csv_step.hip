@@ -1138,15 +1138,14 @@ __device__ __forceinline__ u64 softmax_prefix_key(const StepArgs& a, const Clust
     __syncthreads();
     for (int k2 = 2; k2 <= N; k2 <<= 1) {
         for (int j = k2 >> 1; j > 0; j >>= 1) {
-            for (int i = tid; i < N; i += nt) {
-                const int ixj = i ^ j;
-                if (ixj > i) {
-                    const u64 x = skeys[i], y = skeys[ixj];
-                    const bool first_larger = (i & k2) == 0;
-                    if (first_larger ? (x < y) : (x > y)) {
-                        skeys[i] = y;
-                        skeys[ixj] = x;
-                    }
+            // pair p of the stage: i = the index with bit j clear, partner i + j (every thread does useful work)
+            for (int p = tid; p < (N >> 1); p += nt) {
+                const int i = ((p & ~(j - 1)) << 1) | (p & (j - 1)), ixj = i | j;
+                const u64 x = skeys[i], y = skeys[ixj];
+                const bool first_larger = (i & k2) == 0;
+                if (first_larger ? (x < y) : (x > y)) {
+                    skeys[i] = y;
+                    skeys[ixj] = x;
                 }
             }
             __syncthreads();
