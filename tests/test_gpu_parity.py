@@ -415,12 +415,17 @@ def test_build_index_kmeans_matches_oracle_lloyd():
 
 
 # ------------------------------------------------------------------ the five configurations
-def _run_config(name, step_ids, max_band_frac):
+def _run_config(name, step_ids, max_band_frac, levels_step_ids=None, centroid_bf16=False):
     r = synth.CONFIGS[name]
-    case = Case(r)
+    case = Case(r, centroid_bf16=centroid_bf16)
     h = case.hidden()
     t = case.run_steps(h, r.k, r.eps, r.K_max_rows, O.COMBINE_ALL, name, step_ids=step_ids)
     _finish(t, f"{name} ({len(step_ids)} of {r.steps} steps, B={r.B})", max_band_frac)
+    if levels_step_ids is not None:        # the same workload with the fallback levels of Section IV switched on
+        t2 = case.run_steps(h, r.k, r.eps, r.K_max_rows, O.COMBINE_ALL, name + " levels", step_ids=levels_step_ids,
+                            max_rounds=4, delta_clusters=16, relax=True)
+        _finish(t2, f"{name} with fallback levels ({len(levels_step_ids)} steps)", max_band_frac)
+        t.levels = t2
     case.close()
     return t
 
@@ -436,7 +441,13 @@ def test_config_c2_all_steps():
 
 
 def test_config_c3_sampled_steps():
-    _run_config("c3", range(0, 256, 4), 0.3)
+    t = _run_config("c3", range(0, 256, 4), 0.3, levels_step_ids=range(0, 256, 8))
+    assert t.levels.late_rounds > 0          # the levels are exercised at full size
+
+
+def test_config_c2_bf16_centroids_sampled_steps():
+    t = _run_config("c2", range(0, 512, 8), 0.05, centroid_bf16=True)
+    assert t.fallbacks == 0
 
 
 def test_config_c4_sampled_steps():
