@@ -182,6 +182,15 @@ int csv_full_logits(csv_workspace* ws, const csv_index* idx, const uint16_t* d_h
 int csv_workspace_set_spin_limit(csv_workspace* ws, int polls);
 
 /*
+ * What follows round 0 (further rounds, the full vocabulary for fallback sequences) runs either as one kernel that
+ * keeps all its blocks resident and returns at once when no sequence needs it (small batches: one launch on the
+ * common path), or as one launch per phase (batches of at least min_batch sequences: kernel boundaries instead of
+ * grid barriers).  Default min_batch = 5; 0 restores it; a value above CSV_MAX_BATCH keeps the single kernel for
+ * every batch.  Results do not depend on the choice.
+ */
+int csv_workspace_set_tail_split(csv_workspace* ws, int min_batch);
+
+/*
  * Measurement support (not part of the method): time the stages of csv_decode_step with HIP events recorded on
  * the step's own stream.  csv_profile_begin allocates events for max_steps steps and switches recording on;
  * each following csv_decode_step on this workspace records CSV_PROFILE_STAGES+1 events (steps beyond max_steps

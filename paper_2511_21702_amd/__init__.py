@@ -24,6 +24,7 @@ EXPORTS = [
     "csv_workspace_create", "csv_workspace_free", "csv_decode_step", "csv_bounds", "csv_full_logits",
     "csv_profile_begin", "csv_profile_end", "csv_last_error", "csv_kmax_init", "csv_kmax_update",
     "csv_workspace_set_spin_limit", "csv_index_use_bf16_centroids",
+    "csv_workspace_set_tail_split",
 ]
 PROFILE_STAGES = ["bounds", "round0", "tail"]
 
@@ -74,6 +75,7 @@ def _load() -> C.CDLL:
     lib.csv_kmax_update.argtypes = [C.POINTER(KmaxCtl), ci, ci]
     lib.csv_workspace_set_spin_limit.argtypes = [vp, ci]
     lib.csv_index_use_bf16_centroids.argtypes = [vp, vp]
+    lib.csv_workspace_set_tail_split.argtypes = [vp, ci]
     return lib
 
 
@@ -192,6 +194,10 @@ class CsvWorkspace:
         self._h = out
         self.index = index
         self.B_max, self.K_cap = B_max, K_cap_rows
+
+    def set_tail_split(self, min_batch: int) -> None:
+        """Batches of at least min_batch sequences run the tail as one launch per phase (0 = default)."""
+        _check(lib.csv_workspace_set_tail_split(self._h, min_batch))
 
     def set_spin_limit(self, polls: int) -> None:
         """Polls a grid barrier of the tail kernel waits before giving the step up (0 = default)."""

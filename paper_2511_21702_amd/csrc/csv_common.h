@@ -64,6 +64,7 @@ struct csv_workspace {
     int tail_grid;                     // blocks of the tail kernel (all resident together)
     int spin_limit;                    // polls a grid barrier waits before the step is given up
     int round0_capacity;               // blocks of the round-0 kernel that are resident together
+    int split_min_B;                   // batches of at least this many sequences run the tail as one launch per phase
     size_t tail_lds;                   // its dynamic LDS
     int device;
     float* U;          // [B*C]      cluster bounds

@@ -1856,6 +1856,7 @@ __device__ __forceinline__ void fb_final_device(const StepArgs& a, int slot, Seq
 // the abort flag and every block leaves (the step's unfinished sequences keep the INVALID flag seed_kernel gave them).
 #define TAIL_THREADS 512
 #define TAIL_SPIN_LIMIT (1 << 22)
+#define CSV_SPLIT_TAIL_MIN_B 5   // batches from this size on run the tail as one launch per phase
 
 // Returns false when the step was aborted.  Each barrier of a step uses its own counter.
 __device__ __forceinline__ bool grid_barrier(int* counters, int which, int nblocks, int* s_flag, int spin_limit) {
@@ -1945,6 +1946,44 @@ __global__ __launch_bounds__(TAIL_THREADS, 2) void tail_kernel(StepArgs a, FullA
         __syncthreads();
     }
     if (block == 0) DBG_T(29);
+}
+
+// ------------------------------------------------------------------------------------------------ the tail, one launch per phase
+// Larger batches run the same phases as tail_kernel as separate launches: a kernel boundary costs about 2.5 us on
+// this machine, a grid barrier among 256 resident blocks 14-24 us (every block's device-scope release and acquire
+// writes back and invalidates its XCD's L2), and a step of such a batch takes hundreds of microseconds anyway.
+// Every kernel finds out on the device whether it has anything to do.
+__global__ __launch_bounds__(TAIL_THREADS, 2) void round_gemv_kernel(StepArgs a, int r) {
+    extern __shared__ u64 arena[];
+    __shared__ GemvShared gs;
+    gemv_tiles_device(a, r, reinterpret_cast<uint4*>(arena), gs, blockIdx.x, gridDim.x);
+}
+
+__global__ __launch_bounds__(SEQ_THREADS) void round_cert_kernel(StepArgs a, int r) {   // grid (B, chunks per sequence)
+    __shared__ SeqShared s;
+    cert_device(a, blockIdx.x, blockIdx.y, r, s);
+}
+
+__global__ __launch_bounds__(TAIL_THREADS, 2) void fb_product_kernel(StepArgs a, FullArgs f, int lds_bytes) {
+    extern __shared__ u64 arena[];
+    const int n_fb = a.counters[CNT_FALLBACK];
+    if (n_fb == 0) return;
+    if (n_fb > FULL_G)
+        full_mfma_all(f, n_fb, reinterpret_cast<uint4*>(arena), lds_bytes, blockIdx.x, gridDim.x);
+    else
+        full_gemv_device(f, n_fb, reinterpret_cast<uint4*>(arena), blockIdx.x, gridDim.x);
+}
+
+__global__ __launch_bounds__(SEQ_THREADS) void fb_topk_kernel(StepArgs a) {             // grid (chunks of V, B)
+    __shared__ SeqShared s;
+    if ((int)blockIdx.y >= a.counters[CNT_FALLBACK]) return;
+    fb_topk_device(a, blockIdx.y, blockIdx.x, s);
+}
+
+__global__ __launch_bounds__(SEQ_THREADS) void fb_final_kernel(StepArgs a) {            // grid B
+    __shared__ SeqShared s;
+    if ((int)blockIdx.x >= a.counters[CNT_FALLBACK]) return;
+    fb_final_device(a, blockIdx.x, s);
 }
 
 // ================================================================================================ host side
@@ -2164,6 +2203,11 @@ extern "C" int csv_workspace_create(const csv_index* idx, int B_max, int K_cap_r
         // grid barriers cost more with twice the arrivals, and the row loops already keep enough loads in flight.
         ws->tail_grid = cus;
         ws->spin_limit = TAIL_SPIN_LIMIT;
+        ws->split_min_B = CSV_SPLIT_TAIL_MIN_B;
+        if (e == hipSuccess && cert_lds(ws) + sizeof(SeqShared) > 65536)
+            e = hipFuncSetAttribute((const void*)round_cert_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)cert_lds(ws));
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute((const void*)fb_product_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, MFMA_LDS);
         int r0_per_cu = 0;
         if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&r0_per_cu, round0_kernel, SEQ_THREADS, round0_lds(ws));
         if (e == hipSuccess && r0_per_cu < 1) {
@@ -2265,11 +2309,36 @@ extern "C" int csv_decode_step(csv_workspace* ws, const csv_index* idx, const ui
         FullArgs f;
         f.V = idx->V; f.d = idx->d; f.Wp = idx->Wp; f.bp = idx->bp; f.perm = idx->perm; f.h = d_h;
         f.list = ws->fb_list; f.n_ptr = nullptr; f.n_fixed = 0; f.out = ws->fb_logits; f.out_stride = idx->V; f.scatter = 0;
-        tail_kernel<<<ws->tail_grid, TAIL_THREADS, ws->tail_lds, st>>>(a, f);
-        CSV_LAUNCH_CHECK("tail_kernel");
+        if (B < ws->split_min_B) {
+            // small batches: one launch that returns at once when no sequence needs it
+            tail_kernel<<<ws->tail_grid, TAIL_THREADS, ws->tail_lds, st>>>(a, f);
+            CSV_LAUNCH_CHECK("tail_kernel");
+        } else {
+            const size_t hl = (size_t)2 * idx->d * 2;
+            for (int r = 0; r < max_rounds; ++r) {      // round 0 here: seed prefixes the round-0 kernel handed over
+                round_gemv_kernel<<<ws->tail_grid, TAIL_THREADS, hl, st>>>(a, r);
+                CSV_LAUNCH_CHECK("round_gemv_kernel");
+                round_cert_kernel<<<dim3(B, ws->sp_chunks), SEQ_THREADS, cert_lds(ws), st>>>(a, r);
+                CSV_LAUNCH_CHECK("round_cert_kernel");
+            }
+            const size_t pl = B > FULL_G ? (size_t)MFMA_LDS : (size_t)FULL_G * idx->d * 2;
+            fb_product_kernel<<<ws->tail_grid, TAIL_THREADS, pl, st>>>(a, f, (int)pl);
+            CSV_LAUNCH_CHECK("fb_product_kernel");
+            fb_topk_kernel<<<dim3(ws->n_chunks, B), SEQ_THREADS, (size_t)FB_CHUNK * 4, st>>>(a);
+            CSV_LAUNCH_CHECK("fb_topk_kernel");
+            fb_final_kernel<<<B, SEQ_THREADS, (size_t)STAGE_CAP * 8, st>>>(a);
+            CSV_LAUNCH_CHECK("fb_final_kernel");
+        }
     }
     CSV_MARK(3);
 #undef CSV_MARK
+    return CSV_OK;
+}
+
+extern "C" int csv_workspace_set_tail_split(csv_workspace* ws, int min_batch) {
+    if (!ws) { csv_set_error("null workspace"); return CSV_EINVAL; }
+    if (min_batch < 0) { csv_set_error("min_batch=%d is negative", min_batch); return CSV_EINVAL; }
+    ws->split_min_B = min_batch == 0 ? CSV_SPLIT_TAIL_MIN_B : min_batch;
     return CSV_OK;
 }
 

@@ -87,6 +87,10 @@ def test_step_modes_small(name, mode):
     h = case.hidden()
     t = case.run_steps(h, mode["k"], mode["eps"], r.K_max_rows, mode["combine"], name)
     _finish(t, name)
+    # the same steps with what follows round 0 as a single resident kernel instead of one launch per phase
+    case.ws.set_tail_split(1000)
+    t = case.run_steps(h, mode["k"], mode["eps"], r.K_max_rows, mode["combine"], name + " (single tail kernel)")
+    _finish(t, name + " (single tail kernel)")
     case.close()
 
 
@@ -140,6 +144,11 @@ def test_step_fallback_levels(name, lad):
                 t0 = case.run_steps(h, k, eps, K_max, comb, f"plain {mode} K={K_max} k={k} c={comb}")
                 _finish(t0, f"plain K={K_max}")
                 fb_plain += t0.fallbacks
+            # once more with one launch per phase (a batch of 3 takes the single kernel by default)
+            case.ws.set_tail_split(1)
+            t = case.run_steps(h, r.k, r.eps, K_max, O.COMBINE_ALL, f"{name} {mode} K={K_max} per-phase launches", **lad)
+            _finish(t, f"{name} K={K_max} per-phase launches")
+            case.ws.set_tail_split(0)
         case.close()
     log(f"[{name}] sequences {seen}: relaxed {relaxed}, more than two rounds {late}, fallbacks {fb} (plain schedule: {fb_plain})")
     assert seen == 2 * 3 * 3 * 30 and fb <= fb_plain and fb_plain > 0
@@ -329,6 +338,7 @@ def test_barrier_timeout_gives_the_step_up_cleanly():
             res.append((buf.flags.cpu().numpy().copy(), buf.ids.cpu().numpy().copy(), buf.rounds.cpu().numpy().copy()))
         return res
 
+    case.ws.set_tail_split(1000)            # the single resident kernel is the one with device-side waits
     ref = run_all()
     assert any((rd > 1).any() or (fl & csv.FLAG_FALLBACK).any() for fl, _, rd in ref), "workload never reaches the tail kernel"
     case.ws.set_spin_limit(1)
