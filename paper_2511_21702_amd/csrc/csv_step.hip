@@ -2316,7 +2316,7 @@ extern "C" int csv_decode_step(csv_workspace* ws, const csv_index* idx, const ui
         } else {
             const size_t hl = (size_t)2 * idx->d * 2;
             for (int r = 0; r < max_rounds; ++r) {      // round 0 here: seed prefixes the round-0 kernel handed over
-                round_gemv_kernel<<<ws->tail_grid, TAIL_THREADS, hl, st>>>(a, r);
+                round_gemv_kernel<<<ws->tail_grid, TAIL_THREADS, hl, st>>>(a, r);   // more blocks measured slower
                 CSV_LAUNCH_CHECK("round_gemv_kernel");
                 round_cert_kernel<<<dim3(B, ws->sp_chunks), SEQ_THREADS, cert_lds(ws), st>>>(a, r);
                 CSV_LAUNCH_CHECK("round_cert_kernel");
