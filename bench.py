@@ -242,7 +242,7 @@ def main() -> int:
         olad = dict(max_rounds=max(args.max_rounds, 2), delta_clusters=args.delta_clusters, relax=args.relax)
         O.decode_step(W64, head["b"], oidx, h_bits[0], r.k, r.eps, r.K_max_rows, **olad)
         one = time.perf_counter() - t1
-        n_cpu = args.cpu_steps if args.cpu_steps > 0 else int(max(1, min(64, 15.0 / max(one, 1e-3))))
+        n_cpu = args.cpu_steps if args.cpu_steps > 0 else int(max(1, min(1024, 15.0 / max(one, 1e-3))))
         t1 = time.perf_counter()
         for s in range(n_cpu):
             O.decode_step(W64, head["b"], oidx, h_bits[(1 + s) % nh], r.k, r.eps, r.K_max_rows, **olad)
