@@ -224,6 +224,34 @@ def test_step_single_cluster_and_singletons():
     case.close()
 
 
+def test_step_seeded_random_shapes_and_parameters():
+    # many small cases with ragged shapes (V, d, C, B not multiples of any tile) and every parameter varied
+    rng = np.random.default_rng(2024)
+    total = PAR.Tally()
+    for case_id in range(36):
+        V = int(rng.integers(300, 5000))
+        d = 8 * int(rng.integers(1, 80))
+        C = int(rng.integers(1, min(V, 200)))
+        B = int(rng.choice([1, 1, 2, 3, 4, 5, 6, 9, 17, 33]))
+        k = int(rng.choice([0, 1, 2, 5, 17, 64, 300]))
+        k = min(k, V)
+        eps = float(rng.choice([-1.0, 1e-6, 1e-3, 5e-2, 0.6])) if k > 0 else float(rng.choice([1e-6, 1e-3, 5e-2]))
+        comb = int(rng.choice([O.COMBINE_ALL, O.COMBINE_ANY]))
+        K_max = int(rng.choice([V, V // 2, V // 4, V // 10, max(k, 1)]))
+        lad = dict(max_rounds=int(rng.choice([2, 2, 3, 8])), delta_clusters=int(rng.choice([0, 1, 7])), relax=bool(rng.integers(0, 2)))
+        r = synth.small_recipe(f"rnd{case_id}", V=V, d=d, C=C, B=B, steps=2, k=max(k, 1), eps=1e-3,
+                               sizes=str(rng.choice(["equal", "zipf"])), h_mode=str(rng.choice(["single", "mix"])),
+                               iso_frac=float(rng.choice([0.0, 0.3])), row_noise=float(rng.choice([0.05, 0.5, 2.0])), zipf_min=1)
+        tag = f"rnd{case_id} V={V} d={d} C={C} B={B} k={k} eps={eps:g} comb={comb} K={K_max} {lad}"
+        case = Case(r, seed=100 + case_id, K_cap=V, bias=bool(rng.integers(0, 2)), centroid_bf16=bool(rng.integers(0, 2)))
+        if rng.integers(0, 2):
+            case.ws.set_tail_split(1 if B < 5 else 1000)       # the tail mode the batch size would not pick
+        t = case.run_steps(case.hidden(), k, eps, K_max, comb, tag, tally=total, **lad)
+        assert not t.mismatch, tag + "\n" + "\n".join(t.mismatch[:5])
+        case.close()
+    _finish(total, "seeded random cases", max_band_frac=0.3)
+
+
 def test_step_maximum_sizes():
     # the limits the header states: CSV_MAX_BATCH sequences, CSV_MAX_K results, CSV_MAX_CLUSTERS clusters
     r = synth.small_recipe("B256", V=3000, d=64, C=24, B=256, steps=1, iso_frac=0.2)
