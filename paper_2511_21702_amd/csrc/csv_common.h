@@ -28,12 +28,14 @@ struct csv_index {
 
 enum { ST_ACTIVE = 0, ST_DONE = 1, ST_FALLBACK = 2, ST_INVALID = 3 };
 // counters[]: [CNT_FALLBACK] sequences that fall back this step; [CNT_ABORT] set when a bounded wait ran out;
+// [CNT_TAIL_NEEDED] set by whoever queues work for after round 0 (tiles of a later round or of an oversize seed
+// prefix, a fallback): what follows round 0 looks at this one word first;
 // [CNT_BARRIER + i] arrivals at the i-th grid barrier of the tail kernel (2r, 2r+1: after the GEMV and after the
 // certification of round r; 2*CSV_MAX_ROUNDS + j: the fallback phases); [CNT_TILES + r*CSV_MAX_BATCH + b] row tiles
 // of sequence b in round r's work list; [CNT_CHUNKS + r*CSV_MAX_BATCH + b] chunk blocks of round r's certification
 // that have published their partial results; [CNT_ARRIVE + b] blocks of the round-0 kernel that have finished their
 // share of sequence b's seed rows.  All are zeroed by the bound kernel at the start of a step.
-enum { CNT_FALLBACK = 0, CNT_ABORT = 1, CNT_BARRIER = 16, CNT_TILES = 64, CNT_CHUNKS = 64 + CSV_MAX_ROUNDS * CSV_MAX_BATCH,
+enum { CNT_FALLBACK = 0, CNT_ABORT = 1, CNT_TAIL_NEEDED = 2, CNT_BARRIER = 16, CNT_TILES = 64, CNT_CHUNKS = 64 + CSV_MAX_ROUNDS * CSV_MAX_BATCH,
        CNT_ARRIVE = 64 + 2 * CSV_MAX_ROUNDS * CSV_MAX_BATCH, CNT_TOTAL = 64 + (2 * CSV_MAX_ROUNDS + 1) * CSV_MAX_BATCH };
 
 // A cluster's position in the bound order is carried by one 64-bit key: monotone image of U_c in the high word,

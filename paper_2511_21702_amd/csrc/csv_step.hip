@@ -527,6 +527,7 @@ __device__ __forceinline__ void write_invalid(const StepArgs& a, int b) {
 // Called by one thread: hand sequence b to the full-vocabulary path.
 __device__ __forceinline__ void push_fallback(const StepArgs& a, int b, int rounds) {
     const int slot = atomicAdd(&a.counters[CNT_FALLBACK], 1);
+    a.counters[CNT_TAIL_NEEDED] = 1;
     a.fb_list[slot] = b;
     a.st[b].status = ST_FALLBACK;
     a.st[b].fb_slot = slot;
@@ -635,6 +636,7 @@ __device__ __forceinline__ void emit_clusters(const StepArgs& a, int b, int roun
     block_excl_scan3(cnt, rows, tiles, s.scan3, tot_cnt, tot_rows, tot_tiles);
     if (tid == 0) {
         a.counters[CNT_TILES + round * CSV_MAX_BATCH + b] = tot_tiles;
+        a.counters[CNT_TAIL_NEEDED] = 1;
         s.nbig = 0;
     }
     __syncthreads();
@@ -1504,6 +1506,7 @@ __global__ __launch_bounds__(SEQ_THREADS) void round0_kernel(StepArgs a) {
         }
         if (tid == 0) {
             a.counters[CNT_TILES + b] = ntile;
+            a.counters[CNT_TAIL_NEEDED] = 1;
             a.st[b] = seed_state(m0, rows, kappa, nxtU, T0);
         }
         return;
@@ -1889,6 +1892,7 @@ __global__ __launch_bounds__(TAIL_THREADS, 2) void tail_kernel(StepArgs a, FullA
     __shared__ int s_flag;
     const int tid = threadIdx.x;
     const int nblocks = gridDim.x, block = blockIdx.x;
+    if (a.counters[CNT_TAIL_NEEDED] == 0) return;      // the common case at small batches: one word, no reduction
     // is any sequence waiting for round 0 (a seed prefix too large for the round-0 kernel), for round 1 or for the
     // full product?  Every block reads the same, settled values.
     int mine0 = 0, mine1 = 0;
@@ -1956,11 +1960,13 @@ __global__ __launch_bounds__(TAIL_THREADS, 2) void tail_kernel(StepArgs a, FullA
 __global__ __launch_bounds__(TAIL_THREADS, 2) void round_gemv_kernel(StepArgs a, int r) {
     extern __shared__ u64 arena[];
     __shared__ GemvShared gs;
+    if (a.counters[CNT_TAIL_NEEDED] == 0) return;
     gemv_tiles_device(a, r, reinterpret_cast<uint4*>(arena), gs, blockIdx.x, gridDim.x);
 }
 
 __global__ __launch_bounds__(SEQ_THREADS) void round_cert_kernel(StepArgs a, int r) {   // grid (B, chunks per sequence)
     __shared__ SeqShared s;
+    if (a.counters[CNT_TAIL_NEEDED] == 0) return;
     cert_device(a, blockIdx.x, blockIdx.y, r, s);
 }
 
