@@ -1487,7 +1487,7 @@ __global__ __launch_bounds__(SEQ_THREADS) void round0_kernel(StepArgs a) {
     if (j == 0)
         for (int i = tid; i < m0; i += nt) a.sel[(size_t)b * C + i] = scl[i];
     const int GW = NB * (nt >> 6);
-    if (rows > GW * ROUND0_ROWS_PER_WAVE || nch > ROUND0_HREG * nt) {
+    if (rows > min(GW * ROUND0_ROWS_PER_WAVE, STAGE_CAP) || nch > ROUND0_HREG * nt) {
         // too much for these blocks: the first block queues the prefix for the tail kernel
         if (j != 0) return;
         const float nxtU = nxt ? ckey_bound(nxt) : -INFINITY;
@@ -2306,7 +2306,10 @@ extern "C" int csv_decode_step(csv_workspace* ws, const csv_index* idx, const ui
         // blocks per sequence: enough waves that a typical seed prefix (one or two clusters) is one row per wave
         // as many as stay resident together (a second wave of blocks would double the kernel's time), at most 32
         int nb = ws->round0_capacity / B;
-        nb = nb < 1 ? 1 : (nb > 32 ? 32 : nb);
+#ifndef ROUND0_NB_MAX
+#define ROUND0_NB_MAX 32
+#endif
+        nb = nb < 1 ? 1 : (nb > ROUND0_NB_MAX ? ROUND0_NB_MAX : nb);
         round0_kernel<<<dim3(nb, B), SEQ_THREADS, round0_lds(ws), st>>>(a);
         CSV_LAUNCH_CHECK("round0_kernel");
     }
