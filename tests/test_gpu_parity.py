@@ -252,6 +252,38 @@ def test_step_seeded_random_shapes_and_parameters():
     _finish(total, "seeded random cases", max_band_frac=0.3)
 
 
+def test_adaptive_budget_in_the_decode_loop():
+    # Section IV, adaptive budget: the controller reads each step's fallback count and sets the next step's K_max.
+    # Workload whose fallback rate falls as the budget grows; a large alpha so that 300 steps are enough to see it.
+    r = synth.small_recipe("kmax", V=6000, d=136, C=60, B=4, steps=300, k=8, eps=2e-3, h_mode="mix", sizes="zipf", row_noise=2.0)
+    case = Case(r, seed=21, K_cap=6000)
+    csv = case.csv
+    h = case.hidden()
+    dh = csv.bits_to_device(h)
+
+    def run(literal):
+        ctl = csv.KmaxController(K0=600, K_min=100, K_cap=6000, alpha=0.5, rho_target=0.05, literal=literal)
+        K, fb_first, fb_last, budgets = 600, 0, 0, []
+        for s in range(300):
+            buf = csv.make_step_buffers(case.gidx, r.B, r.k, r.eps, K)
+            csv.csv_decode_step(case.ws, case.gidx, dh[s], buf)
+            torch.cuda.synchronize()
+            nfb = int(((buf.flags.cpu().numpy() & csv.FLAG_FALLBACK) != 0).sum())
+            fb_first += nfb if s < 100 else 0
+            fb_last += nfb if s >= 200 else 0
+            K = ctl.update(nfb, r.B)
+            budgets.append(K)
+        return fb_first, fb_last, budgets
+
+    f0, f1, bud = run(literal=False)
+    log(f"[kmax] feedback sign: fallbacks {f0} in the first 100 steps, {f1} in the last 100, budget 600 -> {bud[-1]}")
+    assert bud[-1] > 600 and f1 < f0
+    g0, g1, bud_l = run(literal=True)
+    log(f"[kmax] printed sign : fallbacks {g0} in the first 100 steps, {g1} in the last 100, budget 600 -> {bud_l[-1]}")
+    assert bud_l[-1] <= 600 and g1 >= f1
+    case.close()
+
+
 def test_step_maximum_sizes():
     # the limits the header states: CSV_MAX_BATCH sequences, CSV_MAX_K results, CSV_MAX_CLUSTERS clusters
     r = synth.small_recipe("B256", V=3000, d=64, C=24, B=256, steps=1, iso_frac=0.2)
