@@ -284,6 +284,42 @@ def test_adaptive_budget_in_the_decode_loop():
     case.close()
 
 
+@pytest.mark.parametrize("B", [1, 6])
+def test_step_replayed_from_a_hip_graph(B):
+    # the step only enqueues kernels (no memset nodes, no allocation): captured once, replayed with new hidden states
+    # in a static buffer, with eager steps and synchronisations between the replays
+    r = synth.small_recipe(f"graph{B}", V=4000, d=256, C=32, B=B, steps=6, iso_frac=0.3, h_mode="mix")
+    case = Case(r, seed=51)
+    csv = case.csv
+    h = case.hidden()
+    dh = csv.bits_to_device(h)
+    eager = []
+    buf_e = csv.make_step_buffers(case.gidx, B, 5, 1e-3, r.K_max_rows)
+    for s in range(6):
+        csv.csv_decode_step(case.ws, case.gidx, dh[s], buf_e)
+        torch.cuda.synchronize()
+        eager.append((buf_e.flags.cpu().numpy().copy(), buf_e.ids.cpu().numpy().copy(), buf_e.logits.cpu().numpy().copy(),
+                      buf_e.lse.cpu().numpy().copy(), buf_e.n_rows.cpu().numpy().copy()))
+    static_h = dh[0].clone()
+    buf_g = csv.make_step_buffers(case.gidx, B, 5, 1e-3, r.K_max_rows)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        csv.csv_decode_step(case.ws, case.gidx, static_h, buf_g)
+    for s in (3, 0, 5, 2, 2, 4):
+        static_h.copy_(dh[s])
+        graph.replay()
+        torch.cuda.synchronize()
+        fl, ids, lg, lse, nr = eager[s]
+        assert np.array_equal(buf_g.flags.cpu().numpy(), fl) and np.array_equal(buf_g.ids.cpu().numpy(), ids)
+        assert np.array_equal(buf_g.logits.cpu().numpy(), lg) and np.array_equal(buf_g.lse.cpu().numpy(), lse)
+        assert np.array_equal(buf_g.n_rows.cpu().numpy(), nr)
+        # eager work on the same workspace between replays
+        csv.csv_decode_step(case.ws, case.gidx, dh[(s + 1) % 6], buf_e)
+        torch.cuda.synchronize()
+    case.close()
+
+
 def test_step_maximum_sizes():
     # the limits the header states: CSV_MAX_BATCH sequences, CSV_MAX_K results, CSV_MAX_CLUSTERS clusters
     r = synth.small_recipe("B256", V=3000, d=64, C=24, B=256, steps=1, iso_frac=0.2)
