@@ -183,10 +183,13 @@ int csv_workspace_set_spin_limit(csv_workspace* ws, int polls);
 
 /*
  * What follows round 0 (further rounds, the full vocabulary for fallback sequences) runs either as one kernel that
- * keeps all its blocks resident and returns at once when no sequence needs it (small batches: one launch on the
- * common path), or as one launch per phase (batches of at least min_batch sequences: kernel boundaries instead of
- * grid barriers).  Default min_batch = 5; 0 restores it; a value above CSV_MAX_BATCH keeps the single kernel for
- * every batch.  Results do not depend on the choice.
+ * keeps all its blocks resident and returns at once when no sequence needs it (one launch on the common path of an
+ * easy workload), or as one launch per phase (kernel boundaries instead of grid barriers: faster whenever that work
+ * is actually needed).  By default (min_batch = 0) every step follows the recent steps: per-phase launches when at
+ * least two of the last eight needed the tail (a device-side bit history mirrored to pinned host memory and read
+ * without synchronising, so it may lag a few steps).  min_batch > 0 fixes the choice: batches of at least min_batch
+ * sequences use per-phase launches, smaller ones the single kernel (a value above CSV_MAX_BATCH: always the single
+ * kernel; 1: always per-phase).  Results do not depend on the choice.
  */
 int csv_workspace_set_tail_split(csv_workspace* ws, int min_batch);
 

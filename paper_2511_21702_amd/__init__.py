@@ -196,7 +196,7 @@ class CsvWorkspace:
         self.B_max, self.K_cap = B_max, K_cap_rows
 
     def set_tail_split(self, min_batch: int) -> None:
-        """Batches of at least min_batch sequences run the tail as one launch per phase (0 = default)."""
+        """Batches of at least min_batch sequences run the tail as one launch per phase (0 = follow recent steps)."""
         _check(lib.csv_workspace_set_tail_split(self._h, min_batch))
 
     def set_spin_limit(self, polls: int) -> None:

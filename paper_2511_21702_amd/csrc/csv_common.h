@@ -36,7 +36,9 @@ enum { ST_ACTIVE = 0, ST_DONE = 1, ST_FALLBACK = 2, ST_INVALID = 3 };
 // that have published their partial results; [CNT_ARRIVE + b] blocks of the round-0 kernel that have finished their
 // share of sequence b's seed rows.  All are zeroed by the bound kernel at the start of a step.
 enum { CNT_FALLBACK = 0, CNT_ABORT = 1, CNT_TAIL_NEEDED = 2, CNT_BARRIER = 16, CNT_TILES = 64, CNT_CHUNKS = 64 + CSV_MAX_ROUNDS * CSV_MAX_BATCH,
-       CNT_ARRIVE = 64 + 2 * CSV_MAX_ROUNDS * CSV_MAX_BATCH, CNT_TOTAL = 64 + (2 * CSV_MAX_ROUNDS + 1) * CSV_MAX_BATCH };
+       CNT_ARRIVE = 64 + 2 * CSV_MAX_ROUNDS * CSV_MAX_BATCH, CNT_TOTAL = 64 + (2 * CSV_MAX_ROUNDS + 1) * CSV_MAX_BATCH,
+       // not reset: bit i = whether the step i steps back needed anything after round 0 (kept behind the reset range)
+       CNT_HISTORY = CNT_TOTAL, CNT_ALLOC = CNT_TOTAL + 16 };
 
 // A cluster's position in the bound order is carried by one 64-bit key: monotone image of U_c in the high word,
 // ~c in the low word.  Larger key = larger bound, equal bounds = smaller cluster id first.  Empty clusters have key 0.
@@ -66,7 +68,10 @@ struct csv_workspace {
     int tail_grid;                     // blocks of the tail kernel (all resident together)
     int spin_limit;                    // polls a grid barrier waits before the step is given up
     int round0_capacity;               // blocks of the round-0 kernel that are resident together
-    int split_min_B;                   // batches of at least this many sequences run the tail as one launch per phase
+    int split_min_B;                   // > 0: batches of at least this many sequences run the tail as one launch per
+                                       // phase; 0: decided per step from the recent steps' history
+    int* h_history;                    // pinned host word the bound kernel copies the history to (read without a sync)
+    int* d_history;                    // the same word as the device sees it
     size_t tail_lds;                   // its dynamic LDS
     int device;
     float* U;          // [B*C]      cluster bounds

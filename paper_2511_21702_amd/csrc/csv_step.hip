@@ -50,6 +50,7 @@ struct StepArgs {
     int cand_chunks;   // chunk stride of the candidate buffers
     int tail_lds;      // dynamic LDS bytes of the tail kernel
     int spin_limit;    // polls a grid barrier of the tail kernel waits before it gives the step up
+    int* host_history; // pinned host word for the history of steps that needed the tail (device-visible address)
     int r0_h_off;      // offset of h in the round-0 kernel's LDS arena, in 128-bit units (behind the cluster data)
     float* U;
     float* hnorm;
@@ -98,9 +99,16 @@ __device__ __forceinline__ u64 ckey(float U, int c) { return ((u64)lkey(U) << 32
 __device__ __forceinline__ float ckey_bound(u64 k) { return fkey_inv((uint32_t)(k >> 32)); }
 
 // Zero the step's counters: the fixed slots and, of every per-sequence row, the entries of the B sequences in use.
-__device__ __forceinline__ void reset_step_counters(int* counters, int B, int nthreads) {
+// Before that, whether the previous step needed anything after round 0 is shifted into the history word (device
+// copy behind the reset range, and a pinned host copy that the next calls read without synchronising).
+__device__ __forceinline__ void reset_step_counters(int* counters, int B, int nthreads, int* host_history) {
     constexpr int rows = (CNT_TOTAL - CNT_TILES) / CSV_MAX_BATCH;
     for (int i = threadIdx.x; i < CNT_TILES + rows * B; i += nthreads) {
+        if (i == CNT_TAIL_NEEDED) {
+            const int h = ((counters[CNT_HISTORY] << 1) | (counters[i] != 0)) & 0xffff;
+            counters[CNT_HISTORY] = h;
+            if (host_history) *host_history = h;
+        }
         const int j = i - CNT_TILES;
         counters[i < CNT_TILES ? i : CNT_TILES + (j / B) * CSV_MAX_BATCH + (j % B)] = 0;
     }
@@ -185,7 +193,7 @@ __global__ __launch_bounds__(BOUND_THREADS) void bound_kernel(StepArgs a, float*
         if (i < BT * nch) hs4[i] = hreg[q];
     }
     if (reset_counters && blockIdx.x == 0 && blockIdx.y == 0)
-        reset_step_counters(a.counters, a.B, BOUND_THREADS);
+        reset_step_counters(a.counters, a.B, BOUND_THREADS, a.host_history);
     __syncthreads();
     for (int s = wave; s < BT; s += BOUND_THREADS / 64) {
         float acc = 0.f;
@@ -281,7 +289,7 @@ __global__ __launch_bounds__(BOUND_THREADS) void bound1_kernel(StepArgs a, float
         ncl = a.n[c];
     }
     if (reset_counters && blockIdx.x == 0)
-        reset_step_counters(a.counters, a.B, BOUND_THREADS);
+        reset_step_counters(a.counters, a.B, BOUND_THREADS, a.host_history);
     float acc = 0.f, hh = 0.f;
     auto step = [&](const uint4& m, const hpiece& hv) {
         acc = mu_fma<MU16>(m, &hv, 0, acc);
@@ -353,7 +361,7 @@ __global__ __launch_bounds__(512) void bound_mfma_kernel(StepArgs a, float* __re
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int li = lane & 15, g = lane >> 4;
     if (reset_counters && blockIdx.x == 0 && blockIdx.y == 0)
-        reset_step_counters(a.counters, a.B, 512);
+        reset_step_counters(a.counters, a.B, 512, a.host_history);
     const int ks = blockIdx.y * BOUND_KS_PER_BLOCK + wave;
     if (ks >= KS) return;
     const int c0 = blockIdx.x * 16;
@@ -1859,7 +1867,6 @@ __device__ __forceinline__ void fb_final_device(const StepArgs& a, int slot, Seq
 // the abort flag and every block leaves (the step's unfinished sequences keep the INVALID flag seed_kernel gave them).
 #define TAIL_THREADS 512
 #define TAIL_SPIN_LIMIT (1 << 22)
-#define CSV_SPLIT_TAIL_MIN_B 5   // batches from this size on run the tail as one launch per phase
 
 // Returns false when the step was aborted.  Each barrier of a step uses its own counter.
 __device__ __forceinline__ bool grid_barrier(int* counters, int which, int nblocks, int* s_flag, int spin_limit) {
@@ -2031,6 +2038,7 @@ static void fill_args(StepArgs& a, const csv_workspace* ws, const csv_index* idx
     a.r0_h_off = (int)(round0_h_off(ws) / 16);
     a.tail_lds = (int)ws->tail_lds;
     a.spin_limit = ws->spin_limit;
+    a.host_history = ws->d_history;
     a.fb_list = ws->fb_list; a.fb_logits = ws->fb_logits; a.cand_val = ws->cand_val; a.cand_id = ws->cand_id;
     a.cand_max = ws->cand_max; a.cand_sum = ws->cand_sum;
 }
@@ -2168,10 +2176,15 @@ extern "C" int csv_workspace_create(const csv_index* idx, int B_max, int K_cap_r
     A((void**)&ws->U, B * C * 4); A((void**)&ws->bound_partial, B_max > 8 ? B * C * 4 * BOUND_KS_MAX : 16); A((void**)&ws->hnorm, B * 4); A((void**)&ws->st, B * sizeof(SeqState));
     A((void**)&ws->sel, B * C * 4); A((void**)&ws->slog, B * K * 4); A((void**)&ws->sid, B * K * 4);
     A((void**)&ws->tiles[0], tcap * sizeof(Tile)); A((void**)&ws->tiles[1], tcap * sizeof(Tile));
-    A((void**)&ws->counters, CNT_TOTAL * 4); A((void**)&ws->fb_list, B * 4); A((void**)&ws->all_list, B * 4);
+    A((void**)&ws->counters, CNT_ALLOC * 4); A((void**)&ws->fb_list, B * 4); A((void**)&ws->all_list, B * 4);
     A((void**)&ws->fb_logits, B * V * 4); A((void**)&ws->cand_val, B * NC * CSV_MAX_K * 4); A((void**)&ws->cand_id, B * NC * CSV_MAX_K * 4);
     A((void**)&ws->cand_max, B * NC * 4); A((void**)&ws->cand_sum, B * NC * 4);
-    if (e == hipSuccess) e = hipMemset(ws->counters, 0, CNT_TOTAL * 4);
+    if (e == hipSuccess) e = hipMemset(ws->counters, 0, CNT_ALLOC * 4);
+    if (e == hipSuccess) e = hipHostMalloc((void**)&ws->h_history, 64, hipHostMallocDefault);
+    if (e == hipSuccess) {
+        *ws->h_history = 0;
+        e = hipHostGetDevicePointer((void**)&ws->d_history, ws->h_history, 0);
+    }
     if (e == hipSuccess) e = hipMemset(ws->st, 0, B * sizeof(SeqState));
     if (e == hipSuccess) e = hipMemset(ws->tiles[0], 0, tcap * sizeof(Tile));
     if (e == hipSuccess) e = hipMemset(ws->tiles[1], 0, tcap * sizeof(Tile));
@@ -2209,7 +2222,7 @@ extern "C" int csv_workspace_create(const csv_index* idx, int B_max, int K_cap_r
         // grid barriers cost more with twice the arrivals, and the row loops already keep enough loads in flight.
         ws->tail_grid = cus;
         ws->spin_limit = TAIL_SPIN_LIMIT;
-        ws->split_min_B = CSV_SPLIT_TAIL_MIN_B;
+        ws->split_min_B = 0;      // decided per step from the history
         if (e == hipSuccess && cert_lds(ws) + sizeof(SeqShared) > 65536)
             e = hipFuncSetAttribute((const void*)round_cert_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)cert_lds(ws));
         if (e == hipSuccess)
@@ -2238,6 +2251,7 @@ extern "C" void csv_workspace_free(csv_workspace* ws) {
                     ws->counters, ws->fb_list, ws->all_list, ws->fb_logits, ws->cand_val, ws->cand_id, ws->cand_max, ws->cand_sum};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
+    if (ws->h_history) (void)hipHostFree(ws->h_history);
     profile_release(ws);
     free(ws);
 }
@@ -2318,7 +2332,18 @@ extern "C" int csv_decode_step(csv_workspace* ws, const csv_index* idx, const ui
         FullArgs f;
         f.V = idx->V; f.d = idx->d; f.Wp = idx->Wp; f.bp = idx->bp; f.perm = idx->perm; f.h = d_h;
         f.list = ws->fb_list; f.n_ptr = nullptr; f.n_fixed = 0; f.out = ws->fb_logits; f.out_stride = idx->V; f.scatter = 0;
-        if (B < ws->split_min_B) {
+        // One launch per phase pays when the tail is needed (kernel boundaries instead of grid barriers: 30 % of a
+        // step even at B = 1), the single kernel when it is not (one launch that returns at once instead of seven).
+        // Unless the caller fixed the choice, follow the recent steps: the bound kernel keeps a bit per step in a
+        // pinned host word, read here without synchronising (it may lag a few steps; either choice is correct).
+        bool split;
+        if (ws->split_min_B > 0) {
+            split = B >= ws->split_min_B;
+        } else {
+            const unsigned recent = (unsigned)*(volatile int*)ws->h_history & 0xffu;
+            split = __builtin_popcount(recent) >= 2;
+        }
+        if (!split) {
             // small batches: one launch that returns at once when no sequence needs it
             tail_kernel<<<ws->tail_grid, TAIL_THREADS, ws->tail_lds, st>>>(a, f);
             CSV_LAUNCH_CHECK("tail_kernel");
@@ -2347,7 +2372,7 @@ extern "C" int csv_decode_step(csv_workspace* ws, const csv_index* idx, const ui
 extern "C" int csv_workspace_set_tail_split(csv_workspace* ws, int min_batch) {
     if (!ws) { csv_set_error("null workspace"); return CSV_EINVAL; }
     if (min_batch < 0) { csv_set_error("min_batch=%d is negative", min_batch); return CSV_EINVAL; }
-    ws->split_min_B = min_batch == 0 ? CSV_SPLIT_TAIL_MIN_B : min_batch;
+    ws->split_min_B = min_batch;
     return CSV_OK;
 }
 
