@@ -131,9 +131,9 @@ typedef struct {
     int32_t*  d_n_rows;       /* [B]    rows scored, |S| (V after fallback) */
     int32_t*  d_n_clusters;   /* [B]    clusters opened (C after fallback) */
     int32_t*  d_rounds;       /* [B] or NULL: scoring rounds used on the sub-vocabulary path (0..max_rounds) */
-    int32_t*  d_sel_clusters; /* [B*C] or NULL: opened cluster ids (first n_clusters entries): round-0 clusters,
-                                 then the clusters of each later round, each group by ascending id; untouched on
-                                 fallback */
+    int32_t*  d_sel_clusters; /* [B*C] or NULL: opened cluster ids (first n_clusters entries): the round-0 clusters
+                                 in bound order, then the clusters of each later round by ascending id; untouched
+                                 on fallback */
     unsigned long long* d_fallback_count; /* or NULL: incremented once per sequence that falls back */
 } csv_step_out;
 
