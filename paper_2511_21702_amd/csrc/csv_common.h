@@ -24,6 +24,7 @@ struct csv_index {
     int32_t* off;    // [C+1] first permuted row of each cluster
     float* lnn;      // [C]   ln n_c (-inf for an empty cluster)
     float ln_nmax;   // ln of the largest cluster size
+    int n_max;       // the largest cluster size
 };
 
 enum { ST_ACTIVE = 0, ST_DONE = 1, ST_FALLBACK = 2, ST_INVALID = 3 };

@@ -400,6 +400,7 @@ extern "C" int csv_build_index(const uint16_t* d_W, const float* d_b, int V, int
         int nmax = 1;
         for (int c = 0; c < C; ++c) nmax = n[c] > nmax ? n[c] : nmax;
         x->ln_nmax = (float)log((double)nmax);
+        x->n_max = nmax;
     }
     if (o->centroid_bf16 && (rc = store_centroids_bf16(x, 0, st))) return fail(rc);
     unsigned long long* d_d2max = nullptr;
@@ -451,6 +452,7 @@ extern "C" int csv_index_from_arrays(const uint16_t* d_W, const float* d_b, int 
         int nmax = 1;
         for (int c = 0; c < C; ++c) nmax = n[c] > nmax ? n[c] : nmax;
         x->ln_nmax = (float)log((double)nmax);
+        x->n_max = nmax;
     }
     hipError_t e = hipMemcpyAsync(x->mu, h_mu, (size_t)C * d * 4, hipMemcpyHostToDevice, st);
     if (e == hipSuccess) e = hipMemcpyAsync(x->R, h_R, (size_t)C * 4, hipMemcpyHostToDevice, st);

@@ -2316,10 +2316,11 @@ extern "C" int csv_decode_step(csv_workspace* ws, const csv_index* idx, const ui
     rc = launch_bounds_kernel(a, ws->U, ws->hnorm, 1, st);
     if (rc) return rc;
     CSV_MARK(1);
+    int nb = 1;
     {
         // blocks per sequence: enough waves that a typical seed prefix (one or two clusters) is one row per wave
         // as many as stay resident together (a second wave of blocks would double the kernel's time), at most 32
-        int nb = ws->round0_capacity / B;
+        nb = ws->round0_capacity / B;
 #ifndef ROUND0_NB_MAX
 #define ROUND0_NB_MAX 32
 #endif
@@ -2349,7 +2350,12 @@ extern "C" int csv_decode_step(csv_workspace* ws, const csv_index* idx, const ui
             CSV_LAUNCH_CHECK("tail_kernel");
         } else {
             const size_t hl = (size_t)2 * idx->d * 2;
-            for (int r = 0; r < max_rounds; ++r) {      // round 0 here: seed prefixes the round-0 kernel handed over
+            // Round 0 appears here only for seed prefixes that the round-0 kernel hands over.  A prefix holds fewer
+            // than max(k,1) rows before its last cluster, so with small clusters that cannot happen: no launches.
+            const long long cap = (long long)nb * (SEQ_THREADS / 64) * ROUND0_ROWS_PER_WAVE;
+            const long long prefix_max = (long long)(p->k > 1 ? p->k : 1) - 1 + idx->n_max;
+            const bool may_hand_over = prefix_max > (cap < STAGE_CAP ? cap : STAGE_CAP) || (idx->d >> 3) > ROUND0_HREG * SEQ_THREADS;
+            for (int r = may_hand_over ? 0 : 1; r < max_rounds; ++r) {
                 round_gemv_kernel<<<ws->tail_grid, TAIL_THREADS, hl, st>>>(a, r);   // more blocks measured slower
                 CSV_LAUNCH_CHECK("round_gemv_kernel");
                 round_cert_kernel<<<dim3(B, ws->sp_chunks), SEQ_THREADS, cert_lds(ws), st>>>(a, r);
