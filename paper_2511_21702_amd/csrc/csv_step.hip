@@ -103,12 +103,16 @@ __device__ __forceinline__ float ckey_bound(u64 k) { return fkey_inv((uint32_t)(
 // copy behind the reset range, and a pinned host copy that the next calls read without synchronising).
 __device__ __forceinline__ void reset_step_counters(int* counters, int B, int nthreads, int* host_history) {
     constexpr int rows = (CNT_TOTAL - CNT_TILES) / CSV_MAX_BATCH;
+    if (threadIdx.x == 0) {      // low half: steps that needed the tail; high half: steps with a fallback
+        const unsigned old = (unsigned)counters[CNT_HISTORY];
+        const unsigned lo = ((old << 1) | (unsigned)(counters[CNT_TAIL_NEEDED] != 0)) & 0xffffu;
+        const unsigned hi = (((old >> 16) << 1) | (unsigned)(counters[CNT_FALLBACK] != 0)) & 0x7fffu;
+        const int h = (int)(lo | (hi << 16));
+        counters[CNT_HISTORY] = h;
+        if (host_history) *host_history = h;
+    }
+    __syncthreads();             // called by every thread of one block: the zeroing below must not overtake the reads
     for (int i = threadIdx.x; i < CNT_TILES + rows * B; i += nthreads) {
-        if (i == CNT_TAIL_NEEDED) {
-            const int h = ((counters[CNT_HISTORY] << 1) | (counters[i] != 0)) & 0xffff;
-            counters[CNT_HISTORY] = h;
-            if (host_history) *host_history = h;
-        }
         const int j = i - CNT_TILES;
         counters[i < CNT_TILES ? i : CNT_TILES + (j / B) * CSV_MAX_BATCH + (j % B)] = 0;
     }
@@ -1892,7 +1896,7 @@ __device__ __forceinline__ bool grid_barrier(int* counters, int which, int nbloc
     return *s_flag != 0;
 }
 
-__global__ __launch_bounds__(TAIL_THREADS, 2) void tail_kernel(StepArgs a, FullArgs f) {
+__global__ __launch_bounds__(TAIL_THREADS, 2) void tail_kernel(StepArgs a, FullArgs f, int fallback_only) {
     extern __shared__ u64 arena[];
     __shared__ SeqShared s;
     __shared__ GemvShared gs;
@@ -1900,6 +1904,7 @@ __global__ __launch_bounds__(TAIL_THREADS, 2) void tail_kernel(StepArgs a, FullA
     const int tid = threadIdx.x;
     const int nblocks = gridDim.x, block = blockIdx.x;
     if (a.counters[CNT_TAIL_NEEDED] == 0) return;      // the common case at small batches: one word, no reduction
+    if (fallback_only && a.counters[CNT_FALLBACK] == 0) return;
     // is any sequence waiting for round 0 (a seed prefix too large for the round-0 kernel), for round 1 or for the
     // full product?  Every block reads the same, settled values.
     int mine0 = 0, mine1 = 0;
@@ -1908,14 +1913,15 @@ __global__ __launch_bounds__(TAIL_THREADS, 2) void tail_kernel(StepArgs a, FullA
         mine1 = a.counters[CNT_TILES + CSV_MAX_BATCH + tid];
     }
     const int n_fb0 = a.counters[CNT_FALLBACK];
-    const int tiles0 = block_sum_i(mine0, s.redi);
+    int tiles0 = block_sum_i(mine0, s.redi);
     int tiles = block_sum_i(mine1, s.redi);
+    if (fallback_only) tiles0 = tiles = 0;      // the rounds ran as launches of their own
     if (tiles0 == 0 && tiles == 0 && n_fb0 == 0) return;
     DBG_T(20);
 
     // Rounds: the GEMV over the round's work list, then the certification, which may plan the next round.
     // Round 0 is here only for seed prefixes that the round-0 kernel handed over.
-    for (int r = tiles0 > 0 ? 0 : 1; r < a.max_rounds; ++r) {
+    for (int r = tiles0 > 0 ? 0 : 1; r < a.max_rounds && !fallback_only; ++r) {
         if (r > 0) {
             if (r > 1 || tiles0 > 0) {   // planned by a certification earlier in this kernel: read past the barrier
                 const int mine = tid < a.B ? __hip_atomic_load(&a.counters[CNT_TILES + r * CSV_MAX_BATCH + tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0;
@@ -2337,16 +2343,19 @@ extern "C" int csv_decode_step(csv_workspace* ws, const csv_index* idx, const ui
         // step even at B = 1), the single kernel when it is not (one launch that returns at once instead of seven).
         // Unless the caller fixed the choice, follow the recent steps: the bound kernel keeps a bit per step in a
         // pinned host word, read here without synchronising (it may lag a few steps; either choice is correct).
-        bool split;
+        bool split, fb_launches = true;
+        const unsigned history = (unsigned)*(volatile int*)ws->h_history;
         if (ws->split_min_B > 0) {
             split = B >= ws->split_min_B;
         } else {
-            const unsigned recent = (unsigned)*(volatile int*)ws->h_history & 0xffu;
-            split = __builtin_popcount(recent) >= 2;
+            split = __builtin_popcount(history & 0xffu) >= 2;
+            // the three fallback phases as launches of their own only while fallbacks occur; otherwise one launch
+            // of the single kernel restricted to them, which returns at once when nobody fell back
+            fb_launches = ((history >> 16) & 0xffu) != 0;
         }
         if (!split) {
             // small batches: one launch that returns at once when no sequence needs it
-            tail_kernel<<<ws->tail_grid, TAIL_THREADS, ws->tail_lds, st>>>(a, f);
+            tail_kernel<<<ws->tail_grid, TAIL_THREADS, ws->tail_lds, st>>>(a, f, 0);
             CSV_LAUNCH_CHECK("tail_kernel");
         } else {
             const size_t hl = (size_t)2 * idx->d * 2;
@@ -2361,13 +2370,18 @@ extern "C" int csv_decode_step(csv_workspace* ws, const csv_index* idx, const ui
                 round_cert_kernel<<<dim3(B, ws->sp_chunks), SEQ_THREADS, cert_lds(ws), st>>>(a, r);
                 CSV_LAUNCH_CHECK("round_cert_kernel");
             }
-            const size_t pl = B > FULL_G ? (size_t)MFMA_LDS : (size_t)FULL_G * idx->d * 2;
-            fb_product_kernel<<<ws->tail_grid, TAIL_THREADS, pl, st>>>(a, f, (int)pl);
-            CSV_LAUNCH_CHECK("fb_product_kernel");
-            fb_topk_kernel<<<dim3(ws->n_chunks, B), SEQ_THREADS, (size_t)FB_CHUNK * 4, st>>>(a);
-            CSV_LAUNCH_CHECK("fb_topk_kernel");
-            fb_final_kernel<<<B, SEQ_THREADS, (size_t)STAGE_CAP * 8, st>>>(a);
-            CSV_LAUNCH_CHECK("fb_final_kernel");
+            if (fb_launches) {
+                const size_t pl = B > FULL_G ? (size_t)MFMA_LDS : (size_t)FULL_G * idx->d * 2;
+                fb_product_kernel<<<ws->tail_grid, TAIL_THREADS, pl, st>>>(a, f, (int)pl);
+                CSV_LAUNCH_CHECK("fb_product_kernel");
+                fb_topk_kernel<<<dim3(ws->n_chunks, B), SEQ_THREADS, (size_t)FB_CHUNK * 4, st>>>(a);
+                CSV_LAUNCH_CHECK("fb_topk_kernel");
+                fb_final_kernel<<<B, SEQ_THREADS, (size_t)STAGE_CAP * 8, st>>>(a);
+                CSV_LAUNCH_CHECK("fb_final_kernel");
+            } else {
+                tail_kernel<<<ws->tail_grid, TAIL_THREADS, ws->tail_lds, st>>>(a, f, 1);
+                CSV_LAUNCH_CHECK("tail_kernel");
+            }
         }
     }
     CSV_MARK(3);
