@@ -1966,10 +1966,10 @@ __global__ __launch_bounds__(TAIL_THREADS, 2) void tail_kernel(StepArgs a, FullA
 }
 
 // ------------------------------------------------------------------------------------------------ the tail, one launch per phase
-// Larger batches run the same phases as tail_kernel as separate launches: a kernel boundary costs about 2.5 us on
-// this machine, a grid barrier among 256 resident blocks 14-24 us (every block's device-scope release and acquire
-// writes back and invalidates its XCD's L2), and a step of such a batch takes hundreds of microseconds anyway.
-// Every kernel finds out on the device whether it has anything to do.
+// The same phases as tail_kernel as separate launches, used while recent steps needed them: a kernel boundary
+// costs about 2.5 us on this machine, a grid barrier among 256 resident blocks 14-24 us (every block's device-scope
+// release and acquire writes back and invalidates its XCD's L2).  Every kernel finds out on the device whether it
+// has anything to do.
 __global__ __launch_bounds__(TAIL_THREADS, 2) void round_gemv_kernel(StepArgs a, int r) {
     extern __shared__ u64 arena[];
     __shared__ GemvShared gs;
