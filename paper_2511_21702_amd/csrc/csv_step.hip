@@ -357,6 +357,7 @@ __device__ __forceinline__ void split3_bf16(const float4& x0, const float4& x1, 
 }
 
 #define BOUND_KS_PER_BLOCK 8
+#define BOUND_WAVE_TARGET 4096   // (cluster tiles x K slices) aimed at; 2048..8192 measured within 5 %
 #define BOUND_KS_MAX 32
 #define BOUND_KB_UNROLL 4      // k-blocks (of 32) whose loads are issued together
 template <int NT, bool MU16>
@@ -1402,6 +1403,7 @@ __device__ __forceinline__ void cert_device(const StepArgs& a, int b, int chunk,
 // the sequence's counter (nobody waits) certifies, or plans round 1, or hands the sequence to the full product.
 // A prefix with more rows than the NB blocks should score themselves (one giant cluster) goes to the round-0
 // work list instead and is scored and certified by the tail kernel with the whole device.
+#define ROUND0_NB_MAX 32           // most blocks of a sequence in the round-0 kernel (8..128 swept: 32-64 fastest)
 #define ROUND0_ROWS_PER_WAVE 8     // with at most 32 blocks of 8 waves a sequence: no more than 2048 <= STAGE_CAP rows;
                                    // with a single block: 64 rows, larger prefixes go to the tail kernel
 #define ROUND0_HREG 4     // 128-bit pieces of h a thread carries in registers across the seed (d <= 4 * 8 * SEQ_THREADS)
@@ -1702,9 +1704,7 @@ __global__ __launch_bounds__(256) void full_gemv_kernel(FullArgs f) {
 // pieces of many rows do not.
 // h is fed as the first operand and W' as the second, so accumulator register r of lane (li, g) is
 // out[sequence 4g + r][row li]: stores are 64-byte runs per sequence instead of 4-byte pieces 4V bytes apart.
-#ifndef MFMA_SBG
-#define MFMA_SBG 2
-#endif
+#define MFMA_SBG 2      // K blocks per batch of W' loads (1, 2, 4, 8 swept)
 template <int NT>
 __device__ __forceinline__ void full_mfma_device(const FullArgs& f, int n, int seq0, uint4* lds, int lds_bytes, int block, int nblocks) {
     const int tid = threadIdx.x, nt = blockDim.x, lane = tid & 63, wave = tid >> 6, nw = nt >> 6;
@@ -2060,9 +2060,6 @@ static int launch_bounds_kernel(const StepArgs& a, float* U, float* hn, int rese
     if (a.B > 8) {
         // enough K slices that (cluster tiles x slices) fills the device; at most BOUND_KS_MAX (size of the partial buffer)
         const int tiles = (a.C + 15) / 16, nkb = (a.d + 31) / 32;
-#ifndef BOUND_WAVE_TARGET
-#define BOUND_WAVE_TARGET 4096
-#endif
         int KS = (BOUND_WAVE_TARGET + tiles - 1) / tiles;
         KS = ((KS + BOUND_KS_PER_BLOCK - 1) / BOUND_KS_PER_BLOCK) * BOUND_KS_PER_BLOCK;
         if (KS > BOUND_KS_MAX) KS = BOUND_KS_MAX;
@@ -2327,9 +2324,6 @@ extern "C" int csv_decode_step(csv_workspace* ws, const csv_index* idx, const ui
         // blocks per sequence: enough waves that a typical seed prefix (one or two clusters) is one row per wave
         // as many as stay resident together (a second wave of blocks would double the kernel's time), at most 32
         nb = ws->round0_capacity / B;
-#ifndef ROUND0_NB_MAX
-#define ROUND0_NB_MAX 32
-#endif
         nb = nb < 1 ? 1 : (nb > ROUND0_NB_MAX ? ROUND0_NB_MAX : nb);
         round0_kernel<<<dim3(nb, B), SEQ_THREADS, round0_lds(ws), st>>>(a);
         CSV_LAUNCH_CHECK("round0_kernel");
