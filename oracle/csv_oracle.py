@@ -18,7 +18,7 @@ Pins (tests/test_oracle_*.py):
   cluster_bounds     Cauchy-Schwarz invariant (Section III-A), homogeneity, singleton clusters, single cluster
   topk certificate   Theorem 1 against brute force; minimal prefix = {U_c >= true k-th logit}
   eps certificate    proof identity TV = R/(Z_S+R) (Theorem 2), cluster-wise tail <= loose tail
-  alg1_step          brute-force enumeration of all prefixes on small C
+  alg1_step          brute-force enumeration of all prefixes on small C (certificates written out on sets, linear domain)
   csv2r_step         contains Algorithm 1's minimal prefix; monotone thresholds; budget extremes
 Parity unpinned: the choices K_max = V/4, radius slack 2^-14, tie tolerance, and the
 default of requiring both certificates are readings of this build, not values the paper fixes.
@@ -239,51 +239,55 @@ def _kth_largest(vals: np.ndarray, k: int) -> float:
     return float(np.sort(vals)[::-1][k - 1])
 
 
-# ----------------------------------------------------------------------------- Algorithm 1, as printed
+# ----------------------------------------------------------------------------- minimal certifying prefix (Algorithm 1)
+def prefix_certificates(index: OracleIndex, U_row: np.ndarray, logits_row: np.ndarray, opened: np.ndarray, k: int,
+                        eps: float):
+    """Both certificates for the open set `opened` (cluster ids), straight from their definitions.
+
+    Definition 1: the top-k of S is certified when every unopened non-empty cluster's bound lies strictly below the
+    k-th largest logit of S (S must hold at least k rows).  Theorem 2, with the cluster-wise tail of its proof:
+    R-hat = sum over unopened clusters of n_c e^{U_c}; certified when R-hat / (e^{Z_S} + R-hat) <= eps, evaluated in
+    the log domain as log R-hat - Z_S <= ln(eps / (1 - eps)) (S must be non-empty).  With nothing left unopened both hold.
+    Returns (topk_ok, softmax_ok, k-th largest logit of S, Z_S)."""
+    mask = index.n > 0
+    mask[np.asarray(opened, dtype=np.int64)] = False
+    rest = np.flatnonzero(mask)
+    rows = np.concatenate([index.rows(c) for c in opened]) if len(opened) else np.empty(0, dtype=np.int64)
+    vals = logits_row[rows]
+    theta = _kth_largest(vals, k) if k >= 1 else NEG_INF
+    Z = logsumexp(vals)
+    if rest.size == 0:
+        return True, True, theta, Z
+    tk = bool(vals.size >= k and np.max(U_row[rest]) < theta)
+    log_Rhat = logsumexp(np.log(index.n[rest].astype(np.float64)) + U_row[rest])
+    sm = bool(vals.size > 0 and log_Rhat - Z <= _lam(eps))
+    return tk, sm, theta, Z
+
+
 def alg1_step(index: OracleIndex, U_row: np.ndarray, logits_row: np.ndarray, k: int, eps: float,
               K_max: int, combine: int = COMBINE_ANY) -> dict:
-    """One decoding step of Algorithm 1: open clusters one at a time in descending bound order.
+    """What Algorithm 1 returns for one decoding step: the shortest prefix of the bound order that certifies.
 
-    Before each opening, test the top-k certificate (Definition 1: every unopened bound strictly below
-    the k-th largest scored logit) and the eps-softmax certificate (Theorem 2 with the cluster-wise tail,
-    tested in the log domain: T - Z_S <= ln(eps/(1-eps))).  combine=ANY stops on either (the listing);
-    combine=ALL stops only when every enabled test holds.  After each opening, |S| > K_max -> fallback.
-    logits_row holds the exact logits by ORIGINAL token id; scoring a cluster reads its rows' entries.
-    """
+    Clusters are opened in descending bound order (equal bounds: smaller id first; empty clusters are never queued).
+    The result is the smallest m such that the first m clusters satisfy the stopping rule of Section III-C - under
+    combine=ANY either certificate (Algorithm 1 stops on the first that holds), under combine=ALL every enabled one -
+    unless a prefix on the way holds more than K_max rows, in which case the step falls back to the full vocabulary
+    (Algorithm 1 tests the budget after each opening).  logits_row holds the exact logits by ORIGINAL token id;
+    scoring a cluster means reading its rows' entries."""
     order = cluster_order(U_row)
-    order = order[index.n[order] > 0]          # an empty cluster is never in the queue
-    lam = _lam(eps)
+    order = order[index.n[order] > 0]
     use_k, use_s = k >= 1, eps > 0
-    S_ids: list[np.ndarray] = []
-    S_vals = np.empty(0)
-    Z = NEG_INF
-    topk_min = NEG_INF
-    opened = 0
-    while True:
-        rest = order[opened:]
-        if rest.size == 0:
-            tk, sm = True, True
-        else:
-            tk = bool(S_vals.size >= k and U_row[rest[0]] < topk_min)
-            with np.errstate(divide="ignore"):
-                T = logsumexp(np.log(index.n[rest].astype(np.float64)) + U_row[rest])
-            sm = bool(S_vals.size > 0 and T - Z <= lam)
+    P = np.concatenate([[0], np.cumsum(index.n[order])])
+    for m in range(order.shape[0] + 1):
+        if m > 0 and P[m] > K_max:
+            return {"fallback": True, "opened": m, "n_rows": int(P[m])}
+        tk, sm, theta, Z = prefix_certificates(index, U_row, logits_row, order[:m], k, eps)
         tk_ok = tk if use_k else (combine == COMBINE_ALL)
         sm_ok = sm if use_s else (combine == COMBINE_ALL)
-        done = (tk_ok and sm_ok) if combine == COMBINE_ALL else (tk_ok or sm_ok)
-        if done:
-            break
-        c = rest[0]
-        rows = index.rows(c)
-        S_ids.append(rows)
-        S_vals = np.concatenate([S_vals, logits_row[rows]])
-        opened += 1
-        topk_min = _kth_largest(S_vals, k) if use_k else NEG_INF
-        Z = logsumexp(S_vals)
-        if S_vals.size > K_max:
-            return {"fallback": True, "opened": opened, "n_rows": int(S_vals.size)}
-    return {"fallback": False, "opened": opened, "n_rows": int(S_vals.size), "topk_cert": tk, "soft_cert": sm,
-            "clusters": order[:opened].copy(), "theta": topk_min, "Z": Z}
+        if (tk_ok and sm_ok) if combine == COMBINE_ALL else (tk_ok or sm_ok):
+            return {"fallback": False, "opened": m, "n_rows": int(P[m]), "topk_cert": tk, "soft_cert": sm,
+                    "clusters": order[:m].copy(), "theta": theta, "Z": Z}
+    raise AssertionError("with every cluster open both certificates hold")
 
 
 # ----------------------------------------------------------------------------- two-round schedule

@@ -616,3 +616,71 @@ def test_bf16_centroids_keep_the_bound_sound_and_cost_little():
                 ids, _ = O.topk_bruteforce(L[b_], 5)
                 assert np.array_equal(res["ids"], ids)
     assert O.metadata_bytes_bf16(1024, 4096) == 1024 * (8192 + 12)
+
+
+# ------------------------------------------------------------------ the softmax prefix s, the order's tie-break, the margins
+def _flat_clusters(values, sizes):
+    """d = 1 head, h = 1: cluster c holds sizes[c] rows that all have the logit values[c] (bf16-exact), no bias, no
+    radius slack: the radius is 0 and the bound of a cluster IS its logit."""
+    vals = np.repeat(np.array(values, dtype=np.float32), sizes)
+    labels = np.repeat(np.arange(len(values)), sizes)
+    W_bits = synth.f32_to_bf16_bits(vals.reshape(-1, 1))
+    idx = O.build_index(W_bits, None, labels, len(values), radius_slack=0.0)
+    L = O.full_logits(O.bf16_to_f64(W_bits), None, np.array([[1.0]]))[0]
+    U, _ = O.cluster_bounds(idx, np.array([[1.0]]))
+    assert np.all(idx.R == 0) and np.array_equal(U[0], np.array(values, dtype=np.float64))
+    return idx, U[0], L
+
+
+def test_softmax_prefix_is_the_shortest_that_meets_theorem2_traced_by_hand():
+    # Four clusters of two rows with logits 10, 8, 6, 0; eps = 0.01, ln(eps/(1-eps)) = ln(1/99) = -4.59512.
+    # Round 0 opens {10,10}: Z0 = 10 + ln 2.  Tail masses (the ln 2 of "two rows each" cancels against Z0):
+    #   one cluster open   ln(e^8 + e^6 + 1) - 10 = -1.87278   > -4.59512   fails
+    #   two clusters open  ln(e^6 + 1)       - 10 = -3.99752   > -4.59512   fails
+    #   three open         ln(1)             - 10 = -10        <= -4.59512  holds      -> s = 3, not 2 and not 4
+    # Even against the larger Z of two open clusters the second prefix fails (-3.99752 - ln(1 + e^-2) = -4.12445), so
+    # three clusters is also the minimal certifying prefix of Algorithm 1.
+    idx, U, L = _flat_clusters([10.0, 8.0, 6.0, 0.0], [2, 2, 2, 2])
+    eps = 0.01
+    lam = math.log(1.0 / 99.0)
+    t1, t2, t3 = math.log(math.exp(8) + math.exp(6) + 1) - 10, math.log(math.exp(6) + 1) - 10, -10.0
+    assert t1 > lam and t2 > lam and t3 <= lam and t2 - math.log(1 + math.exp(-2)) > lam
+    soft = O.csv2r_step(idx, U, L, 0, eps, K_max=8)                       # softmax test alone: m0 = 1 row suffices
+    assert soft["m0"] == 1 and soft["m1"] == 3 and soft["rounds"] == 2 and soft["flags"] == O.FLAG_SOFTMAX_CERT
+    assert soft["n_rows"] == 6 and soft["clusters"].tolist() == [0, 1, 2]
+    assert O.alg1_step(idx, U, L, 0, eps, K_max=8)["opened"] == 3
+    # both certificates, k = 2: theta0 = 10 > next bound 8, so a = m0 = 1 and the softmax prefix alone sets m1 = max(1, 3)
+    both = O.csv2r_step(idx, U, L, 2, eps, K_max=8, combine=O.COMBINE_ALL)
+    assert both["m0"] == 1 and both["m1"] == 3 and both["rounds"] == 2
+    assert both["flags"] == O.FLAG_TOPK_CERT | O.FLAG_SOFTMAX_CERT and both["ids"].tolist() == [0, 1]
+    # either certificate: the top-k test already holds after round 0
+    either = O.csv2r_step(idx, U, L, 2, eps, K_max=8, combine=O.COMBINE_ANY)
+    assert either["m1"] == 1 and either["rounds"] == 1 and either["flags"] == O.FLAG_TOPK_CERT
+    # the budget is tested on the planned prefix (6 rows): 5 rows are not enough, 6 are
+    assert O.csv2r_step(idx, U, L, 0, eps, K_max=5)["fallback"] and not O.csv2r_step(idx, U, L, 0, eps, K_max=6)["fallback"]
+    # the margins the parity tests use as tie bands are the distances of exactly these comparisons
+    mg = soft["margins"]
+    assert mg["sm0"][0] == pytest.approx(t1 - lam, rel=1e-12) and mg["sm0"][1] == pytest.approx(10 + math.log(2), rel=1e-12)
+    assert mg["s_lo"][0] == pytest.approx(t2 - lam, rel=1e-12)          # the prefix one shorter: how far it is from passing
+    assert mg["s_hi"][0] == pytest.approx(lam - t3, rel=1e-12)          # the chosen prefix: how far it is from failing
+    assert mg["seed"] == (2.0, 10.0) and mg["s_order"] == (6.0, 6.0)     # |10 - 8| at the seed boundary, |6 - 0| after s
+    mb = both["margins"]
+    assert mb["tk0"] == (2.0, 10.0)                                       # next bound 8 against theta0 = 10
+    assert mb["tk1"] == (10.0, 10.0)                                      # after round 1: next bound 0 against theta1 = 10
+    assert mb["id_gap"] == (2.0, 10.0)                                    # 2nd logit 10 against the 3rd, 8
+
+
+def test_equal_bounds_open_the_smaller_cluster_id_first():
+    # Two clusters tie for the largest bound and the seed prefix has room for one of them only (softmax test alone,
+    # eps = 0.6: with one of the two equal clusters open the tail ratio is 1/2 + a negligible rest <= 0.6).
+    for values, first in (([4.0, 4.0, -20.0], 0), ([1.0, 4.0, 4.0], 1), ([4.0, -3.0, 4.0], 0)):
+        idx, U, L = _flat_clusters(values, [1, 1, 1])
+        order = O.cluster_order(U)
+        assert order[0] == first and order[1] == max(i for i, v in enumerate(values) if v == 4.0)
+        r = O.csv2r_step(idx, U, L, 0, 0.6, K_max=3)
+        assert r["rounds"] == 1 and r["clusters"].tolist() == [first] and r["flags"] == O.FLAG_SOFTMAX_CERT
+        assert O.alg1_step(idx, U, L, 0, 0.6, K_max=3)["clusters"].tolist() == [first]
+        # k = 1, either certificate: Definition 1 fails (the tied bound is not strictly below theta0), Theorem 2 holds
+        r = O.csv2r_step(idx, U, L, 1, 0.6, K_max=3, combine=O.COMBINE_ANY)
+        assert r["clusters"].tolist() == [first] and r["ids"].tolist() == [first] and r["flags"] == O.FLAG_SOFTMAX_CERT
+        assert r["margins"]["seed"][0] == 0.0 and r["margins"]["tk0"][0] == 0.0      # both comparisons are exact ties
