@@ -48,5 +48,18 @@ def build(verbose: bool = True) -> str:
     return LIB
 
 
+def build_oracle() -> None:
+    """Compile whatever C the CPU oracle holds (it is plain numpy at present: nothing to compile)."""
+    odir = os.path.join(ROOT, "oracle")
+    for f in sorted(os.listdir(odir)):
+        if f.endswith(".c"):
+            out = os.path.join(odir, "lib" + f[:-2] + ".so")
+            r = subprocess.run(["gcc", "-O2", "-fPIC", "-shared", os.path.join(odir, f), "-o", out, "-lm"],
+                               capture_output=True, text=True)
+            if r.returncode != 0:
+                raise RuntimeError(f"gcc failed for {f}:\n{r.stdout}\n{r.stderr}")
+
+
 if __name__ == "__main__":
     build()
+    build_oracle()
