@@ -24,7 +24,7 @@ EXPORTS = [
     "csv_workspace_create", "csv_workspace_free", "csv_decode_step", "csv_bounds", "csv_full_logits",
     "csv_profile_begin", "csv_profile_end", "csv_last_error", "csv_kmax_init", "csv_kmax_update",
     "csv_workspace_set_spin_limit", "csv_index_use_bf16_centroids",
-    "csv_workspace_set_tail_split",
+    "csv_workspace_set_tail_split", "csv_bounds_static",
 ]
 PROFILE_STAGES = ["bounds", "round0", "tail"]
 
@@ -69,6 +69,7 @@ def _load() -> C.CDLL:
     lib.csv_decode_step.argtypes = [vp, vp, vp, ci, C.POINTER(StepParams), C.POINTER(StepOut), vp]
     lib.csv_bounds.argtypes = [vp, vp, vp, ci, vp, vp, vp]
     lib.csv_full_logits.argtypes = [vp, vp, vp, ci, vp, vp]
+    lib.csv_bounds_static.argtypes = [vp, vp, ci, vp, vp, vp]
     lib.csv_profile_begin.argtypes = [vp, ci]
     lib.csv_profile_end.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(ci)]
     lib.csv_kmax_init.argtypes = [C.POINTER(KmaxCtl), ci, ci, ci, C.c_double, C.c_double, ci]
@@ -283,6 +284,16 @@ def csv_bounds(ws: CsvWorkspace, index: CsvIndex, h: torch.Tensor, stream=None):
     hn = torch.empty(B, dtype=torch.float32, device=h.device)
     _check(lib.csv_bounds(ws._h, index._h, h.data_ptr(), B, U.data_ptr(), hn.data_ptr(), _stream(stream)))
     return U, hn
+
+
+def csv_bounds_static(index: CsvIndex, h: torch.Tensor, U: torch.Tensor, hn: torch.Tensor, stream=None) -> None:
+    """csv_bounds without a workspace and without any allocation: the caller passes the output tensors
+    U [B,C] float32 and hn [B] float32."""
+    _dev2(h, "h")
+    B = h.shape[0]
+    assert U.is_cuda and U.dtype == torch.float32 and U.is_contiguous() and tuple(U.shape) == (B, index.C)
+    assert hn.is_cuda and hn.dtype == torch.float32 and hn.is_contiguous() and hn.numel() == B
+    _check(lib.csv_bounds_static(index._h, h.data_ptr(), B, U.data_ptr(), hn.data_ptr(), _stream(stream)))
 
 
 def csv_full_logits(ws: CsvWorkspace, index: CsvIndex, h: torch.Tensor, out: torch.Tensor | None = None, stream=None):

@@ -20,6 +20,7 @@
 #include <stdarg.h>
 #include <stdlib.h>
 #include <string.h>
+#include <pthread.h>
 
 // ------------------------------------------------------------------------------------------------ errors
 static thread_local char g_err[512] = "";
@@ -2056,16 +2057,23 @@ static int check_pair(const csv_workspace* ws, const csv_index* idx, const void*
     return CSV_OK;
 }
 
+// K slices of the batched bound product and k-blocks (of 32) per slice: enough slices that (cluster tiles x slices)
+// fills the device, at most BOUND_KS_MAX (the partial buffer holds KS x B x C floats).
+static void bound_mfma_plan(int C, int d, int& KS, int& kbs) {
+    const int tiles = (C + 15) / 16, nkb = (d + 31) / 32;
+    KS = (BOUND_WAVE_TARGET + tiles - 1) / tiles;
+    KS = ((KS + BOUND_KS_PER_BLOCK - 1) / BOUND_KS_PER_BLOCK) * BOUND_KS_PER_BLOCK;
+    if (KS > BOUND_KS_MAX) KS = BOUND_KS_MAX;
+    kbs = (nkb + KS - 1) / KS;
+    kbs = (kbs + BOUND_KB_UNROLL - 1) / BOUND_KB_UNROLL * BOUND_KB_UNROLL;   // whole trips of the k loop
+    KS = (nkb + kbs - 1) / kbs;
+}
+
 static int launch_bounds_kernel(const StepArgs& a, float* U, float* hn, int reset, hipStream_t st) {
     if (a.B > 8) {
-        // enough K slices that (cluster tiles x slices) fills the device; at most BOUND_KS_MAX (size of the partial buffer)
-        const int tiles = (a.C + 15) / 16, nkb = (a.d + 31) / 32;
-        int KS = (BOUND_WAVE_TARGET + tiles - 1) / tiles;
-        KS = ((KS + BOUND_KS_PER_BLOCK - 1) / BOUND_KS_PER_BLOCK) * BOUND_KS_PER_BLOCK;
-        if (KS > BOUND_KS_MAX) KS = BOUND_KS_MAX;
-        int kbs = (nkb + KS - 1) / KS;
-        kbs = (kbs + BOUND_KB_UNROLL - 1) / BOUND_KB_UNROLL * BOUND_KB_UNROLL;   // whole trips of the k loop
-        KS = (nkb + kbs - 1) / kbs;
+        const int tiles = (a.C + 15) / 16;
+        int KS, kbs;
+        bound_mfma_plan(a.C, a.d, KS, kbs);
         dim3 grid(tiles, (KS + BOUND_KS_PER_BLOCK - 1) / BOUND_KS_PER_BLOCK);
         for (int s0 = 0; s0 < a.B; s0 += 64) {
             const int nseq = a.B - s0 < 64 ? a.B - s0 : 64;
@@ -2267,6 +2275,63 @@ extern "C" int csv_bounds(csv_workspace* ws, const csv_index* idx, const uint16_
     StepArgs a;
     fill_args(a, ws, idx);
     a.B = B; a.h = d_h;
+    return launch_bounds_kernel(a, d_U, d_hnorm, 0, (hipStream_t)stream);
+}
+
+// ------------------------------------------------------------------------------------------------ bounds without a workspace
+// For callers that cannot allocate: the K-slice partial sums of the batched bound product (the only scratch the
+// bound kernels use) live in a file-scope device array instead of a workspace buffer.  Every GPU holds its own copy
+// of the array at its own address; the address is looked up once per device and handed to the kernels as an argument.
+#define CSV_STATIC_SCRATCH_BYTES (8u << 20)
+#define CSV_STATIC_MAX_DEVICES 64
+static __device__ __align__(256) unsigned char scratch[CSV_STATIC_SCRATCH_BYTES];
+static void* g_scratch_ptr[CSV_STATIC_MAX_DEVICES];          // per device: address of `scratch` there (NULL = not looked up yet)
+static pthread_mutex_t g_scratch_lock = PTHREAD_MUTEX_INITIALIZER;
+
+// Address of the array on the current device (looked up on the first call there).
+static int static_scratch(int dev, void** out) {
+    if (dev < 0 || dev >= CSV_STATIC_MAX_DEVICES) { csv_set_error("device %d outside 0..%d", dev, CSV_STATIC_MAX_DEVICES - 1); return CSV_EINVAL; }
+    pthread_mutex_lock(&g_scratch_lock);
+    void* p = g_scratch_ptr[dev];
+    if (!p) {
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) {
+            pthread_mutex_unlock(&g_scratch_lock);
+            csv_set_error("hipGetSymbolAddress(scratch) failed on device %d: %s", dev, hipGetErrorString(e));
+            return CSV_EHIP;
+        }
+        g_scratch_ptr[dev] = p;
+    }
+    pthread_mutex_unlock(&g_scratch_lock);
+    *out = p;
+    return CSV_OK;
+}
+
+extern "C" int csv_bounds_static(const csv_index* idx, const uint16_t* d_h, int B, float* d_U, float* d_hnorm, void* stream) {
+    if (!idx || !d_h || !d_U) { csv_set_error("null index, h or d_U"); return CSV_EINVAL; }
+    if (B < 1 || B > CSV_MAX_BATCH) { csv_set_error("B=%d outside 1..%d", B, CSV_MAX_BATCH); return CSV_ESHAPE; }
+    int dev = -1;
+    CSV_HIP(hipGetDevice(&dev));
+    if (dev != idx->device) { csv_set_error("the index lives on device %d, the current device is %d", idx->device, dev); return CSV_EINVAL; }
+    StepArgs a;
+    memset(&a, 0, sizeof(a));
+    a.V = idx->V; a.d = idx->d; a.C = idx->C;
+    a.mu = idx->mu; a.mu16 = idx->mu16; a.R = idx->R; a.bmax = idx->bmax; a.n = idx->n;
+    a.B = B; a.h = d_h;
+    if (B > 8) {                       // the batched product is the only bound kernel with scratch: KS x B x C partial sums
+        int KS, kbs;
+        bound_mfma_plan(idx->C, idx->d, KS, kbs);
+        const size_t need = (size_t)KS * B * idx->C * sizeof(float);
+        if (need > CSV_STATIC_SCRATCH_BYTES) {
+            csv_set_error("B=%d sequences x C=%d clusters need %zu bytes of partial sums, the static scratch holds %u: "
+                          "use csv_bounds with a workspace", B, idx->C, need, CSV_STATIC_SCRATCH_BYTES);
+            return CSV_ESHAPE;
+        }
+        void* p = nullptr;
+        const int rc = static_scratch(dev, &p);
+        if (rc) return rc;
+        a.bound_partial = (float*)p;
+    }
     return launch_bounds_kernel(a, d_U, d_hnorm, 0, (hipStream_t)stream);
 }
 
