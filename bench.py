@@ -112,6 +112,14 @@ def main() -> int:
     gpu_ms = e0.elapsed_time(e1)
     ms_per_step = wall * 1e3 / K
     log(f"[bench] {K} steps: wall {wall * 1e3:.2f} ms, stream {gpu_ms:.2f} ms -> {K / wall:.0f} steps/s")
+    # the same region a few more times (not part of `value`): how much a region of this length varies from run to run
+    rep_ms = []
+    for _ in range(9):
+        t1 = time.perf_counter()
+        run(K, W)
+        torch.cuda.synchronize()
+        rep_ms.append((time.perf_counter() - t1) * 1e3 / K)
+    repeats = {"n": len(rep_ms), "median": float(np.median(rep_ms)), "min": float(min(rep_ms)), "max": float(max(rep_ms))}
 
     # ---------------- per-stage HIP-event timing over the same K steps (second pass, same stream)
     ws.profile_begin(K)
@@ -164,68 +172,109 @@ def main() -> int:
     full_ms = (time.perf_counter() - t1) * 1e3 / nfull
     full_bytes = r.V * (2 * r.d + 8) + r.B * r.d * 2
 
-    # ---------------- roofline of the dominant kernel
-    # Algorithmic bytes per launch: bound_kernel reads the centroids and cluster metadata once and h, writes U;
-    # the gathered GEMV reads each opened row with its bias and id and h per tile; the tail's full product reads W' once.
+    # ---------------- roofline
+    # At small batches a step is a short chain of dependent launches (bounds -> round 0 with certification), none of
+    # which can be timed alone from the host without adding more than it lasts, so the unit priced against the HBM
+    # roofline is the whole step: algorithmic bytes of a step / the step time of the timed region above.  The
+    # launch that takes most of a step's time is named next to it, with its own bytes and its share of the step
+    # (step time minus the bound launch timed back to back; per-kernel durations from rocprofv3 are in profiles/).
+    # When most steps contain a fallback the full-vocabulary product dominates and is timed as a launch of its own.
     mean_rows_seq = rows_sum / max(1, n_seq - int(round(fb_rate * n_seq)))
-    bound_bytes = r.C * r.d * (2 if args.bf16_centroids else 4) + 12 * r.C + r.B * r.d * 2 + 4 * r.B * r.C
-    gemv_bytes = (rows_sum / nstat) * (2 * r.d + 16) + r.B * r.d * 2
+    mu_b = 2 if args.bf16_centroids else 4
+    bound_bytes = r.C * r.d * mu_b + 12 * r.C + r.B * r.d * 2 + 4 * r.B * r.C
+    rows_step = rows_sum / nstat
+    round0_bytes = rows_step * (2 * r.d + 16) + r.B * r.d * 2 + r.B * (4 * r.C * 2) + r.B * (8 * r.k + 16)
     full_bytes_launch = r.V * (2 * r.d + 8) + r.B * r.d * 2
-    # The dominant kernel is the one that moves most of the step's bytes: the bound kernel (all centroids) on the
-    # sub-vocabulary path, the full-vocabulary product when most steps contain a fallback.  Its average launch
-    # duration is measured with HIP events around back-to-back launches of that kernel alone on the same stream
-    # (events between the kernels of a step would add their own few microseconds to every stage).
-    nrep = 200
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    bstep = step_bytes(r, r.C, rows_union_sum / nstat, anyfb / nstat, r.k, mu_b)
+    eff_gbs = bstep / (ms_per_step * 1e-3) / 1e9
+    sharing = rows_sum / rows_union_sum if rows_union_sum else None     # sum_b |S_b| / |union_b S_b|
+
+    U_out = torch.empty((r.B, r.C), dtype=torch.float32, device="cuda")
+    hn_out = torch.empty(r.B, dtype=torch.float32, device="cuda")
+
+    def time_bounds(nrep, flush=None):
+        """Average duration of one launch of the bound kernel(s): back to back (warm: the centroids stay in the
+        256 MB last-level cache between launches), or each launch preceded by a read of a buffer larger than
+        that cache and timed by its own pair of events (cold: the centroids come from HBM)."""
+        for s in range(10):
+            csv.lib.csv_bounds(ws._h, idx._h, hp[s], r.B, U_out.data_ptr(), hn_out.data_ptr(), sp)
+        torch.cuda.synchronize()
+        if flush is None:
+            a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a0.record(stream)
+            for s in range(nrep):
+                csv.lib.csv_bounds(ws._h, idx._h, hp[s % len(hp)], r.B, U_out.data_ptr(), hn_out.data_ptr(), sp)
+            a1.record(stream)
+            torch.cuda.synchronize()
+            return a0.elapsed_time(a1) * 1e3 / nrep
+        tot = 0.0
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(nrep)]
+        for s in range(nrep):
+            flush.sum()                                   # streams the whole buffer through the caches
+            evs[s][0].record(stream)
+            csv.lib.csv_bounds(ws._h, idx._h, hp[s % len(hp)], r.B, U_out.data_ptr(), hn_out.data_ptr(), sp)
+            evs[s][1].record(stream)
+        torch.cuda.synchronize()
+        # a pair of events around nothing costs a few microseconds of its own: measured and taken off
+        e0_, e1_ = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        empty = []
+        for s in range(20):
+            flush[:1 << 20].sum()
+            e0_.record(stream); e1_.record(stream)
+            torch.cuda.synchronize()
+            empty.append(e0_.elapsed_time(e1_))
+        base = float(np.median(empty))
+        tot = float(np.median([a.elapsed_time(b) for a, b in evs])) - base
+        return tot * 1e3
+
+    bound_name = "bound1_kernel" if r.B == 1 else ("bound_kernel" if r.B <= 8 else "bound_mfma_kernel + bound_finish_kernel")
+    bound_warm_us = time_bounds(200)
+    flush_buf = torch.empty(768 << 20, dtype=torch.uint8, device="cuda").zero_()
+    bound_cold_us = time_bounds(30, flush_buf)
+    del flush_buf
+    kernels = {
+        bound_name: {"bytes_per_launch": bound_bytes, "back_to_back_us": bound_warm_us,
+                     "GBps_back_to_back": bound_bytes / bound_warm_us / 1e3,
+                     "cold_us": bound_cold_us, "GBps_cold": bound_bytes / max(bound_cold_us, 1e-3) / 1e3,
+                     "note": "back to back the centroids are served by the 256 MB last-level cache; cold = after 768 MB "
+                             "of other traffic, one launch between its own events (event cost taken off)"},
+    }
     if anyfb / nstat > 0.5:
-        dom_name, dom_bytes = "full_gemv_kernel (full-vocabulary product, all B sequences)", full_bytes_launch
         nrep = 20
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         ev0.record(stream)
         for s in range(nrep):
             csv.csv_full_logits(ws, idx, dh[s % nh], out=full_out)
         ev1.record(stream)
-    else:
-        dom_name = "bound1_kernel" if r.B == 1 else ("bound_kernel" if r.B <= 8 else "bound_mfma_kernel + bound_finish_kernel")
-        dom_bytes = bound_bytes
-        U_out = torch.empty((r.B, r.C), dtype=torch.float32, device="cuda")
-        hn_out = torch.empty(r.B, dtype=torch.float32, device="cuda")
-        for s in range(10):
-            csv.lib.csv_bounds(ws._h, idx._h, hp[s], r.B, U_out.data_ptr(), hn_out.data_ptr(), sp)
         torch.cuda.synchronize()
-        # The launches are recorded once into a HIP graph and replayed between the events, so the host's per-call
-        # cost (a ctypes call is a few microseconds, about the kernel's own duration) is not in the measurement.
-        graph = None
-        try:
-            graph = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(graph):
-                cs = torch.cuda.current_stream().cuda_stream
-                for s in range(nrep):
-                    csv.lib.csv_bounds(ws._h, idx._h, hp[s % len(hp)], r.B, U_out.data_ptr(), hn_out.data_ptr(), cs)
-            graph.replay()
-            torch.cuda.synchronize()
-        except Exception as e:      # capture not available: time direct launches
-            log(f"[bench] graph capture of the bound launches failed ({e}); timing direct launches")
-            graph = None
-        ev0.record(stream)
-        if graph is not None:
-            graph.replay()
-        else:
-            for s in range(nrep):
-                csv.lib.csv_bounds(ws._h, idx._h, hp[s % len(hp)], r.B, U_out.data_ptr(), hn_out.data_ptr(), sp)
-        ev1.record(stream)
-    torch.cuda.synchronize()
-    dom_us = ev0.elapsed_time(ev1) * 1e3 / nrep
-    achieved = dom_bytes / (dom_us * 1e-6) / 1e9
-    # measured HBM bytes per launch of that kernel: taken from the committed rocprofv3 --pmc summary of this workload
-    traffic = None
+        dom_us = ev0.elapsed_time(ev1) * 1e3 / nrep
+        roof = {"bound": "hbm", "kernel": "full-vocabulary product for all B sequences (full_mfma_kernel / full_gemv_kernel), the launch "
+                                          "that dominates a step when most steps contain a fallback; timed back to back",
+                "achieved": full_bytes_launch / dom_us / 1e3, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "bytes_per_launch": full_bytes_launch, "avg_launch_us": dom_us}
+    else:
+        step_us = ms_per_step * 1e3
+        rest_us = max(step_us - bound_warm_us, 1e-3)
+        kernels["round 0 and what follows it (step_kernel, or round0_kernel + tail launches)"] = {
+            "bytes_per_launch": round0_bytes, "in_step_us": rest_us, "share_of_step": rest_us / step_us,
+            "GBps": round0_bytes / rest_us / 1e3, "frac_of_peak": round0_bytes / rest_us / 1e3 / HBM_PEAK_GBS,
+            "note": "step time minus the bound launch timed back to back: a chain of dependent round trips "
+                    "(bounds -> seed cluster -> its rows -> logits -> top-k, certificates), latency-bound"}
+        roof = {"bound": "hbm", "kernel": f"whole decode step: {bound_name} + round-0/certification launch (dependent launches of one step)",
+                "achieved": eff_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "bytes_per_launch": bstep, "avg_launch_us": step_us}
+    roof["frac"] = roof["achieved"] / HBM_PEAK_GBS
+    # measured HBM bytes per step: taken from the committed rocprofv3 --pmc summary of this workload (not measured in this run)
+    traffic, tsrc = None, None
     tfile = os.path.join(ROOT, "profiles", f"decode_step_{r.name}_hbm_traffic.txt")
     if os.path.exists(tfile):
         for line in open(tfile):
             f = line.split()
-            if len(f) == 3 and f[0] == "traffic_bytes_per_launch" and dom_name.startswith(f[1]):
-                traffic = int(f[2])
-    bstep = step_bytes(r, r.C, rows_union_sum / nstat, anyfb / nstat, r.k, 2 if args.bf16_centroids else 4)
-    eff_gbs = bstep / (ms_per_step * 1e-3) / 1e9
+            if len(f) == 3 and f[0] == "traffic_bytes_per_launch" and f[1] == ("full_product" if anyfb / nstat > 0.5 else "decode_step"):
+                traffic, tsrc = int(f[2]), os.path.relpath(tfile, ROOT)
+    roof["traffic"] = traffic
+    roof["traffic_source"] = tsrc
+    roof["kernels"] = kernels
 
     # ---------------- CPU baseline: the oracle as it stands, on a bounded sample of the same workload
     cpu = None
@@ -255,18 +304,17 @@ def main() -> int:
         "metric": "certified decode steps/sec + effective HBM GB/s, V=128256 d=4096 B=1",
         "value": K / wall, "unit": "steps/s", "n_gpus": 1, "steps": K, "warmup": W,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
+        "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{r.name}: V={r.V} d={r.d} C={r.C} B={r.B} k={r.k} eps={r.eps:g} K_max={r.K_max_rows} "
-                               f"combine=ALL, bf16 W and h, planted clusters"
+                               f"combine=ALL, bf16 W and h, float32 accumulation, planted clusters"
                                + (", bf16 centroids" if args.bf16_centroids else "")
                                + (f", fallback levels max_rounds={args.max_rounds} delta_clusters={args.delta_clusters} relax={int(args.relax)}"
                                   if (args.max_rounds or args.delta_clusters or args.relax) else ""), "batch": r.B},
-        "roofline": {"bound": "hbm", "kernel": dom_name, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                     "bytes_per_launch": dom_bytes, "avg_launch_us": dom_us},
+        "roofline": roof,
         "cpu_baseline": cpu,
         "effective_hbm_GBps": eff_gbs, "algorithmic_bytes_per_step": bstep,
         "stream_ms_per_step": gpu_ms / K,
+        "repeat_ms_per_step": repeats,
         "seq_steps_per_s": K * r.B / wall,
         "stage_us": stage_us,
         "latency_us": {"p50": float(lat[len(lat) // 2] * 1e6), "p95": float(lat[int(len(lat) * 0.95)] * 1e6)},
@@ -274,6 +322,7 @@ def main() -> int:
         "mean_rows_per_certified_seq": mean_rows_seq, "mean_clusters_per_certified_seq": ncl_sum / max(1, n_seq - int(round(fb_rate * n_seq))),
         "sub_vocab_ratio": mean_rows_seq / r.V, "rounds_hist": {k: v for k, v in rounds_hist.items() if v or k <= 2},
         "relaxed_rate": n_relaxed / n_seq,
+        "sharing_factor": sharing,
         "full_gemv": {"ms_per_step": full_ms, "steps_per_s": 1e3 / full_ms, "GBps": full_bytes / (full_ms * 1e-3) / 1e9},
         "speedup_vs_full_gemv": full_ms / ms_per_step,
     }

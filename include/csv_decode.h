@@ -38,8 +38,9 @@ extern "C" {
 #define CSV_FLAG_FALLBACK      4u   /* all V rows were scored for this sequence */
 #define CSV_FLAG_SOFTMAX_RELAXED 16u /* the softmax tail bound holds only at the relaxed tolerance 2*eps (Section IV,
                                        fallback levels); never set together with SOFTMAX_CERT */
-#define CSV_FLAG_INVALID_INPUT 8u   /* ||h||^2 is not finite (other outputs of the sequence are cleared), or the
-                                       step could not finish the sequence (a bounded device-side wait ran out) */
+#define CSV_FLAG_INVALID_INPUT 8u   /* ||h||^2 is not finite (other outputs of the sequence are cleared) */
+#define CSV_FLAG_ABORTED      32u   /* the step could not finish this sequence: a bounded device-side wait ran out (see
+                                       csv_workspace_set_spin_limit); its other outputs are undefined.  Set alone. */
 
 #define CSV_COMBINE_ALL 0   /* certified when every enabled certificate holds */
 #define CSV_COMBINE_ANY 1   /* certified when any enabled certificate holds (Algorithm 1 stops on either) */
@@ -186,18 +187,20 @@ int csv_full_logits(csv_workspace* ws, const csv_index* idx, const uint16_t* d_h
                     float* d_logits, void* stream);
 
 /*
- * Failure handling of the device-side waits.  The kernel that runs round 1 and the fallback keeps all its blocks
- * resident and separates its phases with grid barriers; a block polls a barrier at most `polls` times (default
+ * Failure handling of the device-side waits.  The blocks that run round 1 and the fallback as one kernel stay
+ * resident, wait for round 0 to be settled when they share its launch, and separate their phases with grid barriers;
+ * a block polls such a wait at most `polls` times (default
  * 2^22, about a second), then sets an abort flag that makes every block leave.  Sequences the step had not finished
- * by then keep flag INVALID_INPUT; the next csv_decode_step starts from a clean state.  polls = 0 restores the
+ * by then carry flag ABORTED; the next csv_decode_step starts from a clean state.  polls = 0 restores the
  * default.  A tiny limit is how the error path is exercised in tests without any kernel failing to exit.
  */
 int csv_workspace_set_spin_limit(csv_workspace* ws, int polls);
 
 /*
- * What follows round 0 (further rounds, the full vocabulary for fallback sequences) runs either as one kernel that
- * keeps all its blocks resident and returns at once when no sequence needs it (one launch on the common path of an
- * easy workload), or as one launch per phase (kernel boundaries instead of grid barriers: faster whenever that work
+ * What follows round 0 (further rounds, the full vocabulary for fallback sequences) runs either as one set of blocks
+ * that stay resident and leave at once when no sequence needs them (for small batches they ride in the round-0
+ * launch, parked until round 0 is settled: two launches per step on the common path of an easy workload; otherwise
+ * they are a launch of their own), or as one launch per phase (kernel boundaries instead of grid barriers: faster whenever that work
  * is actually needed).  By default (min_batch = 0) every step follows the recent steps: per-phase launches when at
  * least two of the last eight needed the tail (a device-side bit history mirrored to pinned host memory and read
  * without synchronising, so it may lag a few steps).  min_batch > 0 fixes the choice: batches of at least min_batch

@@ -15,7 +15,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libcsvdecode.so")
 
-FLAG_TOPK_CERT, FLAG_SOFTMAX_CERT, FLAG_FALLBACK, FLAG_INVALID_INPUT, FLAG_SOFTMAX_RELAXED = 1, 2, 4, 8, 16
+FLAG_TOPK_CERT, FLAG_SOFTMAX_CERT, FLAG_FALLBACK, FLAG_INVALID_INPUT, FLAG_SOFTMAX_RELAXED, FLAG_ABORTED = 1, 2, 4, 8, 16, 32
 COMBINE_ALL, COMBINE_ANY = 0, 1
 MAX_K, MAX_CLUSTERS, MAX_BATCH = 1024, 8192, 256
 

@@ -23,6 +23,8 @@ struct csv_index {
     int32_t* n;      // [C]   rows per cluster
     int32_t* off;    // [C+1] first permuted row of each cluster
     float* lnn;      // [C]   ln n_c (-inf for an empty cluster)
+    int4* cmeta;     // [C]   {first permuted row, rows, bit pattern of ln n_c, 0}: what the seed selection needs of a
+                     //       cluster in one 128-bit load
     float ln_nmax;   // ln of the largest cluster size
     int n_max;       // the largest cluster size
 };
@@ -35,8 +37,10 @@ enum { ST_ACTIVE = 0, ST_DONE = 1, ST_FALLBACK = 2, ST_INVALID = 3 };
 // certification of round r; 2*CSV_MAX_ROUNDS + j: the fallback phases); [CNT_TILES + r*CSV_MAX_BATCH + b] row tiles
 // of sequence b in round r's work list; [CNT_CHUNKS + r*CSV_MAX_BATCH + b] chunk blocks of round r's certification
 // that have published their partial results; [CNT_ARRIVE + b] blocks of the round-0 kernel that have finished their
-// share of sequence b's seed rows.  All are zeroed by the bound kernel at the start of a step.
-enum { CNT_FALLBACK = 0, CNT_ABORT = 1, CNT_TAIL_NEEDED = 2, CNT_BARRIER = 16, CNT_TILES = 64, CNT_CHUNKS = 64 + CSV_MAX_ROUNDS * CSV_MAX_BATCH,
+// share of sequence b's seed rows; [CNT_R0_DONE] sequences whose round 0 is settled (certified, planned, handed over
+// or invalid): what the blocks that run the tail inside the round-0 launch wait for.
+// All are zeroed by the bound kernel at the start of a step.
+enum { CNT_FALLBACK = 0, CNT_ABORT = 1, CNT_TAIL_NEEDED = 2, CNT_R0_DONE = 3, CNT_BARRIER = 16, CNT_TILES = 64, CNT_CHUNKS = 64 + CSV_MAX_ROUNDS * CSV_MAX_BATCH,
        CNT_ARRIVE = 64 + 2 * CSV_MAX_ROUNDS * CSV_MAX_BATCH, CNT_TOTAL = 64 + (2 * CSV_MAX_ROUNDS + 1) * CSV_MAX_BATCH,
        // not reset: bit i = whether the step i steps back needed anything after round 0 (kept behind the reset range)
        CNT_HISTORY = CNT_TOTAL, CNT_ALLOC = CNT_TOTAL + 16 };
@@ -74,6 +78,8 @@ struct csv_workspace {
     int* h_history;                    // pinned host word the bound kernel copies the history to (read without a sync)
     int* d_history;                    // the same word as the device sees it
     size_t tail_lds;                   // its dynamic LDS
+    size_t fused_lds;                  // dynamic LDS of the launch that holds round 0 and the tail together
+    int fused_ok;                      // that launch fits one block per compute unit
     int device;
     float* U;          // [B*C]      cluster bounds
     float* bound_partial; // K-slice partial sums of the batched (MFMA) bound product
@@ -333,3 +339,4 @@ __device__ __forceinline__ float lse_value(LseAcc a) { return a.s == 0.f ? -INFI
 
 // ---------------------------------------------------------------------------------------------- internal entry points
 int csv_index_alloc(int V, int d, int C, csv_index** out);
+int csv_index_pack_cmeta(csv_index* x, hipStream_t st);   // fills cmeta from off and lnn (both final)

@@ -229,7 +229,20 @@ __global__ __launch_bounds__(256) void init_centroid_kernel(const uint16_t* __re
     for (int j = threadIdx.x; j < d; j += 256) mu[(size_t)c * d + j] = __uint_as_float((uint32_t)w[j] << 16);
 }
 
+// cmeta[c] = {off[c], off[c+1] - off[c], bits of ln n_c, 0}
+__global__ __launch_bounds__(256) void pack_cmeta_kernel(const int32_t* __restrict__ off, const float* __restrict__ lnn, int C,
+                                                         int4* __restrict__ cmeta) {
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    if (c < C) cmeta[c] = make_int4(off[c], off[c + 1] - off[c], __float_as_int(lnn[c]), 0);
+}
+
 // ------------------------------------------------------------------------------------------------ host side
+int csv_index_pack_cmeta(csv_index* x, hipStream_t st) {
+    pack_cmeta_kernel<<<(x->C + 255) / 256, 256, 0, st>>>(x->off, x->lnn, x->C, x->cmeta);
+    CSV_LAUNCH_CHECK("pack_cmeta_kernel");
+    return CSV_OK;
+}
+
 static int check_shape(int V, int d, int C) {
     if (V < 1 || d < 8 || (d & 7) != 0) { csv_set_error("need V >= 1 and d a positive multiple of 8 (V=%d, d=%d)", V, d); return CSV_ESHAPE; }
     if (C < 1 || C > V || C > CSV_MAX_CLUSTERS) { csv_set_error("C=%d outside 1..min(V,%d)", C, CSV_MAX_CLUSTERS); return CSV_ESHAPE; }
@@ -245,6 +258,7 @@ int csv_index_alloc(int V, int d, int C, csv_index** out) {
     A((void**)&x->Wp, (size_t)V * d * 2); A((void**)&x->bp, (size_t)V * 4); A((void**)&x->perm, (size_t)V * 4);
     A((void**)&x->mu, (size_t)C * d * 4); A((void**)&x->R, (size_t)C * 4); A((void**)&x->bmax, (size_t)C * 4);
     A((void**)&x->n, (size_t)C * 4); A((void**)&x->off, (size_t)(C + 1) * 4); A((void**)&x->lnn, (size_t)C * 4);
+    A((void**)&x->cmeta, (size_t)C * sizeof(int4));
     if (e != hipSuccess) {
         csv_set_error("index allocation failed: %s", hipGetErrorString(e));
         csv_index_free(x);
@@ -256,7 +270,7 @@ int csv_index_alloc(int V, int d, int C, csv_index** out) {
 
 extern "C" void csv_index_free(csv_index* x) {
     if (!x) return;
-    void* ptrs[] = {x->Wp, x->bp, x->perm, x->mu, x->mu16, x->R, x->bmax, x->n, x->off, x->lnn};
+    void* ptrs[] = {x->Wp, x->bp, x->perm, x->mu, x->mu16, x->R, x->bmax, x->n, x->off, x->lnn, x->cmeta};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
     free(x);
@@ -414,6 +428,7 @@ extern "C" int csv_build_index(const uint16_t* d_W, const float* d_b, int V, int
         radius_finish_kernel<<<C, 256, 0, st>>>(x->bp, x->off, x->mu, d, (double)o->radius_slack, d_d2max, x->R, x->bmax, x->lnn);
         launched = hipGetLastError() == hipSuccess;
     }
+    if (launched) launched = csv_index_pack_cmeta(x, st) == CSV_OK;
     const bool synced = hipStreamSynchronize(st) == hipSuccess;
     (void)hipFree(d_d2max);
     if (!launched) { csv_set_error("launch of the radius kernels failed"); return fail(CSV_EHIP); }
@@ -461,6 +476,7 @@ extern "C" int csv_index_from_arrays(const uint16_t* d_W, const float* d_b, int 
     if (e != hipSuccess) { csv_set_error("metadata upload failed: %s", hipGetErrorString(e)); return fail(CSV_EHIP); }
     if ((rc = upload_layout(x, n, off, perm, st))) return fail(rc);
     if ((rc = gather(x, d_W, d_b, st))) return fail(rc);
+    if ((rc = csv_index_pack_cmeta(x, st))) return fail(rc);
     if (hipStreamSynchronize(st) != hipSuccess) { csv_set_error("index import failed on the device"); return fail(CSV_EHIP); }
     *out = x;
     return CSV_OK;

@@ -45,6 +45,7 @@ struct StepArgs {
     const int32_t* n;
     const int32_t* off;
     const float* lnn;
+    const int4* cmeta;      // per cluster {first row, rows, bits of ln n, 0}
     float ln_nmax;
     int B, K_cap, Npad, n_chunks, tile_stride;
     int sp_chunks;     // most STAGE_CAP-sized chunks a sequence's scored rows can span
@@ -93,6 +94,7 @@ struct StepArgs {
 #define BIGQ 32            // clusters whose tiles are written cooperatively per emit call
 
 typedef unsigned long long u64;
+#define CSV_STATIC_MAX_DEVICES 64   // devices the per-device host tables of this file cover
 
 // Key of a value for ordering: -0 and +0 compare equal.
 __device__ __forceinline__ uint32_t lkey(float v) { return fkey(v + 0.0f); }
@@ -541,7 +543,7 @@ __device__ __forceinline__ void write_invalid(const StepArgs& a, int b) {
 // Called by one thread: hand sequence b to the full-vocabulary path.
 __device__ __forceinline__ void push_fallback(const StepArgs& a, int b, int rounds) {
     const int slot = atomicAdd(&a.counters[CNT_FALLBACK], 1);
-    a.counters[CNT_TAIL_NEEDED] = 1;
+    __hip_atomic_store(&a.counters[CNT_TAIL_NEEDED], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     a.fb_list[slot] = b;
     a.st[b].status = ST_FALLBACK;
     a.st[b].fb_slot = slot;
@@ -650,7 +652,7 @@ __device__ __forceinline__ void emit_clusters(const StepArgs& a, int b, int roun
     block_excl_scan3(cnt, rows, tiles, s.scan3, tot_cnt, tot_rows, tot_tiles);
     if (tid == 0) {
         a.counters[CNT_TILES + round * CSV_MAX_BATCH + b] = tot_tiles;
-        a.counters[CNT_TAIL_NEEDED] = 1;
+        __hip_atomic_store(&a.counters[CNT_TAIL_NEEDED], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         s.nbig = 0;
     }
     __syncthreads();
@@ -1428,10 +1430,71 @@ __device__ __forceinline__ SeqState seed_state(int m0, int rows, u64 kappa, floa
     return st;
 }
 
-__global__ __launch_bounds__(SEQ_THREADS) void round0_kernel(StepArgs a) {
+// Seed selection for indexes of at most 64 * SEED_E clusters.  The block stages the sequence's bounds and ln n_c
+// in LDS once (one barrier, shared with the staging of h); after that every wave works alone: lane l looks at
+// clusters l, l + 64, ..., the wave takes the arg-max of the 64-bit keys and fetches the winner's packed metadata.
+// Every wave of every block of the sequence gets the same answer.  When the best cluster alone holds max(k,1) rows
+// (the common case: clusters larger than k) it is the whole seed prefix; the wave requests its row and only then
+// takes, from the same registers, the next bound and the log tail mass of everything else, while the row is in
+// flight.  Otherwise the caller falls through to the general selection.
+#define SEED_E 16
+struct WaveSeed {
+    int c, row0, rows;
+    u64 kappa;
+    float u[SEED_E], l[SEED_E];     // bounds and ln n of the lane's clusters (-inf: empty or out of range)
+};
+// sU, sL: LDS copies of U[b,:] and ln n
+__device__ __forceinline__ void wave_seed_pick(const StepArgs& a, const float* sU, const float* sL, WaveSeed& r) {
+    const int lane = threadIdx.x & 63, C = a.C;
+    u64 best = 0;
+#pragma unroll
+    for (int i = 0; i < SEED_E; ++i) {
+        const int c = lane + 64 * i;
+        r.u[i] = c < C ? sU[c] : -INFINITY;
+        r.l[i] = c < C ? sL[c] : -INFINITY;
+        const u64 kx = r.l[i] > -INFINITY ? ckey(r.u[i], c) : 0ull;
+        best = kx > best ? kx : best;
+    }
+    r.kappa = wave_max_u64(best);
+    r.c = (int)(0xFFFFFFFFu - (uint32_t)r.kappa);
+    r.row0 = 0;
+    r.rows = 0;
+    if (r.kappa != 0) {
+        const int4 cm = a.cmeta[r.c];       // the same address in every lane
+        r.row0 = cm.x;
+        r.rows = cm.y;
+    }
+}
+// next bound and log tail mass with cluster r.c open and everything else unopened
+__device__ __forceinline__ void wave_seed_tail(const StepArgs& a, const WaveSeed& r, float& nxtU, float& T0) {
+    const int lane = threadIdx.x & 63;
+    unsigned nk = 0;
+#pragma unroll
+    for (int i = 0; i < SEED_E; ++i) {
+        const bool rest = r.l[i] > -INFINITY && (lane + 64 * i) != r.c;
+        const unsigned kx = lkey(r.u[i]);
+        nk = (rest && kx > nk) ? kx : nk;
+    }
+    nk = wave_max_u(nk);
+    nxtU = -INFINITY;
+    T0 = -INFINITY;
+    if (nk == 0) return;                                      // the prefix is the whole vocabulary
+    nxtU = fkey_inv(nk);
+    const float shift = a.ln_nmax + nxtU;
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < SEED_E; ++i) {
+        const bool rest = r.l[i] > -INFINITY && (lane + 64 * i) != r.c;
+        if (rest) sum += expf(r.l[i] + r.u[i] - shift);
+    }
+    sum = wave_sum(sum);
+    T0 = shift + logf(sum);
+}
+
+// One sequence's round 0 as seen by block j of its NB blocks.  Returns true in the one block that settled the
+// sequence (certified it, planned its next round, handed it over or flagged it), after all that block's writes.
+__device__ __forceinline__ bool round0_device(const StepArgs& a, int b, int j, int NB, SeqShared& s) {
     extern __shared__ u64 arena[];
-    __shared__ SeqShared s;
-    const int b = blockIdx.y, j = blockIdx.x, NB = gridDim.x;
     const int tid = threadIdx.x, nt = SEQ_THREADS, lane = tid & 63, wave = tid >> 6, C = a.C;
     const int nch = a.d >> 3;
     const ClusterLds L = carve_clusters(arena, a.Npad, C);
@@ -1447,105 +1510,21 @@ __global__ __launch_bounds__(SEQ_THREADS) void round0_kernel(StepArgs a) {
         }
     }
     const float hn = a.hnorm[b];
-    if (j == 0 && tid == 0) a.out.d_flags[b] = CSV_FLAG_INVALID_INPUT;   // pending: overwritten by whichever path finishes the sequence
-    load_clusters(a, b, L);
-    if (!isfinite(hn)) {
-        if (j == 0) write_invalid(a, b);
-        return;
-    }
-    __syncthreads();
-    DBG_T(1);
-    // Open clusters one at a time by block-wide arg-max until max(k,1) rows are open.  Every opened cluster has
-    // at least one row, so at most max(k,1) <= CSV_MAX_K clusters open: their ids and positions fit the k-sized
-    // arrays.  Nothing is written to global memory inside the loop (a store would be waited for at the next barrier).
+    if (j == 0 && tid == 0) a.out.d_flags[b] = CSV_FLAG_ABORTED;   // pending: overwritten by whichever path finishes the sequence
+    const int need = max(a.k, 1);
+    const int GW = NB * (nt >> 6);
+    const int cap_rows = min(GW * ROUND0_ROWS_PER_WAVE, STAGE_CAP);
     int* scl = s.wid;
     int* spos = reinterpret_cast<int*>(s.wval);
-    const int need = max(a.k, 1);
     int rows = 0, m0 = 0;
     u64 kappa = ~0ull, nxt = 0;
-    while (true) {
-        // the best unopened cluster and the one after it, in one reduction: when the best completes the prefix,
-        // the runner-up is already the next unopened bound
-        Top2 t2{0ull, 0ull};
-        for (int c = tid; c < C; c += nt) {
-            const u64 kx = L.keys[c];
-            if (kx < kappa) t2 = top2_push(t2, kx);
-        }
-        t2 = block_top2(t2, s.redu);
-        if (t2.a == 0) {                   // nothing left to open
-            nxt = 0;
-            break;
-        }
-        const int cw = (int)(0xFFFFFFFFu - (uint32_t)t2.a);
-        if (tid == 0) {
-            scl[m0] = cw;
-            spos[m0] = rows;
-        }
-        rows += L.offl[cw + 1] - L.offl[cw];
-        m0 += 1;
-        kappa = t2.a;
-        if (rows >= need) {
-            nxt = t2.b;
-            break;
-        }
-    }
-    DBG_T(2);
-    if (rows > a.K_max) {
-        if (j == 0 && tid == 0) {
-            a.st[b].n_open = m0;
-            a.st[b].n_rows = rows;
-            push_fallback(a, b, 0);
-        }
-        return;
-    }
-    __syncthreads();   // scl / spos complete
-    if (j == 0)
-        for (int i = tid; i < m0; i += nt) a.sel[(size_t)b * C + i] = scl[i];
-    const int GW = NB * (nt >> 6);
-    if (rows > min(GW * ROUND0_ROWS_PER_WAVE, STAGE_CAP) || nch > ROUND0_HREG * nt) {
-        // too much for these blocks: the first block queues the prefix for the tail kernel
-        if (j != 0) return;
-        const float nxtU = nxt ? ckey_bound(nxt) : -INFINITY;
-        const float T0 = seed_tail_mass(a, L, kappa, nxt, nxtU, s);
-        Tile* tl = a.tiles[0] + (size_t)b * a.tile_stride;
-        int ntile = 0;
-        for (int i = 0; i < m0; ++i) {
-            const int r0 = L.offl[scl[i]], p0 = spos[i], n = (i + 1 < m0 ? spos[i + 1] : rows) - p0;
-            const int ntc = (n + TILE_ROWS - 1) / TILE_ROWS;
-            for (int t = tid; t < ntc; t += nt) {
-                Tile x;
-                x.b = b; x.row0 = r0 + t * TILE_ROWS; x.nrows = min(TILE_ROWS, n - t * TILE_ROWS); x.pos = p0 + t * TILE_ROWS;
-                tl[ntile + t] = x;
-            }
-            ntile += ntc;
-        }
-        if (tid == 0) {
-            a.counters[CNT_TILES + b] = ntile;
-            a.counters[CNT_TAIL_NEEDED] = 1;
-            a.st[b] = seed_state(m0, rows, kappa, nxtU, T0);
-        }
-        return;
-    }
-
-    // h goes to its own LDS region behind the cluster data; the wave's first row is requested before the tail
-    // mass is summed, so that sum runs while the loads are in flight
+    float nxtU, T0;
     uint4* hs4 = reinterpret_cast<uint4*>(arena) + a.r0_h_off;
-#pragma unroll
-    for (int q = 0; q < ROUND0_HREG; ++q) {
-        const int i = tid + q * nt;
-        if (i < nch) hs4[i] = hreg[q];
-    }
     uint4 pf[TILE_PF];
     const uint4* w = nullptr;
     float bias = 0.f;
     int id = 0;
-    auto request = [&](int p) {
-        int lo = 0, hi = m0;   // largest i with spos[i] <= p
-        while (hi - lo > 1) {
-            const int mid = (lo + hi) >> 1;
-            if (spos[mid] <= p) lo = mid; else hi = mid;
-        }
-        const int r = L.offl[scl[lo]] + (p - spos[lo]);
+    auto request_row = [&](int r) {
         w = reinterpret_cast<const uint4*>(a.Wp + (size_t)r * a.d);
 #pragma unroll
         for (int q = 0; q < TILE_PF; ++q) {
@@ -1558,11 +1537,151 @@ __global__ __launch_bounds__(SEQ_THREADS) void round0_kernel(StepArgs a) {
         }
     };
     int p = wave * NB + j;   // neighbouring rows go to different compute units
-    if (p < rows) request(p);
-    const float nxtU = nxt ? ckey_bound(nxt) : -INFINITY;
-    const float T0 = seed_tail_mass(a, L, kappa, nxt, nxtU, s);
+    bool fast = false;
+    WaveSeed ws;
+    ws.row0 = 0;
+    if (C <= 64 * SEED_E && nch <= ROUND0_HREG * nt) {
+        // bounds, ln n and h to LDS with one barrier; then every wave picks the seed cluster by itself
+        float* sU = reinterpret_cast<float*>(arena);
+        float* sL = sU + C;
+        {
+            const float* Ub = a.U + (size_t)b * C;
+            float ru[2], rl[2];
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                const int c = tid + q * nt, cc = c < C ? c : 0;
+                ru[q] = Ub[cc];
+                rl[q] = a.lnn[cc];
+            }
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                const int c = tid + q * nt;
+                if (c < C) {
+                    sU[c] = ru[q];
+                    sL[c] = rl[q];
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < ROUND0_HREG; ++q) {
+                const int i = tid + q * nt;
+                if (i < nch) hs4[i] = hreg[q];
+            }
+        }
+        DBG_T(2);
+        __syncthreads();
+        DBG_T(3);
+        if (!isfinite(hn)) {
+            if (j == 0) write_invalid(a, b);
+            return j == 0;
+        }
+        wave_seed_pick(a, sU, sL, ws);
+        fast = ws.kappa != 0 && ws.rows >= need && ws.rows <= cap_rows && ws.rows <= a.K_max;
+        if (!fast) __syncthreads();          // every wave has read the staged bounds: the general path reuses the LDS
+    }
+    DBG_T(1);
+    if (fast) {
+        // the prefix is one cluster: the row first, then the next bound and the tail mass while it is in flight
+        m0 = 1; rows = ws.rows; kappa = ws.kappa;
+        if (p < rows) request_row(ws.row0 + p);
+        if (j == 0 && tid == 0) a.sel[(size_t)b * C] = ws.c;
+        DBG_T(7);
+        wave_seed_tail(a, ws, nxtU, T0);
+        DBG_T(8);
+    } else {
+        load_clusters(a, b, L);
+        if (!isfinite(hn)) {
+            if (j == 0) write_invalid(a, b);
+            return j == 0;
+        }
+        __syncthreads();
+        // Open clusters one at a time by block-wide arg-max until max(k,1) rows are open.  Every opened cluster has
+        // at least one row, so at most max(k,1) <= CSV_MAX_K clusters open: their ids and positions fit the k-sized
+        // arrays.  Nothing is written to global memory inside the loop (a store would be waited for at the next barrier).
+        while (true) {
+            // the best unopened cluster and the one after it, in one reduction: when the best completes the prefix,
+            // the runner-up is already the next unopened bound
+            Top2 t2{0ull, 0ull};
+            for (int c = tid; c < C; c += nt) {
+                const u64 kx = L.keys[c];
+                if (kx < kappa) t2 = top2_push(t2, kx);
+            }
+            t2 = block_top2(t2, s.redu);
+            if (t2.a == 0) {                   // nothing left to open
+                nxt = 0;
+                break;
+            }
+            const int cw = (int)(0xFFFFFFFFu - (uint32_t)t2.a);
+            if (tid == 0) {
+                scl[m0] = cw;
+                spos[m0] = rows;
+            }
+            rows += L.offl[cw + 1] - L.offl[cw];
+            m0 += 1;
+            kappa = t2.a;
+            if (rows >= need) {
+                nxt = t2.b;
+                break;
+            }
+        }
+        DBG_T(2);
+        if (rows > a.K_max) {
+            if (j == 0 && tid == 0) {
+                a.st[b].n_open = m0;
+                a.st[b].n_rows = rows;
+                push_fallback(a, b, 0);
+            }
+            return j == 0;
+        }
+        __syncthreads();   // scl / spos complete
+        if (j == 0)
+            for (int i = tid; i < m0; i += nt) a.sel[(size_t)b * C + i] = scl[i];
+        nxtU = nxt ? ckey_bound(nxt) : -INFINITY;
+        if (rows > cap_rows || nch > ROUND0_HREG * nt) {
+            // too much for these blocks: the first block queues the prefix for the tail
+            if (j != 0) return false;
+            T0 = seed_tail_mass(a, L, kappa, nxt, nxtU, s);
+            Tile* tl = a.tiles[0] + (size_t)b * a.tile_stride;
+            int ntile = 0;
+            for (int i = 0; i < m0; ++i) {
+                const int r0 = L.offl[scl[i]], p0 = spos[i], n = (i + 1 < m0 ? spos[i + 1] : rows) - p0;
+                const int ntc = (n + TILE_ROWS - 1) / TILE_ROWS;
+                for (int t = tid; t < ntc; t += nt) {
+                    Tile x;
+                    x.b = b; x.row0 = r0 + t * TILE_ROWS; x.nrows = min(TILE_ROWS, n - t * TILE_ROWS); x.pos = p0 + t * TILE_ROWS;
+                    tl[ntile + t] = x;
+                }
+                ntile += ntc;
+            }
+            if (tid == 0) {
+                a.counters[CNT_TILES + b] = ntile;
+                __hip_atomic_store(&a.counters[CNT_TAIL_NEEDED], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                a.st[b] = seed_state(m0, rows, kappa, nxtU, T0);
+            }
+            return true;
+        }
+        // h goes to its own LDS region behind the cluster data; the wave's first row is requested before the tail
+        // mass is summed, so that sum runs while the loads are in flight
+#pragma unroll
+        for (int q = 0; q < ROUND0_HREG; ++q) {
+            const int i = tid + q * nt;
+            if (i < nch) hs4[i] = hreg[q];
+        }
+    }
+    auto row_of = [&](int pp) {
+        if (fast) return ws.row0 + pp;
+        int lo = 0, hi = m0;   // largest i with spos[i] <= pp
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (spos[mid] <= pp) lo = mid; else hi = mid;
+        }
+        return L.offl[scl[lo]] + (pp - spos[lo]);
+    };
+    if (!fast) {
+        if (p < rows) request_row(row_of(p));
+        T0 = seed_tail_mass(a, L, kappa, nxt, nxtU, s);
+    }
     const SeqState st = seed_state(m0, rows, kappa, nxtU, T0);
-    __syncthreads();
+    if (!fast) __syncthreads();            // h staged (the fast path staged it before its barrier)
     DBG_T(4);
     while (p < rows) {
         float acc = 0.f;
@@ -1586,7 +1705,7 @@ __global__ __launch_bounds__(SEQ_THREADS) void round0_kernel(StepArgs a) {
             a.sid[(size_t)b * a.K_cap + p] = id;
         }
         p += GW;
-        if (p < rows) request(p);
+        if (p < rows) request_row(row_of(p));
     }
     DBG_T(5);
     // The block that arrives last at the sequence's counter goes on.  Thread 0 releases after the barrier has
@@ -1600,9 +1719,10 @@ __global__ __launch_bounds__(SEQ_THREADS) void round0_kernel(StepArgs a) {
     }
     __syncthreads();
     DBG_T(6);
-    if (!s.sel) return;
+    if (!s.sel) return false;
     if (tid == 0) a.st[b] = st;
     cert_body(a, b, 0, 0, st, s);
+    return true;
 }
 
 // ================================================================================================ full-vocabulary product
@@ -1897,16 +2017,14 @@ __device__ __forceinline__ bool grid_barrier(int* counters, int which, int nbloc
     return *s_flag != 0;
 }
 
-__global__ __launch_bounds__(TAIL_THREADS, 2) void tail_kernel(StepArgs a, FullArgs f, int fallback_only) {
+// block / nblocks: this block's position among the blocks that run the tail together (all resident).
+__device__ __forceinline__ void tail_device(const StepArgs& a, const FullArgs& f, int fallback_only, int block, int nblocks,
+                                            SeqShared& s, GemvShared& gs, int* s_flag) {
     extern __shared__ u64 arena[];
-    __shared__ SeqShared s;
-    __shared__ GemvShared gs;
-    __shared__ int s_flag;
     const int tid = threadIdx.x;
-    const int nblocks = gridDim.x, block = blockIdx.x;
     if (a.counters[CNT_TAIL_NEEDED] == 0) return;      // the common case at small batches: one word, no reduction
     if (fallback_only && a.counters[CNT_FALLBACK] == 0) return;
-    // is any sequence waiting for round 0 (a seed prefix too large for the round-0 kernel), for round 1 or for the
+    // is any sequence waiting for round 0 (a seed prefix too large for the round-0 blocks), for round 1 or for the
     // full product?  Every block reads the same, settled values.
     int mine0 = 0, mine1 = 0;
     if (tid < a.B) {
@@ -1921,7 +2039,7 @@ __global__ __launch_bounds__(TAIL_THREADS, 2) void tail_kernel(StepArgs a, FullA
     DBG_T(20);
 
     // Rounds: the GEMV over the round's work list, then the certification, which may plan the next round.
-    // Round 0 is here only for seed prefixes that the round-0 kernel handed over.
+    // Round 0 is here only for seed prefixes that the round-0 blocks handed over.
     for (int r = tiles0 > 0 ? 0 : 1; r < a.max_rounds && !fallback_only; ++r) {
         if (r > 0) {
             if (r > 1 || tiles0 > 0) {   // planned by a certification earlier in this kernel: read past the barrier
@@ -1932,7 +2050,7 @@ __global__ __launch_bounds__(TAIL_THREADS, 2) void tail_kernel(StepArgs a, FullA
         }
         gemv_tiles_device(a, r, reinterpret_cast<uint4*>(arena), gs, block, nblocks);
         if (r == 1) DBG_T(21);
-        if (!grid_barrier(a.counters, 2 * r, nblocks, &s_flag, a.spin_limit)) return;
+        if (!grid_barrier(a.counters, 2 * r, nblocks, s_flag, a.spin_limit)) return;
         if (r == 1) DBG_T(22);
         // chunk-major items: the first chunks of all sequences (often the only ones with work) go to distinct blocks
         for (int item = block; item < a.B * a.sp_chunks; item += nblocks) {
@@ -1940,7 +2058,7 @@ __global__ __launch_bounds__(TAIL_THREADS, 2) void tail_kernel(StepArgs a, FullA
             __syncthreads();
         }
         if (r == 1) DBG_T(23);
-        if (!grid_barrier(a.counters, 2 * r + 1, nblocks, &s_flag, a.spin_limit)) return;
+        if (!grid_barrier(a.counters, 2 * r + 1, nblocks, s_flag, a.spin_limit)) return;
         if (r == 1) DBG_T(24);
     }
     const int n_fb = __hip_atomic_load(&a.counters[CNT_FALLBACK], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
@@ -1950,20 +2068,80 @@ __global__ __launch_bounds__(TAIL_THREADS, 2) void tail_kernel(StepArgs a, FullA
     else
         full_gemv_device(f, n_fb, reinterpret_cast<uint4*>(arena), block, nblocks);
     if (block == 0) DBG_T(25);
-    if (!grid_barrier(a.counters, 2 * CSV_MAX_ROUNDS, nblocks, &s_flag, a.spin_limit)) return;
+    if (!grid_barrier(a.counters, 2 * CSV_MAX_ROUNDS, nblocks, s_flag, a.spin_limit)) return;
     if (block == 0) DBG_T(26);
     for (int item = block; item < n_fb * a.n_chunks; item += nblocks) {
         fb_topk_device(a, item / a.n_chunks, item % a.n_chunks, s);
         __syncthreads();
     }
     if (block == 0) DBG_T(27);
-    if (!grid_barrier(a.counters, 2 * CSV_MAX_ROUNDS + 1, nblocks, &s_flag, a.spin_limit)) return;
+    if (!grid_barrier(a.counters, 2 * CSV_MAX_ROUNDS + 1, nblocks, s_flag, a.spin_limit)) return;
     if (block == 0) DBG_T(28);
     for (int slot = block; slot < n_fb; slot += nblocks) {
         fb_final_device(a, slot, s);
         __syncthreads();
     }
     if (block == 0) DBG_T(29);
+}
+
+__global__ __launch_bounds__(TAIL_THREADS, 2) void tail_kernel(StepArgs a, FullArgs f, int fallback_only) {
+    __shared__ SeqShared s;
+    __shared__ GemvShared gs;
+    __shared__ int s_flag;
+    tail_device(a, f, fallback_only, blockIdx.x, gridDim.x, s, gs, &s_flag);
+}
+
+// ------------------------------------------------------------------------------------------------ round 0 as a launch
+// Plain form, grid NB x B: round 0 only; what follows is launched separately.
+__global__ __launch_bounds__(SEQ_THREADS) void round0_kernel(StepArgs a, int NB) {
+    __shared__ SeqShared s;
+    round0_device(a, blockIdx.x / NB, blockIdx.x % NB, NB, s);
+}
+
+// Fused form, used while recent steps rarely needed anything after round 0: the first NB x B blocks run round 0,
+// the remaining blocks are the tail's blocks, parked until every sequence's round 0 is settled.  When nothing is
+// queued for them (the common case) they leave at once: the step has saved a kernel launch.  Otherwise they run the
+// tail exactly as tail_kernel does (the round-0 blocks have left by then; the tail's blocks are all resident: the
+// host sizes the grid for one block per compute unit).  Blocks start in index order, so the blocks waited for are
+// already running when a parked block starts; the wait is bounded all the same (the poll limit of the grid barriers).
+__global__ __launch_bounds__(SEQ_THREADS) void step_kernel(StepArgs a, FullArgs f, int NB) {
+    __shared__ SeqShared s;
+    __shared__ GemvShared gs;
+    __shared__ int s_flag;
+    const int n0 = NB * a.B;
+    if ((int)blockIdx.x < n0) {
+        const int b = blockIdx.x / NB;
+        const bool settled = round0_device(a, b, blockIdx.x % NB, NB, s);
+        if (!settled) return;
+        __syncthreads();                      // all of the block's writes are issued
+        if (threadIdx.x == 0) {
+            // Thread 0 wrote the sequence's status itself.  Anything but "done" means something was queued for the
+            // tail's blocks (a work list, a fallback): release it before the count.  A finished sequence left
+            // nothing for them to read.
+            if (a.st[b].status != ST_DONE) __threadfence();
+            atomicAdd(&a.counters[CNT_R0_DONE], 1);
+        }
+        return;
+    }
+    if (threadIdx.x == 0) {
+        int ok = 1, spins = 0;
+        while (__hip_atomic_load(&a.counters[CNT_R0_DONE], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < a.B) {
+            if (++spins > a.spin_limit) {
+                atomicExch(&a.counters[CNT_ABORT], 1);
+                ok = 0;
+                break;
+            }
+            __builtin_amdgcn_s_sleep(8);
+        }
+        // Whoever queued work set this word before its release and its count; the loads of this thread are performed
+        // in order, so a zero read here, after the full count, means that nobody did: leave without an acquire.
+        if (ok && __hip_atomic_load(&a.counters[CNT_TAIL_NEEDED], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0) ok = 0;
+        if (ok) __threadfence();              // acquire
+        s_flag = ok;
+    }
+    __syncthreads();
+    if (!s_flag) return;
+    tail_device(a, f, 0, (int)blockIdx.x - n0, (int)gridDim.x - n0, s, gs, &s_flag);
 }
 
 // ------------------------------------------------------------------------------------------------ the tail, one launch per phase
@@ -2038,7 +2216,7 @@ static void fill_args(StepArgs& a, const csv_workspace* ws, const csv_index* idx
     memset(&a, 0, sizeof(a));
     a.V = idx->V; a.d = idx->d; a.C = idx->C;
     a.Wp = idx->Wp; a.bp = idx->bp; a.perm = idx->perm; a.mu = idx->mu; a.mu16 = idx->mu16; a.R = idx->R; a.bmax = idx->bmax;
-    a.n = idx->n; a.off = idx->off; a.lnn = idx->lnn; a.ln_nmax = idx->ln_nmax;
+    a.n = idx->n; a.off = idx->off; a.lnn = idx->lnn; a.cmeta = idx->cmeta; a.ln_nmax = idx->ln_nmax;
     a.K_cap = ws->K_cap; a.Npad = ws->Npad; a.n_chunks = ws->n_chunks; a.tile_stride = ws->tile_stride; a.sp_chunks = ws->sp_chunks; a.cand_chunks = ws->cand_chunks;
     a.U = ws->U; a.hnorm = ws->hnorm; a.bound_partial = ws->bound_partial; a.st = ws->st; a.sel = ws->sel; a.slog = ws->slog; a.sid = ws->sid;
     a.tiles[0] = ws->tiles[0]; a.tiles[1] = ws->tiles[1]; a.counters = ws->counters;
@@ -2165,6 +2343,24 @@ static int launch_full(const csv_index* idx, const uint16_t* d_h, const int32_t*
     return CSV_OK;
 }
 
+// The dynamic-LDS limit of a kernel is one attribute per process and device, shared by every workspace: it is only
+// ever raised, so a workspace created later with smaller needs cannot take away what an earlier one's launches rely on.
+enum { K_ROUND0, K_STEP, K_TAIL, K_RCERT, K_FBPROD, K_FULLMFMA, K_NKERN };
+static size_t g_lds_limit[CSV_STATIC_MAX_DEVICES][K_NKERN];
+static pthread_mutex_t g_attr_lock = PTHREAD_MUTEX_INITIALIZER;
+#define CSV_STATIC_LDS_MAX 16384     // at least the static shared memory of any kernel here
+static hipError_t raise_lds(int dev, int which, const void* fn, size_t bytes) {
+    if (dev < 0 || dev >= CSV_STATIC_MAX_DEVICES) return hipErrorInvalidDevice;
+    hipError_t e = hipSuccess;
+    pthread_mutex_lock(&g_attr_lock);
+    if (bytes > g_lds_limit[dev][which]) {
+        if (bytes + CSV_STATIC_LDS_MAX > 65536) e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+        if (e == hipSuccess) g_lds_limit[dev][which] = bytes;
+    }
+    pthread_mutex_unlock(&g_attr_lock);
+    return e;
+}
+
 extern "C" int csv_workspace_create(const csv_index* idx, int B_max, int K_cap_rows, csv_workspace** out) {
     if (out) *out = nullptr;
     if (!idx || !out) { csv_set_error("null index or out"); return CSV_EINVAL; }
@@ -2206,10 +2402,8 @@ extern "C" int csv_workspace_create(const csv_index* idx, int B_max, int K_cap_r
         free(tmp);
     }
     // the per-sequence kernels may need more dynamic LDS than the default limit when C is large
-    if (e == hipSuccess)
-        e = hipFuncSetAttribute((const void*)full_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, MFMA_LDS);
-    if (e == hipSuccess && round0_lds(ws) + sizeof(SeqShared) > 65536)
-        e = hipFuncSetAttribute((const void*)round0_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)round0_lds(ws));
+    if (e == hipSuccess) e = raise_lds(ws->device, K_FULLMFMA, (const void*)full_mfma_kernel, MFMA_LDS);
+    if (e == hipSuccess) e = raise_lds(ws->device, K_ROUND0, (const void*)round0_kernel, round0_lds(ws));
     if (e == hipSuccess) {
         size_t l = cert_lds(ws);
         // more than FULL_G fallback sequences go through the MFMA product, whose h fragments want a large LDS chunk
@@ -2217,8 +2411,7 @@ extern "C" int csv_workspace_create(const csv_index* idx, int B_max, int K_cap_r
                                B_max > FULL_G ? (size_t)MFMA_LDS : 0};
         for (size_t c : cand) l = c > l ? c : l;
         ws->tail_lds = l;
-        if (l + sizeof(SeqShared) + sizeof(GemvShared) + 64 > 65536)
-            e = hipFuncSetAttribute((const void*)tail_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)l);
+        e = raise_lds(ws->device, K_TAIL, (const void*)tail_kernel, l);
         int per_cu = 0, dev = 0, cus = 0;
         if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, tail_kernel, TAIL_THREADS, l);
         if (e == hipSuccess) e = hipGetDevice(&dev);
@@ -2234,10 +2427,8 @@ extern "C" int csv_workspace_create(const csv_index* idx, int B_max, int K_cap_r
         ws->tail_grid = cus;
         ws->spin_limit = TAIL_SPIN_LIMIT;
         ws->split_min_B = 0;      // decided per step from the history
-        if (e == hipSuccess && cert_lds(ws) + sizeof(SeqShared) > 65536)
-            e = hipFuncSetAttribute((const void*)round_cert_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)cert_lds(ws));
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute((const void*)fb_product_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, MFMA_LDS);
+        if (e == hipSuccess) e = raise_lds(ws->device, K_RCERT, (const void*)round_cert_kernel, cert_lds(ws));
+        if (e == hipSuccess) e = raise_lds(ws->device, K_FBPROD, (const void*)fb_product_kernel, MFMA_LDS);
         int r0_per_cu = 0;
         if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&r0_per_cu, round0_kernel, SEQ_THREADS, round0_lds(ws));
         if (e == hipSuccess && r0_per_cu < 1) {
@@ -2246,6 +2437,12 @@ extern "C" int csv_workspace_create(const csv_index* idx, int B_max, int K_cap_r
             return CSV_ESHAPE;
         }
         ws->round0_capacity = r0_per_cu * cus;
+        // round 0 and the tail in one launch: every block of that grid (one per compute unit) must be resident
+        ws->fused_lds = round0_lds(ws) > l ? round0_lds(ws) : l;
+        int fused_per_cu = 0;
+        if (e == hipSuccess) e = raise_lds(ws->device, K_STEP, (const void*)step_kernel, ws->fused_lds);
+        if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&fused_per_cu, step_kernel, SEQ_THREADS, ws->fused_lds);
+        ws->fused_ok = fused_per_cu >= 1;
     }
     if (e != hipSuccess) {
         csv_set_error("workspace allocation failed: %s", hipGetErrorString(e));
@@ -2283,7 +2480,6 @@ extern "C" int csv_bounds(csv_workspace* ws, const csv_index* idx, const uint16_
 // bound kernels use) live in a file-scope device array instead of a workspace buffer.  Every GPU holds its own copy
 // of the array at its own address; the address is looked up once per device and handed to the kernels as an argument.
 #define CSV_STATIC_SCRATCH_BYTES (8u << 20)
-#define CSV_STATIC_MAX_DEVICES 64
 static __device__ __align__(256) unsigned char scratch[CSV_STATIC_SCRATCH_BYTES];
 static void* g_scratch_ptr[CSV_STATIC_MAX_DEVICES];          // per device: address of `scratch` there (NULL = not looked up yet)
 static pthread_mutex_t g_scratch_lock = PTHREAD_MUTEX_INITIALIZER;
@@ -2384,36 +2580,46 @@ extern "C" int csv_decode_step(csv_workspace* ws, const csv_index* idx, const ui
     rc = launch_bounds_kernel(a, ws->U, ws->hnorm, 1, st);
     if (rc) return rc;
     CSV_MARK(1);
-    int nb = 1;
+    FullArgs f;
+    f.V = idx->V; f.d = idx->d; f.Wp = idx->Wp; f.bp = idx->bp; f.perm = idx->perm; f.h = d_h;
+    f.list = ws->fb_list; f.n_ptr = nullptr; f.n_fixed = 0; f.out = ws->fb_logits; f.out_stride = idx->V; f.scatter = 0;
+    // One launch per phase pays when the tail is needed (kernel boundaries instead of grid barriers: 30 % of a
+    // step even at B = 1), the single kernel when it is not (one launch that returns at once instead of seven).
+    // Unless the caller fixed the choice, follow the recent steps: the bound kernel keeps a bit per step in a
+    // pinned host word, read here without synchronising (it may lag a few steps; either choice is correct).
+    bool split, fb_launches = true;
+    const unsigned history = (unsigned)*(volatile int*)ws->h_history;
+    if (ws->split_min_B > 0) {
+        split = B >= ws->split_min_B;
+    } else {
+        split = __builtin_popcount(history & 0xffu) >= 2;
+        // the three fallback phases as launches of their own only while fallbacks occur; otherwise one launch
+        // of the single kernel restricted to them, which returns at once when nobody fell back
+        fb_launches = ((history >> 16) & 0xffu) != 0;
+    }
+    // blocks per sequence in round 0: as many as stay resident together (a second wave of blocks would double the
+    // kernel's time), at most ROUND0_NB_MAX, and no more than one wave per row of the largest possible seed prefix
+    // (max(k,1) - 1 rows before its last cluster plus that cluster)
+    const long long prefix_max = (long long)(p->k > 1 ? p->k : 1) - 1 + idx->n_max;
+    int nb = ws->round0_capacity / B;
+    nb = nb < 1 ? 1 : (nb > ROUND0_NB_MAX ? ROUND0_NB_MAX : nb);
     {
-        // blocks per sequence: enough waves that a typical seed prefix (one or two clusters) is one row per wave
-        // as many as stay resident together (a second wave of blocks would double the kernel's time), at most 32
-        nb = ws->round0_capacity / B;
-        nb = nb < 1 ? 1 : (nb > ROUND0_NB_MAX ? ROUND0_NB_MAX : nb);
-        round0_kernel<<<dim3(nb, B), SEQ_THREADS, round0_lds(ws), st>>>(a);
+        const long long want = (prefix_max + (SEQ_THREADS / 64) - 1) / (SEQ_THREADS / 64);
+        if (want < nb) nb = (int)(want < 1 ? 1 : want);
+    }
+    // the tail's blocks ride in the round-0 launch when they all fit next to the round-0 blocks (one block per unit)
+    const bool fused = !split && ws->fused_ok && nb * B * 2 <= ws->tail_grid;
+    if (fused) {
+        step_kernel<<<ws->tail_grid, SEQ_THREADS, ws->fused_lds, st>>>(a, f, nb);
+        CSV_LAUNCH_CHECK("step_kernel");
+    } else {
+        round0_kernel<<<nb * B, SEQ_THREADS, round0_lds(ws), st>>>(a, nb);
         CSV_LAUNCH_CHECK("round0_kernel");
     }
     CSV_MARK(2);
-    {
-        FullArgs f;
-        f.V = idx->V; f.d = idx->d; f.Wp = idx->Wp; f.bp = idx->bp; f.perm = idx->perm; f.h = d_h;
-        f.list = ws->fb_list; f.n_ptr = nullptr; f.n_fixed = 0; f.out = ws->fb_logits; f.out_stride = idx->V; f.scatter = 0;
-        // One launch per phase pays when the tail is needed (kernel boundaries instead of grid barriers: 30 % of a
-        // step even at B = 1), the single kernel when it is not (one launch that returns at once instead of seven).
-        // Unless the caller fixed the choice, follow the recent steps: the bound kernel keeps a bit per step in a
-        // pinned host word, read here without synchronising (it may lag a few steps; either choice is correct).
-        bool split, fb_launches = true;
-        const unsigned history = (unsigned)*(volatile int*)ws->h_history;
-        if (ws->split_min_B > 0) {
-            split = B >= ws->split_min_B;
-        } else {
-            split = __builtin_popcount(history & 0xffu) >= 2;
-            // the three fallback phases as launches of their own only while fallbacks occur; otherwise one launch
-            // of the single kernel restricted to them, which returns at once when nobody fell back
-            fb_launches = ((history >> 16) & 0xffu) != 0;
-        }
+    if (!fused) {
         if (!split) {
-            // small batches: one launch that returns at once when no sequence needs it
+            // one launch that returns at once when no sequence needs it
             tail_kernel<<<ws->tail_grid, TAIL_THREADS, ws->tail_lds, st>>>(a, f, 0);
             CSV_LAUNCH_CHECK("tail_kernel");
         } else {
@@ -2421,7 +2627,6 @@ extern "C" int csv_decode_step(csv_workspace* ws, const csv_index* idx, const ui
             // Round 0 appears here only for seed prefixes that the round-0 kernel hands over.  A prefix holds fewer
             // than max(k,1) rows before its last cluster, so with small clusters that cannot happen: no launches.
             const long long cap = (long long)nb * (SEQ_THREADS / 64) * ROUND0_ROWS_PER_WAVE;
-            const long long prefix_max = (long long)(p->k > 1 ? p->k : 1) - 1 + idx->n_max;
             const bool may_hand_over = prefix_max > (cap < STAGE_CAP ? cap : STAGE_CAP) || (idx->d >> 3) > ROUND0_HREG * SEQ_THREADS;
             for (int r = may_hand_over ? 0 : 1; r < max_rounds; ++r) {
                 round_gemv_kernel<<<ws->tail_grid, TAIL_THREADS, hl, st>>>(a, r);   // more blocks measured slower

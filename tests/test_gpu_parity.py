@@ -20,10 +20,12 @@ pytestmark = pytest.mark.gpu
 torch = pytest.importorskip("torch")
 
 
-def _finish(t: PAR.Tally, tag: str, max_band_frac=0.2):
+def _finish(t: PAR.Tally, tag: str, max_band_frac=0.01):
+    """No mismatch, and at most 1 % (+1) of the (step, sequence) pairs may have needed the tie band at all: on the
+    synthetic workloads the measured number of in-band decisions is 0, so a larger share would itself be a finding."""
     log(f"[{tag}] {t.summary()}")
     assert not t.mismatch, "\n".join(t.mismatch[:10])
-    assert t.inband <= max_band_frac * t.n + 2, f"too many in-band cases: {t.summary()}"
+    assert t.inband <= max_band_frac * t.n + 1, f"too many in-band cases: {t.summary()}"
 
 
 # ------------------------------------------------------------------ per-kernel parity
@@ -220,6 +222,8 @@ def test_step_single_cluster_and_singletons():
     r = synth.small_recipe("CV", V=512, d=64, C=8, B=2, steps=2)
     case = Case(r, seed=15, labels=np.arange(512), K_cap=512, radius_slack=0.0)
     t = case.run_steps(case.hidden(), 5, 1e-3, 512, O.COMBINE_ALL, "C=V", )
+    # one cluster per token and no radius slack: every bound EQUALS its logit, so the strict top-k test sits exactly
+    # on its tie (float64 and float32 evaluate the same two numbers): the one place where any share may be in band
     _finish(t, "C=V", max_band_frac=1.0)
     case.close()
 
@@ -249,7 +253,7 @@ def test_step_seeded_random_shapes_and_parameters():
         t = case.run_steps(case.hidden(), k, eps, K_max, comb, tag, tally=total, **lad)
         assert not t.mismatch, tag + "\n" + "\n".join(t.mismatch[:5])
         case.close()
-    _finish(total, "seeded random cases", max_band_frac=0.3)
+    _finish(total, "seeded random cases")
 
 
 def test_adaptive_budget_in_the_decode_loop():
@@ -417,8 +421,8 @@ def test_step_invalid_hidden_state_is_flagged():
 
 
 def test_barrier_timeout_gives_the_step_up_cleanly():
-    # Error path of the device-side waits, forced from the host: with a poll limit of 1 the grid barriers of the
-    # tail kernel run out, every block leaves, unfinished sequences keep INVALID_INPUT; the next step is clean.
+    # Error path of the device-side waits, forced from the host: with a poll limit of 1 the waits of the tail's blocks
+    # run out, every block leaves, unfinished sequences carry ABORTED (not INVALID_INPUT: h was fine); the next step is clean.
     r = synth.small_recipe("abort", V=4000, d=256, C=32, B=5, steps=6, iso_frac=0.3, h_mode="mix")
     case = Case(r, seed=11)
     csv = case.csv
@@ -442,7 +446,7 @@ def test_barrier_timeout_gives_the_step_up_cleanly():
     n_invalid = 0
     for (fl0, id0, _), (fl1, id1, _) in zip(ref, cut):
         for b in range(r.B):
-            if fl1[b] == csv.FLAG_INVALID_INPUT:
+            if fl1[b] == csv.FLAG_ABORTED:
                 n_invalid += 1
             else:
                 assert fl1[b] == fl0[b] and np.array_equal(id1[b], id0[b])
@@ -520,8 +524,107 @@ def test_build_index_kmeans_matches_oracle_lloyd():
     g.free(); case.close()
 
 
+# ------------------------------------------------------------------ top-p (nucleus) certificate, delta form
+def test_nucleus_certificate_on_the_gpu():
+    # Section III, top-p certification: a step run with eps = delta / (1 + delta) carries the coverage certificate.
+    # The flag the kernels return is compared with the delta-form written out by the oracle on the set the GPU opened,
+    # and a certified step's opened rows must hold all but delta / (1 + delta) of the full-vocabulary softmax mass.
+    r = synth.small_recipe("nucleus", V=6000, d=136, C=60, B=4, steps=10, k=8, eps=1e-3, h_mode="mix", sizes="zipf",
+                           row_noise=0.6, iso_frac=0.1)
+    case = Case(r, seed=71, K_cap=6000)
+    csv = case.csv
+    h = case.hidden()
+    dh = csv.bits_to_device(h)
+    certified = failed = 0
+    for delta in (1e-3, 1e-2, 0.25):
+        eps = O.nucleus_eps(delta)
+        assert math.isclose(math.log(eps / (1 - eps)), math.log(delta), rel_tol=1e-12)
+        for k, comb in ((0, O.COMBINE_ALL), (r.k, O.COMBINE_ANY)):
+            t = case.run_steps(h, k, eps, 1500, comb, f"nucleus delta={delta:g} k={k}")
+            _finish(t, f"nucleus delta={delta:g} k={k}")
+            buf = csv.make_step_buffers(case.gidx, r.B, k, eps, 1500, comb, want_sel=True)
+            for s in range(h.shape[0]):
+                csv.csv_decode_step(case.ws, case.gidx, dh[s], buf)
+                torch.cuda.synchronize()
+                g = PAR.gpu_step_to_numpy(buf)
+                h64 = O.bf16_to_f64(h[s])
+                L = O.full_logits(case.W64, case.b, h64)
+                U, _ = O.cluster_bounds(case.oidx, h64)
+                for b in range(r.B):
+                    fl = int(g["flags"][b])
+                    if fl & O.FLAG_FALLBACK:
+                        continue
+                    sel = g["sel"][b][:int(g["n_clusters"][b])]
+                    rows = np.concatenate([case.oidx.rows(c) for c in sel])
+                    Z_S = O.logsumexp(L[b][rows])
+                    holds = O.nucleus_holds(case.oidx, U[b], sel, Z_S, delta)
+                    inS = np.zeros(r.V, bool); inS[rows] = True
+                    outside = float(np.exp(L[b][~inS] - O.logsumexp(L[b])).sum())
+                    # how far the delta-form is from its threshold: a flag may differ from the float64 statement only there
+                    mask = np.ones(case.oidx.C, bool); mask[sel] = False; mask &= case.oidx.n > 0
+                    slack = abs(O.logsumexp(np.log(case.oidx.n[mask]) + U[b][mask]) - math.log(delta) - Z_S) if mask.any() else math.inf
+                    if fl & O.FLAG_SOFTMAX_CERT:
+                        certified += 1
+                        assert holds or slack < 1e-4, (delta, s, b)
+                        assert outside <= delta / (1 + delta) * (1 + 1e-6), (delta, s, b, outside)
+                    else:
+                        failed += 1
+                        assert not holds or slack < 1e-4, (delta, s, b)
+    log(f"[nucleus] certified {certified}, not certified {failed}")
+    assert certified > 50
+    case.close()
+
+
+# ------------------------------------------------------------------ what the bench runs: index built on the GPU, full size
+def test_c2_index_built_on_the_gpu_and_steps_on_it():
+    # bench.py and smoke() build their index with csv_build_index from the planted labels; here that index is
+    # compared with the oracle's at full size and then drives 64 steps that are compared as usual
+    r = synth.CONFIGS["c2"]
+    case = Case(r)
+    csv = case.csv
+    g = csv.csv_build_index(case.dW, case.db, r.C, init_labels=case.labels.astype(np.int32), iters=0)
+    e = g.export()
+    o = case.oidx
+    assert np.array_equal(e["n"], o.n) and np.array_equal(e["perm"], o.perm) and np.array_equal(e["bmax"], o.bmax)
+    ulp_mu = np.abs(e["mu"].view(np.int32).astype(np.int64) - o.mu.view(np.int32).astype(np.int64))
+    ulp_R = np.abs(e["R"].view(np.int32).astype(np.int64) - o.R.view(np.int32).astype(np.int64))
+    log(f"  c2 index: centroid ulp diff max {ulp_mu.max()}, exact {np.mean(ulp_mu == 0):.6f}; radius ulp diff max {ulp_R.max()}")
+    assert ulp_mu.max() <= 1 and ulp_R.max() <= 2
+    # Cauchy-Schwarz needs the stored radius to cover every member's distance to the STORED centroid (Eq. "cluster_bound")
+    W = case.W64
+    for c in range(0, r.C, 37):
+        rows = o.rows(c)
+        dist = np.sqrt(((W[rows] - e["mu"][c].astype(np.float64)) ** 2).sum(1))
+        assert float(e["R"][c]) >= dist.max(), c
+    ws = csv.CsvWorkspace(g, r.B, r.K_max_rows)
+    h = case.hidden(steps=64)
+    dh = csv.bits_to_device(h)
+    buf = csv.make_step_buffers(g, r.B, r.k, r.eps, r.K_max_rows, want_sel=True)
+    t = PAR.Tally()
+    outs = []
+    for s in range(64):
+        csv.csv_decode_step(ws, g, dh[s], buf)
+        torch.cuda.synchronize()
+        outs.append(PAR.gpu_step_to_numpy(buf))
+    Lall = O.full_logits(case.W64, case.b, O.bf16_to_f64(h.reshape(-1, r.d))).reshape(64, r.B, -1)
+    for s in range(64):
+        orc = O.decode_step(case.W64, case.b, o, h[s], r.k, r.eps, r.K_max_rows, O.COMBINE_ALL, logits=Lall[s])
+        PAR.compare_step(f"c2 gpu-built step={s}", t, orc, outs[s], Lall[s], o, r.k, r.eps, r.K_max_rows, O.COMBINE_ALL)
+    _finish(t, "c2 on the GPU-built index")
+    assert t.fallbacks == 0
+    # full-vocabulary logits, every element, vector path (1 sequence) and MFMA path (8 and 40 sequences)
+    for B in (1, 8, 40):
+        hb = h[:B, 0, :]
+        Lg = csv.csv_full_logits(csv.CsvWorkspace(g, B, 1), g, csv.bits_to_device(hb)).cpu().numpy()
+        L = O.full_logits(case.W64, case.b, O.bf16_to_f64(hb))
+        err = np.abs(Lg - L) / np.maximum(1.0, np.abs(L))
+        log(f"  c2 full logits B={B}: max rel err {err.max():.2e}")
+        assert Lg.shape == (B, r.V) and err.max() < PAR.LOGIT_TIGHT
+    ws.free(); g.free(); case.close()
+
+
 # ------------------------------------------------------------------ the five configurations
-def _run_config(name, step_ids, max_band_frac, levels_step_ids=None, centroid_bf16=False):
+def _run_config(name, step_ids, max_band_frac=0.01, levels_step_ids=None, centroid_bf16=False):
     r = synth.CONFIGS[name]
     case = Case(r, centroid_bf16=centroid_bf16)
     h = case.hidden()
@@ -537,29 +640,29 @@ def _run_config(name, step_ids, max_band_frac, levels_step_ids=None, centroid_bf
 
 
 def test_config_c1_all_steps():
-    t = _run_config("c1", range(64), 0.05)
+    t = _run_config("c1", range(64))
     assert t.fallbacks == 0 and t.rows == 125 * 64
 
 
 def test_config_c2_all_steps():
-    t = _run_config("c2", range(512), 0.05)
+    t = _run_config("c2", range(512))
     assert t.fallbacks == 0
 
 
 def test_config_c3_sampled_steps():
-    t = _run_config("c3", range(0, 256, 4), 0.3, levels_step_ids=range(0, 256, 8))
+    t = _run_config("c3", range(0, 256, 4), levels_step_ids=range(0, 256, 8))
     assert t.levels.late_rounds > 0          # the levels are exercised at full size
 
 
 def test_config_c2_bf16_centroids_sampled_steps():
-    t = _run_config("c2", range(0, 512, 8), 0.05, centroid_bf16=True)
+    t = _run_config("c2", range(0, 512, 8), centroid_bf16=True)
     assert t.fallbacks == 0
 
 
 def test_config_c4_sampled_steps():
-    _run_config("c4", range(0, 128, 8), 0.5)
+    _run_config("c4", range(0, 128, 8))
 
 
 def test_config_c5_sampled_steps():
-    t = _run_config("c5", range(0, 128, 16), 0.1)
+    t = _run_config("c5", range(0, 128, 16))
     assert 0.1 < t.fallbacks / t.n < 0.45
