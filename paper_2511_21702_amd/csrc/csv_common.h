@@ -43,7 +43,10 @@ enum { ST_ACTIVE = 0, ST_DONE = 1, ST_FALLBACK = 2, ST_INVALID = 3 };
 enum { CNT_FALLBACK = 0, CNT_ABORT = 1, CNT_TAIL_NEEDED = 2, CNT_R0_DONE = 3, CNT_BARRIER = 16, CNT_TILES = 64, CNT_CHUNKS = 64 + CSV_MAX_ROUNDS * CSV_MAX_BATCH,
        CNT_ARRIVE = 64 + 2 * CSV_MAX_ROUNDS * CSV_MAX_BATCH, CNT_TOTAL = 64 + (2 * CSV_MAX_ROUNDS + 1) * CSV_MAX_BATCH,
        // not reset: bit i = whether the step i steps back needed anything after round 0 (kept behind the reset range)
-       CNT_HISTORY = CNT_TOTAL, CNT_ALLOC = CNT_TOTAL + 16 };
+       CNT_HISTORY = CNT_TOTAL,
+       // not reset either: set when a step gave up while logits were still on their way through the round-0 slots
+       // (the next step's bound kernel then refills the slots with the "empty" pattern before anything reads them)
+       CNT_SLOTS_DIRTY = CNT_TOTAL + 1, CNT_ALLOC = CNT_TOTAL + 16 };
 
 // A cluster's position in the bound order is carried by one 64-bit key: monotone image of U_c in the high word,
 // ~c in the low word.  Larger key = larger bound, equal bounds = smaller cluster id first.  Empty clusters have key 0.
@@ -64,6 +67,9 @@ struct SeqState {
 struct Tile {
     int b, row0, nrows, pos;
 };
+
+#define CSV_SLOT_ROWS 4096    // seed rows a sequence can pass through the round-0 slots (= rows one block certifies from LDS)
+#define CSV_SLOT_EMPTY 0xFFFFFFFFFFFFFFFFull
 
 struct csv_workspace {
     int B_max, K_cap, V, d, C, Npad;   // Npad: C rounded up to a power of two (sort width)
@@ -87,6 +93,7 @@ struct csv_workspace {
     SeqState* st;      // [B]
     int32_t* sel;      // [B*C]      opened cluster ids
     float* slog;       // [B*K_cap]  logits of opened rows
+    unsigned long long* slots; // [B*CSV_SLOT_ROWS] round 0: one (token id, logit) word per seed row, "empty" = all ones
     int32_t* sid;      // [B*K_cap]  their original token ids
     Tile* tiles[2];    // work lists of round 0 / round 1
     int32_t* counters; // [CNT_TOTAL]

@@ -32,6 +32,8 @@ void csv_set_error(const char* fmt, ...) {
 }
 extern "C" const char* csv_last_error(void) { return g_err; }
 
+typedef unsigned long long u64;
+
 // ------------------------------------------------------------------------------------------------ arguments
 struct StepArgs {
     int V, d, C;
@@ -47,7 +49,7 @@ struct StepArgs {
     const float* lnn;
     const int4* cmeta;      // per cluster {first row, rows, bits of ln n, 0}
     float ln_nmax;
-    int B, K_cap, Npad, n_chunks, tile_stride;
+    int B, B_max, K_cap, Npad, n_chunks, tile_stride;
     int sp_chunks;     // most STAGE_CAP-sized chunks a sequence's scored rows can span
     int cand_chunks;   // chunk stride of the candidate buffers
     int tail_lds;      // dynamic LDS bytes of the tail kernel
@@ -61,6 +63,7 @@ struct StepArgs {
     int32_t* sel;
     float* slog;
     int32_t* sid;
+    u64* slots;        // [B*CSV_SLOT_ROWS] round-0 hand-over words
     Tile* tiles[2];
     int32_t* counters;
     int32_t* fb_list;
@@ -89,11 +92,11 @@ struct StepArgs {
 #define TILE_ROWS 8        // rows per work item of the gathered GEMV (4 waves x 2 rows)
 #define SEQ_THREADS 512    // block size of the per-sequence kernels (seed, cert, fallback top-k)
 #define STAGE_CAP 4096     // scored logits kept in LDS by cert_kernel when a sequence has at most this many
+static_assert(STAGE_CAP == CSV_SLOT_ROWS, "the round-0 slots hold exactly what one block certifies from LDS");
 #define FB_CHUNK 8192      // rows per block of the fallback top-k first stage
 #define FULL_G 4           // sequences per pass of the vector full-vocabulary product
 #define BIGQ 32            // clusters whose tiles are written cooperatively per emit call
 
-typedef unsigned long long u64;
 #define CSV_STATIC_MAX_DEVICES 64   // devices the per-device host tables of this file cover
 
 // Key of a value for ordering: -0 and +0 compare equal.
@@ -104,8 +107,13 @@ __device__ __forceinline__ float ckey_bound(u64 k) { return fkey_inv((uint32_t)(
 // Zero the step's counters: the fixed slots and, of every per-sequence row, the entries of the B sequences in use.
 // Before that, whether the previous step needed anything after round 0 is shifted into the history word (device
 // copy behind the reset range, and a pinned host copy that the next calls read without synchronising).
-__device__ __forceinline__ void reset_step_counters(int* counters, int B, int nthreads, int* host_history) {
+__device__ __forceinline__ void reset_step_counters(int* counters, int B, int nthreads, int* host_history, u64* slots, int B_max) {
     constexpr int rows = (CNT_TOTAL - CNT_TILES) / CSV_MAX_BATCH;
+    if (counters[CNT_SLOTS_DIRTY] != 0) {     // an earlier step gave up with logits still on their way: empty every slot
+        for (size_t i = threadIdx.x; i < (size_t)B_max * CSV_SLOT_ROWS; i += nthreads) slots[i] = CSV_SLOT_EMPTY;
+        __syncthreads();
+        if (threadIdx.x == 0) counters[CNT_SLOTS_DIRTY] = 0;
+    }
     if (threadIdx.x == 0) {      // low half: steps that needed the tail; high half: steps with a fallback
         const unsigned old = (unsigned)counters[CNT_HISTORY];
         const unsigned lo = ((old << 1) | (unsigned)(counters[CNT_TAIL_NEEDED] != 0)) & 0xffffu;
@@ -200,7 +208,7 @@ __global__ __launch_bounds__(BOUND_THREADS) void bound_kernel(StepArgs a, float*
         if (i < BT * nch) hs4[i] = hreg[q];
     }
     if (reset_counters && blockIdx.x == 0 && blockIdx.y == 0)
-        reset_step_counters(a.counters, a.B, BOUND_THREADS, a.host_history);
+        reset_step_counters(a.counters, a.B, BOUND_THREADS, a.host_history, a.slots, a.B_max);
     __syncthreads();
     for (int s = wave; s < BT; s += BOUND_THREADS / 64) {
         float acc = 0.f;
@@ -296,7 +304,7 @@ __global__ __launch_bounds__(BOUND_THREADS) void bound1_kernel(StepArgs a, float
         ncl = a.n[c];
     }
     if (reset_counters && blockIdx.x == 0)
-        reset_step_counters(a.counters, a.B, BOUND_THREADS, a.host_history);
+        reset_step_counters(a.counters, a.B, BOUND_THREADS, a.host_history, a.slots, a.B_max);
     float acc = 0.f, hh = 0.f;
     auto step = [&](const uint4& m, const hpiece& hv) {
         acc = mu_fma<MU16>(m, &hv, 0, acc);
@@ -369,7 +377,7 @@ __global__ __launch_bounds__(512) void bound_mfma_kernel(StepArgs a, float* __re
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int li = lane & 15, g = lane >> 4;
     if (reset_counters && blockIdx.x == 0 && blockIdx.y == 0)
-        reset_step_counters(a.counters, a.B, 512, a.host_history);
+        reset_step_counters(a.counters, a.B, 512, a.host_history, a.slots, a.B_max);
     const int ks = blockIdx.y * BOUND_KS_PER_BLOCK + wave;
     if (ks >= KS) return;
     const int c0 = blockIdx.x * 16;
@@ -1204,7 +1212,9 @@ __device__ __forceinline__ u64 softmax_prefix_key(const StepArgs& a, const Clust
 // Sequences with more than STAGE_CAP scored rows are handled by several blocks: each takes one chunk of STAGE_CAP
 // logits, publishes the chunk's top-k candidates and log-sum-exp partial, and the block that arrives last (a
 // device-scope counter; nobody waits) merges them and goes on to the tests.
-__device__ __forceinline__ void cert_body(const StepArgs& a, int b, int chunk, int round, const SeqState& st, SeqShared& s) {
+// staged: the caller has already put the sequence's logits and ids where the staging below would put them
+__device__ __forceinline__ void cert_body(const StepArgs& a, int b, int chunk, int round, const SeqState& st, SeqShared& s,
+                                          bool staged = false) {
     extern __shared__ u64 arena[];
     const int tid = threadIdx.x, nt = blockDim.x, C = a.C;
     if (st.status != ST_ACTIVE || st.rounds != round) return;
@@ -1213,7 +1223,7 @@ __device__ __forceinline__ void cert_body(const StepArgs& a, int b, int chunk, i
     if (chunk >= nchunks) return;
     const int c0 = chunk * STAGE_CAP, len = min(STAGE_CAP, n - c0);
     if (round >= 1) DBG_T(12);
-    {
+    if (!staged) {
         const float* gv = a.slog + (size_t)b * a.K_cap + c0;
         const int32_t* gi = a.sid + (size_t)b * a.K_cap + c0;
         stage2_to_lds(reinterpret_cast<float*>(arena), gv, reinterpret_cast<int*>(arena) + STAGE_CAP, gi, len);
@@ -1520,6 +1530,7 @@ __device__ __forceinline__ bool round0_device(const StepArgs& a, int b, int j, i
     u64 kappa = ~0ull, nxt = 0;
     float nxtU, T0;
     uint4* hs4 = reinterpret_cast<uint4*>(arena) + a.r0_h_off;
+    u64* slots = a.slots + (size_t)b * CSV_SLOT_ROWS;
     uint4 pf[TILE_PF];
     const uint4* w = nullptr;
     float bias = 0.f;
@@ -1700,28 +1711,52 @@ __device__ __forceinline__ bool round0_device(const StepArgs& a, int b, int j, i
         }
         for (; i < nch; i += 64) acc = dot8_bf16(w[i], hs4[i], acc);
         acc = wave_sum(acc);
-        if (lane == 0) {
-            a.slog[(size_t)b * a.K_cap + p] = acc + bias;
-            a.sid[(size_t)b * a.K_cap + p] = id;
-        }
+        if (lane == 0)      // one word carries the row's token id and logit: whoever reads it gets both or neither
+            __hip_atomic_store(&slots[p], ((u64)(uint32_t)id << 32) | (u64)__float_as_uint(acc + bias), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         p += GW;
         if (p < rows) request_row(row_of(p));
     }
     DBG_T(5);
-    // The block that arrives last at the sequence's counter goes on.  Thread 0 releases after the barrier has
-    // collected the block's stores, and acquires again if it is the last; the barrier hands that on to the block.
-    __syncthreads();
-    if (tid == 0) {
-        __threadfence();
-        const bool last = atomicAdd(&a.counters[CNT_ARRIVE + b], 1) == NB - 1;
-        if (last) __threadfence();
-        s.sel = last;
+    // Block 0 of the sequence collects: each of its threads waits for its rows' words (no counter, no fence: a word
+    // is either still empty or complete), puts the logit and the id where the certification expects its staged
+    // input, copies them to the row arrays that later rounds read, and empties the word for the next step.  All NB
+    // blocks of a sequence are resident together (the host sizes the grid so), and the wait is bounded.
+    if (j != 0) return false;
+    __syncthreads();                       // every wave is done with h in LDS: the staging area overlaps it
+    float* sv = reinterpret_cast<float*>(arena);
+    int* si = reinterpret_cast<int*>(arena) + STAGE_CAP;
+    int gave_up = 0;
+    for (int t = tid; t < rows; t += nt) {
+        u64 v;
+        int spins = 0;
+        while ((v = __hip_atomic_load(&slots[t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) == CSV_SLOT_EMPTY) {
+            if (++spins > a.spin_limit) {
+                gave_up = 1;
+                break;
+            }
+            __builtin_amdgcn_s_sleep(1);
+        }
+        if (gave_up) break;
+        __hip_atomic_store(&slots[t], CSV_SLOT_EMPTY, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const float lv = __uint_as_float((uint32_t)v);
+        const int iv = (int)(uint32_t)(v >> 32);
+        sv[t] = lv;
+        si[t] = iv;
+        a.slog[(size_t)b * a.K_cap + t] = lv;
+        a.sid[(size_t)b * a.K_cap + t] = iv;
     }
-    __syncthreads();
+    if (__syncthreads_or(gave_up)) {
+        // a row never arrived: the step is given up for this sequence (flag ABORTED stays); words may still arrive
+        // later, so the next step has to empty the slots before it uses them
+        if (tid == 0) {
+            atomicExch(&a.counters[CNT_ABORT], 1);
+            __hip_atomic_store(&a.counters[CNT_SLOTS_DIRTY], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        return true;
+    }
     DBG_T(6);
-    if (!s.sel) return false;
     if (tid == 0) a.st[b] = st;
-    cert_body(a, b, 0, 0, st, s);
+    cert_body(a, b, 0, 0, st, s, true);
     return true;
 }
 
@@ -2218,7 +2253,7 @@ static void fill_args(StepArgs& a, const csv_workspace* ws, const csv_index* idx
     a.Wp = idx->Wp; a.bp = idx->bp; a.perm = idx->perm; a.mu = idx->mu; a.mu16 = idx->mu16; a.R = idx->R; a.bmax = idx->bmax;
     a.n = idx->n; a.off = idx->off; a.lnn = idx->lnn; a.cmeta = idx->cmeta; a.ln_nmax = idx->ln_nmax;
     a.K_cap = ws->K_cap; a.Npad = ws->Npad; a.n_chunks = ws->n_chunks; a.tile_stride = ws->tile_stride; a.sp_chunks = ws->sp_chunks; a.cand_chunks = ws->cand_chunks;
-    a.U = ws->U; a.hnorm = ws->hnorm; a.bound_partial = ws->bound_partial; a.st = ws->st; a.sel = ws->sel; a.slog = ws->slog; a.sid = ws->sid;
+    a.U = ws->U; a.hnorm = ws->hnorm; a.bound_partial = ws->bound_partial; a.st = ws->st; a.sel = ws->sel; a.slog = ws->slog; a.sid = ws->sid; a.slots = ws->slots; a.B_max = ws->B_max;
     a.tiles[0] = ws->tiles[0]; a.tiles[1] = ws->tiles[1]; a.counters = ws->counters;
     a.r0_h_off = (int)(round0_h_off(ws) / 16);
     a.tail_lds = (int)ws->tail_lds;
@@ -2382,6 +2417,7 @@ extern "C" int csv_workspace_create(const csv_index* idx, int B_max, int K_cap_r
     auto A = [&](void** p, size_t bytes) { if (e == hipSuccess) e = hipMalloc(p, bytes ? bytes : 16); };
     A((void**)&ws->U, B * C * 4); A((void**)&ws->bound_partial, B_max > 8 ? B * C * 4 * BOUND_KS_MAX : 16); A((void**)&ws->hnorm, B * 4); A((void**)&ws->st, B * sizeof(SeqState));
     A((void**)&ws->sel, B * C * 4); A((void**)&ws->slog, B * K * 4); A((void**)&ws->sid, B * K * 4);
+    A((void**)&ws->slots, B * CSV_SLOT_ROWS * 8);
     A((void**)&ws->tiles[0], tcap * sizeof(Tile)); A((void**)&ws->tiles[1], tcap * sizeof(Tile));
     A((void**)&ws->counters, CNT_ALLOC * 4); A((void**)&ws->fb_list, B * 4); A((void**)&ws->all_list, B * 4);
     A((void**)&ws->fb_logits, B * V * 4); A((void**)&ws->cand_val, B * NC * CSV_MAX_K * 4); A((void**)&ws->cand_id, B * NC * CSV_MAX_K * 4);
@@ -2392,6 +2428,7 @@ extern "C" int csv_workspace_create(const csv_index* idx, int B_max, int K_cap_r
         *ws->h_history = 0;
         e = hipHostGetDevicePointer((void**)&ws->d_history, ws->h_history, 0);
     }
+    if (e == hipSuccess) e = hipMemset(ws->slots, 0xFF, B * CSV_SLOT_ROWS * 8);     // every slot empty
     if (e == hipSuccess) e = hipMemset(ws->st, 0, B * sizeof(SeqState));
     if (e == hipSuccess) e = hipMemset(ws->tiles[0], 0, tcap * sizeof(Tile));
     if (e == hipSuccess) e = hipMemset(ws->tiles[1], 0, tcap * sizeof(Tile));
@@ -2455,7 +2492,7 @@ extern "C" int csv_workspace_create(const csv_index* idx, int B_max, int K_cap_r
 
 extern "C" void csv_workspace_free(csv_workspace* ws) {
     if (!ws) return;
-    void* ptrs[] = {ws->U, ws->bound_partial, ws->hnorm, ws->st, ws->sel, ws->slog, ws->sid, ws->tiles[0], ws->tiles[1],
+    void* ptrs[] = {ws->U, ws->bound_partial, ws->hnorm, ws->st, ws->sel, ws->slog, ws->sid, ws->slots, ws->tiles[0], ws->tiles[1],
                     ws->counters, ws->fb_list, ws->all_list, ws->fb_logits, ws->cand_val, ws->cand_id, ws->cand_max, ws->cand_sum};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
