@@ -1416,7 +1416,8 @@ __device__ __forceinline__ void cert_device(const StepArgs& a, int b, int chunk,
 // the sequence's counter (nobody waits) certifies, or plans round 1, or hands the sequence to the full product.
 // A prefix with more rows than the NB blocks should score themselves (one giant cluster) goes to the round-0
 // work list instead and is scored and certified by the tail kernel with the whole device.
-#define ROUND0_NB_MAX 32           // most blocks of a sequence in the round-0 kernel (8..128 swept: 32-64 fastest)
+#define ROUND0_ROWS_PER_BLOCK 4     // rows of the largest possible seed prefix per block (2..8 swept: 3-4 fastest; 8 costs 1 us)
+#define ROUND0_NB_MAX 64           // most blocks of a sequence in the round-0 kernel (8..128 swept: 32-64 fastest)
 #define ROUND0_ROWS_PER_WAVE 8     // with at most 32 blocks of 8 waves a sequence: no more than 2048 <= STAGE_CAP rows;
                                    // with a single block: 64 rows, larger prefixes go to the tail kernel
 #define ROUND0_HREG 4     // 128-bit pieces of h a thread carries in registers across the seed (d <= 4 * 8 * SEQ_THREADS)
@@ -1453,50 +1454,64 @@ struct WaveSeed {
     u64 kappa;
     float u[SEED_E], l[SEED_E];     // bounds and ln n of the lane's clusters (-inf: empty or out of range)
 };
-// sU, sL: LDS copies of U[b,:] and ln n
-__device__ __forceinline__ void wave_seed_pick(const StepArgs& a, const float* sU, const float* sL, WaveSeed& r) {
+// sU, sL, sR: LDS copies of U[b,:], of ln n_c and of {first row, rows} per cluster.  All LDS reads are issued from
+// clamped indexes before anything is compared (a conditional read would put every read in a basic block of its own,
+// one LDS round trip after the other).
+__device__ __forceinline__ void wave_seed_pick(const StepArgs& a, const float* sU, const float* sL, const int2* sR, WaveSeed& r) {
     const int lane = threadIdx.x & 63, C = a.C;
-    u64 best = 0;
+#pragma unroll
+    for (int i = 0; i < SEED_E; ++i) {
+        const int cc = min(lane + 64 * i, C - 1);
+        r.u[i] = sU[cc];
+        r.l[i] = sL[cc];
+    }
+    // 32-bit keys: the largest bound first, then the smallest cluster id among its holders (the order of the 64-bit keys)
+    unsigned bk = 0;
+    int bc = 0x7fffffff;
 #pragma unroll
     for (int i = 0; i < SEED_E; ++i) {
         const int c = lane + 64 * i;
-        r.u[i] = c < C ? sU[c] : -INFINITY;
-        r.l[i] = c < C ? sL[c] : -INFINITY;
-        const u64 kx = r.l[i] > -INFINITY ? ckey(r.u[i], c) : 0ull;
-        best = kx > best ? kx : best;
+        const bool some = c < C && r.l[i] > -INFINITY;
+        r.u[i] = some ? r.u[i] : -INFINITY;
+        r.l[i] = some ? r.l[i] : -INFINITY;
+        const unsigned kx = some ? lkey(r.u[i]) : 0u;      // lkey is never 0 for a bound that is not NaN
+        const bool better = kx > bk;                       // c grows with i: a tie keeps the smaller id
+        bk = better ? kx : bk;
+        bc = better ? c : bc;
     }
-    r.kappa = wave_max_u64(best);
-    r.c = (int)(0xFFFFFFFFu - (uint32_t)r.kappa);
+    const unsigned top = wave_max_u(bk);
+    const int cw = wave_min_i((bk == top && top != 0u) ? bc : 0x7fffffff);
+    r.kappa = 0;
+    r.c = 0;
     r.row0 = 0;
     r.rows = 0;
-    if (r.kappa != 0) {
-        const int4 cm = a.cmeta[r.c];       // the same address in every lane
-        r.row0 = cm.x;
-        r.rows = cm.y;
+    if (top != 0u) {
+        const int2 rr = sR[cw];
+        r.c = cw;
+        r.row0 = rr.x;
+        r.rows = rr.y;
+        r.kappa = ((u64)top << 32) | (u64)(0xFFFFFFFFu - (uint32_t)cw);
     }
 }
 // next bound and log tail mass with cluster r.c open and everything else unopened
 __device__ __forceinline__ void wave_seed_tail(const StepArgs& a, const WaveSeed& r, float& nxtU, float& T0) {
     const int lane = threadIdx.x & 63;
-    unsigned nk = 0;
+    float mx = -INFINITY;
+    float v[SEED_E];
 #pragma unroll
     for (int i = 0; i < SEED_E; ++i) {
-        const bool rest = r.l[i] > -INFINITY && (lane + 64 * i) != r.c;
-        const unsigned kx = lkey(r.u[i]);
-        nk = (rest && kx > nk) ? kx : nk;
+        const bool rest = (lane + 64 * i) != r.c;          // empty and out-of-range clusters already carry -inf
+        v[i] = rest ? r.l[i] + r.u[i] : -INFINITY;
+        mx = fmaxf(mx, rest ? r.u[i] : -INFINITY);
     }
-    nk = wave_max_u(nk);
-    nxtU = -INFINITY;
+    mx = wave_max(mx + 0.0f);
+    nxtU = mx;
     T0 = -INFINITY;
-    if (nk == 0) return;                                      // the prefix is the whole vocabulary
-    nxtU = fkey_inv(nk);
+    if (mx == -INFINITY) return;                              // the prefix is the whole vocabulary
     const float shift = a.ln_nmax + nxtU;
     float sum = 0.f;
 #pragma unroll
-    for (int i = 0; i < SEED_E; ++i) {
-        const bool rest = r.l[i] > -INFINITY && (lane + 64 * i) != r.c;
-        if (rest) sum += expf(r.l[i] + r.u[i] - shift);
-    }
+    for (int i = 0; i < SEED_E; ++i) sum += expf(v[i] - shift);     // exp(-inf) = 0
     sum = wave_sum(sum);
     T0 = shift + logf(sum);
 }
@@ -1535,17 +1550,16 @@ __device__ __forceinline__ bool round0_device(const StepArgs& a, int b, int j, i
     const uint4* w = nullptr;
     float bias = 0.f;
     int id = 0;
-    auto request_row = [&](int r) {
+    auto request_row = [&](int r) {       // unconditional loads from clamped addresses, then a select: no branches
         w = reinterpret_cast<const uint4*>(a.Wp + (size_t)r * a.d);
 #pragma unroll
         for (int q = 0; q < TILE_PF; ++q) {
             const int i = lane + 64 * q;
-            pf[q] = i < nch ? w[i] : make_uint4(0, 0, 0, 0);
+            const uint4 v = w[min(i, nch - 1)];
+            pf[q] = i < nch ? v : make_uint4(0, 0, 0, 0);
         }
-        if (lane == 0) {
-            bias = a.bp[r];
-            id = a.perm[r];
-        }
+        bias = a.bp[r];                   // every lane the same address: one transaction
+        id = a.perm[r];
     };
     int p = wave * NB + j;   // neighbouring rows go to different compute units
     bool fast = false;
@@ -1555,21 +1569,24 @@ __device__ __forceinline__ bool round0_device(const StepArgs& a, int b, int j, i
         // bounds, ln n and h to LDS with one barrier; then every wave picks the seed cluster by itself
         float* sU = reinterpret_cast<float*>(arena);
         float* sL = sU + C;
+        int2* sR = reinterpret_cast<int2*>(sL + C + (C & 1));
         {
             const float* Ub = a.U + (size_t)b * C;
-            float ru[2], rl[2];
+            float ru[2];
+            int4 rm[2];
 #pragma unroll
             for (int q = 0; q < 2; ++q) {
-                const int c = tid + q * nt, cc = c < C ? c : 0;
+                const int cc = min(tid + q * nt, C - 1);
                 ru[q] = Ub[cc];
-                rl[q] = a.lnn[cc];
+                rm[q] = a.cmeta[cc];
             }
 #pragma unroll
             for (int q = 0; q < 2; ++q) {
                 const int c = tid + q * nt;
                 if (c < C) {
                     sU[c] = ru[q];
-                    sL[c] = rl[q];
+                    sL[c] = __int_as_float(rm[q].z);
+                    sR[c] = make_int2(rm[q].x, rm[q].y);
                 }
             }
 #pragma unroll
@@ -1585,7 +1602,7 @@ __device__ __forceinline__ bool round0_device(const StepArgs& a, int b, int j, i
             if (j == 0) write_invalid(a, b);
             return j == 0;
         }
-        wave_seed_pick(a, sU, sL, ws);
+        wave_seed_pick(a, sU, sL, sR, ws);
         fast = ws.kappa != 0 && ws.rows >= need && ws.rows <= cap_rows && ws.rows <= a.K_max;
         if (!fast) __syncthreads();          // every wave has read the staged bounds: the general path reuses the LDS
     }
@@ -1695,12 +1712,14 @@ __device__ __forceinline__ bool round0_device(const StepArgs& a, int b, int j, i
     if (!fast) __syncthreads();            // h staged (the fast path staged it before its barrier)
     DBG_T(4);
     while (p < rows) {
-        float acc = 0.f;
+        float acc = 0.f, acc2 = 0.f;          // two chains: a dependent FMA costs two issue slots of a lone wave
 #pragma unroll
-        for (int q = 0; q < TILE_PF; ++q) {
+        for (int q = 0; q < TILE_PF; q += 2) {     // pieces past the row are zero and h is finite: no branch needed
             const int i = lane + 64 * q;
-            if (i < nch) acc = dot8_bf16(pf[q], hs4[i], acc);
+            acc = dot8_bf16(pf[q], hs4[min(i, nch - 1)], acc);
+            acc2 = dot8_bf16(pf[q + 1], hs4[min(i + 64, nch - 1)], acc2);
         }
+        acc += acc2;
         int i = lane + 64 * TILE_PF;
         for (; i + 192 < nch; i += 256) {
             const uint4 x0 = w[i], x1 = w[i + 64], x2 = w[i + 128], x3 = w[i + 192];
@@ -2236,7 +2255,11 @@ static int next_pow2(int x) {
 }
 
 // dynamic LDS of the per-sequence kernels
-static size_t seed_lds(const csv_workspace* ws) { return (size_t)ws->Npad * 8 + (size_t)ws->C * 8 + 8; }
+static size_t seed_lds(const csv_workspace* ws) {
+    const size_t general = (size_t)ws->Npad * 8 + (size_t)ws->C * 8 + 8;       // keys, offsets, tail terms
+    const size_t staged = (size_t)ws->C * 16 + 32;                             // bounds, ln n, {first row, rows} (small indexes)
+    return general > staged ? general : staged;
+}
 static size_t cert_lds(const csv_workspace* ws) {
     const size_t plan = seed_lds(ws), stage = (size_t)STAGE_CAP * 8;
     return plan > stage ? plan : stage;
@@ -2635,13 +2658,13 @@ extern "C" int csv_decode_step(csv_workspace* ws, const csv_index* idx, const ui
         fb_launches = ((history >> 16) & 0xffu) != 0;
     }
     // blocks per sequence in round 0: as many as stay resident together (a second wave of blocks would double the
-    // kernel's time), at most ROUND0_NB_MAX, and no more than one wave per row of the largest possible seed prefix
-    // (max(k,1) - 1 rows before its last cluster plus that cluster)
+    // kernel's time), at most ROUND0_NB_MAX, and no more than the largest possible seed prefix needs at
+    // ROUND0_ROWS_PER_BLOCK rows a block (max(k,1) - 1 rows before its last cluster plus that cluster)
     const long long prefix_max = (long long)(p->k > 1 ? p->k : 1) - 1 + idx->n_max;
     int nb = ws->round0_capacity / B;
     nb = nb < 1 ? 1 : (nb > ROUND0_NB_MAX ? ROUND0_NB_MAX : nb);
     {
-        const long long want = (prefix_max + (SEQ_THREADS / 64) - 1) / (SEQ_THREADS / 64);
+        const long long want = (prefix_max + ROUND0_ROWS_PER_BLOCK - 1) / ROUND0_ROWS_PER_BLOCK;
         if (want < nb) nb = (int)(want < 1 ? 1 : want);
     }
     // the tail's blocks ride in the round-0 launch when they all fit next to the round-0 blocks (one block per unit)
