@@ -138,16 +138,18 @@ void csv_set_error(const char* fmt, ...);
 __device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
 
-// sum_j w_j * h_j over eight bf16 pairs packed in two 128-bit words, added to acc
+// sum_j w_j * h_j over eight bf16 pairs packed in two 128-bit words, added to acc.  v_dot2c_f32_bf16 takes two
+// bf16 pairs as they sit in memory and adds both products to a float32 accumulator: one instruction where
+// widening both operands and two FMAs would be six (these loops are bound by instruction issue, not by arithmetic).
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 csv_bf16x2_t;
+__device__ __forceinline__ float dot2_bf16(uint32_t w, uint32_t h, float acc) {
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(csv_bf16x2_t, w), __builtin_bit_cast(csv_bf16x2_t, h), acc, false);
+}
 __device__ __forceinline__ float dot8_bf16(const uint4& w, const uint4& h, float acc) {
-    acc = fmaf(bf16_lo(w.x), bf16_lo(h.x), acc);
-    acc = fmaf(bf16_hi(w.x), bf16_hi(h.x), acc);
-    acc = fmaf(bf16_lo(w.y), bf16_lo(h.y), acc);
-    acc = fmaf(bf16_hi(w.y), bf16_hi(h.y), acc);
-    acc = fmaf(bf16_lo(w.z), bf16_lo(h.z), acc);
-    acc = fmaf(bf16_hi(w.z), bf16_hi(h.z), acc);
-    acc = fmaf(bf16_lo(w.w), bf16_lo(h.w), acc);
-    acc = fmaf(bf16_hi(w.w), bf16_hi(h.w), acc);
+    acc = dot2_bf16(w.x, h.x, acc);
+    acc = dot2_bf16(w.y, h.y, acc);
+    acc = dot2_bf16(w.z, h.z, acc);
+    acc = dot2_bf16(w.w, h.w, acc);
     return acc;
 }
 

@@ -161,51 +161,53 @@ __device__ __forceinline__ float mu_fma(const uint4& m, HP hrow, int unit, float
     }
 }
 #define BOUND_THREADS 512
+#define BOUND_LDS_MAX (128 * 1024)   // h of up to 8 sequences of d = 8192 in LDS: one block serves all 8, the centroids are read once
 #define BOUND_HREG 8       // 128-bit pieces of h per thread: 8 x 512 x 16 B covers the 64 KB that BT sequences may take in LDS
+// 2..8 sequences: h of the block's BT sequences is staged in LDS once, then every wave walks over whole clusters
+// (cluster = wave index among all waves of the grid, then + their number, ...): a centroid row goes through the wave
+// in chunks of BOUND_PFB 128-bit loads per lane, the next chunk (of this or of the wave's next cluster) always
+// requested before the current one is used, and nothing in the loop waits for another wave.  With more clusters
+// than resident waves the staging of h is paid once per block, not once per cluster.
+#ifndef BOUND_PFB
+#define BOUND_PFB 16      // 128-bit loads per lane and chunk of a centroid row (two chunks in flight)
+#endif
 template <int BT, bool MU16>
 __global__ __launch_bounds__(BOUND_THREADS) void bound_kernel(StepArgs a, float* __restrict__ U_out, float* __restrict__ hn_out,
-                                                              int reset_counters, int groups, int groups_per_xcd, int wpc) {
+                                                              int reset_counters) {
     extern __shared__ uint4 hs4[];
     __shared__ float hn[BT];
-    __shared__ float part[BOUND_THREADS / 64][BT];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int b0 = blockIdx.y * BT;
     const int nb = min(BT, a.B - b0);
-    const int nch = a.d >> 3, nq = mu_units<MU16>(a.d);
-    const int cpb = (BOUND_THREADS / 64) / wpc, cl = wave / wpc, slice = wave - cl * wpc;
-    const int g = (blockIdx.x & 7) * groups_per_xcd + (blockIdx.x >> 3);
-    const int c = g * cpb + cl;
-    const bool valid = g < groups && c < a.C;
-    // h of the block's sequences: registers first
-    uint4 hreg[BOUND_HREG];
-    {
-        const uint4* hsrc = reinterpret_cast<const uint4*>(a.h) + (size_t)b0 * nch;
+    const int nch = a.d >> 3, nq = mu_units<MU16>(a.d), C = a.C;
+    const int GW = gridDim.x * (BOUND_THREADS / 64);
+    const int nchk = (nq + 64 * BOUND_PFB - 1) / (64 * BOUND_PFB);
+    int c = blockIdx.x * (BOUND_THREADS / 64) + wave, chunk = 0;
+    uint4 pfA[BOUND_PFB], pfB[BOUND_PFB];
+    auto issue = [&](uint4 (&buf)[BOUND_PFB], int cc, int ch) {      // unconditional loads from clamped addresses, then a select
+        const uint4* mrow = mu_row<MU16>(a, min(cc, C - 1));
+#pragma unroll
+        for (int j = 0; j < BOUND_PFB; ++j) {
+            const int i = ch * 64 * BOUND_PFB + lane + 64 * j;
+            const uint4 v = mrow[min(i, nq - 1)];
+            buf[j] = (cc < C && i < nq) ? v : make_uint4(0, 0, 0, 0);
+        }
+    };
+    issue(pfA, c, 0);                 // in flight while h is staged
+    const uint4* hsrc = reinterpret_cast<const uint4*>(a.h) + (size_t)b0 * nch;
+    for (int base = 0; base < BT * nch; base += BOUND_HREG * BOUND_THREADS) {
+        uint4 hreg[BOUND_HREG];
 #pragma unroll
         for (int q = 0; q < BOUND_HREG; ++q) {
-            const int i = tid + q * BOUND_THREADS;
-            hreg[q] = i < nb * nch ? hsrc[i] : make_uint4(0, 0, 0, 0);
+            const int i = base + tid + q * BOUND_THREADS;
+            const uint4 v = hsrc[min(i, nb * nch - 1)];
+            hreg[q] = i < nb * nch ? v : make_uint4(0, 0, 0, 0);
         }
-    }
-    // this wave's slice of the centroid row
-    const int seg = (nq + wpc - 1) / wpc, lo = slice * seg, hi = min(nq, lo + seg);
-    const uint4* mrow = mu_row<MU16>(a, valid ? c : 0);
-    uint4 pf[BOUND_PF];
 #pragma unroll
-    for (int j = 0; j < BOUND_PF; ++j) {
-        const int i = lo + lane + 64 * j;
-        pf[j] = (valid && i < hi) ? mrow[i] : make_uint4(0, 0, 0, 0);
-    }
-    float Rc = 0.f, bm = 0.f;
-    int ncl = 0;
-    if (valid && slice == 0 && lane == 0) {
-        Rc = a.R[c];
-        bm = a.bmax[c];
-        ncl = a.n[c];
-    }
-#pragma unroll
-    for (int q = 0; q < BOUND_HREG; ++q) {
-        const int i = tid + q * BOUND_THREADS;
-        if (i < BT * nch) hs4[i] = hreg[q];
+        for (int q = 0; q < BOUND_HREG; ++q) {
+            const int i = base + tid + q * BOUND_THREADS;
+            if (i < BT * nch) hs4[i] = hreg[q];
+        }
     }
     if (reset_counters && blockIdx.x == 0 && blockIdx.y == 0)
         reset_step_counters(a.counters, a.B, BOUND_THREADS, a.host_history, a.slots, a.B_max);
@@ -225,44 +227,39 @@ __global__ __launch_bounds__(BOUND_THREADS) void bound_kernel(StepArgs a, float*
     float acc[BT];
 #pragma unroll
     for (int s = 0; s < BT; ++s) acc[s] = 0.f;
-#pragma unroll
-    for (int j = 0; j < BOUND_PF; ++j) {
-        const int i = lo + lane + 64 * j;
-        if (i < hi) {
-#pragma unroll
-            for (int s = 0; s < BT; ++s) acc[s] = mu_fma<MU16>(pf[j], hs4 + s * nch, i, acc[s]);
+    // one trip: request the chunk after (c, chunk) into `nxt`, use `cur`, finish the cluster when that was its last chunk
+    auto trip = [&](uint4 (&cur)[BOUND_PFB], uint4 (&nxt)[BOUND_PFB]) {
+        const bool last = chunk + 1 == nchk;
+        const int c2 = last ? c + GW : c, ch2 = last ? 0 : chunk + 1;
+        float Rc = 0.f, bm = 0.f;
+        int ncl = 0;
+        if (last) {                    // every lane the same address; needed only after the reduction below
+            Rc = a.R[c];
+            bm = a.bmax[c];
+            ncl = a.n[c];
         }
-    }
-    if (valid) {
-#pragma unroll 4
-        for (int i = lo + lane + 64 * BOUND_PF; i < hi; i += 64) {
-            const uint4 m = mrow[i];
+        if (c2 < C) issue(nxt, c2, ch2);
 #pragma unroll
-            for (int s = 0; s < BT; ++s) acc[s] = mu_fma<MU16>(m, hs4 + s * nch, i, acc[s]);
+        for (int j = 0; j < BOUND_PFB; ++j) {
+            const int i = min(chunk * 64 * BOUND_PFB + lane + 64 * j, nq - 1);     // units past the row are zero
+#pragma unroll
+            for (int s = 0; s < BT; ++s) acc[s] = mu_fma<MU16>(cur[j], hs4 + s * nch, i, acc[s]);
         }
-    }
-#pragma unroll
-    for (int s = 0; s < BT; ++s) acc[s] = wave_sum(acc[s]);
-    if (wpc > 1) {   // column slices of a cluster are added in slice order
-        if (lane == 0) {
-#pragma unroll
-            for (int s = 0; s < BT; ++s) part[wave][s] = acc[s];
-        }
-        __syncthreads();
-        if (slice == 0) {
+        if (last) {
 #pragma unroll
             for (int s = 0; s < BT; ++s) {
-                float t = part[wave][s];
-                for (int q = 1; q < wpc; ++q) t += part[wave + q][s];
-                acc[s] = t;
+                const float t = wave_sum(acc[s]);
+                if (lane == 0 && s < nb) U_out[(size_t)(b0 + s) * C + c] = ncl == 0 ? -INFINITY : (t + Rc * hn[s] + bm);
+                acc[s] = 0.f;
             }
         }
-    }
-    if (valid && slice == 0 && lane == 0) {
-        const bool empty = ncl == 0;
-#pragma unroll
-        for (int s = 0; s < BT; ++s)
-            if (s < nb) U_out[(size_t)(b0 + s) * a.C + c] = empty ? -INFINITY : (acc[s] + Rc * hn[s] + bm);
+        c = c2;
+        chunk = ch2;
+    };
+    while (c < C) {
+        trip(pfA, pfB);
+        if (c >= C) break;
+        trip(pfB, pfA);
     }
 }
 
@@ -1953,12 +1950,18 @@ __device__ __forceinline__ void full_mfma_device(const FullArgs& f, int n, int s
     }
 }
 
-// All n sequences through the MFMA path: 32 per pass over W' (16 when that covers them).
+// All n sequences through the MFMA path: up to 64 per pass over W'.
 __device__ __forceinline__ void full_mfma_all(const FullArgs& f, int n, uint4* lds, int lds_bytes, int block, int nblocks) {
     if (n <= 16) {
         full_mfma_device<1>(f, n, 0, lds, lds_bytes, block, nblocks);
+    } else if (n <= 32) {
+        full_mfma_device<2>(f, n, 0, lds, lds_bytes, block, nblocks);
     } else {
-        for (int s0 = 0; s0 < n; s0 += 32) full_mfma_device<2>(f, n, s0, lds, lds_bytes, block, nblocks);
+        // 64 per pass over W': twice the logits are revisited per K chunk, but W' (the large operand) is read once
+        for (int s0 = 0; s0 < n; s0 += 64) {
+            if (n - s0 <= 32) full_mfma_device<2>(f, n, s0, lds, lds_bytes, block, nblocks);
+            else full_mfma_device<4>(f, n, s0, lds, lds_bytes, block, nblocks);
+        }
     }
 }
 
@@ -2293,6 +2296,24 @@ static int check_pair(const csv_workspace* ws, const csv_index* idx, const void*
     return CSV_OK;
 }
 
+// The dynamic-LDS limit of a kernel is one attribute per process and device, shared by every workspace: it is only
+// ever raised, so a workspace created later with smaller needs cannot take away what an earlier one's launches rely on.
+enum { K_ROUND0, K_STEP, K_TAIL, K_RCERT, K_FBPROD, K_FULLMFMA, K_BOUND0, K_NKERN = K_BOUND0 + 8 };
+static size_t g_lds_limit[CSV_STATIC_MAX_DEVICES][K_NKERN];
+static pthread_mutex_t g_attr_lock = PTHREAD_MUTEX_INITIALIZER;
+#define CSV_STATIC_LDS_MAX 16384     // at least the static shared memory of any kernel here
+static hipError_t raise_lds(int dev, int which, const void* fn, size_t bytes) {
+    if (dev < 0 || dev >= CSV_STATIC_MAX_DEVICES) return hipErrorInvalidDevice;
+    hipError_t e = hipSuccess;
+    pthread_mutex_lock(&g_attr_lock);
+    if (bytes > g_lds_limit[dev][which]) {
+        if (bytes + CSV_STATIC_LDS_MAX > 65536) e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+        if (e == hipSuccess) g_lds_limit[dev][which] = bytes;
+    }
+    pthread_mutex_unlock(&g_attr_lock);
+    return e;
+}
+
 // K slices of the batched bound product and k-blocks (of 32) per slice: enough slices that (cluster tiles x slices)
 // fills the device, at most BOUND_KS_MAX (the partial buffer holds KS x B x C floats).
 static void bound_mfma_plan(int C, int d, int& KS, int& kbs) {
@@ -2331,30 +2352,48 @@ static int launch_bounds_kernel(const StepArgs& a, float* U, float* hn, int rese
     }
     int bt = 1;
     while (bt < a.B && bt < 8) bt <<= 1;
-    while (bt > 1 && (size_t)bt * a.d * 2 > 65536) bt >>= 1;
+    while (bt > 1 && (size_t)bt * a.d * 2 > BOUND_LDS_MAX) bt >>= 1;
     const bool m16 = a.mu16 != nullptr;
-    const int nq = m16 ? a.d >> 3 : a.d >> 2;     // 128-bit units per centroid row
-    int wpc = 1;
-    while (wpc < 4 && (nq + wpc - 1) / wpc > 64 * BOUND_PF) wpc <<= 1;
-    const int cpb = (BOUND_THREADS / 64) / wpc;
-    const int groups = (a.C + cpb - 1) / cpb;
-    const int gpx = (groups + 7) / 8;
-    dim3 grid(gpx * 8, (a.B + bt - 1) / bt);
     const size_t lds = (size_t)bt * a.d * 2;
-#define CSV_BOUND_LAUNCH(BT)                                                                                      \
-    do {                                                                                                          \
-        if (m16) bound_kernel<BT, true><<<grid, BOUND_THREADS, lds, st>>>(a, U, hn, reset, groups, gpx, wpc);     \
-        else bound_kernel<BT, false><<<grid, BOUND_THREADS, lds, st>>>(a, U, hn, reset, groups, gpx, wpc);        \
+    if (a.B == 1) {
+        const int nq = m16 ? a.d >> 3 : a.d >> 2;     // 128-bit units per centroid row
+        int wpc = 1;
+        while (wpc < 4 && (nq + wpc - 1) / wpc > 64 * BOUND_PF) wpc <<= 1;
+        const int cpb = (BOUND_THREADS / 64) / wpc;
+        const int groups = (a.C + cpb - 1) / cpb;
+        const int gpx = (groups + 7) / 8;
+        if (m16) bound1_kernel<true><<<gpx * 8, BOUND_THREADS, 0, st>>>(a, U, hn, reset, groups, gpx, wpc);
+        else bound1_kernel<false><<<gpx * 8, BOUND_THREADS, 0, st>>>(a, U, hn, reset, groups, gpx, wpc);
+        CSV_LAUNCH_CHECK("bound1_kernel");
+        return CSV_OK;
+    }
+    int dev = 0, cus = 0;
+    CSV_HIP(hipGetDevice(&dev));
+    CSV_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+    // as many blocks as are resident together (LDS decides), at most one wave per cluster
+    int per_cu = (int)((size_t)(150 * 1024) / (lds + 1024));
+    per_cu = per_cu < 1 ? 1 : (per_cu > 4 ? 4 : per_cu);
+    int gx = (a.C + (BOUND_THREADS / 64) - 1) / (BOUND_THREADS / 64);
+    if (gx > cus * per_cu) gx = cus * per_cu;
+    dim3 grid(gx, (a.B + bt - 1) / bt);
+    if (lds + 4096 > 65536) {        // more dynamic LDS than the default limit: raise this variant's attribute (only ever upwards)
+        const void* fn = nullptr;
+        switch (bt) {
+            case 2: fn = m16 ? (const void*)bound_kernel<2, true> : (const void*)bound_kernel<2, false>; break;
+            case 4: fn = m16 ? (const void*)bound_kernel<4, true> : (const void*)bound_kernel<4, false>; break;
+            case 8: fn = m16 ? (const void*)bound_kernel<8, true> : (const void*)bound_kernel<8, false>; break;
+            default: fn = m16 ? (const void*)bound_kernel<1, true> : (const void*)bound_kernel<1, false>; break;
+        }
+        const int slot = K_BOUND0 + (bt == 1 ? 0 : bt == 2 ? 1 : bt == 4 ? 2 : 3) * 2 + (m16 ? 1 : 0);
+        CSV_HIP(raise_lds(dev, slot, fn, BOUND_LDS_MAX));
+    }
+#define CSV_BOUND_LAUNCH(BT)                                                                   \
+    do {                                                                                       \
+        if (m16) bound_kernel<BT, true><<<grid, BOUND_THREADS, lds, st>>>(a, U, hn, reset);    \
+        else bound_kernel<BT, false><<<grid, BOUND_THREADS, lds, st>>>(a, U, hn, reset);       \
     } while (0)
     switch (bt) {
-        case 1:
-            if (a.B == 1) {
-                if (m16) bound1_kernel<true><<<grid, BOUND_THREADS, 0, st>>>(a, U, hn, reset, groups, gpx, wpc);
-                else bound1_kernel<false><<<grid, BOUND_THREADS, 0, st>>>(a, U, hn, reset, groups, gpx, wpc);
-            } else {
-                CSV_BOUND_LAUNCH(1);
-            }
-            break;
+        case 1: CSV_BOUND_LAUNCH(1); break;        // 2..8 sequences of rows too long for two of them in LDS
         case 2: CSV_BOUND_LAUNCH(2); break;
         case 4: CSV_BOUND_LAUNCH(4); break;
         default: CSV_BOUND_LAUNCH(8); break;
@@ -2399,24 +2438,6 @@ static int launch_full(const csv_index* idx, const uint16_t* d_h, const int32_t*
     full_gemv_kernel<<<grid, 256, (size_t)FULL_G * idx->d * 2, st>>>(f);
     CSV_LAUNCH_CHECK("full_gemv_kernel");
     return CSV_OK;
-}
-
-// The dynamic-LDS limit of a kernel is one attribute per process and device, shared by every workspace: it is only
-// ever raised, so a workspace created later with smaller needs cannot take away what an earlier one's launches rely on.
-enum { K_ROUND0, K_STEP, K_TAIL, K_RCERT, K_FBPROD, K_FULLMFMA, K_NKERN };
-static size_t g_lds_limit[CSV_STATIC_MAX_DEVICES][K_NKERN];
-static pthread_mutex_t g_attr_lock = PTHREAD_MUTEX_INITIALIZER;
-#define CSV_STATIC_LDS_MAX 16384     // at least the static shared memory of any kernel here
-static hipError_t raise_lds(int dev, int which, const void* fn, size_t bytes) {
-    if (dev < 0 || dev >= CSV_STATIC_MAX_DEVICES) return hipErrorInvalidDevice;
-    hipError_t e = hipSuccess;
-    pthread_mutex_lock(&g_attr_lock);
-    if (bytes > g_lds_limit[dev][which]) {
-        if (bytes + CSV_STATIC_LDS_MAX > 65536) e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
-        if (e == hipSuccess) g_lds_limit[dev][which] = bytes;
-    }
-    pthread_mutex_unlock(&g_attr_lock);
-    return e;
 }
 
 extern "C" int csv_workspace_create(const csv_index* idx, int B_max, int K_cap_rows, csv_workspace** out) {

@@ -30,7 +30,8 @@ def _finish(t: PAR.Tally, tag: str, max_band_frac=0.01):
 
 # ------------------------------------------------------------------ per-kernel parity
 @pytest.mark.parametrize("V,d,C,B", [(2000, 256, 16, 1), (3001, 520, 37, 3), (4096, 1024, 64, 8), (1500, 4096, 5, 11),
-                                     (3001, 520, 37, 37), (777, 136, 9, 70)])
+                                     (3001, 520, 37, 37), (777, 136, 9, 70),
+                                     (1200, 5128, 9, 8), (900, 8192, 6, 7)])    # h of 7-8 sequences beyond 64 KB of LDS
 def test_full_logits_and_bounds(V, d, C, B):
     r = synth.small_recipe(f"s{V}", V=V, d=d, C=C, B=B, steps=2)
     log(f"full_logits/bounds V={V} d={d} C={C} B={B}")
