@@ -16,6 +16,7 @@ Pins (tests/test_oracle_*.py):
   topk_bruteforce    three independent selections on tiny V
   build_index        partition/permutation invariants, radius >= every member distance, footprint of Section IV
   cluster_bounds     Cauchy-Schwarz invariant (Section III-A), homogeneity, singleton clusters, single cluster
+  bias_table         a hand-computed cluster; every logit still dominated; never looser than the max-bias bound; m = 1 is that bound
   topk certificate   Theorem 1 against brute force; minimal prefix = {U_c >= true k-th logit}
   eps certificate    proof identity TV = R/(Z_S+R) (Theorem 2), cluster-wise tail <= loose tail
   alg1_step          brute-force enumeration of all prefixes on small C (certificates written out on sets, linear domain)
@@ -95,10 +96,12 @@ def topk_bruteforce(logits: np.ndarray, k: int, ids: np.ndarray | None = None):
 class OracleIndex:
     """Cluster metadata of Section III-A.1 / Section IV: centroids, radii, bias maxima, row permutation."""
 
-    def __init__(self, mu, R, bmax, n, perm):
+    def __init__(self, mu, R, bmax, n, perm, bias_table=None):
         self.mu = np.ascontiguousarray(mu, dtype=np.float32)      # [C,d] stored centroids
         self.R = np.ascontiguousarray(R, dtype=np.float32)        # [C]   stored radii (rounded up)
         self.bmax = np.ascontiguousarray(bmax, dtype=np.float32)  # [C]   max bias in cluster (-inf if empty)
+        # [C,m,2] or None: per cluster m pairs (radius, bias) of the top-m bias table; unused entries (0, -inf)
+        self.bias_table = None if bias_table is None else np.ascontiguousarray(bias_table, dtype=np.float32)
         self.n = np.ascontiguousarray(n, dtype=np.int64)          # [C]   rows per cluster
         self.off = np.concatenate([[0], np.cumsum(self.n)]).astype(np.int64)
         self.perm = np.ascontiguousarray(perm, dtype=np.int64)    # [V]   permuted row -> original token id
@@ -127,7 +130,7 @@ def _round_up_f32(x: np.ndarray) -> np.ndarray:
 
 
 def build_index(W_bits: np.ndarray, b, labels: np.ndarray, C: int, radius_slack: float = 2.0 ** -14,
-                centroid_bf16: bool = False) -> OracleIndex:
+                centroid_bf16: bool = False, bias_table_m: int = 0) -> OracleIndex:
     """Index from a cluster assignment.
 
     mu_c = mean of the cluster's rows, stored as float32;  R_c = max_i ||W_i - mu_c||_2 measured to the
@@ -137,6 +140,8 @@ def build_index(W_bits: np.ndarray, b, labels: np.ndarray, C: int, radius_slack:
     clusters in id order, tokens inside a cluster by ascending original id.
     centroid_bf16: the stored centroid is the mean rounded to bfloat16 (nearest even); the radius is measured to
     that stored value, so the bound of Eq. "cluster_bound" stays valid and the centroids take half the bytes.
+    bias_table_m >= 2: also build the top-m bias table of Section III ("Advanced Theoretical Improvements", bias
+    binning), see bias_table().
     """
     labels = np.asarray(labels, dtype=np.int64)
     V, d = W_bits.shape
@@ -161,7 +166,52 @@ def build_index(W_bits: np.ndarray, b, labels: np.ndarray, C: int, radius_slack:
     mun = np.sqrt(np.einsum("ij,ij->i", mu.astype(np.float64), mu.astype(np.float64)))
     Rt = _round_up_f32(R * (1.0 + radius_slack) + radius_slack * mun)
     Rt[n == 0] = 0.0
-    return OracleIndex(mu, Rt, bmax, n, perm)
+    table = None
+    if bias_table_m >= 2:
+        table = bias_table(W_bits, bb, mu, n, perm, bias_table_m, radius_slack)
+    return OracleIndex(mu, Rt, bmax, n, perm, table)
+
+
+def bias_table(W_bits: np.ndarray, bb, mu: np.ndarray, n: np.ndarray, perm: np.ndarray, m: int,
+               radius_slack: float) -> np.ndarray:
+    """Top-m bias table of a cluster (Section III, "Advanced Theoretical Improvements": bias binning).
+
+    The bound of Eq. "cluster_bound" charges every token of a cluster with the largest radius AND the largest bias,
+    which is loose when one token has an outlying bias.  Reading used here: the m-1 tokens with the largest biases
+    (equal biases: smaller token id first) are bounded one by one, each with its own distance to the centroid and its
+    own bias, <W_i,h> + b_i <= <mu_c,h> + ||W_i - mu_c|| ||h|| + b_i (the Cauchy-Schwarz step of Section III-A for
+    that token alone); all other tokens of the cluster share the largest radius and the largest bias among THEM.
+    The cluster bound is the largest of these m bounds:
+        U_c(h) = <mu_c,h> + max_j (rho_j ||h|| + beta_j).
+    Every token is covered by one of the m terms, so Theorems 1 and 2 hold unchanged; no term exceeds
+    R_c ||h|| + max_i b_i, so the bound is never looser; m = 1 is Eq. "cluster_bound" itself.
+    Returns float32 [C, m, 2] = (rho_j, beta_j); radii get the same slack and upward rounding as R_c; entries a
+    cluster does not need are (0, -inf)."""
+    C = n.shape[0]
+    off = np.concatenate([[0], np.cumsum(n)])
+    out = np.zeros((C, m, 2), dtype=np.float32)
+    out[:, :, 1] = -np.inf
+    mun = np.sqrt(np.einsum("ij,ij->i", mu.astype(np.float64), mu.astype(np.float64)))
+    for c in range(C):
+        rows = perm[off[c]:off[c + 1]]                 # ascending token id
+        if rows.size == 0:
+            continue
+        diff = bf16_to_f64(W_bits[rows]) - mu[c].astype(np.float64)[None, :]
+        dist = np.sqrt(np.einsum("ij,ij->i", diff, diff))
+        bias = np.zeros(rows.size, dtype=np.float32) if bb is None else bb[rows]
+        order = np.lexsort((rows, -bias.astype(np.float64)))      # bias descending, token id ascending
+        ne = min(m - 1, rows.size)
+        pick = order[:ne]
+        rest = order[ne:]
+        rho = list(dist[pick])
+        beta = list(bias[pick])
+        if rest.size:
+            rho.append(dist[rest].max())
+            beta.append(bias[rest].max())
+        rho = _round_up_f32(np.array(rho) * (1.0 + radius_slack) + radius_slack * mun[c])
+        out[c, :len(rho), 0] = rho
+        out[c, :len(rho), 1] = np.array(beta, dtype=np.float32)
+    return out
 
 
 def lloyd_assign(W64: np.ndarray, cent64: np.ndarray) -> np.ndarray:
@@ -196,11 +246,16 @@ def lloyd_kmeans(W_bits: np.ndarray, init_rows: np.ndarray, iters: int):
 
 # ----------------------------------------------------------------------------- bounds
 def cluster_bounds(index: OracleIndex, h64: np.ndarray):
-    """U_c(h) = <mu_c,h> + R_c ||h||_2 + max_{i in c} b_i  (Eq. "cluster_bound").  Empty clusters get -inf."""
+    """U_c(h) = <mu_c,h> + R_c ||h||_2 + max_{i in c} b_i  (Eq. "cluster_bound"); with a top-m bias table the last
+    two terms are replaced by max_j (rho_j ||h|| + beta_j).  Empty clusters get -inf."""
     h64 = np.atleast_2d(h64)
     hn = np.sqrt(np.einsum("ij,ij->i", h64, h64))
-    U = h64 @ index.mu.astype(np.float64).T + hn[:, None] * index.R.astype(np.float64)[None, :] \
-        + index.bmax.astype(np.float64)[None, :]
+    dots = h64 @ index.mu.astype(np.float64).T
+    if index.bias_table is None:
+        U = dots + hn[:, None] * index.R.astype(np.float64)[None, :] + index.bmax.astype(np.float64)[None, :]
+    else:       # top-m bias table: the largest of the m (radius, bias) terms of each cluster, see bias_table()
+        t = index.bias_table.astype(np.float64)
+        U = dots + np.max(hn[:, None, None] * t[None, :, :, 0] + t[None, :, :, 1], axis=2)
     U[:, index.n == 0] = NEG_INF
     return U, hn
 

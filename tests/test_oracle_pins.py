@@ -684,3 +684,71 @@ def test_equal_bounds_open_the_smaller_cluster_id_first():
         r = O.csv2r_step(idx, U, L, 1, 0.6, K_max=3, combine=O.COMBINE_ANY)
         assert r["clusters"].tolist() == [first] and r["ids"].tolist() == [first] and r["flags"] == O.FLAG_SOFTMAX_CERT
         assert r["margins"]["seed"][0] == 0.0 and r["margins"]["tk0"][0] == 0.0      # both comparisons are exact ties
+
+
+# ------------------------------------------------------------------ top-m bias table (Section III, bias binning)
+def test_bias_table_hand_computed_cluster():
+    # one cluster, d = 1: rows 5, 3, 1 -> centroid 3, radius 2; the row AT the centroid carries the outlying bias 4.
+    # h = 1: logits 5, 7, 1.  Eq. "cluster_bound": 3 + 2 + 4 = 9.  With m = 2 the outlier is bounded on its own,
+    # 3 + 0*1 + 4 = 7, and the others by 3 + 2*1 + 0 = 5: the bound is 7, the largest logit itself.
+    Wb = synth.f32_to_bf16_bits(np.array([[5.0], [3.0], [1.0]], dtype=np.float32))
+    b = np.array([0.0, 4.0, 0.0], dtype=np.float32)
+    h = np.array([[1.0]])
+    plain = O.build_index(Wb, b, np.zeros(3, dtype=int), 1, radius_slack=0.0)
+    tab = O.build_index(Wb, b, np.zeros(3, dtype=int), 1, radius_slack=0.0, bias_table_m=2)
+    assert O.cluster_bounds(plain, h)[0][0, 0] == 9.0
+    assert tab.bias_table.tolist() == [[[0.0, 4.0], [2.0, 0.0]]]
+    assert O.cluster_bounds(tab, h)[0][0, 0] == 7.0
+    # which term wins depends on ||h||: at ||h|| = 3 the shared radius takes over: 9 + max(0 + 4, 6 + 0) = 15 (logits 15, 13, 3)
+    assert O.cluster_bounds(tab, 3.0 * h)[0][0, 0] == 15.0 and O.cluster_bounds(plain, 3.0 * h)[0][0, 0] == 19.0
+    # m = 3: two tokens on their own (bias 4, then bias 0 with the smaller id: row 5, distance 2), the rest {row 1}: radius 2
+    t3 = O.build_index(Wb, b, np.zeros(3, dtype=int), 1, radius_slack=0.0, bias_table_m=3).bias_table
+    assert t3.tolist() == [[[0.0, 4.0], [2.0, 0.0], [2.0, 0.0]]]
+    # more table entries than tokens: the unused ones never win
+    t5 = O.build_index(Wb, b, np.zeros(3, dtype=int), 1, radius_slack=0.0, bias_table_m=5)
+    assert np.isneginf(t5.bias_table[0, 3:, 1]).all() and O.cluster_bounds(t5, h)[0][0, 0] == 7.0
+
+
+def test_bias_table_keeps_the_bound_sound_and_never_loosens_it():
+    rng = np.random.default_rng(77)
+    tighter = total = 0
+    for seed in range(6):
+        r, head, h = _small(seed=20 + seed, V=1500, d=48, C=20, steps=5, sizes="zipf" if seed % 2 else "equal")
+        b = head["b"].copy()
+        b[rng.integers(0, r.V, 40)] += rng.normal(0, 1.0, 40).astype(np.float32)      # a few outlying biases
+        W = O.bf16_to_f64(head["W_bits"])
+        plain = O.build_index(head["W_bits"], b, head["labels"], r.C)
+        one = O.build_index(head["W_bits"], b, head["labels"], r.C, bias_table_m=1)
+        assert one.bias_table is None                                               # m = 1 is Eq. "cluster_bound" itself
+        for m in (2, 3, 8):
+            tab = O.build_index(head["W_bits"], b, head["labels"], r.C, bias_table_m=m)
+            assert tab.bias_table.shape == (r.C, m, 2)
+            # the first entry carries the largest bias, the shared entry's radius never exceeds the cluster radius
+            assert np.array_equal(tab.bias_table[:, 0, 1], plain.bmax)
+            assert np.all(tab.bias_table[:, :, 0] <= plain.R[:, None])
+            for t in range(h.shape[0]):
+                h64 = O.bf16_to_f64(h[t])
+                L = O.full_logits(W, b, h64)
+                Up, _ = O.cluster_bounds(plain, h64)
+                Ut, _ = O.cluster_bounds(tab, h64)
+                assert np.all(L <= Ut[:, head["labels"]] + 1e-12)                    # Cauchy-Schwarz invariant still holds
+                assert np.all(Ut <= Up + 1e-12)                                      # never looser
+                tighter += int((Ut < Up - 1e-9).sum())
+                total += Ut.size
+    assert tighter > 0.2 * total
+    # a table with a single shared entry per cluster (every token "rest") is the plain bound
+    r, head, h = _small(seed=31)
+    plain = O.build_index(head["W_bits"], head["b"], head["labels"], r.C)
+    fake = O.OracleIndex(plain.mu, plain.R, plain.bmax, plain.n, plain.perm,
+                         np.stack([plain.R, plain.bmax], axis=1)[:, None, :])
+    h64 = O.bf16_to_f64(h[0])
+    assert np.allclose(O.cluster_bounds(fake, h64)[0], O.cluster_bounds(plain, h64)[0], rtol=1e-14, atol=0)
+    # certified steps stay exact with the tighter bounds, and never open more rows
+    W = O.bf16_to_f64(head["W_bits"])
+    tab = O.build_index(head["W_bits"], head["b"], head["labels"], r.C, bias_table_m=3)
+    for t in range(h.shape[0]):
+        L = O.full_logits(W, head["b"], O.bf16_to_f64(h[t]))
+        for b_, (rp, rt) in enumerate(zip(O.decode_step(W, head["b"], plain, h[t], 5, 1e-3, r.V, logits=L),
+                                          O.decode_step(W, head["b"], tab, h[t], 5, 1e-3, r.V, logits=L))):
+            assert rt["flags"] & O.FLAG_TOPK_CERT and np.array_equal(rt["ids"], O.topk_bruteforce(L[b_], 5)[0])
+            assert O.alg1_step(tab, rt["U"], L[b_], 5, 1e-3, r.V)["n_rows"] <= O.alg1_step(plain, rp["U"], L[b_], 5, 1e-3, r.V)["n_rows"]
