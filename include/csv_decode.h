@@ -49,6 +49,7 @@ extern "C" {
 #define CSV_MAX_CLUSTERS 8192   /* largest C */
 #define CSV_MAX_ROUNDS 8         /* most scoring rounds of a sequence on the sub-vocabulary path */
 #define CSV_MAX_BATCH    256    /* largest B */
+#define CSV_MAX_BIAS_TABLE 8    /* most entries per cluster of the top-m bias table */
 
 typedef struct csv_index csv_index;          /* opaque: permuted W', b', centroids, radii, bias maxima, sizes */
 typedef struct csv_workspace csv_workspace;  /* opaque: per-step device scratch */
@@ -61,6 +62,8 @@ typedef struct {
     float radius_slack;          /* rho >= 0: stored radius = roundup_f32(R_c(1+rho) + rho*||mu_c||) */
     int   centroid_bf16;         /* nonzero: store the centroids rounded to bfloat16 (nearest even) and measure the radii
                                     to the rounded values: the bound stays valid, the bound kernels read half the bytes */
+    int   bias_table_m;          /* >= 2: build the top-m bias table (Section III, "Advanced Theoretical Improvements", bias
+                                    binning; at most CSV_MAX_BIAS_TABLE); 0 or 1: the plain bound */
 } csv_build_opts;
 
 /*
@@ -93,6 +96,19 @@ int csv_index_from_arrays(const uint16_t* d_W, const float* d_b, int V, int d, i
  * been measured to those rounded centroids); otherwise CSV_EINVAL and the index is unchanged.  Allocates C*d*2 bytes.
  */
 int csv_index_use_bf16_centroids(csv_index* idx, void* stream);
+
+/*
+ * Top-m bias table (Section III, "Advanced Theoretical Improvements": bias binning).  Per cluster m pairs
+ * (rho_j, beta_j): the m-1 tokens with the largest biases (equal biases: smaller token id first) each with their own
+ * distance to the centroid and their own bias, and one pair for all other tokens (their largest distance, their
+ * largest bias); unused pairs are (0, -inf).  With a table the bound of a cluster is
+ *   U_c(h) = <mu_c,h> + max_j (rho_j ||h|| + beta_j)  <=  <mu_c,h> + R_c ||h|| + max_i b_i,
+ * still an upper bound of every logit of the cluster, so both certificates hold unchanged.
+ * csv_index_set_bias_table installs a table computed elsewhere (h_table HOST float32[C*m*2], m = 0 removes the table);
+ * csv_index_get_bias_table returns m and, when h_table is not NULL, the table.  Both synchronise.
+ */
+int csv_index_set_bias_table(csv_index* idx, int m, const float* h_table, void* stream);
+int csv_index_get_bias_table(const csv_index* idx, int* m, float* h_table);
 
 /* Copy the metadata back to HOST buffers of the sizes above (any pointer may be NULL to skip it). Synchronous. */
 int csv_index_export(const csv_index* idx, float* h_mu, float* h_R, float* h_bmax, int32_t* h_n, int32_t* h_perm);

@@ -24,14 +24,14 @@ EXPORTS = [
     "csv_workspace_create", "csv_workspace_free", "csv_decode_step", "csv_bounds", "csv_full_logits",
     "csv_profile_begin", "csv_profile_end", "csv_last_error", "csv_kmax_init", "csv_kmax_update",
     "csv_workspace_set_spin_limit", "csv_index_use_bf16_centroids",
-    "csv_workspace_set_tail_split", "csv_bounds_static",
+    "csv_workspace_set_tail_split", "csv_bounds_static", "csv_index_set_bias_table", "csv_index_get_bias_table",
 ]
 PROFILE_STAGES = ["bounds", "round0", "tail"]
 
 
 class BuildOpts(C.Structure):
     _fields_ = [("iters", C.c_int), ("h_init_labels", C.c_void_p), ("h_init_rows", C.c_void_p),
-                ("radius_slack", C.c_float), ("centroid_bf16", C.c_int)]
+                ("radius_slack", C.c_float), ("centroid_bf16", C.c_int), ("bias_table_m", C.c_int)]
 
 
 class StepParams(C.Structure):
@@ -70,6 +70,8 @@ def _load() -> C.CDLL:
     lib.csv_bounds.argtypes = [vp, vp, vp, ci, vp, vp, vp]
     lib.csv_full_logits.argtypes = [vp, vp, vp, ci, vp, vp]
     lib.csv_bounds_static.argtypes = [vp, vp, ci, vp, vp, vp]
+    lib.csv_index_set_bias_table.argtypes = [vp, ci, vp, vp]
+    lib.csv_index_get_bias_table.argtypes = [vp, C.POINTER(ci), vp]
     lib.csv_profile_begin.argtypes = [vp, ci]
     lib.csv_profile_end.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(ci)]
     lib.csv_kmax_init.argtypes = [C.POINTER(KmaxCtl), ci, ci, ci, C.c_double, C.c_double, ci]
@@ -125,6 +127,27 @@ class CsvIndex:
                                     perm.ctypes.data))
         return {"mu": mu, "R": R, "bmax": bmax, "n": n, "perm": perm}
 
+    def set_bias_table(self, table, stream=None) -> None:
+        """table: numpy float32 [C, m, 2] of (radius, bias) pairs, or None to remove the table."""
+        import numpy as np
+        if table is None:
+            _check(lib.csv_index_set_bias_table(self._h, 0, None, _stream(stream)))
+            return
+        t = np.ascontiguousarray(table, dtype=np.float32)
+        assert t.ndim == 3 and t.shape[0] == self.C and t.shape[2] == 2
+        _check(lib.csv_index_set_bias_table(self._h, t.shape[1], t.ctypes.data, _stream(stream)))
+
+    def bias_table(self):
+        """numpy float32 [C, m, 2], or None when the index has no table."""
+        import numpy as np
+        m = C.c_int()
+        _check(lib.csv_index_get_bias_table(self._h, C.byref(m), None))
+        if m.value == 0:
+            return None
+        t = np.empty((self.C, m.value, 2), np.float32)
+        _check(lib.csv_index_get_bias_table(self._h, C.byref(m), t.ctypes.data))
+        return t
+
     def free(self) -> None:
         if self._h:
             lib.csv_index_free(self._h)
@@ -138,7 +161,8 @@ class CsvIndex:
 
 
 def csv_build_index(W: torch.Tensor, b, C_clusters: int, init_labels=None, init_rows=None, iters: int = 0,
-                    radius_slack: float = 2.0 ** -14, stream=None, centroid_bf16: bool = False) -> CsvIndex:
+                    radius_slack: float = 2.0 ** -14, stream=None, centroid_bf16: bool = False,
+                    bias_table_m: int = 0) -> CsvIndex:
     """W: [V,d] 16-bit CUDA tensor (bf16 patterns, original token order); b: float32 CUDA [V] or None.
     init_labels / init_rows: host int32 numpy arrays (see csv_build_opts)."""
     import numpy as np
@@ -146,7 +170,7 @@ def csv_build_index(W: torch.Tensor, b, C_clusters: int, init_labels=None, init_
     V, d = W.shape
     keep = []
     opts = BuildOpts(iters=iters, h_init_labels=None, h_init_rows=None, radius_slack=radius_slack,
-                     centroid_bf16=int(bool(centroid_bf16)))
+                     centroid_bf16=int(bool(centroid_bf16)), bias_table_m=int(bias_table_m))
     if init_labels is not None:
         a = np.ascontiguousarray(init_labels, dtype=np.int32)
         assert a.shape == (V,)

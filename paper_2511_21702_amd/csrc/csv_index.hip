@@ -52,7 +52,7 @@ __device__ __forceinline__ double wave_sum_d(double v) {
 // float64, folded into d2max[c] with an integer atomic max (non-negative doubles order like their bit patterns).
 __global__ __launch_bounds__(256) void row_dist_kernel(const uint16_t* __restrict__ Wp, const int32_t* __restrict__ off,
                                                        const float* __restrict__ mu, int V, int d, int C,
-                                                       unsigned long long* __restrict__ d2max) {
+                                                       unsigned long long* __restrict__ d2max, double* __restrict__ d2row) {
     const int lane = threadIdx.x & 63;
     const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (r >= V) return;
@@ -78,7 +78,104 @@ __global__ __launch_bounds__(256) void row_dist_kernel(const uint16_t* __restric
         }
     }
     acc = wave_sum_d(acc);
-    if (lane == 0) atomicMax(&d2max[lo], (unsigned long long)__double_as_longlong(acc));
+    if (lane == 0) {
+        atomicMax(&d2max[lo], (unsigned long long)__double_as_longlong(acc));
+        if (d2row) d2row[r] = acc;          // squared distance of every row, for the bias table
+    }
+}
+
+// Top-m bias table of one cluster (one block per cluster): the m-1 rows with the largest bias (equal biases: the
+// earlier permuted row, i.e. the smaller token id) get entries of their own (distance to the centroid, bias); the
+// remaining rows share one entry (their largest distance, their largest bias).  Radii are stored like R_c:
+// roundup_f32(r (1+rho) + rho ||mu_c||).  Unused entries are (0, -inf).
+__global__ __launch_bounds__(256) void bias_table_kernel(const float* __restrict__ bp, const int32_t* __restrict__ off,
+                                                         const float* __restrict__ mu, int d, double rho, int m,
+                                                         const double* __restrict__ d2row, float2* __restrict__ bt) {
+    __shared__ float sb[256];
+    __shared__ int si[256];
+    __shared__ double sd[256];
+    __shared__ int picked[CSV_MAX_BIAS_TABLE];
+    __shared__ double mun;
+    const int c = blockIdx.x, tid = threadIdx.x;
+    const int r0 = off[c], r1 = off[c + 1], n = r1 - r0;
+    float2* out = bt + (size_t)c * m;
+    for (int j = tid; j < m; j += 256) out[j] = make_float2(0.f, -INFINITY);
+    if (n == 0) return;
+    {
+        double acc = 0.0;
+        for (int j = tid; j < d; j += 256) acc += (double)mu[(size_t)c * d + j] * (double)mu[(size_t)c * d + j];
+        sd[tid] = acc;
+        __syncthreads();
+        for (int o = 128; o > 0; o >>= 1) {
+            if (tid < o) sd[tid] += sd[tid + o];
+            __syncthreads();
+        }
+        if (tid == 0) mun = sqrt(sd[0]);
+        __syncthreads();
+    }
+    auto store = [&](int slot, double d2, float bias) {
+        const double x = sqrt(d2) * (1.0 + rho) + rho * mun;
+        float y = (float)x;
+        if ((double)y < x) y = nextafterf(y, INFINITY);
+        out[slot] = make_float2(y, bias);
+    };
+    const int ne = min(m - 1, n);
+    for (int e = 0; e < ne; ++e) {
+        // arg-max of (bias, -row) over the rows not picked yet
+        float bb = -INFINITY;
+        int bi = 0x7fffffff;
+        for (int r = r0 + tid; r < r1; r += 256) {
+            bool taken = false;
+            for (int q = 0; q < e; ++q) taken |= picked[q] == r;
+            const float v = bp[r];
+            if (!taken && (v > bb || (v == bb && r < bi))) {
+                bb = v;
+                bi = r;
+            }
+        }
+        sb[tid] = bb;
+        si[tid] = bi;
+        __syncthreads();
+        for (int o = 128; o > 0; o >>= 1) {
+            if (tid < o) {
+                const float v = sb[tid + o];
+                const int i = si[tid + o];
+                if (v > sb[tid] || (v == sb[tid] && i < si[tid])) {
+                    sb[tid] = v;
+                    si[tid] = i;
+                }
+            }
+            __syncthreads();
+        }
+        if (tid == 0) {
+            picked[e] = si[0];
+            store(e, d2row[si[0]], sb[0]);
+        }
+        __syncthreads();
+    }
+    if (n > ne) {       // the rest: largest distance and largest bias among the rows not picked
+        float bb = -INFINITY;
+        double dd = 0.0;
+        for (int r = r0 + tid; r < r1; r += 256) {
+            bool taken = false;
+            for (int q = 0; q < ne; ++q) taken |= picked[q] == r;
+            if (!taken) {
+                bb = fmaxf(bb, bp[r]);
+                dd = fmax(dd, d2row[r]);
+            }
+        }
+        sb[tid] = bb;
+        sd[tid] = dd;
+        __syncthreads();
+        for (int o = 128; o > 0; o >>= 1) {
+            if (tid < o) {
+                sb[tid] = fmaxf(sb[tid], sb[tid + o]);
+                sd[tid] = fmax(sd[tid], sd[tid + o]);
+            }
+            __syncthreads();
+        }
+        if (tid == 0) store(ne, sd[0], sb[0]);
+    }
 }
 
 // Pass 2, one block per cluster: bias maximum, ||mu_c||, the stored radius and ln n_c.
@@ -270,7 +367,7 @@ int csv_index_alloc(int V, int d, int C, csv_index** out) {
 
 extern "C" void csv_index_free(csv_index* x) {
     if (!x) return;
-    void* ptrs[] = {x->Wp, x->bp, x->perm, x->mu, x->mu16, x->R, x->bmax, x->n, x->off, x->lnn, x->cmeta};
+    void* ptrs[] = {x->Wp, x->bp, x->perm, x->mu, x->mu16, x->R, x->bmax, x->n, x->off, x->lnn, x->cmeta, x->bt};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
     free(x);
@@ -369,6 +466,7 @@ extern "C" int csv_build_index(const uint16_t* d_W, const float* d_b, int V, int
     int rc = check_shape(V, d, C);
     if (rc) return rc;
     if (o->iters < 0 || !(o->radius_slack >= 0.f)) { csv_set_error("iters and radius_slack must be >= 0"); return CSV_EINVAL; }
+    if (o->bias_table_m < 0 || o->bias_table_m > CSV_MAX_BIAS_TABLE) { csv_set_error("bias_table_m=%d outside 0..%d", o->bias_table_m, CSV_MAX_BIAS_TABLE); return CSV_EINVAL; }
     if (!o->h_init_labels && !o->h_init_rows) { csv_set_error("need h_init_labels or h_init_rows"); return CSV_EINVAL; }
     hipStream_t st = (hipStream_t)stream;
     csv_index* x = nullptr;
@@ -418,10 +516,23 @@ extern "C" int csv_build_index(const uint16_t* d_W, const float* d_b, int V, int
     }
     if (o->centroid_bf16 && (rc = store_centroids_bf16(x, 0, st))) return fail(rc);
     unsigned long long* d_d2max = nullptr;
+    double* d_d2row = nullptr;
+    const int bt_m = o->bias_table_m >= 2 ? o->bias_table_m : 0;
     if (hipMalloc((void**)&d_d2max, (size_t)C * 8) != hipSuccess) { csv_set_error("out of device memory (radius scratch)"); return fail(CSV_ENOMEM); }
+    if (bt_m && (hipMalloc((void**)&d_d2row, (size_t)V * 8) != hipSuccess || hipMalloc((void**)&x->bt, (size_t)C * bt_m * sizeof(float2)) != hipSuccess)) {
+        (void)hipFree(d_d2max);
+        if (d_d2row) (void)hipFree(d_d2row);
+        csv_set_error("out of device memory (bias table)");
+        return fail(CSV_ENOMEM);
+    }
+    x->bt_m = bt_m;
     bool launched = hipMemsetAsync(d_d2max, 0, (size_t)C * 8, st) == hipSuccess;
     if (launched) {
-        row_dist_kernel<<<(V + 3) / 4, 256, 0, st>>>(x->Wp, x->off, x->mu, V, d, C, d_d2max);
+        row_dist_kernel<<<(V + 3) / 4, 256, 0, st>>>(x->Wp, x->off, x->mu, V, d, C, d_d2max, d_d2row);
+        launched = hipGetLastError() == hipSuccess;
+    }
+    if (launched && bt_m) {
+        bias_table_kernel<<<C, 256, 0, st>>>(x->bp, x->off, x->mu, d, (double)o->radius_slack, bt_m, d_d2row, x->bt);
         launched = hipGetLastError() == hipSuccess;
     }
     if (launched) {
@@ -431,6 +542,7 @@ extern "C" int csv_build_index(const uint16_t* d_W, const float* d_b, int V, int
     if (launched) launched = csv_index_pack_cmeta(x, st) == CSV_OK;
     const bool synced = hipStreamSynchronize(st) == hipSuccess;
     (void)hipFree(d_d2max);
+    if (d_d2row) (void)hipFree(d_d2row);
     if (!launched) { csv_set_error("launch of the radius kernels failed"); return fail(CSV_EHIP); }
     if (!synced) { csv_set_error("index build failed on the device: %s", hipGetErrorString(hipGetLastError())); return fail(CSV_EHIP); }
     (void)hipFree(d_labels);
@@ -489,5 +601,31 @@ extern "C" int csv_index_export(const csv_index* x, float* h_mu, float* h_R, flo
     if (h_bmax) CSV_HIP(hipMemcpy(h_bmax, x->bmax, (size_t)x->C * 4, hipMemcpyDeviceToHost));
     if (h_n) CSV_HIP(hipMemcpy(h_n, x->n, (size_t)x->C * 4, hipMemcpyDeviceToHost));
     if (h_perm) CSV_HIP(hipMemcpy(h_perm, x->perm, (size_t)x->V * 4, hipMemcpyDeviceToHost));
+    return CSV_OK;
+}
+
+extern "C" int csv_index_set_bias_table(csv_index* x, int m, const float* h_table, void* stream) {
+    if (!x) { csv_set_error("null index"); return CSV_EINVAL; }
+    if (m < 0 || m > CSV_MAX_BIAS_TABLE || (m >= 1 && !h_table)) { csv_set_error("bias table: m=%d outside 0..%d, or null table", m, CSV_MAX_BIAS_TABLE); return CSV_EINVAL; }
+    hipStream_t st = (hipStream_t)stream;
+    if (x->bt) {
+        CSV_HIP(hipStreamSynchronize(st));
+        (void)hipFree(x->bt);
+        x->bt = nullptr;
+        x->bt_m = 0;
+    }
+    if (m == 0) return CSV_OK;
+    const size_t bytes = (size_t)x->C * m * sizeof(float2);
+    if (hipMalloc((void**)&x->bt, bytes) != hipSuccess) { csv_set_error("out of device memory (bias table)"); return CSV_ENOMEM; }
+    CSV_HIP(hipMemcpyAsync(x->bt, h_table, bytes, hipMemcpyHostToDevice, st));
+    CSV_HIP(hipStreamSynchronize(st));
+    x->bt_m = m;
+    return CSV_OK;
+}
+
+extern "C" int csv_index_get_bias_table(const csv_index* x, int* m, float* h_table) {
+    if (!x || !m) { csv_set_error("null index or m"); return CSV_EINVAL; }
+    *m = x->bt_m;
+    if (h_table && x->bt_m) CSV_HIP(hipMemcpy(h_table, x->bt, (size_t)x->C * x->bt_m * sizeof(float2), hipMemcpyDeviceToHost));
     return CSV_OK;
 }

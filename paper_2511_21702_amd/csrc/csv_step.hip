@@ -48,6 +48,8 @@ struct StepArgs {
     const int32_t* off;
     const float* lnn;
     const int4* cmeta;      // per cluster {first row, rows, bits of ln n, 0}
+    const float2* bt;       // top-m bias table, [C * bt_m] pairs (radius, bias), or NULL
+    int bt_m;
     float ln_nmax;
     int B, B_max, K_cap, Npad, n_chunks, tile_stride;
     int sp_chunks;     // most STAGE_CAP-sized chunks a sequence's scored rows can span
@@ -130,6 +132,19 @@ __device__ __forceinline__ void reset_step_counters(int* counters, int B, int nt
 }
 
 // ================================================================================================ bounds
+// What a cluster adds to <mu_c,h>: R_c ||h|| + max bias (Eq. "cluster_bound"), or, with a top-m bias table, the
+// largest of its m terms rho_j ||h|| + beta_j (the m-1 tokens with the largest biases one by one, the rest together).
+__device__ __forceinline__ float bound_value(const StepArgs& a, int c, float dot, float Rc, float bm, float hn) {
+    if (!a.bt) return dot + Rc * hn + bm;
+    const float2* t = a.bt + (size_t)c * a.bt_m;
+    float best = -INFINITY;
+    for (int j = 0; j < a.bt_m; ++j) {
+        const float2 e = t[j];
+        best = fmaxf(best, fmaf(e.x, hn, e.y));
+    }
+    return dot + best;
+}
+
 // Block = 8 waves = 8/WPC clusters x WPC column slices (WPC = 1, 2 or 4, chosen so that a wave's slice of the
 // centroid row is at most 8 KB = one batch of eight 128-bit loads per lane), BT sequences per block.
 // Order of requests matters: a wave's loads return in order, so h (needed first, to fill LDS and for ||h||) is
@@ -249,7 +264,7 @@ __global__ __launch_bounds__(BOUND_THREADS) void bound_kernel(StepArgs a, float*
 #pragma unroll
             for (int s = 0; s < BT; ++s) {
                 const float t = wave_sum(acc[s]);
-                if (lane == 0 && s < nb) U_out[(size_t)(b0 + s) * C + c] = ncl == 0 ? -INFINITY : (t + Rc * hn[s] + bm);
+                if (lane == 0 && s < nb) U_out[(size_t)(b0 + s) * C + c] = ncl == 0 ? -INFINITY : bound_value(a, c, t, Rc, bm, hn[s]);
                 acc[s] = 0.f;
             }
         }
@@ -334,7 +349,7 @@ __global__ __launch_bounds__(BOUND_THREADS) void bound1_kernel(StepArgs a, float
         }
         const float hn = sqrtf(th);
         if (blockIdx.x == 0 && wave == 0 && hn_out) hn_out[0] = hn;
-        if (valid) U_out[c] = ncl == 0 ? -INFINITY : (t + Rc * hn + bm);
+        if (valid) U_out[c] = ncl == 0 ? -INFINITY : bound_value(a, c, t, Rc, bm, hn);
     }
 }
 
@@ -478,7 +493,7 @@ __global__ __launch_bounds__(256) void bound_finish_kernel(StepArgs a, const flo
     float u = 0.f;
 #pragma unroll
     for (int ks = 0; ks < BOUND_KS_MAX; ++ks) u += part[ks];
-    U_out[(size_t)b * a.C + c] = nc == 0 ? -INFINITY : (u + Rc * hn + bm);
+    U_out[(size_t)b * a.C + c] = nc == 0 ? -INFINITY : bound_value(a, c, u, Rc, bm, hn);
 }
 
 // ================================================================================================ block scans
@@ -2277,7 +2292,7 @@ static void fill_args(StepArgs& a, const csv_workspace* ws, const csv_index* idx
     memset(&a, 0, sizeof(a));
     a.V = idx->V; a.d = idx->d; a.C = idx->C;
     a.Wp = idx->Wp; a.bp = idx->bp; a.perm = idx->perm; a.mu = idx->mu; a.mu16 = idx->mu16; a.R = idx->R; a.bmax = idx->bmax;
-    a.n = idx->n; a.off = idx->off; a.lnn = idx->lnn; a.cmeta = idx->cmeta; a.ln_nmax = idx->ln_nmax;
+    a.n = idx->n; a.off = idx->off; a.lnn = idx->lnn; a.cmeta = idx->cmeta; a.bt = idx->bt; a.bt_m = idx->bt_m; a.ln_nmax = idx->ln_nmax;
     a.K_cap = ws->K_cap; a.Npad = ws->Npad; a.n_chunks = ws->n_chunks; a.tile_stride = ws->tile_stride; a.sp_chunks = ws->sp_chunks; a.cand_chunks = ws->cand_chunks;
     a.U = ws->U; a.hnorm = ws->hnorm; a.bound_partial = ws->bound_partial; a.st = ws->st; a.sel = ws->sel; a.slog = ws->slog; a.sid = ws->sid; a.slots = ws->slots; a.B_max = ws->B_max;
     a.tiles[0] = ws->tiles[0]; a.tiles[1] = ws->tiles[1]; a.counters = ws->counters;
@@ -2593,7 +2608,7 @@ extern "C" int csv_bounds_static(const csv_index* idx, const uint16_t* d_h, int 
     StepArgs a;
     memset(&a, 0, sizeof(a));
     a.V = idx->V; a.d = idx->d; a.C = idx->C;
-    a.mu = idx->mu; a.mu16 = idx->mu16; a.R = idx->R; a.bmax = idx->bmax; a.n = idx->n;
+    a.mu = idx->mu; a.mu16 = idx->mu16; a.R = idx->R; a.bmax = idx->bmax; a.n = idx->n; a.bt = idx->bt; a.bt_m = idx->bt_m;
     a.B = B; a.h = d_h;
     if (B > 8) {                       // the batched product is the only bound kernel with scratch: KS x B x C partial sums
         int KS, kbs;

@@ -19,7 +19,8 @@ def log(msg: str) -> None:
 
 class Case:
     def __init__(self, recipe: synth.Recipe, seed: int = synth.SEED, bias: bool = True, radius_slack: float = 2.0 ** -14,
-                 labels=None, B_max=None, K_cap=None, want_W64: bool = True, W_bits=None, centroid_bf16: bool = False):
+                 labels=None, B_max=None, K_cap=None, want_W64: bool = True, W_bits=None, centroid_bf16: bool = False,
+                 bias_table_m: int = 0, b=None):
         import torch
         import paper_2511_21702_amd as csv
         self.csv, self.torch = csv, torch
@@ -28,13 +29,13 @@ class Case:
         self.head = synth.make_head(recipe, seed=seed, threads=16)
         if W_bits is not None:                      # a hand-made matrix in place of the generated one
             self.head = dict(self.head, W_bits=np.ascontiguousarray(W_bits))
-        self.b = self.head["b"] if bias else None
+        self.b = (self.head["b"] if b is None else b) if bias else None
         self.labels = self.head["labels"] if labels is None else labels
         self.C = recipe.C if labels is None else int(np.max(labels)) + 1
         log(f"[{recipe.name}] head V={recipe.V} d={recipe.d} C={self.C} generated in {time.time() - t0:.1f}s")
         t0 = time.time()
         self.oidx = O.build_index(self.head["W_bits"], self.b, self.labels, self.C, radius_slack=radius_slack,
-                                  centroid_bf16=centroid_bf16)
+                                  centroid_bf16=centroid_bf16, bias_table_m=bias_table_m)
         log(f"[{recipe.name}] oracle index in {time.time() - t0:.1f}s")
         self.W64 = O.bf16_to_f64(self.head["W_bits"]) if want_W64 else None
         self.dW = csv.bits_to_device(self.head["W_bits"])
@@ -42,6 +43,8 @@ class Case:
         self.gidx = csv.csv_index_from_arrays(self.dW, self.db, self.oidx.mu, self.oidx.R, self.oidx.bmax,
                                               self.oidx.n.astype(np.int32), self.oidx.perm.astype(np.int32),
                                               centroid_bf16=centroid_bf16)
+        if self.oidx.bias_table is not None:
+            self.gidx.set_bias_table(self.oidx.bias_table)
         self.ws = csv.CsvWorkspace(self.gidx, B_max or recipe.B, K_cap if K_cap is not None else recipe.K_max_rows)
         torch.cuda.synchronize()
 

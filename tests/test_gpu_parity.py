@@ -525,6 +525,62 @@ def test_build_index_kmeans_matches_oracle_lloyd():
     g.free(); case.close()
 
 
+# ------------------------------------------------------------------ top-m bias table (Section III, bias binning)
+def _outlier_bias(r, seed):
+    head = synth.make_head(r, seed=seed, threads=4)
+    rng = np.random.default_rng(seed)
+    b = head["b"].copy()
+    b[rng.integers(0, r.V, r.V // 40)] += rng.normal(0, 1.0, r.V // 40).astype(np.float32)
+    return b
+
+
+@pytest.mark.parametrize("B,m,bf16", [(1, 2, False), (3, 3, False), (8, 8, True), (20, 3, False)])
+def test_bias_table_bounds_and_steps(B, m, bf16):
+    # every bound kernel variant with a table installed from the oracle's, then whole steps on the tighter bounds
+    r = synth.small_recipe(f"bt-{B}-{m}", V=3001, d=264, C=37, B=B, steps=3, h_mode="mix", iso_frac=0.2, sizes="zipf")
+    case = Case(r, seed=81, b=_outlier_bias(r, 81), bias_table_m=m, centroid_bf16=bf16)
+    csv = case.csv
+    plain = O.build_index(case.head["W_bits"], case.b, case.labels, r.C, centroid_bf16=bf16)
+    h = case.hidden()
+    dh = csv.bits_to_device(h)
+    tighter = 0
+    for s in range(h.shape[0]):
+        Ug, hg = csv.csv_bounds(case.ws, case.gidx, dh[s])
+        Ug = Ug.cpu().numpy()
+        h64 = O.bf16_to_f64(h[s])
+        U, hn = O.cluster_bounds(case.oidx, h64)
+        Up, _ = O.cluster_bounds(plain, h64)
+        assert np.all(np.abs(Ug - U) <= 1e-5 * np.maximum(1.0, np.abs(U)))
+        tighter += int((U < Up - 1e-6).sum())
+        L = O.full_logits(case.W64, case.b, h64)
+        assert np.all(L <= Ug[:, case.labels].astype(np.float64) + 1e-4)          # the float32 bounds still dominate the logits
+    assert tighter > 0
+    t = case.run_steps(h, 5, 1e-3, r.K_max_rows, O.COMBINE_ALL, f"bias table B={B} m={m}")
+    _finish(t, f"bias table B={B} m={m}")
+    case.close()
+
+
+def test_bias_table_built_on_the_gpu_matches_oracle():
+    r = synth.small_recipe("bt-build", V=5000, d=264, C=40, B=2, steps=2, sizes="zipf", zipf_min=1)
+    b = _outlier_bias(r, 82)
+    b[::7] = b[3]                                                    # many equal biases: the tie-break decides who is picked
+    case = Case(r, seed=82, b=b, bias_table_m=4)
+    csv = case.csv
+    g = csv.csv_build_index(case.dW, case.db, r.C, init_labels=case.labels.astype(np.int32), iters=0, bias_table_m=4)
+    tg, to = g.bias_table(), case.oidx.bias_table
+    assert tg.shape == to.shape == (r.C, 4, 2)
+    assert np.array_equal(tg[:, :, 1], to[:, :, 1])                  # the same tokens picked, the same shared bias
+    ulp = np.abs(tg[:, :, 0].view(np.int32).astype(np.int64) - to[:, :, 0].view(np.int32).astype(np.int64))
+    log(f"  bias table radii: ulp diff max {ulp.max()}")
+    assert ulp.max() <= 2
+    assert csv.csv_build_index(case.dW, case.db, r.C, init_labels=case.labels.astype(np.int32), bias_table_m=1).bias_table() is None
+    with pytest.raises(csv.CsvError):
+        csv.csv_build_index(case.dW, case.db, r.C, init_labels=case.labels.astype(np.int32), bias_table_m=9)
+    g.set_bias_table(None)
+    assert g.bias_table() is None
+    g.free(); case.close()
+
+
 # ------------------------------------------------------------------ top-p (nucleus) certificate, delta form
 def test_nucleus_certificate_on_the_gpu():
     # Section III, top-p certification: a step run with eps = delta / (1 + delta) carries the coverage certificate.
