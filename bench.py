@@ -41,6 +41,7 @@ def main() -> int:
     ap.add_argument("--max-rounds", type=int, default=0, help="fallback levels: scoring rounds allowed (0 = the two-round schedule)")
     ap.add_argument("--delta-clusters", type=int, default=0, help="fallback levels: clusters per partial expansion (0 = off)")
     ap.add_argument("--bf16-centroids", action="store_true", help="index option: centroids stored as bfloat16 (half the bound kernel's bytes)")
+    ap.add_argument("--bias-table", type=int, default=0, help="index option: top-m bias table (Section III, bias binning), m = 2..8")
     ap.add_argument("--relax", action="store_true", help="fallback levels: accept the softmax bound at 2 eps before falling back")
     ap.add_argument("--cpu-steps", type=int, default=-1, help="oracle steps to time (-1: sized to ~15 s, 0: skip)")
     ap.add_argument("--traffic-probe", action="store_true",
@@ -66,7 +67,8 @@ def main() -> int:
     log(f"[bench] {r.name}: V={r.V} d={r.d} C={r.C} B={r.B} generated in {time.time() - t0:.1f}s")
     dW = csv.bits_to_device(head["W_bits"])
     db = torch.from_numpy(head["b"]).cuda()
-    idx = csv.csv_build_index(dW, db, r.C, init_labels=head["labels"].astype(np.int32), centroid_bf16=args.bf16_centroids)
+    idx = csv.csv_build_index(dW, db, r.C, init_labels=head["labels"].astype(np.int32), centroid_bf16=args.bf16_centroids,
+                              bias_table_m=args.bias_table)
     del dW
     ws = csv.CsvWorkspace(idx, r.B, r.K_max_rows)
     dh = csv.bits_to_device(h_bits)
@@ -157,6 +159,24 @@ def main() -> int:
             rounds_hist[int(v)] += 1
     n_seq = nstat * r.B
     fb_rate = int(buf_s.fallback_count.item()) / n_seq
+    # bound tightness xi = (largest logit of a cluster) / (its bound), Section III-A "Bound Quality Analysis", averaged over
+    # the clusters the certified sequences opened; logits and bounds from the library's own entry points, a few steps
+    lab = torch.from_numpy(head["labels"].astype(np.int64)).cuda()
+    xi_sum, xi_n = 0.0, 0
+    for s in range(W, W + min(8, nstat)):
+        csv.csv_decode_step_raw(ws, idx, hp[s], r.B, buf_s, sp)
+        Lf = csv.csv_full_logits(ws, idx, dh[s % nh])
+        Ub, _ = csv.csv_bounds(ws, idx, dh[s % nh])
+        cmax = torch.full((r.B, r.C), float("-inf"), device="cuda").scatter_reduce_(1, lab.expand(r.B, -1), Lf, "amax")
+        torch.cuda.synchronize()
+        fl = buf_s.flags.cpu().numpy(); nc = buf_s.n_clusters.cpu().numpy(); sel = buf_s.sel_clusters.cpu().numpy()
+        ratio = (cmax / Ub).cpu().numpy()
+        for b in np.flatnonzero((fl & csv.FLAG_FALLBACK) == 0):
+            v = ratio[b, sel[b, :nc[b]]]
+            v = v[np.isfinite(v)]
+            xi_sum += float(v.sum()); xi_n += v.size
+    xi = xi_sum / xi_n if xi_n else None
+    del lab
     lat = np.sort(np.array(lat))
 
     # ---------------- full-vocabulary baseline at the same B (in-repo kernel)
@@ -308,6 +328,7 @@ def main() -> int:
         "config": {"workload": f"{r.name}: V={r.V} d={r.d} C={r.C} B={r.B} k={r.k} eps={r.eps:g} K_max={r.K_max_rows} "
                                f"combine=ALL, bf16 W and h, float32 accumulation, planted clusters"
                                + (", bf16 centroids" if args.bf16_centroids else "")
+                               + (f", top-{args.bias_table} bias table" if args.bias_table >= 2 else "")
                                + (f", fallback levels max_rounds={args.max_rounds} delta_clusters={args.delta_clusters} relax={int(args.relax)}"
                                   if (args.max_rounds or args.delta_clusters or args.relax) else ""), "batch": r.B},
         "roofline": roof,
@@ -323,6 +344,7 @@ def main() -> int:
         "sub_vocab_ratio": mean_rows_seq / r.V, "rounds_hist": {k: v for k, v in rounds_hist.items() if v or k <= 2},
         "relaxed_rate": n_relaxed / n_seq,
         "sharing_factor": sharing,
+        "bound_tightness_xi": xi,
         "full_gemv": {"ms_per_step": full_ms, "steps_per_s": 1e3 / full_ms, "GBps": full_bytes / (full_ms * 1e-3) / 1e9},
         "speedup_vs_full_gemv": full_ms / ms_per_step,
     }

@@ -138,6 +138,7 @@ typedef struct {
                               within the budget) and test again; 0 = off */
     int   relax;           /* nonzero: when no further expansion is possible, accept a step whose softmax tail bound
                               holds at 2*eps (flag SOFTMAX_RELAXED) before falling back to the full vocabulary */
+    float top_p;           /* nucleus mass for d_nucleus, in 0..1 (0 = none); see csv_step_out */
 } csv_step_params;
 
 typedef struct {
@@ -152,6 +153,16 @@ typedef struct {
                                  in bound order, then the clusters of each later round by ascending id; untouched
                                  on fallback */
     unsigned long long* d_fallback_count; /* or NULL: incremented once per sequence that falls back */
+    /* Certified sub-vocabulary distribution over the returned list, in its order (Section III, top-p certification;
+       each may be NULL; k >= 1):
+       p~_t = exp(l_t - lse), the probabilities of the softmax restricted to the scored rows S; with SOFTMAX_CERT (or after
+       fallback, eps = 0) the full-vocabulary probability of token t lies in [(1 - eps) p~_t, p~_t], because at most eps of
+       the mass lies outside S;  the running sums of p~ in list order;  the length of the shortest prefix of the list whose
+       running sum reaches params.top_p (0: top_p is 0, or the list ends before that mass): that prefix covers at least
+       (1 - eps) top_p of the full-vocabulary mass.  Entries past the scored rows (k > |S|) have p~ = 0. */
+    float*    d_probs;        /* [B*k] */
+    float*    d_cum;          /* [B*k] */
+    int32_t*  d_nucleus;      /* [B]   */
 } csv_step_out;
 
 /*

@@ -538,6 +538,21 @@ def nucleus_eps(delta: float) -> float:
     return delta / (1.0 + delta)
 
 
+def certified_distribution(logits: np.ndarray, lse: float, top_p: float = 0.0):
+    """Sub-vocabulary distribution over a returned list (Section III, top-p certification): p~_t = exp(l_t - Z_S) in
+    list order, its running sums, and the length of the shortest prefix whose running sum reaches top_p (0 when
+    top_p is 0 or the list ends first).  With the eps-softmax certificate at most eps of the mass lies outside S, so
+    the full-vocabulary probability of token t is within [(1 - eps) p~_t, p~_t] and a prefix with running sum >= top_p
+    covers at least (1 - eps) top_p of the full-vocabulary mass."""
+    p = np.exp(np.asarray(logits, dtype=np.float64) - lse)
+    cum = np.cumsum(p)
+    nucleus = 0
+    if top_p > 0:
+        hit = np.flatnonzero(cum >= top_p)
+        nucleus = int(hit[0]) + 1 if hit.size else 0
+    return p, cum, nucleus
+
+
 def nucleus_holds(index: OracleIndex, U_row: np.ndarray, opened: np.ndarray, Z_S: float, delta: float) -> bool:
     """The delta-form written out: sum over unopened, non-empty clusters of n_c e^{U_c} <= delta e^{Z_S}."""
     mask = np.ones(index.C, dtype=bool)

@@ -36,7 +36,7 @@ class BuildOpts(C.Structure):
 
 class StepParams(C.Structure):
     _fields_ = [("k", C.c_int), ("eps", C.c_float), ("K_max_rows", C.c_int), ("combine", C.c_int),
-                ("max_rounds", C.c_int), ("delta_clusters", C.c_int), ("relax", C.c_int)]
+                ("max_rounds", C.c_int), ("delta_clusters", C.c_int), ("relax", C.c_int), ("top_p", C.c_float)]
 
 
 class KmaxCtl(C.Structure):
@@ -47,7 +47,8 @@ class KmaxCtl(C.Structure):
 class StepOut(C.Structure):
     _fields_ = [("d_ids", C.c_void_p), ("d_logits", C.c_void_p), ("d_lse", C.c_void_p), ("d_flags", C.c_void_p),
                 ("d_n_rows", C.c_void_p), ("d_n_clusters", C.c_void_p), ("d_rounds", C.c_void_p),
-                ("d_sel_clusters", C.c_void_p), ("d_fallback_count", C.c_void_p)]
+                ("d_sel_clusters", C.c_void_p), ("d_fallback_count", C.c_void_p),
+                ("d_probs", C.c_void_p), ("d_cum", C.c_void_p), ("d_nucleus", C.c_void_p)]
 
 
 def _load() -> C.CDLL:
@@ -264,11 +265,14 @@ class StepBuffers:
     fallback_count: torch.Tensor
     params: StepParams
     out: StepOut
+    probs: torch.Tensor | None = None
+    cum: torch.Tensor | None = None
+    nucleus: torch.Tensor | None = None
 
 
 def make_step_buffers(index: CsvIndex, B: int, k: int, eps: float, K_max_rows: int, combine: int = COMBINE_ALL,
                       want_sel: bool = False, device="cuda", max_rounds: int = 0, delta_clusters: int = 0,
-                      relax: bool = False) -> StepBuffers:
+                      relax: bool = False, want_dist: bool = False, top_p: float = 0.0) -> StepBuffers:
     kk = max(k, 1)
     ids = torch.full((B, kk), -2, dtype=torch.int32, device=device)
     logits = torch.zeros((B, kk), dtype=torch.float32, device=device)
@@ -279,11 +283,16 @@ def make_step_buffers(index: CsvIndex, B: int, k: int, eps: float, K_max_rows: i
     rounds = torch.zeros(B, dtype=torch.int32, device=device)
     sel = torch.full((B, index.C), -1, dtype=torch.int32, device=device) if want_sel else None
     fbc = torch.zeros(1, dtype=torch.int64, device=device)
+    probs = torch.full((B, kk), -1.0, dtype=torch.float32, device=device) if want_dist else None
+    cum = torch.full((B, kk), -1.0, dtype=torch.float32, device=device) if want_dist else None
+    nucleus = torch.full((B,), -1, dtype=torch.int32, device=device) if want_dist else None
     params = StepParams(k=k, eps=eps, K_max_rows=K_max_rows, combine=combine, max_rounds=max_rounds,
-                        delta_clusters=delta_clusters, relax=int(bool(relax)))
+                        delta_clusters=delta_clusters, relax=int(bool(relax)), top_p=top_p)
     out = StepOut(ids.data_ptr(), logits.data_ptr(), lse.data_ptr(), flags.data_ptr(), n_rows.data_ptr(),
-                  n_clusters.data_ptr(), rounds.data_ptr(), sel.data_ptr() if want_sel else None, fbc.data_ptr())
-    return StepBuffers(ids, logits, lse, flags, n_rows, n_clusters, rounds, sel, fbc, params, out)
+                  n_clusters.data_ptr(), rounds.data_ptr(), sel.data_ptr() if want_sel else None, fbc.data_ptr(),
+                  probs.data_ptr() if want_dist else None, cum.data_ptr() if want_dist else None,
+                  nucleus.data_ptr() if want_dist else None)
+    return StepBuffers(ids, logits, lse, flags, n_rows, n_clusters, rounds, sel, fbc, params, out, probs, cum, nucleus)
 
 
 def csv_decode_step(ws: CsvWorkspace, index: CsvIndex, h: torch.Tensor, buf: StepBuffers, stream=None) -> StepBuffers:

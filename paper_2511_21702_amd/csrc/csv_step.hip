@@ -79,6 +79,7 @@ struct StepArgs {
     int max_rounds, delta_clusters, relax;   // fallback levels
     float lam;   // ln(eps/(1-eps)); +inf when eps >= 1
     float lam2;  // the same for the relaxed tolerance 2 eps
+    float top_p; // nucleus mass asked for (0 = none)
     csv_step_out out;
 #ifdef CSV_DEBUG_TIMING
     unsigned long long* dbg;   // [B*64] wall-clock marks of the per-sequence kernels (debug builds only)
@@ -549,7 +550,10 @@ __device__ __forceinline__ void write_invalid(const StepArgs& a, int b) {
     for (int t = threadIdx.x; t < a.k; t += blockDim.x) {
         a.out.d_ids[(size_t)b * a.k + t] = -1;
         a.out.d_logits[(size_t)b * a.k + t] = NAN;
+        if (a.out.d_probs) a.out.d_probs[(size_t)b * a.k + t] = NAN;
+        if (a.out.d_cum) a.out.d_cum[(size_t)b * a.k + t] = NAN;
     }
+    if (threadIdx.x == 0 && a.out.d_nucleus) a.out.d_nucleus[b] = 0;
     if (threadIdx.x == 0) {
         a.out.d_lse[b] = NAN;
         a.out.d_flags[b] = CSV_FLAG_INVALID_INPUT;
@@ -1219,6 +1223,33 @@ __device__ __forceinline__ u64 softmax_prefix_key(const StepArgs& a, const Clust
     return skeys[max(best, 1) - 1];
 }
 
+// ================================================================================================ certified distribution
+// Optional outputs (Section III, top-p certification): over the returned list, in its order, the sub-vocabulary
+// probabilities p~_t = exp(l_t - Z_S), their running sums, and the length of the shortest prefix whose running sum
+// reaches top_p (0: not reached within the list).  kk entries of s.wval are valid; Z is the log-sum-exp that goes
+// to d_lse.  Every thread of the block calls.  Each running sum is taken in list order by one thread.
+__device__ __forceinline__ void write_distribution(const StepArgs& a, int b, int kk, float Z, SeqShared& s) {
+    if (!a.out.d_probs && !a.out.d_cum && !a.out.d_nucleus) return;
+    const int tid = threadIdx.x, nt = blockDim.x;
+    int below = 0;
+    for (int t = tid; t < a.k; t += nt) {
+        float p = 0.f, cum = 0.f;
+        const int last = min(t, kk - 1);
+        for (int j = 0; j <= last; ++j) {
+            const float pj = expf(s.wval[j] - Z);
+            cum += pj;
+            if (j == t) p = pj;
+        }
+        if (a.out.d_probs) a.out.d_probs[(size_t)b * a.k + t] = p;
+        if (a.out.d_cum) a.out.d_cum[(size_t)b * a.k + t] = cum;
+        below += (t < kk && cum < a.top_p) ? 1 : 0;
+    }
+    if (a.out.d_nucleus) {
+        below = block_sum_i(below, s.redi);
+        if (tid == 0) a.out.d_nucleus[b] = (a.top_p > 0.f && below < kk) ? below + 1 : 0;
+    }
+}
+
 // ================================================================================================ certification
 // One block per sequence.  round 0: certify, or plan round 1 (or fall back on budget); round 1: certify or fall back.
 // Sequences with more than STAGE_CAP scored rows are handled by several blocks: each takes one chunk of STAGE_CAP
@@ -1313,6 +1344,7 @@ __device__ __forceinline__ void cert_body(const StepArgs& a, int b, int chunk, i
             a.out.d_ids[(size_t)b * a.k + t] = s.wid[t];
             a.out.d_logits[(size_t)b * a.k + t] = s.wval[t];
         }
+        if (a.use_k) write_distribution(a, b, min(a.k, n), Z, s);
         if (a.out.d_sel_clusters)
             for (int j = tid; j < st.n_open; j += nt) a.out.d_sel_clusters[(size_t)b * C + j] = a.sel[(size_t)b * C + j];
         if (tid == 0) {
@@ -2045,6 +2077,7 @@ __device__ __forceinline__ void fb_final_device(const StepArgs& a, int slot, Seq
             a.out.d_ids[(size_t)b * a.k + t] = s.wid[t];
             a.out.d_logits[(size_t)b * a.k + t] = s.wval[t];
         }
+        write_distribution(a, b, min(a.k, a.V), mx + logf(sm), s);
     }
     if (tid == 0) {
         a.out.d_lse[b] = mx + logf(sm);
@@ -2660,6 +2693,8 @@ extern "C" int csv_decode_step(csv_workspace* ws, const csv_index* idx, const ui
     else if (p->eps >= 1.f) a.lam = INFINITY;
     else a.lam = (float)log((double)p->eps / (1.0 - (double)p->eps));
     a.max_rounds = max_rounds; a.delta_clusters = p->delta_clusters; a.relax = p->relax != 0;
+    if (!(p->top_p >= 0.f && p->top_p <= 1.f)) { csv_set_error("top_p=%g outside 0..1", (double)p->top_p); return CSV_EINVAL; }
+    a.top_p = p->top_p;
     if (!use_s) a.lam2 = -INFINITY;
     else if (2.0 * (double)p->eps >= 1.0) a.lam2 = INFINITY;
     else a.lam2 = (float)log(2.0 * (double)p->eps / (1.0 - 2.0 * (double)p->eps));

@@ -632,6 +632,47 @@ def test_nucleus_certificate_on_the_gpu():
     case.close()
 
 
+def test_certified_distribution_outputs():
+    # optional outputs: sub-vocabulary probabilities of the returned list, their running sums, the nucleus length
+    r = synth.small_recipe("dist", V=6000, d=136, C=60, B=5, steps=8, k=40, eps=5e-3, h_mode="mix", sizes="zipf",
+                           row_noise=0.6, iso_frac=0.2)
+    case = Case(r, seed=72, K_cap=6000)
+    csv = case.csv
+    h = case.hidden()
+    dh = csv.bits_to_device(h)
+    seen_nuc = seen_none = seen_fb = 0
+    for top_p in (0.9, 0.5, 0.0):
+        buf = csv.make_step_buffers(case.gidx, r.B, r.k, r.eps, 3000, want_sel=True, want_dist=True, top_p=top_p)
+        for s in range(h.shape[0]):
+            csv.csv_decode_step(case.ws, case.gidx, dh[s], buf)
+            torch.cuda.synchronize()
+            g = PAR.gpu_step_to_numpy(buf)
+            probs, cum, nuc = buf.probs.cpu().numpy(), buf.cum.cpu().numpy(), buf.nucleus.cpu().numpy()
+            L = O.full_logits(case.W64, case.b, O.bf16_to_f64(h[s]))
+            for b in range(r.B):
+                # the definition applied to the list the GPU returned (its own logits and log-sum-exp were compared elsewhere)
+                p, c, n = O.certified_distribution(g["logits"][b].astype(np.float64), float(g["lse"][b]), top_p)
+                assert np.allclose(probs[b], p, rtol=2e-5, atol=1e-9) and np.allclose(cum[b], c, rtol=2e-5, atol=1e-9), (s, b)
+                edge = top_p > 0 and np.any(np.abs(c - top_p) < 1e-5)
+                assert nuc[b] == n or edge, (s, b, nuc[b], n)
+                seen_nuc += n > 0
+                seen_none += n == 0 and top_p > 0
+                fb = bool(g["flags"][b] & O.FLAG_FALLBACK)
+                seen_fb += fb
+                # against the full vocabulary: true probabilities are bracketed by the certified ones
+                if g["flags"][b] & O.FLAG_SOFTMAX_CERT:
+                    true = np.exp(L[b][g["ids"][b]] - O.logsumexp(L[b]))
+                    eps = 0.0 if fb else r.eps
+                    assert np.all(true <= probs[b] * (1 + 1e-4)) and np.all(true >= (1 - eps) * probs[b] * (1 - 1e-4)), (s, b)
+                    if nuc[b] > 0:
+                        assert true[:nuc[b]].sum() >= (1 - eps) * top_p * (1 - 1e-4)
+    log(f"[dist] nucleus found {seen_nuc}, list too short {seen_none}, fallback sequences {seen_fb}")
+    assert seen_nuc > 20 and seen_fb > 0
+    with pytest.raises(csv.CsvError):
+        csv.csv_decode_step(case.ws, case.gidx, dh[0], csv.make_step_buffers(case.gidx, r.B, r.k, r.eps, 3000, top_p=1.5))
+    case.close()
+
+
 # ------------------------------------------------------------------ what the bench runs: index built on the GPU, full size
 def test_c2_index_built_on_the_gpu_and_steps_on_it():
     # bench.py and smoke() build their index with csv_build_index from the planted labels; here that index is

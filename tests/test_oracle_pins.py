@@ -752,3 +752,36 @@ def test_bias_table_keeps_the_bound_sound_and_never_loosens_it():
                                           O.decode_step(W, head["b"], tab, h[t], 5, 1e-3, r.V, logits=L))):
             assert rt["flags"] & O.FLAG_TOPK_CERT and np.array_equal(rt["ids"], O.topk_bruteforce(L[b_], 5)[0])
             assert O.alg1_step(tab, rt["U"], L[b_], 5, 1e-3, r.V)["n_rows"] <= O.alg1_step(plain, rp["U"], L[b_], 5, 1e-3, r.V)["n_rows"]
+
+
+def test_certified_distribution_brackets_the_true_probabilities():
+    # p~ over all of S sums to one; the true probabilities lie in [(1 - eps) p~, p~] for a certified step; the nucleus is
+    # the shortest prefix reaching top_p (checked by enumeration) and covers (1 - eps) top_p of the true mass
+    r = synth.small_recipe(V=1500, d=48, C=30, B=1, steps=20, k=40, eps=5e-3, h_mode="mix", row_noise=0.3)
+    head = synth.make_head(r)
+    h = synth.make_hidden(r, head["centers"], steps=20)
+    W64 = O.bf16_to_f64(head["W_bits"])
+    idx = O.build_index(head["W_bits"], head["b"], head["labels"], r.C)
+    p1, c1, n1 = O.certified_distribution(np.log(np.array([0.5, 0.25, 0.125, 0.125])), 0.0, 0.8)
+    assert np.allclose(p1, [0.5, 0.25, 0.125, 0.125], rtol=1e-15) and np.allclose(c1, [0.5, 0.75, 0.875, 1.0], rtol=1e-15) and n1 == 3
+    assert O.certified_distribution(np.log(np.array([0.5, 0.25])), 0.0, 0.8)[2] == 0          # the list ends first
+    assert O.certified_distribution(np.log(np.array([0.5, 0.5])), 0.0, 0.0)[2] == 0           # no nucleus asked for
+    seen = 0
+    for s in range(20):
+        L = O.full_logits(W64, head["b"], O.bf16_to_f64(np.atleast_2d(h[s])))
+        res = O.decode_step(W64, head["b"], idx, h[s], r.k, r.eps, r.K_max_rows, logits=L)[0]
+        if res["flags"] & O.FLAG_FALLBACK or not res["flags"] & O.FLAG_SOFTMAX_CERT:
+            continue
+        seen += 1
+        p, cum, nuc = O.certified_distribution(res["logits"], res["lse"], 0.9)
+        true = np.exp(L[0][res["ids"]] - O.logsumexp(L[0]))
+        assert np.all(true <= p * (1 + 1e-12)) and np.all(true >= (1 - r.eps) * p * (1 - 1e-12))
+        assert np.all(np.diff(cum) >= 0) and cum[-1] <= 1 + 1e-12
+        want = next((j + 1 for j in range(len(p)) if sum(p[:j + 1]) >= 0.9), 0)
+        assert nuc == want
+        if nuc:
+            assert true[:nuc].sum() >= (1 - r.eps) * 0.9
+        S = np.concatenate([idx.rows(c) for c in res["clusters"]])
+        allp, _, _ = O.certified_distribution(L[0][S], res["lse"])
+        assert math.isclose(allp.sum(), 1.0, rel_tol=1e-12)
+    assert seen > 10
