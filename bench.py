@@ -44,6 +44,9 @@ def main() -> int:
     ap.add_argument("--bias-table", type=int, default=0, help="index option: top-m bias table (Section III, bias binning), m = 2..8")
     ap.add_argument("--relax", action="store_true", help="fallback levels: accept the softmax bound at 2 eps before falling back")
     ap.add_argument("--cpu-steps", type=int, default=-1, help="oracle steps to time (-1: sized to ~15 s, 0: skip)")
+    ap.add_argument("--kmeans", type=int, default=-1, metavar="ITERS",
+                    help="time the offline index build instead: Lloyd's k-means with ITERS iterations from the default seeding "
+                         "rule on the config's head (Section IV, offline preprocessing); prints its own JSON line and exits")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="for `rocprofv3 --pmc FETCH_SIZE|WRITE_SIZE`: launch a device-to-device copy of known size, "
                          "the bound kernel and a few whole steps, then exit (no timing, no JSON)")
@@ -67,6 +70,30 @@ def main() -> int:
     log(f"[bench] {r.name}: V={r.V} d={r.d} C={r.C} B={r.B} generated in {time.time() - t0:.1f}s")
     dW = csv.bits_to_device(head["W_bits"])
     db = torch.from_numpy(head["b"]).cuda()
+    if args.kmeans >= 0:
+        csv.csv_build_index(dW, db, r.C, iters=0).free()           # warm-up (module load, allocations)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        kidx = csv.csv_build_index(dW, db, r.C, iters=args.kmeans)
+        torch.cuda.synchronize()
+        sec = time.perf_counter() - t1
+        e = kidx.export()
+        # how well the planted clusters were found: share of tokens whose cluster holds mostly tokens of their planted cluster
+        lab = np.empty(r.V, dtype=np.int64)
+        off = np.concatenate([[0], np.cumsum(e["n"])])
+        for c in range(r.C):
+            lab[e["perm"][off[c]:off[c + 1]]] = c
+        pairs = np.stack([lab, head["labels"].astype(np.int64)], 1)
+        uniq, cnt = np.unique(pairs, axis=0, return_counts=True)
+        purity = sum(cnt[uniq[:, 0] == c].max() for c in np.unique(lab)) / r.V
+        flops = 2.0 * r.V * r.C * r.d * (args.kmeans + 1)
+        print(json.dumps({"metric": "offline k-means index build", "config": {"workload": f"{r.name}: V={r.V} d={r.d} C={r.C}"},
+                          "lloyd_iterations": args.kmeans, "assignments": args.kmeans + 1, "seconds": sec,
+                          "distance_product_TFLOPs_useful": flops / sec / 1e12,
+                          "note": "whole build: every assignment (MFMA distance product, three bf16 pieces per float32 centroid value), "
+                                  "host-side layout, row gather, centroid means; then radii and metadata",
+                          "empty_clusters": int((e["n"] == 0).sum()), "largest_cluster": int(e["n"].max()), "purity_vs_planted": float(purity)}))
+        return 0
     idx = csv.csv_build_index(dW, db, r.C, init_labels=head["labels"].astype(np.int32), centroid_bf16=args.bf16_centroids,
                               bias_table_m=args.bias_table)
     del dW

@@ -58,7 +58,8 @@ typedef struct {
     int iters;                   /* Lloyd iterations to run (0 = keep the starting assignment) */
     const int32_t* h_init_labels;/* HOST int32[V] starting cluster of each token, or NULL */
     const int32_t* h_init_rows;  /* HOST int32[C] tokens whose rows are the starting centroids; used when
-                                    h_init_labels is NULL */
+                                    h_init_labels is NULL.  Both NULL: the seeding rule is C tokens evenly spread over
+                                    the vocabulary, token floor(c * V / C) for cluster c */
     float radius_slack;          /* rho >= 0: stored radius = roundup_f32(R_c(1+rho) + rho*||mu_c||) */
     int   centroid_bf16;         /* nonzero: store the centroids rounded to bfloat16 (nearest even) and measure the radii
                                     to the rounded values: the bound stays valid, the bound kernels read half the bytes */
@@ -69,7 +70,9 @@ typedef struct {
 /*
  * Offline preprocessing (Section III-A.1, Section IV "Offline Preprocessing").
  * Clusters the rows of W into C clusters by Lloyd's k-means (nearest centroid in squared Euclidean distance,
- * ties to the smaller cluster id; an empty cluster keeps its centroid), then forms for every cluster the
+ * ties to the smaller cluster id; an empty cluster keeps its centroid; the distances are evaluated as
+ * ||mu_c||^2 - 2 <W_i,mu_c> with an MFMA product in float32, so two centroids whose distances to a row agree to
+ * about 1e-5 of ||mu||^2 may be told apart differently than in exact arithmetic), then forms for every cluster the
  * centroid mu_c = mean of its rows (stored float32), the radius R_c = max_i ||W_i - mu_c||_2 measured to the
  * stored centroid, the bias maximum max_i b_i, and the row permutation that makes every cluster a contiguous
  * range of rows (clusters in id order, tokens inside a cluster by ascending id).  The index keeps its own

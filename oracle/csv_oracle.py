@@ -225,6 +225,12 @@ def lloyd_assign(W64: np.ndarray, cent64: np.ndarray) -> np.ndarray:
     return out
 
 
+def strided_seed_rows(V: int, C: int) -> np.ndarray:
+    """Seeding rule used when the caller names no starting rows: C tokens evenly spread over the vocabulary,
+    token floor(c V / C) for cluster c (the paper leaves the seeding of its K-means to a library)."""
+    return (np.arange(C, dtype=np.int64) * V) // C
+
+
 def lloyd_kmeans(W_bits: np.ndarray, init_rows: np.ndarray, iters: int):
     """Plain Lloyd iteration (Section III-A.1: K-means over the rows of W).
 

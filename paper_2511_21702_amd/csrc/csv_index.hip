@@ -219,103 +219,144 @@ __global__ __launch_bounds__(256) void radius_finish_kernel(const float* __restr
     }
 }
 
-// Lloyd assignment: labels[i] = argmin_c sum_j (W_ij - mu_cj)^2, ties to the smaller cluster id.
-// A block owns 64 rows and walks all clusters 64 at a time; each thread holds a 4x4 patch of distances.
-#define AS_TM 64
-#define AS_TN 64
-#define AS_TK 32
-__global__ __launch_bounds__(256) void assign_kernel(const uint16_t* __restrict__ W, const float* __restrict__ mu, int V, int d,
-                                                     int C, int32_t* __restrict__ labels) {
-    __shared__ float Ws[AS_TK][AS_TM + 4];
-    __shared__ float Ms[AS_TK][AS_TN + 4];
-    __shared__ float bd[AS_TM][17];
-    __shared__ int bi[AS_TM][17];
-    const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
-    const int row0 = blockIdx.x * AS_TM;
-    float best[4];
-    int besti[4];
+// Lloyd assignment: labels[i] = argmin_c ||W_i - mu_c||^2, ties to the smaller cluster id.
+// ||W_i - mu_c||^2 = ||W_i||^2 - 2 <W_i,mu_c> + ||mu_c||^2 and the first term does not depend on c, so the work is the
+// dense contraction [V x d] . [d x C]: v_mfma_f32_16x16x32_bf16 with the rows of W (bf16) as one operand and the float32
+// centroids, split exactly into three bf16 pieces (three MFMAs per k-block give float32-exact products), as the other.
+// Block = 8 waves = 128 rows x AS_NT*16 clusters; a wave owns 16 rows and keeps their AS_NT accumulator tiles over the
+// whole of K.  The centroid pieces are shared by the 8 waves: they are split while they are staged into LDS, one K
+// chunk at a time, already in fragment order; the rows of W go straight from global memory to registers.
+// Accumulator register r of lane (li, g) is [row 4g + r][cluster li]: the arg-min over a tile's 16 clusters is a
+// reduction inside a 16-lane DPP row.  Each block writes, per row, the best (distance, cluster) of its cluster group;
+// assign_reduce_kernel picks the best over the groups.
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 as_bf16x8_t;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float as_floatx4_t;
+#define AS_NT 4                 // cluster tiles of 16 per block
+#define AS_KC 256               // K chunk staged in LDS: AS_NT*16 clusters x 3 pieces x AS_KC x 2 bytes = 96 KB
+#define AS_THREADS 512
+#define AS_LDS (AS_NT * 16 * 3 * AS_KC * 2)
+
+__device__ __forceinline__ void as_split3(const float4& x0, const float4& x1, uint4& hi, uint4& mid, uint4& lo) {
+    const float v[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
+    uint32_t h[8], m[8], l[8];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        best[i] = INFINITY;
-        besti[i] = 0x7fffffff;
+    for (int i = 0; i < 8; ++i) {
+        h[i] = __float_as_uint(v[i]) & 0xffff0000u;
+        const float r1 = v[i] - __uint_as_float(h[i]);
+        m[i] = __float_as_uint(r1) & 0xffff0000u;
+        const float r2 = r1 - __uint_as_float(m[i]);
+        l[i] = __float_as_uint(r2) & 0xffff0000u;
     }
-    const int lr = tid >> 2, lc = (tid & 3) * 8;
-    for (int c0 = 0; c0 < C; c0 += AS_TN) {
-        float acc[4][4];
+    hi = make_uint4((h[0] >> 16) | h[1], (h[2] >> 16) | h[3], (h[4] >> 16) | h[5], (h[6] >> 16) | h[7]);
+    mid = make_uint4((m[0] >> 16) | m[1], (m[2] >> 16) | m[3], (m[4] >> 16) | m[5], (m[6] >> 16) | m[7]);
+    lo = make_uint4((l[0] >> 16) | l[1], (l[2] >> 16) | l[3], (l[4] >> 16) | l[5], (l[6] >> 16) | l[7]);
+}
+// minimum over the 16 lanes of a DPP row (lanes 16g .. 16g+15); every lane of the row gets it
+__device__ __forceinline__ unsigned row16_min_u(unsigned v) {
+    v = min(v, (unsigned)dpp_move<0xB1, 0xf>((int)v, (int)v));    // quad_perm [1,0,3,2]
+    v = min(v, (unsigned)dpp_move<0x4E, 0xf>((int)v, (int)v));    // quad_perm [2,3,0,1]
+    v = min(v, (unsigned)dpp_move<0x141, 0xf>((int)v, (int)v));   // row_half_mirror
+    v = min(v, (unsigned)dpp_move<0x140, 0xf>((int)v, (int)v));   // row_mirror
+    return v;
+}
+
+__global__ __launch_bounds__(256) void centroid_norm_kernel(const float* __restrict__ mu, int d, float* __restrict__ cn) {
+    __shared__ double red[4];
+    const int c = blockIdx.x, tid = threadIdx.x;
+    double acc = 0.0;
+    for (int j = tid; j < d; j += 256) acc += (double)mu[(size_t)c * d + j] * (double)mu[(size_t)c * d + j];
+    acc = wave_sum_d(acc);
+    if ((tid & 63) == 0) red[tid >> 6] = acc;
+    __syncthreads();
+    if (tid == 0) cn[c] = (float)((red[0] + red[1]) + (red[2] + red[3]));
+}
+
+// grid (cluster groups, row tiles of 128).  cand_key[row * G + group] = monotone key of the best distance, cand_c = its cluster.
+__global__ __launch_bounds__(AS_THREADS) void assign_mfma_kernel(const uint16_t* __restrict__ W, const float* __restrict__ mu,
+                                                                 const float* __restrict__ cn, int V, int d, int C, int G,
+                                                                 unsigned* __restrict__ cand_key, int32_t* __restrict__ cand_c) {
+    extern __shared__ uint4 as_lds[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int li = lane & 15, g = lane >> 4;
+    const int group = blockIdx.x, cb = group * AS_NT * 16;
+    const int r0 = blockIdx.y * 128 + wave * 16;
+    const int nq = d >> 3;                                   // 16-byte pieces per row of W
+    const uint4* ap = reinterpret_cast<const uint4*>(W + (size_t)min(r0 + li, V - 1) * d);
+    as_floatx4_t acc[AS_NT];
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+    for (int t = 0; t < AS_NT; ++t) acc[t] = as_floatx4_t{0.f, 0.f, 0.f, 0.f};
+    const uint4 zero = make_uint4(0, 0, 0, 0);
+    for (int k0 = 0; k0 < d; k0 += AS_KC) {
+        __syncthreads();
+        // stage: piece (cluster cl of the group, q-th run of 8 k values of the chunk) -> three fragments.
+        // fragment slot of (kb = q / 4, piece s, tile t) is ((kb * 3 + s) * AS_NT + t) * 64 + (q % 4) * 16 + (cl % 16)
+        for (int p = tid; p < AS_NT * 16 * (AS_KC / 8); p += AS_THREADS) {
+            const int cl = p / (AS_KC / 8), q = p - cl * (AS_KC / 8);
+            const int c = cb + cl, k = k0 + q * 8;
+            uint4 hi = zero, mid = zero, lo = zero;
+            if (c < C && k < d) {                            // d is a multiple of 8: the eight values are all in or all out
+                const float4* src = reinterpret_cast<const float4*>(mu + (size_t)c * d + k);
+                as_split3(src[0], src[1], hi, mid, lo);
+            }
+            const int base = (q >> 2) * 3 * AS_NT * 64 + (cl >> 4) * 64 + (q & 3) * 16 + (cl & 15);
+            as_lds[base] = hi;
+            as_lds[base + AS_NT * 64] = mid;
+            as_lds[base + 2 * AS_NT * 64] = lo;
+        }
+        __syncthreads();
+#pragma unroll 2
+        for (int kb = 0; kb < AS_KC / 32; ++kb) {
+            const int q = ((k0 + kb * 32) >> 3) + g;         // this lane's 16-byte piece of its row
+            const uint4 av = ap[min(q, nq - 1)];
+            const as_bf16x8_t A = __builtin_bit_cast(as_bf16x8_t, q < nq ? av : zero);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) acc[i][j] = 0.f;
-        for (int k0 = 0; k0 < d; k0 += AS_TK) {
-            __syncthreads();
-            {
-                const int gr = row0 + lr, col = k0 + lc;
-                uint4 v = make_uint4(0, 0, 0, 0);
-                if (gr < V && col < d) v = *reinterpret_cast<const uint4*>(W + (size_t)gr * d + col);
-                Ws[lc + 0][lr] = bf16_lo(v.x); Ws[lc + 1][lr] = bf16_hi(v.x);
-                Ws[lc + 2][lr] = bf16_lo(v.y); Ws[lc + 3][lr] = bf16_hi(v.y);
-                Ws[lc + 4][lr] = bf16_lo(v.z); Ws[lc + 5][lr] = bf16_hi(v.z);
-                Ws[lc + 6][lr] = bf16_lo(v.w); Ws[lc + 7][lr] = bf16_hi(v.w);
-                const int gc = c0 + lr;
-                float4 m0 = make_float4(0, 0, 0, 0), m1 = m0;
-                if (gc < C && col < d) {
-                    const float4* p = reinterpret_cast<const float4*>(mu + (size_t)gc * d + col);
-                    m0 = p[0];
-                    m1 = p[1];
+            for (int sp = 0; sp < 3; ++sp)
+#pragma unroll
+                for (int t = 0; t < AS_NT; ++t) {
+                    const uint4 Bv = as_lds[((kb * 3 + sp) * AS_NT + t) * 64 + lane];
+                    acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, __builtin_bit_cast(as_bf16x8_t, Bv), acc[t], 0, 0, 0);
                 }
-                Ms[lc + 0][lr] = m0.x; Ms[lc + 1][lr] = m0.y; Ms[lc + 2][lr] = m0.z; Ms[lc + 3][lr] = m0.w;
-                Ms[lc + 4][lr] = m1.x; Ms[lc + 5][lr] = m1.y; Ms[lc + 6][lr] = m1.z; Ms[lc + 7][lr] = m1.w;
-            }
-            __syncthreads();
-#pragma unroll 8
-            for (int kk = 0; kk < AS_TK; ++kk) {
-                float w[4], m[4];
-#pragma unroll
-                for (int i = 0; i < 4; ++i) w[i] = Ws[kk][ty * 4 + i];
-#pragma unroll
-                for (int j = 0; j < 4; ++j) m[j] = Ms[kk][tx * 4 + j];
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const float df = w[i] - m[j];
-                        acc[i][j] = fmaf(df, df, acc[i][j]);
-                    }
-            }
-        }
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int gc = c0 + tx * 4 + j;
-            if (gc < C) {
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    if (acc[i][j] < best[i]) {
-                        best[i] = acc[i][j];
-                        besti[i] = gc;
-                    }
-            }
         }
     }
-    __syncthreads();
+    // ||mu_c||^2 - 2 <W_i,mu_c> for row 4g + r and cluster cb + 16t + li; best over the tiles, then over the 16 lanes of the row
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        bd[ty * 4 + i][tx] = best[i];
-        bi[ty * 4 + i][tx] = besti[i];
-    }
-    __syncthreads();
-    if (tid < AS_TM && row0 + tid < V) {
-        float b = bd[tid][0];
-        int id = bi[tid][0];
-        for (int t = 1; t < 16; ++t) {
-            const float x = bd[tid][t];
-            const int xi = bi[tid][t];
-            if (x < b || (x == b && xi < id)) {
-                b = x;
-                id = xi;
+    for (int r = 0; r < 4; ++r) {
+        unsigned bk = 0xffffffffu;
+        int bc = 0x7fffffff;
+#pragma unroll
+        for (int t = 0; t < AS_NT; ++t) {
+            const int c = cb + 16 * t + li;
+            const float v = c < C ? cn[c] - 2.f * acc[t][r] : INFINITY;
+            const unsigned kx = c < C ? fkey(v + 0.0f) : 0xffffffffu;
+            if (kx < bk) {                                   // tiles in ascending cluster order: a tie keeps the smaller id
+                bk = kx;
+                bc = c;
             }
         }
-        labels[row0 + tid] = id;
+        const unsigned m = row16_min_u(bk);
+        const int cm = (int)row16_min_u(bk == m ? (unsigned)bc : 0x7fffffffu);
+        const int row = r0 + 4 * g + r;
+        if (li == 0 && row < V) {
+            cand_key[(size_t)row * G + group] = m;
+            cand_c[(size_t)row * G + group] = cm;
+        }
     }
+}
+
+__global__ __launch_bounds__(256) void assign_reduce_kernel(const unsigned* __restrict__ cand_key, const int32_t* __restrict__ cand_c,
+                                                            int V, int G, int32_t* __restrict__ labels) {
+    const int row = blockIdx.x * 256 + threadIdx.x;
+    if (row >= V) return;
+    unsigned bk = 0xffffffffu;
+    int bc = 0x7fffffff;
+    for (int gq = 0; gq < G; ++gq) {                         // groups in ascending cluster order: a tie keeps the smaller id
+        const unsigned kx = cand_key[(size_t)row * G + gq];
+        if (kx < bk) {
+            bk = kx;
+            bc = cand_c[(size_t)row * G + gq];
+        }
+    }
+    labels[row] = bc;
 }
 
 // mu[c] = row init_rows[c] of W widened to float32 (starting centroids).
@@ -467,23 +508,43 @@ extern "C" int csv_build_index(const uint16_t* d_W, const float* d_b, int V, int
     if (rc) return rc;
     if (o->iters < 0 || !(o->radius_slack >= 0.f)) { csv_set_error("iters and radius_slack must be >= 0"); return CSV_EINVAL; }
     if (o->bias_table_m < 0 || o->bias_table_m > CSV_MAX_BIAS_TABLE) { csv_set_error("bias_table_m=%d outside 0..%d", o->bias_table_m, CSV_MAX_BIAS_TABLE); return CSV_EINVAL; }
-    if (!o->h_init_labels && !o->h_init_rows) { csv_set_error("need h_init_labels or h_init_rows"); return CSV_EINVAL; }
+
     hipStream_t st = (hipStream_t)stream;
     csv_index* x = nullptr;
     rc = csv_index_alloc(V, d, C, &x);
     if (rc) return rc;
     int32_t* d_labels = nullptr;
     std::vector<int32_t> labels(V), n, off, perm;
-    auto fail = [&](int code) {
+    // scratch of the assignment: per row and cluster group the best (distance key, cluster); centroid norms
+    unsigned* d_ckey = nullptr;
+    int32_t* d_cc = nullptr;
+    float* d_cn = nullptr;
+    auto free_scratch = [&]() {
         if (d_labels) (void)hipFree(d_labels);
+        if (d_ckey) (void)hipFree(d_ckey);
+        if (d_cc) (void)hipFree(d_cc);
+        if (d_cn) (void)hipFree(d_cn);
+    };
+    auto fail = [&](int code) {
+        free_scratch();
         csv_index_free(x);
         return code;
     };
     if (hipMalloc((void**)&d_labels, (size_t)V * 4) != hipSuccess) { csv_set_error("label buffer allocation failed"); return fail(CSV_ENOMEM); }
     const dim3 cgrid(C, (d + 255) / 256);
+    const int G = (C + AS_NT * 16 - 1) / (AS_NT * 16);
     auto assign = [&]() -> int {
-        assign_kernel<<<(V + AS_TM - 1) / AS_TM, 256, 0, st>>>(d_W, x->mu, V, d, C, d_labels);
-        CSV_LAUNCH_CHECK("assign_kernel");
+        if (!d_ckey) {
+            if (hipMalloc((void**)&d_ckey, (size_t)V * G * 4) != hipSuccess || hipMalloc((void**)&d_cc, (size_t)V * G * 4) != hipSuccess ||
+                hipMalloc((void**)&d_cn, (size_t)C * 4) != hipSuccess) { csv_set_error("out of device memory (assignment scratch)"); return CSV_ENOMEM; }
+            CSV_HIP(hipFuncSetAttribute((const void*)assign_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, AS_LDS));
+        }
+        centroid_norm_kernel<<<C, 256, 0, st>>>(x->mu, d, d_cn);
+        CSV_LAUNCH_CHECK("centroid_norm_kernel");
+        assign_mfma_kernel<<<dim3(G, (V + 127) / 128), AS_THREADS, AS_LDS, st>>>(d_W, x->mu, d_cn, V, d, C, G, d_ckey, d_cc);
+        CSV_LAUNCH_CHECK("assign_mfma_kernel");
+        assign_reduce_kernel<<<(V + 255) / 256, 256, 0, st>>>(d_ckey, d_cc, V, G, d_labels);
+        CSV_LAUNCH_CHECK("assign_reduce_kernel");
         CSV_HIP(hipMemcpyAsync(labels.data(), d_labels, (size_t)V * 4, hipMemcpyDeviceToHost, st));
         CSV_HIP(hipStreamSynchronize(st));
         return CSV_OK;
@@ -491,10 +552,13 @@ extern "C" int csv_build_index(const uint16_t* d_W, const float* d_b, int V, int
     if (o->h_init_labels) {
         memcpy(labels.data(), o->h_init_labels, (size_t)V * 4);
     } else {
+        // seeding rule when the caller names no rows: C tokens evenly spread over the vocabulary, token floor(c V / C)
+        std::vector<int32_t> seed(C);
+        for (int c = 0; c < C; ++c) seed[c] = o->h_init_rows ? o->h_init_rows[c] : (int32_t)((long long)c * V / C);
         for (int c = 0; c < C; ++c)
-            if (o->h_init_rows[c] < 0 || o->h_init_rows[c] >= V) { csv_set_error("init row %d outside 0..V-1", o->h_init_rows[c]); return fail(CSV_EINVAL); }
+            if (seed[c] < 0 || seed[c] >= V) { csv_set_error("init row %d outside 0..V-1", seed[c]); return fail(CSV_EINVAL); }
         // x->n doubles as the staging buffer for the starting rows
-        if (hipMemcpyAsync(x->n, o->h_init_rows, (size_t)C * 4, hipMemcpyHostToDevice, st) != hipSuccess) { csv_set_error("copy of init rows failed"); return fail(CSV_EHIP); }
+        if (hipMemcpy(x->n, seed.data(), (size_t)C * 4, hipMemcpyHostToDevice) != hipSuccess) { csv_set_error("copy of init rows failed"); return fail(CSV_EHIP); }
         init_centroid_kernel<<<C, 256, 0, st>>>(d_W, x->n, d, x->mu);
         if ((rc = assign())) return fail(rc);
     }
@@ -545,7 +609,7 @@ extern "C" int csv_build_index(const uint16_t* d_W, const float* d_b, int V, int
     if (d_d2row) (void)hipFree(d_d2row);
     if (!launched) { csv_set_error("launch of the radius kernels failed"); return fail(CSV_EHIP); }
     if (!synced) { csv_set_error("index build failed on the device: %s", hipGetErrorString(hipGetLastError())); return fail(CSV_EHIP); }
-    (void)hipFree(d_labels);
+    free_scratch();
     *out = x;
     return CSV_OK;
 }

@@ -721,6 +721,55 @@ def test_c2_index_built_on_the_gpu_and_steps_on_it():
     ws.free(); g.free(); case.close()
 
 
+def test_build_index_kmeans_at_c1_size_with_zipf_clusters():
+    # Lloyd on the GPU (MFMA distance product) at V = 32000, d = 1024, C = 256 with Zipf cluster sizes, from the
+    # default seeding rule (evenly spread tokens).  The oracle's assignment is checked row by row on a sample (its
+    # plain distance evaluation is slow): labels after t+1 iterations must be the nearest centroid of the index after
+    # t iterations, outside a tie band; centroids, sizes and the permutation must be those of the final labels.
+    r = synth.CONFIGS["c1"].scaled(sizes="zipf")
+    case = Case(r, want_W64=True)
+    csv = case.csv
+    seeds = O.strided_seed_rows(r.V, r.C)
+    assert len(set(seeds.tolist())) == r.C and seeds[0] == 0 and seeds[-1] == (r.C - 1) * r.V // r.C
+    rng = np.random.default_rng(5)
+    sample = np.sort(rng.choice(r.V, 1500, replace=False))
+    prev = None
+    for iters in (0, 1, 2):
+        g = csv.csv_build_index(case.dW, case.db, r.C, iters=iters)            # no labels, no rows: the seeding rule
+        e = g.export()
+        labels = np.empty(r.V, dtype=np.int64)
+        off = np.concatenate([[0], np.cumsum(e["n"])])
+        for c in range(r.C):
+            labels[e["perm"][off[c]:off[c + 1]]] = c
+        # metadata of the final labels, against the oracle's
+        want = O.build_index(case.head["W_bits"], case.b, labels, r.C)
+        assert np.array_equal(e["n"], want.n) and np.array_equal(e["perm"], want.perm)
+        ulp = np.abs(e["mu"].view(np.int32).astype(np.int64) - want.mu.view(np.int32).astype(np.int64))
+        assert ulp.max() <= 1
+        # assignment: nearest centroid of the previous index (iters = 0: of the seed rows themselves)
+        cent = case.W64[seeds] if prev is None else prev
+        d2 = ((case.W64[sample][:, None, :] - cent[None, :, :]) ** 2).sum(-1) if False else None
+        x = case.W64[sample]
+        d2 = (x * x).sum(1)[:, None] - 2.0 * x @ cent.T + (cent * cent).sum(1)[None, :]     # same distances, float64
+        best = d2.argmin(1)
+        got = labels[sample]
+        srt = np.sort(d2, axis=1)
+        margin = srt[:, 1] - srt[:, 0]
+        band = margin < 1e-4 * np.maximum(1.0, (cent * cent).sum(1).max())
+        ok = (got == best) | (band & (np.abs(d2[np.arange(sample.size), got] - srt[:, 0]) < 2e-4 * np.maximum(1.0, (cent * cent).sum(1).max())))
+        log(f"  Lloyd iters={iters}: sampled rows {sample.size}, in tie band {int(band.sum())}, empty clusters {int((e['n'] == 0).sum())}")
+        assert ok.all(), np.flatnonzero(~ok)[:10]
+        # exact distances (the definition) on a few rows agree with the expanded form used above
+        few = sample[:20]
+        exact = ((case.W64[few][:, None, :] - cent[None, :, :]) ** 2).sum(-1)
+        assert np.array_equal(exact.argmin(1), best[:20])
+        if (e["n"] == 0).any():
+            break           # an empty cluster keeps its old centroid inside the loop but is exported as zero: the chain ends here
+        prev = e["mu"].astype(np.float64)
+        g.free()
+    case.close()
+
+
 # ------------------------------------------------------------------ the five configurations
 def _run_config(name, step_ids, max_band_frac=0.01, levels_step_ids=None, centroid_bf16=False):
     r = synth.CONFIGS[name]
