@@ -16,6 +16,8 @@ Pins (tests/test_oracle_*.py):
   topk_bruteforce    three independent selections on tiny V
   build_index        partition/permutation invariants, radius >= every member distance, footprint of Section IV
   cluster_bounds     Cauchy-Schwarz invariant (Section III-A), homogeneity, singleton clusters, single cluster
+  angular_bounds     two hand-computed planar clusters (tight at the cone's edge, ||w|| ||h|| inside it), every logit dominated
+  spherical_kmeans   planted directions recovered; assignment is the largest cosine with ties to the smaller id
   bias_table         a hand-computed cluster; every logit still dominated; never looser than the max-bias bound; m = 1 is that bound
   topk certificate   Theorem 1 against brute force; minimal prefix = {U_c >= true k-th logit}
   eps certificate    proof identity TV = R/(Z_S+R) (Theorem 2), cluster-wise tail <= loose tail
@@ -96,12 +98,15 @@ def topk_bruteforce(logits: np.ndarray, k: int, ids: np.ndarray | None = None):
 class OracleIndex:
     """Cluster metadata of Section III-A.1 / Section IV: centroids, radii, bias maxima, row permutation."""
 
-    def __init__(self, mu, R, bmax, n, perm, bias_table=None):
+    def __init__(self, mu, R, bmax, n, perm, bias_table=None, ang=None):
         self.mu = np.ascontiguousarray(mu, dtype=np.float32)      # [C,d] stored centroids
         self.R = np.ascontiguousarray(R, dtype=np.float32)        # [C]   stored radii (rounded up)
         self.bmax = np.ascontiguousarray(bmax, dtype=np.float32)  # [C]   max bias in cluster (-inf if empty)
         # [C,m,2] or None: per cluster m pairs (radius, bias) of the top-m bias table; unused entries (0, -inf)
         self.bias_table = None if bias_table is None else np.ascontiguousarray(bias_table, dtype=np.float32)
+        # [C,4] or None: angular index (spherical clustering): (cos theta_c, sin theta_c, largest row norm, smallest row
+        # norm) with their slack; mu then holds the unit centroid directions and R is unused
+        self.ang = None if ang is None else np.ascontiguousarray(ang, dtype=np.float32)
         self.n = np.ascontiguousarray(n, dtype=np.int64)          # [C]   rows per cluster
         self.off = np.concatenate([[0], np.cumsum(self.n)]).astype(np.int64)
         self.perm = np.ascontiguousarray(perm, dtype=np.int64)    # [V]   permuted row -> original token id
@@ -225,6 +230,109 @@ def lloyd_assign(W64: np.ndarray, cent64: np.ndarray) -> np.ndarray:
     return out
 
 
+def _round_down_f32(x: np.ndarray) -> np.ndarray:
+    x = np.asarray(x, dtype=np.float64)
+    y = x.astype(np.float32)
+    high = y.astype(np.float64) > x
+    y[high] = np.nextafter(y[high], np.float32(-np.inf))
+    return y
+
+
+def build_index_angular(W_bits: np.ndarray, b, labels: np.ndarray, C: int, slack: float = 2.0 ** -14,
+                        angle_slack: float = 2.0 ** -12) -> OracleIndex:
+    """Angular index for spherical clustering (Section III, "Advanced Theoretical Improvements", spherical metrics).
+
+    Per cluster: the unit centroid direction m_c = normalise(sum_i W_i / ||W_i||), stored as float32; the angular radius
+    theta_c = max_i angle(W_i, m_c) measured to the STORED direction; the largest and smallest row norm.
+    Stored with slack so that a float32 evaluation of the bound stays above the logits: theta_c + theta_c*slack +
+    angle_slack (its cosine and sine are what is kept), the largest norm times (1 + slack) rounded up, the smallest
+    times (1 - slack) rounded down.  Rows of zero norm count as having the centroid's own direction."""
+    labels = np.asarray(labels, dtype=np.int64)
+    V, d = W_bits.shape
+    n = np.bincount(labels, minlength=C).astype(np.int64)
+    perm = np.argsort(labels, kind="stable").astype(np.int64)
+    off = np.concatenate([[0], np.cumsum(n)])
+    mu = np.zeros((C, d), dtype=np.float32)
+    ang = np.zeros((C, 4), dtype=np.float32)
+    ang[:, 0] = 1.0
+    bmax = np.full(C, -np.inf, dtype=np.float32)
+    bb = None if b is None else np.asarray(b, dtype=np.float32)
+    for c in range(C):
+        rows = perm[off[c]:off[c + 1]]
+        if rows.size == 0:
+            continue
+        Wc = bf16_to_f64(W_bits[rows])
+        nrm = np.sqrt(np.einsum("ij,ij->i", Wc, Wc))
+        unit = Wc / np.where(nrm > 0, nrm, 1.0)[:, None]
+        m = unit.sum(axis=0)
+        mn = math.sqrt(float(m @ m))
+        mu[c] = (m / mn if mn > 0 else m).astype(np.float32)
+        ms = mu[c].astype(np.float64)
+        msn = math.sqrt(float(ms @ ms))
+        cosv = np.where(nrm > 0, (Wc @ ms) / (np.where(nrm > 0, nrm, 1.0) * (msn if msn > 0 else 1.0)), 1.0)
+        theta = math.acos(float(np.clip(cosv.min(), -1.0, 1.0)))
+        theta = min(math.pi, theta * (1.0 + slack) + angle_slack)
+        ang[c, 0] = _round_down_f32(np.array([math.cos(theta)]))[0] if theta < math.pi else np.float32(-1.0)
+        ang[c, 1] = _round_up_f32(np.array([math.sin(theta)]))[0]
+        ang[c, 2] = _round_up_f32(np.array([nrm.max() * (1.0 + slack)]))[0]
+        ang[c, 3] = _round_down_f32(np.array([nrm.min() * (1.0 - slack)]))[0]
+        bmax[c] = np.float32(0.0) if bb is None else bb[rows].max()
+    return OracleIndex(mu, np.zeros(C, dtype=np.float32), bmax, n, perm, None, ang)
+
+
+def angular_bounds(index: OracleIndex, h64: np.ndarray):
+    """Angular cluster bound.  For a row w of cluster c, angle(w,h) >= phi - theta_c with phi = angle(m_c,h), so
+        <w,h> <= ||w|| ||h|| cos(phi - theta_c)          when phi > theta_c,        <w,h> <= ||w|| ||h||  otherwise,
+    and with t = <m_c,h> = ||h|| cos(phi):  ||h|| cos(phi - theta_c) = t cos(theta_c) + sqrt(||h||^2 - t^2) sin(theta_c).
+    The row norm is replaced by the cluster's largest (when that factor is positive) or smallest (when negative).
+    The paper prints ||h|| (||mu_c|| cos(theta_c) + sin(theta_c)), which does not depend on the direction of h and so
+    cannot order clusters; it follows from the form used here with cos(phi) and sin(phi) replaced by 1."""
+    h64 = np.atleast_2d(h64)
+    hn = np.sqrt(np.einsum("ij,ij->i", h64, h64))
+    t = h64 @ index.mu.astype(np.float64).T                       # [B,C]
+    a = index.ang.astype(np.float64)
+    ct, st, rmax, rmin = a[:, 0][None, :], a[:, 1][None, :], a[:, 2][None, :], a[:, 3][None, :]
+    perp = np.sqrt(np.maximum(hn[:, None] ** 2 - t ** 2, 0.0))
+    inside = t >= hn[:, None] * ct                                # phi <= theta_c: the cone contains the direction of h
+    g = t * ct + perp * st
+    val = np.where(inside, rmax * hn[:, None], np.where(g >= 0, rmax * g, rmin * g))
+    U = val + index.bmax.astype(np.float64)[None, :]
+    U[:, index.n == 0] = NEG_INF
+    return U, hn
+
+
+def spherical_assign(W64: np.ndarray, dirs64: np.ndarray) -> np.ndarray:
+    """Largest cosine to a unit direction (rows of zero norm go to cluster 0); ties go to the smaller cluster id."""
+    out = np.empty(W64.shape[0], dtype=np.int64)
+    nrm = np.sqrt(np.einsum("ij,ij->i", W64, W64))
+    step = max(1, int(2e7) // max(1, dirs64.shape[0]))
+    for lo in range(0, W64.shape[0], step):
+        x = W64[lo:lo + step]
+        cosv = (x @ dirs64.T) / np.where(nrm[lo:lo + step] > 0, nrm[lo:lo + step], 1.0)[:, None]
+        out[lo:lo + step] = np.argmax(cosv, axis=1)             # argmax returns the first (smallest id) maximum
+    return out
+
+
+def spherical_kmeans(W_bits: np.ndarray, init_rows: np.ndarray, iters: int):
+    """Spherical K-means (Section III, spherical clustering metrics): directions start at the given rows (normalised);
+    each iteration assigns every row to the direction of largest cosine and replaces each direction by the
+    float32-rounded normalised sum of its rows' unit vectors (an empty cluster keeps its direction)."""
+    W64 = bf16_to_f64(W_bits)
+    nrm = np.sqrt(np.einsum("ij,ij->i", W64, W64))
+    unit = W64 / np.where(nrm > 0, nrm, 1.0)[:, None]
+    dirs = unit[np.asarray(init_rows, dtype=np.int64)].astype(np.float32)
+    labels = spherical_assign(W64, dirs.astype(np.float64))
+    for _ in range(iters):
+        for c in range(dirs.shape[0]):
+            m = labels == c
+            if m.any():
+                v = unit[m].sum(axis=0)
+                vn = math.sqrt(float(v @ v))
+                dirs[c] = (v / vn if vn > 0 else v).astype(np.float32)
+        labels = spherical_assign(W64, dirs.astype(np.float64))
+    return labels, dirs
+
+
 def strided_seed_rows(V: int, C: int) -> np.ndarray:
     """Seeding rule used when the caller names no starting rows: C tokens evenly spread over the vocabulary,
     token floor(c V / C) for cluster c (the paper leaves the seeding of its K-means to a library)."""
@@ -255,6 +363,8 @@ def cluster_bounds(index: OracleIndex, h64: np.ndarray):
     """U_c(h) = <mu_c,h> + R_c ||h||_2 + max_{i in c} b_i  (Eq. "cluster_bound"); with a top-m bias table the last
     two terms are replaced by max_j (rho_j ||h|| + beta_j).  Empty clusters get -inf."""
     h64 = np.atleast_2d(h64)
+    if index.ang is not None:
+        return angular_bounds(index, h64)
     hn = np.sqrt(np.einsum("ij,ij->i", h64, h64))
     dots = h64 @ index.mu.astype(np.float64).T
     if index.bias_table is None:

@@ -785,3 +785,90 @@ def test_certified_distribution_brackets_the_true_probabilities():
         allp, _, _ = O.certified_distribution(L[0][S], res["lse"])
         assert math.isclose(allp.sum(), 1.0, rel_tol=1e-12)
     assert seen > 10
+
+
+# ------------------------------------------------------------------ spherical clustering and the angular bound (Section III)
+def _planar(angles_deg, norms):
+    a = np.radians(np.array(angles_deg, dtype=np.float64))
+    W = (np.array(norms)[:, None] * np.stack([np.cos(a), np.sin(a)], 1)).astype(np.float32)
+    return np.pad(W, ((0, 0), (0, 6)))                               # d = 8
+
+
+def test_angular_bound_hand_computed_in_the_plane():
+    # unit rows at -10 and +10 degrees: direction (1,0), angular radius 10 degrees.  h of norm 2 at 40 degrees:
+    # phi - theta = 30 degrees, bound 2 cos 30 = sqrt 3, attained by the row at +10 degrees.
+    W = _planar([-10, 10], [1, 1])
+    Wb = synth.f32_to_bf16_bits(W)
+    idx = O.build_index_angular(Wb, None, np.zeros(2, dtype=int), 1, slack=0.0, angle_slack=0.0)
+    W64 = O.bf16_to_f64(Wb)
+    theta = math.acos(float(W64[0] @ idx.mu[0].astype(np.float64) / np.linalg.norm(W64[0]) / np.linalg.norm(idx.mu[0])))
+    assert abs(math.degrees(theta) - 10) < 0.3                        # bf16 rounding of the rows moves it a little
+    def hvec(deg, norm):
+        v = np.zeros((1, 8)); v[0, 0] = norm * math.cos(math.radians(deg)); v[0, 1] = norm * math.sin(math.radians(deg))
+        return v
+    for deg in (40.0, 95.0, 170.0, -60.0):
+        h = hvec(deg, 2.0)
+        L = O.full_logits(W64, None, h)[0]
+        U = O.cluster_bounds(idx, h)[0][0, 0]
+        rho = np.linalg.norm(W64, axis=1)
+        phi = math.radians(abs(deg))
+        g = math.cos(phi - theta)
+        want = 2.0 * (rho.max() if g >= 0 else rho.min()) * g
+        assert U >= L.max() - 1e-6 and abs(U - want) < 2e-3 * max(1.0, abs(want))   # float32 storage of cos/sin/norms
+        assert abs(U - L.max()) < 2e-2                                 # and tight: the row on the near edge attains it
+    # h inside the cone: nothing better than ||w|| ||h|| can be said
+    U = O.cluster_bounds(idx, hvec(5.0, 3.0))[0][0, 0]
+    assert abs(U - 3.0 * np.linalg.norm(W64, axis=1).max()) < 1e-6
+    # rows of different length: the longest decides a positive bound, the shortest a negative one
+    W2 = _planar([-10, 10], [1, 3])
+    idx2 = O.build_index_angular(synth.f32_to_bf16_bits(W2), None, np.zeros(2, dtype=int), 1, slack=0.0, angle_slack=0.0)
+    assert abs(idx2.ang[0, 2] - 3.0) < 1e-2 and abs(idx2.ang[0, 3] - 1.0) < 1e-2     # bf16 rows: lengths 3 and 1 up to rounding
+    L = O.full_logits(O.bf16_to_f64(synth.f32_to_bf16_bits(W2)), None, hvec(170.0, 2.0))[0]
+    U = O.cluster_bounds(idx2, hvec(170.0, 2.0))[0][0, 0]
+    assert U < 0 and U >= L.max() - 1e-6
+
+
+def test_angular_bound_dominates_every_logit():
+    rng = np.random.default_rng(91)
+    for seed in range(5):
+        r, head, h = _small(seed=40 + seed, V=1500, d=48, C=20, steps=6, iso_frac=0.4, h_mode="mix", row_noise=0.5 + seed)
+        Wf = synth.bf16_bits_to_f32(head["W_bits"]) * rng.uniform(0.3, 2.0, (r.V, 1)).astype(np.float32)     # scattered row norms
+        Wb = synth.f32_to_bf16_bits(Wf)
+        W = O.bf16_to_f64(Wb)
+        for slack in (0.0, 2.0 ** -14):
+            idx = O.build_index_angular(Wb, head["b"], head["labels"], r.C, slack=slack, angle_slack=0.0 if slack == 0 else 2.0 ** -12)
+            assert np.all(np.abs(np.linalg.norm(idx.mu.astype(np.float64), axis=1) - 1) < 1e-6)
+            for t in range(h.shape[0]):
+                h64 = np.concatenate([O.bf16_to_f64(h[t]), -O.bf16_to_f64(h[t]), W[rng.integers(0, r.V, 2)] * 5.0])   # also opposite and in-cone directions
+                L = O.full_logits(W, head["b"], h64)
+                U, hn = O.cluster_bounds(idx, h64)
+                assert np.all(L <= U[:, head["labels"]] + 1e-9)
+    # certified steps on an angular index return the full-vocabulary top-k
+    r, head, h = _small(seed=46, V=2000, d=64, C=16, steps=6)
+    idx = O.build_index_angular(head["W_bits"], head["b"], head["labels"], r.C)
+    W = O.bf16_to_f64(head["W_bits"])
+    for t in range(h.shape[0]):
+        L = O.full_logits(W, head["b"], O.bf16_to_f64(h[t]))
+        for b_, res in enumerate(O.decode_step(W, head["b"], idx, h[t], 5, 1e-3, r.V, logits=L)):
+            assert res["flags"] & O.FLAG_TOPK_CERT and np.array_equal(res["ids"], O.topk_bruteforce(L[b_], 5)[0])
+
+
+def test_spherical_kmeans_recovers_planted_directions():
+    rng = np.random.default_rng(92)
+    C, per, d = 6, 60, 32
+    dirs = rng.standard_normal((C, d)); dirs /= np.linalg.norm(dirs, axis=1, keepdims=True)
+    lab = np.repeat(np.arange(C), per)
+    W = dirs[lab] + 0.05 * rng.standard_normal((C * per, d))
+    W *= rng.uniform(0.2, 5.0, (C * per, 1))                           # lengths carry no information
+    Wb = synth.f32_to_bf16_bits(W.astype(np.float32))
+    first = np.array([c * per for c in range(C)])
+    labels, got = O.spherical_kmeans(Wb, first, iters=3)
+    assert np.array_equal(labels, lab)
+    assert np.all(np.abs(np.linalg.norm(got.astype(np.float64), axis=1) - 1) < 1e-6)
+    assert np.all(np.einsum("ij,ij->i", got.astype(np.float64), dirs) > 0.99)
+    # Euclidean Lloyd from the same start is misled by the lengths
+    assert not np.array_equal(O.lloyd_kmeans(Wb, first, iters=3)[0], lab)
+    # assignment: largest cosine, ties to the smaller id, length of the row irrelevant
+    Wt = np.array([[2.0, 0.0], [0.0, 0.1], [3.0, 3.0], [-1.0, 0.0]])
+    D = np.array([[1.0, 0.0], [0.0, 1.0], [1.0, 0.0]])
+    assert O.spherical_assign(Wt, D).tolist() == [0, 1, 0, 1]
