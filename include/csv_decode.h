@@ -63,6 +63,9 @@ typedef struct {
     float radius_slack;          /* rho >= 0: stored radius = roundup_f32(R_c(1+rho) + rho*||mu_c||) */
     int   centroid_bf16;         /* nonzero: store the centroids rounded to bfloat16 (nearest even) and measure the radii
                                     to the rounded values: the bound stays valid, the bound kernels read half the bytes */
+    int   spherical;             /* nonzero: spherical K-means (rows compared by direction: largest cosine) and the angular
+                                    bound in place of Eq. "cluster_bound" (Section III, spherical clustering metrics);
+                                    see csv_index_set_angular.  Not together with centroid_bf16 or bias_table_m */
     int   bias_table_m;          /* >= 2: build the top-m bias table (Section III, "Advanced Theoretical Improvements", bias
                                     binning; at most CSV_MAX_BIAS_TABLE); 0 or 1: the plain bound */
 } csv_build_opts;
@@ -112,6 +115,21 @@ int csv_index_use_bf16_centroids(csv_index* idx, void* stream);
  */
 int csv_index_set_bias_table(csv_index* idx, int m, const float* h_table, void* stream);
 int csv_index_get_bias_table(const csv_index* idx, int* m, float* h_table);
+
+/*
+ * Angular index (Section III, "Advanced Theoretical Improvements": spherical clustering metrics).  The centroid array
+ * holds unit directions m_c = normalise(sum_i W_i / ||W_i||); per cluster four numbers: cos and sin of the angular radius
+ * theta_c = max_i angle(W_i, m_c), the largest and the smallest row norm (all stored with slack on the safe side).
+ * For a row w of cluster c the angle to h is at least phi - theta_c, phi = angle(m_c, h), hence with t = <m_c,h>
+ *   <w,h> <= rho (t cos(theta_c) + sqrt(||h||^2 - t^2) sin(theta_c))   when phi > theta_c,    <w,h> <= rho_max ||h||   otherwise,
+ * rho = rho_max when the bracket is positive, rho_min when it is negative; the cluster bound adds the largest bias.
+ * (As printed in the paper the bound, ||h|| (||mu_c|| cos(theta_c) + sin(theta_c)), does not depend on the direction of h and
+ * cannot order clusters; it is the form above with cos(phi) and sin(phi) replaced by 1.)
+ * csv_index_set_angular installs h_ang HOST float32[C*4] on an index whose centroids are such directions (NULL removes it);
+ * csv_index_get_angular reports whether the index is angular and, when h_ang is not NULL, copies the four numbers per cluster.
+ */
+int csv_index_set_angular(csv_index* idx, const float* h_ang, void* stream);
+int csv_index_get_angular(const csv_index* idx, int* present, float* h_ang);
 
 /* Copy the metadata back to HOST buffers of the sizes above (any pointer may be NULL to skip it). Synchronous. */
 int csv_index_export(const csv_index* idx, float* h_mu, float* h_R, float* h_bmax, int32_t* h_n, int32_t* h_perm);

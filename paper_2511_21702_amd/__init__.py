@@ -25,13 +25,14 @@ EXPORTS = [
     "csv_profile_begin", "csv_profile_end", "csv_last_error", "csv_kmax_init", "csv_kmax_update",
     "csv_workspace_set_spin_limit", "csv_index_use_bf16_centroids",
     "csv_workspace_set_tail_split", "csv_bounds_static", "csv_index_set_bias_table", "csv_index_get_bias_table",
+    "csv_index_set_angular", "csv_index_get_angular",
 ]
 PROFILE_STAGES = ["bounds", "round0", "tail"]
 
 
 class BuildOpts(C.Structure):
     _fields_ = [("iters", C.c_int), ("h_init_labels", C.c_void_p), ("h_init_rows", C.c_void_p),
-                ("radius_slack", C.c_float), ("centroid_bf16", C.c_int), ("bias_table_m", C.c_int)]
+                ("radius_slack", C.c_float), ("centroid_bf16", C.c_int), ("spherical", C.c_int), ("bias_table_m", C.c_int)]
 
 
 class StepParams(C.Structure):
@@ -73,6 +74,8 @@ def _load() -> C.CDLL:
     lib.csv_bounds_static.argtypes = [vp, vp, ci, vp, vp, vp]
     lib.csv_index_set_bias_table.argtypes = [vp, ci, vp, vp]
     lib.csv_index_get_bias_table.argtypes = [vp, C.POINTER(ci), vp]
+    lib.csv_index_set_angular.argtypes = [vp, vp, vp]
+    lib.csv_index_get_angular.argtypes = [vp, C.POINTER(ci), vp]
     lib.csv_profile_begin.argtypes = [vp, ci]
     lib.csv_profile_end.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(ci)]
     lib.csv_kmax_init.argtypes = [C.POINTER(KmaxCtl), ci, ci, ci, C.c_double, C.c_double, ci]
@@ -128,6 +131,27 @@ class CsvIndex:
                                     perm.ctypes.data))
         return {"mu": mu, "R": R, "bmax": bmax, "n": n, "perm": perm}
 
+    def set_angular(self, ang, stream=None) -> None:
+        """ang: numpy float32 [C, 4] (cos, sin of the angular radius, largest, smallest row norm), or None to remove."""
+        import numpy as np
+        if ang is None:
+            _check(lib.csv_index_set_angular(self._h, None, _stream(stream)))
+            return
+        t = np.ascontiguousarray(ang, dtype=np.float32)
+        assert t.shape == (self.C, 4)
+        _check(lib.csv_index_set_angular(self._h, t.ctypes.data, _stream(stream)))
+
+    def angular(self):
+        """numpy float32 [C, 4], or None for a Euclidean index."""
+        import numpy as np
+        present = C.c_int()
+        _check(lib.csv_index_get_angular(self._h, C.byref(present), None))
+        if not present.value:
+            return None
+        t = np.empty((self.C, 4), np.float32)
+        _check(lib.csv_index_get_angular(self._h, C.byref(present), t.ctypes.data))
+        return t
+
     def set_bias_table(self, table, stream=None) -> None:
         """table: numpy float32 [C, m, 2] of (radius, bias) pairs, or None to remove the table."""
         import numpy as np
@@ -163,7 +187,7 @@ class CsvIndex:
 
 def csv_build_index(W: torch.Tensor, b, C_clusters: int, init_labels=None, init_rows=None, iters: int = 0,
                     radius_slack: float = 2.0 ** -14, stream=None, centroid_bf16: bool = False,
-                    bias_table_m: int = 0) -> CsvIndex:
+                    bias_table_m: int = 0, spherical: bool = False) -> CsvIndex:
     """W: [V,d] 16-bit CUDA tensor (bf16 patterns, original token order); b: float32 CUDA [V] or None.
     init_labels / init_rows: host int32 numpy arrays (see csv_build_opts)."""
     import numpy as np
@@ -171,7 +195,7 @@ def csv_build_index(W: torch.Tensor, b, C_clusters: int, init_labels=None, init_
     V, d = W.shape
     keep = []
     opts = BuildOpts(iters=iters, h_init_labels=None, h_init_rows=None, radius_slack=radius_slack,
-                     centroid_bf16=int(bool(centroid_bf16)), bias_table_m=int(bias_table_m))
+                     centroid_bf16=int(bool(centroid_bf16)), spherical=int(bool(spherical)), bias_table_m=int(bias_table_m))
     if init_labels is not None:
         a = np.ascontiguousarray(init_labels, dtype=np.int32)
         assert a.shape == (V,)

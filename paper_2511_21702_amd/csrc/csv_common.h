@@ -25,6 +25,8 @@ struct csv_index {
     float* lnn;      // [C]   ln n_c (-inf for an empty cluster)
     int4* cmeta;     // [C]   {first permuted row, rows, bit pattern of ln n_c, 0}: what the seed selection needs of a
                      //       cluster in one 128-bit load
+    float4* ang;     // [C] angular index (spherical clustering): {cos, sin of the angular radius, largest, smallest row norm},
+                     //     all with slack; mu then holds unit directions and R is unused.  NULL = Euclidean index
     float2* bt;      // [C*bt_m] top-m bias table: pairs (radius, bias) per cluster, unused entries (0, -inf); NULL = none
     int bt_m;        // entries per cluster (0 = no table)
     float ln_nmax;   // ln of the largest cluster size

@@ -231,6 +231,7 @@ __global__ __launch_bounds__(256) void radius_finish_kernel(const float* __restr
 // assign_reduce_kernel picks the best over the groups.
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 as_bf16x8_t;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float as_floatx4_t;
+#define CSV_ANGLE_SLACK (1.0 / 4096.0)     // added to every angular radius (radians), next to the relative slack
 #define AS_NT 4                 // cluster tiles of 16 per block
 #define AS_KC 256               // K chunk staged in LDS: AS_NT*16 clusters x 3 pieces x AS_KC x 2 bytes = 96 KB
 #define AS_THREADS 512
@@ -260,9 +261,14 @@ __device__ __forceinline__ unsigned row16_min_u(unsigned v) {
     return v;
 }
 
-__global__ __launch_bounds__(256) void centroid_norm_kernel(const float* __restrict__ mu, int d, float* __restrict__ cn) {
+// unit != 0 (spherical clustering): every direction counts as of length one, so the arg-min is the largest cosine
+__global__ __launch_bounds__(256) void centroid_norm_kernel(const float* __restrict__ mu, int d, int unit, float* __restrict__ cn) {
     __shared__ double red[4];
     const int c = blockIdx.x, tid = threadIdx.x;
+    if (unit) {
+        if (tid == 0) cn[c] = 1.f;
+        return;
+    }
     double acc = 0.0;
     for (int j = tid; j < d; j += 256) acc += (double)mu[(size_t)c * d + j] * (double)mu[(size_t)c * d + j];
     acc = wave_sum_d(acc);
@@ -367,6 +373,144 @@ __global__ __launch_bounds__(256) void init_centroid_kernel(const uint16_t* __re
     for (int j = threadIdx.x; j < d; j += 256) mu[(size_t)c * d + j] = __uint_as_float((uint32_t)w[j] << 16);
 }
 
+// ------------------------------------------------------------------------------------------------ spherical clustering
+// (Section III, "Advanced Theoretical Improvements", spherical clustering metrics)
+// ||W_r|| of every row (original or permuted order, whichever W is), float64.  One wave per row.
+__global__ __launch_bounds__(256) void row_norm_kernel(const uint16_t* __restrict__ W, int V, int d, double* __restrict__ nrm) {
+    const int lane = threadIdx.x & 63;
+    const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (r >= V) return;
+    const uint4* w = reinterpret_cast<const uint4*>(W + (size_t)r * d);
+    double acc = 0.0;
+    for (int q = lane; q < (d >> 3); q += 64) {
+        const uint4 x = w[q];
+        const uint32_t xs[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const double a0 = (double)__uint_as_float(xs[e] << 16), a1 = (double)__uint_as_float(xs[e] & 0xffff0000u);
+            acc = fma(a0, a0, acc);
+            acc = fma(a1, a1, acc);
+        }
+    }
+    acc = wave_sum_d(acc);
+    if (lane == 0) nrm[r] = sqrt(acc);
+}
+
+// Starting directions: row init_rows[c] of W, normalised, as float32.
+__global__ __launch_bounds__(256) void init_direction_kernel(const uint16_t* __restrict__ W, const int32_t* __restrict__ rows,
+                                                             const double* __restrict__ nrm, int d, float* __restrict__ mu) {
+    const int c = blockIdx.x;
+    const uint16_t* w = W + (size_t)rows[c] * d;
+    const double nr = nrm[rows[c]];
+    for (int j = threadIdx.x; j < d; j += 256) {
+        const double v = (double)__uint_as_float((uint32_t)w[j] << 16);
+        mu[(size_t)c * d + j] = (float)(nr > 0.0 ? v / nr : v);
+    }
+}
+
+// sums[c][col] = sum over the cluster's rows of W'[r][col] / ||W'[r]||, float64, row by row (nrm in permuted order).
+__global__ __launch_bounds__(256) void direction_sum_kernel(const uint16_t* __restrict__ Wp, const int32_t* __restrict__ off,
+                                                            const double* __restrict__ nrm, int d, double* __restrict__ sums) {
+    const int c = blockIdx.x;
+    const int col = blockIdx.y * 256 + threadIdx.x;
+    if (col >= d) return;
+    const int r0 = off[c], r1 = off[c + 1];
+    double sum = 0.0;
+    for (int r = r0; r < r1; ++r) {
+        const double nr = nrm[r];
+        const double v = (double)__uint_as_float((uint32_t)Wp[(size_t)r * d + col] << 16);
+        sum += nr > 0.0 ? v / nr : v;
+    }
+    sums[(size_t)c * d + col] = sum;
+}
+
+// mu[c] = sums[c] / ||sums[c]|| as float32; an empty cluster keeps its direction (Lloyd) or is zeroed (final metadata).
+__global__ __launch_bounds__(256) void direction_finish_kernel(const double* __restrict__ sums, const int32_t* __restrict__ off, int d,
+                                                               int zero_empty, float* __restrict__ mu) {
+    __shared__ double red[4];
+    const int c = blockIdx.x, tid = threadIdx.x;
+    if (off[c + 1] == off[c]) {
+        if (zero_empty)
+            for (int j = tid; j < d; j += 256) mu[(size_t)c * d + j] = 0.f;
+        return;
+    }
+    double acc = 0.0;
+    for (int j = tid; j < d; j += 256) acc += sums[(size_t)c * d + j] * sums[(size_t)c * d + j];
+    acc = wave_sum_d(acc);
+    if ((tid & 63) == 0) red[tid >> 6] = acc;
+    __syncthreads();
+    const double nr = sqrt((red[0] + red[1]) + (red[2] + red[3]));
+    for (int j = tid; j < d; j += 256) {
+        const double v = sums[(size_t)c * d + j];
+        mu[(size_t)c * d + j] = (float)(nr > 0.0 ? v / nr : v);
+    }
+}
+
+// Per row (one wave): cosine to its cluster's stored direction and its norm, folded into per-cluster extremes with
+// integer atomics: cosines are shifted by +2 (positive doubles order like their bit patterns).
+// ext[c] = {min (cos + 2), max ||w||^2 bits, min ||w||^2 bits}
+__global__ __launch_bounds__(256) void row_angle_kernel(const uint16_t* __restrict__ Wp, const int32_t* __restrict__ off,
+                                                        const float* __restrict__ mu, int V, int d, int C,
+                                                        unsigned long long* __restrict__ ext) {
+    const int lane = threadIdx.x & 63;
+    const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (r >= V) return;
+    int lo = 0, hi = C;
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (off[mid] <= r) lo = mid; else hi = mid;
+    }
+    const uint4* w = reinterpret_cast<const uint4*>(Wp + (size_t)r * d);
+    const float4* m = reinterpret_cast<const float4*>(mu + (size_t)lo * d);
+    double ww = 0.0, wm = 0.0, mm = 0.0;
+    for (int q = lane; q < (d >> 3); q += 64) {
+        const uint4 x = w[q];
+        const float4 m0 = m[2 * q], m1 = m[2 * q + 1];
+        const uint32_t xs[4] = {x.x, x.y, x.z, x.w};
+        const float ms[8] = {m0.x, m0.y, m0.z, m0.w, m1.x, m1.y, m1.z, m1.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const double a0 = (double)__uint_as_float(xs[e] << 16), a1 = (double)__uint_as_float(xs[e] & 0xffff0000u);
+            const double b0 = (double)ms[2 * e], b1 = (double)ms[2 * e + 1];
+            ww = fma(a0, a0, ww); ww = fma(a1, a1, ww);
+            wm = fma(a0, b0, wm); wm = fma(a1, b1, wm);
+            mm = fma(b0, b0, mm); mm = fma(b1, b1, mm);
+        }
+    }
+    ww = wave_sum_d(ww);
+    wm = wave_sum_d(wm);
+    mm = wave_sum_d(mm);
+    if (lane == 0) {
+        const double nw = sqrt(ww), nm = sqrt(mm);
+        double cs = nw > 0.0 ? wm / (nw * (nm > 0.0 ? nm : 1.0)) : 1.0;
+        cs = fmin(1.0, fmax(-1.0, cs));
+        atomicMin(&ext[3 * lo], (unsigned long long)__double_as_longlong(cs + 2.0));
+        atomicMax(&ext[3 * lo + 1], (unsigned long long)__double_as_longlong(ww));
+        atomicMin(&ext[3 * lo + 2], (unsigned long long)__double_as_longlong(ww));
+    }
+}
+
+// ang[c] = {cos, sin of the angular radius with slack, largest norm (1+slack) rounded up, smallest (1-slack) rounded down}
+__global__ __launch_bounds__(256) void angular_finish_kernel(const int32_t* __restrict__ off, int C, double slack, double angle_slack,
+                                                             const unsigned long long* __restrict__ ext, float4* __restrict__ ang) {
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    if (c >= C) return;
+    if (off[c + 1] == off[c]) {
+        ang[c] = make_float4(1.f, 0.f, 0.f, 0.f);
+        return;
+    }
+    const double mincos = __longlong_as_double((long long)ext[3 * c]) - 2.0;
+    double theta = acos(fmin(1.0, fmax(-1.0, mincos)));
+    const double pi = 3.14159265358979323846;
+    theta = fmin(pi, theta * (1.0 + slack) + angle_slack);
+    auto up = [](double x) { float y = (float)x; if ((double)y < x) y = nextafterf(y, INFINITY); return y; };
+    auto down = [](double x) { float y = (float)x; if ((double)y > x) y = nextafterf(y, -INFINITY); return y; };
+    const float ct = theta < pi ? down(cos(theta)) : -1.f;
+    const float st = up(sin(theta));
+    const double nmax = sqrt(__longlong_as_double((long long)ext[3 * c + 1])), nmin = sqrt(__longlong_as_double((long long)ext[3 * c + 2]));
+    ang[c] = make_float4(ct, st, up(nmax * (1.0 + slack)), down(nmin * (1.0 - slack)));
+}
+
 // cmeta[c] = {off[c], off[c+1] - off[c], bits of ln n_c, 0}
 __global__ __launch_bounds__(256) void pack_cmeta_kernel(const int32_t* __restrict__ off, const float* __restrict__ lnn, int C,
                                                          int4* __restrict__ cmeta) {
@@ -408,7 +552,7 @@ int csv_index_alloc(int V, int d, int C, csv_index** out) {
 
 extern "C" void csv_index_free(csv_index* x) {
     if (!x) return;
-    void* ptrs[] = {x->Wp, x->bp, x->perm, x->mu, x->mu16, x->R, x->bmax, x->n, x->off, x->lnn, x->cmeta, x->bt};
+    void* ptrs[] = {x->Wp, x->bp, x->perm, x->mu, x->mu16, x->R, x->bmax, x->n, x->off, x->lnn, x->cmeta, x->bt, x->ang};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
     free(x);
@@ -519,11 +663,17 @@ extern "C" int csv_build_index(const uint16_t* d_W, const float* d_b, int V, int
     unsigned* d_ckey = nullptr;
     int32_t* d_cc = nullptr;
     float* d_cn = nullptr;
+    // spherical clustering: row norms in original and in permuted order, float64 sums of unit rows
+    const int sph = o->spherical != 0;
+    double *d_nrm = nullptr, *d_nrmp = nullptr, *d_sums = nullptr;
     auto free_scratch = [&]() {
         if (d_labels) (void)hipFree(d_labels);
         if (d_ckey) (void)hipFree(d_ckey);
         if (d_cc) (void)hipFree(d_cc);
         if (d_cn) (void)hipFree(d_cn);
+        if (d_nrm) (void)hipFree(d_nrm);
+        if (d_nrmp) (void)hipFree(d_nrmp);
+        if (d_sums) (void)hipFree(d_sums);
     };
     auto fail = [&](int code) {
         free_scratch();
@@ -532,6 +682,13 @@ extern "C" int csv_build_index(const uint16_t* d_W, const float* d_b, int V, int
     };
     if (hipMalloc((void**)&d_labels, (size_t)V * 4) != hipSuccess) { csv_set_error("label buffer allocation failed"); return fail(CSV_ENOMEM); }
     const dim3 cgrid(C, (d + 255) / 256);
+    if (sph) {
+        if (o->centroid_bf16 || o->bias_table_m >= 2) { csv_set_error("spherical clustering takes neither bf16 centroids nor a bias table"); return fail(CSV_EINVAL); }
+        if (hipMalloc((void**)&d_nrm, (size_t)V * 8) != hipSuccess || hipMalloc((void**)&d_nrmp, (size_t)V * 8) != hipSuccess ||
+            hipMalloc((void**)&d_sums, (size_t)C * d * 8) != hipSuccess) { csv_set_error("out of device memory (spherical clustering scratch)"); return fail(CSV_ENOMEM); }
+        row_norm_kernel<<<(V + 3) / 4, 256, 0, st>>>(d_W, V, d, d_nrm);
+        if (hipGetLastError() != hipSuccess) { csv_set_error("launch of row_norm_kernel failed"); return fail(CSV_EHIP); }
+    }
     const int G = (C + AS_NT * 16 - 1) / (AS_NT * 16);
     auto assign = [&]() -> int {
         if (!d_ckey) {
@@ -539,7 +696,7 @@ extern "C" int csv_build_index(const uint16_t* d_W, const float* d_b, int V, int
                 hipMalloc((void**)&d_cn, (size_t)C * 4) != hipSuccess) { csv_set_error("out of device memory (assignment scratch)"); return CSV_ENOMEM; }
             CSV_HIP(hipFuncSetAttribute((const void*)assign_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, AS_LDS));
         }
-        centroid_norm_kernel<<<C, 256, 0, st>>>(x->mu, d, d_cn);
+        centroid_norm_kernel<<<C, 256, 0, st>>>(x->mu, d, sph, d_cn);
         CSV_LAUNCH_CHECK("centroid_norm_kernel");
         assign_mfma_kernel<<<dim3(G, (V + 127) / 128), AS_THREADS, AS_LDS, st>>>(d_W, x->mu, d_cn, V, d, C, G, d_ckey, d_cc);
         CSV_LAUNCH_CHECK("assign_mfma_kernel");
@@ -559,7 +716,8 @@ extern "C" int csv_build_index(const uint16_t* d_W, const float* d_b, int V, int
             if (seed[c] < 0 || seed[c] >= V) { csv_set_error("init row %d outside 0..V-1", seed[c]); return fail(CSV_EINVAL); }
         // x->n doubles as the staging buffer for the starting rows
         if (hipMemcpy(x->n, seed.data(), (size_t)C * 4, hipMemcpyHostToDevice) != hipSuccess) { csv_set_error("copy of init rows failed"); return fail(CSV_EHIP); }
-        init_centroid_kernel<<<C, 256, 0, st>>>(d_W, x->n, d, x->mu);
+        if (sph) init_direction_kernel<<<C, 256, 0, st>>>(d_W, x->n, d_nrm, d, x->mu);
+        else init_centroid_kernel<<<C, 256, 0, st>>>(d_W, x->n, d, x->mu);
         if ((rc = assign())) return fail(rc);
     }
     for (int it = 0;; ++it) {
@@ -567,8 +725,14 @@ extern "C" int csv_build_index(const uint16_t* d_W, const float* d_b, int V, int
         if ((rc = upload_layout(x, n, off, perm, st))) return fail(rc);
         if ((rc = gather(x, d_W, d_b, st))) return fail(rc);
         const bool last = it == o->iters;
-        centroid_kernel<<<cgrid, 256, 0, st>>>(x->Wp, x->off, d, last ? 1 : 0, x->mu);
-        if (hipGetLastError() != hipSuccess) { csv_set_error("launch of centroid_kernel failed"); return fail(CSV_EHIP); }
+        if (sph) {
+            row_norm_kernel<<<(V + 3) / 4, 256, 0, st>>>(x->Wp, V, d, d_nrmp);
+            direction_sum_kernel<<<cgrid, 256, 0, st>>>(x->Wp, x->off, d_nrmp, d, d_sums);
+            direction_finish_kernel<<<C, 256, 0, st>>>(d_sums, x->off, d, last ? 1 : 0, x->mu);
+        } else {
+            centroid_kernel<<<cgrid, 256, 0, st>>>(x->Wp, x->off, d, last ? 1 : 0, x->mu);
+        }
+        if (hipGetLastError() != hipSuccess) { csv_set_error("launch of the centroid kernels failed"); return fail(CSV_EHIP); }
         if (last) break;
         if ((rc = assign())) return fail(rc);
     }
@@ -604,7 +768,24 @@ extern "C" int csv_build_index(const uint16_t* d_W, const float* d_b, int V, int
         launched = hipGetLastError() == hipSuccess;
     }
     if (launched) launched = csv_index_pack_cmeta(x, st) == CSV_OK;
+    unsigned long long* d_ext = nullptr;
+    if (launched && sph) {          // angular metadata in place of the Euclidean radius (which stays unused)
+        std::vector<unsigned long long> init((size_t)3 * C);
+        for (int c = 0; c < C; ++c) {
+            init[3 * c] = ~0ull;
+            init[3 * c + 1] = 0ull;
+            init[3 * c + 2] = ~0ull;
+        }
+        launched = hipMalloc((void**)&d_ext, (size_t)3 * C * 8) == hipSuccess && hipMalloc((void**)&x->ang, (size_t)C * sizeof(float4)) == hipSuccess &&
+                   hipMemcpy(d_ext, init.data(), (size_t)3 * C * 8, hipMemcpyHostToDevice) == hipSuccess;
+        if (launched) {
+            row_angle_kernel<<<(V + 3) / 4, 256, 0, st>>>(x->Wp, x->off, x->mu, V, d, C, d_ext);
+            angular_finish_kernel<<<(C + 255) / 256, 256, 0, st>>>(x->off, C, (double)o->radius_slack, CSV_ANGLE_SLACK, d_ext, x->ang);
+            launched = hipGetLastError() == hipSuccess;
+        }
+    }
     const bool synced = hipStreamSynchronize(st) == hipSuccess;
+    if (d_ext) (void)hipFree(d_ext);
     (void)hipFree(d_d2max);
     if (d_d2row) (void)hipFree(d_d2row);
     if (!launched) { csv_set_error("launch of the radius kernels failed"); return fail(CSV_EHIP); }
@@ -691,5 +872,30 @@ extern "C" int csv_index_get_bias_table(const csv_index* x, int* m, float* h_tab
     if (!x || !m) { csv_set_error("null index or m"); return CSV_EINVAL; }
     *m = x->bt_m;
     if (h_table && x->bt_m) CSV_HIP(hipMemcpy(h_table, x->bt, (size_t)x->C * x->bt_m * sizeof(float2), hipMemcpyDeviceToHost));
+    return CSV_OK;
+}
+
+extern "C" int csv_index_set_angular(csv_index* x, const float* h_ang, void* stream) {
+    if (!x) { csv_set_error("null index"); return CSV_EINVAL; }
+    hipStream_t st = (hipStream_t)stream;
+    if (!h_ang) {
+        if (x->ang) {
+            CSV_HIP(hipStreamSynchronize(st));
+            (void)hipFree(x->ang);
+            x->ang = nullptr;
+        }
+        return CSV_OK;
+    }
+    if (x->bt || x->mu16) { csv_set_error("an angular index takes neither a bias table nor bf16 centroids"); return CSV_EINVAL; }
+    if (!x->ang && hipMalloc((void**)&x->ang, (size_t)x->C * sizeof(float4)) != hipSuccess) { csv_set_error("out of device memory (angular metadata)"); return CSV_ENOMEM; }
+    CSV_HIP(hipMemcpyAsync(x->ang, h_ang, (size_t)x->C * sizeof(float4), hipMemcpyHostToDevice, st));
+    CSV_HIP(hipStreamSynchronize(st));
+    return CSV_OK;
+}
+
+extern "C" int csv_index_get_angular(const csv_index* x, int* present, float* h_ang) {
+    if (!x || !present) { csv_set_error("null index or present"); return CSV_EINVAL; }
+    *present = x->ang != nullptr;
+    if (h_ang && x->ang) CSV_HIP(hipMemcpy(h_ang, x->ang, (size_t)x->C * sizeof(float4), hipMemcpyDeviceToHost));
     return CSV_OK;
 }

@@ -49,6 +49,7 @@ struct StepArgs {
     const float* lnn;
     const int4* cmeta;      // per cluster {first row, rows, bits of ln n, 0}
     const float2* bt;       // top-m bias table, [C * bt_m] pairs (radius, bias), or NULL
+    const float4* ang;      // angular index: {cos, sin of the angular radius, largest, smallest row norm} per cluster, or NULL
     int bt_m;
     float ln_nmax;
     int B, B_max, K_cap, Npad, n_chunks, tile_stride;
@@ -135,7 +136,18 @@ __device__ __forceinline__ void reset_step_counters(int* counters, int B, int nt
 // ================================================================================================ bounds
 // What a cluster adds to <mu_c,h>: R_c ||h|| + max bias (Eq. "cluster_bound"), or, with a top-m bias table, the
 // largest of its m terms rho_j ||h|| + beta_j (the m-1 tokens with the largest biases one by one, the rest together).
+// With an angular index (spherical clustering) mu_c is a unit direction and the bound is
+//   rho ||h|| cos(phi - theta_c) = rho (t cos(theta_c) + sqrt(||h||^2 - t^2) sin(theta_c)),  t = <mu_c,h> = ||h|| cos(phi),
+// outside the cluster's cone and rho_max ||h|| inside it; rho is the largest row norm for a positive value, the smallest
+// for a negative one.
 __device__ __forceinline__ float bound_value(const StepArgs& a, int c, float dot, float Rc, float bm, float hn) {
+    if (a.ang) {
+        const float4 g = a.ang[c];
+        const float perp = sqrtf(fmaxf(hn * hn - dot * dot, 0.f));
+        const float v = dot * g.x + perp * g.y;
+        const float val = dot >= hn * g.x ? g.z * hn : (v >= 0.f ? g.z * v : g.w * v);
+        return val + bm;
+    }
     if (!a.bt) return dot + Rc * hn + bm;
     const float2* t = a.bt + (size_t)c * a.bt_m;
     float best = -INFINITY;
@@ -2325,7 +2337,7 @@ static void fill_args(StepArgs& a, const csv_workspace* ws, const csv_index* idx
     memset(&a, 0, sizeof(a));
     a.V = idx->V; a.d = idx->d; a.C = idx->C;
     a.Wp = idx->Wp; a.bp = idx->bp; a.perm = idx->perm; a.mu = idx->mu; a.mu16 = idx->mu16; a.R = idx->R; a.bmax = idx->bmax;
-    a.n = idx->n; a.off = idx->off; a.lnn = idx->lnn; a.cmeta = idx->cmeta; a.bt = idx->bt; a.bt_m = idx->bt_m; a.ln_nmax = idx->ln_nmax;
+    a.n = idx->n; a.off = idx->off; a.lnn = idx->lnn; a.cmeta = idx->cmeta; a.bt = idx->bt; a.bt_m = idx->bt_m; a.ang = idx->ang; a.ln_nmax = idx->ln_nmax;
     a.K_cap = ws->K_cap; a.Npad = ws->Npad; a.n_chunks = ws->n_chunks; a.tile_stride = ws->tile_stride; a.sp_chunks = ws->sp_chunks; a.cand_chunks = ws->cand_chunks;
     a.U = ws->U; a.hnorm = ws->hnorm; a.bound_partial = ws->bound_partial; a.st = ws->st; a.sel = ws->sel; a.slog = ws->slog; a.sid = ws->sid; a.slots = ws->slots; a.B_max = ws->B_max;
     a.tiles[0] = ws->tiles[0]; a.tiles[1] = ws->tiles[1]; a.counters = ws->counters;
@@ -2641,7 +2653,7 @@ extern "C" int csv_bounds_static(const csv_index* idx, const uint16_t* d_h, int 
     StepArgs a;
     memset(&a, 0, sizeof(a));
     a.V = idx->V; a.d = idx->d; a.C = idx->C;
-    a.mu = idx->mu; a.mu16 = idx->mu16; a.R = idx->R; a.bmax = idx->bmax; a.n = idx->n; a.bt = idx->bt; a.bt_m = idx->bt_m;
+    a.mu = idx->mu; a.mu16 = idx->mu16; a.R = idx->R; a.bmax = idx->bmax; a.n = idx->n; a.bt = idx->bt; a.bt_m = idx->bt_m; a.ang = idx->ang;
     a.B = B; a.h = d_h;
     if (B > 8) {                       // the batched product is the only bound kernel with scratch: KS x B x C partial sums
         int KS, kbs;

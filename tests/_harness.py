@@ -20,7 +20,7 @@ def log(msg: str) -> None:
 class Case:
     def __init__(self, recipe: synth.Recipe, seed: int = synth.SEED, bias: bool = True, radius_slack: float = 2.0 ** -14,
                  labels=None, B_max=None, K_cap=None, want_W64: bool = True, W_bits=None, centroid_bf16: bool = False,
-                 bias_table_m: int = 0, b=None):
+                 bias_table_m: int = 0, b=None, angular: bool = False):
         import torch
         import paper_2511_21702_amd as csv
         self.csv, self.torch = csv, torch
@@ -34,8 +34,11 @@ class Case:
         self.C = recipe.C if labels is None else int(np.max(labels)) + 1
         log(f"[{recipe.name}] head V={recipe.V} d={recipe.d} C={self.C} generated in {time.time() - t0:.1f}s")
         t0 = time.time()
-        self.oidx = O.build_index(self.head["W_bits"], self.b, self.labels, self.C, radius_slack=radius_slack,
-                                  centroid_bf16=centroid_bf16, bias_table_m=bias_table_m)
+        if angular:
+            self.oidx = O.build_index_angular(self.head["W_bits"], self.b, self.labels, self.C, slack=radius_slack)
+        else:
+            self.oidx = O.build_index(self.head["W_bits"], self.b, self.labels, self.C, radius_slack=radius_slack,
+                                      centroid_bf16=centroid_bf16, bias_table_m=bias_table_m)
         log(f"[{recipe.name}] oracle index in {time.time() - t0:.1f}s")
         self.W64 = O.bf16_to_f64(self.head["W_bits"]) if want_W64 else None
         self.dW = csv.bits_to_device(self.head["W_bits"])
@@ -45,6 +48,8 @@ class Case:
                                               centroid_bf16=centroid_bf16)
         if self.oidx.bias_table is not None:
             self.gidx.set_bias_table(self.oidx.bias_table)
+        if self.oidx.ang is not None:
+            self.gidx.set_angular(self.oidx.ang)
         self.ws = csv.CsvWorkspace(self.gidx, B_max or recipe.B, K_cap if K_cap is not None else recipe.K_max_rows)
         torch.cuda.synchronize()
 

@@ -581,6 +581,71 @@ def test_bias_table_built_on_the_gpu_matches_oracle():
     g.free(); case.close()
 
 
+# ------------------------------------------------------------------ spherical clustering and the angular bound (Section III)
+def _scaled_rows(r, seed):
+    """The generated head with every row stretched by its own factor: directions cluster, lengths do not."""
+    head = synth.make_head(r, seed=seed, threads=4)
+    rng = np.random.default_rng(seed)
+    Wf = synth.bf16_bits_to_f32(head["W_bits"]) * rng.uniform(0.4, 2.5, (r.V, 1)).astype(np.float32)
+    return synth.f32_to_bf16_bits(Wf)
+
+
+@pytest.mark.parametrize("B", [1, 3, 8, 20])
+def test_angular_bounds_and_steps(B):
+    r = synth.small_recipe(f"ang-{B}", V=3001, d=264, C=37, B=B, steps=4, h_mode="mix", iso_frac=0.25, row_noise=0.6)
+    case = Case(r, seed=91, W_bits=_scaled_rows(r, 91), angular=True)
+    csv = case.csv
+    h = case.hidden()
+    h[1] = synth.f32_to_bf16_bits(-synth.bf16_bits_to_f32(h[0]))          # directions opposite to the clusters: negative bounds
+    dh = csv.bits_to_device(h)
+    neg = 0
+    for s in range(h.shape[0]):
+        Ug, hg = csv.csv_bounds(case.ws, case.gidx, dh[s])
+        Ug = Ug.cpu().numpy()
+        h64 = O.bf16_to_f64(h[s])
+        U, hn = O.cluster_bounds(case.oidx, h64)
+        assert np.all(np.abs(Ug - U) <= 2e-5 * np.maximum(1.0, np.abs(U)))
+        neg += int((U < -0.5).sum())
+        L = O.full_logits(case.W64, case.b, h64)
+        assert np.all(L <= Ug[:, case.labels].astype(np.float64) + 1e-4)          # the float32 bounds dominate every logit
+    assert neg > 0
+    t = case.run_steps(h, 5, 1e-3, r.K_max_rows, O.COMBINE_ALL, f"angular B={B}")
+    _finish(t, f"angular B={B}")
+    case.close()
+
+
+def test_spherical_kmeans_and_angular_metadata_built_on_the_gpu():
+    r = synth.small_recipe("sph", V=4000, d=136, C=24, B=2, steps=2, sizes="zipf", row_noise=0.3)
+    Wb = _scaled_rows(r, 92)
+    case = Case(r, seed=92, W_bits=Wb, angular=True)
+    csv = case.csv
+    # metadata from the planted labels
+    g = csv.csv_build_index(case.dW, case.db, r.C, init_labels=case.labels.astype(np.int32), spherical=True)
+    e, ang, o = g.export(), g.angular(), case.oidx
+    assert np.array_equal(e["n"], o.n) and np.array_equal(e["perm"], o.perm) and np.array_equal(e["bmax"], o.bmax)
+    ulp_mu = np.abs(e["mu"].view(np.int32).astype(np.int64) - o.mu.view(np.int32).astype(np.int64))
+    ulp_ang = np.abs(ang.view(np.int32).astype(np.int64) - o.ang.view(np.int32).astype(np.int64))
+    log(f"  angular index: direction ulp diff max {ulp_mu.max()}, metadata ulp diff max {ulp_ang.max()}")
+    assert ulp_mu.max() <= 1 and ulp_ang.max() <= 4
+    g.free()
+    # spherical Lloyd from given rows, two iterations
+    first = np.array([int(np.flatnonzero(case.labels == c)[0]) for c in range(r.C)], dtype=np.int32)
+    labels, dirs = O.spherical_kmeans(Wb, first, iters=2)
+    want = O.build_index_angular(Wb, case.b, labels, r.C)
+    g = csv.csv_build_index(case.dW, case.db, r.C, init_rows=first, iters=2, spherical=True)
+    e = g.export()
+    assert np.array_equal(e["n"], want.n) and np.array_equal(e["perm"], want.perm)
+    assert np.allclose(e["mu"], want.mu, rtol=0, atol=2e-7)
+    assert np.allclose(g.angular(), want.ang, rtol=1e-5, atol=1e-6)
+    # Euclidean Lloyd groups these rows differently (their lengths vary): the two modes are really different
+    ge = csv.csv_build_index(case.dW, case.db, r.C, init_rows=first, iters=2)
+    assert not np.array_equal(ge.export()["perm"], e["perm"])
+    assert ge.angular() is None
+    with pytest.raises(csv.CsvError):
+        csv.csv_build_index(case.dW, case.db, r.C, init_rows=first, spherical=True, bias_table_m=3)
+    ge.free(); g.free(); case.close()
+
+
 # ------------------------------------------------------------------ top-p (nucleus) certificate, delta form
 def test_nucleus_certificate_on_the_gpu():
     # Section III, top-p certification: a step run with eps = delta / (1 + delta) carries the coverage certificate.
