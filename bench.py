@@ -42,6 +42,7 @@ def main() -> int:
     ap.add_argument("--delta-clusters", type=int, default=0, help="fallback levels: clusters per partial expansion (0 = off)")
     ap.add_argument("--bf16-centroids", action="store_true", help="index option: centroids stored as bfloat16 (half the bound kernel's bytes)")
     ap.add_argument("--bias-table", type=int, default=0, help="index option: top-m bias table (Section III, bias binning), m = 2..8")
+    ap.add_argument("--spherical", action="store_true", help="index option: unit directions and the angular bound (Section III, spherical clustering)")
     ap.add_argument("--relax", action="store_true", help="fallback levels: accept the softmax bound at 2 eps before falling back")
     ap.add_argument("--cpu-steps", type=int, default=-1, help="oracle steps to time (-1: sized to ~15 s, 0: skip)")
     ap.add_argument("--kmeans", type=int, default=-1, metavar="ITERS",
@@ -95,7 +96,7 @@ def main() -> int:
                           "empty_clusters": int((e["n"] == 0).sum()), "largest_cluster": int(e["n"].max()), "purity_vs_planted": float(purity)}))
         return 0
     idx = csv.csv_build_index(dW, db, r.C, init_labels=head["labels"].astype(np.int32), centroid_bf16=args.bf16_centroids,
-                              bias_table_m=args.bias_table)
+                              bias_table_m=args.bias_table, spherical=args.spherical)
     del dW
     ws = csv.CsvWorkspace(idx, r.B, r.K_max_rows)
     dh = csv.bits_to_device(h_bits)
@@ -333,7 +334,11 @@ def main() -> int:
         except Exception:
             cores = os.cpu_count()
         W64 = O.bf16_to_f64(head["W_bits"])
-        oidx = O.build_index(head["W_bits"], head["b"], head["labels"], r.C, centroid_bf16=args.bf16_centroids)
+        if args.spherical:
+            oidx = O.build_index_angular(head["W_bits"], head["b"], head["labels"], r.C)
+        else:
+            oidx = O.build_index(head["W_bits"], head["b"], head["labels"], r.C, centroid_bf16=args.bf16_centroids,
+                                 bias_table_m=args.bias_table)
         t1 = time.perf_counter()
         olad = dict(max_rounds=max(args.max_rounds, 2), delta_clusters=args.delta_clusters, relax=args.relax)
         O.decode_step(W64, head["b"], oidx, h_bits[0], r.k, r.eps, r.K_max_rows, **olad)
@@ -356,6 +361,7 @@ def main() -> int:
                                f"combine=ALL, bf16 W and h, float32 accumulation, planted clusters"
                                + (", bf16 centroids" if args.bf16_centroids else "")
                                + (f", top-{args.bias_table} bias table" if args.bias_table >= 2 else "")
+                               + (", angular index" if args.spherical else "")
                                + (f", fallback levels max_rounds={args.max_rounds} delta_clusters={args.delta_clusters} relax={int(args.relax)}"
                                   if (args.max_rounds or args.delta_clusters or args.relax) else ""), "batch": r.B},
         "roofline": roof,
