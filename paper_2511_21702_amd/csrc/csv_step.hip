@@ -1268,14 +1268,16 @@ __device__ __forceinline__ void write_distribution(const StepArgs& a, int b, int
 // logits, publishes the chunk's top-k candidates and log-sum-exp partial, and the block that arrives last (a
 // device-scope counter; nobody waits) merges them and goes on to the tests.
 // staged: the caller has already put the sequence's logits and ids where the staging below would put them
-__device__ __forceinline__ void cert_body(const StepArgs& a, int b, int chunk, int round, const SeqState& st, SeqShared& s,
+// Returns true when the sequence is finished (its outputs are written), false when work was queued for later phases
+// (another round, the full vocabulary) or nothing was done.
+__device__ __forceinline__ bool cert_body(const StepArgs& a, int b, int chunk, int round, const SeqState& st, SeqShared& s,
                                           bool staged = false) {
     extern __shared__ u64 arena[];
     const int tid = threadIdx.x, nt = blockDim.x, C = a.C;
-    if (st.status != ST_ACTIVE || st.rounds != round) return;
+    if (st.status != ST_ACTIVE || st.rounds != round) return false;
     const int n = st.n_rows;
     const int nchunks = (n + STAGE_CAP - 1) / STAGE_CAP;
-    if (chunk >= nchunks) return;
+    if (chunk >= nchunks) return false;
     const int c0 = chunk * STAGE_CAP, len = min(STAGE_CAP, n - c0);
     if (round >= 1) DBG_T(12);
     if (!staged) {
@@ -1317,7 +1319,7 @@ __device__ __forceinline__ void cert_body(const StepArgs& a, int b, int chunk, i
         __syncthreads();
         if (tid == 0) s.sel = atomicAdd(&a.counters[CNT_CHUNKS + round * CSV_MAX_BATCH + b], 1) == nchunks - 1;
         __syncthreads();
-        if (!s.sel) return;
+        if (!s.sel) return false;
         __threadfence();
         float mx = -INFINITY;
         for (int i = tid; i < nchunks; i += nt) mx = fmaxf(mx, a.cand_max[pb + i]);
@@ -1371,7 +1373,7 @@ __device__ __forceinline__ void cert_body(const StepArgs& a, int b, int chunk, i
     if (ok) {
         finish(((tk && a.use_k) ? CSV_FLAG_TOPK_CERT : 0u) | ((sm && a.use_s) ? CSV_FLAG_SOFTMAX_CERT : 0u));
         if (round >= 1) DBG_T(16);
-        return;
+        return true;
     }
     if (round + 1 < a.max_rounds) {
         // ---- plan the next round: the open set grows from {key >= kappa0} to {key >= kappa1}
@@ -1445,7 +1447,7 @@ __device__ __forceinline__ void cert_body(const StepArgs& a, int b, int chunk, i
                 o.n_open = st.n_open + cnt; o.n_rows = n + rows; o.rounds = round + 1; o.kappa = kappa1; o.nxtU = nxtU; o.T = T1;
                 a.st[b] = o;
             }
-            return;
+            return false;
         }
     }
     // ---- no further expansion: the relaxed tolerance, then the full vocabulary
@@ -1454,10 +1456,11 @@ __device__ __forceinline__ void cert_body(const StepArgs& a, int b, int chunk, i
         const bool ok2 = a.combine == CSV_COMBINE_ALL ? ((tk || !a.use_k) && sm2) : ((tk && a.use_k) || sm2);
         if (ok2) {
             finish(((tk && a.use_k) ? CSV_FLAG_TOPK_CERT : 0u) | (sm ? CSV_FLAG_SOFTMAX_CERT : (sm2 ? CSV_FLAG_SOFTMAX_RELAXED : 0u)));
-            return;
+            return true;
         }
     }
     if (tid == 0) push_fallback(a, b, round + 1);
+    return false;
 }
 
 __device__ __forceinline__ void cert_device(const StepArgs& a, int b, int chunk, int round, SeqShared& s) {
@@ -1572,9 +1575,10 @@ __device__ __forceinline__ void wave_seed_tail(const StepArgs& a, const WaveSeed
     T0 = shift + logf(sum);
 }
 
-// One sequence's round 0 as seen by block j of its NB blocks.  Returns true in the one block that settled the
-// sequence (certified it, planned its next round, handed it over or flagged it), after all that block's writes.
-__device__ __forceinline__ bool round0_device(const StepArgs& a, int b, int j, int NB, SeqShared& s) {
+// One sequence's round 0 as seen by block j of its NB blocks.  Returns nonzero in the one block that settled the
+// sequence: 1 when the sequence is finished (certified, or flagged invalid), 2 when it left work for later phases
+// (a planned round, a hand-over, a fallback) or gave up.
+__device__ __forceinline__ int round0_device(const StepArgs& a, int b, int j, int NB, SeqShared& s) {
     extern __shared__ u64 arena[];
     const int tid = threadIdx.x, nt = SEQ_THREADS, lane = tid & 63, wave = tid >> 6, C = a.C;
     const int nch = a.d >> 3;
@@ -1656,7 +1660,7 @@ __device__ __forceinline__ bool round0_device(const StepArgs& a, int b, int j, i
         DBG_T(3);
         if (!isfinite(hn)) {
             if (j == 0) write_invalid(a, b);
-            return j == 0;
+            return j == 0 ? 1 : 0;
         }
         wave_seed_pick(a, sU, sL, sR, ws);
         fast = ws.kappa != 0 && ws.rows >= need && ws.rows <= cap_rows && ws.rows <= a.K_max;
@@ -1668,14 +1672,13 @@ __device__ __forceinline__ bool round0_device(const StepArgs& a, int b, int j, i
         m0 = 1; rows = ws.rows; kappa = ws.kappa;
         if (p < rows) request_row(ws.row0 + p);
         if (j == 0 && tid == 0) a.sel[(size_t)b * C] = ws.c;
-        DBG_T(7);
-        wave_seed_tail(a, ws, nxtU, T0);
-        DBG_T(8);
+        nxtU = -INFINITY;        // the next bound and the tail mass are needed by the certifying block only: taken after its rows
+        T0 = -INFINITY;
     } else {
         load_clusters(a, b, L);
         if (!isfinite(hn)) {
             if (j == 0) write_invalid(a, b);
-            return j == 0;
+            return j == 0 ? 1 : 0;
         }
         __syncthreads();
         // Open clusters one at a time by block-wide arg-max until max(k,1) rows are open.  Every opened cluster has
@@ -1714,7 +1717,7 @@ __device__ __forceinline__ bool round0_device(const StepArgs& a, int b, int j, i
                 a.st[b].n_rows = rows;
                 push_fallback(a, b, 0);
             }
-            return j == 0;
+            return j == 0 ? 2 : 0;
         }
         __syncthreads();   // scl / spos complete
         if (j == 0)
@@ -1722,7 +1725,7 @@ __device__ __forceinline__ bool round0_device(const StepArgs& a, int b, int j, i
         nxtU = nxt ? ckey_bound(nxt) : -INFINITY;
         if (rows > cap_rows || nch > ROUND0_HREG * nt) {
             // too much for these blocks: the first block queues the prefix for the tail
-            if (j != 0) return false;
+            if (j != 0) return 0;
             T0 = seed_tail_mass(a, L, kappa, nxt, nxtU, s);
             Tile* tl = a.tiles[0] + (size_t)b * a.tile_stride;
             int ntile = 0;
@@ -1741,7 +1744,7 @@ __device__ __forceinline__ bool round0_device(const StepArgs& a, int b, int j, i
                 __hip_atomic_store(&a.counters[CNT_TAIL_NEEDED], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 a.st[b] = seed_state(m0, rows, kappa, nxtU, T0);
             }
-            return true;
+            return 2;
         }
         // h goes to its own LDS region behind the cluster data; the wave's first row is requested before the tail
         // mass is summed, so that sum runs while the loads are in flight
@@ -1764,7 +1767,6 @@ __device__ __forceinline__ bool round0_device(const StepArgs& a, int b, int j, i
         if (p < rows) request_row(row_of(p));
         T0 = seed_tail_mass(a, L, kappa, nxt, nxtU, s);
     }
-    const SeqState st = seed_state(m0, rows, kappa, nxtU, T0);
     if (!fast) __syncthreads();            // h staged (the fast path staged it before its barrier)
     DBG_T(4);
     while (p < rows) {
@@ -1796,7 +1798,9 @@ __device__ __forceinline__ bool round0_device(const StepArgs& a, int b, int j, i
     // is either still empty or complete), puts the logit and the id where the certification expects its staged
     // input, copies them to the row arrays that later rounds read, and empties the word for the next step.  All NB
     // blocks of a sequence are resident together (the host sizes the grid so), and the wait is bounded.
-    if (j != 0) return false;
+    if (j != 0) return 0;
+    if (fast) wave_seed_tail(a, ws, nxtU, T0);      // while the other blocks' words are on their way
+    const SeqState st = seed_state(m0, rows, kappa, nxtU, T0);
     __syncthreads();                       // every wave is done with h in LDS: the staging area overlaps it
     float* sv = reinterpret_cast<float*>(arena);
     int* si = reinterpret_cast<int*>(arena) + STAGE_CAP;
@@ -1827,12 +1831,11 @@ __device__ __forceinline__ bool round0_device(const StepArgs& a, int b, int j, i
             atomicExch(&a.counters[CNT_ABORT], 1);
             __hip_atomic_store(&a.counters[CNT_SLOTS_DIRTY], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
-        return true;
+        return 2;
     }
     DBG_T(6);
     if (tid == 0) a.st[b] = st;
-    cert_body(a, b, 0, 0, st, s, true);
-    return true;
+    return cert_body(a, b, 0, 0, st, s, true) ? 1 : 2;
 }
 
 // ================================================================================================ full-vocabulary product
@@ -2227,32 +2230,29 @@ __global__ __launch_bounds__(SEQ_THREADS) void step_kernel(StepArgs a, FullArgs 
     __shared__ int s_flag;
     const int n0 = NB * a.B;
     if ((int)blockIdx.x < n0) {
-        const int b = blockIdx.x / NB;
-        const bool settled = round0_device(a, b, blockIdx.x % NB, NB, s);
+        const int settled = round0_device(a, blockIdx.x / NB, blockIdx.x % NB, NB, s);
         if (!settled) return;
         __syncthreads();                      // all of the block's writes are issued
         if (threadIdx.x == 0) {
-            // Thread 0 wrote the sequence's status itself.  Anything but "done" means something was queued for the
-            // tail's blocks (a work list, a fallback): release it before the count.  A finished sequence left
-            // nothing for them to read.
-            if (a.st[b].status != ST_DONE) __threadfence();
-            atomicAdd(&a.counters[CNT_R0_DONE], 1);
+            // One word tells the parked blocks both things: sequences settled (low half) and whether any of them
+            // left work for the tail (high half).  Work is released before the count; a finished sequence left
+            // nothing for the tail to read.
+            if (settled == 2) __threadfence();
+            atomicAdd(&a.counters[CNT_R0_DONE], settled == 2 ? 0x10001 : 1);
         }
         return;
     }
     if (threadIdx.x == 0) {
-        int ok = 1, spins = 0;
-        while (__hip_atomic_load(&a.counters[CNT_R0_DONE], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < a.B) {
+        int ok = 1, spins = 0, v;
+        while (((v = __hip_atomic_load(&a.counters[CNT_R0_DONE], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) & 0xffff) < a.B) {
             if (++spins > a.spin_limit) {
                 atomicExch(&a.counters[CNT_ABORT], 1);
                 ok = 0;
                 break;
             }
-            __builtin_amdgcn_s_sleep(8);
+            __builtin_amdgcn_s_sleep(4);
         }
-        // Whoever queued work set this word before its release and its count; the loads of this thread are performed
-        // in order, so a zero read here, after the full count, means that nobody did: leave without an acquire.
-        if (ok && __hip_atomic_load(&a.counters[CNT_TAIL_NEEDED], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0) ok = 0;
+        if (ok && (v >> 16) == 0) ok = 0;     // every sequence finished in round 0: nothing to do, nothing to acquire
         if (ok) __threadfence();              // acquire
         s_flag = ok;
     }
