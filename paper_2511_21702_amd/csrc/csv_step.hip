@@ -1284,6 +1284,7 @@ __device__ __forceinline__ bool cert_body(const StepArgs& a, int b, int chunk, i
         const float* gv = a.slog + (size_t)b * a.K_cap + c0;
         const int32_t* gi = a.sid + (size_t)b * a.K_cap + c0;
         stage2_to_lds(reinterpret_cast<float*>(arena), gv, reinterpret_cast<int*>(arena) + STAGE_CAP, gi, len);
+        if (tid < 4 && len + tid < STAGE_CAP) reinterpret_cast<float*>(arena)[len + tid] = -INFINITY;   // see the small path below
         __syncthreads();
     }
     if (round == 0) DBG_T(9); else DBG_T(13);
@@ -1292,7 +1293,60 @@ __device__ __forceinline__ bool cert_body(const StepArgs& a, int b, int chunk, i
     auto idf = [](int i) { return reinterpret_cast<const int*>(arena)[STAGE_CAP + i]; };
     // with a top-k the largest logit is already known when the sum is taken: one block reduction instead of two
     LseAcc l;
-    if (a.use_k) {
+    if (a.use_k && len <= nt) {
+        // Up to one value per thread: ordered top-k and log-sum-exp in one pass with two barriers.  Thread (e, slice)
+        // compares value e with one slice of the others (larger ones, equal ones) and notes the slice's maximum;
+        // after the barrier thread e adds the slices' counts to its rank (ids are looked at only among equal
+        // values), writes itself to its place in the list and contributes exp(v - max) to the sum.
+        int lg = 5;
+        while ((1 << lg) < len) ++lg;
+        const int npad = 1 << lg, slices = nt >> lg;           // slices <= 16
+        const int e = tid & (npad - 1), sl = tid >> lg;
+        // slices of whole float4's; the staged values are followed by -inf up to the next multiple of four
+        const int len4 = (len + 3) >> 2;
+        const int seg4 = (len4 + slices - 1) / slices;
+        const int q0 = min(len4, sl * seg4), q1 = min(len4, q0 + seg4);
+        const float v = val(min(e, len - 1));
+        int gt = 0, eq = 0;
+        float mx = -INFINITY;
+        const float4* v4 = reinterpret_cast<const float4*>(arena);
+#pragma unroll 8
+        for (int q = q0; q < q1; ++q) {
+            const float4 x = v4[q];
+            gt += (x.x > v) + (x.y > v) + (x.z > v) + (x.w > v);
+            eq += (x.x == v) + (x.y == v) + (x.z == v) + (x.w == v);
+            mx = fmaxf(fmaxf(mx, fmaxf(x.x, x.y)), fmaxf(x.z, x.w));
+        }
+        s.rank[tid] = gt | (eq << 16);                          // rank[sl * npad + e]
+        if (e == 0) s.redf[sl] = mx;
+        __syncthreads();
+        float vmax = s.redf[0];
+        for (int q = 1; q < slices; ++q) vmax = fmaxf(vmax, s.redf[q]);
+        float pe = 0.f;
+        const int kk = min(a.k, len);
+        if (tid < len) {
+            int packed = 0;
+            for (int q = 0; q < slices; ++q) packed += s.rank[q * npad + tid];
+            int rank = packed & 0xffff;
+            const int id = idf(tid);
+            if ((packed >> 16) > 1)
+                for (int i = 0; i < len; ++i)
+                    if (val(i) == v && idf(i) < id) rank += 1;
+            if (rank < kk) {
+                s.wval[rank] = v;
+                s.wid[rank] = id;
+            }
+            pe = vmax > -INFINITY ? expf(v - vmax) : 0.f;
+        }
+        pe = wave_sum(pe);
+        float* wsum = reinterpret_cast<float*>(s.hist);
+        if ((tid & 63) == 0) wsum[tid >> 6] = pe;
+        __syncthreads();
+        float tot = 0.f;
+        for (int q = 0; q < (nt >> 6); ++q) tot += wsum[q];
+        l.m = vmax;
+        l.s = tot;
+    } else if (a.use_k) {
         block_topk(len, a.k, val, idf, s);
         if (round == 0) DBG_T(10); else DBG_T(14);
         l.m = s.wval[0];
@@ -1824,6 +1878,7 @@ __device__ __forceinline__ int round0_device(const StepArgs& a, int b, int j, in
         a.slog[(size_t)b * a.K_cap + t] = lv;
         a.sid[(size_t)b * a.K_cap + t] = iv;
     }
+    if (tid < 4 && rows + tid < STAGE_CAP) sv[rows + tid] = -INFINITY;     // the certification reads the values four at a time
     if (__syncthreads_or(gave_up)) {
         // a row never arrived: the step is given up for this sequence (flag ABORTED stays); words may still arrive
         // later, so the next step has to empty the slots before it uses them
@@ -1834,8 +1889,7 @@ __device__ __forceinline__ int round0_device(const StepArgs& a, int b, int j, in
         return 2;
     }
     DBG_T(6);
-    if (tid == 0) a.st[b] = st;
-    return cert_body(a, b, 0, 0, st, s, true) ? 1 : 2;
+    return cert_body(a, b, 0, 0, st, s, true) ? 1 : 2;     // every path of it that leaves work behind writes the state it needs
 }
 
 // ================================================================================================ full-vocabulary product
