@@ -264,8 +264,8 @@ int csv_workspace_set_tail_split(csv_workspace* ws, int min_batch);
  * are not recorded).  csv_profile_end synchronises, writes the summed milliseconds of every stage to
  * h_stage_ms[CSV_PROFILE_STAGES] and the number of recorded steps to *h_steps, frees the events and switches
  * recording off.  Stage order: bounds; round 0 (seed selection, gathered GEMV over the seed prefix and its
- * certification; one kernel); the tail (round-1 GEMV and certification, full-vocabulary product and top-k for
- * fallback sequences; one kernel).
+ * certification; one launch, which for small batches also carries the parked blocks of the tail); the tail (round-1
+ * GEMV and certification, full-vocabulary product and top-k for fallback sequences) when it is launched separately.
  * A stage's time runs from the end of the previous stage to its own end, so it includes its launch gap.
  */
 #define CSV_PROFILE_STAGES 3

@@ -82,16 +82,7 @@ struct StepArgs {
     float lam2;  // the same for the relaxed tolerance 2 eps
     float top_p; // nucleus mass asked for (0 = none)
     csv_step_out out;
-#ifdef CSV_DEBUG_TIMING
-    unsigned long long* dbg;   // [B*64] wall-clock marks of the per-sequence kernels (debug builds only)
-#endif
 };
-
-#ifdef CSV_DEBUG_TIMING
-#define DBG_T(slot) do { if (threadIdx.x == 0 && a.dbg) { a.dbg[blockIdx.x * 64 + (slot)] = wall_clock64(); a.dbg[blockIdx.x * 64 + 32 + (slot)] = clock64(); } } while (0)
-#else
-#define DBG_T(slot) do { } while (0)
-#endif
 
 #define TILE_ROWS 8        // rows per work item of the gathered GEMV (4 waves x 2 rows)
 #define SEQ_THREADS 512    // block size of the per-sequence kernels (seed, cert, fallback top-k)
@@ -816,9 +807,6 @@ __device__ __forceinline__ void gemv_tiles_device(const StepArgs& a, int round, 
     // a block takes a contiguous run of the list: mostly one sequence (h is staged once or twice per block, not
     // once per tile) and neighbouring rows
     const int per = (total + nblocks - 1) / nblocks;
-#ifdef CSV_DEBUG_TIMING
-    if (threadIdx.x == 0 && a.dbg && round == 1) a.dbg[blockIdx.x * 64 + 30] = (unsigned long long)total;
-#endif
     const int g0 = block * per, g1 = min(total, g0 + per);
     int cached[2] = {-1, -1};
     Tile tA = fetch(g0 < g1 ? g0 : total), tB = fetch(g0 + 1 < g1 ? g0 + 1 : total);
@@ -1279,7 +1267,6 @@ __device__ __forceinline__ bool cert_body(const StepArgs& a, int b, int chunk, i
     const int nchunks = (n + STAGE_CAP - 1) / STAGE_CAP;
     if (chunk >= nchunks) return false;
     const int c0 = chunk * STAGE_CAP, len = min(STAGE_CAP, n - c0);
-    if (round >= 1) DBG_T(12);
     if (!staged) {
         const float* gv = a.slog + (size_t)b * a.K_cap + c0;
         const int32_t* gi = a.sid + (size_t)b * a.K_cap + c0;
@@ -1287,7 +1274,6 @@ __device__ __forceinline__ bool cert_body(const StepArgs& a, int b, int chunk, i
         if (tid < 4 && len + tid < STAGE_CAP) reinterpret_cast<float*>(arena)[len + tid] = -INFINITY;   // see the small path below
         __syncthreads();
     }
-    if (round == 0) DBG_T(9); else DBG_T(13);
     // the accessors name the LDS array itself so that the reads compile to LDS instructions
     auto val = [](int i) { return reinterpret_cast<const float*>(arena)[i]; };
     auto idf = [](int i) { return reinterpret_cast<const int*>(arena)[STAGE_CAP + i]; };
@@ -1348,7 +1334,6 @@ __device__ __forceinline__ bool cert_body(const StepArgs& a, int b, int chunk, i
         l.s = tot;
     } else if (a.use_k) {
         block_topk(len, a.k, val, idf, s);
-        if (round == 0) DBG_T(10); else DBG_T(14);
         l.m = s.wval[0];
         float sm = 0.f;
         if (l.m > -INFINITY)
@@ -1357,7 +1342,6 @@ __device__ __forceinline__ bool cert_body(const StepArgs& a, int b, int chunk, i
     } else {
         l = block_lse(len, val, s);
     }
-    if (round == 0) DBG_T(11); else DBG_T(15);
     if (nchunks > 1) {
         const size_t pb = (size_t)b * a.cand_chunks, pc = pb + chunk;
         const int kk = min(a.k, len);
@@ -1426,7 +1410,6 @@ __device__ __forceinline__ bool cert_body(const StepArgs& a, int b, int chunk, i
     };
     if (ok) {
         finish(((tk && a.use_k) ? CSV_FLAG_TOPK_CERT : 0u) | ((sm && a.use_s) ? CSV_FLAG_SOFTMAX_CERT : 0u));
-        if (round >= 1) DBG_T(16);
         return true;
     }
     if (round + 1 < a.max_rounds) {
@@ -1637,7 +1620,6 @@ __device__ __forceinline__ int round0_device(const StepArgs& a, int b, int j, in
     const int tid = threadIdx.x, nt = SEQ_THREADS, lane = tid & 63, wave = tid >> 6, C = a.C;
     const int nch = a.d >> 3;
     const ClusterLds L = carve_clusters(arena, a.Npad, C);
-    DBG_T(0);
     // h is requested now and parked in registers: it moves to LDS once the cluster data there is dead
     uint4 hreg[ROUND0_HREG];
     {
@@ -1709,9 +1691,7 @@ __device__ __forceinline__ int round0_device(const StepArgs& a, int b, int j, in
                 if (i < nch) hs4[i] = hreg[q];
             }
         }
-        DBG_T(2);
         __syncthreads();
-        DBG_T(3);
         if (!isfinite(hn)) {
             if (j == 0) write_invalid(a, b);
             return j == 0 ? 1 : 0;
@@ -1720,7 +1700,6 @@ __device__ __forceinline__ int round0_device(const StepArgs& a, int b, int j, in
         fast = ws.kappa != 0 && ws.rows >= need && ws.rows <= cap_rows && ws.rows <= a.K_max;
         if (!fast) __syncthreads();          // every wave has read the staged bounds: the general path reuses the LDS
     }
-    DBG_T(1);
     if (fast) {
         // the prefix is one cluster: the row first, then the next bound and the tail mass while it is in flight
         m0 = 1; rows = ws.rows; kappa = ws.kappa;
@@ -1764,7 +1743,6 @@ __device__ __forceinline__ int round0_device(const StepArgs& a, int b, int j, in
                 break;
             }
         }
-        DBG_T(2);
         if (rows > a.K_max) {
             if (j == 0 && tid == 0) {
                 a.st[b].n_open = m0;
@@ -1822,7 +1800,6 @@ __device__ __forceinline__ int round0_device(const StepArgs& a, int b, int j, in
         T0 = seed_tail_mass(a, L, kappa, nxt, nxtU, s);
     }
     if (!fast) __syncthreads();            // h staged (the fast path staged it before its barrier)
-    DBG_T(4);
     while (p < rows) {
         float acc = 0.f, acc2 = 0.f;          // two chains: a dependent FMA costs two issue slots of a lone wave
 #pragma unroll
@@ -1847,7 +1824,6 @@ __device__ __forceinline__ int round0_device(const StepArgs& a, int b, int j, in
         p += GW;
         if (p < rows) request_row(row_of(p));
     }
-    DBG_T(5);
     // Block 0 of the sequence collects: each of its threads waits for its rows' words (no counter, no fence: a word
     // is either still empty or complete), puts the logit and the id where the certification expects its staged
     // input, copies them to the row arrays that later rounds read, and empties the word for the next step.  All NB
@@ -1888,7 +1864,6 @@ __device__ __forceinline__ int round0_device(const StepArgs& a, int b, int j, in
         }
         return 2;
     }
-    DBG_T(6);
     return cert_body(a, b, 0, 0, st, s, true) ? 1 : 2;     // every path of it that leaves work behind writes the state it needs
 }
 
@@ -2210,7 +2185,6 @@ __device__ __forceinline__ void tail_device(const StepArgs& a, const FullArgs& f
     int tiles = block_sum_i(mine1, s.redi);
     if (fallback_only) tiles0 = tiles = 0;      // the rounds ran as launches of their own
     if (tiles0 == 0 && tiles == 0 && n_fb0 == 0) return;
-    DBG_T(20);
 
     // Rounds: the GEMV over the round's work list, then the certification, which may plan the next round.
     // Round 0 is here only for seed prefixes that the round-0 blocks handed over.
@@ -2223,17 +2197,13 @@ __device__ __forceinline__ void tail_device(const StepArgs& a, const FullArgs& f
             if (tiles == 0) break;
         }
         gemv_tiles_device(a, r, reinterpret_cast<uint4*>(arena), gs, block, nblocks);
-        if (r == 1) DBG_T(21);
         if (!grid_barrier(a.counters, 2 * r, nblocks, s_flag, a.spin_limit)) return;
-        if (r == 1) DBG_T(22);
         // chunk-major items: the first chunks of all sequences (often the only ones with work) go to distinct blocks
         for (int item = block; item < a.B * a.sp_chunks; item += nblocks) {
             cert_device(a, item % a.B, item / a.B, r, s);
             __syncthreads();
         }
-        if (r == 1) DBG_T(23);
         if (!grid_barrier(a.counters, 2 * r + 1, nblocks, s_flag, a.spin_limit)) return;
-        if (r == 1) DBG_T(24);
     }
     const int n_fb = __hip_atomic_load(&a.counters[CNT_FALLBACK], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
     if (n_fb == 0) return;
@@ -2241,21 +2211,16 @@ __device__ __forceinline__ void tail_device(const StepArgs& a, const FullArgs& f
         full_mfma_all(f, n_fb, reinterpret_cast<uint4*>(arena), a.tail_lds, block, nblocks);
     else
         full_gemv_device(f, n_fb, reinterpret_cast<uint4*>(arena), block, nblocks);
-    if (block == 0) DBG_T(25);
     if (!grid_barrier(a.counters, 2 * CSV_MAX_ROUNDS, nblocks, s_flag, a.spin_limit)) return;
-    if (block == 0) DBG_T(26);
     for (int item = block; item < n_fb * a.n_chunks; item += nblocks) {
         fb_topk_device(a, item / a.n_chunks, item % a.n_chunks, s);
         __syncthreads();
     }
-    if (block == 0) DBG_T(27);
     if (!grid_barrier(a.counters, 2 * CSV_MAX_ROUNDS + 1, nblocks, s_flag, a.spin_limit)) return;
-    if (block == 0) DBG_T(28);
     for (int slot = block; slot < n_fb; slot += nblocks) {
         fb_final_device(a, slot, s);
         __syncthreads();
     }
-    if (block == 0) DBG_T(29);
 }
 
 __global__ __launch_bounds__(TAIL_THREADS, 2) void tail_kernel(StepArgs a, FullArgs f, int fallback_only) {
@@ -2356,13 +2321,6 @@ __global__ __launch_bounds__(SEQ_THREADS) void fb_final_kernel(StepArgs a) {    
 }
 
 // ================================================================================================ host side
-#ifdef CSV_DEBUG_TIMING
-static unsigned long long* g_dbg = nullptr;
-extern "C" int csv_debug_read(unsigned long long* h_out, int n) {
-    if (!g_dbg) return -1;
-    return hipMemcpy(h_out, g_dbg, (size_t)n * 8, hipMemcpyDeviceToHost) == hipSuccess ? 0 : -3;
-}
-#endif
 static void profile_release(csv_workspace* ws);
 
 static int next_pow2(int x) {
@@ -2765,10 +2723,6 @@ extern "C" int csv_decode_step(csv_workspace* ws, const csv_index* idx, const ui
     else if (2.0 * (double)p->eps >= 1.0) a.lam2 = INFINITY;
     else a.lam2 = (float)log(2.0 * (double)p->eps / (1.0 - 2.0 * (double)p->eps));
     a.out = *o;
-#ifdef CSV_DEBUG_TIMING
-    if (!g_dbg) CSV_HIP(hipMalloc((void**)&g_dbg, CSV_MAX_BATCH * 64 * 8));
-    a.dbg = g_dbg;
-#endif
 
     hipEvent_t* ev = nullptr;
     if (ws->prof_on && ws->prof_n < ws->prof_cap) ev = ws->prof_ev + (size_t)ws->prof_n++ * (CSV_PROFILE_STAGES + 1);
