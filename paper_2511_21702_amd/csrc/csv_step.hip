@@ -1955,114 +1955,158 @@ __global__ __launch_bounds__(256) void full_gemv_kernel(FullArgs f) {
 }
 
 // MFMA path of the full-vocabulary product, used when more than FULL_G sequences share the pass over W' (then it
-// is a real dense contraction: [V x d] . [d x n]).  v_mfma_f32_16x16x32_bf16: a wave owns 16 rows of W' and 16*NT
-// sequences.  Lane (li = lane%16, g = lane/16) feeds row/sequence li and, for the jj-th MFMA of a 128-wide K block,
-// the eight k values at  block + 32 jj + 8 g.
-// The h operand is shared by every wave of the block, so it is staged once per K chunk in LDS, already in fragment
-// order (the 64 lanes of a fragment read 1 KB contiguously: no bank conflicts), instead of being fetched from L2 by
-// every wave for every row tile; a chunk is as many K blocks as fit (16*NT sequences x chunk x 2 bytes).  With
-// several chunks a wave revisits its own row tiles and adds to the logits it wrote in the previous chunk.
-// The W' operand goes straight from global memory to registers, MFMA_SBG K blocks (MFMA_SBG x 256 contiguous bytes
-// of each of the 16 rows) per batch of loads: long runs per row keep the DRAM pages open, which short 64-byte
-// pieces of many rows do not.
+// is a real dense contraction: [V x d] . [d x n]).  v_mfma_f32_16x16x32_bf16.  A block of eight waves owns
+// 128 TW consecutive rows of W' at a time, a wave 16 TW of them (TW row tiles) for 16 NT sequences, and keeps the
+// logits of its tiles in accumulator registers over the whole of K: every logit is written once.
+//   h  (shared by all waves) moves through LDS in chunks of one to four K blocks of 128, already in fragment order
+//      (the 64 lanes of a fragment read 1 KB contiguously: no bank conflicts), double-buffered: while a chunk is
+//      consumed the next one is fetched into registers and stored to the other buffer; one barrier per chunk, which
+//      waits for LDS traffic only, so the W' loads in flight cross it.  A fragment read from LDS serves TW MFMAs.
+//   W' goes straight from global memory to registers: lane (li = lane%16, g = lane/16) feeds row li of a tile and, for
+//      the jj-th MFMA of a K block, the eight k values at  128 block + 32 jj + 8 g.  A wave always has a chunk's worth
+//      of K blocks requested ahead (register buffer kb is refilled for the next chunk as soon as its MFMAs are
+//      issued): 8 to 32 KB per wave in flight at any time, in 256-byte runs per row.
 // h is fed as the first operand and W' as the second, so accumulator register r of lane (li, g) is
 // out[sequence 4g + r][row li]: stores are 64-byte runs per sequence instead of 4-byte pieces 4V bytes apart.
-#define MFMA_SBG 2      // K blocks per batch of W' loads (1, 2, 4, 8 swept)
-template <int NT>
-__device__ __forceinline__ void full_mfma_device(const FullArgs& f, int n, int seq0, uint4* lds, int lds_bytes, int block, int nblocks) {
-    const int tid = threadIdx.x, nt = blockDim.x, lane = tid & 63, wave = tid >> 6, nw = nt >> 6;
+#define MFMA_THREADS 512
+#define MFMA_LDS (64 * 1024)        // two buffers of K blocks x 4 fragments x 1 KB x groups of 16 sequences: 4x1, 4x2 or 2x4
+__device__ __forceinline__ uint4 keep_if(bool c, const uint4& v) {     // v or zero, component by component (no select between objects in memory)
+    return make_uint4(c ? v.x : 0u, c ? v.y : 0u, c ? v.z : 0u, c ? v.w : 0u);
+}
+__device__ __forceinline__ void lds_barrier() {      // all LDS accesses of the block's waves are done; global loads stay in flight
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+template <int NT, int TW, int MFMA_PIPE>
+__device__ __forceinline__ void full_mfma_device(const FullArgs& f, int n, int seq0, uint4* lds, int block, int nblocks) {
+    constexpr int NW = MFMA_THREADS / 64;
+    constexpr int CH = MFMA_PIPE * 4 * NT * 64;       // 16-byte pieces per LDS buffer
+    constexpr int SPT = CH / MFMA_THREADS;            // pieces a thread stages per chunk
+    static_assert(CH % MFMA_THREADS == 0 && NW % NT == 0 && 2 * CH * 16 <= MFMA_LDS, "staging layout");
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int li = lane & 15, g = lane >> 4;
     const int ntiles = (f.V + 15) >> 4;
-    const int nq = f.d >> 3;                         // 16-byte chunks per row
-    const int nsb = (f.d + 127) >> 7;                // K blocks of 128
-    int sb_chunk = lds_bytes / (NT * 16 * 256);      // K blocks whose h fragments fit: NT*16 sequences x 128 x 2 bytes each
-    if (sb_chunk > nsb) sb_chunk = nsb;
-    const uint4 zero = make_uint4(0, 0, 0, 0);
-    for (int sb0 = 0; sb0 < nsb; sb0 += sb_chunk) {
-        const int sbn = min(sb_chunk, nsb - sb0);
-        __syncthreads();
-        // stage h: piece (t, seq, q) -> fragment slot ((q/4)*NT + t)*64 + (q%4)*16 + seq, q counted from the chunk start
-        const int qn = sbn * 16;
-        for (int p = tid; p < NT * 16 * qn; p += nt) {
-            const int sl = p / qn, q = p - sl * qn;           // sl = t*16 + seq
-            const int sq = seq0 + sl, qa = sb0 * 16 + q;
-            uint4 v = zero;
-            if (sq < n && qa < nq) v = (reinterpret_cast<const uint4*>(f.h) + (size_t)f.list[sq] * nq)[qa];
-            lds[(((q >> 2) * NT + (sl >> 4)) << 6) + ((q & 3) << 4) + (sl & 15)] = v;
-        }
-        __syncthreads();
-        for (int tile = block * nw + wave; tile < ntiles; tile += nblocks * nw) {
-            const int r0 = tile << 4;
-            const uint4* ap = reinterpret_cast<const uint4*>(f.Wp + (size_t)min(r0 + li, f.V - 1) * f.d);
-            floatx4_t acc[NT];
+    const int nq = f.d >> 3;                          // 16-byte pieces per row
+    const int nsb = (f.d + 127) >> 7;                 // K blocks of 128
+    const int nchunk = (nsb + MFMA_PIPE - 1) / MFMA_PIPE;
+    const int ngroups = (ntiles + NW * TW - 1) / (NW * TW);
+    // Staging: piece p = tid + 512 s of a buffer is lane p % 64 = lane of fragment p / 64 = (4 kb + jj) NT + t.  NT divides
+    // the eight waves, so t, and with it the sequence 16 t + li, is the same for every piece a thread stages.
+    const int st_sq = seq0 + (wave % NT) * 16 + li;
+    const bool st_on = st_sq < n;
+    const uint4* st_h = reinterpret_cast<const uint4*>(f.h) + (size_t)f.list[st_on ? st_sq : seq0] * nq;
+    for (int grp = block; grp < ngroups; grp += nblocks) {
+        const int tile0 = (grp * NW + wave) * TW;
+        const uint4* ap[TW];
 #pragma unroll
-            for (int t = 0; t < NT; ++t) acc[t] = floatx4_t{0.f, 0.f, 0.f, 0.f};
-            for (int s0 = 0; s0 < sbn; s0 += MFMA_SBG) {
-                uint4 A[MFMA_SBG][4];
+        for (int tw = 0; tw < TW; ++tw) ap[tw] = reinterpret_cast<const uint4*>(f.Wp + (size_t)min((tile0 + tw) * 16 + li, f.V - 1) * f.d);
+        floatx4_t acc[TW][NT];
 #pragma unroll
-                for (int u = 0; u < MFMA_SBG; ++u)
+        for (int tw = 0; tw < TW; ++tw)
 #pragma unroll
-                    for (int jj = 0; jj < 4; ++jj) {
-                        const int q = (sb0 + s0 + u) * 16 + jj * 4 + g;     // chunk index of k = 128 sb + 32 jj + 8 g
-                        const uint4 v = ap[min(q, nq - 1)];
-                        A[u][jj] = (s0 + u < sbn && q < nq) ? v : zero;
+            for (int t = 0; t < NT; ++t) acc[tw][t] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+        uint4 A[MFMA_PIPE][TW][4];
+        uint4 sreg[SPT];
+        // Nothing is done to a loaded value before its MFMA or its LDS store: an instruction on it would be waited for
+        // where it stands, right behind the load.  Past the end of a row W' is read from a clamped address (the row's
+        // own last piece) and meets zeros staged for h there; the zeros are selected when the piece is stored.
+        auto load_A = [&](int kb, int sb) {           // K block sb of the wave's rows
+#pragma unroll
+            for (int tw = 0; tw < TW; ++tw)
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) A[kb][tw][jj] = ap[tw][min(sb * 16 + jj * 4 + g, nq - 1)];
+        };
+        auto stage_q = [&](int c, int s) {
+            const int kbjj = wave / NT + (NW / NT) * s;
+            return (c * MFMA_PIPE + (kbjj >> 2)) * 16 + (kbjj & 3) * 4 + g;
+        };
+        auto stage_load = [&](int c) {
+#pragma unroll
+            for (int s = 0; s < SPT; ++s) sreg[s] = st_h[min(stage_q(c, s), nq - 1)];
+        };
+        auto stage_store = [&](uint4* buf, int c) {
+#pragma unroll
+            for (int s = 0; s < SPT; ++s) buf[tid + MFMA_THREADS * s] = keep_if(st_on && stage_q(c, s) < nq, sreg[s]);
+        };
+        stage_load(0);
+#pragma unroll
+        for (int kb = 0; kb < MFMA_PIPE; ++kb) load_A(kb, kb);
+        stage_store(lds, 0);
+        lds_barrier();
+        // The last chunk is a copy of the loop body without the requests for a next one: with the requests under a
+        // condition the compiler could not count, at compile time, how many younger loads a wait may leave open.
+        auto chunk = [&](auto more_t, int c) {
+            constexpr bool more = decltype(more_t)::value;
+            const uint4* cur = lds + (c & 1) * CH;
+            if (more) stage_load(c + 1);
+            __builtin_amdgcn_sched_barrier(0);      // requests are issued where they are written: the scheduler would sink them
+#pragma unroll
+            for (int kb = 0; kb < MFMA_PIPE; ++kb) {
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj)
+#pragma unroll
+                    for (int t = 0; t < NT; ++t) {
+                        const uint4 Bv = cur[(((kb * 4 + jj) * NT + t) << 6) + lane];
+#pragma unroll
+                        for (int tw = 0; tw < TW; ++tw)
+                            acc[tw][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, Bv),
+                                                                                 __builtin_bit_cast(bf16x8_t, A[kb][tw][jj]), acc[tw][t], 0, 0, 0);
                     }
-#pragma unroll
-                for (int u = 0; u < MFMA_SBG; ++u) {
-                    const int sk = min(s0 + u, sbn - 1);    // past the chunk the A fragments are zero
-#pragma unroll
-                    for (int jj = 0; jj < 4; ++jj)
-#pragma unroll
-                        for (int t = 0; t < NT; ++t) {
-                            const uint4 Bv = lds[(((sk * 4 + jj) * NT + t) << 6) + lane];
-                            acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, Bv),
-                                                                             __builtin_bit_cast(bf16x8_t, A[u][jj]), acc[t], 0, 0, 0);
-                        }
-                }
+                __builtin_amdgcn_sched_barrier(0);
+                if (more) load_A(kb, (c + 1) * MFMA_PIPE + kb);
+                __builtin_amdgcn_sched_barrier(0);
             }
-            // h is the first MFMA operand: register r of lane (li, g) is out[sequence 4g + r][row li], so the 16 lanes
-            // of a group store 64 contiguous bytes of one sequence's logits
-            const int row = r0 + li;
+            if (more) stage_store(lds + ((c + 1) & 1) * CH, c + 1);
+            lds_barrier();          // the chunk just consumed may be overwritten, the next one is complete
+        };
+        for (int c = 0; c + 1 < nchunk; ++c) chunk(std::true_type{}, c);
+        chunk(std::false_type{}, nchunk - 1);
+#pragma unroll
+        for (int tw = 0; tw < TW; ++tw) {
+            const int row = (tile0 + tw) * 16 + li;
             if (row < f.V) {
-                const float bias = sb0 == 0 ? f.bp[row] : 0.f;
+                const float bias = f.bp[row];
                 const size_t col = f.scatter ? (size_t)f.perm[row] : (size_t)row;
 #pragma unroll
                 for (int t = 0; t < NT; ++t)
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
                         const int sq = seq0 + t * 16 + 4 * g + r;
-                        if (sq < n) {
-                            float* o = f.out + (size_t)sq * f.out_stride + col;
-                            *o = (sb0 == 0 ? 0.f : *o) + acc[t][r] + bias;
-                        }
+                        if (sq < n) f.out[(size_t)sq * f.out_stride + col] = acc[tw][t][r] + bias;
                     }
             }
         }
     }
 }
 
-// All n sequences through the MFMA path: up to 64 per pass over W'.
-__device__ __forceinline__ void full_mfma_all(const FullArgs& f, int n, uint4* lds, int lds_bytes, int block, int nblocks) {
-    if (n <= 16) {
-        full_mfma_device<1>(f, n, 0, lds, lds_bytes, block, nblocks);
-    } else if (n <= 32) {
-        full_mfma_device<2>(f, n, 0, lds, lds_bytes, block, nblocks);
-    } else {
-        // 64 per pass over W': twice the logits are revisited per K chunk, but W' (the large operand) is read once
-        for (int s0 = 0; s0 < n; s0 += 64) {
-            if (n - s0 <= 32) full_mfma_device<2>(f, n, s0, lds, lds_bytes, block, nblocks);
-            else full_mfma_device<4>(f, n, s0, lds, lds_bytes, block, nblocks);
-        }
+// All n sequences through the MFMA path: up to 64 per pass over W'.  Four K blocks are requested ahead (two with 64
+// sequences, whose accumulators need the registers).  The groups of 128 TW rows are dealt to the blocks in rounds:
+// two row tiles per wave (a fragment of h read from LDS then serves two MFMAs) unless one tile per wave saves a
+// round's worth of idle blocks.  Four tiles per wave with half the K blocks ahead measured 4-7 % slower at d = 8192.
+template <int TW>
+__device__ __forceinline__ void full_mfma_pass(const FullArgs& f, int n, uint4* lds, int block, int nblocks) {
+    for (int s0 = 0; s0 < n; s0 += 64) {
+        const int m = n - s0;
+        if (m <= 16) full_mfma_device<1, TW, 4>(f, n, s0, lds, block, nblocks);
+        else if (m <= 32) full_mfma_device<2, TW, 4>(f, n, s0, lds, block, nblocks);
+        else full_mfma_device<4, TW, 2>(f, n, s0, lds, block, nblocks);
     }
 }
+__device__ __forceinline__ void full_mfma_all(const FullArgs& f, int n, uint4* lds, int block, int nblocks) {
+    const int ntiles = (f.V + 15) >> 4, NW = MFMA_THREADS / 64;
+    auto cost = [&](int tw) {           // rounds of groups x time of a group
+        const int groups = (ntiles + NW * tw - 1) / (NW * tw);
+        return (groups + nblocks - 1) / nblocks * tw;
+    };
+    if (cost(2) <= cost(1)) full_mfma_pass<2>(f, n, lds, block, nblocks);
+    else full_mfma_pass<1>(f, n, lds, block, nblocks);
+}
 
-#define MFMA_THREADS 512
-#define MFMA_LDS (128 * 1024)
-__global__ __launch_bounds__(MFMA_THREADS, 2) void full_mfma_kernel(FullArgs f) {
+__global__ __launch_bounds__(MFMA_THREADS) void full_mfma_kernel(FullArgs f) {
     extern __shared__ uint4 mfma_lds[];
     const int n = f.n_ptr ? *f.n_ptr : f.n_fixed;
     if (n <= 0) return;
-    full_mfma_all(f, n, mfma_lds, MFMA_LDS, blockIdx.x, gridDim.x);
+    full_mfma_all(f, n, mfma_lds, blockIdx.x, gridDim.x);
 }
 
 // First stage of top-k / log-sum-exp over V: one block per (chunk of rows, fallback slot).  The chunk's logits
@@ -2207,8 +2251,9 @@ __device__ __forceinline__ void tail_device(const StepArgs& a, const FullArgs& f
     }
     const int n_fb = __hip_atomic_load(&a.counters[CNT_FALLBACK], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
     if (n_fb == 0) return;
+    // the same rule as the separate launches, so that a sequence's logits do not depend on how the step was launched
     if (n_fb > FULL_G)
-        full_mfma_all(f, n_fb, reinterpret_cast<uint4*>(arena), a.tail_lds, block, nblocks);
+        full_mfma_all(f, n_fb, reinterpret_cast<uint4*>(arena), block, nblocks);
     else
         full_gemv_device(f, n_fb, reinterpret_cast<uint4*>(arena), block, nblocks);
     if (!grid_barrier(a.counters, 2 * CSV_MAX_ROUNDS, nblocks, s_flag, a.spin_limit)) return;
@@ -2223,7 +2268,7 @@ __device__ __forceinline__ void tail_device(const StepArgs& a, const FullArgs& f
     }
 }
 
-__global__ __launch_bounds__(TAIL_THREADS, 2) void tail_kernel(StepArgs a, FullArgs f, int fallback_only) {
+__global__ __launch_bounds__(TAIL_THREADS) void tail_kernel(StepArgs a, FullArgs f, int fallback_only) {
     __shared__ SeqShared s;
     __shared__ GemvShared gs;
     __shared__ int s_flag;
@@ -2298,14 +2343,20 @@ __global__ __launch_bounds__(SEQ_THREADS) void round_cert_kernel(StepArgs a, int
     cert_device(a, blockIdx.x, blockIdx.y, r, s);
 }
 
-__global__ __launch_bounds__(TAIL_THREADS, 2) void fb_product_kernel(StepArgs a, FullArgs f, int lds_bytes) {
+// Up to FULL_G fallback sequences take the vector product, more the MFMA product, which needs a compute unit's whole
+// register file: two kernels, of which one returns at once.
+__global__ __launch_bounds__(TAIL_THREADS, 2) void fb_product_kernel(StepArgs a, FullArgs f) {
     extern __shared__ u64 arena[];
     const int n_fb = a.counters[CNT_FALLBACK];
-    if (n_fb == 0) return;
-    if (n_fb > FULL_G)
-        full_mfma_all(f, n_fb, reinterpret_cast<uint4*>(arena), lds_bytes, blockIdx.x, gridDim.x);
-    else
-        full_gemv_device(f, n_fb, reinterpret_cast<uint4*>(arena), blockIdx.x, gridDim.x);
+    if (n_fb == 0 || n_fb > FULL_G) return;
+    full_gemv_device(f, n_fb, reinterpret_cast<uint4*>(arena), blockIdx.x, gridDim.x);
+}
+
+__global__ __launch_bounds__(MFMA_THREADS) void fb_product_mfma_kernel(StepArgs a, FullArgs f) {
+    extern __shared__ uint4 mfma_lds[];
+    const int n_fb = a.counters[CNT_FALLBACK];
+    if (n_fb <= FULL_G) return;
+    full_mfma_all(f, n_fb, mfma_lds, blockIdx.x, gridDim.x);
 }
 
 __global__ __launch_bounds__(SEQ_THREADS) void fb_topk_kernel(StepArgs a) {             // grid (chunks of V, B)
@@ -2370,7 +2421,7 @@ static int check_pair(const csv_workspace* ws, const csv_index* idx, const void*
 
 // The dynamic-LDS limit of a kernel is one attribute per process and device, shared by every workspace: it is only
 // ever raised, so a workspace created later with smaller needs cannot take away what an earlier one's launches rely on.
-enum { K_ROUND0, K_STEP, K_TAIL, K_RCERT, K_FBPROD, K_FULLMFMA, K_BOUND0, K_NKERN = K_BOUND0 + 8 };
+enum { K_ROUND0, K_STEP, K_TAIL, K_RCERT, K_FBPROD, K_FBPRODM, K_FULLMFMA, K_BOUND0, K_NKERN = K_BOUND0 + 8 };
 static size_t g_lds_limit[CSV_STATIC_MAX_DEVICES][K_NKERN];
 static pthread_mutex_t g_attr_lock = PTHREAD_MUTEX_INITIALIZER;
 #define CSV_STATIC_LDS_MAX 16384     // at least the static shared memory of any kernel here
@@ -2559,9 +2610,8 @@ extern "C" int csv_workspace_create(const csv_index* idx, int B_max, int K_cap_r
     if (e == hipSuccess) e = raise_lds(ws->device, K_ROUND0, (const void*)round0_kernel, round0_lds(ws));
     if (e == hipSuccess) {
         size_t l = cert_lds(ws);
-        // more than FULL_G fallback sequences go through the MFMA product, whose h fragments want a large LDS chunk
         const size_t cand[] = {(size_t)FULL_G * idx->d * 2 /* also covers the two h slots of the tile loop */, (size_t)FB_CHUNK * 4, (size_t)STAGE_CAP * 8,
-                               B_max > FULL_G ? (size_t)MFMA_LDS : 0};
+                               B_max > FULL_G ? (size_t)MFMA_LDS : 0 /* more than FULL_G fallback sequences: the MFMA product's h fragments */};
         for (size_t c : cand) l = c > l ? c : l;
         ws->tail_lds = l;
         e = raise_lds(ws->device, K_TAIL, (const void*)tail_kernel, l);
@@ -2581,7 +2631,8 @@ extern "C" int csv_workspace_create(const csv_index* idx, int B_max, int K_cap_r
         ws->spin_limit = TAIL_SPIN_LIMIT;
         ws->split_min_B = 0;      // decided per step from the history
         if (e == hipSuccess) e = raise_lds(ws->device, K_RCERT, (const void*)round_cert_kernel, cert_lds(ws));
-        if (e == hipSuccess) e = raise_lds(ws->device, K_FBPROD, (const void*)fb_product_kernel, MFMA_LDS);
+        if (e == hipSuccess) e = raise_lds(ws->device, K_FBPROD, (const void*)fb_product_kernel, (size_t)FULL_G * idx->d * 2);
+        if (e == hipSuccess) e = raise_lds(ws->device, K_FBPRODM, (const void*)fb_product_mfma_kernel, MFMA_LDS);
         int r0_per_cu = 0;
         if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&r0_per_cu, round0_kernel, SEQ_THREADS, round0_lds(ws));
         if (e == hipSuccess && r0_per_cu < 1) {
@@ -2786,9 +2837,12 @@ extern "C" int csv_decode_step(csv_workspace* ws, const csv_index* idx, const ui
                 CSV_LAUNCH_CHECK("round_cert_kernel");
             }
             if (fb_launches) {
-                const size_t pl = B > FULL_G ? (size_t)MFMA_LDS : (size_t)FULL_G * idx->d * 2;
-                fb_product_kernel<<<ws->tail_grid, TAIL_THREADS, pl, st>>>(a, f, (int)pl);
+                fb_product_kernel<<<ws->tail_grid, TAIL_THREADS, (size_t)FULL_G * idx->d * 2, st>>>(a, f);
                 CSV_LAUNCH_CHECK("fb_product_kernel");
+                if (B > FULL_G) {
+                    fb_product_mfma_kernel<<<ws->tail_grid, MFMA_THREADS, MFMA_LDS, st>>>(a, f);
+                    CSV_LAUNCH_CHECK("fb_product_mfma_kernel");
+                }
                 fb_topk_kernel<<<dim3(ws->n_chunks, B), SEQ_THREADS, (size_t)FB_CHUNK * 4, st>>>(a);
                 CSV_LAUNCH_CHECK("fb_topk_kernel");
                 fb_final_kernel<<<B, SEQ_THREADS, (size_t)STAGE_CAP * 8, st>>>(a);
