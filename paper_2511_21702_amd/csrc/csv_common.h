@@ -64,7 +64,8 @@ struct SeqState {
     float nxtU;               // largest bound among unopened clusters (-inf if none)
     float T;                  // log tail mass  log sum_{unopened} n_c exp(U_c)
     int fb_slot;              // row of the fallback logits buffer
-    int pad[3];
+    float theta;              // k-th largest logit scored so far (-inf: unknown): a later round's top-k starts from it
+    int pad[2];
 };
 
 // Work item of the gathered GEMV: nrows (<= 8) consecutive rows of W' from row0, results to positions pos.. of sequence b.

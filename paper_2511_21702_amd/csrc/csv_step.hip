@@ -533,6 +533,8 @@ __device__ __forceinline__ LseAcc block_excl_suffix_lse(LseAcc v, LseAcc* wtot) 
 struct BigItem {
     int row0, n, pos, tbase;
 };
+#define CAND_CAP SEQ_THREADS
+#define RANK_DIRECT 256      // up to this many values are ranked against each other directly (a multiple of four, at most SEQ_THREADS)
 struct SeqShared {
     unsigned hist[256];
     float redf[16];
@@ -547,6 +549,10 @@ struct SeqShared {
     float wval[CSV_MAX_K];
     int wid[CSV_MAX_K];
 };
+// Later rounds collect the values at or above the previous round's k-th logit, and their ids, behind the staged
+// logits in the dynamic LDS (a region the cluster data of a large index covers anyway).
+#define CAND_OFF (STAGE_CAP * 8)
+#define CAND_BYTES ((CAND_CAP + 4) * 4 + CAND_CAP * 4)
 
 // ================================================================================================ helpers shared by seed/cert
 __device__ __forceinline__ void write_invalid(const StepArgs& a, int b) {
@@ -1223,6 +1229,54 @@ __device__ __forceinline__ u64 softmax_prefix_key(const StepArgs& a, const Clust
     return skeys[max(best, 1) - 1];
 }
 
+// Ordered top-kk (value descending, id ascending) of len <= blockDim.x values V in LDS with ids I; V is followed by
+// -inf up to the next multiple of four.  One pass, one barrier: thread (e, slice) compares value e with one slice of
+// the others (larger ones, equal ones) and notes the slice's maximum; after the barrier thread e adds the slices'
+// counts to its rank (ids are looked at only among equal values) and writes itself to its place in s.wval / s.wid.
+// Returns the largest value; v is the value of element threadIdx.x (threadIdx.x < len).  The caller's next barrier
+// publishes the list.  blockDim.x is a power of two.
+__device__ __forceinline__ float rank_small(const float* V, const int* I, int len, int kk, SeqShared& s, float& v) {
+    const int tid = threadIdx.x, nt = blockDim.x;
+    int lg = 5;
+    while ((1 << lg) < len) ++lg;
+    const int npad = 1 << lg, slices = nt >> lg;           // slices <= 16
+    const int e = tid & (npad - 1), sl = tid >> lg;
+    const int len4 = (len + 3) >> 2;                         // slices of whole float4's
+    const int seg4 = (len4 + slices - 1) / slices;
+    const int q0 = min(len4, sl * seg4), q1 = min(len4, q0 + seg4);
+    const float ve = V[min(e, max(len, 1) - 1)];
+    int gt = 0, eq = 0;
+    float mx = -INFINITY;
+    const float4* v4 = reinterpret_cast<const float4*>(V);
+#pragma unroll 8
+    for (int q = q0; q < q1; ++q) {
+        const float4 x = v4[q];
+        gt += (x.x > ve) + (x.y > ve) + (x.z > ve) + (x.w > ve);
+        eq += (x.x == ve) + (x.y == ve) + (x.z == ve) + (x.w == ve);
+        mx = fmaxf(fmaxf(mx, fmaxf(x.x, x.y)), fmaxf(x.z, x.w));
+    }
+    s.rank[tid] = gt | (eq << 16);                          // rank[sl * npad + e]
+    if (e == 0) s.redf[sl] = mx;
+    __syncthreads();
+    float vmax = s.redf[0];
+    for (int q = 1; q < slices; ++q) vmax = fmaxf(vmax, s.redf[q]);
+    v = ve;                                                 // tid < len <= npad: e is tid
+    if (tid < len) {
+        int packed = 0;
+        for (int q = 0; q < slices; ++q) packed += s.rank[q * npad + tid];
+        int rank = packed & 0xffff;
+        const int id = I[tid];
+        if ((packed >> 16) > 1)
+            for (int i = 0; i < len; ++i)
+                if (V[i] == v && I[i] < id) rank += 1;
+        if (rank < kk) {
+            s.wval[rank] = v;
+            s.wid[rank] = id;
+        }
+    }
+    return vmax;
+}
+
 // ================================================================================================ certified distribution
 // Optional outputs (Section III, top-p certification): over the returned list, in its order, the sub-vocabulary
 // probabilities p~_t = exp(l_t - Z_S), their running sums, and the length of the shortest prefix whose running sum
@@ -1279,51 +1333,13 @@ __device__ __forceinline__ bool cert_body(const StepArgs& a, int b, int chunk, i
     auto idf = [](int i) { return reinterpret_cast<const int*>(arena)[STAGE_CAP + i]; };
     // with a top-k the largest logit is already known when the sum is taken: one block reduction instead of two
     LseAcc l;
-    if (a.use_k && len <= nt) {
-        // Up to one value per thread: ordered top-k and log-sum-exp in one pass with two barriers.  Thread (e, slice)
-        // compares value e with one slice of the others (larger ones, equal ones) and notes the slice's maximum;
-        // after the barrier thread e adds the slices' counts to its rank (ids are looked at only among equal
-        // values), writes itself to its place in the list and contributes exp(v - max) to the sum.
-        int lg = 5;
-        while ((1 << lg) < len) ++lg;
-        const int npad = 1 << lg, slices = nt >> lg;           // slices <= 16
-        const int e = tid & (npad - 1), sl = tid >> lg;
-        // slices of whole float4's; the staged values are followed by -inf up to the next multiple of four
-        const int len4 = (len + 3) >> 2;
-        const int seg4 = (len4 + slices - 1) / slices;
-        const int q0 = min(len4, sl * seg4), q1 = min(len4, q0 + seg4);
-        const float v = val(min(e, len - 1));
-        int gt = 0, eq = 0;
-        float mx = -INFINITY;
-        const float4* v4 = reinterpret_cast<const float4*>(arena);
-#pragma unroll 8
-        for (int q = q0; q < q1; ++q) {
-            const float4 x = v4[q];
-            gt += (x.x > v) + (x.y > v) + (x.z > v) + (x.w > v);
-            eq += (x.x == v) + (x.y == v) + (x.z == v) + (x.w == v);
-            mx = fmaxf(fmaxf(mx, fmaxf(x.x, x.y)), fmaxf(x.z, x.w));
-        }
-        s.rank[tid] = gt | (eq << 16);                          // rank[sl * npad + e]
-        if (e == 0) s.redf[sl] = mx;
-        __syncthreads();
-        float vmax = s.redf[0];
-        for (int q = 1; q < slices; ++q) vmax = fmaxf(vmax, s.redf[q]);
-        float pe = 0.f;
-        const int kk = min(a.k, len);
-        if (tid < len) {
-            int packed = 0;
-            for (int q = 0; q < slices; ++q) packed += s.rank[q * npad + tid];
-            int rank = packed & 0xffff;
-            const int id = idf(tid);
-            if ((packed >> 16) > 1)
-                for (int i = 0; i < len; ++i)
-                    if (val(i) == v && idf(i) < id) rank += 1;
-            if (rank < kk) {
-                s.wval[rank] = v;
-                s.wid[rank] = id;
-            }
-            pe = vmax > -INFINITY ? expf(v - vmax) : 0.f;
-        }
+    int kkv = min(a.k, len);                 // entries of the ordered list this chunk contributes
+    bool have_topk = false;
+    if (a.use_k && len <= RANK_DIRECT) {
+        // few values: ordered top-k and log-sum-exp in one pass with two barriers
+        float v;
+        const float vmax = rank_small(reinterpret_cast<const float*>(arena), reinterpret_cast<const int*>(arena) + STAGE_CAP, len, kkv, s, v);
+        float pe = (tid < len && vmax > -INFINITY) ? expf(v - vmax) : 0.f;
         pe = wave_sum(pe);
         float* wsum = reinterpret_cast<float*>(s.hist);
         if ((tid & 63) == 0) wsum[tid >> 6] = pe;
@@ -1332,6 +1348,73 @@ __device__ __forceinline__ bool cert_body(const StepArgs& a, int b, int chunk, i
         for (int q = 0; q < (nt >> 6); ++q) tot += wsum[q];
         l.m = vmax;
         l.s = tot;
+        have_topk = true;
+    } else if (a.use_k) {
+        // More values (ranking all of them against each other costs len^2 comparisons: 10 us at 512).  Everything
+        // below a threshold that k of the values are known to reach is out; the values at or above it (usually few
+        // more than k) are collected and ranked in one pass, and the log-sum-exp runs over all values.  First
+        // threshold: the previous round's k-th logit (its rows are among these).  Failing that, or when too many
+        // values reach it: the k-th largest of the first RANK_DIRECT values (the clusters come in bound order, so
+        // they hold most of the top).  The collected order depends on timing, the ranking does not.
+        const int lane = tid & 63;
+        const int k0 = kkv;
+        auto try_threshold = [&](float th) -> bool {
+            float* wmax = reinterpret_cast<float*>(s.hist);
+            float* cval = reinterpret_cast<float*>(reinterpret_cast<char*>(arena) + CAND_OFF);
+            int* cid = reinterpret_cast<int*>(cval + CAND_CAP + 4);
+            if (tid < CAND_CAP) cval[tid] = -INFINITY;
+            if (tid < 4) cval[CAND_CAP + tid] = -INFINITY;
+            if (tid == 0) s.cnt = 0;
+            __syncthreads();
+            float mx = -INFINITY;
+            for (int i0 = 0; i0 < len; i0 += nt) {
+                const int i = i0 + tid;
+                const float v = i < len ? val(i) : -INFINITY;
+                mx = fmaxf(mx, v);
+                const bool in = i < len && v >= th;
+                const unsigned long long bal = __ballot(in);
+                if (bal) {
+                    const int lead = __ffsll((long long)bal) - 1;
+                    unsigned base = 0;
+                    if (lane == lead) base = atomicAdd(&s.cnt, (unsigned)__popcll(bal));
+                    base = __shfl(base, lead, CSV_WAVE);
+                    const unsigned slot = base + (unsigned)__popcll(bal & ((1ull << lane) - 1ull));
+                    if (in && slot < CAND_CAP) {
+                        cval[slot] = v;
+                        cid[slot] = idf(i);
+                    }
+                }
+            }
+            mx = wave_max(mx);
+            if (lane == 0) wmax[tid >> 6] = mx;
+            __syncthreads();
+            const int m = (int)s.cnt;
+            if (m > CAND_CAP || (nchunks == 1 && m < k0)) return false;
+            float vmax = wmax[0];
+            for (int q = 1; q < (nt >> 6); ++q) vmax = fmaxf(vmax, wmax[q]);
+            kkv = min(a.k, m);
+            float v;
+            rank_small(cval, cid, m, kkv, s, v);
+            float sm = 0.f;
+            if (vmax > -INFINITY)
+                for (int i = tid; i < len; i += nt) sm += expf(val(i) - vmax);
+            l.m = vmax;
+            l.s = block_sum(sm, s.redf);
+            return true;
+        };
+        if (st.theta > -INFINITY) have_topk = try_threshold(st.theta);
+        if (!have_topk && a.k <= RANK_DIRECT) {
+            float v;
+            __syncthreads();
+            rank_small(reinterpret_cast<const float*>(arena), reinterpret_cast<const int*>(arena) + STAGE_CAP, RANK_DIRECT, a.k, s, v);
+            __syncthreads();
+            const float th = fmaxf(s.wval[a.k - 1], st.theta);
+            __syncthreads();
+            have_topk = try_threshold(th);
+        }
+    }
+    if (have_topk) {
+        // list and log-sum-exp are set
     } else if (a.use_k) {
         block_topk(len, a.k, val, idf, s);
         l.m = s.wval[0];
@@ -1344,7 +1427,7 @@ __device__ __forceinline__ bool cert_body(const StepArgs& a, int b, int chunk, i
     }
     if (nchunks > 1) {
         const size_t pb = (size_t)b * a.cand_chunks, pc = pb + chunk;
-        const int kk = min(a.k, len);
+        const int kk = kkv;
         for (int t = tid; t < a.k; t += nt) {
             a.cand_val[pc * a.k + t] = t < kk ? s.wval[t] : -INFINITY;
             a.cand_id[pc * a.k + t] = t < kk ? s.wid[t] : 0x7fffffff;
@@ -1482,6 +1565,7 @@ __device__ __forceinline__ bool cert_body(const StepArgs& a, int b, int chunk, i
             if (tid == 0) {
                 SeqState o = st;
                 o.n_open = st.n_open + cnt; o.n_rows = n + rows; o.rounds = round + 1; o.kappa = kappa1; o.nxtU = nxtU; o.T = T1;
+                o.theta = (a.use_k && n >= a.k) ? theta : -INFINITY;
                 a.st[b] = o;
             }
             return false;
@@ -1533,7 +1617,7 @@ __device__ __forceinline__ float seed_tail_mass(const StepArgs& a, const Cluster
 __device__ __forceinline__ SeqState seed_state(int m0, int rows, u64 kappa, float nxtU, float T0) {
     SeqState st;
     st.status = ST_ACTIVE; st.n_open = m0; st.n_rows = rows; st.rounds = 0; st.kappa = kappa; st.nxtU = nxtU; st.T = T0;
-    st.fb_slot = -1; st.pad[0] = st.pad[1] = st.pad[2] = 0;
+    st.fb_slot = -1; st.theta = -INFINITY; st.pad[0] = st.pad[1] = 0;
     return st;
 }
 
@@ -2387,7 +2471,7 @@ static size_t seed_lds(const csv_workspace* ws) {
     return general > staged ? general : staged;
 }
 static size_t cert_lds(const csv_workspace* ws) {
-    const size_t plan = seed_lds(ws), stage = (size_t)STAGE_CAP * 8;
+    const size_t plan = seed_lds(ws), stage = (size_t)CAND_OFF + CAND_BYTES;      // staged logits and ids, then the candidates of a later round
     return plan > stage ? plan : stage;
 }
 static size_t round0_h_off(const csv_workspace* ws) { return (seed_lds(ws) + 15) / 16 * 16; }
