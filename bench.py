@@ -275,7 +275,7 @@ def main() -> int:
         tot = float(np.median([a.elapsed_time(b) for a, b in evs])) - base
         return tot * 1e3
 
-    bound_name = "bound1_kernel" if r.B == 1 else ("bound_kernel" if r.B <= 8 else "bound_mfma_kernel + bound_finish_kernel")
+    bound_name = "bound1_kernel" if r.B == 1 else ("bound_kernel" if r.B <= 4 else "bound_mfma_kernel + bound_finish_kernel")
     bound_warm_us = time_bounds(200)
     flush_buf = torch.empty(768 << 20, dtype=torch.uint8, device="cuda").zero_()
     bound_cold_us = time_bounds(30, flush_buf)

@@ -218,8 +218,8 @@ int csv_bounds(csv_workspace* ws, const csv_index* idx, const uint16_t* d_h, int
  * csv_bounds for callers that cannot allocate device memory and hold no workspace: code under HIP graph capture,
  * tight serving loops, harnesses that forbid hipMalloc.  Same results as csv_bounds, bit for bit.  Calls no
  * hipMalloc / hipFree and nothing that allocates.  The only scratch the bound kernels use (partial sums of the batched
- * product, more than 8 sequences) lives in an 8 MiB device array inside the library, one copy per GPU, held until the
- * process ends: for more than 8 sequences B * C may be at most about 2^21 / KS, KS <= 32 being the number of K slices
+ * product, more than 4 sequences) lives in an 8 MiB device array inside the library, one copy per GPU, held until the
+ * process ends: for more than 4 sequences B * C may be at most about 2^21 / KS, KS <= 32 being the number of K slices
  * chosen for the shape (e.g. B = 32 at C = 4096, B = 256 at C = 1024); larger requests fail with CSV_ESHAPE and a message,
  * nothing is launched.  The device of the index must be current.  Every call on a GPU shares that GPU's array: calls
  * that overlap on one GPU (different streams, different threads) race on it; stream-ordered calls are safe.  Nothing

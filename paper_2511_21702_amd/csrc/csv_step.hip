@@ -1,7 +1,7 @@
 // Per-step kernels of the certified sub-vocabulary LM-head path and the entry points that enqueue them.
 //
 //   bound1_kernel / bound_kernel / bound_mfma_kernel + bound_finish_kernel
-//                      U[b,c] = <mu_c,h_b> + R_c ||h_b|| + bmax_c  for 1, 2..8 and more sequences   (Eq. "cluster_bound")
+//                      U[b,c] = <mu_c,h_b> + R_c ||h_b|| + bmax_c  for 1, 2..4 and more sequences   (Eq. "cluster_bound")
 //   round0_kernel      per sequence: shortest prefix of the bound order holding >= max(k,1) rows, next bound, log tail
 //                      mass (Algorithm 1: queue, PopMax); logits of the prefix rows of W' (Algorithm 1: sparse GEMV);
 //                      top-k, log-sum-exp and both certificates, or the plan of the next round
@@ -182,7 +182,7 @@ __device__ __forceinline__ float mu_fma(const uint4& m, HP hrow, int unit, float
 #define BOUND_THREADS 512
 #define BOUND_LDS_MAX (128 * 1024)   // h of up to 8 sequences of d = 8192 in LDS: one block serves all 8, the centroids are read once
 #define BOUND_HREG 8       // 128-bit pieces of h per thread: 8 x 512 x 16 B covers the 64 KB that BT sequences may take in LDS
-// 2..8 sequences: h of the block's BT sequences is staged in LDS once, then every wave walks over whole clusters
+// 2..4 sequences (up to 8 supported): h of the block's BT sequences is staged in LDS once, then every wave walks over whole clusters
 // (cluster = wave index among all waves of the grid, then + their number, ...): a centroid row goes through the wave
 // in chunks of BOUND_PFB 128-bit loads per lane, the next chunk (of this or of the wave's next cluster) always
 // requested before the current one is used, and nothing in the loop waits for another wave.  With more clusters
@@ -357,7 +357,7 @@ __global__ __launch_bounds__(BOUND_THREADS) void bound1_kernel(StepArgs a, float
     }
 }
 
-// Bounds for larger batches (B > 8): [C x d] fp32 centroids times [d x B] bf16 hidden states is a dense contraction,
+// Bounds for larger batches (B >= BOUND_MFMA_MIN_B): [C x d] fp32 centroids times [d x B] bf16 hidden states is a dense contraction,
 // done with v_mfma_f32_16x16x32_bf16.  A float32 centroid value is split exactly into three bf16 pieces
 // (x = hi + mid + lo, 8 mantissa bits each), so three MFMAs per k-block give the float32-exact products with float32
 // accumulation; the split costs a handful of vector instructions per value, independent of B.
@@ -384,9 +384,11 @@ __device__ __forceinline__ void split3_bf16(const float4& x0, const float4& x1, 
 }
 
 #define BOUND_KS_PER_BLOCK 8
+#define BOUND_MFMA_MIN_B 5       // from this many sequences on the MFMA product is faster than the vector kernel, whose reads of h
+                                 // from LDS (eight sequences: 128 bytes per lane for 16 bytes of a centroid) bound it: 15 vs 23 us at B = 8
 #define BOUND_WAVE_TARGET 4096   // (cluster tiles x K slices) aimed at; 2048..8192 measured within 5 %
 #define BOUND_KS_MAX 32
-#define BOUND_KB_UNROLL 4      // k-blocks (of 32) whose loads are issued together
+#define BOUND_KB_UNROLL 4        // k-blocks (of 32) whose loads are issued together (2, 4, 8 measured within 5 %)
 template <int NT, bool MU16>
 __global__ __launch_bounds__(512) void bound_mfma_kernel(StepArgs a, float* __restrict__ P, int seq0, int KS, int kb_per_slice,
                                                          int reset_counters) {
@@ -1175,58 +1177,85 @@ __device__ __forceinline__ LseAcc block_lse(int n, ValFn val, SeqShared& s) {
     return r;
 }
 
-// ================================================================================================ sorted prefix search
-// s = min{m >= m0 : log tail mass with the first m clusters of the bound order open  -  Z0 <= lam}; returns the key
-// of the s-th cluster of the order (the threshold of that prefix).  Sorts the keys in LDS with a bitonic network;
-// only needed when the softmax test fails after round 0.  Destroys the by-cluster order of L.keys (L.vl stays valid).
-__device__ __forceinline__ u64 softmax_prefix_key(const StepArgs& a, const ClusterLds& L, int m0, float Z0, SeqShared& s) {
-    const int tid = threadIdx.x, nt = blockDim.x, N = a.Npad;
-    u64* skeys = L.keys;
-    for (int i = a.C + tid; i < N; i += nt) skeys[i] = 0ull;
-    __syncthreads();
-    for (int k2 = 2; k2 <= N; k2 <<= 1) {
-        for (int j = k2 >> 1; j > 0; j >>= 1) {
-            // pair p of the stage: i = the index with bit j clear, partner i + j (every thread does useful work)
-            for (int p = tid; p < (N >> 1); p += nt) {
-                const int i = ((p & ~(j - 1)) << 1) | (p & (j - 1)), ixj = i | j;
-                const u64 x = skeys[i], y = skeys[ixj];
-                const bool first_larger = (i & k2) == 0;
-                if (first_larger ? (x < y) : (x > y)) {
-                    skeys[i] = y;
-                    skeys[ixj] = x;
-                }
+// ================================================================================================ prefix search
+// The shortest prefix of the bound order, no shorter than the open one, whose log tail mass is within lam of Z0
+// (Theorem 2): returns the key of its last cluster.  In terms of keys: the largest key kappa <= kappa0 such that the
+// clusters below it weigh  sum_{key_c < kappa} n_c exp(U_c)  <=  exp(Z0 + lam).  No sort: the key is found digit by
+// digit from the top (eight bits a pass).  Among the keys that share the digits fixed so far, the clusters of a
+// smaller digit all lie below those of a larger one, so a digit can hold the answer when it is not empty and the
+// weight below its smallest key (everything below the fixed digits, plus the smaller digits) is within the limit;
+// the largest such digit is taken.  Weights are summed as 64-bit fixed point relative to the limit (2^-40 steps, each
+// term capped at 2^9, which already exceeds the limit of 1): integer sums do not depend on the order of the atomic
+// additions, so the result is the same in every run.  Leaves the cluster data in LDS as it is.  Uses s.rank and s.hist.
+__device__ __forceinline__ u64 softmax_prefix_key(const StepArgs& a, const ClusterLds& L, u64 kappa0, float Z0, SeqShared& s) {
+    const int tid = threadIdx.x, nt = blockDim.x, lane = tid & 63;
+    u64* H = reinterpret_cast<u64*>(s.rank);               // 256 weights
+    unsigned* cnt = s.hist;                                // 256 counts
+    const float shift = Z0 + a.lam;
+    const u64 LIMIT = 1ull << 40;
+    u64 prefix = 0, base = 0;
+    for (int sb = 56; sb >= 0; sb -= 8) {
+        if (sb == 24 || sb == 16) {                        // bits 16..31 of ~c: ones for every cluster id below 65536
+            prefix |= 0xffull << sb;
+            continue;
+        }
+        if (tid < 256) {
+            H[tid] = 0ull;
+            cnt[tid] = 0u;
+        }
+        __syncthreads();
+        for (int c = tid; c < a.C; c += nt) {
+            const u64 kx = L.keys[c];
+            const bool match = sb == 56 || ((kx ^ prefix) >> (sb + 8)) == 0;
+            if (kx != 0 && kx <= kappa0 && match) {
+                const float e = expf(fminf(L.vl[c] - shift, 6.f));         // e^6 < 2^9
+                const unsigned dg = (unsigned)(kx >> sb) & 255u;
+                atomicAdd(reinterpret_cast<unsigned long long*>(&H[dg]), (unsigned long long)(e * 1099511627776.f));
+                atomicAdd(&cnt[dg], 1u);
             }
-            __syncthreads();
         }
-    }
-    // each thread owns E consecutive sorted positions
-    const int E = N >= nt ? N / nt : 1;
-    const int j0 = tid * E, j1 = min(N, j0 + E);
-    LseAcc run;
-    run.m = -INFINITY;
-    run.s = 0.f;
-    int nonempty = 0;
-    for (int j = j1 - 1; j >= j0 && j < N; --j) {
-        const u64 kx = skeys[j];
-        if (kx) {
-            run = lse_combine(lse_push(LseAcc{-INFINITY, 0.f}, L.vl[(int)(0xFFFFFFFFu - (uint32_t)kx)]), run);
-            nonempty += 1;
+        __syncthreads();
+        if (tid < 64) {
+            // lane l owns digits 4l..4l+3; weights below a digit by an ascending scan inside the first wave
+            u64 h[4];
+            unsigned n4[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                h[q] = H[4 * lane + q];
+                n4[q] = cnt[4 * lane + q];
+            }
+            const u64 mine = h[0] + h[1] + h[2] + h[3];
+            u64 x = mine;
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const u64 y = __shfl_up(x, o, CSV_WAVE);
+                if (lane >= o) x += y;
+            }
+            u64 below[4];
+            below[0] = base + (x - mine);
+            below[1] = below[0] + h[0];
+            below[2] = below[1] + h[1];
+            below[3] = below[2] + h[2];
+            int pick = -1;
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                if (n4[q] != 0 && below[q] <= LIMIT) pick = 4 * lane + q;
+            const int best = (int)wave_max_u((unsigned)(pick + 1)) - 1;
+            if (best >= 0 && (best >> 2) == lane) {
+                s.sel = (unsigned)best;
+                s.redu[0] = below[best & 3];
+            }
+            if (best < 0 && lane == 0) {                  // cannot happen (the smallest key has nothing below it); stay defined
+                s.sel = 0u;
+                s.redu[0] = base;
+            }
         }
+        __syncthreads();
+        prefix |= (u64)s.sel << sb;
+        base = s.redu[0];
     }
-    const LseAcc after = block_excl_suffix_lse(tid * E < N ? run : LseAcc{-INFINITY, 0.f}, s.redl);
-    const int ceff = block_sum_i(tid * E < N ? nonempty : 0, s.redi);
-    int best = ceff;
-    run = after;
-    for (int j = j1 - 1; j >= j0 && j < N; --j) {
-        const u64 kx = skeys[j];
-        if (kx) {
-            run = lse_combine(lse_push(LseAcc{-INFINITY, 0.f}, L.vl[(int)(0xFFFFFFFFu - (uint32_t)kx)]), run);
-            const float Tj = lse_value(run);     // tail with the first j clusters open
-            if (j >= m0 && (Tj - Z0 <= a.lam)) best = min(best, j);
-        }
-    }
-    best = block_min_i(best, s.redi);
-    return skeys[max(best, 1) - 1];
+    __syncthreads();
+    return prefix;
 }
 
 // Ordered top-kk (value descending, id ascending) of len <= blockDim.x values V in LDS with ids I; V is followed by
@@ -1312,6 +1341,10 @@ __device__ __forceinline__ void write_distribution(const StepArgs& a, int b, int
 // staged: the caller has already put the sequence's logits and ids where the staging below would put them
 // Returns true when the sequence is finished (its outputs are written), false when work was queued for later phases
 // (another round, the full vocabulary) or nothing was done.
+// THRESH: compile the threshold selection for more than RANK_DIRECT values.  The fused step kernel leaves it out (its
+// rare larger selections take the general path): with that code in the kernel a single-sequence step took 0.3 us
+// longer, although the step never runs it.
+template <bool THRESH>
 __device__ __forceinline__ bool cert_body(const StepArgs& a, int b, int chunk, int round, const SeqState& st, SeqShared& s,
                                           bool staged = false) {
     extern __shared__ u64 arena[];
@@ -1349,7 +1382,7 @@ __device__ __forceinline__ bool cert_body(const StepArgs& a, int b, int chunk, i
         l.m = vmax;
         l.s = tot;
         have_topk = true;
-    } else if (a.use_k) {
+    } else if (THRESH && a.use_k) {
         // More values (ranking all of them against each other costs len^2 comparisons: 10 us at 512).  Everything
         // below a threshold that k of the values are known to reach is out; the values at or above it (usually few
         // more than k) are collected and ranked in one pass, and the log-sum-exp runs over all values.  First
@@ -1502,19 +1535,33 @@ __device__ __forceinline__ bool cert_body(const StepArgs& a, int b, int chunk, i
         const u64 kappa0 = st.kappa;
         u64 kappa_a = kappa0, kappa_s = kappa0;
         if (a.use_k && !tk) kappa_a = (u64)lkey(theta) << 32;                 // every cluster with U_c >= theta
+        bool intact = false;                               // the by-cluster data is in LDS
         if (a.use_s && !sm) {
             load_clusters(a, b, L);
             __syncthreads();
-            kappa_s = softmax_prefix_key(a, L, st.n_open, Z, s);
-            __syncthreads();
+            bool hopeless = false;
+            if (a.use_k && !tk && a.combine == CSV_COMBINE_ALL && a.delta_clusters == 0) {
+                // when the top-k threshold alone opens more rows than allowed, the joint plan (a superset) does too:
+                // the sorted prefix search for the softmax threshold would change nothing
+                int r2 = 0;
+                for (int c = tid; c < C; c += nt) {
+                    const u64 kx = L.keys[c];
+                    if (kx >= kappa_a && kx < kappa0 && kx != 0) r2 += L.offl[c + 1] - L.offl[c];
+                }
+                hopeless = n + block_sum_i(r2, s.redi) > a.K_max;
+            }
+            if (!hopeless) kappa_s = softmax_prefix_key(a, L, kappa0, Z, s);
+            intact = true;
         }
         u64 kappa1;
         if (a.use_k && a.use_s)
             kappa1 = a.combine == CSV_COMBINE_ALL ? (kappa_a < kappa_s ? kappa_a : kappa_s) : (kappa_a > kappa_s ? kappa_a : kappa_s);
         else
             kappa1 = a.use_k ? kappa_a : kappa_s;
-        load_clusters(a, b, L);
-        __syncthreads();
+        if (!intact) {
+            load_clusters(a, b, L);
+            __syncthreads();
+        }
         int cnt = 0, rows = 0;
         for (int c = tid; c < C; c += nt) {
             const u64 kx = L.keys[c];
@@ -1584,9 +1631,10 @@ __device__ __forceinline__ bool cert_body(const StepArgs& a, int b, int chunk, i
     return false;
 }
 
+template <bool THRESH>
 __device__ __forceinline__ void cert_device(const StepArgs& a, int b, int chunk, int round, SeqShared& s) {
     const SeqState st = a.st[b];
-    cert_body(a, b, chunk, round, st, s);
+    cert_body<THRESH>(a, b, chunk, round, st, s);
 }
 
 // ================================================================================================ round 0
@@ -1948,7 +1996,7 @@ __device__ __forceinline__ int round0_device(const StepArgs& a, int b, int j, in
         }
         return 2;
     }
-    return cert_body(a, b, 0, 0, st, s, true) ? 1 : 2;     // every path of it that leaves work behind writes the state it needs
+    return cert_body<false>(a, b, 0, 0, st, s, true) ? 1 : 2;     // every path of it that leaves work behind writes the state it needs
 }
 
 // ================================================================================================ full-vocabulary product
@@ -2295,6 +2343,7 @@ __device__ __forceinline__ bool grid_barrier(int* counters, int which, int nbloc
 }
 
 // block / nblocks: this block's position among the blocks that run the tail together (all resident).
+template <bool THRESH>
 __device__ __forceinline__ void tail_device(const StepArgs& a, const FullArgs& f, int fallback_only, int block, int nblocks,
                                             SeqShared& s, GemvShared& gs, int* s_flag) {
     extern __shared__ u64 arena[];
@@ -2328,7 +2377,7 @@ __device__ __forceinline__ void tail_device(const StepArgs& a, const FullArgs& f
         if (!grid_barrier(a.counters, 2 * r, nblocks, s_flag, a.spin_limit)) return;
         // chunk-major items: the first chunks of all sequences (often the only ones with work) go to distinct blocks
         for (int item = block; item < a.B * a.sp_chunks; item += nblocks) {
-            cert_device(a, item % a.B, item / a.B, r, s);
+            cert_device<THRESH>(a, item % a.B, item / a.B, r, s);
             __syncthreads();
         }
         if (!grid_barrier(a.counters, 2 * r + 1, nblocks, s_flag, a.spin_limit)) return;
@@ -2356,7 +2405,7 @@ __global__ __launch_bounds__(TAIL_THREADS) void tail_kernel(StepArgs a, FullArgs
     __shared__ SeqShared s;
     __shared__ GemvShared gs;
     __shared__ int s_flag;
-    tail_device(a, f, fallback_only, blockIdx.x, gridDim.x, s, gs, &s_flag);
+    tail_device<true>(a, f, fallback_only, blockIdx.x, gridDim.x, s, gs, &s_flag);
 }
 
 // ------------------------------------------------------------------------------------------------ round 0 as a launch
@@ -2406,7 +2455,7 @@ __global__ __launch_bounds__(SEQ_THREADS) void step_kernel(StepArgs a, FullArgs 
     }
     __syncthreads();
     if (!s_flag) return;
-    tail_device(a, f, 0, (int)blockIdx.x - n0, (int)gridDim.x - n0, s, gs, &s_flag);
+    tail_device<false>(a, f, 0, (int)blockIdx.x - n0, (int)gridDim.x - n0, s, gs, &s_flag);   // the lean form: see cert_body
 }
 
 // ------------------------------------------------------------------------------------------------ the tail, one launch per phase
@@ -2424,7 +2473,7 @@ __global__ __launch_bounds__(TAIL_THREADS, 2) void round_gemv_kernel(StepArgs a,
 __global__ __launch_bounds__(SEQ_THREADS) void round_cert_kernel(StepArgs a, int r) {   // grid (B, chunks per sequence)
     __shared__ SeqShared s;
     if (a.counters[CNT_TAIL_NEEDED] == 0) return;
-    cert_device(a, blockIdx.x, blockIdx.y, r, s);
+    cert_device<true>(a, blockIdx.x, blockIdx.y, r, s);
 }
 
 // Up to FULL_G fallback sequences take the vector product, more the MFMA product, which needs a compute unit's whole
@@ -2534,7 +2583,7 @@ static void bound_mfma_plan(int C, int d, int& KS, int& kbs) {
 }
 
 static int launch_bounds_kernel(const StepArgs& a, float* U, float* hn, int reset, hipStream_t st) {
-    if (a.B > 8) {
+    if (a.B >= BOUND_MFMA_MIN_B) {
         const int tiles = (a.C + 15) / 16;
         int KS, kbs;
         bound_mfma_plan(a.C, a.d, KS, kbs);
@@ -2666,7 +2715,7 @@ extern "C" int csv_workspace_create(const csv_index* idx, int B_max, int K_cap_r
     const size_t tcap = B * (size_t)ws->tile_stride;
     hipError_t e = hipSuccess;
     auto A = [&](void** p, size_t bytes) { if (e == hipSuccess) e = hipMalloc(p, bytes ? bytes : 16); };
-    A((void**)&ws->U, B * C * 4); A((void**)&ws->bound_partial, B_max > 8 ? B * C * 4 * BOUND_KS_MAX : 16); A((void**)&ws->hnorm, B * 4); A((void**)&ws->st, B * sizeof(SeqState));
+    A((void**)&ws->U, B * C * 4); A((void**)&ws->bound_partial, B_max >= BOUND_MFMA_MIN_B ? B * C * 4 * BOUND_KS_MAX : 16); A((void**)&ws->hnorm, B * 4); A((void**)&ws->st, B * sizeof(SeqState));
     A((void**)&ws->sel, B * C * 4); A((void**)&ws->slog, B * K * 4); A((void**)&ws->sid, B * K * 4);
     A((void**)&ws->slots, B * CSV_SLOT_ROWS * 8);
     A((void**)&ws->tiles[0], tcap * sizeof(Tile)); A((void**)&ws->tiles[1], tcap * sizeof(Tile));
@@ -2802,7 +2851,7 @@ extern "C" int csv_bounds_static(const csv_index* idx, const uint16_t* d_h, int 
     a.V = idx->V; a.d = idx->d; a.C = idx->C;
     a.mu = idx->mu; a.mu16 = idx->mu16; a.R = idx->R; a.bmax = idx->bmax; a.n = idx->n; a.bt = idx->bt; a.bt_m = idx->bt_m; a.ang = idx->ang;
     a.B = B; a.h = d_h;
-    if (B > 8) {                       // the batched product is the only bound kernel with scratch: KS x B x C partial sums
+    if (B >= BOUND_MFMA_MIN_B) {       // the batched product is the only bound kernel with scratch: KS x B x C partial sums
         int KS, kbs;
         bound_mfma_plan(idx->C, idx->d, KS, kbs);
         const size_t need = (size_t)KS * B * idx->C * sizeof(float);
@@ -2881,7 +2930,7 @@ extern "C" int csv_decode_step(csv_workspace* ws, const csv_index* idx, const ui
         split = __builtin_popcount(history & 0xffu) >= 2;
         // the three fallback phases as launches of their own only while fallbacks occur; otherwise one launch
         // of the single kernel restricted to them, which returns at once when nobody fell back
-        fb_launches = ((history >> 16) & 0xffu) != 0;
+        fb_launches = (history >> 16) != 0;         // any of the last 15 steps
     }
     // blocks per sequence in round 0: as many as stay resident together (a second wave of blocks would double the
     // kernel's time), at most ROUND0_NB_MAX, and no more than the largest possible seed prefix needs at

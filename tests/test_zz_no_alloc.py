@@ -49,7 +49,7 @@ def test_static_bounds_reject_what_the_scratch_cannot_hold():
     with pytest.raises(csv.CsvError) as e:
         csv.csv_bounds_static(idx, h, U, hn)                  # 2 K slices x 256 x 8192 floats = 16 MiB > 8 MiB
     assert e.value.code == -4 and "static scratch" in str(e.value)
-    csv.csv_bounds_static(idx, h[:8], U[:8], hn[:8])          # up to 8 sequences need no scratch at all
+    csv.csv_bounds_static(idx, h[:4], U[:4], hn[:4])          # up to 4 sequences need no scratch at all
     csv.csv_bounds_static(idx, h[:100], U[:100], hn[:100])    # 2 x 100 x 8192 floats fit
     torch.cuda.synchronize()
     assert np.all(U[:100].cpu().numpy() == 0.0)               # h = 0: every bound is the bias maximum, 0
