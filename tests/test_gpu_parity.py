@@ -214,6 +214,19 @@ def test_step_zipf_sizes_no_bias_ragged_batch():
     case.close()
 
 
+@pytest.mark.gpu
+@pytest.mark.parametrize("k", [5, 200, 300])
+def test_step_later_rounds_rank_many_rows(k):
+    # rounds after the first rank several hundred to several thousand rows: up to 256 directly, more through a
+    # threshold (k <= 256) or the general selection (k = 300), more than 4096 in chunks whose lists are merged
+    r = synth.small_recipe(f"many{k}", V=24000, d=72, C=48, B=5, steps=4, h_mode="mix", iso_frac=0.2, k=k, eps=1e-5)
+    case = Case(r, seed=61, K_cap=24000)
+    t = case.run_steps(case.hidden(), k, r.eps, 20000, O.COMBINE_ALL, f"many rows k={k}")
+    _finish(t, f"many rows k={k}")
+    assert t.rows / t.n > 600, t.summary()        # the certified sequences opened several clusters of 500 rows each
+    case.close()
+
+
 def test_step_single_cluster_and_singletons():
     r = synth.small_recipe("C1", V=700, d=64, C=1, B=2, steps=2)
     case = Case(r, seed=14, K_cap=700)
