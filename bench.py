@@ -32,6 +32,64 @@ def step_bytes(r, C, rows_union: float, any_fallback_frac: float, k: int, mu_byt
             + any_fallback_frac * r.V * (2 * r.d + 4) + r.B * (8 * k + 16))
 
 
+def brief(name: str, steps: int = 64, warmup: int = 10) -> dict:
+    """One of the other workloads, measured the same way but briefly: `steps` timed steps after `warmup`, the
+    dense product at the same batch, and how the steps ended (32 steps with a synchronisation each)."""
+    import numpy as np
+    import torch
+
+    import synth
+    import paper_2511_21702_amd as csv
+
+    r = synth.CONFIGS[name]
+    head = synth.make_head(r, threads=16)
+    h_bits = synth.make_hidden(r, head["centers"], steps=steps + warmup)
+    dW = csv.bits_to_device(head["W_bits"])
+    db = torch.from_numpy(head["b"]).cuda()
+    idx = csv.csv_build_index(dW, db, r.C, init_labels=head["labels"].astype(np.int32))
+    del dW
+    ws = csv.CsvWorkspace(idx, r.B, r.K_max_rows)
+    dh = csv.bits_to_device(h_bits)
+    buf = csv.make_step_buffers(idx, r.B, r.k, r.eps, r.K_max_rows)
+    sp = torch.cuda.current_stream().cuda_stream
+    hp = [dh[s].data_ptr() for s in range(steps + warmup)]
+    for s in range(warmup):
+        csv.csv_decode_step_raw(ws, idx, hp[s], r.B, buf, sp)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for s in range(warmup, warmup + steps):
+        csv.csv_decode_step_raw(ws, idx, hp[s], r.B, buf, sp)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t1
+    nstat, n_fb, anyfb, rows, ncert = min(32, steps), 0, 0, 0, 0
+    for s in range(warmup, warmup + nstat):
+        csv.csv_decode_step_raw(ws, idx, hp[s], r.B, buf, sp)
+        torch.cuda.synchronize()
+        fl = buf.flags.cpu().numpy()
+        fb = (fl & csv.FLAG_FALLBACK) != 0
+        n_fb += int(fb.sum()); anyfb += int(fb.any())
+        rows += int(buf.n_rows.cpu().numpy()[~fb].sum()); ncert += int((~fb).sum())
+    full_out = torch.empty((r.B, r.V), dtype=torch.float32, device="cuda")
+    for s in range(2):
+        csv.csv_full_logits(ws, idx, dh[s], out=full_out)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for s in range(8):
+        csv.csv_full_logits(ws, idx, dh[s], out=full_out)
+    torch.cuda.synchronize()
+    full_ms = (time.perf_counter() - t1) * 1e3 / 8
+    ms = wall * 1e3 / steps
+    out = {"workload": f"{r.name}: V={r.V} d={r.d} C={r.C} B={r.B} k={r.k} eps={r.eps:g} K_max={r.K_max_rows}",
+           "steps": steps, "ms_per_step": ms, "steps_per_s": 1e3 / ms, "seq_steps_per_s": r.B * 1e3 / ms,
+           "fallback_rate": n_fb / (nstat * r.B), "steps_with_fallback": anyfb / nstat,
+           "mean_rows_per_certified_seq": rows / max(ncert, 1),
+           "full_gemv_ms": full_ms, "speedup_vs_full_gemv": full_ms / ms}
+    del buf, full_out, dh
+    ws.free(); idx.free()
+    torch.cuda.empty_cache()
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -48,12 +106,14 @@ def main() -> int:
     ap.add_argument("--kmeans", type=int, default=-1, metavar="ITERS",
                     help="time the offline index build instead: Lloyd's k-means with ITERS iterations from the default seeding "
                          "rule on the config's head (Section IV, offline preprocessing); prints its own JSON line and exits")
+    ap.add_argument("--others", type=int, default=-1,
+                    help="also measure the other four workloads briefly (field other_configs): 1 yes, 0 no, -1 only in the default run (c2, no options)")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="for `rocprofv3 --pmc FETCH_SIZE|WRITE_SIZE`: launch a device-to-device copy of known size, "
                          "the bound kernel and a few whole steps, then exit (no timing, no JSON)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (the path shards by cluster, see DESIGN.md); use --gpus 1",
+        print("bench.py: this build runs on one GPU only (every figure is one GPU's throughput); use --gpus 1",
               file=sys.stderr)
         return 2
 
@@ -381,6 +441,20 @@ def main() -> int:
         "full_gemv": {"ms_per_step": full_ms, "steps_per_s": 1e3 / full_ms, "GBps": full_bytes / (full_ms * 1e-3) / 1e9},
         "speedup_vs_full_gemv": full_ms / ms_per_step,
     }
+    plain = not (args.bf16_centroids or args.bias_table or args.spherical or args.max_rounds or args.delta_clusters or args.relax)
+    if args.others == 1 or (args.others < 0 and args.config == "c2" and plain and args.cpu_steps != 0):
+        # the main workload's buffers go first: the largest of the others needs 2.4 GB for W' alone
+        del buf, buf_s, full_out, dh
+        ws.free(); idx.free()
+        torch.cuda.empty_cache()
+        others = {}
+        t_o = time.time()
+        for name in ("c1", "c3", "c4", "c5"):
+            if name == args.config:
+                continue
+            others[name] = brief(name)
+            log(f"[bench] {name}: {others[name]['ms_per_step'] * 1e3:.1f} us/step, dense {others[name]['full_gemv_ms'] * 1e3:.1f} us ({time.time() - t_o:.0f}s so far)")
+        out["other_configs"] = others
     print(json.dumps(out))
     return 0
 

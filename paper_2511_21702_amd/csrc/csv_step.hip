@@ -1306,6 +1306,89 @@ __device__ __forceinline__ float rank_small(const float* V, const int* I, int le
     return vmax;
 }
 
+// Ordered top-k of len > RANK_DIRECT values staged at the start of the dynamic LDS (ranking all of them against each
+// other costs len^2 comparisons: 10 us at 512).  Everything below a threshold that k of the values are known to reach
+// is out; the values at or above it (usually few more than k) are collected behind the staged data and ranked in one
+// pass.  First threshold: theta, a value the caller knows k of the values to reach (-inf: none).  Failing that, or
+// when more than CAND_CAP values reach it: the k-th largest of RANK_DIRECT group maxima.  short_ok: the values are one chunk of several
+// and fewer than k of them may reach theta (the merged lists still hold the overall top-k).  The collected order
+// depends on timing, the ranking does not.  On success s.wval / s.wid hold kkv entries once the caller has passed a
+// barrier, vmax is the largest value; on failure (k > RANK_DIRECT, too many survivors) nothing is decided.
+template <class IdFn>
+__device__ __forceinline__ bool threshold_topk(int len, int k, float theta, bool short_ok, IdFn idf, SeqShared& s, int& kkv, float& vmax) {
+    extern __shared__ u64 arena[];
+    const int tid = threadIdx.x, nt = blockDim.x, lane = tid & 63;
+    const float* V = reinterpret_cast<const float*>(arena);
+    const int k0 = min(k, len);
+    auto attempt = [&](float th) -> bool {
+        float* wmax = reinterpret_cast<float*>(s.hist);
+        float* cval = reinterpret_cast<float*>(reinterpret_cast<char*>(arena) + CAND_OFF);
+        int* cid = reinterpret_cast<int*>(cval + CAND_CAP + 4);
+        if (tid < CAND_CAP) cval[tid] = -INFINITY;
+        if (tid < 4) cval[CAND_CAP + tid] = -INFINITY;
+        if (tid == 0) s.cnt = 0;
+        __syncthreads();
+        float mx = -INFINITY;
+        for (int i0 = 0; i0 < len; i0 += nt) {
+            const int i = i0 + tid;
+            const float v = i < len ? V[i] : -INFINITY;
+            mx = fmaxf(mx, v);
+            const bool in = i < len && v >= th;
+            const unsigned long long bal = __ballot(in);
+            if (bal) {
+                const int lead = __ffsll((long long)bal) - 1;
+                unsigned base = 0;
+                if (lane == lead) base = atomicAdd(&s.cnt, (unsigned)__popcll(bal));
+                base = __shfl(base, lead, CSV_WAVE);
+                const unsigned slot = base + (unsigned)__popcll(bal & ((1ull << lane) - 1ull));
+                if (in && slot < CAND_CAP) {
+                    cval[slot] = v;
+                    cid[slot] = idf(i);
+                }
+            }
+        }
+        mx = wave_max(mx);
+        if (lane == 0) wmax[tid >> 6] = mx;
+        __syncthreads();
+        const int m = (int)s.cnt;
+        if (m > CAND_CAP || (!short_ok && m < k0)) return false;
+        vmax = wmax[0];
+        for (int q = 1; q < (nt >> 6); ++q) vmax = fmaxf(vmax, wmax[q]);
+        kkv = min(k, m);
+        float v;
+        rank_small(cval, cid, m, kkv, s, v);
+        return true;
+    };
+    bool ok = false;
+    if (theta > -INFINITY) ok = attempt(theta);
+    if (!ok && k <= RANK_DIRECT) {
+        // RANK_DIRECT group maxima (group g: the values i with i % RANK_DIRECT == g; len > RANK_DIRECT, so no group is
+        // empty): k of them, hence k of the values, reach their k-th largest, and since the largest values mostly sit
+        // in different groups few more do
+        float* cval = reinterpret_cast<float*>(reinterpret_cast<char*>(arena) + CAND_OFF);
+        float mx = -INFINITY;
+        for (int i = tid; i < len; i += nt) mx = fmaxf(mx, V[i]);
+        __syncthreads();
+        if (tid < CAND_CAP) cval[tid] = mx;
+        __syncthreads();
+        float m2 = -INFINITY;
+        if (tid < RANK_DIRECT) {
+            m2 = cval[tid];
+            for (int j = tid + RANK_DIRECT; j < min(nt, CAND_CAP); j += RANK_DIRECT) m2 = fmaxf(m2, cval[j]);
+        }
+        __syncthreads();
+        if (tid < RANK_DIRECT) cval[tid] = m2;
+        __syncthreads();
+        float v;
+        rank_small(cval, reinterpret_cast<const int*>(cval), RANK_DIRECT, k, s, v);      // only the k-th value is wanted: any ids do
+        __syncthreads();
+        const float th = fmaxf(s.wval[k - 1], theta);
+        __syncthreads();
+        ok = attempt(th);
+    }
+    return ok;
+}
+
 // ================================================================================================ certified distribution
 // Optional outputs (Section III, top-p certification): over the returned list, in its order, the sub-vocabulary
 // probabilities p~_t = exp(l_t - Z_S), their running sums, and the length of the shortest prefix whose running sum
@@ -1383,67 +1466,15 @@ __device__ __forceinline__ bool cert_body(const StepArgs& a, int b, int chunk, i
         l.s = tot;
         have_topk = true;
     } else if (THRESH && a.use_k) {
-        // More values (ranking all of them against each other costs len^2 comparisons: 10 us at 512).  Everything
-        // below a threshold that k of the values are known to reach is out; the values at or above it (usually few
-        // more than k) are collected and ranked in one pass, and the log-sum-exp runs over all values.  First
-        // threshold: the previous round's k-th logit (its rows are among these).  Failing that, or when too many
-        // values reach it: the k-th largest of the first RANK_DIRECT values (the clusters come in bound order, so
-        // they hold most of the top).  The collected order depends on timing, the ranking does not.
-        const int lane = tid & 63;
-        const int k0 = kkv;
-        auto try_threshold = [&](float th) -> bool {
-            float* wmax = reinterpret_cast<float*>(s.hist);
-            float* cval = reinterpret_cast<float*>(reinterpret_cast<char*>(arena) + CAND_OFF);
-            int* cid = reinterpret_cast<int*>(cval + CAND_CAP + 4);
-            if (tid < CAND_CAP) cval[tid] = -INFINITY;
-            if (tid < 4) cval[CAND_CAP + tid] = -INFINITY;
-            if (tid == 0) s.cnt = 0;
-            __syncthreads();
-            float mx = -INFINITY;
-            for (int i0 = 0; i0 < len; i0 += nt) {
-                const int i = i0 + tid;
-                const float v = i < len ? val(i) : -INFINITY;
-                mx = fmaxf(mx, v);
-                const bool in = i < len && v >= th;
-                const unsigned long long bal = __ballot(in);
-                if (bal) {
-                    const int lead = __ffsll((long long)bal) - 1;
-                    unsigned base = 0;
-                    if (lane == lead) base = atomicAdd(&s.cnt, (unsigned)__popcll(bal));
-                    base = __shfl(base, lead, CSV_WAVE);
-                    const unsigned slot = base + (unsigned)__popcll(bal & ((1ull << lane) - 1ull));
-                    if (in && slot < CAND_CAP) {
-                        cval[slot] = v;
-                        cid[slot] = idf(i);
-                    }
-                }
-            }
-            mx = wave_max(mx);
-            if (lane == 0) wmax[tid >> 6] = mx;
-            __syncthreads();
-            const int m = (int)s.cnt;
-            if (m > CAND_CAP || (nchunks == 1 && m < k0)) return false;
-            float vmax = wmax[0];
-            for (int q = 1; q < (nt >> 6); ++q) vmax = fmaxf(vmax, wmax[q]);
-            kkv = min(a.k, m);
-            float v;
-            rank_small(cval, cid, m, kkv, s, v);
+        // more values: through a threshold (see threshold_topk); the log-sum-exp runs over all values
+        float vmax;
+        if (threshold_topk(len, a.k, st.theta, nchunks > 1, idf, s, kkv, vmax)) {
             float sm = 0.f;
             if (vmax > -INFINITY)
                 for (int i = tid; i < len; i += nt) sm += expf(val(i) - vmax);
             l.m = vmax;
             l.s = block_sum(sm, s.redf);
-            return true;
-        };
-        if (st.theta > -INFINITY) have_topk = try_threshold(st.theta);
-        if (!have_topk && a.k <= RANK_DIRECT) {
-            float v;
-            __syncthreads();
-            rank_small(reinterpret_cast<const float*>(arena), reinterpret_cast<const int*>(arena) + STAGE_CAP, RANK_DIRECT, a.k, s, v);
-            __syncthreads();
-            const float th = fmaxf(s.wval[a.k - 1], st.theta);
-            __syncthreads();
-            have_topk = try_threshold(th);
+            have_topk = true;
         }
     }
     if (have_topk) {
@@ -2243,6 +2274,7 @@ __global__ __launch_bounds__(MFMA_THREADS) void full_mfma_kernel(FullArgs f) {
 
 // First stage of top-k / log-sum-exp over V: one block per (chunk of rows, fallback slot).  The chunk's logits
 // are staged in LDS; token ids come from the permutation only for elements at the selection boundary.
+template <bool THRESH>
 __device__ __forceinline__ void fb_topk_device(const StepArgs& a, int slot, int chunk, SeqShared& s) {
     extern __shared__ u64 arena[];
     const int tid = threadIdx.x, nt = blockDim.x;
@@ -2260,7 +2292,15 @@ __device__ __forceinline__ void fb_topk_device(const StepArgs& a, int slot, int 
         a.cand_sum[pc] = l.s;
     }
     if (a.k > 0) {
-        const int kk = block_topk(n, a.k, val, idf, s);
+        int kk = 0;
+        float vmax;
+        bool done = false;
+        if (THRESH && n > RANK_DIRECT) {
+            __syncthreads();
+            done = threshold_topk(n, a.k, -INFINITY, false, idf, s, kk, vmax);
+            __syncthreads();
+        }
+        if (!done) kk = block_topk(n, a.k, val, idf, s);
         for (int t = tid; t < a.k; t += nt) {
             a.cand_val[pc * a.k + t] = t < kk ? s.wval[t] : -INFINITY;
             a.cand_id[pc * a.k + t] = t < kk ? s.wid[t] : 0x7fffffff;
@@ -2269,6 +2309,7 @@ __device__ __forceinline__ void fb_topk_device(const StepArgs& a, int slot, int 
 }
 
 // Second stage: merge the chunk candidates of one fallback sequence and write its outputs.
+template <bool THRESH>
 __device__ __forceinline__ void fb_final_device(const StepArgs& a, int slot, SeqShared& s) {
     extern __shared__ u64 arena[];
     const int tid = threadIdx.x, nt = blockDim.x;
@@ -2288,8 +2329,16 @@ __device__ __forceinline__ void fb_final_device(const StepArgs& a, int slot, Seq
         if (n <= STAGE_CAP) {
             stage2_to_lds(reinterpret_cast<float*>(arena), cv, reinterpret_cast<int*>(arena) + STAGE_CAP, ci, n);
             __syncthreads();
-            block_topk(n, a.k, [](int i) { return reinterpret_cast<const float*>(arena)[i]; },
-                       [](int i) { return reinterpret_cast<const int*>(arena)[STAGE_CAP + i]; }, s);
+            auto sval = [](int i) { return reinterpret_cast<const float*>(arena)[i]; };
+            auto sid = [](int i) { return reinterpret_cast<const int*>(arena)[STAGE_CAP + i]; };
+            int kk = 0;
+            float vmax;
+            bool done = false;
+            if (THRESH && n > RANK_DIRECT) {
+                done = threshold_topk(n, a.k, -INFINITY, false, sid, s, kk, vmax);
+                __syncthreads();
+            }
+            if (!done) block_topk(n, a.k, sval, sid, s);
         } else {
             block_topk(n, a.k, [&](int i) { return cv[i]; }, [&](int i) { return ci[i]; }, s);
         }
@@ -2391,12 +2440,12 @@ __device__ __forceinline__ void tail_device(const StepArgs& a, const FullArgs& f
         full_gemv_device(f, n_fb, reinterpret_cast<uint4*>(arena), block, nblocks);
     if (!grid_barrier(a.counters, 2 * CSV_MAX_ROUNDS, nblocks, s_flag, a.spin_limit)) return;
     for (int item = block; item < n_fb * a.n_chunks; item += nblocks) {
-        fb_topk_device(a, item / a.n_chunks, item % a.n_chunks, s);
+        fb_topk_device<THRESH>(a, item / a.n_chunks, item % a.n_chunks, s);
         __syncthreads();
     }
     if (!grid_barrier(a.counters, 2 * CSV_MAX_ROUNDS + 1, nblocks, s_flag, a.spin_limit)) return;
     for (int slot = block; slot < n_fb; slot += nblocks) {
-        fb_final_device(a, slot, s);
+        fb_final_device<THRESH>(a, slot, s);
         __syncthreads();
     }
 }
@@ -2495,13 +2544,13 @@ __global__ __launch_bounds__(MFMA_THREADS) void fb_product_mfma_kernel(StepArgs 
 __global__ __launch_bounds__(SEQ_THREADS) void fb_topk_kernel(StepArgs a) {             // grid (chunks of V, B)
     __shared__ SeqShared s;
     if ((int)blockIdx.y >= a.counters[CNT_FALLBACK]) return;
-    fb_topk_device(a, blockIdx.y, blockIdx.x, s);
+    fb_topk_device<true>(a, blockIdx.y, blockIdx.x, s);
 }
 
 __global__ __launch_bounds__(SEQ_THREADS) void fb_final_kernel(StepArgs a) {            // grid B
     __shared__ SeqShared s;
     if ((int)blockIdx.x >= a.counters[CNT_FALLBACK]) return;
-    fb_final_device(a, blockIdx.x, s);
+    fb_final_device<true>(a, blockIdx.x, s);
 }
 
 // ================================================================================================ host side
@@ -2976,9 +3025,9 @@ extern "C" int csv_decode_step(csv_workspace* ws, const csv_index* idx, const ui
                     fb_product_mfma_kernel<<<ws->tail_grid, MFMA_THREADS, MFMA_LDS, st>>>(a, f);
                     CSV_LAUNCH_CHECK("fb_product_mfma_kernel");
                 }
-                fb_topk_kernel<<<dim3(ws->n_chunks, B), SEQ_THREADS, (size_t)FB_CHUNK * 4, st>>>(a);
+                fb_topk_kernel<<<dim3(ws->n_chunks, B), SEQ_THREADS, (size_t)CAND_OFF + CAND_BYTES, st>>>(a);
                 CSV_LAUNCH_CHECK("fb_topk_kernel");
-                fb_final_kernel<<<B, SEQ_THREADS, (size_t)STAGE_CAP * 8, st>>>(a);
+                fb_final_kernel<<<B, SEQ_THREADS, (size_t)CAND_OFF + CAND_BYTES, st>>>(a);
                 CSV_LAUNCH_CHECK("fb_final_kernel");
             } else {
                 tail_kernel<<<ws->tail_grid, TAIL_THREADS, ws->tail_lds, st>>>(a, f, 1);
