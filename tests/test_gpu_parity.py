@@ -227,6 +227,24 @@ def test_step_later_rounds_rank_many_rows(k):
     case.close()
 
 
+@pytest.mark.gpu
+def test_two_live_workspaces_with_different_lds_needs():
+    # the per-kernel dynamic-LDS limit is process-wide: a later, smaller workspace must not lower what an earlier,
+    # larger one (C = 4096: more than 64 KB of cluster data per block) still needs
+    big = synth.small_recipe("ldsbig", V=12000, d=64, C=4096, B=2, steps=2, h_mode="mix", k=5, eps=1e-3)
+    small = synth.small_recipe("ldssmall", V=3000, d=64, C=16, B=9, steps=2, k=5, eps=1e-3)
+    c_big = Case(big, seed=71)
+    t = c_big.run_steps(c_big.hidden(), 5, 1e-3, big.K_max_rows, O.COMBINE_ALL, "big before")
+    _finish(t, "big before")
+    c_small = Case(small, seed=72)
+    t = c_small.run_steps(c_small.hidden(), 5, 1e-3, small.K_max_rows, O.COMBINE_ALL, "small")
+    _finish(t, "small")
+    t = c_big.run_steps(c_big.hidden(), 5, 1e-3, big.K_max_rows, O.COMBINE_ALL, "big after")
+    _finish(t, "big after")
+    c_small.close()
+    c_big.close()
+
+
 def test_step_single_cluster_and_singletons():
     r = synth.small_recipe("C1", V=700, d=64, C=1, B=2, steps=2)
     case = Case(r, seed=14, K_cap=700)
