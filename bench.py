@@ -102,6 +102,7 @@ def main() -> int:
     ap.add_argument("--bias-table", type=int, default=0, help="index option: top-m bias table (Section III, bias binning), m = 2..8")
     ap.add_argument("--spherical", action="store_true", help="index option: unit directions and the angular bound (Section III, spherical clustering)")
     ap.add_argument("--relax", action="store_true", help="fallback levels: accept the softmax bound at 2 eps before falling back")
+    ap.add_argument("--alg1", action="store_true", help="Algorithm 1's own order (one cluster per iteration, the reference mode) instead of the round-based schedule; use with --cpu-steps 0")
     ap.add_argument("--cpu-steps", type=int, default=-1, help="oracle steps to time (-1: sized to ~15 s, 0: skip)")
     ap.add_argument("--kmeans", type=int, default=-1, metavar="ITERS",
                     help="time the offline index build instead: Lloyd's k-means with ITERS iterations from the default seeding "
@@ -161,7 +162,7 @@ def main() -> int:
     ws = csv.CsvWorkspace(idx, r.B, r.K_max_rows)
     dh = csv.bits_to_device(h_bits)
     nh = h_bits.shape[0]
-    lad = dict(max_rounds=args.max_rounds, delta_clusters=args.delta_clusters, relax=args.relax)
+    lad = dict(max_rounds=args.max_rounds, delta_clusters=args.delta_clusters, relax=args.relax, schedule=1 if args.alg1 else 0)
     buf = csv.make_step_buffers(idx, r.B, r.k, r.eps, r.K_max_rows, **lad)
     stream = torch.cuda.current_stream()
     sp = stream.cuda_stream
@@ -244,7 +245,7 @@ def main() -> int:
             opened.update(sel[b, :nc[b]].tolist())
         rows_union_sum += float(sizes[list(opened)].sum()) if opened else 0.0
         for v in buf_s.rounds.cpu().numpy():
-            rounds_hist[int(v)] += 1
+            rounds_hist[int(v)] = rounds_hist.get(int(v), 0) + 1
     n_seq = nstat * r.B
     fb_rate = int(buf_s.fallback_count.item()) / n_seq
     # bound tightness xi = (largest logit of a cluster) / (its bound), Section III-A "Bound Quality Analysis", averaged over
@@ -422,6 +423,7 @@ def main() -> int:
                                + (", bf16 centroids" if args.bf16_centroids else "")
                                + (f", top-{args.bias_table} bias table" if args.bias_table >= 2 else "")
                                + (", angular index" if args.spherical else "")
+                               + (", Algorithm 1's order (one cluster per iteration)" if args.alg1 else "")
                                + (f", fallback levels max_rounds={args.max_rounds} delta_clusters={args.delta_clusters} relax={int(args.relax)}"
                                   if (args.max_rounds or args.delta_clusters or args.relax) else ""), "batch": r.B},
         "roofline": roof,
@@ -441,7 +443,7 @@ def main() -> int:
         "full_gemv": {"ms_per_step": full_ms, "steps_per_s": 1e3 / full_ms, "GBps": full_bytes / (full_ms * 1e-3) / 1e9},
         "speedup_vs_full_gemv": full_ms / ms_per_step,
     }
-    plain = not (args.bf16_centroids or args.bias_table or args.spherical or args.max_rounds or args.delta_clusters or args.relax)
+    plain = not (args.bf16_centroids or args.bias_table or args.spherical or args.max_rounds or args.delta_clusters or args.relax or args.alg1)
     if args.others == 1 or (args.others < 0 and args.config == "c2" and plain and args.cpu_steps != 0):
         # the main workload's buffers go first: the largest of the others needs 2.4 GB for W' alone
         del buf, buf_s, full_out, dh

@@ -42,6 +42,9 @@ extern "C" {
 #define CSV_FLAG_ABORTED      32u   /* the step could not finish this sequence: a bounded device-side wait ran out (see
                                        csv_workspace_set_spin_limit); its other outputs are undefined.  Set alone. */
 
+#define CSV_SCHEDULE_ROUNDS 0   /* the round-based schedule: tests at round boundaries (see csv_decode_step) */
+#define CSV_SCHEDULE_ALG1   1   /* Algorithm 1's own order: one cluster per iteration, the tests after every opening */
+
 #define CSV_COMBINE_ALL 0   /* certified when every enabled certificate holds */
 #define CSV_COMBINE_ANY 1   /* certified when any enabled certificate holds (Algorithm 1 stops on either) */
 
@@ -160,6 +163,15 @@ typedef struct {
     int   relax;           /* nonzero: when no further expansion is possible, accept a step whose softmax tail bound
                               holds at 2*eps (flag SOFTMAX_RELAXED) before falling back to the full vocabulary */
     float top_p;           /* nucleus mass for d_nucleus, in 0..1 (0 = none); see csv_step_out */
+    int   schedule;        /* CSV_SCHEDULE_ROUNDS (0, the fast path) or CSV_SCHEDULE_ALG1: open clusters one at a time in
+                              bound order and stop at the first prefix that certifies (Algorithm 1, Section III-C), i.e.
+                              with the smallest certifying set of clusters.  A reference mode: one thread block per
+                              sequence does all the work of that sequence, so it is slow when many clusters are needed.
+                              The budget is tested before a cluster's rows are scored (more than K_max_rows -> fallback).
+                              d_rounds reports the clusters opened; d_sel_clusters lists them in bound order; entries of
+                              d_ids / d_logits past the rows scored are -1 / -inf (softmax-only certification may stop
+                              with fewer than k rows).  No fallback levels.  CSV_ESHAPE when the cluster data (24 bytes
+                              per cluster) and h do not fit a compute unit's LDS next to 36 KB of staging. */
 } csv_step_params;
 
 typedef struct {

@@ -16,6 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libcsvdecode.so")
 
 FLAG_TOPK_CERT, FLAG_SOFTMAX_CERT, FLAG_FALLBACK, FLAG_INVALID_INPUT, FLAG_SOFTMAX_RELAXED, FLAG_ABORTED = 1, 2, 4, 8, 16, 32
+SCHEDULE_ROUNDS, SCHEDULE_ALG1 = 0, 1
 COMBINE_ALL, COMBINE_ANY = 0, 1
 MAX_K, MAX_CLUSTERS, MAX_BATCH = 1024, 8192, 256
 
@@ -37,7 +38,8 @@ class BuildOpts(C.Structure):
 
 class StepParams(C.Structure):
     _fields_ = [("k", C.c_int), ("eps", C.c_float), ("K_max_rows", C.c_int), ("combine", C.c_int),
-                ("max_rounds", C.c_int), ("delta_clusters", C.c_int), ("relax", C.c_int), ("top_p", C.c_float)]
+                ("max_rounds", C.c_int), ("delta_clusters", C.c_int), ("relax", C.c_int), ("top_p", C.c_float),
+                ("schedule", C.c_int)]
 
 
 class KmaxCtl(C.Structure):
@@ -296,7 +298,7 @@ class StepBuffers:
 
 def make_step_buffers(index: CsvIndex, B: int, k: int, eps: float, K_max_rows: int, combine: int = COMBINE_ALL,
                       want_sel: bool = False, device="cuda", max_rounds: int = 0, delta_clusters: int = 0,
-                      relax: bool = False, want_dist: bool = False, top_p: float = 0.0) -> StepBuffers:
+                      relax: bool = False, want_dist: bool = False, top_p: float = 0.0, schedule: int = 0) -> StepBuffers:
     kk = max(k, 1)
     ids = torch.full((B, kk), -2, dtype=torch.int32, device=device)
     logits = torch.zeros((B, kk), dtype=torch.float32, device=device)
@@ -311,7 +313,7 @@ def make_step_buffers(index: CsvIndex, B: int, k: int, eps: float, K_max_rows: i
     cum = torch.full((B, kk), -1.0, dtype=torch.float32, device=device) if want_dist else None
     nucleus = torch.full((B,), -1, dtype=torch.int32, device=device) if want_dist else None
     params = StepParams(k=k, eps=eps, K_max_rows=K_max_rows, combine=combine, max_rounds=max_rounds,
-                        delta_clusters=delta_clusters, relax=int(bool(relax)), top_p=top_p)
+                        delta_clusters=delta_clusters, relax=int(bool(relax)), top_p=top_p, schedule=schedule)
     out = StepOut(ids.data_ptr(), logits.data_ptr(), lse.data_ptr(), flags.data_ptr(), n_rows.data_ptr(),
                   n_clusters.data_ptr(), rounds.data_ptr(), sel.data_ptr() if want_sel else None, fbc.data_ptr(),
                   probs.data_ptr() if want_dist else None, cum.data_ptr() if want_dist else None,

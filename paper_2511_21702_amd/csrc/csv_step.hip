@@ -2030,6 +2030,139 @@ __device__ __forceinline__ int round0_device(const StepArgs& a, int b, int j, in
     return cert_body<false>(a, b, 0, 0, st, s, true) ? 1 : 2;     // every path of it that leaves work behind writes the state it needs
 }
 
+// ================================================================================================ Algorithm 1's own order
+// One cluster per iteration, the tests after every opening: the shortest certifying prefix of the bound order
+// (Algorithm 1, Section III-C).  A reference mode, not the fast path: one block per sequence does everything itself, so
+// an iteration is a block-wide arg-max, the rows of one cluster (a row per wave at a time) and a top-k update, with
+// no dependency between blocks.  Dynamic LDS: staged values and ids with the candidates behind them (as the
+// certification lays them out), then the sequence's cluster data, then h.
+#define ALG1_PIECE 2048            // rows of a cluster scored between two updates of the list (a piece plus the list fit the staging area)
+#define ALG1_CL_OFF (CAND_OFF + CAND_BYTES + 16)      // bytes; a multiple of 16
+static_assert(ALG1_PIECE + CSV_MAX_K <= STAGE_CAP && ALG1_CL_OFF % 16 == 0, "Algorithm-1 mode: staging layout");
+__global__ __launch_bounds__(SEQ_THREADS) void alg1_kernel(StepArgs a, int h_off16) {
+    extern __shared__ u64 arena[];
+    __shared__ SeqShared s;
+    const int b = blockIdx.x, tid = threadIdx.x, nt = SEQ_THREADS, lane = tid & 63, wave = tid >> 6, C = a.C;
+    const int nch = a.d >> 3;
+    float* sv = reinterpret_cast<float*>(arena);
+    int* si = reinterpret_cast<int*>(arena) + STAGE_CAP;
+    const ClusterLds L = carve_clusters(reinterpret_cast<u64*>(reinterpret_cast<char*>(arena) + ALG1_CL_OFF), a.Npad, C);
+    uint4* hs4 = reinterpret_cast<uint4*>(arena) + h_off16;
+    auto val = [](int i) { return reinterpret_cast<const float*>(arena)[i]; };
+    auto idf = [](int i) { return reinterpret_cast<const int*>(arena)[STAGE_CAP + i]; };
+    const float hn = a.hnorm[b];
+    if (!isfinite(hn)) {
+        write_invalid(a, b);
+        return;
+    }
+    load_clusters(a, b, L);
+    for (int i = tid; i < nch; i += nt) hs4[i] = (reinterpret_cast<const uint4*>(a.h) + (size_t)b * nch)[i];
+    __syncthreads();
+    u64 kappa = ~0ull;
+    int rows = 0, m = 0, kcur = 0;         // rows scored, clusters open, entries of the list in s.wval / s.wid
+    LseAcc run;
+    run.m = -INFINITY;
+    run.s = 0.f;
+    while (true) {
+        // ---- both tests on the open prefix (m = 0: nothing scored, only "no cluster at all" certifies)
+        float nxtU, T;
+        tail_stats(a, L, kappa, s, nxtU, T);
+        __syncthreads();
+        const float Z = lse_value(run);
+        const float theta = (a.use_k && kcur >= a.k) ? s.wval[a.k - 1] : -INFINITY;
+        const bool none_left = nxtU == -INFINITY;
+        const bool tk = none_left || (kcur >= a.k && nxtU < theta);
+        const bool sm = none_left || (rows > 0 && T - Z <= a.lam);
+        const bool tk_ok = a.use_k ? tk : (a.combine == CSV_COMBINE_ALL);
+        const bool sm_ok = a.use_s ? sm : (a.combine == CSV_COMBINE_ALL);
+        const bool ok = a.combine == CSV_COMBINE_ALL ? (tk_ok && sm_ok) : (tk_ok || sm_ok);
+        if (ok) {
+            for (int t = tid; t < a.k; t += nt) {
+                a.out.d_ids[(size_t)b * a.k + t] = t < kcur ? s.wid[t] : -1;
+                a.out.d_logits[(size_t)b * a.k + t] = t < kcur ? s.wval[t] : -INFINITY;
+            }
+            if (a.use_k) write_distribution(a, b, kcur, Z, s);
+            if (tid == 0) {
+                a.out.d_lse[b] = Z;
+                a.out.d_flags[b] = ((tk && a.use_k) ? CSV_FLAG_TOPK_CERT : 0u) | ((sm && a.use_s) ? CSV_FLAG_SOFTMAX_CERT : 0u);
+                a.out.d_n_rows[b] = rows;
+                a.out.d_n_clusters[b] = m;
+                if (a.out.d_rounds) a.out.d_rounds[b] = m;
+                a.st[b].status = ST_DONE;
+            }
+            if (a.out.d_sel_clusters)
+                for (int j = tid; j < m; j += nt)       // written by thread 0 of this block: read past the first-level cache
+                    a.out.d_sel_clusters[(size_t)b * C + j] = __hip_atomic_load(&a.sel[(size_t)b * C + j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            return;
+        }
+        // ---- open the next cluster of the bound order; the budget is tested before its rows are scored
+        u64 best = 0;
+        for (int c = tid; c < C; c += nt) {
+            const u64 kx = L.keys[c];
+            if (kx < kappa && kx > best) best = kx;
+        }
+        best = block_max_u64(best, s.redu);
+        const int cw = (int)(0xFFFFFFFFu - (uint32_t)best);       // best != 0: some cluster is unopened, or the tests had held
+        const int r0 = L.offl[cw], nc = L.offl[cw + 1] - r0;
+        if (rows + nc > a.K_max) {
+            if (tid == 0) {
+                a.st[b].n_open = m + 1;
+                a.st[b].n_rows = rows + nc;
+                push_fallback(a, b, m + 1);
+            }
+            return;
+        }
+        if (tid == 0) a.sel[(size_t)b * C + m] = cw;
+        kappa = best;
+        m += 1;
+        for (int p0 = 0; p0 < nc; p0 += ALG1_PIECE) {
+            const int P = min(ALG1_PIECE, nc - p0);
+            __syncthreads();                                  // the staging area is free
+            for (int p = wave; p < P; p += nt >> 6) {
+                const int r = r0 + p0 + p;
+                const uint4* w = reinterpret_cast<const uint4*>(a.Wp + (size_t)r * a.d);
+                float acc = 0.f;
+                for (int i = lane; i < nch; i += 64) acc = dot8_bf16(w[i], hs4[i], acc);
+                acc = wave_sum(acc);
+                if (lane == 0) {
+                    sv[p] = acc + a.bp[r];
+                    si[p] = a.perm[r];
+                }
+            }
+            __syncthreads();
+            // log-sum-exp of the piece joins the running one; the list joins the piece and the top k of both is the new list
+            const LseAcc lp = block_lse(P, val, s);
+            run = lse_combine(run, lp);
+            __syncthreads();
+            for (int t = tid; t < kcur; t += nt) {
+                sv[P + t] = s.wval[t];
+                si[P + t] = s.wid[t];
+            }
+            const int ntot = P + kcur;
+            if (tid < 4 && ntot + tid < STAGE_CAP) sv[ntot + tid] = -INFINITY;
+            __syncthreads();
+            if (a.use_k) {
+                const int knew = min(a.k, ntot);
+                bool done = false;
+                if (ntot <= RANK_DIRECT) {
+                    float v;
+                    rank_small(sv, si, ntot, knew, s, v);
+                    done = true;
+                } else {
+                    int kk = 0;
+                    float vmax;
+                    done = threshold_topk(ntot, a.k, kcur >= a.k ? s.wval[a.k - 1] : -INFINITY, false, idf, s, kk, vmax);
+                }
+                __syncthreads();
+                if (!done) block_topk(ntot, a.k, val, idf, s);
+                kcur = knew;
+            }
+            rows += P;
+        }
+        __syncthreads();
+    }
+}
+
 // ================================================================================================ full-vocabulary product
 struct FullArgs {
     int V, d;
@@ -2603,7 +2736,7 @@ static int check_pair(const csv_workspace* ws, const csv_index* idx, const void*
 
 // The dynamic-LDS limit of a kernel is one attribute per process and device, shared by every workspace: it is only
 // ever raised, so a workspace created later with smaller needs cannot take away what an earlier one's launches rely on.
-enum { K_ROUND0, K_STEP, K_TAIL, K_RCERT, K_FBPROD, K_FBPRODM, K_FULLMFMA, K_BOUND0, K_NKERN = K_BOUND0 + 8 };
+enum { K_ROUND0, K_STEP, K_TAIL, K_RCERT, K_FBPROD, K_FBPRODM, K_FULLMFMA, K_ALG1, K_BOUND0, K_NKERN = K_BOUND0 + 8 };
 static size_t g_lds_limit[CSV_STATIC_MAX_DEVICES][K_NKERN];
 static pthread_mutex_t g_attr_lock = PTHREAD_MUTEX_INITIALIZER;
 #define CSV_STATIC_LDS_MAX 16384     // at least the static shared memory of any kernel here
@@ -2967,6 +3100,37 @@ extern "C" int csv_decode_step(csv_workspace* ws, const csv_index* idx, const ui
     FullArgs f;
     f.V = idx->V; f.d = idx->d; f.Wp = idx->Wp; f.bp = idx->bp; f.perm = idx->perm; f.h = d_h;
     f.list = ws->fb_list; f.n_ptr = nullptr; f.n_fixed = 0; f.out = ws->fb_logits; f.out_stride = idx->V; f.scatter = 0;
+    if (p->schedule == CSV_SCHEDULE_ALG1) {
+        // Algorithm 1's own order: one block per sequence opens one cluster per iteration; then the fallback launches
+        const size_t general = (size_t)ws->Npad * 8 + (size_t)ws->C * 8 + 8;
+        const size_t h_off = (ALG1_CL_OFF + general + 15) / 16 * 16;
+        const size_t lds = h_off + (size_t)idx->d * 2;
+        if (lds + sizeof(SeqShared) + 256 > 160u * 1024u) {
+            csv_set_error("schedule=ALG1: C=%d, d=%d need %zu bytes of LDS per block, more than a compute unit has", idx->C, idx->d, lds);
+            return CSV_ESHAPE;
+        }
+        if (p->max_rounds > 2 || p->delta_clusters != 0 || p->relax) {
+            csv_set_error("schedule=ALG1 has no fallback levels (max_rounds, delta_clusters, relax must be 0)");
+            return CSV_EINVAL;
+        }
+        CSV_HIP(raise_lds(ws->device, K_ALG1, (const void*)alg1_kernel, lds));
+        alg1_kernel<<<B, SEQ_THREADS, lds, st>>>(a, (int)(h_off / 16));
+        CSV_LAUNCH_CHECK("alg1_kernel");
+        CSV_MARK(2);
+        fb_product_kernel<<<ws->tail_grid, TAIL_THREADS, (size_t)FULL_G * idx->d * 2, st>>>(a, f);
+        CSV_LAUNCH_CHECK("fb_product_kernel");
+        if (B > FULL_G) {
+            fb_product_mfma_kernel<<<ws->tail_grid, MFMA_THREADS, MFMA_LDS, st>>>(a, f);
+            CSV_LAUNCH_CHECK("fb_product_mfma_kernel");
+        }
+        fb_topk_kernel<<<dim3(ws->n_chunks, B), SEQ_THREADS, (size_t)CAND_OFF + CAND_BYTES, st>>>(a);
+        CSV_LAUNCH_CHECK("fb_topk_kernel");
+        fb_final_kernel<<<B, SEQ_THREADS, (size_t)CAND_OFF + CAND_BYTES, st>>>(a);
+        CSV_LAUNCH_CHECK("fb_final_kernel");
+        CSV_MARK(3);
+        return CSV_OK;
+    }
+    if (p->schedule != CSV_SCHEDULE_ROUNDS) { csv_set_error("bad schedule=%d", p->schedule); return CSV_EINVAL; }
     // One launch per phase pays when the tail is needed (kernel boundaries instead of grid barriers: 30 % of a
     // step even at B = 1), the single kernel when it is not (one launch that returns at once instead of seven).
     // Unless the caller fixed the choice, follow the recent steps: the bound kernel keeps a bit per step in a

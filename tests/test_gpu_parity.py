@@ -245,6 +245,83 @@ def test_two_live_workspaces_with_different_lds_needs():
     c_big.close()
 
 
+def _alg1_margin(oidx, U_row, L_row, m, k, eps):
+    """Smallest distance of either test from its threshold at the first m clusters of the bound order."""
+    order = O.cluster_order(U_row)
+    order = order[oidx.n[order] > 0]
+    tk, sm, theta, Z = O.prefix_certificates(oidx, U_row, L_row, order[:m], k, eps)
+    rest = order[m:]
+    if rest.size == 0 or m == 0:
+        return np.inf
+    out = []
+    if k >= 1 and np.isfinite(theta):
+        out.append(abs(theta - U_row[rest].max()))
+    if eps > 0:
+        out.append(abs(O._lam(eps) - (O.logsumexp(np.log(oidx.n[rest].astype(np.float64)) + U_row[rest]) - Z)))
+    return min(out) if out else np.inf
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("combine,k,eps,V,C,K_max", [(O.COMBINE_ANY, 5, 1e-3, 9000, 60, 3000), (O.COMBINE_ALL, 20, 1e-4, 9000, 60, 3000),
+                                                     (O.COMBINE_ANY, 0, 1e-3, 9000, 60, 3000), (O.COMBINE_ALL, 300, 1e-3, 9000, 60, 3000),
+                                                     (O.COMBINE_ALL, 40, 1e-3, 24000, 12, 20000)])
+def test_algorithm1_order_opens_the_shortest_certifying_prefix(combine, k, eps, V, C, K_max):
+    # schedule = ALG1: one cluster per iteration, tests after every opening (Algorithm 1): the opened prefix, the flags,
+    # the fallback decisions and the list are the oracle's prefix scan.  The last case has clusters of several
+    # thousand rows (scored in pieces).
+    import paper_2511_21702_amd as csv
+    r = synth.small_recipe(f"alg1-{k}", V=V, d=136, C=C, B=6, steps=3, sizes="zipf", h_mode="mix", iso_frac=0.25, k=k, eps=eps)
+    case = Case(r, seed=81, K_cap=K_max)
+    h = case.hidden()
+    buf = csv.make_step_buffers(case.gidx, r.B, k, eps, K_max, combine, want_sel=True, schedule=csv.SCHEDULE_ALG1)
+    dh = csv.bits_to_device(h)
+    n_cmp = n_band = n_fb = 0
+    for st in range(h.shape[0]):
+        csv.csv_decode_step(case.ws, case.gidx, dh[st], buf)
+        torch.cuda.synchronize()
+        g = PAR.gpu_step_to_numpy(buf)
+        h64 = O.bf16_to_f64(h[st])
+        Lall = O.full_logits(case.W64, case.b, h64)
+        Uall = O.cluster_bounds(case.oidx, h64)[0]
+        for b in range(r.B):
+            orc = O.alg1_step(case.oidx, Uall[b], Lall[b], k, eps, K_max, combine)
+            gfb = bool(g["flags"][b] & csv.FLAG_FALLBACK)
+            mg = int(g["rounds"][b]) if not gfb else None
+            same = gfb == orc["fallback"] and (gfb or (mg == orc["opened"]))
+            if not same:
+                ms = [m for m in (orc["opened"], mg) if m is not None]
+                marg = min(_alg1_margin(case.oidx, Uall[b], Lall[b], m, k, eps) for m in range(1, max(ms) + 1))
+                assert marg < 1e-4 * max(1.0, float(np.abs(Lall[b]).max())), (st, b, orc, g["flags"][b], mg, marg)
+                n_band += 1
+                continue
+            n_cmp += 1
+            if gfb:
+                n_fb += 1
+                exp_ids, exp_vals = O.topk_bruteforce(Lall[b], k) if k else (np.empty(0, int), np.empty(0))
+                assert np.isclose(g["lse"][b], O.logsumexp(Lall[b]), rtol=2e-6)
+            else:
+                m = orc["opened"]
+                assert np.array_equal(g["sel"][b, :m], orc["clusters"]) and g["n_clusters"][b] == m
+                assert g["n_rows"][b] == orc["n_rows"]
+                assert bool(g["flags"][b] & csv.FLAG_TOPK_CERT) == (orc["topk_cert"] and k >= 1)
+                assert bool(g["flags"][b] & csv.FLAG_SOFTMAX_CERT) == (orc["soft_cert"] and eps > 0)
+                rows = np.concatenate([case.oidx.rows(c) for c in orc["clusters"]]) if m else np.empty(0, np.int64)
+                kk = min(k, rows.size)
+                exp_ids, exp_vals = O.topk_bruteforce(Lall[b][rows], kk, rows) if kk else (np.empty(0, int), np.empty(0))
+                assert np.isclose(g["lse"][b], orc["Z"], rtol=2e-6, atol=1e-6)
+                if k:
+                    assert (g["ids"][b, kk:] == -1).all() and np.isneginf(g["logits"][b, kk:]).all()
+            kk = len(exp_ids)
+            if kk:
+                assert np.allclose(g["logits"][b, :kk], exp_vals, rtol=2e-5, atol=1e-6)
+                swapped = g["ids"][b, :kk] != exp_ids
+                # ids may differ only where neighbouring logits are closer than float32 resolves
+                assert np.allclose(Lall[b][g["ids"][b, :kk][swapped]], exp_vals[swapped], rtol=2e-5, atol=1e-6)
+    log(f"[alg1 k={k} eps={eps:g} combine={combine}] compared {n_cmp} sequences ({n_fb} fallbacks), {n_band} within the tie band")
+    assert n_band <= 1 and n_cmp >= 15
+    case.close()
+
+
 def test_step_single_cluster_and_singletons():
     r = synth.small_recipe("C1", V=700, d=64, C=1, B=2, steps=2)
     case = Case(r, seed=14, K_cap=700)
@@ -396,6 +473,9 @@ def test_workspace_for_the_largest_shape_fits():
     # every logit is 0 and every bound is R ||h|| = 1 > 0: no certificate can hold before all rows are open
     assert (buf.flags.cpu().numpy() & csv.FLAG_INVALID_INPUT == 0).all()
     assert np.allclose(buf.lse.cpu().numpy(), math.log(V), rtol=1e-6)
+    with pytest.raises(csv.CsvError) as e:            # the one-block-per-sequence mode cannot hold this much cluster data in LDS
+        csv.csv_decode_step(ws, idx, h, csv.make_step_buffers(idx, 2, 4, 1e-3, V, schedule=csv.SCHEDULE_ALG1))
+    assert e.value.code == -4
     ws.free(); idx.free()
 
 
@@ -507,6 +587,9 @@ def test_argument_errors():
             csv.csv_decode_step(case.ws, case.gidx, dh, csv.make_step_buffers(case.gidx, 2, 5, 1e-3, 10, **bad))
     with pytest.raises(csv.CsvError):
         csv.CsvWorkspace(case.gidx, 1000, 10)                                                              # B_max too large
+    for bad in (dict(schedule=2), dict(schedule=csv.SCHEDULE_ALG1, max_rounds=3), dict(schedule=csv.SCHEDULE_ALG1, relax=True)):
+        with pytest.raises(csv.CsvError):
+            csv.csv_decode_step(case.ws, case.gidx, dh, csv.make_step_buffers(case.gidx, 2, 5, 1e-3, 10, **bad))
     case.close()
 
 
