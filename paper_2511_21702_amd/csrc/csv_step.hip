@@ -182,7 +182,7 @@ __device__ __forceinline__ float mu_fma(const uint4& m, HP hrow, int unit, float
 #define BOUND_THREADS 512
 #define BOUND_LDS_MAX (128 * 1024)   // h of up to 8 sequences of d = 8192 in LDS: one block serves all 8, the centroids are read once
 #define BOUND_HREG 8       // 128-bit pieces of h per thread: 8 x 512 x 16 B covers the 64 KB that BT sequences may take in LDS
-// 2..4 sequences (up to 8 supported): h of the block's BT sequences is staged in LDS once, then every wave walks over whole clusters
+// 2..4 sequences: h of the block's BT sequences is staged in LDS once, then every wave walks over whole clusters
 // (cluster = wave index among all waves of the grid, then + their number, ...): a centroid row goes through the wave
 // in chunks of BOUND_PFB 128-bit loads per lane, the next chunk (of this or of the wave's next cluster) always
 // requested before the current one is used, and nothing in the loop waits for another wave.  With more clusters
@@ -2789,7 +2789,7 @@ static int launch_bounds_kernel(const StepArgs& a, float* U, float* hn, int rese
         return CSV_OK;
     }
     int bt = 1;
-    while (bt < a.B && bt < 8) bt <<= 1;
+    while (bt < a.B && bt < 4) bt <<= 1;       // B <= 4 here (more sequences take the MFMA product)
     while (bt > 1 && (size_t)bt * a.d * 2 > BOUND_LDS_MAX) bt >>= 1;
     const bool m16 = a.mu16 != nullptr;
     const size_t lds = (size_t)bt * a.d * 2;
@@ -2819,7 +2819,6 @@ static int launch_bounds_kernel(const StepArgs& a, float* U, float* hn, int rese
         switch (bt) {
             case 2: fn = m16 ? (const void*)bound_kernel<2, true> : (const void*)bound_kernel<2, false>; break;
             case 4: fn = m16 ? (const void*)bound_kernel<4, true> : (const void*)bound_kernel<4, false>; break;
-            case 8: fn = m16 ? (const void*)bound_kernel<8, true> : (const void*)bound_kernel<8, false>; break;
             default: fn = m16 ? (const void*)bound_kernel<1, true> : (const void*)bound_kernel<1, false>; break;
         }
         const int slot = K_BOUND0 + (bt == 1 ? 0 : bt == 2 ? 1 : bt == 4 ? 2 : 3) * 2 + (m16 ? 1 : 0);
@@ -2831,10 +2830,9 @@ static int launch_bounds_kernel(const StepArgs& a, float* U, float* hn, int rese
         else bound_kernel<BT, false><<<grid, BOUND_THREADS, lds, st>>>(a, U, hn, reset);       \
     } while (0)
     switch (bt) {
-        case 1: CSV_BOUND_LAUNCH(1); break;        // 2..8 sequences of rows too long for two of them in LDS
+        case 1: CSV_BOUND_LAUNCH(1); break;        // 2..4 sequences of rows too long for two of them in LDS
         case 2: CSV_BOUND_LAUNCH(2); break;
-        case 4: CSV_BOUND_LAUNCH(4); break;
-        default: CSV_BOUND_LAUNCH(8); break;
+        default: CSV_BOUND_LAUNCH(4); break;
     }
 #undef CSV_BOUND_LAUNCH
     CSV_LAUNCH_CHECK("bound_kernel");
