@@ -2118,15 +2118,31 @@ __global__ __launch_bounds__(SEQ_THREADS) void alg1_kernel(StepArgs a, int h_off
         for (int p0 = 0; p0 < nc; p0 += ALG1_PIECE) {
             const int P = min(ALG1_PIECE, nc - p0);
             __syncthreads();                                  // the staging area is free
-            for (int p = wave; p < P; p += nt >> 6) {
-                const int r = r0 + p0 + p;
-                const uint4* w = reinterpret_cast<const uint4*>(a.Wp + (size_t)r * a.d);
-                float acc = 0.f;
-                for (int i = lane; i < nch; i += 64) acc = dot8_bf16(w[i], hs4[i], acc);
-                acc = wave_sum(acc);
-                if (lane == 0) {
-                    sv[p] = acc + a.bp[r];
-                    si[p] = a.perm[r];
+            // two rows per wave at a time, a whole row (up to TILE_PF pieces per lane) requested before anything is added up
+            for (int p = 2 * wave; p < P; p += 2 * (nt >> 6)) {
+                uint4 pf[2][TILE_PF];
+                const uint4* w[2];
+#pragma unroll
+                for (int q = 0; q < 2; ++q) {
+                    w[q] = reinterpret_cast<const uint4*>(a.Wp + (size_t)(r0 + p0 + min(p + q, P - 1)) * a.d);
+#pragma unroll
+                    for (int j = 0; j < TILE_PF; ++j) pf[q][j] = w[q][min(lane + 64 * j, nch - 1)];
+                }
+#pragma unroll
+                for (int q = 0; q < 2; ++q) {
+                    float acc = 0.f;
+#pragma unroll
+                    for (int j = 0; j < TILE_PF; ++j) {
+                        const int i = lane + 64 * j;
+                        if (i < nch) acc = dot8_bf16(pf[q][j], hs4[i], acc);
+                    }
+                    for (int i = lane + 64 * TILE_PF; i < nch; i += 64) acc = dot8_bf16(w[q][i], hs4[i], acc);
+                    acc = wave_sum(acc);
+                    if (lane == 0 && p + q < P) {
+                        const int r = r0 + p0 + p + q;
+                        sv[p + q] = acc + a.bp[r];
+                        si[p + q] = a.perm[r];
+                    }
                 }
             }
             __syncthreads();
