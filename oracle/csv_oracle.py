@@ -22,9 +22,18 @@ Pins (tests/test_oracle_*.py):
   topk certificate   Theorem 1 against brute force; minimal prefix = {U_c >= true k-th logit}
   eps certificate    proof identity TV = R/(Z_S+R) (Theorem 2), cluster-wise tail <= loose tail
   alg1_step          brute-force enumeration of all prefixes on small C (certificates written out on sets, linear domain)
-  csv2r_step         contains Algorithm 1's minimal prefix; monotone thresholds; budget extremes
-Parity unpinned: the choices K_max = V/4, radius slack 2^-14, tie tolerance, and the
-default of requiring both certificates are readings of this build, not values the paper fixes.
+  csv2r_step         contains Algorithm 1's minimal prefix; monotone thresholds; budget extremes; the softmax prefix of
+                     round 1 traced by hand; equal bounds open the smaller cluster id first
+  fallback levels    two hand-traced one-dimensional examples (a rescue by one more cluster, an acceptance between eps
+                     and 2 eps); Theorems 1 and 2 by brute force over V; levels only ever remove fallbacks
+  kmax_update        the printed expression evaluated by hand; a closed loop with a monotone rate model
+  nucleus_holds      agrees with the step's flag and with brute-force coverage over V
+  certified_distribution   brackets the true probabilities over V; running sums and nucleus length against their definitions
+  lloyd_kmeans       planted clusters recovered; assignment is the nearest centroid with ties to the smaller id
+  centroid_bf16      the bound stays sound with rounded centroids and costs little
+Parity unpinned: the choices K_max = V/4, radius slack 2^-14 and the angular slacks, the tie tolerance, the default of
+requiring both certificates, the order and triggers of the fallback levels, the sign of the budget update, which tokens
+get their own bias-table entry and the seeding rule are readings of this build, not values the paper fixes.
 """
 from __future__ import annotations
 
