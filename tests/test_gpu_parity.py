@@ -261,18 +261,8 @@ def _alg1_margin(oidx, U_row, L_row, m, k, eps):
     return min(out) if out else np.inf
 
 
-@pytest.mark.gpu
-@pytest.mark.parametrize("combine,k,eps,V,C,K_max", [(O.COMBINE_ANY, 5, 1e-3, 9000, 60, 3000), (O.COMBINE_ALL, 20, 1e-4, 9000, 60, 3000),
-                                                     (O.COMBINE_ANY, 0, 1e-3, 9000, 60, 3000), (O.COMBINE_ALL, 300, 1e-3, 9000, 60, 3000),
-                                                     (O.COMBINE_ALL, 40, 1e-3, 24000, 12, 20000)])
-def test_algorithm1_order_opens_the_shortest_certifying_prefix(combine, k, eps, V, C, K_max):
-    # schedule = ALG1: one cluster per iteration, tests after every opening (Algorithm 1): the opened prefix, the flags,
-    # the fallback decisions and the list are the oracle's prefix scan.  The last case has clusters of several
-    # thousand rows (scored in pieces).
+def _alg1_compare(case, r, h, k, eps, K_max, combine):
     import paper_2511_21702_amd as csv
-    r = synth.small_recipe(f"alg1-{k}", V=V, d=136, C=C, B=6, steps=3, sizes="zipf", h_mode="mix", iso_frac=0.25, k=k, eps=eps)
-    case = Case(r, seed=81, K_cap=K_max)
-    h = case.hidden()
     buf = csv.make_step_buffers(case.gidx, r.B, k, eps, K_max, combine, want_sel=True, schedule=csv.SCHEDULE_ALG1)
     dh = csv.bits_to_device(h)
     n_cmp = n_band = n_fb = 0
@@ -301,7 +291,15 @@ def test_algorithm1_order_opens_the_shortest_certifying_prefix(combine, k, eps, 
                 assert np.isclose(g["lse"][b], O.logsumexp(Lall[b]), rtol=2e-6)
             else:
                 m = orc["opened"]
-                assert np.array_equal(g["sel"][b, :m], orc["clusters"]) and g["n_clusters"][b] == m
+                assert g["n_clusters"][b] == m
+                if not np.array_equal(g["sel"][b, :m], orc["clusters"]):
+                    # the same number of clusters in a different order or with a different last one: only clusters whose
+                    # bounds float32 cannot tell apart may trade places
+                    ug, uo = Uall[b][g["sel"][b, :m]], Uall[b][orc["clusters"]]
+                    assert np.all(np.abs(ug - uo) <= 1e-5 * np.maximum(1.0, np.abs(uo))), (st, b, g["sel"][b, :m], orc["clusters"])
+                    n_band += 1
+                    n_cmp -= 1
+                    continue
                 assert g["n_rows"][b] == orc["n_rows"]
                 assert bool(g["flags"][b] & csv.FLAG_TOPK_CERT) == (orc["topk_cert"] and k >= 1)
                 assert bool(g["flags"][b] & csv.FLAG_SOFTMAX_CERT) == (orc["soft_cert"] and eps > 0)
@@ -318,6 +316,23 @@ def test_algorithm1_order_opens_the_shortest_certifying_prefix(combine, k, eps, 
                 # ids may differ only where neighbouring logits are closer than float32 resolves
                 assert np.allclose(Lall[b][g["ids"][b, :kk][swapped]], exp_vals[swapped], rtol=2e-5, atol=1e-6)
     log(f"[alg1 k={k} eps={eps:g} combine={combine}] compared {n_cmp} sequences ({n_fb} fallbacks), {n_band} within the tie band")
+    return n_cmp, n_band
+
+
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("combine,k,eps,V,C,K_max", [(O.COMBINE_ANY, 5, 1e-3, 9000, 60, 3000), (O.COMBINE_ALL, 20, 1e-4, 9000, 60, 3000),
+                                                     (O.COMBINE_ANY, 0, 1e-3, 9000, 60, 3000), (O.COMBINE_ALL, 300, 1e-3, 9000, 60, 3000),
+                                                     (O.COMBINE_ALL, 40, 1e-3, 24000, 12, 20000)])
+def test_algorithm1_order_opens_the_shortest_certifying_prefix(combine, k, eps, V, C, K_max):
+    # schedule = ALG1: one cluster per iteration, tests after every opening (Algorithm 1): the opened prefix, the flags,
+    # the fallback decisions and the list are the oracle's prefix scan.  The last case has clusters of several
+    # thousand rows (scored in pieces).
+    r = synth.small_recipe(f"alg1-{k}", V=V, d=136, C=C, B=6, steps=3, sizes="zipf", h_mode="mix", iso_frac=0.25, k=k, eps=eps)
+    case = Case(r, seed=81, K_cap=K_max)
+    h = case.hidden()
+    n_cmp, n_band = _alg1_compare(case, r, h, k, eps, K_max, combine)
     assert n_band <= 1 and n_cmp >= 15
     case.close()
 
