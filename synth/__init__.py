@@ -162,7 +162,7 @@ def make_hidden(r: Recipe, centers: np.ndarray, steps: int | None = None, seed: 
         mix = _rng(seed, _S_HMIX)
         a = np.empty((n, d))
         for i in range(n):
-            m = int(pick.integers(1, 4))
+            m = min(int(pick.integers(1, 4)), C)          # at most as many distinct centres as there are
             ids = pick.choice(C, size=m, replace=False)
             w = mix.dirichlet(np.full(m, 0.5))
             v = (w[:, None] * chat[ids]).sum(0)

@@ -356,7 +356,7 @@ def test_step_seeded_random_shapes_and_parameters():
     # many small cases with ragged shapes (V, d, C, B not multiples of any tile) and every parameter varied
     rng = np.random.default_rng(2024)
     total = PAR.Tally()
-    for case_id in range(36):
+    for case_id in range(48):
         V = int(rng.integers(300, 5000))
         d = 8 * int(rng.integers(1, 80))
         C = int(rng.integers(1, min(V, 200)))
@@ -371,7 +371,9 @@ def test_step_seeded_random_shapes_and_parameters():
                                sizes=str(rng.choice(["equal", "zipf"])), h_mode=str(rng.choice(["single", "mix"])),
                                iso_frac=float(rng.choice([0.0, 0.3])), row_noise=float(rng.choice([0.05, 0.5, 2.0])), zipf_min=1)
         tag = f"rnd{case_id} V={V} d={d} C={C} B={B} k={k} eps={eps:g} comb={comb} K={K_max} {lad}"
-        case = Case(r, seed=100 + case_id, K_cap=V, bias=bool(rng.integers(0, 2)), centroid_bf16=bool(rng.integers(0, 2)))
+        mode = int(rng.integers(0, 4))     # the index as built by default, with bf16 centroids, with a bias table, angular
+        kw = dict(centroid_bf16=True) if mode == 1 else dict(bias_table_m=int(rng.choice([2, 3, 8]))) if mode == 2 else dict(angular=True) if mode == 3 else {}
+        case = Case(r, seed=100 + case_id, K_cap=V, bias=bool(rng.integers(0, 2)) or mode == 2, **kw)
         if rng.integers(0, 2):
             case.ws.set_tail_split(1 if B < 5 else 1000)       # the tail mode the batch size would not pick
         t = case.run_steps(case.hidden(), k, eps, K_max, comb, tag, tally=total, **lad)
