@@ -1306,6 +1306,63 @@ __device__ __forceinline__ float rank_small(const float* V, const int* I, int le
     return vmax;
 }
 
+// Ordered top-kk of m <= blockDim.x candidates V / I in LDS (one per thread), none of them below lo: a counting
+// sort into 256 equal-width buckets between lo and hi, largest values first, then every candidate whose bucket starts within the first
+// kk places ranks itself against the members of its bucket (equal values by id); values above hi share the first bucket.  Exact for any distribution of the
+// values (a crowded bucket only costs time); the comparisons of rank_small grow with m * m, these with m.  V / I are
+// reordered (bucket by bucket; the order inside a bucket depends on timing, the ranks do not).  The caller's next
+// barrier publishes s.wval / s.wid.  Uses s.hist, s.rank, s.redi.
+__device__ __forceinline__ void rank_buckets(float* V, int* I, int m, int kk, float lo, float hi, SeqShared& s) {
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const float scale = (hi > lo && lo > -INFINITY && hi < INFINITY) ? 255.f / (hi - lo) : 0.f;
+    float v = 0.f;
+    int id = 0, d = 0;
+    if (tid < m) {
+        v = V[tid];
+        id = I[tid];
+        d = scale > 0.f ? 255 - min(255, max(0, (int)((v - lo) * scale))) : 0;
+    }
+    if (tid < 256) s.hist[tid] = 0;
+    __syncthreads();
+    unsigned slot = 0;
+    if (tid < m) slot = atomicAdd(&s.hist[d], 1u);
+    __syncthreads();
+    if (tid < 256) {
+        const int c = (int)s.hist[tid];
+        int x = c;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int y = __shfl_up(x, o, CSV_WAVE);
+            if (lane >= o) x += y;
+        }
+        if (lane == 63) s.redi[w] = x;
+        s.rank[tid] = x - c;                                // first place of the bucket, counted within its wave of buckets
+    }
+    __syncthreads();
+    int start = 0, cnt = 0;
+    if (tid < m) {
+        start = s.rank[d];
+        for (int i = 0; i < (d >> 6); ++i) start += s.redi[i];
+        cnt = (int)s.hist[d];
+        V[start + (int)slot] = v;
+        I[start + (int)slot] = id;
+    }
+    __syncthreads();
+    if (tid < m && start < kk) {
+        int r = start;
+#pragma unroll 4
+        for (int j = start; j < start + cnt; ++j) {
+            const float x = V[j];
+            r += (x > v || (x == v && I[j] < id)) ? 1 : 0;
+        }
+        if (r < kk) {
+            s.wval[r] = v;
+            s.wid[r] = id;
+        }
+    }
+}
+#define RANK_BUCKETS_MIN 128     // more candidates than this (with a finite range) take rank_buckets instead of rank_small
+
 // Ordered top-k of len > RANK_DIRECT values staged at the start of the dynamic LDS (ranking all of them against each
 // other costs len^2 comparisons: 10 us at 512).  Everything below a threshold that k of the values are known to reach
 // is out; the values at or above it (usually few more than k) are collected behind the staged data and ranked in one
@@ -1314,26 +1371,29 @@ __device__ __forceinline__ float rank_small(const float* V, const int* I, int le
 // and fewer than k of them may reach theta (the merged lists still hold the overall top-k).  The collected order
 // depends on timing, the ranking does not.  On success s.wval / s.wid hold kkv entries once the caller has passed a
 // barrier, vmax is the largest value; on failure (k > RANK_DIRECT, too many survivors) nothing is decided.
-template <class IdFn>
+// MERGE: the values are lists of several chunks, unused places marked by the id 0x7fffffff (and the value -inf): those are
+// left out, and the first attempt also runs without a threshold (len may then be RANK_DIRECT or less).
+template <bool MERGE = false, class IdFn>
 __device__ __forceinline__ bool threshold_topk(int len, int k, float theta, bool short_ok, IdFn idf, SeqShared& s, int& kkv, float& vmax) {
     extern __shared__ u64 arena[];
     const int tid = threadIdx.x, nt = blockDim.x, lane = tid & 63;
     const float* V = reinterpret_cast<const float*>(arena);
     const int k0 = min(k, len);
     auto attempt = [&](float th) -> bool {
-        float* wmax = reinterpret_cast<float*>(s.hist);
+        float* wmax = reinterpret_cast<float*>(s.redu);        // not s.hist / s.redf: the ranking writes those while others still read here
         float* cval = reinterpret_cast<float*>(reinterpret_cast<char*>(arena) + CAND_OFF);
         int* cid = reinterpret_cast<int*>(cval + CAND_CAP + 4);
         if (tid < CAND_CAP) cval[tid] = -INFINITY;
         if (tid < 4) cval[CAND_CAP + tid] = -INFINITY;
         if (tid == 0) s.cnt = 0;
         __syncthreads();
-        float mx = -INFINITY;
+        float mx = -INFINITY, over = 0.f;                  // over: sum of (v - th) over the collected values
         for (int i0 = 0; i0 < len; i0 += nt) {
             const int i = i0 + tid;
             const float v = i < len ? V[i] : -INFINITY;
             mx = fmaxf(mx, v);
-            const bool in = i < len && v >= th;
+            const bool in = i < len && v >= th && (!MERGE || idf(i) != 0x7fffffff);
+            if (in) over += v - th;
             const unsigned long long bal = __ballot(in);
             if (bal) {
                 const int lead = __ffsll((long long)bal) - 1;
@@ -1348,20 +1408,32 @@ __device__ __forceinline__ bool threshold_topk(int len, int k, float theta, bool
             }
         }
         mx = wave_max(mx);
-        if (lane == 0) wmax[tid >> 6] = mx;
+        over = wave_sum(over);
+        if (lane == 0) {
+            wmax[tid >> 6] = mx;
+            wmax[16 + (tid >> 6)] = over;
+        }
         __syncthreads();
         const int m = (int)s.cnt;
         if (m > CAND_CAP || (!short_ok && m < k0)) return false;
         vmax = wmax[0];
         for (int q = 1; q < (nt >> 6); ++q) vmax = fmaxf(vmax, wmax[q]);
         kkv = min(k, m);
-        float v;
-        rank_small(cval, cid, m, kkv, s, v);
+        if (m > RANK_BUCKETS_MIN && th > -INFINITY) {
+            // the values thin out above the threshold: equal-width buckets up to eight times their mean excess hold a
+            // few values each, whatever lies beyond (a handful of outstanding logits) shares the first bucket
+            float tot = 0.f;
+            for (int q = 0; q < (nt >> 6); ++q) tot += wmax[16 + q];
+            rank_buckets(cval, cid, m, kkv, th, fminf(vmax, th + 8.f * tot / (float)m), s);
+        } else {
+            float v;
+            rank_small(cval, cid, m, kkv, s, v);
+        }
         return true;
     };
     bool ok = false;
-    if (theta > -INFINITY) ok = attempt(theta);
-    if (!ok && k <= RANK_DIRECT) {
+    if (MERGE || theta > -INFINITY) ok = attempt(theta);
+    if (!ok && k <= RANK_DIRECT && len > RANK_DIRECT) {
         // RANK_DIRECT group maxima (group g: the values i with i % RANK_DIRECT == g; len > RANK_DIRECT, so no group is
         // empty): k of them, hence k of the values, reach their k-th largest, and since the largest values mostly sit
         // in different groups few more do
@@ -1521,7 +1593,14 @@ __device__ __forceinline__ bool cert_body(const StepArgs& a, int b, int chunk, i
                 __syncthreads();
                 stage2_to_lds(reinterpret_cast<float*>(arena), cv, reinterpret_cast<int*>(arena) + STAGE_CAP, ci, nc);
                 __syncthreads();
-                block_topk(nc, a.k, val, idf, s);
+                bool merged = false;
+                if (THRESH) {
+                    int kq;
+                    float vm;
+                    merged = threshold_topk<true>(nc, a.k, st.theta, false, idf, s, kq, vm);
+                    __syncthreads();
+                }
+                if (!merged) block_topk(nc, a.k, val, idf, s);
             } else {
                 block_topk(nc, a.k, [&](int i) { return cv[i]; }, [&](int i) { return ci[i]; }, s);
             }

@@ -228,6 +228,26 @@ def test_step_later_rounds_rank_many_rows(k):
 
 
 @pytest.mark.gpu
+@pytest.mark.parametrize("k", [40, 200])
+def test_step_equal_logits_rank_by_token_id(k):
+    # rows repeated four times inside their cluster (same bias): every logit comes four times, so every selection and
+    # every merge of lists has to order equal values by token id and must neither drop nor repeat one
+    r = synth.small_recipe(f"ties{k}", V=24000, d=72, C=48, B=5, steps=3, h_mode="mix", iso_frac=0.2, k=k, eps=1e-5)
+    head = synth.make_head(r, seed=67, threads=16)
+    W, b, labels = head["W_bits"].copy(), head["b"].copy(), head["labels"]
+    for c in range(r.C):
+        rows = np.nonzero(labels == c)[0]
+        src = rows[(np.arange(len(rows)) // 4) * 4]
+        W[rows] = head["W_bits"][src]
+        b[rows] = head["b"][src]
+    case = Case(r, seed=67, K_cap=24000, W_bits=W, b=b)
+    t = case.run_steps(case.hidden(), k, r.eps, 20000, O.COMBINE_ALL, f"equal logits k={k}")
+    _finish(t, f"equal logits k={k}")
+    assert t.rows / t.n > 600, t.summary()
+    case.close()
+
+
+@pytest.mark.gpu
 def test_two_live_workspaces_with_different_lds_needs():
     # the per-kernel dynamic-LDS limit is process-wide: a later, smaller workspace must not lower what an earlier,
     # larger one (C = 4096: more than 64 KB of cluster data per block) still needs
