@@ -383,83 +383,114 @@ __device__ __forceinline__ void split3_bf16(const float4& x0, const float4& x1, 
     lo = make_uint4((l[0] >> 16) | l[1], (l[2] >> 16) | l[3], (l[4] >> 16) | l[5], (l[6] >> 16) | l[7]);
 }
 
-#define BOUND_KS_PER_BLOCK 8
+#define BOUND_TILES_PER_BLOCK 8   // waves of a block: each owns 16 clusters, all share the block's K slice (and its h in LDS)
 #define BOUND_MFMA_MIN_B 5       // from this many sequences on the MFMA product is faster than the vector kernel, whose reads of h
                                  // from LDS (eight sequences: 128 bytes per lane for 16 bytes of a centroid) bound it: 15 vs 23 us at B = 8
-#define BOUND_WAVE_TARGET 4096   // (cluster tiles x K slices) aimed at; 2048..8192 measured within 5 %
+#ifndef BOUND_BLOCK_TARGET
+#define BOUND_BLOCK_TARGET 256   // (groups of cluster tiles x K slices) aimed at: one block per compute unit (64..2048 swept)
+#endif
 #define BOUND_KS_MAX 32
-#define BOUND_KB_UNROLL 4        // k-blocks (of 32) whose loads are issued together (2, 4, 8 measured within 5 %)
+#ifndef BOUND_PIPE
+#define BOUND_PIPE 4             // k-blocks (of 32) a wave has requested ahead: 8 KB of float32 centroids
+#endif
+#define BOUND_LDS_KB 48          // most LDS for the h of one K slice (1 KB per k-block and 16 sequences)
+__device__ __forceinline__ uint4 keep_if(bool c, const uint4& v) {     // v or zero, component by component (no select between objects in memory)
+    return make_uint4(c ? v.x : 0u, c ? v.y : 0u, c ? v.z : 0u, c ? v.w : 0u);
+}
+__device__ __forceinline__ void lds_barrier() {      // all LDS accesses of the block's waves are done; global loads stay in flight
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// Grid (groups of 8 cluster tiles, K slices).  The block's slice of h goes to LDS once, in fragment order (1 KB per
+// k-block and sequence tile, read without bank conflicts), zero where the sequence, the k-block or k itself lies
+// outside: centroid values can then be read from clamped addresses without a select, which would be waited for right
+// behind the load.  Every wave has BOUND_PIPE k-blocks of its 16 centroid rows requested ahead; a register buffer is
+// requested again as soon as its values are split.  The last chunk is a copy of the loop body without requests, so
+// that the waits the compiler places are counted at compile time.
 template <int NT, bool MU16>
 __global__ __launch_bounds__(512) void bound_mfma_kernel(StepArgs a, float* __restrict__ P, int seq0, int KS, int kb_per_slice,
                                                          int reset_counters) {
+    extern __shared__ uint4 bound_lds[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int li = lane & 15, g = lane >> 4;
     if (reset_counters && blockIdx.x == 0 && blockIdx.y == 0)
         reset_step_counters(a.counters, a.B, 512, a.host_history, a.slots, a.B_max);
-    const int ks = blockIdx.y * BOUND_KS_PER_BLOCK + wave;
-    if (ks >= KS) return;
-    const int c0 = blockIdx.x * 16;
-    const float4* ap = reinterpret_cast<const float4*>(a.mu + (size_t)min(c0 + li, a.C - 1) * a.d);
-    const uint4* ap16 = reinterpret_cast<const uint4*>(a.mu16 + (size_t)min(c0 + li, a.C - 1) * a.d);   // used when MU16
-    const uint4* hp[NT];
-    bool hv[NT];
+    const int ks = blockIdx.y;
+    const int nkb = (a.d + 31) >> 5;
+    const int kb0 = ks * kb_per_slice, kb1 = min(nkb, kb0 + kb_per_slice);      // the host gives every slice at least one k-block
+    const int nchunk = (kb1 - kb0 + BOUND_PIPE - 1) / BOUND_PIPE;
+    const int c0 = (blockIdx.x * BOUND_TILES_PER_BLOCK + wave) * 16;            // past C: the wave computes a copy of the last rows and stores nothing
+    const size_t crow = (size_t)min(c0 + li, a.C - 1) * a.d;
+    const uint4* ap = MU16 ? reinterpret_cast<const uint4*>(a.mu16 + crow) : reinterpret_cast<const uint4*>(a.mu + crow);
+    uint4 X[BOUND_PIPE][MU16 ? 1 : 2];
+    auto load_x = [&](int u, int kb) {          // the lane's eight values of k-block kb, or (k past d) eight finite values that meet zeros
+        const int k = min(kb * 32 + g * 8, a.d - 8);
+        if constexpr (MU16) {
+            X[u][0] = ap[k >> 3];
+        } else {
+            X[u][0] = ap[k >> 2];
+            X[u][1] = ap[(k >> 2) + 1];
+        }
+    };
+    // h first (older loads are waited for first), then the centroid requests, which stay in flight across the staging
+    constexpr int HS = (BOUND_LDS_KB * 64 + 511) / 512;           // staged 128-bit pieces per thread at most
+    const int items = nchunk * BOUND_PIPE * NT * 64;
+    const uint4* hsrc = reinterpret_cast<const uint4*>(a.h);
+    uint4 hreg[HS];
+    bool hok[HS];
 #pragma unroll
-    for (int t = 0; t < NT; ++t) {
-        const int sq = seq0 + t * 16 + li;
-        hv[t] = sq < a.B;
-        hp[t] = reinterpret_cast<const uint4*>(a.h) + (size_t)(hv[t] ? sq : 0) * (a.d >> 3);
+    for (int q = 0; q < HS; ++q) {
+        const int it = tid + q * 512;
+        const int ln = it & 63, t = (it >> 6) % NT, kbl = (it >> 6) / NT;
+        const int sq = seq0 + t * 16 + (ln & 15), kb = kb0 + kbl, k = kb * 32 + (ln >> 4) * 8;
+        hok[q] = it < items && sq < a.B && kb < kb1 && k < a.d;
+        hreg[q] = make_uint4(0, 0, 0, 0);
+        if (it < items) hreg[q] = hsrc[(size_t)(hok[q] ? sq : 0) * (a.d >> 3) + (hok[q] ? k >> 3 : 0)];
     }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int u = 0; u < BOUND_PIPE; ++u) load_x(u, kb0 + u);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int q = 0; q < HS; ++q) {
+        const int it = tid + q * 512;
+        if (it < items) bound_lds[it] = keep_if(hok[q], hreg[q]);
+    }
+    lds_barrier();
     floatx4_t acc[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) acc[t] = floatx4_t{0.f, 0.f, 0.f, 0.f};
-    const int nkb = (a.d + 31) >> 5;
-    const int kb0 = ks * kb_per_slice, kb1 = min(nkb, kb0 + kb_per_slice);
-    const uint4 zero = make_uint4(0, 0, 0, 0);
-    const float4 fzero = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int kb = kb0; kb < kb1; kb += BOUND_KB_UNROLL) {
-        float4 x[BOUND_KB_UNROLL][2];
-        uint4 x16[BOUND_KB_UNROLL];
-        uint4 hb[BOUND_KB_UNROLL][NT];
+    auto chunk = [&](auto more_t, int c) {
+        constexpr bool more = decltype(more_t)::value;
 #pragma unroll
-        for (int u = 0; u < BOUND_KB_UNROLL; ++u) {
-            const int k = (kb + u) * 32 + g * 8;
-            const bool ok = kb + u < kb1 && k < a.d;       // d is a multiple of 8: the eight values are all in or all out
-            // unconditional 128-bit loads at a clamped address, then a select: a predicated load would be split up
-            const int kc = ok ? k : 0;
-            if constexpr (MU16) {
-                const uint4 v = ap16[kc >> 3];
-                x16[u] = ok ? v : zero;
-            } else {
-                const float4 v0 = ap[kc >> 2], v1 = ap[(kc >> 2) + 1];
-                x[u][0] = ok ? v0 : fzero;
-                x[u][1] = ok ? v1 : fzero;
-            }
-#pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                const uint4 hvv = hp[t][kc >> 3];
-                hb[u][t] = (ok && hv[t]) ? hvv : zero;
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < BOUND_KB_UNROLL; ++u) {
+        for (int u = 0; u < BOUND_PIPE; ++u) {
+            const uint4* hb = bound_lds + ((c * BOUND_PIPE + u) * NT << 6) + lane;
             if constexpr (MU16) {       // bf16 centroids feed the MFMA as they are
+                const bf16x8_t xv = __builtin_bit_cast(bf16x8_t, X[u][0]);
+                __builtin_amdgcn_sched_barrier(0);
+                if (more) load_x(u, kb0 + (c + 1) * BOUND_PIPE + u);
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int t = 0; t < NT; ++t)
-                    acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, hb[u][t]),
-                                                                     __builtin_bit_cast(bf16x8_t, x16[u]), acc[t], 0, 0, 0);
+                    acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, hb[t << 6]), xv, acc[t], 0, 0, 0);
             } else {
                 uint4 hi, mid, lo;
-                split3_bf16(x[u][0], x[u][1], hi, mid, lo);
+                split3_bf16(__builtin_bit_cast(float4, X[u][0]), __builtin_bit_cast(float4, X[u][1]), hi, mid, lo);
+                __builtin_amdgcn_sched_barrier(0);
+                if (more) load_x(u, kb0 + (c + 1) * BOUND_PIPE + u);
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int t = 0; t < NT; ++t) {
-                    const bf16x8_t bv = __builtin_bit_cast(bf16x8_t, hb[u][t]);
+                    const bf16x8_t bv = __builtin_bit_cast(bf16x8_t, hb[t << 6]);
                     acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bv, __builtin_bit_cast(bf16x8_t, hi), acc[t], 0, 0, 0);
                     acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bv, __builtin_bit_cast(bf16x8_t, mid), acc[t], 0, 0, 0);
                     acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bv, __builtin_bit_cast(bf16x8_t, lo), acc[t], 0, 0, 0);
                 }
             }
         }
-    }
+    };
+    for (int c = 0; c + 1 < nchunk; ++c) chunk(std::true_type{}, c);
+    chunk(std::false_type{}, nchunk - 1);
     // h is the first operand: accumulator register r of lane (li, g) is  [sequence 4g + r][cluster li], so the 16
     // lanes of a group store 64 contiguous bytes of one sequence's partial bounds
     const int c = c0 + li;
@@ -2361,13 +2392,6 @@ __global__ __launch_bounds__(256) void full_gemv_kernel(FullArgs f) {
 // out[sequence 4g + r][row li]: stores are 64-byte runs per sequence instead of 4-byte pieces 4V bytes apart.
 #define MFMA_THREADS 512
 #define MFMA_LDS (64 * 1024)        // two buffers of K blocks x 4 fragments x 1 KB x groups of 16 sequences: 4x1, 4x2 or 2x4
-__device__ __forceinline__ uint4 keep_if(bool c, const uint4& v) {     // v or zero, component by component (no select between objects in memory)
-    return make_uint4(c ? v.x : 0u, c ? v.y : 0u, c ? v.z : 0u, c ? v.w : 0u);
-}
-__device__ __forceinline__ void lds_barrier() {      // all LDS accesses of the block's waves are done; global loads stay in flight
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-}
-
 template <int NT, int TW, int MFMA_PIPE>
 __device__ __forceinline__ void full_mfma_device(const FullArgs& f, int n, int seq0, uint4* lds, int block, int nblocks) {
     constexpr int NW = MFMA_THREADS / 64;
@@ -2847,15 +2871,19 @@ static hipError_t raise_lds(int dev, int which, const void* fn, size_t bytes) {
     return e;
 }
 
-// K slices of the batched bound product and k-blocks (of 32) per slice: enough slices that (cluster tiles x slices)
-// fills the device, at most BOUND_KS_MAX (the partial buffer holds KS x B x C floats).
-static void bound_mfma_plan(int C, int d, int& KS, int& kbs) {
-    const int tiles = (C + 15) / 16, nkb = (d + 31) / 32;
-    KS = (BOUND_WAVE_TARGET + tiles - 1) / tiles;
-    KS = ((KS + BOUND_KS_PER_BLOCK - 1) / BOUND_KS_PER_BLOCK) * BOUND_KS_PER_BLOCK;
+// K slices of the batched bound product and k-blocks (of 32) per slice: enough slices that (groups of cluster tiles x
+// slices) fills the device, a whole number of request chunks per slice, a slice's h within BOUND_LDS_KB of LDS, at most
+// BOUND_KS_MAX slices (the partial buffer holds KS x B x C floats).  B decides how many sequence tiles a block carries.
+static int bound_mfma_nt(int B) { return B > 32 ? 4 : (B > 16 ? 2 : 1); }
+static void bound_mfma_plan(int C, int d, int B, int& KS, int& kbs) {
+    const int tiles = (C + 15) / 16, groups = (tiles + BOUND_TILES_PER_BLOCK - 1) / BOUND_TILES_PER_BLOCK, nkb = (d + 31) / 32;
+    KS = (BOUND_BLOCK_TARGET + groups - 1) / groups;
     if (KS > BOUND_KS_MAX) KS = BOUND_KS_MAX;
+    if (KS > nkb) KS = nkb;
     kbs = (nkb + KS - 1) / KS;
-    kbs = (kbs + BOUND_KB_UNROLL - 1) / BOUND_KB_UNROLL * BOUND_KB_UNROLL;   // whole trips of the k loop
+    kbs = (kbs + BOUND_PIPE - 1) / BOUND_PIPE * BOUND_PIPE;     // whole chunks
+    const int cap = BOUND_LDS_KB / bound_mfma_nt(B) / BOUND_PIPE * BOUND_PIPE;
+    if (kbs > cap) kbs = cap;                                   // d <= 8192: 256 k-blocks in at most 32 slices of 8 always fit
     KS = (nkb + kbs - 1) / kbs;
 }
 
@@ -2863,19 +2891,21 @@ static int launch_bounds_kernel(const StepArgs& a, float* U, float* hn, int rese
     if (a.B >= BOUND_MFMA_MIN_B) {
         const int tiles = (a.C + 15) / 16;
         int KS, kbs;
-        bound_mfma_plan(a.C, a.d, KS, kbs);
-        dim3 grid(tiles, (KS + BOUND_KS_PER_BLOCK - 1) / BOUND_KS_PER_BLOCK);
+        bound_mfma_plan(a.C, a.d, a.B, KS, kbs);
+        dim3 grid((tiles + BOUND_TILES_PER_BLOCK - 1) / BOUND_TILES_PER_BLOCK, KS);
         for (int s0 = 0; s0 < a.B; s0 += 64) {
             const int nseq = a.B - s0 < 64 ? a.B - s0 : 64;
             const int r = reset && s0 == 0;
+            const int nt = nseq <= 16 ? 1 : (nseq <= 32 ? 2 : 4);
+            const size_t lds = (size_t)kbs * nt * 1024;
             if (a.mu16) {
-                if (nseq <= 16) bound_mfma_kernel<1, true><<<grid, 512, 0, st>>>(a, a.bound_partial, s0, KS, kbs, r);
-                else if (nseq <= 32) bound_mfma_kernel<2, true><<<grid, 512, 0, st>>>(a, a.bound_partial, s0, KS, kbs, r);
-                else bound_mfma_kernel<4, true><<<grid, 512, 0, st>>>(a, a.bound_partial, s0, KS, kbs, r);
+                if (nt == 1) bound_mfma_kernel<1, true><<<grid, 512, lds, st>>>(a, a.bound_partial, s0, KS, kbs, r);
+                else if (nt == 2) bound_mfma_kernel<2, true><<<grid, 512, lds, st>>>(a, a.bound_partial, s0, KS, kbs, r);
+                else bound_mfma_kernel<4, true><<<grid, 512, lds, st>>>(a, a.bound_partial, s0, KS, kbs, r);
             } else {
-                if (nseq <= 16) bound_mfma_kernel<1, false><<<grid, 512, 0, st>>>(a, a.bound_partial, s0, KS, kbs, r);
-                else if (nseq <= 32) bound_mfma_kernel<2, false><<<grid, 512, 0, st>>>(a, a.bound_partial, s0, KS, kbs, r);
-                else bound_mfma_kernel<4, false><<<grid, 512, 0, st>>>(a, a.bound_partial, s0, KS, kbs, r);
+                if (nt == 1) bound_mfma_kernel<1, false><<<grid, 512, lds, st>>>(a, a.bound_partial, s0, KS, kbs, r);
+                else if (nt == 2) bound_mfma_kernel<2, false><<<grid, 512, lds, st>>>(a, a.bound_partial, s0, KS, kbs, r);
+                else bound_mfma_kernel<4, false><<<grid, 512, lds, st>>>(a, a.bound_partial, s0, KS, kbs, r);
             }
             CSV_LAUNCH_CHECK("bound_mfma_kernel");
         }
@@ -3128,7 +3158,7 @@ extern "C" int csv_bounds_static(const csv_index* idx, const uint16_t* d_h, int 
     a.B = B; a.h = d_h;
     if (B >= BOUND_MFMA_MIN_B) {       // the batched product is the only bound kernel with scratch: KS x B x C partial sums
         int KS, kbs;
-        bound_mfma_plan(idx->C, idx->d, KS, kbs);
+        bound_mfma_plan(idx->C, idx->d, B, KS, kbs);
         const size_t need = (size_t)KS * B * idx->C * sizeof(float);
         if (need > CSV_STATIC_SCRATCH_BYTES) {
             csv_set_error("B=%d sequences x C=%d clusters need %zu bytes of partial sums, the static scratch holds %u: "
