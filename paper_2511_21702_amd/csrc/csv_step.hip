@@ -2391,7 +2391,7 @@ __global__ __launch_bounds__(256) void full_gemv_kernel(FullArgs f) {
 // h is fed as the first operand and W' as the second, so accumulator register r of lane (li, g) is
 // out[sequence 4g + r][row li]: stores are 64-byte runs per sequence instead of 4-byte pieces 4V bytes apart.
 #define MFMA_THREADS 512
-#define MFMA_LDS (64 * 1024)        // two buffers of K blocks x 4 fragments x 1 KB x groups of 16 sequences: 4x1, 4x2 or 2x4
+#define MFMA_LDS (64 * 1024)        // two buffers of K blocks x 4 fragments x 1 KB x groups of 16 sequences: at most 2x4
 template <int NT, int TW, int MFMA_PIPE>
 __device__ __forceinline__ void full_mfma_device(const FullArgs& f, int n, int seq0, uint4* lds, int block, int nblocks) {
     constexpr int NW = MFMA_THREADS / 64;
@@ -2494,16 +2494,16 @@ __device__ __forceinline__ void full_mfma_device(const FullArgs& f, int n, int s
     }
 }
 
-// All n sequences through the MFMA path: up to 64 per pass over W'.  Four K blocks are requested ahead (two with 64
-// sequences, whose accumulators need the registers).  The groups of 128 TW rows are dealt to the blocks in rounds:
+// All n sequences through the MFMA path: up to 64 per pass over W'.  Two K blocks (of 128) are requested ahead: four
+// measured 2-8 % slower at d = 8192 for up to 32 sequences (and spill with 64), one no faster, eight far slower.  The groups of 128 TW rows are dealt to the blocks in rounds:
 // two row tiles per wave (a fragment of h read from LDS then serves two MFMAs) unless one tile per wave saves a
 // round's worth of idle blocks.  Four tiles per wave with half the K blocks ahead measured 4-7 % slower at d = 8192.
 template <int TW>
 __device__ __forceinline__ void full_mfma_pass(const FullArgs& f, int n, uint4* lds, int block, int nblocks) {
     for (int s0 = 0; s0 < n; s0 += 64) {
         const int m = n - s0;
-        if (m <= 16) full_mfma_device<1, TW, 4>(f, n, s0, lds, block, nblocks);
-        else if (m <= 32) full_mfma_device<2, TW, 4>(f, n, s0, lds, block, nblocks);
+        if (m <= 16) full_mfma_device<1, TW, 2>(f, n, s0, lds, block, nblocks);
+        else if (m <= 32) full_mfma_device<2, TW, 2>(f, n, s0, lds, block, nblocks);
         else full_mfma_device<4, TW, 2>(f, n, s0, lds, block, nblocks);
     }
 }
