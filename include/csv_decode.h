@@ -232,7 +232,7 @@ int csv_bounds(csv_workspace* ws, const csv_index* idx, const uint16_t* d_h, int
  * hipMalloc / hipFree and nothing that allocates.  The only scratch the bound kernels use (partial sums of the batched
  * product, more than 4 sequences) lives in an 8 MiB device array inside the library, one copy per GPU, held until the
  * process ends: for more than 4 sequences B * C may be at most about 2^21 / KS, KS <= 32 being the number of K slices
- * chosen for the shape (e.g. B = 32 at C = 4096, B = 256 at C = 1024); larger requests fail with CSV_ESHAPE and a message,
+ * chosen for the shape (e.g. up to B = 42 at C = 4096, d = 4608, where KS = 12 beyond 32 sequences; up to B = 64 at C = 1024, d = 4096, where KS = 32); larger requests fail with CSV_ESHAPE and a message,
  * nothing is launched.  The device of the index must be current.  Every call on a GPU shares that GPU's array: calls
  * that overlap on one GPU (different streams, different threads) race on it; stream-ordered calls are safe.  Nothing
  * in the array needs to start at zero (every partial sum is written before it is read).
