@@ -248,6 +248,44 @@ def test_step_equal_logits_rank_by_token_id(k):
 
 
 @pytest.mark.gpu
+def test_step_outputs_do_not_depend_on_timing_or_launch_form():
+    # the same steps five times: three times with the launch form following the history, once as one resident kernel
+    # after round 0, once as one launch per phase; every output word must be the same each time (candidates are
+    # collected in arrival order, chunk lists merged by whichever block comes last, fallbacks take the vector or the
+    # MFMA product by their number only)
+    r = synth.small_recipe("repeat", V=24000, d=72, C=48, B=7, steps=6, h_mode="mix", iso_frac=0.3, k=40, eps=1e-5)
+    case = Case(r, seed=71, K_cap=24000, want_W64=False)
+    csv, torch = case.csv, case.torch
+    dh = csv.bits_to_device(case.hidden())
+    buf = csv.make_step_buffers(case.gidx, r.B, r.k, r.eps, 9000, O.COMBINE_ALL, want_sel=True)
+
+    def run():
+        outs = []
+        for s in range(r.steps):
+            csv.csv_decode_step(case.ws, case.gidx, dh[s], buf)
+            torch.cuda.synchronize()
+            g = PAR.gpu_step_to_numpy(buf)
+            for b in range(r.B):                      # only the opened part of the cluster list is defined
+                g["sel"][b, g["n_clusters"][b] if not (g["flags"][b] & O.FLAG_FALLBACK) else 0:] = -1
+            outs.append(g)
+        return outs
+
+    ref = run()
+    fb = sum(int(((g["flags"] & O.FLAG_FALLBACK) != 0).sum()) for g in ref)
+    late = sum(int((g["rounds"] >= 2).sum()) for g in ref)
+    assert 0 < fb < r.B * r.steps and late > 0, (fb, late)      # the case has fallbacks, later rounds and plain certificates
+    for form in (0, 0, 1000, 1):
+        case.ws.set_tail_split(form)
+        got = run()
+        for s in range(r.steps):
+            for key in ("ids", "flags", "n_rows", "n_clusters", "rounds", "sel"):
+                assert np.array_equal(ref[s][key], got[s][key]), (form, s, key)
+            for key in ("logits", "lse"):
+                assert np.array_equal(ref[s][key].view(np.uint32), got[s][key].view(np.uint32)), (form, s, key)
+    case.close()
+
+
+@pytest.mark.gpu
 def test_two_live_workspaces_with_different_lds_needs():
     # the per-kernel dynamic-LDS limit is process-wide: a later, smaller workspace must not lower what an earlier,
     # larger one (C = 4096: more than 64 KB of cluster data per block) still needs
