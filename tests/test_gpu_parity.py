@@ -248,6 +248,22 @@ def test_step_equal_logits_rank_by_token_id(k):
 
 
 @pytest.mark.gpu
+def test_step_masked_tokens_with_minus_infinity_bias():
+    # a bias of -inf takes a token out (its logit is -inf, it adds nothing to any sum); a cluster of such tokens has the
+    # bound -inf and is never opened
+    r = synth.small_recipe("masked", V=6000, d=264, C=40, B=6, steps=4, h_mode="mix", iso_frac=0.2, k=20, eps=1e-4)
+    head = synth.make_head(r, seed=73, threads=16)
+    b = head["b"].copy()
+    b[np.random.default_rng(5).random(r.V) < 0.1] = -np.inf
+    b[head["labels"] == 7] = -np.inf
+    case = Case(r, seed=73, b=b)
+    t = case.run_steps(case.hidden(), r.k, r.eps, r.K_max_rows, O.COMBINE_ALL, "masked")
+    _finish(t, "masked")
+    assert 0 < t.fallbacks < t.n, t.summary()
+    case.close()
+
+
+@pytest.mark.gpu
 def test_step_outputs_do_not_depend_on_timing_or_launch_form():
     # the same steps five times: three times with the launch form following the history, once as one resident kernel
     # after round 0, once as one launch per phase; every output word must be the same each time (candidates are
