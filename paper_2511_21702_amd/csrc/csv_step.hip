@@ -1404,9 +1404,11 @@ __device__ __forceinline__ void rank_buckets(float* V, int* I, int m, int kk, fl
 // barrier, vmax is the largest value; on failure (k > RANK_DIRECT, too many survivors) nothing is decided.
 // MERGE: the values are lists of several chunks, unused places marked by the id 0x7fffffff (and the value -inf): those are
 // left out, and the first attempt also runs without a threshold (len may then be RANK_DIRECT or less).
-template <bool MERGE = false, class IdFn>
+// LATE_IDS: idf reads global memory: the candidates are collected with their positions and all look their ids up
+// together afterwards (a load in the collecting loop would be waited for in every trip that collects something).
+template <bool MERGE = false, bool LATE_IDS = false, class IdFn>
 __device__ __forceinline__ bool threshold_topk(int len, int k, float theta, bool short_ok, IdFn idf, SeqShared& s, int& kkv, float& vmax) {
-    extern __shared__ u64 arena[];
+    extern __shared__ __align__(16) u64 arena[];
     const int tid = threadIdx.x, nt = blockDim.x, lane = tid & 63;
     const float* V = reinterpret_cast<const float*>(arena);
     const int k0 = min(k, len);
@@ -1434,7 +1436,7 @@ __device__ __forceinline__ bool threshold_topk(int len, int k, float theta, bool
                 const unsigned slot = base + (unsigned)__popcll(bal & ((1ull << lane) - 1ull));
                 if (in && slot < CAND_CAP) {
                     cval[slot] = v;
-                    cid[slot] = idf(i);
+                    cid[slot] = LATE_IDS ? i : idf(i);
                 }
             }
         }
@@ -1449,6 +1451,10 @@ __device__ __forceinline__ bool threshold_topk(int len, int k, float theta, bool
         if (m > CAND_CAP || (!short_ok && m < k0)) return false;
         vmax = wmax[0];
         for (int q = 1; q < (nt >> 6); ++q) vmax = fmaxf(vmax, wmax[q]);
+        if (LATE_IDS) {
+            if (tid < m) cid[tid] = idf(cid[tid]);
+            __syncthreads();
+        }
         kkv = min(k, m);
         if (m > RANK_BUCKETS_MIN && th > -INFINITY) {
             // the values thin out above the threshold: equal-width buckets up to eight times their mean excess hold a
@@ -1533,7 +1539,7 @@ __device__ __forceinline__ void write_distribution(const StepArgs& a, int b, int
 template <bool THRESH>
 __device__ __forceinline__ bool cert_body(const StepArgs& a, int b, int chunk, int round, const SeqState& st, SeqShared& s,
                                           bool staged = false) {
-    extern __shared__ u64 arena[];
+    extern __shared__ __align__(16) u64 arena[];
     const int tid = threadIdx.x, nt = blockDim.x, C = a.C;
     if (st.status != ST_ACTIVE || st.rounds != round) return false;
     const int n = st.n_rows;
@@ -1889,7 +1895,7 @@ __device__ __forceinline__ void wave_seed_tail(const StepArgs& a, const WaveSeed
 // sequence: 1 when the sequence is finished (certified, or flagged invalid), 2 when it left work for later phases
 // (a planned round, a hand-over, a fallback) or gave up.
 __device__ __forceinline__ int round0_device(const StepArgs& a, int b, int j, int NB, SeqShared& s) {
-    extern __shared__ u64 arena[];
+    extern __shared__ __align__(16) u64 arena[];
     const int tid = threadIdx.x, nt = SEQ_THREADS, lane = tid & 63, wave = tid >> 6, C = a.C;
     const int nch = a.d >> 3;
     const ClusterLds L = carve_clusters(arena, a.Npad, C);
@@ -2150,7 +2156,7 @@ __device__ __forceinline__ int round0_device(const StepArgs& a, int b, int j, in
 #define ALG1_CL_OFF (CAND_OFF + CAND_BYTES + 16)      // bytes; a multiple of 16
 static_assert(ALG1_PIECE + CSV_MAX_K <= STAGE_CAP && ALG1_CL_OFF % 16 == 0, "Algorithm-1 mode: staging layout");
 __global__ __launch_bounds__(SEQ_THREADS) void alg1_kernel(StepArgs a, int h_off16) {
-    extern __shared__ u64 arena[];
+    extern __shared__ __align__(16) u64 arena[];
     __shared__ SeqShared s;
     const int b = blockIdx.x, tid = threadIdx.x, nt = SEQ_THREADS, lane = tid & 63, wave = tid >> 6, C = a.C;
     const int nch = a.d >> 3;
@@ -2524,21 +2530,131 @@ __global__ __launch_bounds__(MFMA_THREADS) void full_mfma_kernel(FullArgs f) {
     full_mfma_all(f, n, mfma_lds, blockIdx.x, gridDim.x);
 }
 
+// The first stage for k <= RANK_DIRECT < n with the chunk's logits in registers (blockDim.x = SEQ_THREADS, sixteen values
+// a thread): no staging, two passes over the registers.  Pass one: the thread's maximum, hence the maxima of 256 groups
+// (the values i with i % 256 == g); their k-th largest is a threshold that k values reach (each thread counts the
+// groups above its own, over half of them), their largest the chunk's maximum.  Pass two: the sum for the log-sum-exp,
+// in block_lse's order (the same bits), and the values at or above the threshold, which are ranked like any other
+// candidates.  Returns false (nothing decided) when more than CAND_CAP values reach the threshold.
+template <class IdFn>
+__device__ __forceinline__ bool fb_topk_regs(const float* __restrict__ vals, int n, int k, IdFn idf, SeqShared& s, LseAcc& l, int& kk) {
+    extern __shared__ __align__(16) u64 arena[];
+    constexpr int PER = FB_CHUNK / SEQ_THREADS;
+    const int tid = threadIdx.x, lane = tid & 63;
+    float v[PER];
+    // all sixteen loads first, from clamped addresses; values past the end are replaced afterwards (a select behind each
+    // load would be waited for where it stands: sixteen round trips one after the other)
+#pragma unroll
+    for (int j = 0; j < PER; ++j) v[j] = vals[min(tid + SEQ_THREADS * j, n - 1)];
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int j = 0; j < PER; ++j)
+        if (tid + SEQ_THREADS * j >= n) v[j] = -INFINITY;
+    float* gm = reinterpret_cast<float*>(arena);
+    float* cval = reinterpret_cast<float*>(reinterpret_cast<char*>(arena) + CAND_OFF);
+    int* cid = reinterpret_cast<int*>(cval + CAND_CAP + 4);
+    float mx = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < PER; ++j) mx = fmaxf(mx, v[j]);
+    gm[tid] = mx;
+    if (tid < CAND_CAP) cval[tid] = -INFINITY;
+    if (tid < 4) cval[CAND_CAP + tid] = -INFINITY;
+    if (tid == 0) {
+        s.cnt = 0;
+        s.eq = 0xFFFFFFFFu;
+    }
+    __syncthreads();
+    const int e = tid & 255, half = tid >> 8;
+    const float ve = fmaxf(gm[e], gm[e + 256]);                  // the maximum of group e
+    int gt = 0;
+    const float4* gm4 = reinterpret_cast<const float4*>(gm);
+#pragma unroll 8
+    for (int q = half * 32; q < half * 32 + 32; ++q) {
+        const float4 x = gm4[q], y = gm4[64 + q];
+        gt += (fmaxf(x.x, y.x) > ve) + (fmaxf(x.y, y.y) > ve) + (fmaxf(x.z, y.z) > ve) + (fmaxf(x.w, y.w) > ve);
+    }
+    s.rank[tid] = gt;
+    __syncthreads();
+    if (tid < 256) {
+        const int g = s.rank[tid] + s.rank[tid + 256];           // groups with a larger maximum
+        if (g < k) atomicMin(&s.eq, lkey(ve));                   // the k-th largest is the smallest of those with fewer than k above
+        if (g == 0) s.rem = __float_as_uint(ve);                 // the chunk's maximum (equal writes if it comes twice)
+    }
+    __syncthreads();
+    const float th = fkey_inv(s.eq), vmax = __uint_as_float(s.rem);
+    float sm = 0.f, over = 0.f;
+#pragma unroll
+    for (int j = 0; j < PER; ++j) {
+        const int i = tid + SEQ_THREADS * j;
+        if (vmax > -INFINITY && i < n) sm += expf(v[j] - vmax);
+        const bool in = i < n && v[j] >= th;
+        if (in) over += v[j] - th;
+        const unsigned long long bal = __ballot(in);
+        if (bal) {
+            const int lead = __ffsll((long long)bal) - 1;
+            unsigned base = 0;
+            if (lane == lead) base = atomicAdd(&s.cnt, (unsigned)__popcll(bal));
+            base = __shfl(base, lead, CSV_WAVE);
+            const unsigned slot = base + (unsigned)__popcll(bal & ((1ull << lane) - 1ull));
+            if (in && slot < CAND_CAP) {
+                cval[slot] = v[j];
+                cid[slot] = i;           // the token id is looked up below, for all candidates at once: a load from global
+            }                            // memory in this loop would be waited for in every trip that collects something
+        }
+    }
+    over = wave_sum(over);
+    float* wover = reinterpret_cast<float*>(s.redu);
+    if (lane == 0) wover[tid >> 6] = over;
+    l.m = vmax;
+    l.s = block_sum(sm, reinterpret_cast<float*>(s.redl));        // its barriers also publish the candidates and wover; not s.redf, which the ranking writes
+    const int m = (int)s.cnt;
+    if (m > CAND_CAP) return false;
+    if (tid < m) cid[tid] = idf(cid[tid]);
+    __syncthreads();
+    kk = min(k, m);
+    if (m > RANK_BUCKETS_MIN && th > -INFINITY) {
+        float tot = 0.f;
+        for (int q = 0; q < (SEQ_THREADS >> 6); ++q) tot += wover[q];
+        rank_buckets(cval, cid, m, kk, th, fminf(vmax, th + 8.f * tot / (float)m), s);
+    } else {
+        float dummy;
+        rank_small(cval, cid, m, kk, s, dummy);
+    }
+    return true;
+}
+
 // First stage of top-k / log-sum-exp over V: one block per (chunk of rows, fallback slot).  The chunk's logits
 // are staged in LDS; token ids come from the permutation only for elements at the selection boundary.
 template <bool THRESH>
 __device__ __forceinline__ void fb_topk_device(const StepArgs& a, int slot, int chunk, SeqShared& s) {
-    extern __shared__ u64 arena[];
+    extern __shared__ __align__(16) u64 arena[];
     const int tid = threadIdx.x, nt = blockDim.x;
     const int c0 = chunk * FB_CHUNK;
     const int n = min(FB_CHUNK, a.V - c0);
     const float* vals = a.fb_logits + (size_t)slot * a.V + c0;
+    auto idf = [&](int i) { return a.perm[c0 + i]; };
+    const size_t pc = (size_t)slot * a.n_chunks + chunk;
+    if (THRESH && a.k > 0 && a.k <= RANK_DIRECT && n > RANK_DIRECT) {
+        LseAcc lr;
+        int kr = 0;
+        const bool done = fb_topk_regs(vals, n, a.k, idf, s, lr, kr);
+        __syncthreads();
+        if (done) {
+            if (tid == 0) {
+                a.cand_max[pc] = lr.m;
+                a.cand_sum[pc] = lr.s;
+            }
+            for (int t = tid; t < a.k; t += nt) {
+                a.cand_val[pc * a.k + t] = t < kr ? s.wval[t] : -INFINITY;
+                a.cand_id[pc * a.k + t] = t < kr ? s.wid[t] : 0x7fffffff;
+            }
+            return;
+        }
+    }
     stage_to_lds(reinterpret_cast<float*>(arena), vals, n);
     __syncthreads();
     auto val = [](int i) { return reinterpret_cast<const float*>(arena)[i]; };
-    auto idf = [&](int i) { return a.perm[c0 + i]; };
     const LseAcc l = block_lse(n, val, s);
-    const size_t pc = (size_t)slot * a.n_chunks + chunk;
     if (tid == 0) {
         a.cand_max[pc] = l.m;
         a.cand_sum[pc] = l.s;
@@ -2549,7 +2665,7 @@ __device__ __forceinline__ void fb_topk_device(const StepArgs& a, int slot, int 
         bool done = false;
         if (THRESH && n > RANK_DIRECT) {
             __syncthreads();
-            done = threshold_topk(n, a.k, -INFINITY, false, idf, s, kk, vmax);
+            done = threshold_topk<false, true>(n, a.k, -INFINITY, false, idf, s, kk, vmax);
             __syncthreads();
         }
         if (!done) kk = block_topk(n, a.k, val, idf, s);
@@ -2563,7 +2679,7 @@ __device__ __forceinline__ void fb_topk_device(const StepArgs& a, int slot, int 
 // Second stage: merge the chunk candidates of one fallback sequence and write its outputs.
 template <bool THRESH>
 __device__ __forceinline__ void fb_final_device(const StepArgs& a, int slot, SeqShared& s) {
-    extern __shared__ u64 arena[];
+    extern __shared__ __align__(16) u64 arena[];
     const int tid = threadIdx.x, nt = blockDim.x;
     const int b = a.fb_list[slot];
     const float* cm = a.cand_max + (size_t)slot * a.n_chunks;
@@ -2617,6 +2733,7 @@ __device__ __forceinline__ void fb_final_device(const StepArgs& a, int slot, Seq
 // by the host so that all blocks are resident together; every wait is bounded: a block that waits too long raises
 // the abort flag and every block leaves (the step's unfinished sequences keep the INVALID flag seed_kernel gave them).
 #define TAIL_THREADS 512
+static_assert(TAIL_THREADS == SEQ_THREADS, "the per-sequence phases assume one block size");
 #define TAIL_SPIN_LIMIT (1 << 22)
 
 // Returns false when the step was aborted.  Each barrier of a step uses its own counter.
@@ -2647,7 +2764,7 @@ __device__ __forceinline__ bool grid_barrier(int* counters, int which, int nbloc
 template <bool THRESH>
 __device__ __forceinline__ void tail_device(const StepArgs& a, const FullArgs& f, int fallback_only, int block, int nblocks,
                                             SeqShared& s, GemvShared& gs, int* s_flag) {
-    extern __shared__ u64 arena[];
+    extern __shared__ __align__(16) u64 arena[];
     const int tid = threadIdx.x;
     if (a.counters[CNT_TAIL_NEEDED] == 0) return;      // the common case at small batches: one word, no reduction
     if (fallback_only && a.counters[CNT_FALLBACK] == 0) return;
@@ -2765,7 +2882,7 @@ __global__ __launch_bounds__(SEQ_THREADS) void step_kernel(StepArgs a, FullArgs 
 // release and acquire writes back and invalidates its XCD's L2).  Every kernel finds out on the device whether it
 // has anything to do.
 __global__ __launch_bounds__(TAIL_THREADS, 2) void round_gemv_kernel(StepArgs a, int r) {
-    extern __shared__ u64 arena[];
+    extern __shared__ __align__(16) u64 arena[];
     __shared__ GemvShared gs;
     if (a.counters[CNT_TAIL_NEEDED] == 0) return;
     gemv_tiles_device(a, r, reinterpret_cast<uint4*>(arena), gs, blockIdx.x, gridDim.x);
@@ -2780,7 +2897,7 @@ __global__ __launch_bounds__(SEQ_THREADS) void round_cert_kernel(StepArgs a, int
 // Up to FULL_G fallback sequences take the vector product, more the MFMA product, which needs a compute unit's whole
 // register file: two kernels, of which one returns at once.
 __global__ __launch_bounds__(TAIL_THREADS, 2) void fb_product_kernel(StepArgs a, FullArgs f) {
-    extern __shared__ u64 arena[];
+    extern __shared__ __align__(16) u64 arena[];
     const int n_fb = a.counters[CNT_FALLBACK];
     if (n_fb == 0 || n_fb > FULL_G) return;
     full_gemv_device(f, n_fb, reinterpret_cast<uint4*>(arena), blockIdx.x, gridDim.x);
