@@ -1538,7 +1538,7 @@ __device__ __forceinline__ void write_distribution(const StepArgs& a, int b, int
 // longer, although the step never runs it.
 template <bool THRESH>
 __device__ __forceinline__ bool cert_body(const StepArgs& a, int b, int chunk, int round, const SeqState& st, SeqShared& s,
-                                          bool staged = false) {
+                                          bool staged = false, int* settled_count = nullptr) {
     extern __shared__ __align__(16) u64 arena[];
     const int tid = threadIdx.x, nt = blockDim.x, C = a.C;
     if (st.status != ST_ACTIVE || st.rounds != round) return false;
@@ -1655,6 +1655,9 @@ __device__ __forceinline__ bool cert_body(const StepArgs& a, int b, int chunk, i
         ok = (tk && a.use_k) || (sm && a.use_s);
 
     auto finish = [&](unsigned flags) {
+        // the fused step kernel's parked blocks wait for this count: a finished sequence leaves nothing for them to
+        // read, so they are told before the outputs are written rather than after
+        if (settled_count && tid == 0) atomicAdd(settled_count, 1);
         for (int t = tid; t < a.k; t += nt) {
             a.out.d_ids[(size_t)b * a.k + t] = s.wid[t];
             a.out.d_logits[(size_t)b * a.k + t] = s.wval[t];
@@ -1894,7 +1897,8 @@ __device__ __forceinline__ void wave_seed_tail(const StepArgs& a, const WaveSeed
 // One sequence's round 0 as seen by block j of its NB blocks.  Returns nonzero in the one block that settled the
 // sequence: 1 when the sequence is finished (certified, or flagged invalid), 2 when it left work for later phases
 // (a planned round, a hand-over, a fallback) or gave up.
-__device__ __forceinline__ int round0_device(const StepArgs& a, int b, int j, int NB, SeqShared& s) {
+// settled_count: where a sequence that finishes here is counted as soon as that is decided (the return value is then 3).
+__device__ __forceinline__ int round0_device(const StepArgs& a, int b, int j, int NB, SeqShared& s, int* settled_count = nullptr) {
     extern __shared__ __align__(16) u64 arena[];
     const int tid = threadIdx.x, nt = SEQ_THREADS, lane = tid & 63, wave = tid >> 6, C = a.C;
     const int nch = a.d >> 3;
@@ -2143,7 +2147,7 @@ __device__ __forceinline__ int round0_device(const StepArgs& a, int b, int j, in
         }
         return 2;
     }
-    return cert_body<false>(a, b, 0, 0, st, s, true) ? 1 : 2;     // every path of it that leaves work behind writes the state it needs
+    return cert_body<false>(a, b, 0, 0, st, s, true, settled_count) ? (settled_count ? 3 : 1) : 2;     // every path of it that leaves work behind writes the state it needs
 }
 
 // ================================================================================================ Algorithm 1's own order
@@ -2845,8 +2849,8 @@ __global__ __launch_bounds__(SEQ_THREADS) void step_kernel(StepArgs a, FullArgs 
     __shared__ int s_flag;
     const int n0 = NB * a.B;
     if ((int)blockIdx.x < n0) {
-        const int settled = round0_device(a, blockIdx.x / NB, blockIdx.x % NB, NB, s);
-        if (!settled) return;
+        const int settled = round0_device(a, blockIdx.x / NB, blockIdx.x % NB, NB, s, &a.counters[CNT_R0_DONE]);
+        if (!settled || settled == 3) return;          // 3: finished and already counted
         __syncthreads();                      // all of the block's writes are issued
         if (threadIdx.x == 0) {
             // One word tells the parked blocks both things: sequences settled (low half) and whether any of them
