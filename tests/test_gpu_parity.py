@@ -261,6 +261,19 @@ def test_step_masked_tokens_with_minus_infinity_bias():
     _finish(t, "masked")
     assert 0 < t.fallbacks < t.n, t.summary()
     case.close()
+    # more than half of the vocabulary masked, cluster by cluster: one whole chunk of the fallback's first stage holds
+    # nothing but -inf, and with k = 200 a chunk has fewer finite logits than the list is long
+    r = synth.small_recipe("masked-chunk", V=20000, d=136, C=40, B=6, steps=3, h_mode="mix", iso_frac=0.5, k=20, eps=1e-4)
+    head = synth.make_head(r, seed=77, threads=16)
+    b = head["b"].copy()
+    for c in range(14, 37):
+        b[head["labels"] == c] = -np.inf
+    case = Case(r, seed=77, b=b, K_cap=20000)
+    for k in (20, 200):
+        t = case.run_steps(case.hidden(), k, r.eps, 2000, O.COMBINE_ALL, f"masked chunk k={k}")
+        _finish(t, f"masked chunk k={k}")
+        assert t.fallbacks > t.n // 2, t.summary()
+    case.close()
 
 
 @pytest.mark.gpu
