@@ -2080,9 +2080,8 @@ __device__ __forceinline__ int round0_device(const StepArgs& a, int b, int j, in
     };
     if (!fast) {
         if (p < rows) request_row(row_of(p));
-        T0 = seed_tail_mass(a, L, kappa, nxt, nxtU, s);
+        __syncthreads();                   // h staged (the fast path staged it before its barrier)
     }
-    if (!fast) __syncthreads();            // h staged (the fast path staged it before its barrier)
     while (p < rows) {
         float acc = 0.f, acc2 = 0.f;          // two chains: a dependent FMA costs two issue slots of a lone wave
 #pragma unroll
@@ -2112,7 +2111,10 @@ __device__ __forceinline__ int round0_device(const StepArgs& a, int b, int j, in
     // input, copies them to the row arrays that later rounds read, and empties the word for the next step.  All NB
     // blocks of a sequence are resident together (the host sizes the grid so), and the wait is bounded.
     if (j != 0) return 0;
-    if (fast) wave_seed_tail(a, ws, nxtU, T0);      // while the other blocks' words are on their way
+    // the tail mass, which only this block needs, while the other blocks' words are on their way (the cluster data
+    // in LDS is still whole: h sits behind it)
+    if (fast) wave_seed_tail(a, ws, nxtU, T0);
+    else T0 = seed_tail_mass(a, L, kappa, nxt, nxtU, s);
     const SeqState st = seed_state(m0, rows, kappa, nxtU, T0);
     __syncthreads();                       // every wave is done with h in LDS: the staging area overlaps it
     float* sv = reinterpret_cast<float*>(arena);
