@@ -2901,7 +2901,8 @@ __global__ __launch_bounds__(SEQ_THREADS) void round_cert_kernel(StepArgs a, int
 }
 
 // Up to FULL_G fallback sequences take the vector product, more the MFMA product, which needs a compute unit's whole
-// register file: two kernels, of which one returns at once.
+// register file.  A batch of at most FULL_G sequences launches the first kernel, a larger one the second, which holds
+// both products and picks by the number of fallback sequences.
 __global__ __launch_bounds__(TAIL_THREADS, 2) void fb_product_kernel(StepArgs a, FullArgs f) {
     extern __shared__ __align__(16) u64 arena[];
     const int n_fb = a.counters[CNT_FALLBACK];
@@ -2912,8 +2913,9 @@ __global__ __launch_bounds__(TAIL_THREADS, 2) void fb_product_kernel(StepArgs a,
 __global__ __launch_bounds__(MFMA_THREADS) void fb_product_mfma_kernel(StepArgs a, FullArgs f) {
     extern __shared__ uint4 mfma_lds[];
     const int n_fb = a.counters[CNT_FALLBACK];
-    if (n_fb <= FULL_G) return;
-    full_mfma_all(f, n_fb, mfma_lds, blockIdx.x, gridDim.x);
+    if (n_fb == 0) return;
+    if (n_fb > FULL_G) full_mfma_all(f, n_fb, mfma_lds, blockIdx.x, gridDim.x);
+    else full_gemv_device(f, n_fb, mfma_lds, blockIdx.x, gridDim.x);
 }
 
 __global__ __launch_bounds__(SEQ_THREADS) void fb_topk_kernel(StepArgs a) {             // grid (chunks of V, B)
@@ -3363,11 +3365,12 @@ extern "C" int csv_decode_step(csv_workspace* ws, const csv_index* idx, const ui
         alg1_kernel<<<B, SEQ_THREADS, lds, st>>>(a, (int)(h_off / 16));
         CSV_LAUNCH_CHECK("alg1_kernel");
         CSV_MARK(2);
-        fb_product_kernel<<<ws->tail_grid, TAIL_THREADS, (size_t)FULL_G * idx->d * 2, st>>>(a, f);
-        CSV_LAUNCH_CHECK("fb_product_kernel");
         if (B > FULL_G) {
             fb_product_mfma_kernel<<<ws->tail_grid, MFMA_THREADS, MFMA_LDS, st>>>(a, f);
             CSV_LAUNCH_CHECK("fb_product_mfma_kernel");
+        } else {
+            fb_product_kernel<<<ws->tail_grid, TAIL_THREADS, (size_t)FULL_G * idx->d * 2, st>>>(a, f);
+            CSV_LAUNCH_CHECK("fb_product_kernel");
         }
         fb_topk_kernel<<<dim3(ws->n_chunks, B), SEQ_THREADS, (size_t)CAND_OFF + CAND_BYTES, st>>>(a);
         CSV_LAUNCH_CHECK("fb_topk_kernel");
@@ -3429,11 +3432,12 @@ extern "C" int csv_decode_step(csv_workspace* ws, const csv_index* idx, const ui
                 CSV_LAUNCH_CHECK("round_cert_kernel");
             }
             if (fb_launches) {
-                fb_product_kernel<<<ws->tail_grid, TAIL_THREADS, (size_t)FULL_G * idx->d * 2, st>>>(a, f);
-                CSV_LAUNCH_CHECK("fb_product_kernel");
                 if (B > FULL_G) {
                     fb_product_mfma_kernel<<<ws->tail_grid, MFMA_THREADS, MFMA_LDS, st>>>(a, f);
                     CSV_LAUNCH_CHECK("fb_product_mfma_kernel");
+                } else {
+                    fb_product_kernel<<<ws->tail_grid, TAIL_THREADS, (size_t)FULL_G * idx->d * 2, st>>>(a, f);
+                    CSV_LAUNCH_CHECK("fb_product_kernel");
                 }
                 fb_topk_kernel<<<dim3(ws->n_chunks, B), SEQ_THREADS, (size_t)CAND_OFF + CAND_BYTES, st>>>(a);
                 CSV_LAUNCH_CHECK("fb_topk_kernel");
